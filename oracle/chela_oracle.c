@@ -1,0 +1,172 @@
+/*
+ * chela_oracle.c -- TEST INFRASTRUCTURE, not part of the product path.
+ *
+ * Plain, slow, fp64 CPU definition of causal (un-normalised) linear attention,
+ *     O_t = sum_{s<=t} (q_t . k_s) v_s ,
+ * i.e. the right-product linear attention of CHELA Sec. 2.1 Eq. 2 with the
+ * lower-triangular (inclusive) mask that Sec. 4.1 applies inside a block, and
+ * with Norm, scaling and feature maps left outside (the kernel's contract).
+ * Sec. 4.1 describes a tiled evaluation of exactly this quantity ("lossless",
+ * Sec. 4.4), so the oracle is the untiled definition written out twice:
+ *
+ *   quadratic form : the masked N x N score matrix applied to V, row by row;
+ *   recurrent form : the token-by-token running sum of k v^T (the "cumsum"
+ *                    formulation that Sec. 1 and Sec. 3 name as the baseline).
+ *
+ * No chunking, no blocking, no fusion: every loop below is the formula.
+ * The backward pass is not described in the paper; it is the exact gradient of
+ * the definition above (O is linear in each of Q, K and V separately).
+ *
+ * Layout: every tensor is [B, H, N, d] contiguous, d fastest; Q, K use d = dk,
+ * V, O, dO, dV use d = dv.  All arithmetic is IEEE double.  The only
+ * parallelism is OpenMP over the independent (b, h) pairs.
+ *
+ * Only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg may
+ * call this library.  It shares no code with the HIP library.
+ */
+#include <stddef.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+int chela_oracle_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* ---- quadratic (masked parallel) form: Eq. 2 + causal mask of Sec. 4.1 ---- */
+/* A[t,s] = q_t . k_s for s <= t, else 0 ;  O[t,:] = sum_s A[t,s] V[s,:].     */
+void chela_oracle_fwd_quadratic(const double *Q, const double *K, const double *V,
+                                double *O, int B, int H, int N, int dk, int dv)
+{
+    const long BH = (long)B * H;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long bh = 0; bh < BH; ++bh) {
+        const double *q = Q + bh * (long)N * dk;
+        const double *k = K + bh * (long)N * dk;
+        const double *v = V + bh * (long)N * dv;
+        double *o = O + bh * (long)N * dv;
+        for (int t = 0; t < N; ++t) {
+            for (int j = 0; j < dv; ++j) o[(long)t * dv + j] = 0.0;
+            for (int s = 0; s <= t; ++s) {
+                double a = 0.0;
+                for (int i = 0; i < dk; ++i) a += q[(long)t * dk + i] * k[(long)s * dk + i];
+                for (int j = 0; j < dv; ++j) o[(long)t * dv + j] += a * v[(long)s * dv + j];
+            }
+        }
+    }
+}
+
+/* Gradient of the quadratic form.  With A as above and                        */
+/* dA[t,s] = dO_t . v_s for s <= t, else 0:                                    */
+/*   dQ = dA K,   dK = dA^T Q,   dV = A^T dO.                                  */
+void chela_oracle_bwd_quadratic(const double *Q, const double *K, const double *V,
+                                const double *dO, double *dQ, double *dK, double *dV,
+                                int B, int H, int N, int dk, int dv)
+{
+    const long BH = (long)B * H;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long bh = 0; bh < BH; ++bh) {
+        const double *q = Q + bh * (long)N * dk;
+        const double *k = K + bh * (long)N * dk;
+        const double *v = V + bh * (long)N * dv;
+        const double *g = dO + bh * (long)N * dv;
+        double *dq = dQ + bh * (long)N * dk;
+        double *dkk = dK + bh * (long)N * dk;
+        double *dvv = dV + bh * (long)N * dv;
+        memset(dq, 0, sizeof(double) * (size_t)N * dk);
+        memset(dkk, 0, sizeof(double) * (size_t)N * dk);
+        memset(dvv, 0, sizeof(double) * (size_t)N * dv);
+        for (int t = 0; t < N; ++t) {
+            for (int s = 0; s <= t; ++s) {
+                double a = 0.0, da = 0.0;
+                for (int i = 0; i < dk; ++i) a += q[(long)t * dk + i] * k[(long)s * dk + i];
+                for (int j = 0; j < dv; ++j) da += g[(long)t * dv + j] * v[(long)s * dv + j];
+                for (int i = 0; i < dk; ++i) dq[(long)t * dk + i] += da * k[(long)s * dk + i];
+                for (int i = 0; i < dk; ++i) dkk[(long)s * dk + i] += da * q[(long)t * dk + i];
+                for (int j = 0; j < dv; ++j) dvv[(long)s * dv + j] += a * g[(long)t * dv + j];
+            }
+        }
+    }
+}
+
+/* ---- recurrent (token-by-token) form: the running KV state of Sec. 4.1 ---- */
+/* S <- 0 (dk x dv); for t = 0..N-1:  S += k_t v_t^T ;  o_t = S^T q_t.         */
+void chela_oracle_fwd_recurrent(const double *Q, const double *K, const double *V,
+                                double *O, int B, int H, int N, int dk, int dv)
+{
+    const long BH = (long)B * H;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long bh = 0; bh < BH; ++bh) {
+        const double *q = Q + bh * (long)N * dk;
+        const double *k = K + bh * (long)N * dk;
+        const double *v = V + bh * (long)N * dv;
+        double *o = O + bh * (long)N * dv;
+        double *S = (double *)calloc((size_t)dk * dv, sizeof(double));
+        for (int t = 0; t < N; ++t) {
+            for (int i = 0; i < dk; ++i)
+                for (int j = 0; j < dv; ++j)
+                    S[(long)i * dv + j] += k[(long)t * dk + i] * v[(long)t * dv + j];
+            for (int j = 0; j < dv; ++j) {
+                double acc = 0.0;
+                for (int i = 0; i < dk; ++i) acc += S[(long)i * dv + j] * q[(long)t * dk + i];
+                o[(long)t * dv + j] = acc;
+            }
+        }
+        free(S);
+    }
+}
+
+/* Gradient in recurrent form.                                                 */
+/* Forward sweep : S_t = S_{t-1} + k_t v_t^T ;  dq_t = S_t dO_t.               */
+/* Reverse sweep : R_t = R_{t+1} + q_t dO_t^T ; dk_t = R_t v_t ; dv_t = R_t^T k_t. */
+void chela_oracle_bwd_recurrent(const double *Q, const double *K, const double *V,
+                                const double *dO, double *dQ, double *dK, double *dV,
+                                int B, int H, int N, int dk, int dv)
+{
+    const long BH = (long)B * H;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long bh = 0; bh < BH; ++bh) {
+        const double *q = Q + bh * (long)N * dk;
+        const double *k = K + bh * (long)N * dk;
+        const double *v = V + bh * (long)N * dv;
+        const double *g = dO + bh * (long)N * dv;
+        double *dq = dQ + bh * (long)N * dk;
+        double *dkk = dK + bh * (long)N * dk;
+        double *dvv = dV + bh * (long)N * dv;
+        double *S = (double *)calloc((size_t)dk * dv, sizeof(double));
+        for (int t = 0; t < N; ++t) {
+            for (int i = 0; i < dk; ++i)
+                for (int j = 0; j < dv; ++j)
+                    S[(long)i * dv + j] += k[(long)t * dk + i] * v[(long)t * dv + j];
+            for (int i = 0; i < dk; ++i) {
+                double acc = 0.0;
+                for (int j = 0; j < dv; ++j) acc += S[(long)i * dv + j] * g[(long)t * dv + j];
+                dq[(long)t * dk + i] = acc;
+            }
+        }
+        memset(S, 0, sizeof(double) * (size_t)dk * dv);   /* S now plays the role of R */
+        for (int t = N - 1; t >= 0; --t) {
+            for (int i = 0; i < dk; ++i)
+                for (int j = 0; j < dv; ++j)
+                    S[(long)i * dv + j] += q[(long)t * dk + i] * g[(long)t * dv + j];
+            for (int i = 0; i < dk; ++i) {
+                double acc = 0.0;
+                for (int j = 0; j < dv; ++j) acc += S[(long)i * dv + j] * v[(long)t * dv + j];
+                dkk[(long)t * dk + i] = acc;
+            }
+            for (int j = 0; j < dv; ++j) {
+                double acc = 0.0;
+                for (int i = 0; i < dk; ++i) acc += S[(long)i * dv + j] * k[(long)t * dk + i];
+                dvv[(long)t * dv + j] = acc;
+            }
+        }
+        free(S);
+    }
+}

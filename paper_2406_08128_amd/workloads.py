@@ -1,0 +1,94 @@
+"""Seeded synthetic inputs for causal linear attention.
+
+This module only draws random tensors; it holds none of the method's arithmetic
+and is the one piece shared by the HIP path's tests/bench and the CPU oracle's
+tests.  It imports neither of them.
+
+The five workloads are synthetic stand-ins for the shapes of the paper's
+experiments (byte-level LRA Text at length 4K, Sec. 5.1; the ~200M-parameter
+WikiText-103 speed benchmark of Fig. 4 / Sec. 6 Q1); the datasets themselves are
+not used because the kernel's cost does not depend on the values.
+
+Recipe: torch.Generator(cpu).manual_seed(seed); torch.randn in fp32, drawn in
+the order Q, K, V, dO, each [B, H, N, d]; scaling / feature map applied in fp32;
+cast to the I/O dtype (round-to-nearest-even for bf16) last.
+"""
+from dataclasses import dataclass, replace
+from typing import Dict, Optional
+
+import torch
+
+
+@dataclass(frozen=True)
+class Workload:
+    name: str
+    B: int
+    H: int
+    N: int
+    dk: int
+    dv: int
+    dtype: str            # "f32" or "bf16": the I/O dtype
+    backward: bool
+    seed: int
+    qk_map: str           # "gauss_over_8" or "elu1_over_128"
+    chunks: tuple         # chunk sizes checked for this workload
+
+    @property
+    def token_heads(self) -> int:
+        return self.B * self.H * self.N
+
+    @property
+    def tokens(self) -> int:
+        return self.B * self.N
+
+
+WORKLOADS: Dict[str, Workload] = {
+    # Tiny fwd only, fp32 I/O.
+    "tiny_f32": Workload("tiny_f32", 1, 1, 1024, 64, 64, "f32", False, 0, "gauss_over_8", (64,)),
+    # LRA-shaped fwd, bf16 I/O.
+    "lra_bf16": Workload("lra_bf16", 32, 8, 4096, 64, 64, "bf16", False, 1, "gauss_over_8", (64, 128)),
+    # LM-shaped fwd+bwd, bf16 (d_model 768 = 12 heads x 64): the headline workload.
+    "lm_bf16": Workload("lm_bf16", 4, 12, 16384, 64, 64, "bf16", True, 2, "gauss_over_8", (64,)),
+    # Long-sequence fwd, bf16, positive feature map.
+    "long_bf16": Workload("long_bf16", 1, 16, 65536, 128, 128, "bf16", False, 3, "elu1_over_128", (64,)),
+    # Mixed-head fwd+bwd, bf16, rectangular state.
+    "mixed_bf16": Workload("mixed_bf16", 8, 12, 4096, 64, 128, "bf16", True, 4, "gauss_over_8", (64,)),
+}
+
+
+def shrink(w: Workload, **kw) -> Workload:
+    """Same recipe at a smaller (or otherwise different) shape."""
+    return replace(w, **kw)
+
+
+def _torch_dtype(name: str) -> torch.dtype:
+    return {"f32": torch.float32, "bf16": torch.bfloat16}[name]
+
+
+def make_inputs(w: Workload, with_dO: Optional[bool] = None) -> Dict[str, torch.Tensor]:
+    """Return CPU tensors {"Q","K","V"[,"dO"]} in the workload's I/O dtype."""
+    if with_dO is None:
+        with_dO = w.backward
+    g = torch.Generator(device="cpu")
+    g.manual_seed(w.seed)
+    xq = torch.randn(w.B, w.H, w.N, w.dk, generator=g, dtype=torch.float32)
+    xk = torch.randn(w.B, w.H, w.N, w.dk, generator=g, dtype=torch.float32)
+    v = torch.randn(w.B, w.H, w.N, w.dv, generator=g, dtype=torch.float32)
+    if w.qk_map == "gauss_over_8":
+        q, k = xq / 8.0, xk / 8.0
+    elif w.qk_map == "elu1_over_128":
+        q = (torch.nn.functional.elu(xq) + 1.0) / 128.0
+        k = (torch.nn.functional.elu(xk) + 1.0) / 128.0
+    else:
+        raise ValueError(w.qk_map)
+    dt = _torch_dtype(w.dtype)
+    out = {"Q": q.to(dt).contiguous(), "K": k.to(dt).contiguous(), "V": v.to(dt).contiguous()}
+    if with_dO:
+        dO = torch.randn(w.B, w.H, w.N, w.dv, generator=g, dtype=torch.float32)
+        out["dO"] = dO.to(dt).contiguous()
+    return out
+
+
+def to_f64_numpy(t: torch.Tensor):
+    """Exact up-cast of an fp32/bf16 tensor to a float64 numpy array (oracle input)."""
+    return t.detach().to("cpu").to(torch.float64).numpy()

@@ -1,0 +1,283 @@
+"""Pins for the fp64 CPU oracle (no GPU).
+
+The oracle is the plain definition of causal linear attention (CHELA Sec. 2.1
+Eq. 2 with the inclusive causal mask of Sec. 4.1; backward = its exact
+gradient).  Nothing here compares the oracle with a retyped copy of itself:
+each test checks it against a hand-worked fixture, brute-force scalar loops, a
+library routine (numpy matmul / cumsum), a closed form, or an identity that the
+mathematics fixes (adjointness, causality, time-reversal duality, agreement of
+the two forms).
+"""
+import itertools
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+FWD = {"quadratic": oracle.fwd_quadratic, "recurrent": oracle.fwd_recurrent}
+BWD = {"quadratic": oracle.bwd_quadratic, "recurrent": oracle.bwd_recurrent}
+
+
+def _rand(rng, B, H, N, dk, dv, with_dO=True):
+    Q = rng.standard_normal((B, H, N, dk))
+    K = rng.standard_normal((B, H, N, dk))
+    V = rng.standard_normal((B, H, N, dv))
+    dO = rng.standard_normal((B, H, N, dv)) if with_dO else None
+    return Q, K, V, dO
+
+
+# --------------------------------------------------------------------------- fixture
+def _load_golden(path):
+    out = {}
+    with open(path) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            tok = line.split()
+            name, r, c = tok[0], int(tok[1]), int(tok[2])
+            out[name] = np.array([float(x) for x in tok[3:]], dtype=np.float64).reshape(1, 1, r, c)
+    return out
+
+
+@pytest.mark.parametrize("form", ["quadratic", "recurrent"])
+def test_hand_worked_example(form):
+    g = _load_golden(os.path.join(HERE, "golden", "hand_worked_n3.txt"))
+    O = FWD[form](g["Q"], g["K"], g["V"])
+    dQ, dK, dV = BWD[form](g["Q"], g["K"], g["V"], g["dO"])
+    # small integers: every operation is exact in fp64
+    assert np.array_equal(O, g["O"])
+    assert np.array_equal(dQ, g["dQ"])
+    assert np.array_equal(dK, g["dK"])
+    assert np.array_equal(dV, g["dV"])
+
+
+# --------------------------------------------------------------------------- brute force
+def _brute_fwd(Q, K, V):
+    B, H, N, dk = Q.shape
+    dv = V.shape[3]
+    O = np.zeros((B, H, N, dv))
+    for b, h, t, j in itertools.product(range(B), range(H), range(N), range(dv)):
+        acc = 0.0
+        for s in range(t + 1):
+            for i in range(dk):
+                acc += Q[b, h, t, i] * K[b, h, s, i] * V[b, h, s, j]
+        O[b, h, t, j] = acc
+    return O
+
+
+def _brute_bwd(Q, K, V, dO):
+    """Gradient of L = <O, dO> taken term by term: L = sum_{t, s<=t, i, j} Q[t,i] K[s,i] V[s,j] dO[t,j]."""
+    B, H, N, dk = Q.shape
+    dv = V.shape[3]
+    dQ, dK, dV = np.zeros_like(Q), np.zeros_like(K), np.zeros_like(V)
+    for b, h in itertools.product(range(B), range(H)):
+        for t in range(N):
+            for s in range(t + 1):
+                for i in range(dk):
+                    for j in range(dv):
+                        dQ[b, h, t, i] += K[b, h, s, i] * V[b, h, s, j] * dO[b, h, t, j]
+                        dK[b, h, s, i] += Q[b, h, t, i] * V[b, h, s, j] * dO[b, h, t, j]
+                        dV[b, h, s, j] += Q[b, h, t, i] * K[b, h, s, i] * dO[b, h, t, j]
+    return dQ, dK, dV
+
+
+@pytest.mark.parametrize("form", ["quadratic", "recurrent"])
+@pytest.mark.parametrize("shape", [(1, 1, 1, 1, 1), (2, 1, 5, 3, 2), (1, 2, 8, 2, 3), (1, 1, 6, 1, 4)])
+def test_brute_force_small_integers(form, shape):
+    B, H, N, dk, dv = shape
+    r = np.random.default_rng(7 + N)
+    Q = r.integers(-3, 4, (B, H, N, dk)).astype(np.float64)
+    K = r.integers(-3, 4, (B, H, N, dk)).astype(np.float64)
+    V = r.integers(-3, 4, (B, H, N, dv)).astype(np.float64)
+    dO = r.integers(-3, 4, (B, H, N, dv)).astype(np.float64)
+    assert np.array_equal(FWD[form](Q, K, V), _brute_fwd(Q, K, V))
+    got = BWD[form](Q, K, V, dO)
+    want = _brute_bwd(Q, K, V, dO)
+    for g, w in zip(got, want):
+        assert np.array_equal(g, w)
+
+
+# --------------------------------------------------------------------------- library routines
+@pytest.mark.parametrize("form", ["quadratic", "recurrent"])
+def test_against_numpy_masked_matmul(form, rng):
+    Q, K, V, dO = _rand(rng, 2, 3, 37, 5, 7)
+    A = np.tril(Q @ K.transpose(0, 1, 3, 2))
+    dA = np.tril(dO @ V.transpose(0, 1, 3, 2))
+    assert oracle.rel_l2(FWD[form](Q, K, V), A @ V) < 1e-13
+    dQ, dK, dV = BWD[form](Q, K, V, dO)
+    assert oracle.rel_l2(dQ, dA @ K) < 1e-13
+    assert oracle.rel_l2(dK, dA.transpose(0, 1, 3, 2) @ Q) < 1e-13
+    assert oracle.rel_l2(dV, A.transpose(0, 1, 3, 2) @ dO) < 1e-13
+
+
+@pytest.mark.parametrize("form", ["quadratic", "recurrent"])
+def test_cumsum_special_case(form, rng):
+    # dk = 1 and q = k = 1 turns the method into the plain running sum of V (the paper's cumsum view).
+    N, dv = 50, 6
+    V = rng.standard_normal((2, 2, N, dv))
+    ones = np.ones((2, 2, N, 1))
+    assert oracle.rel_l2(FWD[form](ones, ones, V), np.cumsum(V, axis=2)) < 1e-14
+
+
+@pytest.mark.parametrize("form", ["quadratic", "recurrent"])
+def test_last_row_is_noncausal_right_product(form, rng):
+    # Row N-1 sees every token, so it equals Eq. 2 as printed (no mask): q_{N-1} (K^T V).
+    Q, K, V, _ = _rand(rng, 1, 2, 29, 4, 3, with_dO=False)
+    O = FWD[form](Q, K, V)
+    KV = K.transpose(0, 1, 3, 2) @ V
+    want = (Q[:, :, -1:, :] @ KV)[:, :, 0, :]
+    assert oracle.rel_l2(O[:, :, -1, :], want) < 1e-13
+
+
+# --------------------------------------------------------------------------- closed forms
+@pytest.mark.parametrize("form", ["quadratic", "recurrent"])
+def test_all_ones_closed_form(form):
+    N, dk, dv = 33, 5, 3
+    O = FWD[form](np.ones((1, 1, N, dk)), np.ones((1, 1, N, dk)), np.ones((1, 1, N, dv)))
+    want = dk * (np.arange(N) + 1.0)            # inclusive mask: token t sees t+1 tokens
+    assert np.array_equal(O[0, 0], np.repeat(want[:, None], dv, axis=1))
+    dQ, dK, dV = BWD[form](np.ones((1, 1, N, dk)), np.ones((1, 1, N, dk)), np.ones((1, 1, N, dv)),
+                           np.ones((1, 1, N, dv)))
+    assert np.array_equal(dQ[0, 0], np.repeat((dv * (np.arange(N) + 1.0))[:, None], dk, axis=1))
+    assert np.array_equal(dK[0, 0], np.repeat((dv * (N - np.arange(N) + 0.0))[:, None], dk, axis=1))
+    assert np.array_equal(dV[0, 0], np.repeat((dk * (N - np.arange(N) + 0.0))[:, None], dv, axis=1))
+
+
+@pytest.mark.parametrize("form", ["quadratic", "recurrent"])
+def test_orthonormal_keys_reproduce_values(form, rng):
+    # N <= dk and q_t = k_t = e_t  =>  (q_t . k_s) = delta_ts  =>  O = V.
+    N, dk, dv = 6, 8, 5
+    E = np.eye(N, dk)[None, None]
+    V = rng.standard_normal((1, 1, N, dv))
+    assert np.array_equal(FWD[form](E, E, V), V)
+
+
+# --------------------------------------------------------------------------- two forms agree
+@pytest.mark.parametrize("shape", [(1, 1, 1, 4, 4), (1, 1, 7, 3, 5), (2, 2, 64, 1, 9), (1, 3, 130, 16, 8),
+                                   (1, 1, 257, 64, 64)])
+def test_two_forms_agree(shape, rng):
+    Q, K, V, dO = _rand(rng, *shape)
+    assert oracle.rel_l2(oracle.fwd_recurrent(Q, K, V), oracle.fwd_quadratic(Q, K, V)) < 1e-12
+    for a, b in zip(oracle.bwd_recurrent(Q, K, V, dO), oracle.bwd_quadratic(Q, K, V, dO)):
+        assert oracle.rel_l2(a, b) < 1e-12
+
+
+def test_two_forms_agree_on_tiny_workload():
+    from paper_2406_08128_amd.workloads import WORKLOADS, make_inputs, to_f64_numpy
+    x = make_inputs(WORKLOADS["tiny_f32"])
+    Q, K, V = (to_f64_numpy(x[n]) for n in "QKV")
+    assert oracle.rel_l2(oracle.fwd_recurrent(Q, K, V), oracle.fwd_quadratic(Q, K, V)) < 1e-12
+
+
+# --------------------------------------------------------------------------- causality
+@pytest.mark.parametrize("form", ["quadratic", "recurrent"])
+def test_causality_bit_exact(form, rng):
+    N, cut = 40, 23
+    Q, K, V, dO = _rand(rng, 1, 2, N, 6, 5)
+    O = FWD[form](Q, K, V)
+    dQ, dK, dV = BWD[form](Q, K, V, dO)
+    # perturb everything strictly after `cut`: O[<=cut], dQ[<=cut] must not move at all
+    Q2, K2, V2, dO2 = (x.copy() for x in (Q, K, V, dO))
+    for x in (Q2, K2, V2, dO2):
+        x[:, :, cut + 1:, :] += rng.standard_normal(x[:, :, cut + 1:, :].shape)
+    O2 = FWD[form](Q2, K2, V2)
+    dQ2, _, _ = BWD[form](Q2, K2, V2, dO2)
+    assert np.array_equal(O[:, :, :cut + 1], O2[:, :, :cut + 1])
+    assert np.array_equal(dQ[:, :, :cut + 1], dQ2[:, :, :cut + 1])
+    assert not np.array_equal(O[:, :, cut + 1:], O2[:, :, cut + 1:])
+    # perturb Q, dO strictly before `cut`: dK[>=cut], dV[>=cut] must not move at all
+    Q3, dO3 = Q.copy(), dO.copy()
+    Q3[:, :, :cut, :] += 1.0
+    dO3[:, :, :cut, :] -= 2.0
+    _, dK3, dV3 = BWD[form](Q3, K, V, dO3)
+    assert np.array_equal(dK[:, :, cut:], dK3[:, :, cut:])
+    assert np.array_equal(dV[:, :, cut:], dV3[:, :, cut:])
+    # and the diagonal is included: token t depends on its own key/value
+    V4 = V.copy()
+    V4[:, :, cut, :] += 1.0
+    assert not np.array_equal(FWD[form](Q, K, V4)[:, :, cut], O[:, :, cut])
+
+
+# --------------------------------------------------------------------------- backward: adjoint + FD + duality
+@pytest.mark.parametrize("form", ["quadratic", "recurrent"])
+def test_adjoint_identities(form, rng):
+    # O is linear in each argument, so <O(X+E) - O(X), dO> = <E, dX> exactly (up to fp64 rounding).
+    Q, K, V, dO = _rand(rng, 2, 2, 45, 7, 4)
+    dQ, dK, dV = BWD[form](Q, K, V, dO)
+    O = FWD[form](Q, K, V)
+    for name, X, dX in (("Q", Q, dQ), ("K", K, dK), ("V", V, dV)):
+        E = rng.standard_normal(X.shape)
+        args = {"Q": Q, "K": K, "V": V}
+        args[name] = X + E
+        lhs = np.sum((FWD[form](args["Q"], args["K"], args["V"]) - O) * dO)
+        rhs = np.sum(E * dX)
+        assert abs(lhs - rhs) <= 1e-11 * max(1.0, abs(rhs)), name
+
+
+@pytest.mark.parametrize("form", ["quadratic", "recurrent"])
+def test_finite_differences(form, rng):
+    Q, K, V, dO = _rand(rng, 1, 1, 6, 3, 2)
+    grads = dict(zip("QKV", BWD[form](Q, K, V, dO)))
+    eps = 1e-5
+    for name in "QKV":
+        base = {"Q": Q, "K": K, "V": V}
+        num = np.zeros_like(base[name])
+        it = np.nditer(base[name], flags=["multi_index"])
+        for _ in it:
+            idx = it.multi_index
+            p = {k: v.copy() for k, v in base.items()}
+            m = {k: v.copy() for k, v in base.items()}
+            p[name][idx] += eps
+            m[name][idx] -= eps
+            num[idx] = np.sum((oracle.fwd_quadratic(p["Q"], p["K"], p["V"])
+                               - oracle.fwd_quadratic(m["Q"], m["K"], m["V"])) * dO) / (2 * eps)
+        assert oracle.rel_l2(grads[name], num) < 1e-8, name
+
+
+@pytest.mark.parametrize("form", ["quadratic", "recurrent"])
+def test_backward_by_time_reversal_duality(form, rng):
+    # dQ is causal linear attention with (query, key, value) = (dO, V, K); dV and dK are the same map run
+    # on the reversed sequence with (K, Q, dO) and (V, dO, Q).
+    Q, K, V, dO = _rand(rng, 1, 2, 31, 5, 6)
+    dQ, dK, dV = BWD[form](Q, K, V, dO)
+    flip = lambda x: x[:, :, ::-1, :].copy()
+    assert oracle.rel_l2(dQ, oracle.fwd_quadratic(dO, V, K)) < 1e-12
+    assert oracle.rel_l2(dV, flip(oracle.fwd_quadratic(flip(K), flip(Q), flip(dO)))) < 1e-12
+    assert oracle.rel_l2(dK, flip(oracle.fwd_quadratic(flip(V), flip(dO), flip(Q)))) < 1e-12
+
+
+# --------------------------------------------------------------------------- scaling, batching
+@pytest.mark.parametrize("form", ["quadratic", "recurrent"])
+def test_power_of_two_scaling_is_exact(form, rng):
+    Q, K, V, dO = _rand(rng, 1, 1, 20, 4, 4)
+    O = FWD[form](Q, K, V)
+    assert np.array_equal(FWD[form](2.0 * Q, K, V), 2.0 * O)
+    assert np.array_equal(FWD[form](Q, 0.5 * K, V), 0.5 * O)
+    assert np.array_equal(FWD[form](Q, K, 4.0 * V), 4.0 * O)
+
+
+@pytest.mark.parametrize("form", ["quadratic", "recurrent"])
+def test_heads_are_independent(form, rng):
+    Q, K, V, dO = _rand(rng, 2, 3, 17, 4, 5)
+    O = FWD[form](Q, K, V)
+    dQ, dK, dV = BWD[form](Q, K, V, dO)
+    for b, h in ((0, 0), (1, 2)):
+        sl = (slice(b, b + 1), slice(h, h + 1))
+        assert np.array_equal(FWD[form](Q[sl], K[sl], V[sl]), O[sl])
+        got = BWD[form](Q[sl], K[sl], V[sl], dO[sl])
+        for g, w in zip(got, (dQ[sl], dK[sl], dV[sl])):
+            assert np.array_equal(g, w)
+
+
+def test_empty_sequence():
+    z = np.zeros((1, 1, 0, 4))
+    assert oracle.fwd_quadratic(z, z, z).shape == (1, 1, 0, 4)
+    assert oracle.fwd_recurrent(z, z, z).shape == (1, 1, 0, 4)
+
+
+def test_oracle_reports_threads():
+    assert oracle.num_threads() >= 1
