@@ -1,0 +1,157 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path: causal linear attention forward + backward on one MI355X.
+
+A step is one pass of the whole hot path -- chela_linattn_fwd followed by chela_linattn_bwd -- over one batch of
+synthetic, seeded input that is already resident in HBM.  Default workload: the LM-shaped configuration the headline
+metric is quoted on (B=4, H=12, N=16384, dk=dv=64, bf16 I/O, fp32 accumulation).  Prints one JSON line.
+"""
+import argparse
+import json
+import os
+import re
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
+
+
+def algorithmic_bytes_per_token_head(dk, dv, es=2):
+    """Each I/O tensor moved once, states stay on chip: fwd reads Q,K,V writes O; bwd reads Q,K,V,dO writes dQ,dK,dV."""
+    fwd = es * (2 * dk + 2 * dv)
+    bwd = es * (2 * dk + 2 * dv + 2 * dk + dv)
+    return fwd, bwd
+
+
+def flops_per_token_head(dk, dv, C):
+    """Full-tile count of matrix-core work: fwd 2C(dk+dv) + 4 dk dv; bwd 6C dk + 4C dv + 10 dk dv."""
+    return 2 * C * (dk + dv) + 4 * dk * dv, 6 * C * dk + 4 * C * dv + 10 * dk * dv
+
+
+def read_traffic(path):
+    """HBM bytes per launch of the dominant kernel as measured by rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE),
+    taken from a committed profile summary; None if the summary is absent."""
+    try:
+        txt = open(path).read()
+    except OSError:
+        return None
+    m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", txt, flags=re.M)
+    return float(m.group(1)) if m else None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="lm_bf16")
+    ap.add_argument("--chunk", type=int, default=64)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--traffic-file", default=os.path.join(ROOT, "profiles", "bwd_sweep_lm_bf16_pmc.txt"))
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU (one MI355X per box); --gpus %d is not supported. "
+              "(b,h) pairs are independent, so N GPUs would each run this same kernel on B*H/N of them."
+              % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2406_08128_amd import binding
+    from paper_2406_08128_amd.workloads import WORKLOADS, make_inputs, to_f64_numpy
+
+    w = WORKLOADS[args.workload]
+    assert w.dtype == "bf16", "bench.py times the bf16 path"
+    torch.cuda.set_device(0)
+    x = make_inputs(w, with_dO=True)
+    d = {k: v.cuda() for k, v in x.items()}
+    O = torch.empty_like(d["V"])
+    dQ, dK, dV = torch.empty_like(d["Q"]), torch.empty_like(d["K"]), torch.empty_like(d["V"])
+    chunk = args.chunk
+
+    def step():
+        binding.chela_linattn_fwd(d["Q"], d["K"], d["V"], O=O, chunk=chunk)
+        binding.chela_linattn_bwd(d["Q"], d["K"], d["V"], d["dO"], dQ=dQ, dK=dK, dV=dV, chunk=chunk)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    tokens_per_s = w.tokens / (ms_per_step * 1e-3)
+
+    # Per-kernel durations: the same steps again with the library's HIP-event brackets switched on (events are
+    # recorded on the launch stream around each kernel).  Kept out of the region that `value` is computed from.
+    binding.chela_profile_reset()
+    binding.chela_profile_enable(True)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    prof = binding.chela_profile_read()
+    binding.chela_profile_enable(False)
+    binding.chela_profile_reset()
+    kernels = {k: {"launches": n, "avg_us": ms * 1e3 / n} for k, (n, ms) in prof.items()}
+
+    fwd_b, bwd_b = algorithmic_bytes_per_token_head(w.dk, w.dv)
+    fwd_f, bwd_f = flops_per_token_head(w.dk, w.dv, chunk)
+    th = w.token_heads
+    dom = "bf16_bwd_sweep_kernel"
+    dom_us = kernels[dom]["avg_us"]
+    achieved = bwd_b * th / (dom_us * 1e-6) / 1e9
+    traffic = read_traffic(args.traffic_file) if args.workload == "lm_bf16" else None
+    roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                "algorithmic_bytes_per_launch": bwd_b * th, "avg_launch_us": round(dom_us, 2)}
+    step_bytes = (fwd_b + bwd_b) * th
+    step_flops = (fwd_f + bwd_f) * th
+    whole = {"hbm_GBs_algorithmic": round(step_bytes / (ms_per_step * 1e-3) / 1e9, 1),
+             "hbm_frac": round(step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+             "mfma_TFLOPs_full_tile_model": round(step_flops / (ms_per_step * 1e-3) / 1e12, 1),
+             "mfma_frac": round(step_flops / (ms_per_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)}
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        Qn, Kn, Vn, Gn = (to_f64_numpy(x[n]) for n in ("Q", "K", "V", "dO"))
+        c0 = time.perf_counter()
+        oracle.fwd_recurrent(Qn, Kn, Vn)
+        oracle.bwd_recurrent(Qn, Kn, Vn, Gn)
+        c1 = time.perf_counter()
+        cpu = {"value": round(w.tokens / (c1 - c0), 1), "unit": "tokens/s", "cores": oracle.num_threads(),
+               "kind": "oracle", "seconds": round(c1 - c0, 3),
+               "sample": "fp64 recurrent-form oracle, fwd+bwd, all %d (b,h) pairs of the workload, one repetition"
+                         % (w.B * w.H)}
+
+    out = {
+        "metric": "causal linear-attn fwd+bwd tokens/s",
+        "value": round(tokens_per_s, 1),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "%s: B%d H%d N%d dk%d dv%d bf16 I/O fp32 accumulate, fwd+bwd, chunk %d"
+                               % (w.name, w.B, w.H, w.N, w.dk, w.dv, chunk),
+                   "tokens_per_step": w.tokens, "token_heads_per_step": th},
+        "roofline": roofline,
+        "whole_step": whole,
+        "kernels": {k: {"launches": v["launches"], "avg_us": round(v["avg_us"], 2)} for k, v in kernels.items()},
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

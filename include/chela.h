@@ -1,0 +1,130 @@
+/*
+ * chela.h -- C ABI of libchela.so: causal linear attention for AMD gfx950 (MI355X).
+ *
+ * The operation is the hardware-efficient linear attention of CHELA Sec. 4.1:
+ * given Q, K, V it returns
+ *
+ *        O[b,h,t,:] = sum_{s <= t} ( Q[b,h,t,:] . K[b,h,s,:] ) * V[b,h,s,:]
+ *
+ * i.e. the right-product linear attention of Sec. 2.1 Eq. 2 under a causal mask
+ * that includes the diagonal, evaluated block-wise as Sec. 4.1 describes: the
+ * masked left product (Q K^T) V inside a block of `chunk` tokens, the right
+ * product Q (K^T V) between blocks through a d_k x d_v state that is carried
+ * on chip, the two parts summed before the result goes to HBM.  Norm, the
+ * 1/sqrt(d) scale and any feature map are NOT applied: callers pre-scale Q, K.
+ * The backward entry points return the exact gradient of that map (the paper
+ * times a backward pass, Fig. 4, but does not describe one).
+ *
+ * Conventions for every entry point
+ *   Pointers : DEVICE pointers (hipMalloc'ed or owned by a framework such as
+ *              PyTorch), 16-byte aligned, valid on the current HIP device.
+ *   Layout   : [B, H, N, d] contiguous, d fastest.  Q, K, dQ, dK use d = dk;
+ *              V, O, dO, dV use d = dv.  No strides.
+ *   Dtype    : *_fwd / *_bwd take bfloat16 tensors and accumulate in fp32
+ *              (scores and states are rounded to bf16 only as matrix-core
+ *              operands); *_f32 take and return IEEE fp32.
+ *   Shapes   : B, H, N >= 0 (any of them 0 -> nothing is done, success);
+ *              dk, dv in {64, 128}; chunk in {64, 128} for bf16 and
+ *              {16, 32, 64} for fp32.  N need not be a multiple of chunk.
+ *              `chunk` is a tiling choice: it never changes the result beyond
+ *              floating-point re-association.
+ *   Ownership: the caller owns all tensors; the library keeps no reference
+ *              once the enqueued work has finished.  Outputs are overwritten,
+ *              never accumulated into, and must not overlap any input.
+ *   Stream   : `stream` is a hipStream_t passed as void* (NULL = the default
+ *              stream).  Work is enqueued and the call returns without
+ *              synchronising.
+ *   Scratch  : per-(b,h)-segment states, chela_linattn_workspace_bytes() bytes.
+ *              Taken from the buffer given to chela_set_workspace(), else from
+ *              an internal allocation that grows on demand (growing it
+ *              synchronises the device) and lives until chela_shutdown().
+ *              Calls that may overlap in time on different streams must not
+ *              share one workspace.
+ *   Errors   : 0 on success, a negative CHELA_ERR_* otherwise.  Every argument
+ *              check is done on the host before the first HIP call, so a
+ *              rejected call has touched nothing.  No exceptions, no abort.
+ */
+#ifndef CHELA_H
+#define CHELA_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CHELA_VERSION 100 /* 0.1.0 */
+
+enum {
+    CHELA_OK                  = 0,
+    CHELA_ERR_NULL_POINTER    = -1, /* a tensor pointer is NULL while B*H*N > 0            */
+    CHELA_ERR_BAD_SHAPE       = -2, /* B, H or N negative, or element count overflows      */
+    CHELA_ERR_UNSUPPORTED_DIM = -3, /* dk or dv not in {64, 128}                           */
+    CHELA_ERR_BAD_CHUNK       = -4, /* chunk not in the supported set for this dtype       */
+    CHELA_ERR_MISALIGNED      = -5, /* a tensor pointer is not 16-byte aligned             */
+    CHELA_ERR_ALIASING        = -6, /* an output range overlaps an input or another output */
+    CHELA_ERR_WORKSPACE       = -7, /* caller workspace too small / allocation failed      */
+    CHELA_ERR_HIP             = -8  /* a HIP call failed (launch, allocation, no device)   */
+};
+
+enum { CHELA_DTYPE_BF16 = 0, CHELA_DTYPE_F32 = 1 };
+
+/* Forward, bf16 I/O, fp32 accumulation (Sec. 4.1; Eq. 2 with the causal mask).
+ * Q, K: [B,H,N,dk] in; V: [B,H,N,dv] in; O: [B,H,N,dv] out. */
+int chela_linattn_fwd(const void *Q, const void *K, const void *V, void *O,
+                      int B, int H, int N, int dk, int dv, int chunk, void *stream);
+
+/* Backward of the map above, bf16 I/O, fp32 accumulation.  Nothing is saved by
+ * the forward call: the states are recomputed from Q, K, V, dO.
+ *   dQ_t = sum_{s<=t} (dO_t . v_s) k_s
+ *   dK_s = sum_{t>=s} (dO_t . v_s) q_t
+ *   dV_s = sum_{t>=s} (q_t . k_s) dO_t
+ * dO: [B,H,N,dv] in; dQ, dK: [B,H,N,dk] out; dV: [B,H,N,dv] out. */
+int chela_linattn_bwd(const void *Q, const void *K, const void *V, const void *dO,
+                      void *dQ, void *dK, void *dV,
+                      int B, int H, int N, int dk, int dv, int chunk, void *stream);
+
+/* The same two maps with fp32 tensors and fp32 arithmetic throughout. */
+int chela_linattn_fwd_f32(const void *Q, const void *K, const void *V, void *O,
+                          int B, int H, int N, int dk, int dv, int chunk, void *stream);
+int chela_linattn_bwd_f32(const void *Q, const void *K, const void *V, const void *dO,
+                          void *dQ, void *dK, void *dV,
+                          int B, int H, int N, int dk, int dv, int chunk, void *stream);
+
+/* Bytes of device scratch one call with these arguments needs (0 if the shape
+ * needs none or the arguments are invalid).  The size is O(B*H*dk*dv*segments)
+ * with a bounded number of segments per (b,h): it does not grow with N once
+ * the GPU is full, which is the fixed-memory property claimed in Sec. 1. */
+size_t chela_linattn_workspace_bytes(int B, int H, int N, int dk, int dv, int chunk,
+                                     int is_bwd, int dtype);
+
+/* Hand the library a caller-owned device buffer to use as scratch (256-byte
+ * aligned).  NULL/0 returns to the internal allocation.  The buffer must stay
+ * valid until every call that used it has finished. */
+int chela_set_workspace(void *dev_ptr, size_t bytes);
+
+/* Human-readable name of a status code (static storage, never NULL). */
+const char *chela_status_string(int status);
+
+/* CHELA_VERSION of the loaded library. */
+int chela_version(void);
+
+/* Free the internal workspace (synchronises the device).  Safe to call twice. */
+void chela_shutdown(void);
+
+/* ---- per-kernel timing aid (for benchmarks; off by default) -------------------------------------------
+ * While enabled, every kernel the library launches is bracketed by two HIP events recorded on the stream
+ * the kernel is launched on.  Kernel classes are numbered 0 .. chela_profile_num_kernels()-1.
+ * chela_profile_read() waits for the recorded events and returns, for class `id`, how many launches were
+ * recorded since the last chela_profile_reset() and their summed duration in milliseconds.
+ * Not thread-safe against concurrent launches; returns CHELA_ERR_BAD_SHAPE for an unknown id. */
+int chela_profile_enable(int on);
+int chela_profile_num_kernels(void);
+const char *chela_profile_kernel_name(int id);
+int chela_profile_read(int id, long long *launches, double *total_ms);
+void chela_profile_reset(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CHELA_H */

@@ -1,0 +1,170 @@
+"""Thin ctypes binding of libchela.so (see include/chela.h).
+
+Argument marshalling only: torch tensors supply device pointers and the current HIP stream; every step of
+the computation runs in the library's kernels.  There is no fallback: if the library is missing or a call
+returns an error status, an exception is raised.
+"""
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libchela.so")
+
+DTYPE_BF16 = 0
+DTYPE_F32 = 1
+
+_lib = None
+
+
+class ChelaError(RuntimeError):
+    def __init__(self, status: int, msg: str):
+        super().__init__("libchela status %d: %s" % (status, msg))
+        self.status = status
+
+
+def lib() -> ctypes.CDLL:
+    """Load libchela.so (built by `python -m paper_2406_08128_amd.build`); raises if it is absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            "%s not found: build it with `python -m paper_2406_08128_amd.build` (there is no CPU fallback)" % LIB_PATH)
+    L = ctypes.CDLL(LIB_PATH)
+    vp, i, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+    for name in ("chela_linattn_fwd", "chela_linattn_fwd_f32"):
+        f = getattr(L, name)
+        f.argtypes = [vp, vp, vp, vp, i, i, i, i, i, i, vp]
+        f.restype = i
+    for name in ("chela_linattn_bwd", "chela_linattn_bwd_f32"):
+        f = getattr(L, name)
+        f.argtypes = [vp, vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, vp]
+        f.restype = i
+    L.chela_linattn_workspace_bytes.argtypes = [i, i, i, i, i, i, i, i]
+    L.chela_linattn_workspace_bytes.restype = sz
+    L.chela_set_workspace.argtypes = [vp, sz]
+    L.chela_set_workspace.restype = i
+    L.chela_status_string.argtypes = [i]
+    L.chela_status_string.restype = ctypes.c_char_p
+    L.chela_version.argtypes = []
+    L.chela_version.restype = i
+    L.chela_shutdown.argtypes = []
+    L.chela_shutdown.restype = None
+    L.chela_profile_enable.argtypes = [i]
+    L.chela_profile_enable.restype = i
+    L.chela_profile_num_kernels.argtypes = []
+    L.chela_profile_num_kernels.restype = i
+    L.chela_profile_kernel_name.argtypes = [i]
+    L.chela_profile_kernel_name.restype = ctypes.c_char_p
+    L.chela_profile_read.argtypes = [i, ctypes.POINTER(ctypes.c_longlong), ctypes.POINTER(ctypes.c_double)]
+    L.chela_profile_read.restype = i
+    L.chela_profile_reset.argtypes = []
+    L.chela_profile_reset.restype = None
+    _lib = L
+    return L
+
+
+def status_string(status: int) -> str:
+    return lib().chela_status_string(int(status)).decode()
+
+
+def _check(status: int) -> None:
+    if status != 0:
+        raise ChelaError(status, status_string(status))
+
+
+def _stream_ptr(stream: Optional[torch.cuda.Stream]) -> int:
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return int(s.cuda_stream)
+
+
+def _suffix(t: torch.Tensor) -> Tuple[str, int]:
+    if t.dtype == torch.bfloat16:
+        return "", DTYPE_BF16
+    if t.dtype == torch.float32:
+        return "_f32", DTYPE_F32
+    raise TypeError("chela_linattn: tensors must be bfloat16 or float32, got %s" % t.dtype)
+
+
+def _dims(Q, K, V):
+    if Q.dim() != 4 or K.shape != Q.shape or V.dim() != 4 or V.shape[:3] != Q.shape[:3]:
+        raise ValueError("expected Q, K: [B,H,N,dk] and V: [B,H,N,dv]")
+    for t in (Q, K, V):
+        if not t.is_cuda or not t.is_contiguous():
+            raise ValueError("tensors must be contiguous device tensors")
+        if t.dtype != Q.dtype:
+            raise TypeError("all tensors must share one dtype")
+    B, H, N, dk = Q.shape
+    return B, H, N, dk, V.shape[3]
+
+
+def chela_linattn_fwd(Q, K, V, O=None, chunk: int = 64, stream=None):
+    """O = causal linear attention of (Q, K, V); enqueues on the current (or given) stream."""
+    B, H, N, dk, dv = _dims(Q, K, V)
+    sfx, _ = _suffix(Q)
+    if O is None:
+        O = torch.empty((B, H, N, dv), dtype=Q.dtype, device=Q.device)
+    f = getattr(lib(), "chela_linattn_fwd" + sfx)
+    with torch.cuda.device(Q.device):
+        _check(f(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), B, H, N, dk, dv, int(chunk),
+                 _stream_ptr(stream)))
+    return O
+
+
+def chela_linattn_bwd(Q, K, V, dO, dQ=None, dK=None, dV=None, chunk: int = 64, stream=None):
+    """(dQ, dK, dV) for upstream gradient dO; nothing from the forward call is needed."""
+    B, H, N, dk, dv = _dims(Q, K, V)
+    if dO.shape != V.shape or dO.dtype != Q.dtype or not dO.is_contiguous():
+        raise ValueError("dO must match V")
+    sfx, _ = _suffix(Q)
+    dQ = torch.empty_like(Q) if dQ is None else dQ
+    dK = torch.empty_like(K) if dK is None else dK
+    dV = torch.empty_like(V) if dV is None else dV
+    f = getattr(lib(), "chela_linattn_bwd" + sfx)
+    with torch.cuda.device(Q.device):
+        _check(f(Q.data_ptr(), K.data_ptr(), V.data_ptr(), dO.data_ptr(), dQ.data_ptr(), dK.data_ptr(),
+                 dV.data_ptr(), B, H, N, dk, dv, int(chunk), _stream_ptr(stream)))
+    return dQ, dK, dV
+
+
+def chela_linattn_workspace_bytes(B, H, N, dk, dv, chunk, is_bwd, dtype) -> int:
+    return int(lib().chela_linattn_workspace_bytes(B, H, N, dk, dv, chunk, int(bool(is_bwd)), int(dtype)))
+
+
+def chela_set_workspace(buf: Optional[torch.Tensor]) -> None:
+    if buf is None:
+        _check(lib().chela_set_workspace(None, 0))
+    else:
+        _check(lib().chela_set_workspace(buf.data_ptr(), buf.numel() * buf.element_size()))
+
+
+def chela_version() -> int:
+    return int(lib().chela_version())
+
+
+def chela_shutdown() -> None:
+    lib().chela_shutdown()
+
+
+def chela_profile_enable(on: bool) -> None:
+    _check(lib().chela_profile_enable(int(bool(on))))
+
+
+def chela_profile_reset() -> None:
+    lib().chela_profile_reset()
+
+
+def chela_profile_read() -> dict:
+    """{kernel class name: (launches, total_ms)} for the launches recorded since the last reset."""
+    L = lib()
+    out = {}
+    for k in range(L.chela_profile_num_kernels()):
+        n = ctypes.c_longlong(0)
+        ms = ctypes.c_double(0.0)
+        _check(L.chela_profile_read(k, ctypes.byref(n), ctypes.byref(ms)))
+        if n.value:
+            out[L.chela_profile_kernel_name(k).decode()] = (int(n.value), float(ms.value))
+    return out

@@ -1,0 +1,342 @@
+// Host side of libchela.so: argument validation, work partitioning, scratch management, dispatch.
+// Every check below runs before the first HIP call so that a rejected call has touched nothing.
+#include "../../include/chela.h"
+#include "chela_internal.h"
+
+#include <cstdlib>
+#include <mutex>
+#include <vector>
+
+namespace chela {
+
+static int env_int(const char* name, int dflt)
+{
+    const char* s = std::getenv(name);
+    if (!s || !*s) return dflt;
+    return std::atoi(s);
+}
+
+// Segment length: long enough that the per-segment state traffic (one d_k x d_v fp32 state written, scanned
+// and read back per segment) stays a small fraction of the segment's own Q/K/V bytes, short enough that
+// B*H*n_seg workgroups fill 256 compute units several times over.
+Plan make_plan(long BH, int N, int dk, int dv, int chunk, int dtype, bool is_bwd)
+{
+    Plan p{};
+    p.chunk = chunk;
+    p.state_elems = (size_t)dk * dv;
+    if (BH <= 0 || N <= 0) { p.seg_len = chunk; p.n_seg = 0; p.ws_bytes = 0; return p; }
+    const long n_chunks = ((long)N + chunk - 1) / chunk;
+    long target_wgs = env_int("CHELA_TARGET_WGS", 1024);
+    long min_seg_tokens = env_int("CHELA_MIN_SEG_TOKENS", (dk >= 128 && dv >= 128) ? 1024 : 512);
+    long min_cps = (min_seg_tokens + chunk - 1) / chunk;
+    if (min_cps < 1) min_cps = 1;
+    long cps = (n_chunks * BH) / target_wgs;      // chunks per segment that would give target_wgs groups
+    if (cps < min_cps) cps = min_cps;
+    int forced = env_int("CHELA_SEG_TOKENS", 0);
+    if (forced > 0) cps = (forced + chunk - 1) / chunk;
+    if (cps > n_chunks) cps = n_chunks;
+    if (cps < 1) cps = 1;
+    p.seg_len = (int)(cps * chunk);
+    p.n_seg = (int)((n_chunks + cps - 1) / cps);
+    const int n_states = (dtype == CHELA_DTYPE_BF16 && is_bwd) ? 2 : 1;   // fp32 bwd reuses one array 3 times
+    p.ws_bytes = (p.n_seg > 1) ? (size_t)BH * p.n_seg * p.state_elems * sizeof(float) * n_states : 0;
+    return p;
+}
+
+// ------------------------------------------------------------------ per-kernel timing aid
+struct ProfRec { int id; hipEvent_t a, b; };
+static bool g_prof_on = false;
+static std::vector<ProfRec> g_prof;          // records in use
+static std::vector<ProfRec> g_prof_free;     // event pairs to re-use
+static const char* const kKernelNames[KID_COUNT] = {
+    "bf16_seg_state_kernel", "scan_states_kernel", "bf16_fwd_sweep_kernel", "bf16_bwd_sweep_kernel",
+    "f32_seg_state_kernel", "f32_sweep_kernel"};
+
+ProfScope::ProfScope(int id, hipStream_t s) : slot(-1), st(s)
+{
+    if (!g_prof_on) return;
+    ProfRec r{};
+    if (!g_prof_free.empty()) { r = g_prof_free.back(); g_prof_free.pop_back(); }
+    else if (hipEventCreate(&r.a) != hipSuccess || hipEventCreate(&r.b) != hipSuccess) return;
+    r.id = id;
+    (void)hipEventRecord(r.a, st);
+    g_prof.push_back(r);
+    slot = (int)g_prof.size() - 1;
+}
+
+ProfScope::~ProfScope()
+{
+    if (slot >= 0) (void)hipEventRecord(g_prof[slot].b, st);
+}
+
+// ------------------------------------------------------------------ scratch
+static std::mutex g_mu;
+static void* g_user_ws = nullptr;
+static size_t g_user_bytes = 0;
+static constexpr int kMaxDev = 64;
+static void* g_own_ws[kMaxDev] = {nullptr};
+static size_t g_own_bytes[kMaxDev] = {0};
+
+static int get_workspace(size_t bytes, float** out)
+{
+    *out = nullptr;
+    if (bytes == 0) return CHELA_OK;
+    std::lock_guard<std::mutex> lk(g_mu);
+    if (g_user_ws) {
+        if (bytes > g_user_bytes) return CHELA_ERR_WORKSPACE;
+        *out = (float*)g_user_ws;
+        return CHELA_OK;
+    }
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return CHELA_ERR_HIP;
+    if (dev < 0 || dev >= kMaxDev) return CHELA_ERR_HIP;
+    if (g_own_bytes[dev] < bytes) {
+        if (g_own_ws[dev]) { (void)hipDeviceSynchronize(); (void)hipFree(g_own_ws[dev]); }
+        g_own_ws[dev] = nullptr; g_own_bytes[dev] = 0;
+        size_t want = bytes + bytes / 4;
+        void* p = nullptr;
+        if (hipMalloc(&p, want) != hipSuccess) { (void)hipGetLastError(); return CHELA_ERR_WORKSPACE; }
+        g_own_ws[dev] = p; g_own_bytes[dev] = want;
+    }
+    *out = (float*)g_own_ws[dev];
+    return CHELA_OK;
+}
+
+// ------------------------------------------------------------------ validation
+struct Range { const char* p; size_t n; };
+static bool overlap(const Range& a, const Range& b)
+{
+    if (!a.n || !b.n) return false;
+    return a.p < b.p + b.n && b.p < a.p + a.n;
+}
+
+static int validate(const void* const* in, const size_t* in_bytes, int n_in,
+                    void* const* out, const size_t* out_bytes, int n_out,
+                    int B, int H, int N, int dk, int dv, int chunk, int dtype, bool* empty)
+{
+    *empty = false;
+    if (B < 0 || H < 0 || N < 0) return CHELA_ERR_BAD_SHAPE;
+    if (!((dk == 64 || dk == 128) && (dv == 64 || dv == 128))) return CHELA_ERR_UNSUPPORTED_DIM;
+    if (dtype == CHELA_DTYPE_BF16) { if (!(chunk == 64 || chunk == 128)) return CHELA_ERR_BAD_CHUNK; }
+    else { if (!(chunk == 16 || chunk == 32 || chunk == 64)) return CHELA_ERR_BAD_CHUNK; }
+    const unsigned long long elems = (unsigned long long)B * (unsigned long long)H * (unsigned long long)N;
+    if (elems > (1ull << 40)) return CHELA_ERR_BAD_SHAPE;
+    if ((unsigned long long)B * (unsigned long long)H > 0x7fffffffull) return CHELA_ERR_BAD_SHAPE;
+    if (elems == 0) { *empty = true; return CHELA_OK; }
+    for (int i = 0; i < n_in; ++i) if (!in[i]) return CHELA_ERR_NULL_POINTER;
+    for (int i = 0; i < n_out; ++i) if (!out[i]) return CHELA_ERR_NULL_POINTER;
+    for (int i = 0; i < n_in; ++i) if ((uintptr_t)in[i] & 15u) return CHELA_ERR_MISALIGNED;
+    for (int i = 0; i < n_out; ++i) if ((uintptr_t)out[i] & 15u) return CHELA_ERR_MISALIGNED;
+    for (int o = 0; o < n_out; ++o) {
+        Range ro{(const char*)out[o], out_bytes[o]};
+        for (int i = 0; i < n_in; ++i)
+            if (overlap(ro, Range{(const char*)in[i], in_bytes[i]})) return CHELA_ERR_ALIASING;
+        for (int o2 = o + 1; o2 < n_out; ++o2)
+            if (overlap(ro, Range{(const char*)out[o2], out_bytes[o2]})) return CHELA_ERR_ALIASING;
+    }
+    return CHELA_OK;
+}
+
+static int f32_effective_chunk(int dk, int dv, int chunk)
+{
+    // The fp32 kernel keeps Q, K, V tiles, the score tile and the whole state in LDS (160 KB per workgroup).
+    auto lds = [&](int c) {
+        return sizeof(float) * ((size_t)2 * c * (dk + 1) + (size_t)c * (dv + 1) + (size_t)c * (c + 1) +
+                                (size_t)dk * (dv + 1));
+    };
+    while (chunk > 16 && lds(chunk) > 150 * 1024) chunk /= 2;
+    return chunk;
+}
+
+// The backward sweep keeps four input tiles and two states in LDS; 128-token chunks only fit with 64-wide heads.
+static int bf16_bwd_effective_chunk(int dk, int dv, int chunk)
+{
+    return (chunk == 128 && dk == 64 && dv == 64) ? 128 : 64;
+}
+
+static int fwd_common(const void* Q, const void* K, const void* V, void* O, int B, int H, int N, int dk, int dv,
+                      int chunk, void* stream, int dtype)
+{
+    const size_t es = dtype == CHELA_DTYPE_BF16 ? 2 : 4;
+    const size_t th = (B > 0 && H > 0 && N > 0) ? (size_t)B * H * N : 0;
+    const void* in[3] = {Q, K, V};
+    const size_t inb[3] = {th * dk * es, th * dk * es, th * dv * es};
+    void* out[1] = {O};
+    const size_t outb[1] = {th * dv * es};
+    bool empty = false;
+    int rc = validate(in, inb, 3, out, outb, 1, B, H, N, dk, dv, chunk, dtype, &empty);
+    if (rc != CHELA_OK || empty) return rc;
+    const long BH = (long)B * H;
+    if (dtype == CHELA_DTYPE_F32) chunk = f32_effective_chunk(dk, dv, chunk);
+    Plan plan = make_plan(BH, N, dk, dv, chunk, dtype, false);
+    float* ws = nullptr;
+    rc = get_workspace(plan.ws_bytes, &ws);
+    if (rc != CHELA_OK) return rc;
+    hipError_t e = dtype == CHELA_DTYPE_BF16
+        ? launch_bf16_fwd(Q, K, V, O, BH, N, dk, dv, plan, false, ws, (hipStream_t)stream)
+        : launch_f32((const float*)Q, (const float*)K, (const float*)V, (float*)O, BH, N, dk, dv, plan, false, ws,
+                     (hipStream_t)stream);
+    return e == hipSuccess ? CHELA_OK : CHELA_ERR_HIP;
+}
+
+static int bwd_common(const void* Q, const void* K, const void* V, const void* dO, void* dQ, void* dK, void* dV,
+                      int B, int H, int N, int dk, int dv, int chunk, void* stream, int dtype)
+{
+    const size_t es = dtype == CHELA_DTYPE_BF16 ? 2 : 4;
+    const size_t th = (B > 0 && H > 0 && N > 0) ? (size_t)B * H * N : 0;
+    const void* in[4] = {Q, K, V, dO};
+    const size_t inb[4] = {th * dk * es, th * dk * es, th * dv * es, th * dv * es};
+    void* out[3] = {dQ, dK, dV};
+    const size_t outb[3] = {th * dk * es, th * dk * es, th * dv * es};
+    bool empty = false;
+    int rc = validate(in, inb, 4, out, outb, 3, B, H, N, dk, dv, chunk, dtype, &empty);
+    if (rc != CHELA_OK || empty) return rc;
+    const long BH = (long)B * H;
+    hipStream_t st = (hipStream_t)stream;
+    if (dtype == CHELA_DTYPE_BF16) {
+        Plan plan = make_plan(BH, N, dk, dv, bf16_bwd_effective_chunk(dk, dv, chunk), dtype, true);
+        float* ws = nullptr;
+        rc = get_workspace(plan.ws_bytes, &ws);
+        if (rc != CHELA_OK) return rc;
+        hipError_t e = launch_bf16_bwd(Q, K, V, dO, dQ, dK, dV, BH, N, dk, dv, plan, ws, st);
+        return e == hipSuccess ? CHELA_OK : CHELA_ERR_HIP;
+    }
+    // fp32: the gradient is three instances of the forward map (time-reversal duality):
+    //   dQ = LinAttn(query dO, key V, value K)             causal
+    //   dV = LinAttn(query K,  key Q, value dO)            anti-causal
+    //   dK = LinAttn(query V,  key dO, value Q)            anti-causal
+    const int c1 = f32_effective_chunk(dv, dk, chunk);   // query/key width dv, value width dk
+    const int c2 = f32_effective_chunk(dk, dv, chunk);
+    Plan p1 = make_plan(BH, N, dv, dk, c1, dtype, true);
+    Plan p2 = make_plan(BH, N, dk, dv, c2, dtype, true);
+    float* ws = nullptr;
+    rc = get_workspace(p1.ws_bytes > p2.ws_bytes ? p1.ws_bytes : p2.ws_bytes, &ws);
+    if (rc != CHELA_OK) return rc;
+    hipError_t e = launch_f32((const float*)dO, (const float*)V, (const float*)K, (float*)dQ, BH, N, dv, dk, p1,
+                              false, ws, st);
+    if (e == hipSuccess)
+        e = launch_f32((const float*)K, (const float*)Q, (const float*)dO, (float*)dV, BH, N, dk, dv, p2, true, ws, st);
+    if (e == hipSuccess)
+        e = launch_f32((const float*)V, (const float*)dO, (const float*)Q, (float*)dK, BH, N, dv, dk, p1, true, ws, st);
+    return e == hipSuccess ? CHELA_OK : CHELA_ERR_HIP;
+}
+
+}  // namespace chela
+
+using namespace chela;
+
+extern "C" {
+
+int chela_linattn_fwd(const void* Q, const void* K, const void* V, void* O, int B, int H, int N, int dk, int dv,
+                      int chunk, void* stream)
+{
+    return fwd_common(Q, K, V, O, B, H, N, dk, dv, chunk, stream, CHELA_DTYPE_BF16);
+}
+
+int chela_linattn_fwd_f32(const void* Q, const void* K, const void* V, void* O, int B, int H, int N, int dk,
+                          int dv, int chunk, void* stream)
+{
+    return fwd_common(Q, K, V, O, B, H, N, dk, dv, chunk, stream, CHELA_DTYPE_F32);
+}
+
+int chela_linattn_bwd(const void* Q, const void* K, const void* V, const void* dO, void* dQ, void* dK, void* dV,
+                      int B, int H, int N, int dk, int dv, int chunk, void* stream)
+{
+    return bwd_common(Q, K, V, dO, dQ, dK, dV, B, H, N, dk, dv, chunk, stream, CHELA_DTYPE_BF16);
+}
+
+int chela_linattn_bwd_f32(const void* Q, const void* K, const void* V, const void* dO, void* dQ, void* dK,
+                          void* dV, int B, int H, int N, int dk, int dv, int chunk, void* stream)
+{
+    return bwd_common(Q, K, V, dO, dQ, dK, dV, B, H, N, dk, dv, chunk, stream, CHELA_DTYPE_F32);
+}
+
+size_t chela_linattn_workspace_bytes(int B, int H, int N, int dk, int dv, int chunk, int is_bwd, int dtype)
+{
+    if (B <= 0 || H <= 0 || N <= 0) return 0;
+    if (!((dk == 64 || dk == 128) && (dv == 64 || dv == 128))) return 0;
+    if (dtype == CHELA_DTYPE_BF16) {
+        if (!(chunk == 64 || chunk == 128)) return 0;
+        if (is_bwd) chunk = bf16_bwd_effective_chunk(dk, dv, chunk);
+        return make_plan((long)B * H, N, dk, dv, chunk, dtype, is_bwd != 0).ws_bytes;
+    }
+    if (dtype != CHELA_DTYPE_F32) return 0;
+    if (!(chunk == 16 || chunk == 32 || chunk == 64)) return 0;
+    size_t a = make_plan((long)B * H, N, dk, dv, f32_effective_chunk(dk, dv, chunk), dtype, is_bwd != 0).ws_bytes;
+    if (is_bwd) {
+        size_t b = make_plan((long)B * H, N, dv, dk, f32_effective_chunk(dv, dk, chunk), dtype, true).ws_bytes;
+        if (b > a) a = b;
+    }
+    return a;
+}
+
+int chela_set_workspace(void* dev_ptr, size_t bytes)
+{
+    std::lock_guard<std::mutex> lk(g_mu);
+    if (dev_ptr == nullptr || bytes == 0) { g_user_ws = nullptr; g_user_bytes = 0; return CHELA_OK; }
+    if ((uintptr_t)dev_ptr & 255u) return CHELA_ERR_MISALIGNED;
+    g_user_ws = dev_ptr; g_user_bytes = bytes;
+    return CHELA_OK;
+}
+
+const char* chela_status_string(int status)
+{
+    switch (status) {
+        case CHELA_OK: return "CHELA_OK";
+        case CHELA_ERR_NULL_POINTER: return "CHELA_ERR_NULL_POINTER: a tensor pointer is NULL";
+        case CHELA_ERR_BAD_SHAPE: return "CHELA_ERR_BAD_SHAPE: negative or overflowing B, H or N";
+        case CHELA_ERR_UNSUPPORTED_DIM: return "CHELA_ERR_UNSUPPORTED_DIM: dk and dv must be 64 or 128";
+        case CHELA_ERR_BAD_CHUNK: return "CHELA_ERR_BAD_CHUNK: chunk must be 64/128 (bf16) or 16/32/64 (fp32)";
+        case CHELA_ERR_MISALIGNED: return "CHELA_ERR_MISALIGNED: pointer not sufficiently aligned";
+        case CHELA_ERR_ALIASING: return "CHELA_ERR_ALIASING: an output overlaps an input or another output";
+        case CHELA_ERR_WORKSPACE: return "CHELA_ERR_WORKSPACE: workspace too small or allocation failed";
+        case CHELA_ERR_HIP: return "CHELA_ERR_HIP: a HIP runtime call failed";
+        default: return "CHELA: unknown status";
+    }
+}
+
+int chela_version(void) { return CHELA_VERSION; }
+
+int chela_profile_enable(int on) { g_prof_on = (on != 0); return CHELA_OK; }
+
+int chela_profile_num_kernels(void) { return KID_COUNT; }
+
+const char* chela_profile_kernel_name(int id) { return (id >= 0 && id < KID_COUNT) ? kKernelNames[id] : ""; }
+
+int chela_profile_read(int id, long long* launches, double* total_ms)
+{
+    if (id < 0 || id >= KID_COUNT || !launches || !total_ms) return CHELA_ERR_BAD_SHAPE;
+    long long n = 0;
+    double ms = 0.0;
+    for (const ProfRec& r : g_prof) {
+        if (r.id != id) continue;
+        if (hipEventSynchronize(r.b) != hipSuccess) return CHELA_ERR_HIP;
+        float t = 0.f;
+        if (hipEventElapsedTime(&t, r.a, r.b) != hipSuccess) return CHELA_ERR_HIP;
+        ms += t; ++n;
+    }
+    *launches = n; *total_ms = ms;
+    return CHELA_OK;
+}
+
+void chela_profile_reset(void)
+{
+    for (const ProfRec& r : g_prof) g_prof_free.push_back(r);
+    g_prof.clear();
+}
+
+void chela_shutdown(void)
+{
+    std::lock_guard<std::mutex> lk(g_mu);
+    int cur = 0;
+    bool have_cur = false;
+    for (int d = 0; d < kMaxDev; ++d) {
+        if (!g_own_ws[d]) continue;
+        if (!have_cur) { have_cur = (hipGetDevice(&cur) == hipSuccess); }
+        if (hipSetDevice(d) == hipSuccess) { (void)hipDeviceSynchronize(); (void)hipFree(g_own_ws[d]); }
+        g_own_ws[d] = nullptr; g_own_bytes[d] = 0;
+    }
+    if (have_cur) (void)hipSetDevice(cur);
+}
+
+}  // extern "C"

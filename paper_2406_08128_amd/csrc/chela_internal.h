@@ -1,0 +1,51 @@
+// Internal declarations shared by the translation units of libchela.so (not installed).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace chela {
+
+// How one call is cut up.  A (b,h) sequence of N tokens is split into n_seg segments of seg_len tokens
+// (a multiple of the chunk); one workgroup walks one segment chunk by chunk with the d_k x d_v state in
+// registers, starting from a state that a cheap pre-pass (segment totals + scan) provides.
+struct Plan {
+    int chunk;     // tokens per chunk actually used by the kernels
+    int seg_len;   // tokens per segment, multiple of chunk
+    int n_seg;     // segments per (b,h); 1 means no pre-pass and no workspace
+    size_t state_elems;  // dk*dv
+    size_t ws_bytes;     // scratch bytes for the whole call
+};
+
+Plan make_plan(long BH, int N, int dk, int dv, int chunk, int dtype, bool is_bwd);
+
+// scan modes for scan_states()
+enum { SCAN_EXCL_PREFIX = 0, SCAN_INCL_PREFIX = 1, SCAN_EXCL_SUFFIX = 2 };
+
+// In-place scan over the segment axis of states[BH][n_seg][elems] (fp32).
+hipError_t scan_states(float* states, long BH, int n_seg, int elems, int mode, hipStream_t st);
+
+// fp32 path.  `rev` runs the same map on the time-reversed sequence (anti-causal mask), which is what the
+// gradient with respect to K and V is (the backward is three calls of this launcher).
+hipError_t launch_f32(const float* Q, const float* K, const float* V, float* O, long BH, int N, int dk, int dv,
+                      const Plan& plan, bool rev, float* ws, hipStream_t st);
+
+// bf16 path.
+hipError_t launch_bf16_fwd(const void* Q, const void* K, const void* V, void* O, long BH, int N, int dk, int dv,
+                           const Plan& plan, bool rev, float* ws, hipStream_t st);
+hipError_t launch_bf16_bwd(const void* Q, const void* K, const void* V, const void* dO, void* dQ, void* dK,
+                           void* dV, long BH, int N, int dk, int dv, const Plan& plan, float* ws, hipStream_t st);
+
+// Kernel classes for the per-kernel timing aid.
+enum { KID_SEG_STATE_BF16 = 0, KID_SCAN = 1, KID_FWD_SWEEP_BF16 = 2, KID_BWD_SWEEP_BF16 = 3, KID_SEG_STATE_F32 = 4,
+       KID_SWEEP_F32 = 5, KID_COUNT = 6 };
+
+// Brackets one kernel launch with HIP events on its stream while profiling is enabled; otherwise does nothing.
+struct ProfScope {
+    ProfScope(int id, hipStream_t st);
+    ~ProfScope();
+    int slot;
+    hipStream_t st;
+};
+
+}  // namespace chela

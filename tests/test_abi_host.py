@@ -1,0 +1,129 @@
+"""Host-side checks of the C ABI (no GPU): the library loads, exports every declared symbol, and rejects bad
+arguments before any HIP call."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "chela.h")
+
+
+@pytest.fixture(scope="module")
+def L():
+    from paper_2406_08128_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2406_08128_amd.build import build
+        build(verbose=False)
+    return binding.lib()
+
+
+def _declared_symbols():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(chela_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(L):
+    names = _declared_symbols()
+    assert "chela_linattn_fwd" in names and "chela_linattn_bwd" in names and len(names) >= 9
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_version_and_status_strings(L):
+    assert L.chela_version() == 100
+    for code in range(0, -9, -1):
+        s = L.chela_status_string(code).decode()
+        assert s.startswith("CHELA_")
+    assert b"unknown" in L.chela_status_string(-99)
+
+
+A = 0x10000        # fake, aligned, non-null "device pointers": validation must reject before touching them
+SZ = 1 << 30
+
+
+def _fwd(L, name="chela_linattn_fwd", Q=A, K=A + SZ, V=A + 2 * SZ, O=A + 3 * SZ, B=1, H=1, N=64, dk=64, dv=64,
+         chunk=64):
+    return getattr(L, name)(Q, K, V, O, B, H, N, dk, dv, chunk, None)
+
+
+def _bwd(L, name="chela_linattn_bwd", Q=A, K=A + SZ, V=A + 2 * SZ, dO=A + 3 * SZ, dQ=A + 4 * SZ, dK=A + 5 * SZ,
+         dV=A + 6 * SZ, B=1, H=1, N=64, dk=64, dv=64, chunk=64):
+    return getattr(L, name)(Q, K, V, dO, dQ, dK, dV, B, H, N, dk, dv, chunk, None)
+
+
+@pytest.mark.parametrize("name", ["chela_linattn_fwd", "chela_linattn_fwd_f32"])
+def test_fwd_argument_errors(L, name):
+    assert _fwd(L, name, Q=None) == -1
+    assert _fwd(L, name, O=None) == -1
+    assert _fwd(L, name, B=-1) == -2
+    assert _fwd(L, name, N=-5) == -2
+    assert _fwd(L, name, dk=48) == -3
+    assert _fwd(L, name, dv=256) == -3
+    assert _fwd(L, name, chunk=7) == -4
+    assert _fwd(L, name, chunk=0) == -4
+    assert _fwd(L, name, K=A + SZ + 2) == -5
+    assert _fwd(L, name, O=A + 8) == -5
+    assert _fwd(L, name, O=A) == -6                       # output == Q
+    assert _fwd(L, name, O=A + 2 * SZ + 64) == -6         # output overlaps V
+    # empty problems succeed without touching anything, even with null pointers
+    assert _fwd(L, name, N=0, Q=None, K=None, V=None, O=None) == 0
+    assert _fwd(L, name, B=0) == 0
+    assert _fwd(L, name, H=0) == 0
+
+
+def test_chunk_sets_differ_by_dtype(L):
+    assert _fwd(L, "chela_linattn_fwd", chunk=32) == -4
+    assert _fwd(L, "chela_linattn_fwd_f32", chunk=128) == -4
+
+
+@pytest.mark.parametrize("name", ["chela_linattn_bwd", "chela_linattn_bwd_f32"])
+def test_bwd_argument_errors(L, name):
+    assert _bwd(L, name, dO=None) == -1
+    assert _bwd(L, name, dV=None) == -1
+    assert _bwd(L, name, H=-2) == -2
+    assert _bwd(L, name, dk=32) == -3
+    assert _bwd(L, name, chunk=1) == -4
+    assert _bwd(L, name, dK=A + 5 * SZ + 4) == -5
+    assert _bwd(L, name, dQ=A + 3 * SZ) == -6             # dQ == dO
+    assert _bwd(L, name, dK=A + 4 * SZ) == -6             # dK == dQ
+    assert _bwd(L, name, N=0) == 0
+
+
+def test_shape_overflow_is_rejected(L):
+    assert _fwd(L, B=1 << 20, H=1 << 20, N=1 << 20) == -2
+
+
+def test_workspace_bytes(L):
+    w = L.chela_linattn_workspace_bytes
+    assert w(0, 1, 64, 64, 64, 64, 0, 0) == 0
+    assert w(1, 1, 64, 64, 64, 64, 0, 0) == 0                     # one segment: no scratch
+    assert w(1, 1, 64, 48, 64, 64, 0, 0) == 0                     # invalid -> 0
+    fwd = w(4, 12, 16384, 64, 64, 64, 0, 0)
+    bwd = w(4, 12, 16384, 64, 64, 64, 1, 0)
+    assert fwd > 0 and bwd == 2 * fwd
+    assert fwd % (48 * 64 * 64 * 4) == 0
+    # fixed-memory property: once the GPU is full the scratch does not grow with N
+    assert w(4, 12, 65536, 64, 64, 64, 0, 0) <= 2 * w(4, 12, 32768, 64, 64, 64, 0, 0)
+    assert w(4, 12, 1 << 20, 64, 64, 64, 0, 0) <= 2 * w(4, 12, 1 << 19, 64, 64, 64, 0, 0) + 1
+    assert w(4, 12, 1 << 20, 64, 64, 64, 0, 0) < 64 * 48 * 64 * 64 * 4
+
+
+def test_set_workspace_alignment(L):
+    assert L.chela_set_workspace(ctypes.c_void_p(0x1001), 1024) == -5
+    assert L.chela_set_workspace(None, 0) == 0
+
+
+def test_shutdown_is_idempotent(L):
+    L.chela_shutdown()
+    L.chela_shutdown()
+
+
+def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
+    from paper_2406_08128_amd import binding
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(FileNotFoundError):
+        binding.lib()

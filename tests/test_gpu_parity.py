@@ -1,0 +1,240 @@
+"""GPU parity: the HIP path (through the C ABI) against the fp64 CPU oracle on the same seeded inputs.
+
+Bars (rel-L2 over each whole output tensor): <= 1e-5 for fp32 I/O, <= 2e-2 for bf16 I/O with fp32 accumulation.
+The bf16 error budget is dominated by the final rounding of the output (2^-9/sqrt(3) ~ 1.1e-3) plus the bf16
+rounding of the score tile and of the carried state as matrix-core operands; anything above ~6e-3 is treated as a
+bug here, well inside the 2e-2 bar.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2406_08128_amd import binding
+from paper_2406_08128_amd.workloads import WORKLOADS, make_inputs, shrink, to_f64_numpy
+
+pytestmark = pytest.mark.gpu
+
+BAR = {"f32": 1e-5, "bf16": 2e-2}
+EXPECT = {"f32": 2e-6, "bf16": 6e-3}
+
+
+def _dev(x):
+    return {k: v.cuda() for k, v in x.items()}
+
+
+def _check(name, got, ref, dtype):
+    err = oracle.rel_l2(to_f64_numpy(got), ref)
+    print("   rel-L2 %-3s = %.3e" % (name, err), flush=True)
+    assert np.isfinite(err) and err <= BAR[dtype], (name, err)
+    assert err <= EXPECT[dtype], (name, err, "inside the bar but larger than rounding explains")
+    return err
+
+
+def _run_case(w, chunk, bwd, heads=None):
+    print("\ncase %s B%d H%d N%d dk%d dv%d chunk%d bwd=%s" % (w.name, w.B, w.H, w.N, w.dk, w.dv, chunk, bwd), flush=True)
+    x = make_inputs(w, with_dO=bwd)
+    d = _dev(x)
+    O = binding.chela_linattn_fwd(d["Q"], d["K"], d["V"], chunk=chunk)
+    if bwd:
+        dQ, dK, dV = binding.chela_linattn_bwd(d["Q"], d["K"], d["V"], d["dO"], chunk=chunk)
+    torch.cuda.synchronize()
+    if heads is None:
+        sel = lambda t: t
+    else:
+        idx = torch.tensor(heads)
+        sel = lambda t: t.reshape(1, w.B * w.H, w.N, -1)[:, idx.to(t.device)]
+    Qn, Kn, Vn = (to_f64_numpy(sel(x[n])) for n in "QKV")
+    _check("O", sel(O), oracle.fwd_recurrent(Qn, Kn, Vn), w.dtype)
+    if bwd:
+        ref = oracle.bwd_recurrent(Qn, Kn, Vn, to_f64_numpy(sel(x["dO"])))
+        for name, got, r in zip(("dQ", "dK", "dV"), (dQ, dK, dV), ref):
+            _check(name, sel(got), r, w.dtype)
+
+
+# ------------------------------------------------------------------------------------------ fp32
+def test_tiny_f32_workload_against_both_oracle_forms():
+    w = WORKLOADS["tiny_f32"]
+    x = make_inputs(w)
+    d = _dev(x)
+    O = binding.chela_linattn_fwd(d["Q"], d["K"], d["V"], chunk=64)
+    Qn, Kn, Vn = (to_f64_numpy(x[n]) for n in "QKV")
+    _check("O(quad)", O, oracle.fwd_quadratic(Qn, Kn, Vn), "f32")
+    _check("O(rec)", O, oracle.fwd_recurrent(Qn, Kn, Vn), "f32")
+
+
+@pytest.mark.parametrize("shape", [(1, 1, 1, 64, 64), (2, 3, 77, 64, 64), (1, 2, 1000, 64, 128), (1, 2, 1500, 128, 64),
+                                   (1, 1, 1100, 128, 128)])
+@pytest.mark.parametrize("chunk", [16, 32, 64])
+def test_f32_fwd_bwd_small(shape, chunk):
+    B, H, N, dk, dv = shape
+    w = shrink(WORKLOADS["tiny_f32"], B=B, H=H, N=N, dk=dk, dv=dv, seed=10 + N, backward=True)
+    _run_case(w, chunk, True)
+
+
+# ------------------------------------------------------------------------------------------ bf16, reduced sizes
+SMALL_BF16 = [
+    (1, 1, 64, 64, 64), (1, 1, 1, 64, 64), (2, 2, 1000, 64, 64), (1, 3, 2048, 64, 64), (2, 1, 1100, 64, 128),
+    (1, 2, 1300, 128, 64), (1, 2, 2500, 128, 128), (3, 1, 33, 128, 128),
+]
+
+
+@pytest.mark.parametrize("shape", SMALL_BF16)
+@pytest.mark.parametrize("chunk", [64, 128])
+def test_bf16_fwd_bwd_small(shape, chunk):
+    B, H, N, dk, dv = shape
+    w = shrink(WORKLOADS["lm_bf16"], B=B, H=H, N=N, dk=dk, dv=dv, seed=20 + N)
+    _run_case(w, chunk, True)
+
+
+def test_bf16_positive_feature_map_small():
+    w = shrink(WORKLOADS["long_bf16"], H=2, N=4096)
+    _run_case(w, 64, False)
+
+
+# ------------------------------------------------------------------------------------------ full-size workloads
+def _sample_heads(w, k=6):
+    bh = w.B * w.H
+    return sorted(set([0, 1, bh // 3, bh // 2, bh - 2, bh - 1]) & set(range(bh)))[:k]
+
+
+@pytest.mark.parametrize("chunk", [64, 128])
+def test_lra_bf16_full(chunk):
+    w = WORKLOADS["lra_bf16"]
+    _run_case(w, chunk, False, heads=_sample_heads(w))
+
+
+def test_lm_bf16_full():
+    w = WORKLOADS["lm_bf16"]
+    _run_case(w, 64, True, heads=_sample_heads(w))
+
+
+def test_long_bf16_full():
+    w = WORKLOADS["long_bf16"]
+    _run_case(w, 64, False, heads=[0, 7, 15])
+
+
+def test_mixed_bf16_full():
+    w = WORKLOADS["mixed_bf16"]
+    _run_case(w, 64, True, heads=_sample_heads(w))
+
+
+# ------------------------------------------------------------------------------------------ properties on the GPU
+def _small(dtype="bf16", N=1536, dk=64, dv=64, seed=99, B=1, H=2):
+    base = WORKLOADS["lm_bf16"] if dtype == "bf16" else WORKLOADS["tiny_f32"]
+    return shrink(base, B=B, H=H, N=N, dk=dk, dv=dv, seed=seed, backward=True)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_two_runs_are_bit_identical(dtype):
+    d = _dev(make_inputs(_small(dtype)))
+    a = binding.chela_linattn_fwd(d["Q"], d["K"], d["V"])
+    b = binding.chela_linattn_fwd(d["Q"], d["K"], d["V"])
+    ga = binding.chela_linattn_bwd(d["Q"], d["K"], d["V"], d["dO"])
+    gb = binding.chela_linattn_bwd(d["Q"], d["K"], d["V"], d["dO"])
+    assert torch.equal(a, b)
+    for x, y in zip(ga, gb):
+        assert torch.equal(x, y)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_power_of_two_scaling_is_bit_exact(dtype):
+    d = _dev(make_inputs(_small(dtype)))
+    O = binding.chela_linattn_fwd(d["Q"], d["K"], d["V"])
+    assert torch.equal(binding.chela_linattn_fwd(d["Q"] * 2, d["K"], d["V"]), O * 2)
+    assert torch.equal(binding.chela_linattn_fwd(d["Q"], d["K"] * 0.5, d["V"]), O * 0.5)
+    assert torch.equal(binding.chela_linattn_fwd(d["Q"], d["K"], d["V"] * 4), O * 4)
+
+
+def test_chunk_size_only_reassociates():
+    d = _dev(make_inputs(_small("bf16", N=2000)))
+    a = binding.chela_linattn_fwd(d["Q"], d["K"], d["V"], chunk=64).double()
+    b = binding.chela_linattn_fwd(d["Q"], d["K"], d["V"], chunk=128).double()
+    assert float((a - b).norm() / a.norm()) < 6e-3
+    d = _dev(make_inputs(_small("f32", N=700)))
+    outs = [binding.chela_linattn_fwd(d["Q"], d["K"], d["V"], chunk=c).double() for c in (16, 32, 64)]
+    for o in outs[1:]:
+        assert float((o - outs[0]).norm() / outs[0].norm()) < 2e-6
+
+
+def test_causality_on_device():
+    w = _small("bf16", N=1000)
+    d = _dev(make_inputs(w))
+    cut = 517
+    O = binding.chela_linattn_fwd(d["Q"], d["K"], d["V"])
+    d2 = {k: v.clone() for k, v in d.items()}
+    for k in "QKV":
+        d2[k][:, :, cut + 1:] = torch.randn_like(d2[k][:, :, cut + 1:].float()).to(d2[k].dtype)
+    O2 = binding.chela_linattn_fwd(d2["Q"], d2["K"], d2["V"])
+    assert torch.equal(O[:, :, :cut + 1], O2[:, :, :cut + 1])
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_backward_matches_three_forward_calls(dtype):
+    # time-reversal duality: dQ = F(dO, V, K); dV = flip F(flip K, flip Q, flip dO); dK = flip F(flip V, flip dO, flip Q)
+    d = _dev(make_inputs(_small(dtype, N=900, dk=64, dv=128)))
+    dQ, dK, dV = binding.chela_linattn_bwd(d["Q"], d["K"], d["V"], d["dO"])
+    fl = lambda t: t.flip(2).contiguous()
+    dQ2 = binding.chela_linattn_fwd(d["dO"], d["V"], d["K"])
+    dV2 = fl(binding.chela_linattn_fwd(fl(d["K"]), fl(d["Q"]), fl(d["dO"])))
+    dK2 = fl(binding.chela_linattn_fwd(fl(d["V"]), fl(d["dO"]), fl(d["Q"])))
+    tol = 8e-3 if dtype == "bf16" else 3e-6
+    for a, b in ((dQ, dQ2), (dK, dK2), (dV, dV2)):
+        assert float((a.double() - b.double()).norm() / b.double().norm()) < tol
+
+
+def test_outputs_stay_inside_their_buffers():
+    w = _small("bf16", N=777, dk=64, dv=128)
+    d = _dev(make_inputs(w))
+    pad = 4096
+    def padded(n):
+        buf = torch.full((n + 2 * pad,), 7.0, dtype=torch.bfloat16, device="cuda")
+        return buf, buf[pad:pad + n]
+    th = w.B * w.H * w.N
+    bO, vO = padded(th * w.dv)
+    bQ, vQ = padded(th * w.dk)
+    bK, vK = padded(th * w.dk)
+    bV, vV = padded(th * w.dv)
+    O = vO.view(w.B, w.H, w.N, w.dv)
+    binding.chela_linattn_fwd(d["Q"], d["K"], d["V"], O=O)
+    binding.chela_linattn_bwd(d["Q"], d["K"], d["V"], d["dO"], dQ=vQ.view(w.B, w.H, w.N, w.dk),
+                              dK=vK.view(w.B, w.H, w.N, w.dk), dV=vV.view(w.B, w.H, w.N, w.dv))
+    torch.cuda.synchronize()
+    for b in (bO, bQ, bK, bV):
+        assert bool((b[:pad] == 7.0).all()) and bool((b[-pad:] == 7.0).all())
+    ref = binding.chela_linattn_fwd(d["Q"], d["K"], d["V"])
+    assert torch.equal(ref, O)
+
+
+def test_caller_workspace_and_side_stream():
+    w = _small("bf16", N=4096, B=2, H=2)
+    d = _dev(make_inputs(w))
+    ref = binding.chela_linattn_fwd(d["Q"], d["K"], d["V"])
+    gref = binding.chela_linattn_bwd(d["Q"], d["K"], d["V"], d["dO"])
+    need = binding.chela_linattn_workspace_bytes(w.B, w.H, w.N, w.dk, w.dv, 64, True, binding.DTYPE_BF16)
+    assert need > 0
+    buf = torch.empty(need, dtype=torch.uint8, device="cuda")
+    torch.cuda.synchronize()
+    try:
+        binding.chela_set_workspace(buf)
+        s = torch.cuda.Stream()
+        with torch.cuda.stream(s):
+            O = binding.chela_linattn_fwd(d["Q"], d["K"], d["V"])
+            g = binding.chela_linattn_bwd(d["Q"], d["K"], d["V"], d["dO"])
+        s.synchronize()
+        assert torch.equal(O, ref)
+        for a, b in zip(g, gref):
+            assert torch.equal(a, b)
+        small = torch.empty(256, dtype=torch.uint8, device="cuda")
+        binding.chela_set_workspace(small)
+        with pytest.raises(binding.ChelaError) as ei:
+            binding.chela_linattn_fwd(d["Q"], d["K"], d["V"])
+        assert ei.value.status == -7
+    finally:
+        binding.chela_set_workspace(None)
+
+
+def test_empty_inputs_on_device():
+    z = torch.empty((2, 2, 0, 64), dtype=torch.bfloat16, device="cuda")
+    O = binding.chela_linattn_fwd(z, z, z)
+    assert O.shape == (2, 2, 0, 64)
