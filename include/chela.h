@@ -112,6 +112,12 @@ int chela_version(void);
 /* Free the internal workspace (synchronises the device).  Safe to call twice. */
 void chela_shutdown(void);
 
+/* Plain device-to-device copy of `bytes` bytes (a multiple of 16; both pointers 16-byte aligned) done by an
+ * ordinary streaming kernel of this library, enqueued on `stream`.  It is the "copy kernel of known size" that
+ * hardware byte counters (FETCH_SIZE / WRITE_SIZE) are calibrated against and that gives the copy bandwidth
+ * this GPU actually reaches; it is not part of the attention path. */
+int chela_copy_probe(const void *src, void *dst, size_t bytes, void *stream);
+
 /* ---- per-kernel timing aid (for benchmarks; off by default) -------------------------------------------
  * While enabled, every kernel the library launches is bracketed by two HIP events recorded on the stream
  * the kernel is launched on.  Kernel classes are numbered 0 .. chela_profile_num_kernels()-1.

@@ -53,6 +53,8 @@ def lib() -> ctypes.CDLL:
     L.chela_version.restype = i
     L.chela_shutdown.argtypes = []
     L.chela_shutdown.restype = None
+    L.chela_copy_probe.argtypes = [vp, vp, sz, vp]
+    L.chela_copy_probe.restype = i
     L.chela_profile_enable.argtypes = [i]
     L.chela_profile_enable.restype = i
     L.chela_profile_num_kernels.argtypes = []
@@ -147,6 +149,14 @@ def chela_version() -> int:
 
 def chela_shutdown() -> None:
     lib().chela_shutdown()
+
+
+def chela_copy_probe(src: torch.Tensor, dst: torch.Tensor, stream=None) -> None:
+    """Plain streaming copy src -> dst (same byte size) by the library's copy kernel."""
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes:
+        raise ValueError("size mismatch")
+    _check(lib().chela_copy_probe(src.data_ptr(), dst.data_ptr(), nbytes, _stream_ptr(stream)))
 
 
 def chela_profile_enable(on: bool) -> None:

@@ -16,6 +16,9 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed-fp32 VALU forms are switched off for every device compile (they have given wrong results on this pool)
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # keep MFMA accumulators in architectural VGPRs: every accumulator here is read back by the vector ALU
+         # (rounding to bf16) once per chunk, and AGPR<->VGPR copies would double that work
+         "-mllvm", "-amdgpu-mfma-vgpr-form",
          "-Wno-unused-command-line-argument", "-Wno-unknown-warning-option"]
 
 

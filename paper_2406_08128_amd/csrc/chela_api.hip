@@ -50,7 +50,7 @@ static std::vector<ProfRec> g_prof;          // records in use
 static std::vector<ProfRec> g_prof_free;     // event pairs to re-use
 static const char* const kKernelNames[KID_COUNT] = {
     "bf16_seg_state_kernel", "scan_states_kernel", "bf16_fwd_sweep_kernel", "bf16_bwd_sweep_kernel",
-    "f32_seg_state_kernel", "f32_sweep_kernel"};
+    "f32_seg_state_kernel", "f32_sweep_kernel", "copy_probe_kernel"};
 
 ProfScope::ProfScope(int id, hipStream_t s) : slot(-1), st(s)
 {
@@ -173,7 +173,7 @@ static int fwd_common(const void* Q, const void* K, const void* V, void* O, int 
     rc = get_workspace(plan.ws_bytes, &ws);
     if (rc != CHELA_OK) return rc;
     hipError_t e = dtype == CHELA_DTYPE_BF16
-        ? launch_bf16_fwd(Q, K, V, O, BH, N, dk, dv, plan, false, ws, (hipStream_t)stream)
+        ? launch_bf16_fwd(Q, K, V, O, BH, N, dk, dv, plan, ws, (hipStream_t)stream)
         : launch_f32((const float*)Q, (const float*)K, (const float*)V, (float*)O, BH, N, dk, dv, plan, false, ws,
                      (hipStream_t)stream);
     return e == hipSuccess ? CHELA_OK : CHELA_ERR_HIP;
@@ -297,6 +297,15 @@ const char* chela_status_string(int status)
 
 int chela_version(void) { return CHELA_VERSION; }
 
+int chela_copy_probe(const void* src, void* dst, size_t bytes, void* stream)
+{
+    if (bytes == 0) return CHELA_OK;
+    if (!src || !dst) return CHELA_ERR_NULL_POINTER;
+    if (((uintptr_t)src | (uintptr_t)dst | (uintptr_t)bytes) & 15u) return CHELA_ERR_MISALIGNED;
+    if (overlap(Range{(const char*)src, bytes}, Range{(const char*)dst, bytes})) return CHELA_ERR_ALIASING;
+    return launch_copy(src, dst, bytes, (hipStream_t)stream) == hipSuccess ? CHELA_OK : CHELA_ERR_HIP;
+}
+
 int chela_profile_enable(int on) { g_prof_on = (on != 0); return CHELA_OK; }
 
 int chela_profile_num_kernels(void) { return KID_COUNT; }
@@ -336,6 +345,8 @@ void chela_shutdown(void)
         if (hipSetDevice(d) == hipSuccess) { (void)hipDeviceSynchronize(); (void)hipFree(g_own_ws[d]); }
         g_own_ws[d] = nullptr; g_own_bytes[d] = 0;
     }
+    if (!have_cur) have_cur = (hipGetDevice(&cur) == hipSuccess);
+    free_bf16_resources();
     if (have_cur) (void)hipSetDevice(cur);
 }
 

@@ -22,8 +22,13 @@ Plan make_plan(long BH, int N, int dk, int dv, int chunk, int dtype, bool is_bwd
 // scan modes for scan_states()
 enum { SCAN_EXCL_PREFIX = 0, SCAN_INCL_PREFIX = 1, SCAN_EXCL_SUFFIX = 2 };
 
-// In-place scan over the segment axis of states[BH][n_seg][elems] (fp32).
-hipError_t scan_states(float* states, long BH, int n_seg, int elems, int mode, hipStream_t st);
+// In-place scan over the segment axis of n_arrays (1 or 2) arrays states[z][BH][n_seg][elems] (fp32), the arrays
+// `array_stride` floats apart, array z scanned in mode modes[z].  elems must be a multiple of 4.
+hipError_t scan_states(float* states, size_t array_stride, int n_arrays, const int* modes, long BH, int n_seg, int elems,
+                       hipStream_t st);
+
+// Streaming copy used to calibrate byte counters.
+hipError_t launch_copy(const void* src, void* dst, size_t bytes, hipStream_t st);
 
 // fp32 path.  `rev` runs the same map on the time-reversed sequence (anti-causal mask), which is what the
 // gradient with respect to K and V is (the backward is three calls of this launcher).
@@ -32,13 +37,16 @@ hipError_t launch_f32(const float* Q, const float* K, const float* V, float* O, 
 
 // bf16 path.
 hipError_t launch_bf16_fwd(const void* Q, const void* K, const void* V, void* O, long BH, int N, int dk, int dv,
-                           const Plan& plan, bool rev, float* ws, hipStream_t st);
+                           const Plan& plan, float* ws, hipStream_t st);
 hipError_t launch_bf16_bwd(const void* Q, const void* K, const void* V, const void* dO, void* dQ, void* dK,
                            void* dV, long BH, int N, int dk, int dv, const Plan& plan, float* ws, hipStream_t st);
 
+// Frees the arrival counters of the in-kernel scan (called by chela_shutdown).
+void free_bf16_resources();
+
 // Kernel classes for the per-kernel timing aid.
 enum { KID_SEG_STATE_BF16 = 0, KID_SCAN = 1, KID_FWD_SWEEP_BF16 = 2, KID_BWD_SWEEP_BF16 = 3, KID_SEG_STATE_F32 = 4,
-       KID_SWEEP_F32 = 5, KID_COUNT = 6 };
+       KID_SWEEP_F32 = 5, KID_COPY = 6, KID_COUNT = 7 };
 
 // Brackets one kernel launch with HIP events on its stream while profiling is enabled; otherwise does nothing.
 struct ProfScope {

@@ -2,26 +2,33 @@
 // (v_mfma_f32_32x32x16_bf16, fp32 accumulation), tiles staged in LDS, 64-wide wavefronts.
 //
 // Structure (Sec. 4.1): a (b,h) sequence is cut into segments of a few hundred to a few thousand tokens.
-//   pass 1  seg_state   : per segment, the total of X^T Y over its tokens (K^T V for the forward state)
-//   pass 2  scan_states : prefix (or suffix) over the segments of one (b,h)                 [fp32 file]
-//   pass 3  sweep       : one workgroup per segment walks its chunks with the state in accumulator registers:
+//   pre-pass  seg_state : per segment, the total of X^T Y over its tokens (K^T V for the forward state)
+//   scan                : prefix (or suffix) over the segments of one (b,h)                  [fp32 file]
+//   sweep               : one workgroup per segment walks its chunks with the state in accumulator registers:
 //                         masked left product inside the chunk, right product with the carried state, both summed
 //                         in registers before the result is written to HBM.
 //
 // Operand plumbing.  D = A B on a 32x32x16 MFMA wants, per lane, 8 consecutive k of one row of A and 8
-// consecutive k of one column of B.  Products that contract over the feature axis read row-major tiles
+// consecutive k of one column of B.  Products that contract over the feature axis read row-major LDS tiles
 // directly (ld_nat).  Products that contract over the token axis read the same row-major tiles through the
 // LDS transposing read ds_read_b64_tr_b16 (ld_tr), so no transposed copy is ever written.  A score tile
-// leaves the MFMA with 4 consecutive rows per lane; it is fed back as an A operand as it is, which permutes k
+// leaves the MFMA with 4 consecutive rows per lane; it is fed back as an operand as it is, which permutes k
 // inside each 16-wide step, and the partner operand is fetched with the same permutation (ld_tr_perm).
+// Every output tile is accumulated TRANSPOSED (features in rows, tokens in columns): a lane then owns 4
+// consecutive features of one token, one v_permlane32_swap makes that 8, and the tile leaves as 16-byte stores.
 #include "chela_internal.h"
+
+#include <cstdlib>
 
 namespace chela {
 
 typedef __bf16 bf16;
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
 typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
 
 constexpr int PAD = 8;   // bf16 elements of padding per LDS row (16 bytes): keeps 16-byte row reads conflict-free
@@ -65,7 +72,7 @@ __device__ __forceinline__ bf16x8 ld_tr(const bf16* T, int ld, int k0, int m0, i
     return cat(ds_tr(a), ds_tr(a + 4 * ld));
 }
 
-// Same, with the k order of an accumulator tile re-used as A operand: slot e of lane (r, h) is
+// Same, with the k order of an accumulator tile re-used as an operand: slot e of lane (r, h) is
 // row k0 + 8*(e/4) + 4h + (e%4).
 __device__ __forceinline__ bf16x8 ld_tr_perm(const bf16* T, int ld, int k0, int m0, int lane)
 {
@@ -74,58 +81,81 @@ __device__ __forceinline__ bf16x8 ld_tr_perm(const bf16* T, int ld, int k0, int 
     return cat(ds_tr(a), ds_tr(a + 8 * ld));
 }
 
-// Accumulator registers [base, base+8) rounded to bf16 (round-to-nearest-even): one 16-wide k step of an A operand.
-__device__ __forceinline__ bf16x8 cvt8(const f32x16& p, int base)
+// Two fp32 -> one register of two bf16 (round-to-nearest-even), first argument in the low half.
+template <bool NEG = false>
+__device__ __forceinline__ unsigned pack2(float lo, float hi)
 {
-    bf16x8 r;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) r[e] = (bf16)p[base + e];
-    return r;
-}
-
-__device__ __forceinline__ bf16x8 negate(bf16x8 v)
-{
-    typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
-    u32x4 u = __builtin_bit_cast(u32x4, v);
-    u ^= 0x80008000u;
-    return __builtin_bit_cast(bf16x8, u);
+    bf16x2 v;
+    v[0] = (bf16)(NEG ? -lo : lo);
+    v[1] = (bf16)(NEG ? -hi : hi);
+    return __builtin_bit_cast(unsigned, v);
 }
 
 // Accumulator tile D[row][col]: register 4a+b of lane (r, h) is D[8a + 4h + b][r].
-// Zero the strictly-upper part (row-index-in-tile > col-index-in-tile is kept or dropped by `keep_lower`):
-//   rows_are_keys = true : tile is P^T[s][t], keep s <= t  -> zero where row > col
-//   rows_are_keys = false: tile is P[t][s],   keep s <= t  -> zero where col > row
-template <bool ROWS_ARE_KEYS>
-__device__ __forceinline__ void mask_diag(f32x16& p, int lane)
+// Keep-masks for a DIAGONAL 32x32 score tile after packing to bf16 pairs (register 2a+p holds rows 8a+4h+2p, +1):
+//   KEYS_IN_ROWS = true : tile is P^T[s][t], keep s <= t, i.e. row <= col
+//   KEYS_IN_ROWS = false: tile is P[t][s],   keep s <= t, i.e. col <= row
+template <bool KEYS_IN_ROWS>
+__device__ __forceinline__ void make_masks(unsigned (&m)[8], int lane)
 {
     const int r = lane & 31, h = lane >> 5;
 #pragma unroll
     for (int a = 0; a < 4; ++a)
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            const int row = 8 * a + 4 * h + b;
-            const bool drop = ROWS_ARE_KEYS ? (row > r) : (r > row);
-            if (drop) p[4 * a + b] = 0.f;
+        for (int p = 0; p < 2; ++p) {
+            const int row0 = 8 * a + 4 * h + 2 * p, row1 = row0 + 1;
+            const bool k0 = KEYS_IN_ROWS ? (row0 <= r) : (r <= row0);
+            const bool k1 = KEYS_IN_ROWS ? (row1 <= r) : (r <= row1);
+            m[2 * a + p] = (k0 ? 0x0000ffffu : 0u) | (k1 ? 0xffff0000u : 0u);
         }
 }
 
-__device__ __forceinline__ int phys_row(int p, int N, bool rev) { return rev ? (N - 1 - p) : p; }
+// A score tile rounded to bf16 as two 16-wide k steps of an MFMA operand (k permuted as ld_tr_perm expects).
+__device__ __forceinline__ void cvt_tile(const f32x16& p, bf16x8& a0, bf16x8& a1)
+{
+    u32x4 lo, hi;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        lo[q] = pack2(p[2 * q], p[2 * q + 1]);
+        hi[q] = pack2(p[8 + 2 * q], p[8 + 2 * q + 1]);
+    }
+    a0 = __builtin_bit_cast(bf16x8, lo);
+    a1 = __builtin_bit_cast(bf16x8, hi);
+}
 
-// A C x D bf16 tile travels HBM -> registers (16-byte vectors, NV per thread) -> LDS (row stride D + PAD).
+__device__ __forceinline__ void cvt_tile_masked(const f32x16& p, const unsigned (&m)[8], bf16x8& a0, bf16x8& a1)
+{
+    u32x4 lo, hi;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        lo[q] = pack2(p[2 * q], p[2 * q + 1]) & m[q];
+        hi[q] = pack2(p[8 + 2 * q], p[8 + 2 * q + 1]) & m[4 + q];
+    }
+    a0 = __builtin_bit_cast(bf16x8, lo);
+    a1 = __builtin_bit_cast(bf16x8, hi);
+}
+
+// A C x D bf16 tile (C consecutive rows of a row-major [N][D] matrix, i.e. one contiguous block of memory) travels
+// HBM -> registers (16-byte vectors, NV per thread) -> LDS (row stride D + PAD).
 template <int C, int D>
 struct TileRegs {
     static constexpr int VPR = D / 8;              // 16-byte vectors per row
     static constexpr int NV = C * D / 8 / 256;     // vectors per thread
     uint4 v[NV];
-    __device__ __forceinline__ void load(const bf16* base, int c0, int p_end, int N, bool rev, int tid)
+    // `tile` points at the first row; rows >= valid_rows read as zero.
+    __device__ __forceinline__ void load(const bf16* tile, int valid_rows, int tid)
     {
+        const uint4* src = reinterpret_cast<const uint4*>(tile);
+        if (valid_rows >= C) {
 #pragma unroll
-        for (int n = 0; n < NV; ++n) {
-            const int x = tid + 256 * n, row = x / VPR, cv = x % VPR, p = c0 + row;
-            if (p < p_end)
-                v[n] = *reinterpret_cast<const uint4*>(base + (size_t)phys_row(p, N, rev) * D + cv * 8);
-            else
-                v[n] = make_uint4(0, 0, 0, 0);
+            for (int n = 0; n < NV; ++n) v[n] = src[tid + 256 * n];
+        } else {
+            const int lim = valid_rows * VPR;
+#pragma unroll
+            for (int n = 0; n < NV; ++n) {
+                const int x = tid + 256 * n;
+                v[n] = x < lim ? src[x] : make_uint4(0, 0, 0, 0);
+            }
         }
     }
     __device__ __forceinline__ void store(bf16* lds, int tid) const
@@ -138,25 +168,34 @@ struct TileRegs {
     }
 };
 
-// Store a 32x32 accumulator tile D[row][col] as bf16 into a row-major global matrix (leading dim ld);
-// tile rows are logical positions p = prow0 + 8a+4h+b, stored only when p < p_end.
-__device__ __forceinline__ void store_tile(bf16* G, int ld, int prow0, int col0, const f32x16& acc, int p_end, int N,
-                                           bool rev, int lane)
+// Store a TRANSPOSED 32x32 accumulator tile (register 4a+b of lane (r,h) = feature 8a+4h+b of token r) as bf16 into
+// rows [0,32) x columns [col0, col0+32) of the row-major matrix at `rows` (leading dimension ld).  The two half-waves
+// trade registers so that every lane ends up with 8 consecutive features of its token: two 16-byte stores per lane.
+__device__ __forceinline__ void store_tile_T(bf16* rows, int ld, int col0, const f32x16& acc, int valid_rows, int lane)
 {
     const int r = lane & 31, h = lane >> 5;
+    bf16* dst = rows + (size_t)r * ld + col0 + 8 * h;
 #pragma unroll
-    for (int a = 0; a < 4; ++a)
-#pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            const int p = prow0 + 8 * a + 4 * h + b;
-            if (p < p_end) G[(size_t)phys_row(p, N, rev) * ld + col0 + r] = (bf16)acc[4 * a + b];
-        }
+    for (int ap = 0; ap < 2; ++ap) {
+        const unsigned x0 = pack2(acc[8 * ap + 0], acc[8 * ap + 1]), x1 = pack2(acc[8 * ap + 2], acc[8 * ap + 3]);
+        const unsigned y0 = pack2(acc[8 * ap + 4], acc[8 * ap + 5]), y1 = pack2(acc[8 * ap + 6], acc[8 * ap + 7]);
+        // lanes 32..63 of x <-> lanes 0..31 of y
+        const u32x2 s0 = __builtin_amdgcn_permlane32_swap(x0, y0, false, false);
+        const u32x2 s1 = __builtin_amdgcn_permlane32_swap(x1, y1, false, false);
+        if (r < valid_rows) *reinterpret_cast<uint4*>(dst + 16 * ap) = make_uint4(s0[0], s1[0], s0[1], s1[1]);
+    }
 }
 
-// =============================================================================================== pass 1
+// =============================================================================================== pre-pass
 // out[a][b] = sum over the segment's tokens s of X[s][a] * Y[s][b]   (fp32, [DA][DB] row-major).
-// Two (X, Y) pairs can be served by one launch (blockIdx.z); `skip_seg[z]` names a segment whose total the
-// following scan never uses (-1: none).
+// Up to two (X, Y) pairs are served by one launch (blockIdx.z).  `skip_seg[z]` names a segment whose total the scan
+// never uses (-1: none).
+//
+// This kernel only reads, so it is built to stream: the four waves of a workgroup never meet inside the main loop.
+// Each wave takes every TOKW-th block of 16 tokens, passes it through a wave-private LDS patch (only to get the
+// token-contiguous MFMA operands out of the transposing read) and accumulates ALL output tiles for its tokens.  The
+// partial sums of the waves are added once at the end, in a fixed order.  With 128 x 128 outputs the 16 tiles do not
+// fit one wave's registers, so two waves share a token block and each owns half of the columns of Y.
 struct SegStateArgs {
     const bf16* X[2];
     const bf16* Y[2];
@@ -165,59 +204,146 @@ struct SegStateArgs {
 };
 
 template <int DA, int DB>
-__global__ __launch_bounds__(256) void bf16_seg_state_kernel(SegStateArgs args, int N, int seg_len, int n_seg, int rev)
+__global__ __launch_bounds__(256) void bf16_seg_state_kernel(SegStateArgs args, int N, int seg_len, int n_seg)
 {
-    constexpr int R = 64;
-    __shared__ __attribute__((aligned(16))) bf16 sX[R * (DA + PAD)];
-    __shared__ __attribute__((aligned(16))) bf16 sY[R * (DB + PAD)];
+    constexpr int AB = DA / 32, BB = DB / 32;
+    constexpr int WSPLIT = (AB * BB > 8) ? 2 : 1;   // waves sharing one token block
+    constexpr int BBW = BB / WSPLIT;                 // column tiles of Y per wave
+    constexpr int DBW = DB / WSPLIT;                 // columns of Y per wave
+    constexpr int NT = AB * BBW;                     // output tiles per wave
+    constexpr int TOKW = 4 / WSPLIT;                 // waves working on different token blocks
+    constexpr int T = 16;                            // tokens per block = one MFMA k step
+    constexpr int LDA = DA + PAD, LDB = DBW + PAD;
+    constexpr int NVX = T * DA / 8 / 64, NVY = T * DBW / 8 / 64;   // 16-byte vectors per lane per block
+    constexpr int PF = 3;                            // blocks in flight per wave
+    constexpr int STAGE_BYTES = 4 * (T * LDA + T * LDB) * 2;
+    constexpr int RED_BYTES = (TOKW / 2) * WSPLIT * NT * 1024 * 4;
+    constexpr int LDS_BYTES = STAGE_BYTES > RED_BYTES ? STAGE_BYTES : RED_BYTES;
+    __shared__ __attribute__((aligned(16))) unsigned char lds_raw[LDS_BYTES];
+
     const int z = blockIdx.z;
     const int seg = blockIdx.x;
     const long bh = blockIdx.y;
     if (seg == args.skip_seg[z]) return;
-    const bf16* X = args.X[z] + (size_t)bh * N * DA;
-    const bf16* Y = args.Y[z] + (size_t)bh * N * DB;
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int tl = w / WSPLIT, cgw = w % WSPLIT;
     const int p0 = seg * seg_len, p1 = min(N, p0 + seg_len);
-    constexpr int AB = DA / 32, BB = DB / 32, NT = AB * BB / 4;
+    const bf16* X = args.X[z] + ((size_t)bh * N + p0) * DA;
+    const bf16* Y = args.Y[z] + ((size_t)bh * N + p0) * DB + cgw * DBW;
+    bf16* sX = reinterpret_cast<bf16*>(lds_raw) + w * (T * LDA + T * LDB);
+    bf16* sY = sX + T * LDA;
+
+    const int ntok = p1 - p0;
+    const int nb_total = (ntok + T - 1) / T;
+    const int nblk = nb_total > tl ? (nb_total - tl + TOKW - 1) / TOKW : 0;   // blocks of this wave
+
     f32x16 acc[NT];
 #pragma unroll
     for (int n = 0; n < NT; ++n) acc[n] = zero16();
-    TileRegs<R, DA> rx;
-    TileRegs<R, DB> ry;
-    rx.load(X, p0, p1, N, rev, tid);
-    ry.load(Y, p0, p1, N, rev, tid);
-    for (int c0 = p0; c0 < p1; c0 += R) {
-        rx.store(sX, tid);
-        ry.store(sY, tid);
-        __syncthreads();
-        if (c0 + R < p1) {
-            rx.load(X, c0 + R, p1, N, rev, tid);
-            ry.load(Y, c0 + R, p1, N, rev, tid);
+
+    uint4 rx[PF][NVX], ry[PF][NVY];
+    auto load_block = [&](int u, int i) {
+        const int tok0 = (tl + TOKW * i) * T;          // first token of the block, relative to the segment
+        const int valid = ntok - tok0;
+        const bf16* xs = X + (size_t)tok0 * DA;
+        const bf16* ys = Y + (size_t)tok0 * DB;
+        if (valid >= T) {
+#pragma unroll
+            for (int n = 0; n < NVX; ++n) rx[u][n] = reinterpret_cast<const uint4*>(xs)[lane + 64 * n];
+#pragma unroll
+            for (int n = 0; n < NVY; ++n) {
+                const int x = lane + 64 * n, row = x / (DBW / 8), cv = x % (DBW / 8);
+                ry[u][n] = *reinterpret_cast<const uint4*>(ys + (size_t)row * DB + cv * 8);
+            }
+        } else {
+#pragma unroll
+            for (int n = 0; n < NVX; ++n) {
+                const int x = lane + 64 * n, row = x / (DA / 8);
+                rx[u][n] = row < valid ? reinterpret_cast<const uint4*>(xs)[x] : make_uint4(0, 0, 0, 0);
+            }
+#pragma unroll
+            for (int n = 0; n < NVY; ++n) {
+                const int x = lane + 64 * n, row = x / (DBW / 8), cv = x % (DBW / 8);
+                ry[u][n] = row < valid ? *reinterpret_cast<const uint4*>(ys + (size_t)row * DB + cv * 8)
+                                       : make_uint4(0, 0, 0, 0);
+            }
         }
+    };
+
 #pragma unroll
-        for (int n = 0; n < NT; ++n) {
-            const int id = w + 4 * n, ab = id / BB, bb = id % BB;
+    for (int u = 0; u < PF; ++u)
+        if (u < nblk) load_block(u, u);
+
+    for (int i0 = 0; i0 < nblk; i0 += PF) {
 #pragma unroll
-            for (int s0 = 0; s0 < R; s0 += 16)
-                acc[n] = mfma(ld_tr(sX, DA + PAD, s0, ab * 32, lane), ld_tr(sY, DB + PAD, s0, bb * 32, lane), acc[n]);
+        for (int u = 0; u < PF; ++u) {
+            const int i = i0 + u;
+            if (i < nblk) {
+#pragma unroll
+                for (int n = 0; n < NVX; ++n) {
+                    const int x = lane + 64 * n, row = x / (DA / 8), cv = x % (DA / 8);
+                    *reinterpret_cast<uint4*>(sX + row * LDA + cv * 8) = rx[u][n];
+                }
+#pragma unroll
+                for (int n = 0; n < NVY; ++n) {
+                    const int x = lane + 64 * n, row = x / (DBW / 8), cv = x % (DBW / 8);
+                    *reinterpret_cast<uint4*>(sY + row * LDB + cv * 8) = ry[u][n];
+                }
+                if (i + PF < nblk) load_block(u, i + PF);
+                __builtin_amdgcn_wave_barrier();
+                bf16x8 fa[AB], fb[BBW];
+#pragma unroll
+                for (int a = 0; a < AB; ++a) fa[a] = ld_tr(sX, LDA, 0, a * 32, lane);
+#pragma unroll
+                for (int b = 0; b < BBW; ++b) fb[b] = ld_tr(sY, LDB, 0, b * 32, lane);
+#pragma unroll
+                for (int a = 0; a < AB; ++a)
+#pragma unroll
+                    for (int b = 0; b < BBW; ++b) acc[a * BBW + b] = mfma(fa[a], fb[b], acc[a * BBW + b]);
+                __builtin_amdgcn_wave_barrier();
+            }
+        }
+    }
+
+    // add the partial sums of the TOKW waves that share a column group: tl >= TOKW/2 hand theirs over, then tl = 1
+    float* red = reinterpret_cast<float*>(lds_raw);
+    __syncthreads();
+#pragma unroll
+    for (int half = TOKW / 2; half >= 1; half /= 2) {
+        if (tl >= half && tl < 2 * half) {
+            float* dst = red + (size_t)((tl - half) * WSPLIT + cgw) * NT * 1024;
+#pragma unroll
+            for (int n = 0; n < NT; ++n)
+#pragma unroll
+                for (int k = 0; k < 16; ++k) dst[(n * 16 + k) * 64 + lane] = acc[n][k];
+        }
+        __syncthreads();
+        if (tl < half) {
+            const float* src = red + (size_t)(tl * WSPLIT + cgw) * NT * 1024;
+#pragma unroll
+            for (int n = 0; n < NT; ++n)
+#pragma unroll
+                for (int k = 0; k < 16; ++k) acc[n][k] += src[(n * 16 + k) * 64 + lane];
         }
         __syncthreads();
     }
-    float* o = args.out[z] + ((size_t)bh * n_seg + seg) * DA * DB;
+    if (tl != 0) return;
+    float* o = args.out[z] + ((size_t)bh * n_seg + seg) * DA * DB + cgw * DBW;
     const int r = lane & 31, h = lane >> 5;
 #pragma unroll
-    for (int n = 0; n < NT; ++n) {
-        const int id = w + 4 * n, ab = id / BB, bb = id % BB;
+    for (int a = 0; a < AB; ++a)
 #pragma unroll
-        for (int a = 0; a < 4; ++a)
+        for (int b = 0; b < BBW; ++b)
 #pragma unroll
-            for (int b = 0; b < 4; ++b)
-                o[(ab * 32 + 8 * a + 4 * h + b) * DB + bb * 32 + r] = acc[n][4 * a + b];
-    }
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+                    o[(a * 32 + 8 * q + 4 * h + k) * DB + b * 32 + r] = acc[a * BBW + b][4 * q + k];
 }
 
-// Load / keep a [DA][DB] fp32 state as accumulator tiles: tile id = w + 4n -> (ab, bb) = (id / BB, id % BB).
-template <int DA, int DB>
+// Load a [DA][DB] fp32 state as accumulator tiles: tile id = w + 4n -> (ab, bb) = (id / BB, id % BB).
+template <int DA, int DB, bool NEG>
 __device__ __forceinline__ void load_state(f32x16* acc, const float* src, int w, int lane)
 {
     constexpr int BB = DB / 32, NT = (DA / 32) * BB / 4;
@@ -228,14 +354,16 @@ __device__ __forceinline__ void load_state(f32x16* acc, const float* src, int w,
 #pragma unroll
         for (int a = 0; a < 4; ++a)
 #pragma unroll
-            for (int b = 0; b < 4; ++b)
-                acc[n][4 * a + b] = src ? src[(ab * 32 + 8 * a + 4 * h + b) * DB + bb * 32 + r] : 0.f;
+            for (int b = 0; b < 4; ++b) {
+                const float v = src ? src[(ab * 32 + 8 * a + 4 * h + b) * DB + bb * 32 + r] : 0.f;
+                acc[n][4 * a + b] = NEG ? -v : v;
+            }
     }
 }
 
 // Write a [DA][DB] state held as accumulator tiles into LDS as bf16, TRANSPOSED: dst[b][a] (row stride DA + PAD).
-// A lane owns 4 consecutive a for one b, i.e. 8 contiguous bytes of dst.
-template <int DA, int DB>
+// A lane owns 4 consecutive a for one b, i.e. 8 contiguous bytes of dst.  NEG writes the negated value.
+template <int DA, int DB, bool NEG>
 __device__ __forceinline__ void state_to_lds_T(bf16* dst, const f32x16* acc, int w, int lane)
 {
     constexpr int BB = DB / 32, NT = (DA / 32) * BB / 4;
@@ -245,20 +373,20 @@ __device__ __forceinline__ void state_to_lds_T(bf16* dst, const f32x16* acc, int
         const int id = w + 4 * n, ab = id / BB, bb = id % BB;
 #pragma unroll
         for (int a = 0; a < 4; ++a) {
-            bf16x4 v;
-#pragma unroll
-            for (int b = 0; b < 4; ++b) v[b] = (bf16)acc[n][4 * a + b];
-            *reinterpret_cast<bf16x4*>(dst + (bb * 32 + r) * (DA + PAD) + ab * 32 + 8 * a + 4 * h) = v;
+            u32x2 v;
+            v[0] = pack2<NEG>(acc[n][4 * a + 0], acc[n][4 * a + 1]);
+            v[1] = pack2<NEG>(acc[n][4 * a + 2], acc[n][4 * a + 3]);
+            *reinterpret_cast<u32x2*>(dst + (bb * 32 + r) * (DA + PAD) + ab * 32 + 8 * a + 4 * h) = v;
         }
     }
 }
 
 // =============================================================================================== forward sweep
 // One workgroup (4 waves) per (segment, bh).  Per chunk of C tokens:
-//   P^T = K Q^T (masked), O = P V + Q S_prev, store O, S += K^T V.
+//   P^T = K Q^T (masked), O^T = V^T P^T + S_prev^T Q^T, store O, S += K^T V.
 // Wave w owns output rows [32*tb, 32*tb+32) with tb = w % WT and NJ column tiles; it recomputes the score
 // tiles of its row block itself (matrix-core time is cheap here, LDS round trips and barriers are not).
-template <int C, int DK, int DV, bool REV>
+template <int C, int DK, int DV>
 __global__ __launch_bounds__(256) void bf16_fwd_sweep_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K,
                                                             const bf16* __restrict__ V, bf16* __restrict__ O,
                                                             const float* __restrict__ S0, int N, int seg_len, int n_seg)
@@ -275,7 +403,8 @@ __global__ __launch_bounds__(256) void bf16_fwd_sweep_kernel(const bf16* __restr
 
     const int seg = blockIdx.x;
     const long bh = blockIdx.y;
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int tb = w % WT, jg = w / WT;
     const bf16* Qb = Q + (size_t)bh * N * DK;
     const bf16* Kb = K + (size_t)bh * N * DK;
@@ -283,57 +412,66 @@ __global__ __launch_bounds__(256) void bf16_fwd_sweep_kernel(const bf16* __restr
     bf16* Ob = O + (size_t)bh * N * DV;
     const int p0 = seg * seg_len, p1 = min(N, p0 + seg_len);
 
+    unsigned maskK[8];
+    make_masks<true>(maskK, lane);
+
     f32x16 accS[NS];
-    load_state<DK, DV>(accS, (S0 != nullptr && seg > 0) ? S0 + ((size_t)bh * n_seg + seg) * DK * DV : nullptr, w, lane);
+    load_state<DK, DV, false>(accS, (S0 != nullptr && seg > 0) ? S0 + ((size_t)bh * n_seg + seg) * DK * DV : nullptr,
+                              w, lane);
 
     TileRegs<C, DK> rq, rk;
     TileRegs<C, DV> rv;
-    rq.load(Qb, p0, p1, N, REV, tid);
-    rk.load(Kb, p0, p1, N, REV, tid);
-    rv.load(Vb, p0, p1, N, REV, tid);
+    rq.load(Qb + (size_t)p0 * DK, p1 - p0, tid);
+    rk.load(Kb + (size_t)p0 * DK, p1 - p0, tid);
+    rv.load(Vb + (size_t)p0 * DV, p1 - p0, tid);
 
     for (int c0 = p0; c0 < p1; c0 += C) {
         rq.store(sQ, tid);
         rk.store(sK, tid);
         rv.store(sV, tid);
-        state_to_lds_T<DK, DV>(sST, accS, w, lane);
+        state_to_lds_T<DK, DV, false>(sST, accS, w, lane);
         __syncthreads();
         const bool more = c0 + C < p1;
         if (more) {
-            rq.load(Qb, c0 + C, p1, N, REV, tid);
-            rk.load(Kb, c0 + C, p1, N, REV, tid);
-            rv.load(Vb, c0 + C, p1, N, REV, tid);
+            rq.load(Qb + (size_t)(c0 + C) * DK, p1 - c0 - C, tid);
+            rk.load(Kb + (size_t)(c0 + C) * DK, p1 - c0 - C, tid);
+            rv.load(Vb + (size_t)(c0 + C) * DV, p1 - c0 - C, tid);
         }
-        bf16x8 aQ[DK / 16];
+        bf16x8 bQ[DK / 16];   // Q rows of this wave's token block: the B operand (n = token, k = feature i)
 #pragma unroll
-        for (int kk = 0; kk < DK / 16; ++kk) aQ[kk] = ld_nat(sQ, LDK, tb * 32, kk * 16, lane);
-        f32x16 accO[NJ];
+        for (int kk = 0; kk < DK / 16; ++kk) bQ[kk] = ld_nat(sQ, LDK, tb * 32, kk * 16, lane);
+        f32x16 accO[NJ];      // O^T tiles: rows = features j, columns = tokens t
 #pragma unroll
         for (int n = 0; n < NJ; ++n) accO[n] = zero16();
-        // inter-chunk part: Q S_prev
+        // inter-chunk part: S_prev^T Q^T
 #pragma unroll
         for (int n = 0; n < NJ; ++n)
 #pragma unroll
             for (int kk = 0; kk < DK / 16; ++kk)
-                accO[n] = mfma(aQ[kk], ld_nat(sST, LDK, (jg * NJ + n) * 32, kk * 16, lane), accO[n]);
-        // intra-chunk part: masked (Q K^T) V, key blocks sb <= tb
+                accO[n] = mfma(ld_nat(sST, LDK, (jg * NJ + n) * 32, kk * 16, lane), bQ[kk], accO[n]);
+        // intra-chunk part: V^T (masked K Q^T), key blocks sb <= tb
 #pragma unroll
         for (int sb = 0; sb < TB; ++sb) {
             if (sb <= tb) {
                 f32x16 pT = zero16();
 #pragma unroll
-                for (int kk = 0; kk < DK / 16; ++kk) pT = mfma(ld_nat(sK, LDK, sb * 32, kk * 16, lane), aQ[kk], pT);
-                if (sb == tb) mask_diag<true>(pT, lane);
-                const bf16x8 pa0 = cvt8(pT, 0), pa1 = cvt8(pT, 8);
+                for (int kk = 0; kk < DK / 16; ++kk) pT = mfma(ld_nat(sK, LDK, sb * 32, kk * 16, lane), bQ[kk], pT);
+                bf16x8 p0v, p1v;
+                if (sb == tb) cvt_tile_masked(pT, maskK, p0v, p1v);
+                else cvt_tile(pT, p0v, p1v);
 #pragma unroll
                 for (int n = 0; n < NJ; ++n) {
-                    accO[n] = mfma(pa0, ld_tr_perm(sV, LDV, sb * 32, (jg * NJ + n) * 32, lane), accO[n]);
-                    accO[n] = mfma(pa1, ld_tr_perm(sV, LDV, sb * 32 + 16, (jg * NJ + n) * 32, lane), accO[n]);
+                    accO[n] = mfma(ld_tr_perm(sV, LDV, sb * 32, (jg * NJ + n) * 32, lane), p0v, accO[n]);
+                    accO[n] = mfma(ld_tr_perm(sV, LDV, sb * 32 + 16, (jg * NJ + n) * 32, lane), p1v, accO[n]);
                 }
             }
         }
+        {
+            bf16* rows = Ob + (size_t)(c0 + tb * 32) * DV;
+            const int valid = p1 - (c0 + tb * 32);
 #pragma unroll
-        for (int n = 0; n < NJ; ++n) store_tile(Ob, DV, c0 + tb * 32, (jg * NJ + n) * 32, accO[n], p1, N, REV, lane);
+            for (int n = 0; n < NJ; ++n) store_tile_T(rows, DV, (jg * NJ + n) * 32, accO[n], valid, lane);
+        }
         // state update S += K^T V (not needed after the segment's last chunk)
         if (more) {
 #pragma unroll
@@ -352,11 +490,12 @@ __global__ __launch_bounds__(256) void bf16_fwd_sweep_kernel(const bf16* __restr
 // One workgroup per (segment, bh), walking the chunks from the LAST to the first, so that each input tile is
 // read once for all three gradients.  Two states live in accumulator registers, both stored transposed
 // ([dv][dk], lane = one feature i, 4 consecutive j):
-//   S^T : sum of V^T K over tokens before the current chunk.  It enters as the inclusive prefix at the end of
-//         the segment and is rolled BACK by one chunk per step (S_{c-1} = S_c - V_c^T K_c, fp32).
+//   -S^T: minus the sum of V^T K over tokens before the current chunk.  It enters as the inclusive prefix at the
+//         end of the segment and is rolled BACK by one chunk per step (S_{c-1} = S_c - V_c^T K_c, fp32); keeping
+//         the negative makes the roll-back a plain accumulate and the sign is restored for free when rounding.
 //   R^T : sum of dO^T Q over tokens after the current chunk; it grows by one chunk per step.
 // Per chunk:  dQ = dP K + dO S^T',  dK = dP^T Q + V R^T',  dV = P^T dO + K R,
-//             P = (Q K^T) o M,  dP = (dO V^T) o M.
+//             P = (Q K^T) o M,  dP = (dO V^T) o M, every output accumulated transposed.
 template <int C, int DK, int DV>
 __global__ __launch_bounds__(256) void bf16_bwd_sweep_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K,
                                                             const bf16* __restrict__ V, const bf16* __restrict__ dO,
@@ -379,7 +518,8 @@ __global__ __launch_bounds__(256) void bf16_bwd_sweep_kernel(const bf16* __restr
 
     const int seg = blockIdx.x;
     const long bh = blockIdx.y;
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int rb = w % WT, cg = w / WT;
     const bf16* Qb = Q + (size_t)bh * N * DK;
     const bf16* Kb = K + (size_t)bh * N * DK;
@@ -391,22 +531,25 @@ __global__ __launch_bounds__(256) void bf16_bwd_sweep_kernel(const bf16* __restr
     const int p0 = seg * seg_len, p1 = min(N, p0 + seg_len);
     const int n_ch = (p1 - p0 + C - 1) / C;
 
-    // states, transposed: [DV][DK]
-    f32x16 accST[NS], accRT[NS];
+    unsigned maskK[8], maskQ[8];
+    make_masks<true>(maskK, lane);
+    make_masks<false>(maskQ, lane);
+
+    // states, transposed: [DV][DK]; accNS holds MINUS S^T
+    f32x16 accNS[NS], accRT[NS];
     const size_t soff = ((size_t)bh * n_seg + seg) * DK * DV;
-    load_state<DV, DK>(accST, Send ? Send + soff : nullptr, w, lane);
-    load_state<DV, DK>(accRT, (Rnext != nullptr && seg < n_seg - 1) ? Rnext + soff : nullptr, w, lane);
-    const bool single = (Send == nullptr);   // one segment: S is built below instead of being read
+    load_state<DV, DK, true>(accNS, Send ? Send + soff : nullptr, w, lane);
+    load_state<DV, DK, false>(accRT, (Rnext != nullptr && seg < n_seg - 1) ? Rnext + soff : nullptr, w, lane);
 
     TileRegs<C, DK> rq, rk;
     TileRegs<C, DV> rv, rg;
 
-    if (single) {
-        // whole sequence in this workgroup: accumulate S^T = sum V^T K over all chunks first
+    if (Send == nullptr) {
+        // single segment: no pre-pass ran, build -S^T = -sum V^T K over the whole sequence here
         for (int ci = 0; ci < n_ch; ++ci) {
             const int c0 = p0 + ci * C;
-            rk.load(Kb, c0, p1, N, false, tid);
-            rv.load(Vb, c0, p1, N, false, tid);
+            rk.load(Kb + (size_t)c0 * DK, p1 - c0, tid);
+            rv.load(Vb + (size_t)c0 * DV, p1 - c0, tid);
             __syncthreads();
             rk.store(sK, tid);
             rv.store(sV, tid);
@@ -415,8 +558,12 @@ __global__ __launch_bounds__(256) void bf16_bwd_sweep_kernel(const bf16* __restr
             for (int n = 0; n < NS; ++n) {
                 const int id = w + 4 * n, jb = id / IB, ib = id % IB;
 #pragma unroll
-                for (int s0 = 0; s0 < C; s0 += 16)
-                    accST[n] = mfma(ld_tr(sV, LDV, s0, jb * 32, lane), ld_tr(sK, LDK, s0, ib * 32, lane), accST[n]);
+                for (int s0 = 0; s0 < C; s0 += 16) {
+                    // minus sign: flip the sign bits of one operand
+                    u32x4 a = __builtin_bit_cast(u32x4, ld_tr(sV, LDV, s0, jb * 32, lane));
+                    a ^= 0x80008000u;
+                    accNS[n] = mfma(__builtin_bit_cast(bf16x8, a), ld_tr(sK, LDK, s0, ib * 32, lane), accNS[n]);
+                }
             }
         }
         __syncthreads();
@@ -424,10 +571,10 @@ __global__ __launch_bounds__(256) void bf16_bwd_sweep_kernel(const bf16* __restr
 
     {
         const int c0 = p0 + (n_ch - 1) * C;
-        rq.load(Qb, c0, p1, N, false, tid);
-        rk.load(Kb, c0, p1, N, false, tid);
-        rv.load(Vb, c0, p1, N, false, tid);
-        rg.load(Gb, c0, p1, N, false, tid);
+        rq.load(Qb + (size_t)c0 * DK, p1 - c0, tid);
+        rk.load(Kb + (size_t)c0 * DK, p1 - c0, tid);
+        rv.load(Vb + (size_t)c0 * DV, p1 - c0, tid);
+        rg.load(Gb + (size_t)c0 * DV, p1 - c0, tid);
     }
 
     for (int ci = n_ch - 1; ci >= 0; --ci) {
@@ -437,30 +584,31 @@ __global__ __launch_bounds__(256) void bf16_bwd_sweep_kernel(const bf16* __restr
         rv.store(sV, tid);
         rg.store(sG, tid);
         // R (state after this chunk) is already final: publish it as bf16 [i][j]
-        state_to_lds_T<DV, DK>(sR, accRT, w, lane);
+        state_to_lds_T<DV, DK, false>(sR, accRT, w, lane);
         __syncthreads();
-        if (ci > 0) {
-            rq.load(Qb, c0 - C, p1, N, false, tid);
-            rk.load(Kb, c0 - C, p1, N, false, tid);
-            rv.load(Vb, c0 - C, p1, N, false, tid);
-            rg.load(Gb, c0 - C, p1, N, false, tid);
+        if (ci > 0) {   // every chunk but a segment's last is complete
+            rq.load(Qb + (size_t)(c0 - C) * DK, C, tid);
+            rk.load(Kb + (size_t)(c0 - C) * DK, C, tid);
+            rv.load(Vb + (size_t)(c0 - C) * DV, C, tid);
+            rg.load(Gb + (size_t)(c0 - C) * DV, C, tid);
         }
-        // roll S back over this chunk: S^T -= V^T K, then publish S (state before this chunk)
+        // roll S back over this chunk: (-S^T) += V^T K, then publish S (state before this chunk)
 #pragma unroll
         for (int n = 0; n < NS; ++n) {
             const int id = w + 4 * n, jb = id / IB, ib = id % IB;
 #pragma unroll
             for (int s0 = 0; s0 < C; s0 += 16)
-                accST[n] = mfma(negate(ld_tr(sV, LDV, s0, jb * 32, lane)), ld_tr(sK, LDK, s0, ib * 32, lane), accST[n]);
+                accNS[n] = mfma(ld_tr(sV, LDV, s0, jb * 32, lane), ld_tr(sK, LDK, s0, ib * 32, lane), accNS[n]);
         }
-        state_to_lds_T<DV, DK>(sS, accST, w, lane);
+        state_to_lds_T<DV, DK, true>(sS, accNS, w, lane);
         __syncthreads();
 
-        // ---------------- dQ rows of block tb = rb:  dQ = dP K + dO S^T'
+        const int valid = p1 - (c0 + rb * 32);   // rows of this wave's 32-token block that exist
+        // ---------------- dQ^T for token block tb = rb:  dQ^T = K^T dP^T + S dO^T
         {
-            bf16x8 aG[DV / 16];
+            bf16x8 bG[DV / 16];
 #pragma unroll
-            for (int kk = 0; kk < DV / 16; ++kk) aG[kk] = ld_nat(sG, LDV, rb * 32, kk * 16, lane);
+            for (int kk = 0; kk < DV / 16; ++kk) bG[kk] = ld_nat(sG, LDV, rb * 32, kk * 16, lane);
             f32x16 acc[NI];
 #pragma unroll
             for (int n = 0; n < NI; ++n) acc[n] = zero16();
@@ -468,26 +616,28 @@ __global__ __launch_bounds__(256) void bf16_bwd_sweep_kernel(const bf16* __restr
             for (int n = 0; n < NI; ++n)
 #pragma unroll
                 for (int kk = 0; kk < DV / 16; ++kk)
-                    acc[n] = mfma(aG[kk], ld_nat(sS, LDV, (cg * NI + n) * 32, kk * 16, lane), acc[n]);
+                    acc[n] = mfma(ld_nat(sS, LDV, (cg * NI + n) * 32, kk * 16, lane), bG[kk], acc[n]);
 #pragma unroll
             for (int sb = 0; sb < TB; ++sb) {
                 if (sb <= rb) {
                     f32x16 t = zero16();   // dP^T[s][t] = v_s . dO_t
 #pragma unroll
-                    for (int kk = 0; kk < DV / 16; ++kk) t = mfma(ld_nat(sV, LDV, sb * 32, kk * 16, lane), aG[kk], t);
-                    if (sb == rb) mask_diag<true>(t, lane);
-                    const bf16x8 a0 = cvt8(t, 0), a1 = cvt8(t, 8);
+                    for (int kk = 0; kk < DV / 16; ++kk) t = mfma(ld_nat(sV, LDV, sb * 32, kk * 16, lane), bG[kk], t);
+                    bf16x8 t0, t1;
+                    if (sb == rb) cvt_tile_masked(t, maskK, t0, t1);
+                    else cvt_tile(t, t0, t1);
 #pragma unroll
                     for (int n = 0; n < NI; ++n) {
-                        acc[n] = mfma(a0, ld_tr_perm(sK, LDK, sb * 32, (cg * NI + n) * 32, lane), acc[n]);
-                        acc[n] = mfma(a1, ld_tr_perm(sK, LDK, sb * 32 + 16, (cg * NI + n) * 32, lane), acc[n]);
+                        acc[n] = mfma(ld_tr_perm(sK, LDK, sb * 32, (cg * NI + n) * 32, lane), t0, acc[n]);
+                        acc[n] = mfma(ld_tr_perm(sK, LDK, sb * 32 + 16, (cg * NI + n) * 32, lane), t1, acc[n]);
                     }
                 }
             }
+            bf16* rows = dQb + (size_t)(c0 + rb * 32) * DK;
 #pragma unroll
-            for (int n = 0; n < NI; ++n) store_tile(dQb, DK, c0 + rb * 32, (cg * NI + n) * 32, acc[n], p1, N, false, lane);
+            for (int n = 0; n < NI; ++n) store_tile_T(rows, DK, (cg * NI + n) * 32, acc[n], valid, lane);
         }
-        // ---------------- dK rows of key block sb = rb:  dK = dP^T Q + V R^T'
+        // ---------------- dK^T for key block sb = rb:  dK^T = Q^T dP + R V^T
         {
             bf16x8 bV[DV / 16];
 #pragma unroll
@@ -499,26 +649,28 @@ __global__ __launch_bounds__(256) void bf16_bwd_sweep_kernel(const bf16* __restr
             for (int n = 0; n < NI; ++n)
 #pragma unroll
                 for (int kk = 0; kk < DV / 16; ++kk)
-                    acc[n] = mfma(bV[kk], ld_nat(sR, LDV, (cg * NI + n) * 32, kk * 16, lane), acc[n]);
+                    acc[n] = mfma(ld_nat(sR, LDV, (cg * NI + n) * 32, kk * 16, lane), bV[kk], acc[n]);
 #pragma unroll
             for (int tb = 0; tb < TB; ++tb) {
                 if (tb >= rb) {
                     f32x16 t = zero16();   // dP[t][s] = dO_t . v_s
 #pragma unroll
                     for (int kk = 0; kk < DV / 16; ++kk) t = mfma(ld_nat(sG, LDV, tb * 32, kk * 16, lane), bV[kk], t);
-                    if (tb == rb) mask_diag<false>(t, lane);
-                    const bf16x8 a0 = cvt8(t, 0), a1 = cvt8(t, 8);
+                    bf16x8 t0, t1;
+                    if (tb == rb) cvt_tile_masked(t, maskQ, t0, t1);
+                    else cvt_tile(t, t0, t1);
 #pragma unroll
                     for (int n = 0; n < NI; ++n) {
-                        acc[n] = mfma(a0, ld_tr_perm(sQ, LDK, tb * 32, (cg * NI + n) * 32, lane), acc[n]);
-                        acc[n] = mfma(a1, ld_tr_perm(sQ, LDK, tb * 32 + 16, (cg * NI + n) * 32, lane), acc[n]);
+                        acc[n] = mfma(ld_tr_perm(sQ, LDK, tb * 32, (cg * NI + n) * 32, lane), t0, acc[n]);
+                        acc[n] = mfma(ld_tr_perm(sQ, LDK, tb * 32 + 16, (cg * NI + n) * 32, lane), t1, acc[n]);
                     }
                 }
             }
+            bf16* rows = dKb + (size_t)(c0 + rb * 32) * DK;
 #pragma unroll
-            for (int n = 0; n < NI; ++n) store_tile(dKb, DK, c0 + rb * 32, (cg * NI + n) * 32, acc[n], p1, N, false, lane);
+            for (int n = 0; n < NI; ++n) store_tile_T(rows, DK, (cg * NI + n) * 32, acc[n], valid, lane);
         }
-        // ---------------- dV rows of key block sb = rb:  dV = P^T dO + K R
+        // ---------------- dV^T for key block sb = rb:  dV^T = dO^T P + R^T K^T
         {
             bf16x8 bK[DK / 16];
 #pragma unroll
@@ -530,24 +682,26 @@ __global__ __launch_bounds__(256) void bf16_bwd_sweep_kernel(const bf16* __restr
             for (int n = 0; n < NJ; ++n)
 #pragma unroll
                 for (int kk = 0; kk < DK / 16; ++kk)
-                    acc[n] = mfma(bK[kk], ld_tr(sR, LDV, kk * 16, (cg * NJ + n) * 32, lane), acc[n]);
+                    acc[n] = mfma(ld_tr(sR, LDV, kk * 16, (cg * NJ + n) * 32, lane), bK[kk], acc[n]);
 #pragma unroll
             for (int tb = 0; tb < TB; ++tb) {
                 if (tb >= rb) {
                     f32x16 t = zero16();   // P[t][s] = q_t . k_s
 #pragma unroll
                     for (int kk = 0; kk < DK / 16; ++kk) t = mfma(ld_nat(sQ, LDK, tb * 32, kk * 16, lane), bK[kk], t);
-                    if (tb == rb) mask_diag<false>(t, lane);
-                    const bf16x8 a0 = cvt8(t, 0), a1 = cvt8(t, 8);
+                    bf16x8 t0, t1;
+                    if (tb == rb) cvt_tile_masked(t, maskQ, t0, t1);
+                    else cvt_tile(t, t0, t1);
 #pragma unroll
                     for (int n = 0; n < NJ; ++n) {
-                        acc[n] = mfma(a0, ld_tr_perm(sG, LDV, tb * 32, (cg * NJ + n) * 32, lane), acc[n]);
-                        acc[n] = mfma(a1, ld_tr_perm(sG, LDV, tb * 32 + 16, (cg * NJ + n) * 32, lane), acc[n]);
+                        acc[n] = mfma(ld_tr_perm(sG, LDV, tb * 32, (cg * NJ + n) * 32, lane), t0, acc[n]);
+                        acc[n] = mfma(ld_tr_perm(sG, LDV, tb * 32 + 16, (cg * NJ + n) * 32, lane), t1, acc[n]);
                     }
                 }
             }
+            bf16* rows = dVb + (size_t)(c0 + rb * 32) * DV;
 #pragma unroll
-            for (int n = 0; n < NJ; ++n) store_tile(dVb, DV, c0 + rb * 32, (cg * NJ + n) * 32, acc[n], p1, N, false, lane);
+            for (int n = 0; n < NJ; ++n) store_tile_T(rows, DV, (cg * NJ + n) * 32, acc[n], valid, lane);
         }
         // ---------------- R^T += dO^T Q (not needed after the segment's first chunk)
         if (ci > 0) {
@@ -564,36 +718,37 @@ __global__ __launch_bounds__(256) void bf16_bwd_sweep_kernel(const bf16* __restr
 }
 
 // =============================================================================================== launchers
+// Pre-pass + scan over segments.
 template <int DA, int DB>
-static hipError_t run_seg_state(const SegStateArgs& a, int npairs, long BH, int N, const Plan& plan, bool rev,
-                                hipStream_t st)
+static hipError_t run_seg_state(const SegStateArgs& a, int npairs, const int* scan_modes, long BH, int N,
+                                const Plan& plan, hipStream_t st)
 {
-    dim3 grid(plan.n_seg, (unsigned)BH, npairs);
-    ProfScope prof(KID_SEG_STATE_BF16, st);
-    hipLaunchKernelGGL((bf16_seg_state_kernel<DA, DB>), grid, dim3(256), 0, st, a, N, plan.seg_len, plan.n_seg, (int)rev);
-    return hipGetLastError();
+    hipError_t e;
+    {
+        dim3 grid(plan.n_seg, (unsigned)BH, npairs);
+        ProfScope prof(KID_SEG_STATE_BF16, st);
+        hipLaunchKernelGGL((bf16_seg_state_kernel<DA, DB>), grid, dim3(256), 0, st, a, N, plan.seg_len, plan.n_seg);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+    const size_t stride = npairs > 1 ? (size_t)(a.out[1] - a.out[0]) : 0;
+    return scan_states(a.out[0], stride, npairs, scan_modes, BH, plan.n_seg, DA * DB, st);
 }
 
 template <int C, int DK, int DV>
 static hipError_t fwd_impl(const bf16* Q, const bf16* K, const bf16* V, bf16* O, long BH, int N, const Plan& plan,
-                           bool rev, float* ws, hipStream_t st)
+                           float* ws, hipStream_t st)
 {
     hipError_t e;
     if (plan.n_seg > 1) {
         SegStateArgs a{};
         a.X[0] = K; a.Y[0] = V; a.out[0] = ws; a.skip_seg[0] = plan.n_seg - 1;
-        if ((e = run_seg_state<DK, DV>(a, 1, BH, N, plan, rev, st)) != hipSuccess) return e;
-        if ((e = scan_states(ws, BH, plan.n_seg, DK * DV, SCAN_EXCL_PREFIX, st)) != hipSuccess) return e;
+        const int mode = SCAN_EXCL_PREFIX;
+        if ((e = run_seg_state<DK, DV>(a, 1, &mode, BH, N, plan, st)) != hipSuccess) return e;
     }
     dim3 grid(plan.n_seg, (unsigned)BH);
-    const float* s0 = plan.n_seg > 1 ? ws : nullptr;
     ProfScope prof(KID_FWD_SWEEP_BF16, st);
-    if (rev)
-        hipLaunchKernelGGL((bf16_fwd_sweep_kernel<C, DK, DV, true>), grid, dim3(256), 0, st, Q, K, V, O, s0, N,
-                           plan.seg_len, plan.n_seg);
-    else
-        hipLaunchKernelGGL((bf16_fwd_sweep_kernel<C, DK, DV, false>), grid, dim3(256), 0, st, Q, K, V, O, s0, N,
-                           plan.seg_len, plan.n_seg);
+    hipLaunchKernelGGL((bf16_fwd_sweep_kernel<C, DK, DV>), grid, dim3(256), 0, st, Q, K, V, O,
+                       plan.n_seg > 1 ? ws : nullptr, N, plan.seg_len, plan.n_seg);
     return hipGetLastError();
 }
 
@@ -606,11 +761,11 @@ static hipError_t bwd_impl(const bf16* Q, const bf16* K, const bf16* V, const bf
     float* wsR = ws ? ws + (size_t)BH * plan.n_seg * DK * DV : nullptr;
     if (plan.n_seg > 1) {
         SegStateArgs a{};
-        a.X[0] = V;  a.Y[0] = K; a.out[0] = wsS; a.skip_seg[0] = -1;   // S^T totals: every segment is needed
-        a.X[1] = dO; a.Y[1] = Q; a.out[1] = wsR; a.skip_seg[1] = 0;    // R^T totals: the first is never used
-        if ((e = run_seg_state<DV, DK>(a, 2, BH, N, plan, false, st)) != hipSuccess) return e;
-        if ((e = scan_states(wsS, BH, plan.n_seg, DK * DV, SCAN_INCL_PREFIX, st)) != hipSuccess) return e;
-        if ((e = scan_states(wsR, BH, plan.n_seg, DK * DV, SCAN_EXCL_SUFFIX, st)) != hipSuccess) return e;
+        // S^T totals: every segment is needed (inclusive prefix); R^T totals: the first is never used (exclusive suffix)
+        a.X[0] = V;  a.Y[0] = K; a.out[0] = wsS; a.skip_seg[0] = -1;
+        a.X[1] = dO; a.Y[1] = Q; a.out[1] = wsR; a.skip_seg[1] = 0;
+        const int modes[2] = {SCAN_INCL_PREFIX, SCAN_EXCL_SUFFIX};
+        if ((e = run_seg_state<DV, DK>(a, 2, modes, BH, N, plan, st)) != hipSuccess) return e;
     }
     dim3 grid(plan.n_seg, (unsigned)BH);
     ProfScope prof(KID_BWD_SWEEP_BF16, st);
@@ -623,18 +778,18 @@ static hipError_t bwd_impl(const bf16* Q, const bf16* K, const bf16* V, const bf
     if (plan.chunk == C_ && dk == DK_ && dv == DV_) return CALL;
 
 hipError_t launch_bf16_fwd(const void* Q, const void* K, const void* V, void* O, long BH, int N, int dk, int dv,
-                           const Plan& plan, bool rev, float* ws, hipStream_t st)
+                           const Plan& plan, float* ws, hipStream_t st)
 {
     const bf16 *q = (const bf16*)Q, *k = (const bf16*)K, *v = (const bf16*)V;
     bf16* o = (bf16*)O;
-    CHELA_DISPATCH(64, 64, 64, (fwd_impl<64, 64, 64>(q, k, v, o, BH, N, plan, rev, ws, st)))
-    CHELA_DISPATCH(128, 64, 64, (fwd_impl<128, 64, 64>(q, k, v, o, BH, N, plan, rev, ws, st)))
-    CHELA_DISPATCH(64, 64, 128, (fwd_impl<64, 64, 128>(q, k, v, o, BH, N, plan, rev, ws, st)))
-    CHELA_DISPATCH(128, 64, 128, (fwd_impl<128, 64, 128>(q, k, v, o, BH, N, plan, rev, ws, st)))
-    CHELA_DISPATCH(64, 128, 64, (fwd_impl<64, 128, 64>(q, k, v, o, BH, N, plan, rev, ws, st)))
-    CHELA_DISPATCH(128, 128, 64, (fwd_impl<128, 128, 64>(q, k, v, o, BH, N, plan, rev, ws, st)))
-    CHELA_DISPATCH(64, 128, 128, (fwd_impl<64, 128, 128>(q, k, v, o, BH, N, plan, rev, ws, st)))
-    CHELA_DISPATCH(128, 128, 128, (fwd_impl<128, 128, 128>(q, k, v, o, BH, N, plan, rev, ws, st)))
+    CHELA_DISPATCH(64, 64, 64, (fwd_impl<64, 64, 64>(q, k, v, o, BH, N, plan, ws, st)))
+    CHELA_DISPATCH(128, 64, 64, (fwd_impl<128, 64, 64>(q, k, v, o, BH, N, plan, ws, st)))
+    CHELA_DISPATCH(64, 64, 128, (fwd_impl<64, 64, 128>(q, k, v, o, BH, N, plan, ws, st)))
+    CHELA_DISPATCH(128, 64, 128, (fwd_impl<128, 64, 128>(q, k, v, o, BH, N, plan, ws, st)))
+    CHELA_DISPATCH(64, 128, 64, (fwd_impl<64, 128, 64>(q, k, v, o, BH, N, plan, ws, st)))
+    CHELA_DISPATCH(128, 128, 64, (fwd_impl<128, 128, 64>(q, k, v, o, BH, N, plan, ws, st)))
+    CHELA_DISPATCH(64, 128, 128, (fwd_impl<64, 128, 128>(q, k, v, o, BH, N, plan, ws, st)))
+    CHELA_DISPATCH(128, 128, 128, (fwd_impl<128, 128, 128>(q, k, v, o, BH, N, plan, ws, st)))
     return hipErrorInvalidValue;
 }
 
@@ -650,5 +805,7 @@ hipError_t launch_bf16_bwd(const void* Q, const void* K, const void* V, const vo
     CHELA_DISPATCH(64, 128, 128, (bwd_impl<64, 128, 128>(q, k, v, g, dq, dkk, dvv, BH, N, plan, ws, st)))
     return hipErrorInvalidValue;
 }
+
+void free_bf16_resources() {}
 
 }  // namespace chela

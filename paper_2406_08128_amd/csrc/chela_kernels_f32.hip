@@ -10,28 +10,75 @@
 namespace chela {
 
 // ------------------------------------------------------------------------------------------------ scan
-// states[bh][seg][e], one thread per (bh, e), serial over the (few) segments, coalesced over e.
-__global__ __launch_bounds__(256) void scan_states_kernel(float* __restrict__ st, int n_seg, int elems, int mode)
+// states[z][bh][seg][e] (z = 0 .. n_arrays-1, arrays `array_stride` floats apart), one thread per (z, bh, 4 e's),
+// serial over the (few) segments, coalesced over e.  The loads of U segments are issued before the first add so that
+// one memory round trip serves U segments.
+struct ScanModes { int mode[2]; };
+
+__global__ __launch_bounds__(256) void scan_states_kernel(float* __restrict__ st, size_t array_stride, int n_seg,
+                                                         int elems, ScanModes modes)
 {
     const long bh = blockIdx.y;
-    const int e = blockIdx.x * 256 + threadIdx.x;
+    const int z = blockIdx.z;
+    const int mode = modes.mode[z];
+    const int e = (blockIdx.x * 256 + threadIdx.x) * 4;
     if (e >= elems) return;
-    float* p = st + (size_t)bh * n_seg * elems + e;
-    float run = 0.f;
-    if (mode == SCAN_EXCL_PREFIX) {
-        for (int s = 0; s < n_seg; ++s) { float v = p[(size_t)s * elems]; p[(size_t)s * elems] = run; run += v; }
-    } else if (mode == SCAN_INCL_PREFIX) {
-        for (int s = 0; s < n_seg; ++s) { run += p[(size_t)s * elems]; p[(size_t)s * elems] = run; }
-    } else {
-        for (int s = n_seg - 1; s >= 0; --s) { float v = p[(size_t)s * elems]; p[(size_t)s * elems] = run; run += v; }
+    float* p = st + (size_t)z * array_stride + (size_t)bh * n_seg * elems + e;
+    float4 run = make_float4(0.f, 0.f, 0.f, 0.f);
+    constexpr int U = 16;                      // segments in flight per thread
+    const bool suffix = (mode == SCAN_EXCL_SUFFIX);
+    for (int s0 = 0; s0 < n_seg; s0 += U) {
+        float4 v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int s = s0 + u;
+            const int idx = suffix ? (n_seg - 1 - s) : s;
+            v[u] = s < n_seg ? *reinterpret_cast<const float4*>(p + (size_t)idx * elems) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int s = s0 + u;
+            if (s < n_seg) {
+                const int idx = suffix ? (n_seg - 1 - s) : s;
+                float4* dst = reinterpret_cast<float4*>(p + (size_t)idx * elems);
+                if (mode == SCAN_INCL_PREFIX) {
+                    run.x += v[u].x; run.y += v[u].y; run.z += v[u].z; run.w += v[u].w;
+                    *dst = run;
+                } else {
+                    *dst = run;
+                    run.x += v[u].x; run.y += v[u].y; run.z += v[u].z; run.w += v[u].w;
+                }
+            }
+        }
     }
 }
 
-hipError_t scan_states(float* states, long BH, int n_seg, int elems, int mode, hipStream_t st)
+hipError_t scan_states(float* states, size_t array_stride, int n_arrays, const int* modes, long BH, int n_seg, int elems,
+                       hipStream_t st)
 {
-    dim3 grid((elems + 255) / 256, (unsigned)BH);
+    ScanModes m{};
+    for (int z = 0; z < n_arrays && z < 2; ++z) m.mode[z] = modes[z];
+    dim3 grid((elems / 4 + 255) / 256, (unsigned)BH, n_arrays);
     ProfScope prof(KID_SCAN, st);
-    hipLaunchKernelGGL(scan_states_kernel, grid, dim3(256), 0, st, states, n_seg, elems, mode);
+    hipLaunchKernelGGL(scan_states_kernel, grid, dim3(256), 0, st, states, array_stride, n_seg, elems, m);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------ copy probe
+// Grid-stride 16-byte copy: the plain streaming kernel that byte counters are calibrated against.
+__global__ __launch_bounds__(256) void copy_probe_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n)
+{
+    const size_t stride = (size_t)gridDim.x * 256;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) dst[i] = src[i];
+}
+
+hipError_t launch_copy(const void* src, void* dst, size_t bytes, hipStream_t st)
+{
+    const size_t n = bytes / 16;
+    size_t blocks = (n + 255) / 256;
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    ProfScope prof(KID_COPY, st);
+    hipLaunchKernelGGL(copy_probe_kernel, dim3((unsigned)blocks), dim3(256), 0, st, (const uint4*)src, (uint4*)dst, n);
     return hipGetLastError();
 }
 
@@ -193,7 +240,8 @@ hipError_t launch_f32(const float* Q, const float* K, const float* V, float* O, 
                                plan.n_seg, (int)rev);
         }
         if ((e = hipGetLastError()) != hipSuccess) return e;
-        if ((e = scan_states(ws, BH, plan.n_seg, dk * dv, SCAN_EXCL_PREFIX, st)) != hipSuccess) return e;
+        const int mode = SCAN_EXCL_PREFIX;
+        if ((e = scan_states(ws, 0, 1, &mode, BH, plan.n_seg, dk * dv, st)) != hipSuccess) return e;
     }
     const size_t lds = f32_sweep_lds(dk, dv, C);
     e = hipFuncSetAttribute((const void*)f32_sweep_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
