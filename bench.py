@@ -51,6 +51,9 @@ def main():
     ap.add_argument("--workload", default="lm_bf16")
     ap.add_argument("--chunk", type=int, default=64)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe-mib", type=int, default=0,
+                    help="also run the library's plain copy kernel on a buffer of this many MiB (3 launches): the "
+                         "kernel of known size that rocprofv3 byte counters are calibrated against")
     ap.add_argument("--traffic-file", default=os.path.join(ROOT, "profiles", "bwd_sweep_lm_bf16_pmc.txt"))
     args = ap.parse_args()
     if args.gpus != 1:
@@ -75,6 +78,14 @@ def main():
     def step():
         binding.chela_linattn_fwd(d["Q"], d["K"], d["V"], O=O, chunk=chunk)
         binding.chela_linattn_bwd(d["Q"], d["K"], d["V"], d["dO"], dQ=dQ, dK=dK, dV=dV, chunk=chunk)
+
+    if args.copy_probe_mib > 0:
+        src = torch.zeros(args.copy_probe_mib << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            binding.chela_copy_probe(src, dst)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step()

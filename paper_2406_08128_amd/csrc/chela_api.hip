@@ -16,9 +16,51 @@ static int env_int(const char* name, int dflt)
     return std::atoi(s);
 }
 
-// Segment length: long enough that the per-segment state traffic (one d_k x d_v fp32 state written, scanned
-// and read back per segment) stays a small fraction of the segment's own Q/K/V bytes, short enough that
-// B*H*n_seg workgroups fill 256 compute units several times over.
+// Workgroups of the sweep kernel that fit the GPU at once (256 compute units x resident workgroups per unit, the
+// latter set by the kernel's LDS and register footprint).
+static long sweep_slots(int dk, int dv, int chunk, int dtype, bool is_bwd)
+{
+    if (dtype != CHELA_DTYPE_BF16) return 512;
+    const bool narrow = (dk == 64 && dv == 64), wide = (dk == 128 && dv == 128);
+    int per_cu;
+    if (is_bwd) per_cu = (narrow && chunk == 64) ? 2 : 1;
+    else if (chunk == 64) per_cu = narrow ? 4 : (wide ? 1 : 2);
+    else per_cu = narrow ? 2 : 1;
+    return 256L * per_cu;
+}
+
+// Segments per (b,h).  Every extra segment costs HBM traffic (its d_k x d_v fp32 state is written by the pre-pass,
+// read and written by the scan and read by the sweep), too few leave compute units idle, and a workgroup count just
+// above a multiple of what the GPU holds at once wastes most of a round.  The plan minimises a small cost model, in
+// units of one chunk step of one workgroup on a full GPU:
+//     sweep  = (full rounds + g(fill of the last round)) * (chunks per segment + 0.5)
+//     states = segments * heads * w
+// g() says that a sparsely filled last round runs its workgroups faster, but not proportionally (and not at all when
+// a compute unit only ever holds one workgroup: then nothing hides that workgroup's latencies); w is the measured
+// cost of one more segment state relative to a chunk step.  With 256 or more (b,h) pairs one workgroup per pair keeps
+// every unit busy and the pre-pass (which re-reads K and V) disappears altogether, so no segmentation is used.
+static long choose_segments(long BH, long n_chunks, long slots, double g_min, double w_state)
+{
+    if (BH >= 256 || n_chunks <= 4) return 1;
+    long best = 1;
+    double best_cost = 1e300;
+    const long max_seg = n_chunks / 4 > 0 ? n_chunks / 4 : 1;     // at least 4 chunks per segment
+    for (long n = 1; n <= max_seg && n <= 4096; ++n) {
+        const long cps = (n_chunks + n - 1) / n;
+        const long real_n = (n_chunks + cps - 1) / cps;
+        if (real_n != n) continue;                                 // same split as a smaller n
+        const long wgs = BH * n;
+        const long full = wgs / slots;
+        const double f = (double)(wgs - full * slots) / (double)slots;
+        double g = 0.0;
+        if (f > 0.0) { g = f / 0.75; if (g > 1.0) g = 1.0; if (g < g_min) g = g_min; }
+        double cost = ((double)full + g) * ((double)cps + 0.5) + (double)(n * BH) * w_state;
+        if (n > 1) cost += 0.5 * (double)(n_chunks * BH) / (double)slots + 3.0;   // pre-pass re-read + two more launches
+        if (cost < best_cost) { best_cost = cost; best = n; }
+    }
+    return best;
+}
+
 Plan make_plan(long BH, int N, int dk, int dv, int chunk, int dtype, bool is_bwd)
 {
     Plan p{};
@@ -26,13 +68,13 @@ Plan make_plan(long BH, int N, int dk, int dv, int chunk, int dtype, bool is_bwd
     p.state_elems = (size_t)dk * dv;
     if (BH <= 0 || N <= 0) { p.seg_len = chunk; p.n_seg = 0; p.ws_bytes = 0; return p; }
     const long n_chunks = ((long)N + chunk - 1) / chunk;
-    long target_wgs = env_int("CHELA_TARGET_WGS", 1024);
-    long min_seg_tokens = env_int("CHELA_MIN_SEG_TOKENS", (dk >= 128 && dv >= 128) ? 1024 : 512);
-    long min_cps = (min_seg_tokens + chunk - 1) / chunk;
-    if (min_cps < 1) min_cps = 1;
-    long cps = (n_chunks * BH) / target_wgs;      // chunks per segment that would give target_wgs groups
-    if (cps < min_cps) cps = min_cps;
-    int forced = env_int("CHELA_SEG_TOKENS", 0);
+    const long slots = sweep_slots(dk, dv, chunk, dtype, is_bwd);
+    // one more state costs about 48 KB (fp32, 64 x 64) of traffic spread over the whole GPU; a chunk step moves
+    // 32 KB (forward) or 56 KB (backward) per resident workgroup
+    const double w_state = (is_bwd ? 0.0019 : 0.0033) * ((double)dk * dv / 4096.0) * (512.0 / (double)slots);
+    long n_seg = choose_segments(BH, n_chunks, slots, slots > 256 ? 0.55 : 1.0, w_state);
+    long cps = (n_chunks + n_seg - 1) / n_seg;
+    const int forced = env_int("CHELA_SEG_TOKENS", 0);
     if (forced > 0) cps = (forced + chunk - 1) / chunk;
     if (cps > n_chunks) cps = n_chunks;
     if (cps < 1) cps = 1;
@@ -345,8 +387,6 @@ void chela_shutdown(void)
         if (hipSetDevice(d) == hipSuccess) { (void)hipDeviceSynchronize(); (void)hipFree(g_own_ws[d]); }
         g_own_ws[d] = nullptr; g_own_bytes[d] = 0;
     }
-    if (!have_cur) have_cur = (hipGetDevice(&cur) == hipSuccess);
-    free_bf16_resources();
     if (have_cur) (void)hipSetDevice(cur);
 }
 

@@ -41,9 +41,6 @@ hipError_t launch_bf16_fwd(const void* Q, const void* K, const void* V, void* O,
 hipError_t launch_bf16_bwd(const void* Q, const void* K, const void* V, const void* dO, void* dQ, void* dK,
                            void* dV, long BH, int N, int dk, int dv, const Plan& plan, float* ws, hipStream_t st);
 
-// Frees the arrival counters of the in-kernel scan (called by chela_shutdown).
-void free_bf16_resources();
-
 // Kernel classes for the per-kernel timing aid.
 enum { KID_SEG_STATE_BF16 = 0, KID_SCAN = 1, KID_FWD_SWEEP_BF16 = 2, KID_BWD_SWEEP_BF16 = 3, KID_SEG_STATE_F32 = 4,
        KID_SWEEP_F32 = 5, KID_COPY = 6, KID_COUNT = 7 };

@@ -2,11 +2,11 @@
 // (v_mfma_f32_32x32x16_bf16, fp32 accumulation), tiles staged in LDS, 64-wide wavefronts.
 //
 // Structure (Sec. 4.1): a (b,h) sequence is cut into segments of a few hundred to a few thousand tokens.
-//   pre-pass  seg_state : per segment, the total of X^T Y over its tokens (K^T V for the forward state)
-//   scan                : prefix (or suffix) over the segments of one (b,h)                  [fp32 file]
-//   sweep               : one workgroup per segment walks its chunks with the state in accumulator registers:
-//                         masked left product inside the chunk, right product with the carried state, both summed
-//                         in registers before the result is written to HBM.
+//   pre-pass : per segment, the total of X^T Y over its tokens (K^T V for the forward state)
+//   scan     : prefix (or suffix) over the segments of one (b,h)
+//   sweep    : one workgroup per segment walks its chunks with the state in accumulator registers: masked left
+//              product inside the chunk, right product with the carried state, both summed in registers before the
+//              result is written to HBM.
 //
 // Operand plumbing.  D = A B on a 32x32x16 MFMA wants, per lane, 8 consecutive k of one row of A and 8
 // consecutive k of one column of B.  Products that contract over the feature axis read row-major LDS tiles
@@ -186,162 +186,7 @@ __device__ __forceinline__ void store_tile_T(bf16* rows, int ld, int col0, const
     }
 }
 
-// =============================================================================================== pre-pass
-// out[a][b] = sum over the segment's tokens s of X[s][a] * Y[s][b]   (fp32, [DA][DB] row-major).
-// Up to two (X, Y) pairs are served by one launch (blockIdx.z).  `skip_seg[z]` names a segment whose total the scan
-// never uses (-1: none).
-//
-// This kernel only reads, so it is built to stream: the four waves of a workgroup never meet inside the main loop.
-// Each wave takes every TOKW-th block of 16 tokens, passes it through a wave-private LDS patch (only to get the
-// token-contiguous MFMA operands out of the transposing read) and accumulates ALL output tiles for its tokens.  The
-// partial sums of the waves are added once at the end, in a fixed order.  With 128 x 128 outputs the 16 tiles do not
-// fit one wave's registers, so two waves share a token block and each owns half of the columns of Y.
-struct SegStateArgs {
-    const bf16* X[2];
-    const bf16* Y[2];
-    float* out[2];
-    int skip_seg[2];
-};
-
-template <int DA, int DB>
-__global__ __launch_bounds__(256) void bf16_seg_state_kernel(SegStateArgs args, int N, int seg_len, int n_seg)
-{
-    constexpr int AB = DA / 32, BB = DB / 32;
-    constexpr int WSPLIT = (AB * BB > 8) ? 2 : 1;   // waves sharing one token block
-    constexpr int BBW = BB / WSPLIT;                 // column tiles of Y per wave
-    constexpr int DBW = DB / WSPLIT;                 // columns of Y per wave
-    constexpr int NT = AB * BBW;                     // output tiles per wave
-    constexpr int TOKW = 4 / WSPLIT;                 // waves working on different token blocks
-    constexpr int T = 16;                            // tokens per block = one MFMA k step
-    constexpr int LDA = DA + PAD, LDB = DBW + PAD;
-    constexpr int NVX = T * DA / 8 / 64, NVY = T * DBW / 8 / 64;   // 16-byte vectors per lane per block
-    constexpr int PF = 3;                            // blocks in flight per wave
-    constexpr int STAGE_BYTES = 4 * (T * LDA + T * LDB) * 2;
-    constexpr int RED_BYTES = (TOKW / 2) * WSPLIT * NT * 1024 * 4;
-    constexpr int LDS_BYTES = STAGE_BYTES > RED_BYTES ? STAGE_BYTES : RED_BYTES;
-    __shared__ __attribute__((aligned(16))) unsigned char lds_raw[LDS_BYTES];
-
-    const int z = blockIdx.z;
-    const int seg = blockIdx.x;
-    const long bh = blockIdx.y;
-    if (seg == args.skip_seg[z]) return;
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int tl = w / WSPLIT, cgw = w % WSPLIT;
-    const int p0 = seg * seg_len, p1 = min(N, p0 + seg_len);
-    const bf16* X = args.X[z] + ((size_t)bh * N + p0) * DA;
-    const bf16* Y = args.Y[z] + ((size_t)bh * N + p0) * DB + cgw * DBW;
-    bf16* sX = reinterpret_cast<bf16*>(lds_raw) + w * (T * LDA + T * LDB);
-    bf16* sY = sX + T * LDA;
-
-    const int ntok = p1 - p0;
-    const int nb_total = (ntok + T - 1) / T;
-    const int nblk = nb_total > tl ? (nb_total - tl + TOKW - 1) / TOKW : 0;   // blocks of this wave
-
-    f32x16 acc[NT];
-#pragma unroll
-    for (int n = 0; n < NT; ++n) acc[n] = zero16();
-
-    uint4 rx[PF][NVX], ry[PF][NVY];
-    auto load_block = [&](int u, int i) {
-        const int tok0 = (tl + TOKW * i) * T;          // first token of the block, relative to the segment
-        const int valid = ntok - tok0;
-        const bf16* xs = X + (size_t)tok0 * DA;
-        const bf16* ys = Y + (size_t)tok0 * DB;
-        if (valid >= T) {
-#pragma unroll
-            for (int n = 0; n < NVX; ++n) rx[u][n] = reinterpret_cast<const uint4*>(xs)[lane + 64 * n];
-#pragma unroll
-            for (int n = 0; n < NVY; ++n) {
-                const int x = lane + 64 * n, row = x / (DBW / 8), cv = x % (DBW / 8);
-                ry[u][n] = *reinterpret_cast<const uint4*>(ys + (size_t)row * DB + cv * 8);
-            }
-        } else {
-#pragma unroll
-            for (int n = 0; n < NVX; ++n) {
-                const int x = lane + 64 * n, row = x / (DA / 8);
-                rx[u][n] = row < valid ? reinterpret_cast<const uint4*>(xs)[x] : make_uint4(0, 0, 0, 0);
-            }
-#pragma unroll
-            for (int n = 0; n < NVY; ++n) {
-                const int x = lane + 64 * n, row = x / (DBW / 8), cv = x % (DBW / 8);
-                ry[u][n] = row < valid ? *reinterpret_cast<const uint4*>(ys + (size_t)row * DB + cv * 8)
-                                       : make_uint4(0, 0, 0, 0);
-            }
-        }
-    };
-
-#pragma unroll
-    for (int u = 0; u < PF; ++u)
-        if (u < nblk) load_block(u, u);
-
-    for (int i0 = 0; i0 < nblk; i0 += PF) {
-#pragma unroll
-        for (int u = 0; u < PF; ++u) {
-            const int i = i0 + u;
-            if (i < nblk) {
-#pragma unroll
-                for (int n = 0; n < NVX; ++n) {
-                    const int x = lane + 64 * n, row = x / (DA / 8), cv = x % (DA / 8);
-                    *reinterpret_cast<uint4*>(sX + row * LDA + cv * 8) = rx[u][n];
-                }
-#pragma unroll
-                for (int n = 0; n < NVY; ++n) {
-                    const int x = lane + 64 * n, row = x / (DBW / 8), cv = x % (DBW / 8);
-                    *reinterpret_cast<uint4*>(sY + row * LDB + cv * 8) = ry[u][n];
-                }
-                if (i + PF < nblk) load_block(u, i + PF);
-                __builtin_amdgcn_wave_barrier();
-                bf16x8 fa[AB], fb[BBW];
-#pragma unroll
-                for (int a = 0; a < AB; ++a) fa[a] = ld_tr(sX, LDA, 0, a * 32, lane);
-#pragma unroll
-                for (int b = 0; b < BBW; ++b) fb[b] = ld_tr(sY, LDB, 0, b * 32, lane);
-#pragma unroll
-                for (int a = 0; a < AB; ++a)
-#pragma unroll
-                    for (int b = 0; b < BBW; ++b) acc[a * BBW + b] = mfma(fa[a], fb[b], acc[a * BBW + b]);
-                __builtin_amdgcn_wave_barrier();
-            }
-        }
-    }
-
-    // add the partial sums of the TOKW waves that share a column group: tl >= TOKW/2 hand theirs over, then tl = 1
-    float* red = reinterpret_cast<float*>(lds_raw);
-    __syncthreads();
-#pragma unroll
-    for (int half = TOKW / 2; half >= 1; half /= 2) {
-        if (tl >= half && tl < 2 * half) {
-            float* dst = red + (size_t)((tl - half) * WSPLIT + cgw) * NT * 1024;
-#pragma unroll
-            for (int n = 0; n < NT; ++n)
-#pragma unroll
-                for (int k = 0; k < 16; ++k) dst[(n * 16 + k) * 64 + lane] = acc[n][k];
-        }
-        __syncthreads();
-        if (tl < half) {
-            const float* src = red + (size_t)(tl * WSPLIT + cgw) * NT * 1024;
-#pragma unroll
-            for (int n = 0; n < NT; ++n)
-#pragma unroll
-                for (int k = 0; k < 16; ++k) acc[n][k] += src[(n * 16 + k) * 64 + lane];
-        }
-        __syncthreads();
-    }
-    if (tl != 0) return;
-    float* o = args.out[z] + ((size_t)bh * n_seg + seg) * DA * DB + cgw * DBW;
-    const int r = lane & 31, h = lane >> 5;
-#pragma unroll
-    for (int a = 0; a < AB; ++a)
-#pragma unroll
-        for (int b = 0; b < BBW; ++b)
-#pragma unroll
-            for (int q = 0; q < 4; ++q)
-#pragma unroll
-                for (int k = 0; k < 4; ++k)
-                    o[(a * 32 + 8 * q + 4 * h + k) * DB + b * 32 + r] = acc[a * BBW + b][4 * q + k];
-}
-
+// =============================================================================================== shared pieces
 // Load a [DA][DB] fp32 state as accumulator tiles: tile id = w + 4n -> (ab, bb) = (id / BB, id % BB).
 template <int DA, int DB, bool NEG>
 __device__ __forceinline__ void load_state(f32x16* acc, const float* src, int w, int lane)
@@ -381,61 +226,124 @@ __device__ __forceinline__ void state_to_lds_T(bf16* dst, const f32x16* acc, int
     }
 }
 
-// =============================================================================================== forward sweep
-// One workgroup (4 waves) per (segment, bh).  Per chunk of C tokens:
+// =============================================================================================== pre-pass body
+// out[a][b] = sum over `ntok` tokens s of X[s][a] * Y[s][b]   (fp32, [DA][DB] row-major).  One workgroup; wave w owns
+// output tiles w, w+4, ...  LDS: 64 x (DA + PAD) + 64 x (DB + PAD) bf16.
+template <int DA, int DB>
+struct PrepassLds {
+    static constexpr int R = 64;
+    static constexpr int BYTES = (R * (DA + PAD) + R * (DB + PAD)) * 2;
+};
+
+template <int DA, int DB>
+__device__ __forceinline__ void prepass_body(const bf16* __restrict__ X, const bf16* __restrict__ Y,
+                                             float* __restrict__ out, int ntok, unsigned char* lds, int tid, int w,
+                                             int lane)
+{
+    constexpr int R = 64;
+    constexpr int PF = 2;          // 64-token blocks in flight per workgroup: this kernel only reads, so it lives
+                                   // off memory-level parallelism
+    bf16* sX = reinterpret_cast<bf16*>(lds);
+    bf16* sY = sX + R * (DA + PAD);
+    constexpr int BB = DB / 32, NT = (DA / 32) * BB / 4;
+    f32x16 acc[NT];
+#pragma unroll
+    for (int n = 0; n < NT; ++n) acc[n] = zero16();
+    TileRegs<R, DA> rx[PF];
+    TileRegs<R, DB> ry[PF];
+#pragma unroll
+    for (int u = 0; u < PF; ++u)
+        if (u * R < ntok) {
+            rx[u].load(X + (size_t)(u * R) * DA, ntok - u * R, tid);
+            ry[u].load(Y + (size_t)(u * R) * DB, ntok - u * R, tid);
+        }
+    for (int c0 = 0; c0 < ntok; c0 += PF * R) {
+#pragma unroll
+        for (int u = 0; u < PF; ++u) {
+            const int c = c0 + u * R;
+            if (c < ntok) {
+                rx[u].store(sX, tid);
+                ry[u].store(sY, tid);
+                __syncthreads();
+                if (c + PF * R < ntok) {
+                    rx[u].load(X + (size_t)(c + PF * R) * DA, ntok - c - PF * R, tid);
+                    ry[u].load(Y + (size_t)(c + PF * R) * DB, ntok - c - PF * R, tid);
+                }
+#pragma unroll
+                for (int n = 0; n < NT; ++n) {
+                    const int id = w + 4 * n, ab = id / BB, bb = id % BB;
+#pragma unroll
+                    for (int s0 = 0; s0 < R; s0 += 16)
+                        acc[n] = mfma(ld_tr(sX, DA + PAD, s0, ab * 32, lane), ld_tr(sY, DB + PAD, s0, bb * 32, lane),
+                                      acc[n]);
+                }
+                __syncthreads();
+            }
+        }
+    }
+    const int r = lane & 31, h = lane >> 5;
+#pragma unroll
+    for (int n = 0; n < NT; ++n) {
+        const int id = w + 4 * n, ab = id / BB, bb = id % BB;
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+#pragma unroll
+            for (int b = 0; b < 4; ++b)
+                out[(ab * 32 + 8 * a + 4 * h + b) * DB + bb * 32 + r] = acc[n][4 * a + b];
+    }
+}
+
+// =============================================================================================== forward sweep body
+// One workgroup (4 waves) per segment.  Per chunk of C tokens:
 //   P^T = K Q^T (masked), O^T = V^T P^T + S_prev^T Q^T, store O, S += K^T V.
 // Wave w owns output rows [32*tb, 32*tb+32) with tb = w % WT and NJ column tiles; it recomputes the score
 // tiles of its row block itself (matrix-core time is cheap here, LDS round trips and barriers are not).
 template <int C, int DK, int DV>
-__global__ __launch_bounds__(256) void bf16_fwd_sweep_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K,
-                                                            const bf16* __restrict__ V, bf16* __restrict__ O,
-                                                            const float* __restrict__ S0, int N, int seg_len, int n_seg)
+struct FwdLds {
+    static constexpr int LDK = DK + PAD, LDV = DV + PAD;
+    static constexpr int BYTES = (2 * C * LDK + C * LDV + DV * LDK) * 2;
+};
+
+template <int C, int DK, int DV>
+__device__ __forceinline__ void fwd_sweep_body(const bf16* __restrict__ Qb, const bf16* __restrict__ Kb,
+                                               const bf16* __restrict__ Vb, bf16* __restrict__ Ob,
+                                               const float* __restrict__ S0, int ntok, unsigned char* lds, int tid,
+                                               int w, int lane)
 {
     constexpr int LDK = DK + PAD, LDV = DV + PAD;
     constexpr int TB = C / 32, JB = DV / 32, IB = DK / 32;
     constexpr int WT = TB < 4 ? TB : 4, WJ = 4 / WT, NJ = JB / WJ;
     constexpr int NS = IB * JB / 4;
     static_assert(TB <= 4 && JB % WJ == 0, "unsupported tile shape");
-    __shared__ __attribute__((aligned(16))) bf16 sQ[C * LDK];
-    __shared__ __attribute__((aligned(16))) bf16 sK[C * LDK];
-    __shared__ __attribute__((aligned(16))) bf16 sV[C * LDV];
-    __shared__ __attribute__((aligned(16))) bf16 sST[DV * LDK];   // S^T as bf16: [j][i]
-
-    const int seg = blockIdx.x;
-    const long bh = blockIdx.y;
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    bf16* sQ = reinterpret_cast<bf16*>(lds);
+    bf16* sK = sQ + C * LDK;
+    bf16* sV = sK + C * LDK;
+    bf16* sST = sV + C * LDV;          // S^T as bf16: [j][i]
     const int tb = w % WT, jg = w / WT;
-    const bf16* Qb = Q + (size_t)bh * N * DK;
-    const bf16* Kb = K + (size_t)bh * N * DK;
-    const bf16* Vb = V + (size_t)bh * N * DV;
-    bf16* Ob = O + (size_t)bh * N * DV;
-    const int p0 = seg * seg_len, p1 = min(N, p0 + seg_len);
 
     unsigned maskK[8];
     make_masks<true>(maskK, lane);
 
-    f32x16 accS[NS];
-    load_state<DK, DV, false>(accS, (S0 != nullptr && seg > 0) ? S0 + ((size_t)bh * n_seg + seg) * DK * DV : nullptr,
-                              w, lane);
-
     TileRegs<C, DK> rq, rk;
     TileRegs<C, DV> rv;
-    rq.load(Qb + (size_t)p0 * DK, p1 - p0, tid);
-    rk.load(Kb + (size_t)p0 * DK, p1 - p0, tid);
-    rv.load(Vb + (size_t)p0 * DV, p1 - p0, tid);
+    rq.load(Qb, ntok, tid);
+    rk.load(Kb, ntok, tid);
+    rv.load(Vb, ntok, tid);
 
-    for (int c0 = p0; c0 < p1; c0 += C) {
+    f32x16 accS[NS];
+    load_state<DK, DV, false>(accS, S0, w, lane);
+
+    for (int c0 = 0; c0 < ntok; c0 += C) {
         rq.store(sQ, tid);
         rk.store(sK, tid);
         rv.store(sV, tid);
         state_to_lds_T<DK, DV, false>(sST, accS, w, lane);
         __syncthreads();
-        const bool more = c0 + C < p1;
+        const bool more = c0 + C < ntok;
         if (more) {
-            rq.load(Qb + (size_t)(c0 + C) * DK, p1 - c0 - C, tid);
-            rk.load(Kb + (size_t)(c0 + C) * DK, p1 - c0 - C, tid);
-            rv.load(Vb + (size_t)(c0 + C) * DV, p1 - c0 - C, tid);
+            rq.load(Qb + (size_t)(c0 + C) * DK, ntok - c0 - C, tid);
+            rk.load(Kb + (size_t)(c0 + C) * DK, ntok - c0 - C, tid);
+            rv.load(Vb + (size_t)(c0 + C) * DV, ntok - c0 - C, tid);
         }
         bf16x8 bQ[DK / 16];   // Q rows of this wave's token block: the B operand (n = token, k = feature i)
 #pragma unroll
@@ -468,7 +376,7 @@ __global__ __launch_bounds__(256) void bf16_fwd_sweep_kernel(const bf16* __restr
         }
         {
             bf16* rows = Ob + (size_t)(c0 + tb * 32) * DV;
-            const int valid = p1 - (c0 + tb * 32);
+            const int valid = ntok - (c0 + tb * 32);
 #pragma unroll
             for (int n = 0; n < NJ; ++n) store_tile_T(rows, DV, (jg * NJ + n) * 32, accO[n], valid, lane);
         }
@@ -486,70 +394,60 @@ __global__ __launch_bounds__(256) void bf16_fwd_sweep_kernel(const bf16* __restr
     }
 }
 
-// =============================================================================================== backward sweep
-// One workgroup per (segment, bh), walking the chunks from the LAST to the first, so that each input tile is
-// read once for all three gradients.  Two states live in accumulator registers, both stored transposed
-// ([dv][dk], lane = one feature i, 4 consecutive j):
+// =============================================================================================== backward sweep body
+// One workgroup per segment, walking the chunks from the LAST to the first, so that each input tile is read once
+// for all three gradients.  Two states live in accumulator registers, both stored transposed ([dv][dk], lane = one
+// feature i, 4 consecutive j):
 //   -S^T: minus the sum of V^T K over tokens before the current chunk.  It enters as the inclusive prefix at the
 //         end of the segment and is rolled BACK by one chunk per step (S_{c-1} = S_c - V_c^T K_c, fp32); keeping
 //         the negative makes the roll-back a plain accumulate and the sign is restored for free when rounding.
 //   R^T : sum of dO^T Q over tokens after the current chunk; it grows by one chunk per step.
 // Per chunk:  dQ = dP K + dO S^T',  dK = dP^T Q + V R^T',  dV = P^T dO + K R,
 //             P = (Q K^T) o M,  dP = (dO V^T) o M, every output accumulated transposed.
+// Send == nullptr means the whole sequence is this one segment: S is then built here, R starts at zero.
 template <int C, int DK, int DV>
-__global__ __launch_bounds__(256) void bf16_bwd_sweep_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K,
-                                                            const bf16* __restrict__ V, const bf16* __restrict__ dO,
-                                                            bf16* __restrict__ dQ, bf16* __restrict__ dK,
-                                                            bf16* __restrict__ dV, const float* __restrict__ Send,
-                                                            const float* __restrict__ Rnext, int N, int seg_len,
-                                                            int n_seg)
+struct BwdLds {
+    static constexpr int LDK = DK + PAD, LDV = DV + PAD;
+    static constexpr int BYTES = (2 * C * LDK + 2 * C * LDV + 2 * DK * LDV) * 2;
+};
+
+template <int C, int DK, int DV>
+__device__ __forceinline__ void bwd_sweep_body(const bf16* __restrict__ Qb, const bf16* __restrict__ Kb,
+                                               const bf16* __restrict__ Vb, const bf16* __restrict__ Gb,
+                                               bf16* __restrict__ dQb, bf16* __restrict__ dKb, bf16* __restrict__ dVb,
+                                               const float* __restrict__ Send, const float* __restrict__ Rnext,
+                                               int ntok, unsigned char* lds, int tid, int w, int lane)
 {
     constexpr int LDK = DK + PAD, LDV = DV + PAD;
     constexpr int TB = C / 32, JB = DV / 32, IB = DK / 32;
     constexpr int WT = TB < 4 ? TB : 4, WJ = 4 / WT, NJ = JB / WJ, NI = IB / WJ;
     constexpr int NS = IB * JB / 4;
     static_assert(TB <= 4 && JB % WJ == 0 && IB % WJ == 0, "unsupported tile shape");
-    __shared__ __attribute__((aligned(16))) bf16 sQ[C * LDK];
-    __shared__ __attribute__((aligned(16))) bf16 sK[C * LDK];
-    __shared__ __attribute__((aligned(16))) bf16 sV[C * LDV];
-    __shared__ __attribute__((aligned(16))) bf16 sG[C * LDV];     // dO
-    __shared__ __attribute__((aligned(16))) bf16 sS[DK * LDV];    // S  [i][j] bf16
-    __shared__ __attribute__((aligned(16))) bf16 sR[DK * LDV];    // R  [i][j] bf16
-
-    const int seg = blockIdx.x;
-    const long bh = blockIdx.y;
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    bf16* sQ = reinterpret_cast<bf16*>(lds);
+    bf16* sK = sQ + C * LDK;
+    bf16* sV = sK + C * LDK;
+    bf16* sG = sV + C * LDV;           // dO
+    bf16* sS = sG + C * LDV;           // S  [i][j] bf16
+    bf16* sR = sS + DK * LDV;          // R  [i][j] bf16
     const int rb = w % WT, cg = w / WT;
-    const bf16* Qb = Q + (size_t)bh * N * DK;
-    const bf16* Kb = K + (size_t)bh * N * DK;
-    const bf16* Vb = V + (size_t)bh * N * DV;
-    const bf16* Gb = dO + (size_t)bh * N * DV;
-    bf16* dQb = dQ + (size_t)bh * N * DK;
-    bf16* dKb = dK + (size_t)bh * N * DK;
-    bf16* dVb = dV + (size_t)bh * N * DV;
-    const int p0 = seg * seg_len, p1 = min(N, p0 + seg_len);
-    const int n_ch = (p1 - p0 + C - 1) / C;
+    const int n_ch = (ntok + C - 1) / C;
 
     unsigned maskK[8], maskQ[8];
     make_masks<true>(maskK, lane);
     make_masks<false>(maskQ, lane);
 
-    // states, transposed: [DV][DK]; accNS holds MINUS S^T
-    f32x16 accNS[NS], accRT[NS];
-    const size_t soff = ((size_t)bh * n_seg + seg) * DK * DV;
-    load_state<DV, DK, true>(accNS, Send ? Send + soff : nullptr, w, lane);
-    load_state<DV, DK, false>(accRT, (Rnext != nullptr && seg < n_seg - 1) ? Rnext + soff : nullptr, w, lane);
-
     TileRegs<C, DK> rq, rk;
     TileRegs<C, DV> rv, rg;
+    f32x16 accNS[NS], accRT[NS];       // states, transposed: [DV][DK]; accNS holds MINUS S^T
 
     if (Send == nullptr) {
         // single segment: no pre-pass ran, build -S^T = -sum V^T K over the whole sequence here
+#pragma unroll
+        for (int n = 0; n < NS; ++n) { accNS[n] = zero16(); accRT[n] = zero16(); }
         for (int ci = 0; ci < n_ch; ++ci) {
-            const int c0 = p0 + ci * C;
-            rk.load(Kb + (size_t)c0 * DK, p1 - c0, tid);
-            rv.load(Vb + (size_t)c0 * DV, p1 - c0, tid);
+            const int c0 = ci * C;
+            rk.load(Kb + (size_t)c0 * DK, ntok - c0, tid);
+            rv.load(Vb + (size_t)c0 * DV, ntok - c0, tid);
             __syncthreads();
             rk.store(sK, tid);
             rv.store(sV, tid);
@@ -559,9 +457,8 @@ __global__ __launch_bounds__(256) void bf16_bwd_sweep_kernel(const bf16* __restr
                 const int id = w + 4 * n, jb = id / IB, ib = id % IB;
 #pragma unroll
                 for (int s0 = 0; s0 < C; s0 += 16) {
-                    // minus sign: flip the sign bits of one operand
                     u32x4 a = __builtin_bit_cast(u32x4, ld_tr(sV, LDV, s0, jb * 32, lane));
-                    a ^= 0x80008000u;
+                    a ^= 0x80008000u;   // minus sign: flip the sign bits of one operand
                     accNS[n] = mfma(__builtin_bit_cast(bf16x8, a), ld_tr(sK, LDK, s0, ib * 32, lane), accNS[n]);
                 }
             }
@@ -570,15 +467,19 @@ __global__ __launch_bounds__(256) void bf16_bwd_sweep_kernel(const bf16* __restr
     }
 
     {
-        const int c0 = p0 + (n_ch - 1) * C;
-        rq.load(Qb + (size_t)c0 * DK, p1 - c0, tid);
-        rk.load(Kb + (size_t)c0 * DK, p1 - c0, tid);
-        rv.load(Vb + (size_t)c0 * DV, p1 - c0, tid);
-        rg.load(Gb + (size_t)c0 * DV, p1 - c0, tid);
+        const int c0 = (n_ch - 1) * C;
+        rq.load(Qb + (size_t)c0 * DK, ntok - c0, tid);
+        rk.load(Kb + (size_t)c0 * DK, ntok - c0, tid);
+        rv.load(Vb + (size_t)c0 * DV, ntok - c0, tid);
+        rg.load(Gb + (size_t)c0 * DV, ntok - c0, tid);
+    }
+    if (Send != nullptr) {
+        load_state<DV, DK, true>(accNS, Send, w, lane);
+        load_state<DV, DK, false>(accRT, Rnext, w, lane);
     }
 
     for (int ci = n_ch - 1; ci >= 0; --ci) {
-        const int c0 = p0 + ci * C;
+        const int c0 = ci * C;
         rq.store(sQ, tid);
         rk.store(sK, tid);
         rv.store(sV, tid);
@@ -603,7 +504,7 @@ __global__ __launch_bounds__(256) void bf16_bwd_sweep_kernel(const bf16* __restr
         state_to_lds_T<DV, DK, true>(sS, accNS, w, lane);
         __syncthreads();
 
-        const int valid = p1 - (c0 + rb * 32);   // rows of this wave's 32-token block that exist
+        const int valid = ntok - (c0 + rb * 32);   // rows of this wave's 32-token block that exist
         // ---------------- dQ^T for token block tb = rb:  dQ^T = K^T dP^T + S dO^T
         {
             bf16x8 bG[DV / 16];
@@ -717,6 +618,67 @@ __global__ __launch_bounds__(256) void bf16_bwd_sweep_kernel(const bf16* __restr
     }
 }
 
+// =============================================================================================== kernels
+struct SegStateArgs {
+    const bf16* X[2];
+    const bf16* Y[2];
+    float* out[2];
+    int skip_seg[2];   // a segment whose total the scan never uses (-1: none)
+};
+
+template <int DA, int DB>
+__global__ __launch_bounds__(256) void bf16_seg_state_kernel(SegStateArgs args, int N, int seg_len, int n_seg)
+{
+    __shared__ __attribute__((aligned(16))) unsigned char lds[PrepassLds<DA, DB>::BYTES];
+    const int z = blockIdx.z, seg = blockIdx.x;
+    const long bh = blockIdx.y;
+    if (seg == args.skip_seg[z]) return;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int p0 = seg * seg_len, p1 = min(N, p0 + seg_len);
+    prepass_body<DA, DB>(args.X[z] + ((size_t)bh * N + p0) * DA, args.Y[z] + ((size_t)bh * N + p0) * DB,
+                                args.out[z] + ((size_t)bh * n_seg + seg) * DA * DB, p1 - p0, lds, tid, w, lane);
+}
+
+template <int C, int DK, int DV>
+__global__ __launch_bounds__(256) void bf16_fwd_sweep_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K,
+                                                            const bf16* __restrict__ V, bf16* __restrict__ O,
+                                                            const float* __restrict__ S0, int N, int seg_len, int n_seg)
+{
+    __shared__ __attribute__((aligned(16))) unsigned char lds[FwdLds<C, DK, DV>::BYTES];
+    const int seg = blockIdx.x;
+    const long bh = blockIdx.y;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int p0 = seg * seg_len, p1 = min(N, p0 + seg_len);
+    const size_t rk = ((size_t)bh * N + p0) * DK, rv = ((size_t)bh * N + p0) * DV;
+    fwd_sweep_body<C, DK, DV>(Q + rk, K + rk, V + rv, O + rv,
+                                     (S0 != nullptr && seg > 0) ? S0 + ((size_t)bh * n_seg + seg) * DK * DV : nullptr,
+                                     p1 - p0, lds, tid, w, lane);
+}
+
+template <int C, int DK, int DV>
+__global__ __launch_bounds__(256) void bf16_bwd_sweep_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K,
+                                                            const bf16* __restrict__ V, const bf16* __restrict__ dO,
+                                                            bf16* __restrict__ dQ, bf16* __restrict__ dK,
+                                                            bf16* __restrict__ dV, const float* __restrict__ Send,
+                                                            const float* __restrict__ Rnext, int N, int seg_len,
+                                                            int n_seg)
+{
+    __shared__ __attribute__((aligned(16))) unsigned char lds[BwdLds<C, DK, DV>::BYTES];
+    const int seg = blockIdx.x;
+    const long bh = blockIdx.y;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int p0 = seg * seg_len, p1 = min(N, p0 + seg_len);
+    const size_t rk = ((size_t)bh * N + p0) * DK, rv = ((size_t)bh * N + p0) * DV;
+    const size_t soff = ((size_t)bh * n_seg + seg) * DK * DV;
+    // the scan leaves zeros in the last segment's R slot, so Rnext can be read for every segment
+    bwd_sweep_body<C, DK, DV>(Q + rk, K + rk, V + rv, dO + rv, dQ + rk, dK + rk, dV + rv,
+                                     Send ? Send + soff : nullptr, Rnext ? Rnext + soff : nullptr, p1 - p0, lds, tid, w,
+                                     lane);
+}
+
 // =============================================================================================== launchers
 // Pre-pass + scan over segments.
 template <int DA, int DB>
@@ -739,16 +701,17 @@ static hipError_t fwd_impl(const bf16* Q, const bf16* K, const bf16* V, bf16* O,
                            float* ws, hipStream_t st)
 {
     hipError_t e;
+    float* states = ws;
     if (plan.n_seg > 1) {
         SegStateArgs a{};
-        a.X[0] = K; a.Y[0] = V; a.out[0] = ws; a.skip_seg[0] = plan.n_seg - 1;
+        a.X[0] = K; a.Y[0] = V; a.out[0] = states; a.skip_seg[0] = plan.n_seg - 1;
         const int mode = SCAN_EXCL_PREFIX;
         if ((e = run_seg_state<DK, DV>(a, 1, &mode, BH, N, plan, st)) != hipSuccess) return e;
     }
     dim3 grid(plan.n_seg, (unsigned)BH);
     ProfScope prof(KID_FWD_SWEEP_BF16, st);
     hipLaunchKernelGGL((bf16_fwd_sweep_kernel<C, DK, DV>), grid, dim3(256), 0, st, Q, K, V, O,
-                       plan.n_seg > 1 ? ws : nullptr, N, plan.seg_len, plan.n_seg);
+                       plan.n_seg > 1 ? states : nullptr, N, plan.seg_len, plan.n_seg);
     return hipGetLastError();
 }
 
@@ -758,7 +721,7 @@ static hipError_t bwd_impl(const bf16* Q, const bf16* K, const bf16* V, const bf
 {
     hipError_t e;
     float* wsS = ws;
-    float* wsR = ws ? ws + (size_t)BH * plan.n_seg * DK * DV : nullptr;
+    float* wsR = ws ? wsS + (size_t)BH * plan.n_seg * DK * DV : nullptr;
     if (plan.n_seg > 1) {
         SegStateArgs a{};
         // S^T totals: every segment is needed (inclusive prefix); R^T totals: the first is never used (exclusive suffix)
@@ -805,7 +768,5 @@ hipError_t launch_bf16_bwd(const void* Q, const void* K, const void* V, const vo
     CHELA_DISPATCH(64, 128, 128, (bwd_impl<64, 128, 128>(q, k, v, g, dq, dkk, dvv, BH, N, plan, ws, st)))
     return hipErrorInvalidValue;
 }
-
-void free_bf16_resources() {}
 
 }  // namespace chela
