@@ -78,6 +78,7 @@ Plan make_plan(long BH, int N, int dk, int dv, int chunk, int dtype, bool is_bwd
     if (forced > 0) cps = (forced + chunk - 1) / chunk;
     if (cps > n_chunks) cps = n_chunks;
     if (cps < 1) cps = 1;
+    if ((n_chunks + cps - 1) / cps > 32768) cps = (n_chunks + 32767) / 32768;   // segments ride on grid.y
     p.seg_len = (int)(cps * chunk);
     p.n_seg = (int)((n_chunks + cps - 1) / cps);
     const int n_states = (dtype == CHELA_DTYPE_BF16 && is_bwd) ? 2 : 1;   // fp32 bwd reuses one array 3 times

@@ -630,8 +630,8 @@ template <int DA, int DB>
 __global__ __launch_bounds__(256) void bf16_seg_state_kernel(SegStateArgs args, int N, int seg_len, int n_seg)
 {
     __shared__ __attribute__((aligned(16))) unsigned char lds[PrepassLds<DA, DB>::BYTES];
-    const int z = blockIdx.z, seg = blockIdx.x;
-    const long bh = blockIdx.y;
+    const int z = blockIdx.z, seg = blockIdx.y;   // heads on grid.x: its limit is 2^31-1, the others' 65535
+    const long bh = blockIdx.x;
     if (seg == args.skip_seg[z]) return;
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -646,8 +646,8 @@ __global__ __launch_bounds__(256) void bf16_fwd_sweep_kernel(const bf16* __restr
                                                             const float* __restrict__ S0, int N, int seg_len, int n_seg)
 {
     __shared__ __attribute__((aligned(16))) unsigned char lds[FwdLds<C, DK, DV>::BYTES];
-    const int seg = blockIdx.x;
-    const long bh = blockIdx.y;
+    const int seg = blockIdx.y;
+    const long bh = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int p0 = seg * seg_len, p1 = min(N, p0 + seg_len);
@@ -666,8 +666,8 @@ __global__ __launch_bounds__(256) void bf16_bwd_sweep_kernel(const bf16* __restr
                                                             int n_seg)
 {
     __shared__ __attribute__((aligned(16))) unsigned char lds[BwdLds<C, DK, DV>::BYTES];
-    const int seg = blockIdx.x;
-    const long bh = blockIdx.y;
+    const int seg = blockIdx.y;
+    const long bh = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int p0 = seg * seg_len, p1 = min(N, p0 + seg_len);
@@ -687,7 +687,7 @@ static hipError_t run_seg_state(const SegStateArgs& a, int npairs, const int* sc
 {
     hipError_t e;
     {
-        dim3 grid(plan.n_seg, (unsigned)BH, npairs);
+        dim3 grid((unsigned)BH, plan.n_seg, npairs);
         ProfScope prof(KID_SEG_STATE_BF16, st);
         hipLaunchKernelGGL((bf16_seg_state_kernel<DA, DB>), grid, dim3(256), 0, st, a, N, plan.seg_len, plan.n_seg);
         if ((e = hipGetLastError()) != hipSuccess) return e;
@@ -708,7 +708,7 @@ static hipError_t fwd_impl(const bf16* Q, const bf16* K, const bf16* V, bf16* O,
         const int mode = SCAN_EXCL_PREFIX;
         if ((e = run_seg_state<DK, DV>(a, 1, &mode, BH, N, plan, st)) != hipSuccess) return e;
     }
-    dim3 grid(plan.n_seg, (unsigned)BH);
+    dim3 grid((unsigned)BH, plan.n_seg);
     ProfScope prof(KID_FWD_SWEEP_BF16, st);
     hipLaunchKernelGGL((bf16_fwd_sweep_kernel<C, DK, DV>), grid, dim3(256), 0, st, Q, K, V, O,
                        plan.n_seg > 1 ? states : nullptr, N, plan.seg_len, plan.n_seg);
@@ -730,7 +730,7 @@ static hipError_t bwd_impl(const bf16* Q, const bf16* K, const bf16* V, const bf
         const int modes[2] = {SCAN_INCL_PREFIX, SCAN_EXCL_SUFFIX};
         if ((e = run_seg_state<DV, DK>(a, 2, modes, BH, N, plan, st)) != hipSuccess) return e;
     }
-    dim3 grid(plan.n_seg, (unsigned)BH);
+    dim3 grid((unsigned)BH, plan.n_seg);
     ProfScope prof(KID_BWD_SWEEP_BF16, st);
     hipLaunchKernelGGL((bf16_bwd_sweep_kernel<C, DK, DV>), grid, dim3(256), 0, st, Q, K, V, dO, dQ, dK, dV,
                        plan.n_seg > 1 ? wsS : nullptr, plan.n_seg > 1 ? wsR : nullptr, N, plan.seg_len, plan.n_seg);

@@ -18,10 +18,10 @@ struct ScanModes { int mode[2]; };
 __global__ __launch_bounds__(256) void scan_states_kernel(float* __restrict__ st, size_t array_stride, int n_seg,
                                                          int elems, ScanModes modes)
 {
-    const long bh = blockIdx.y;
+    const long bh = blockIdx.x;     // heads on grid.x: its limit is 2^31-1, the others' 65535
     const int z = blockIdx.z;
     const int mode = modes.mode[z];
-    const int e = (blockIdx.x * 256 + threadIdx.x) * 4;
+    const int e = (blockIdx.y * 256 + threadIdx.x) * 4;
     if (e >= elems) return;
     float* p = st + (size_t)z * array_stride + (size_t)bh * n_seg * elems + e;
     float4 run = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -58,7 +58,7 @@ hipError_t scan_states(float* states, size_t array_stride, int n_arrays, const i
 {
     ScanModes m{};
     for (int z = 0; z < n_arrays && z < 2; ++z) m.mode[z] = modes[z];
-    dim3 grid((elems / 4 + 255) / 256, (unsigned)BH, n_arrays);
+    dim3 grid((unsigned)BH, (elems / 4 + 255) / 256, n_arrays);
     ProfScope prof(KID_SCAN, st);
     hipLaunchKernelGGL(scan_states_kernel, grid, dim3(256), 0, st, states, array_stride, n_seg, elems, m);
     return hipGetLastError();
@@ -93,8 +93,8 @@ __global__ __launch_bounds__(256) void f32_seg_state_kernel(const float* __restr
                                                            int seg_len, int n_seg, int rev)
 {
     extern __shared__ float lds[];
-    const int seg = blockIdx.x;
-    const long bh = blockIdx.y;
+    const int seg = blockIdx.y;
+    const long bh = blockIdx.x;
     if (seg == n_seg - 1) return;
     constexpr int R = 16;                         // rows staged per step
     float* sK = lds;                              // [R][dk]
@@ -150,8 +150,8 @@ __global__ __launch_bounds__(256) void f32_sweep_kernel(const float* __restrict_
     float* sV = sK + C * ldk;
     float* sP = sV + C * ldv;
     float* sS = sP + C * ldp;
-    const int seg = blockIdx.x;
-    const long bh = blockIdx.y;
+    const int seg = blockIdx.y;
+    const long bh = blockIdx.x;
     const int tid = threadIdx.x;
     const float* Qb = Q + (size_t)bh * N * dk;
     const float* Kb = K + (size_t)bh * N * dk;
@@ -232,7 +232,7 @@ hipError_t launch_f32(const float* Q, const float* K, const float* V, float* O, 
     hipError_t e;
     const int C = plan.chunk;
     if (plan.n_seg > 1) {
-        dim3 grid(plan.n_seg, (unsigned)BH);
+        dim3 grid((unsigned)BH, plan.n_seg);
         size_t lds1 = sizeof(float) * 16 * (size_t)(dk + dv);
         {
             ProfScope prof(KID_SEG_STATE_F32, st);
@@ -246,7 +246,7 @@ hipError_t launch_f32(const float* Q, const float* K, const float* V, float* O, 
     const size_t lds = f32_sweep_lds(dk, dv, C);
     e = hipFuncSetAttribute((const void*)f32_sweep_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    dim3 grid(plan.n_seg, (unsigned)BH);
+    dim3 grid((unsigned)BH, plan.n_seg);
     ProfScope prof(KID_SWEEP_F32, st);
     hipLaunchKernelGGL(f32_sweep_kernel, grid, dim3(256), lds, st, Q, K, V, O, plan.n_seg > 1 ? ws : nullptr, N, dk,
                        dv, C, plan.seg_len, plan.n_seg, (int)rev);

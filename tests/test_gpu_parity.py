@@ -234,6 +234,25 @@ def test_caller_workspace_and_side_stream():
         binding.chela_set_workspace(None)
 
 
+def test_more_heads_than_a_grid_dimension_holds():
+    # 70 000 (b,h) pairs: more than the 65 535 a secondary grid dimension can carry
+    B, H, N, d = 1, 70000, 64, 64
+    g = torch.Generator(device="cpu")
+    g.manual_seed(5)
+    mk = lambda: (torch.randn(B, H, N, d, generator=g) / 8).to(torch.bfloat16)
+    Q, K, V, dO = mk(), mk(), mk() * 8, mk() * 8
+    dev = [t.cuda() for t in (Q, K, V, dO)]
+    O = binding.chela_linattn_fwd(*dev[:3])
+    dQ, dK, dV = binding.chela_linattn_bwd(*dev)
+    torch.cuda.synchronize()
+    idx = torch.tensor([0, 1, 32767, 65535, 65536, 69998, 69999])
+    sel = lambda t: t[:, idx.to(t.device)]
+    Qn, Kn, Vn, Gn = (to_f64_numpy(sel(t)) for t in (Q, K, V, dO))
+    _check("O", sel(O), oracle.fwd_recurrent(Qn, Kn, Vn), "bf16")
+    for name, got, ref in zip(("dQ", "dK", "dV"), (dQ, dK, dV), oracle.bwd_recurrent(Qn, Kn, Vn, Gn)):
+        _check(name, sel(got), ref, "bf16")
+
+
 def test_empty_inputs_on_device():
     z = torch.empty((2, 2, 0, 64), dtype=torch.bfloat16, device="cuda")
     O = binding.chela_linattn_fwd(z, z, z)
