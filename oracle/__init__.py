@@ -35,6 +35,15 @@ def _load():
             f = getattr(_lib, name)
             f.argtypes = [dp, dp, dp, dp, dp, dp, dp, i, i, i, i, i]
             f.restype = None
+        f = _lib.chela_oracle_fwd_state
+        f.argtypes = [dp, dp, dp, dp, dp, dp, i, i, i, i, i]
+        f.restype = None
+        f = _lib.chela_oracle_bwd_state
+        f.argtypes = [dp] * 10 + [i, i, i, i, i]
+        f.restype = None
+        f = _lib.chela_oracle_step
+        f.argtypes = [dp, dp, dp, dp, dp, i, i, i, i]
+        f.restype = None
         _lib.chela_oracle_num_threads.restype = ctypes.c_int
     return _lib
 
@@ -106,6 +115,54 @@ def bwd_quadratic(Q, K, V, dO):
 def bwd_recurrent(Q, K, V, dO):
     """(dQ, dK, dV) by a forward state sweep (dQ) and a reverse state sweep (dK, dV)."""
     return _bwd("chela_oracle_bwd_recurrent", Q, K, V, dO)
+
+
+def _opt_state(S, B, H, dk, dv):
+    if S is None:
+        return None, None
+    a = np.ascontiguousarray(np.asarray(S, dtype=np.float64))
+    if a.shape != (B, H, dk, dv):
+        raise ValueError("state must be [B, H, dk, dv]")
+    return a, _ptr(a)
+
+
+def fwd_state(Q, K, V, S_in=None):
+    """(O, S_out) with the running state started at S_in (zero if None): segment-wise processing, Sec. 5.2."""
+    Q, K, V = _f64(Q), _f64(K), _f64(V)
+    B, H, N, dk, dv = _shapes(Q, K, V)
+    S_in, p_in = _opt_state(S_in, B, H, dk, dv)
+    O = np.empty((B, H, N, dv), dtype=np.float64)
+    S_out = np.zeros((B, H, dk, dv), dtype=np.float64)
+    _load().chela_oracle_fwd_state(_ptr(Q), _ptr(K), _ptr(V), p_in, _ptr(O), _ptr(S_out), B, H, N, dk, dv)
+    return O, S_out
+
+
+def bwd_state(Q, K, V, dO, S_in=None, dS_out=None):
+    """(dQ, dK, dV, dS_in) of (Q, K, V, S_in) -> (O, S_out) for upstream gradients dO and dS_out."""
+    Q, K, V, dO = _f64(Q), _f64(K), _f64(V), _f64(dO)
+    B, H, N, dk, dv = _shapes(Q, K, V)
+    S_in, p_in = _opt_state(S_in, B, H, dk, dv)
+    dS_out, p_out = _opt_state(dS_out, B, H, dk, dv)
+    dQ, dK, dV = np.empty_like(Q), np.empty_like(K), np.empty_like(V)
+    dS_in = np.zeros((B, H, dk, dv), dtype=np.float64)
+    _load().chela_oracle_bwd_state(_ptr(Q), _ptr(K), _ptr(V), p_in, _ptr(dO), p_out, _ptr(dQ), _ptr(dK), _ptr(dV),
+                                   _ptr(dS_in), B, H, N, dk, dv)
+    return dQ, dK, dV, dS_in
+
+
+def step(q, k, v, S):
+    """One decode step: returns (o, S_new) with S_new = S + k v^T and o = S_new^T q; q,k: [B,H,dk], v: [B,H,dv]."""
+    q = np.ascontiguousarray(np.asarray(q, dtype=np.float64))
+    k = np.ascontiguousarray(np.asarray(k, dtype=np.float64))
+    v = np.ascontiguousarray(np.asarray(v, dtype=np.float64))
+    S = np.array(S, dtype=np.float64, order="C", copy=True)
+    B, H, dk = q.shape
+    dv = v.shape[2]
+    if k.shape != q.shape or v.shape[:2] != (B, H) or S.shape != (B, H, dk, dv):
+        raise ValueError("shapes: q,k [B,H,dk]; v [B,H,dv]; S [B,H,dk,dv]")
+    o = np.empty((B, H, dv), dtype=np.float64)
+    _load().chela_oracle_step(_ptr(q), _ptr(k), _ptr(v), _ptr(S), _ptr(o), B, H, dk, dv)
+    return o, S
 
 
 def rel_l2(x, ref) -> float:

@@ -170,3 +170,111 @@ void chela_oracle_bwd_recurrent(const double *Q, const double *K, const double *
         free(S);
     }
 }
+
+/* ==========================================================================
+ * State carry-in / carry-out (segment-wise processing, Sec. 5.2 and App. A:
+ * training data is split into segments of consecutive chunks and test data
+ * is processed segment by segment).  The running state of the recurrent form
+ * is the only thing one segment hands to the next:
+ *
+ *     S_0 = S_in ;  S_t = S_{t-1} + k_t v_t^T ;  o_t = S_t^T q_t ;  S_out = S_N .
+ *
+ * S_in, S_out: [B, H, dk, dv].  A NULL S_in means zero; a NULL S_out is not
+ * written.  With S_in = NULL and S_out = NULL this is chela_oracle_fwd_recurrent.
+ * ========================================================================== */
+void chela_oracle_fwd_state(const double *Q, const double *K, const double *V, const double *S_in,
+                            double *O, double *S_out, int B, int H, int N, int dk, int dv)
+{
+    const long BH = (long)B * H;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long bh = 0; bh < BH; ++bh) {
+        const double *q = Q + bh * (long)N * dk;
+        const double *k = K + bh * (long)N * dk;
+        const double *v = V + bh * (long)N * dv;
+        double *o = O + bh * (long)N * dv;
+        double *S = (double *)calloc((size_t)dk * dv, sizeof(double));
+        if (S_in) memcpy(S, S_in + bh * (long)dk * dv, sizeof(double) * (size_t)dk * dv);
+        for (int t = 0; t < N; ++t) {
+            for (int i = 0; i < dk; ++i)
+                for (int j = 0; j < dv; ++j)
+                    S[(long)i * dv + j] += k[(long)t * dk + i] * v[(long)t * dv + j];
+            for (int j = 0; j < dv; ++j) {
+                double acc = 0.0;
+                for (int i = 0; i < dk; ++i) acc += S[(long)i * dv + j] * q[(long)t * dk + i];
+                o[(long)t * dv + j] = acc;
+            }
+        }
+        if (S_out) memcpy(S_out + bh * (long)dk * dv, S, sizeof(double) * (size_t)dk * dv);
+        free(S);
+    }
+}
+
+/* Gradient of the map (Q, K, V, S_in) -> (O, S_out) for upstream gradients dO and dS_out (NULL = zero).
+ * Forward sweep : S_t as above ;  dq_t = S_t dO_t.
+ * Reverse sweep : R_{N+1} = dS_out ;  R_t = R_{t+1} + q_t dO_t^T ;  dk_t = R_t v_t ;  dv_t = R_t^T k_t.
+ * dS_in = R_1 (every later state contains S_in once).  A NULL dS_in is not written. */
+void chela_oracle_bwd_state(const double *Q, const double *K, const double *V, const double *S_in,
+                            const double *dO, const double *dS_out, double *dQ, double *dK, double *dV,
+                            double *dS_in, int B, int H, int N, int dk, int dv)
+{
+    const long BH = (long)B * H;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long bh = 0; bh < BH; ++bh) {
+        const double *q = Q + bh * (long)N * dk;
+        const double *k = K + bh * (long)N * dk;
+        const double *v = V + bh * (long)N * dv;
+        const double *g = dO + bh * (long)N * dv;
+        double *dq = dQ + bh * (long)N * dk;
+        double *dkk = dK + bh * (long)N * dk;
+        double *dvv = dV + bh * (long)N * dv;
+        double *S = (double *)calloc((size_t)dk * dv, sizeof(double));
+        if (S_in) memcpy(S, S_in + bh * (long)dk * dv, sizeof(double) * (size_t)dk * dv);
+        for (int t = 0; t < N; ++t) {
+            for (int i = 0; i < dk; ++i)
+                for (int j = 0; j < dv; ++j)
+                    S[(long)i * dv + j] += k[(long)t * dk + i] * v[(long)t * dv + j];
+            for (int i = 0; i < dk; ++i) {
+                double acc = 0.0;
+                for (int j = 0; j < dv; ++j) acc += S[(long)i * dv + j] * g[(long)t * dv + j];
+                dq[(long)t * dk + i] = acc;
+            }
+        }
+        memset(S, 0, sizeof(double) * (size_t)dk * dv);   /* S now plays the role of R */
+        if (dS_out) memcpy(S, dS_out + bh * (long)dk * dv, sizeof(double) * (size_t)dk * dv);
+        for (int t = N - 1; t >= 0; --t) {
+            for (int i = 0; i < dk; ++i)
+                for (int j = 0; j < dv; ++j)
+                    S[(long)i * dv + j] += q[(long)t * dk + i] * g[(long)t * dv + j];
+            for (int i = 0; i < dk; ++i) {
+                double acc = 0.0;
+                for (int j = 0; j < dv; ++j) acc += S[(long)i * dv + j] * v[(long)t * dv + j];
+                dkk[(long)t * dk + i] = acc;
+            }
+            for (int j = 0; j < dv; ++j) {
+                double acc = 0.0;
+                for (int i = 0; i < dk; ++i) acc += S[(long)i * dv + j] * k[(long)t * dk + i];
+                dvv[(long)t * dv + j] = acc;
+            }
+        }
+        if (dS_in) memcpy(dS_in + bh * (long)dk * dv, S, sizeof(double) * (size_t)dk * dv);
+        free(S);
+    }
+}
+
+/* One decode step (autoregressive inference): S += k v^T ; o = S^T q, for every (b, h).
+ * q, k: [B, H, dk]; v, o: [B, H, dv]; S: [B, H, dk, dv], updated in place. */
+void chela_oracle_step(const double *q, const double *k, const double *v, double *S, double *o,
+                       int B, int H, int dk, int dv)
+{
+    const long BH = (long)B * H;
+    for (long bh = 0; bh < BH; ++bh) {
+        double *s = S + bh * (long)dk * dv;
+        for (int i = 0; i < dk; ++i)
+            for (int j = 0; j < dv; ++j) s[(long)i * dv + j] += k[bh * dk + i] * v[bh * dv + j];
+        for (int j = 0; j < dv; ++j) {
+            double acc = 0.0;
+            for (int i = 0; i < dk; ++i) acc += s[(long)i * dv + j] * q[bh * dk + i];
+            o[bh * dv + j] = acc;
+        }
+    }
+}

@@ -281,3 +281,91 @@ def test_empty_sequence():
 
 def test_oracle_reports_threads():
     assert oracle.num_threads() >= 1
+
+
+# =========================================================================== state carry-in / carry-out, decode step
+# The stateful oracle is pinned to the (already pinned) stateless one by the splitting identity -- processing a
+# sequence in two segments with the state handed over must equal processing it whole -- and by identities that the
+# mathematics fixes for the extra arguments.
+def test_state_oracle_reduces_to_stateless(rng):
+    Q, K, V, dO = _rand(rng, 2, 2, 19, 4, 3)
+    O, S_out = oracle.fwd_state(Q, K, V)
+    assert np.array_equal(O, oracle.fwd_recurrent(Q, K, V))
+    assert oracle.rel_l2(S_out, K.transpose(0, 1, 3, 2) @ V) < 1e-13       # final state = K^T V (library matmul)
+    dQ, dK, dV, dS_in = oracle.bwd_state(Q, K, V, dO)
+    for a, b in zip((dQ, dK, dV), oracle.bwd_recurrent(Q, K, V, dO)):
+        assert np.array_equal(a, b)
+    assert oracle.rel_l2(dS_in, Q.transpose(0, 1, 3, 2) @ dO) < 1e-13      # dS_in = Q^T dO when dS_out = 0
+
+
+@pytest.mark.parametrize("cut", [1, 7, 18])
+def test_splitting_identity_forward(cut, rng):
+    Q, K, V, _ = _rand(rng, 1, 3, 19, 5, 4, with_dO=False)
+    whole = oracle.fwd_quadratic(Q, K, V)                                   # the pinned definition
+    O1, S1 = oracle.fwd_state(Q[:, :, :cut], K[:, :, :cut], V[:, :, :cut])
+    O2, S2 = oracle.fwd_state(Q[:, :, cut:], K[:, :, cut:], V[:, :, cut:], S_in=S1)
+    assert oracle.rel_l2(np.concatenate([O1, O2], axis=2), whole) < 1e-13
+    assert oracle.rel_l2(S2, K.transpose(0, 1, 3, 2) @ V) < 1e-13
+
+
+@pytest.mark.parametrize("cut", [1, 9])
+def test_splitting_identity_backward(cut, rng):
+    # backward of the second segment yields dS_in, which is the first segment's dS_out
+    Q, K, V, dO = _rand(rng, 2, 1, 17, 3, 5)
+    want = oracle.bwd_quadratic(Q, K, V, dO)
+    a = (slice(None), slice(None), slice(0, cut))
+    b = (slice(None), slice(None), slice(cut, None))
+    _, S1 = oracle.fwd_state(Q[a], K[a], V[a])
+    dQ2, dK2, dV2, dS1 = oracle.bwd_state(Q[b], K[b], V[b], dO[b], S_in=S1)
+    dQ1, dK1, dV1, dS0 = oracle.bwd_state(Q[a], K[a], V[a], dO[a], dS_out=dS1)
+    for got, w in zip((np.concatenate([dQ1, dQ2], 2), np.concatenate([dK1, dK2], 2), np.concatenate([dV1, dV2], 2)), want):
+        assert oracle.rel_l2(got, w) < 1e-13
+    assert oracle.rel_l2(dS0, Q.transpose(0, 1, 3, 2) @ dO) < 1e-13
+
+
+def test_state_adjoint_identities(rng):
+    # L = <O, dO> + <S_out, dS_out> is linear in each of Q, K, V, S_in: <L(X+E) - L(X)> = <E, dX>
+    Q, K, V, dO = _rand(rng, 1, 2, 13, 4, 3)
+    S_in = rng.standard_normal((1, 2, 4, 3))
+    dS_out = rng.standard_normal((1, 2, 4, 3))
+    def L(Q, K, V, S):
+        O, So = oracle.fwd_state(Q, K, V, S_in=S)
+        return np.sum(O * dO) + np.sum(So * dS_out)
+    grads = dict(zip(("Q", "K", "V", "S"), oracle.bwd_state(Q, K, V, dO, S_in=S_in, dS_out=dS_out)))
+    base = {"Q": Q, "K": K, "V": V, "S": S_in}
+    L0 = L(**base)
+    for name in base:
+        E = rng.standard_normal(base[name].shape)
+        args = dict(base)
+        args[name] = base[name] + E
+        assert abs((L(**args) - L0) - np.sum(E * grads[name])) <= 1e-11 * max(1.0, abs(L0)), name
+
+
+def test_state_brute_force_small_integers():
+    r = np.random.default_rng(3)
+    B, H, N, dk, dv = 1, 2, 5, 2, 3
+    Q = r.integers(-2, 3, (B, H, N, dk)).astype(np.float64)
+    K = r.integers(-2, 3, (B, H, N, dk)).astype(np.float64)
+    V = r.integers(-2, 3, (B, H, N, dv)).astype(np.float64)
+    S = r.integers(-2, 3, (B, H, dk, dv)).astype(np.float64)
+    O, S_out = oracle.fwd_state(Q, K, V, S_in=S)
+    want = _brute_fwd(Q, K, V)
+    for b, h, t, j in itertools.product(range(B), range(H), range(N), range(dv)):
+        want[b, h, t, j] += sum(Q[b, h, t, i] * S[b, h, i, j] for i in range(dk))   # the carried-in state is seen by every token
+    assert np.array_equal(O, want)
+    assert np.array_equal(S_out, S + np.einsum("bhti,bhtj->bhij", K, V))
+
+
+def test_decode_steps_equal_the_sequence_form(rng):
+    Q, K, V, _ = _rand(rng, 2, 2, 11, 4, 3, with_dO=False)
+    S = rng.standard_normal((2, 2, 4, 3))
+    O, S_out = oracle.fwd_state(Q, K, V, S_in=S)
+    cur = S
+    for t in range(Q.shape[2]):
+        o, cur = oracle.step(Q[:, :, t], K[:, :, t], V[:, :, t], cur)
+        assert oracle.rel_l2(o, O[:, :, t]) < 1e-14
+    assert oracle.rel_l2(cur, S_out) < 1e-14
+    # one step by hand: S = 0, k = e_0, v = (1,2,3), q = (2,0,0,0) -> o = 2 * v
+    o, S1 = oracle.step(np.array([[[2.0, 0, 0, 0]]]), np.array([[[1.0, 0, 0, 0]]]), np.array([[[1.0, 2, 3]]]),
+                        np.zeros((1, 1, 4, 3)))
+    assert np.array_equal(o[0, 0], [2.0, 4.0, 6.0]) and np.array_equal(S1[0, 0, 0], [1.0, 2.0, 3.0])
