@@ -91,8 +91,30 @@ int chela_linattn_bwd_f32(const void *Q, const void *K, const void *V, const voi
                           void *dQ, void *dK, void *dV,
                           int B, int H, int N, int dk, int dv, int chunk, void *stream);
 
-/* Bytes of device scratch one call with these arguments needs (0 if the shape
- * needs none or the arguments are invalid).  The size is O(B*H*dk*dv*segments)
+/* ---- carried state (segment-wise processing, Sec. 5.2 / App. A: sequences are cut into segments that are
+ * processed one after the other; the running d_k x d_v state is all one segment hands to the next) ------------
+ * Same maps as above, bf16 I/O, with the state made explicit.  States are fp32, [B, H, dk, dv], 16-byte aligned.
+ *   forward : S_0 = S_in (NULL: zero);  O_t = q_t . (S_in + sum_{s<=t} k_s v_s^T);  S_out = S_in + sum_s k_s v_s^T
+ *             (NULL: not written).  S_out may equal S_in (update in place).
+ *   backward: for upstream gradients dO and dS_out (NULL: zero) returns dQ, dK, dV and, unless NULL,
+ *             dS_in = dS_out + sum_t q_t dO_t^T.  dS_in may equal dS_out.
+ * With N = 0 the state passes through (S_out = S_in, dS_in = dS_out).  Everything else as for the calls above. */
+int chela_linattn_fwd_state(const void *Q, const void *K, const void *V, const float *S_in,
+                            void *O, float *S_out,
+                            int B, int H, int N, int dk, int dv, int chunk, void *stream);
+int chela_linattn_bwd_state(const void *Q, const void *K, const void *V, const float *S_in,
+                            const void *dO, const float *dS_out,
+                            void *dQ, void *dK, void *dV, float *dS_in,
+                            int B, int H, int N, int dk, int dv, int chunk, void *stream);
+
+/* One decode step of autoregressive inference (the recurrent form, one token per (b,h)):
+ *     S += k v^T  (in place, fp32) ;  o = S^T q.
+ * q, k: [B, H, dk] bf16; v, o: [B, H, dv] bf16; S: [B, H, dk, dv] fp32.  Needs no scratch. */
+int chela_linattn_step(const void *q, const void *k, const void *v, float *S, void *o,
+                       int B, int H, int dk, int dv, void *stream);
+
+/* Bytes of device scratch one call with these arguments needs, with or without
+ * carried states (0 if the arguments are invalid).  The size is O(B*H*dk*dv*segments)
  * with a bounded number of segments per (b,h): it does not grow with N once
  * the GPU is full, which is the fixed-memory property claimed in Sec. 1. */
 size_t chela_linattn_workspace_bytes(int B, int H, int N, int dk, int dv, int chunk,

@@ -43,6 +43,12 @@ def lib() -> ctypes.CDLL:
         f = getattr(L, name)
         f.argtypes = [vp, vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, vp]
         f.restype = i
+    L.chela_linattn_fwd_state.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, vp]
+    L.chela_linattn_fwd_state.restype = i
+    L.chela_linattn_bwd_state.argtypes = [vp] * 10 + [i, i, i, i, i, i, vp]
+    L.chela_linattn_bwd_state.restype = i
+    L.chela_linattn_step.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, vp]
+    L.chela_linattn_step.restype = i
     L.chela_linattn_workspace_bytes.argtypes = [i, i, i, i, i, i, i, i]
     L.chela_linattn_workspace_bytes.restype = sz
     L.chela_set_workspace.argtypes = [vp, sz]
@@ -130,6 +136,62 @@ def chela_linattn_bwd(Q, K, V, dO, dQ=None, dK=None, dV=None, chunk: int = 64, s
         _check(f(Q.data_ptr(), K.data_ptr(), V.data_ptr(), dO.data_ptr(), dQ.data_ptr(), dK.data_ptr(),
                  dV.data_ptr(), B, H, N, dk, dv, int(chunk), _stream_ptr(stream)))
     return dQ, dK, dV
+
+
+def _state_ptr(S, B, H, dk, dv, name):
+    if S is None:
+        return None
+    if S.dtype != torch.float32 or tuple(S.shape) != (B, H, dk, dv) or not S.is_cuda or not S.is_contiguous():
+        raise ValueError("%s must be a contiguous float32 device tensor [B,H,dk,dv]" % name)
+    return S.data_ptr()
+
+
+def chela_linattn_fwd_state(Q, K, V, S_in=None, O=None, S_out=None, chunk: int = 64, stream=None):
+    """(O, S_out): forward with the running state started at S_in; S_out may be S_in (in place)."""
+    B, H, N, dk, dv = _dims(Q, K, V)
+    if Q.dtype != torch.bfloat16:
+        raise TypeError("the stateful entry points are bf16")
+    if O is None:
+        O = torch.empty((B, H, N, dv), dtype=Q.dtype, device=Q.device)
+    if S_out is None:
+        S_out = torch.empty((B, H, dk, dv), dtype=torch.float32, device=Q.device)
+    with torch.cuda.device(Q.device):
+        _check(lib().chela_linattn_fwd_state(Q.data_ptr(), K.data_ptr(), V.data_ptr(),
+                                             _state_ptr(S_in, B, H, dk, dv, "S_in"), O.data_ptr(),
+                                             _state_ptr(S_out, B, H, dk, dv, "S_out"), B, H, N, dk, dv, int(chunk),
+                                             _stream_ptr(stream)))
+    return O, S_out
+
+
+def chela_linattn_bwd_state(Q, K, V, dO, S_in=None, dS_out=None, chunk: int = 64, stream=None):
+    """(dQ, dK, dV, dS_in) for upstream gradients dO and dS_out."""
+    B, H, N, dk, dv = _dims(Q, K, V)
+    if Q.dtype != torch.bfloat16:
+        raise TypeError("the stateful entry points are bf16")
+    dQ, dK, dV = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
+    dS_in = torch.empty((B, H, dk, dv), dtype=torch.float32, device=Q.device)
+    with torch.cuda.device(Q.device):
+        _check(lib().chela_linattn_bwd_state(Q.data_ptr(), K.data_ptr(), V.data_ptr(),
+                                             _state_ptr(S_in, B, H, dk, dv, "S_in"), dO.data_ptr(),
+                                             _state_ptr(dS_out, B, H, dk, dv, "dS_out"), dQ.data_ptr(), dK.data_ptr(),
+                                             dV.data_ptr(), dS_in.data_ptr(), B, H, N, dk, dv, int(chunk),
+                                             _stream_ptr(stream)))
+    return dQ, dK, dV, dS_in
+
+
+def chela_linattn_step(q, k, v, S, o=None, stream=None):
+    """One decode step: S += k v^T in place, returns o = S^T q.  q,k: [B,H,dk] bf16, v: [B,H,dv] bf16, S fp32."""
+    B, H, dk = q.shape
+    dv = v.shape[2]
+    if o is None:
+        o = torch.empty((B, H, dv), dtype=torch.bfloat16, device=q.device)
+    for t in (q, k, v, o):
+        if t.dtype != torch.bfloat16 or not t.is_cuda or not t.is_contiguous():
+            raise ValueError("q, k, v, o must be contiguous bf16 device tensors")
+    with torch.cuda.device(q.device):
+        _check(lib().chela_linattn_step(q.data_ptr(), k.data_ptr(), v.data_ptr(), _state_ptr(S, B, H, dk, dv, "S"),
+                                        o.data_ptr(), B, H, dk, dv, _stream_ptr(stream)))
+    return o
 
 
 def chela_linattn_workspace_bytes(B, H, N, dk, dv, chunk, is_bwd, dtype) -> int:

@@ -61,7 +61,7 @@ static long choose_segments(long BH, long n_chunks, long slots, double g_min, do
     return best;
 }
 
-Plan make_plan(long BH, int N, int dk, int dv, int chunk, int dtype, bool is_bwd)
+Plan make_plan(long BH, int N, int dk, int dv, int chunk, int dtype, bool is_bwd, bool stateful)
 {
     Plan p{};
     p.chunk = chunk;
@@ -82,7 +82,8 @@ Plan make_plan(long BH, int N, int dk, int dv, int chunk, int dtype, bool is_bwd
     p.seg_len = (int)(cps * chunk);
     p.n_seg = (int)((n_chunks + cps - 1) / cps);
     const int n_states = (dtype == CHELA_DTYPE_BF16 && is_bwd) ? 2 : 1;   // fp32 bwd reuses one array 3 times
-    p.ws_bytes = (p.n_seg > 1) ? (size_t)BH * p.n_seg * p.state_elems * sizeof(float) * n_states : 0;
+    // a carried-in state goes through the scan even when there is a single segment
+    p.ws_bytes = (p.n_seg > 1 || stateful) ? (size_t)BH * p.n_seg * p.state_elems * sizeof(float) * n_states : 0;
     return p;
 }
 
@@ -93,7 +94,7 @@ static std::vector<ProfRec> g_prof;          // records in use
 static std::vector<ProfRec> g_prof_free;     // event pairs to re-use
 static const char* const kKernelNames[KID_COUNT] = {
     "bf16_seg_state_kernel", "scan_states_kernel", "bf16_fwd_sweep_kernel", "bf16_bwd_sweep_kernel",
-    "f32_seg_state_kernel", "f32_sweep_kernel", "copy_probe_kernel"};
+    "f32_seg_state_kernel", "f32_sweep_kernel", "copy_probe_kernel", "bf16_step_kernel"};
 
 ProfScope::ProfScope(int id, hipStream_t s) : slot(-1), st(s)
 {
@@ -197,51 +198,80 @@ static int bf16_bwd_effective_chunk(int dk, int dv, int chunk)
     return (chunk == 128 && dk == 64 && dv == 64) ? 128 : 64;
 }
 
-static int fwd_common(const void* Q, const void* K, const void* V, void* O, int B, int H, int N, int dk, int dv,
-                      int chunk, void* stream, int dtype)
+static int fwd_common(const void* Q, const void* K, const void* V, void* O, const float* S_in, float* S_out, int B,
+                      int H, int N, int dk, int dv, int chunk, void* stream, int dtype)
 {
     const size_t es = dtype == CHELA_DTYPE_BF16 ? 2 : 4;
     const size_t th = (B > 0 && H > 0 && N > 0) ? (size_t)B * H * N : 0;
-    const void* in[3] = {Q, K, V};
-    const size_t inb[3] = {th * dk * es, th * dk * es, th * dv * es};
-    void* out[1] = {O};
-    const size_t outb[1] = {th * dv * es};
+    const size_t sb = (B > 0 && H > 0) ? (size_t)B * H * dk * dv * sizeof(float) : 0;
+    const void* in[4] = {Q, K, V, S_in};
+    // S_out may be S_in (state updated in place): the carried-in state is consumed by the scan before the sweep's
+    // last workgroup writes the final one
+    const size_t inb[4] = {th * dk * es, th * dk * es, th * dv * es, (S_in && (const void*)S_in != (const void*)S_out) ? sb : 0};
+    void* out[2] = {O, S_out};
+    const size_t outb[2] = {th * dv * es, S_out ? sb : 0};
     bool empty = false;
-    int rc = validate(in, inb, 3, out, outb, 1, B, H, N, dk, dv, chunk, dtype, &empty);
-    if (rc != CHELA_OK || empty) return rc;
+    // the optional states are validated like tensors where present (a placeholder stands in where absent)
+    const void* in_v[4] = {Q, K, V, S_in ? (const void*)S_in : Q};
+    void* out_v[2] = {O, S_out ? (void*)S_out : O};
+    int rc = validate(in_v, inb, 4, out_v, outb, 2, B, H, N, dk, dv, chunk, dtype, &empty);
+    (void)in; (void)out;
+    if (rc != CHELA_OK) return rc;
     const long BH = (long)B * H;
+    if (empty) {
+        // no tokens: the state passes through unchanged
+        if (S_out && BH > 0) {
+            hipError_t e = S_in ? hipMemcpyAsync(S_out, S_in, sb, hipMemcpyDeviceToDevice, (hipStream_t)stream)
+                                : hipMemsetAsync(S_out, 0, sb, (hipStream_t)stream);
+            return e == hipSuccess ? CHELA_OK : CHELA_ERR_HIP;
+        }
+        return CHELA_OK;
+    }
     if (dtype == CHELA_DTYPE_F32) chunk = f32_effective_chunk(dk, dv, chunk);
-    Plan plan = make_plan(BH, N, dk, dv, chunk, dtype, false);
+    Plan plan = make_plan(BH, N, dk, dv, chunk, dtype, false, S_in != nullptr);
     float* ws = nullptr;
     rc = get_workspace(plan.ws_bytes, &ws);
     if (rc != CHELA_OK) return rc;
     hipError_t e = dtype == CHELA_DTYPE_BF16
-        ? launch_bf16_fwd(Q, K, V, O, BH, N, dk, dv, plan, ws, (hipStream_t)stream)
+        ? launch_bf16_fwd(Q, K, V, O, S_in, S_out, BH, N, dk, dv, plan, ws, (hipStream_t)stream)
         : launch_f32((const float*)Q, (const float*)K, (const float*)V, (float*)O, BH, N, dk, dv, plan, false, ws,
                      (hipStream_t)stream);
     return e == hipSuccess ? CHELA_OK : CHELA_ERR_HIP;
 }
 
-static int bwd_common(const void* Q, const void* K, const void* V, const void* dO, void* dQ, void* dK, void* dV,
-                      int B, int H, int N, int dk, int dv, int chunk, void* stream, int dtype)
+static int bwd_common(const void* Q, const void* K, const void* V, const void* dO, const float* S_in,
+                      const float* dS_out, void* dQ, void* dK, void* dV, float* dS_in, int B, int H, int N, int dk,
+                      int dv, int chunk, void* stream, int dtype)
 {
     const size_t es = dtype == CHELA_DTYPE_BF16 ? 2 : 4;
     const size_t th = (B > 0 && H > 0 && N > 0) ? (size_t)B * H * N : 0;
-    const void* in[4] = {Q, K, V, dO};
-    const size_t inb[4] = {th * dk * es, th * dk * es, th * dv * es, th * dv * es};
-    void* out[3] = {dQ, dK, dV};
-    const size_t outb[3] = {th * dk * es, th * dk * es, th * dv * es};
+    const size_t sb = (B > 0 && H > 0) ? (size_t)B * H * dk * dv * sizeof(float) : 0;
+    const void* in_v[6] = {Q, K, V, dO, S_in ? (const void*)S_in : Q, dS_out ? (const void*)dS_out : Q};
+    // dS_in may be dS_out (in place), for the same reason as in the forward
+    const size_t inb[6] = {th * dk * es, th * dk * es, th * dv * es, th * dv * es, S_in ? sb : 0,
+                           (dS_out && (const void*)dS_out != (const void*)dS_in) ? sb : 0};
+    void* out_v[4] = {dQ, dK, dV, dS_in ? (void*)dS_in : dQ};
+    const size_t outb[4] = {th * dk * es, th * dk * es, th * dv * es, dS_in ? sb : 0};
     bool empty = false;
-    int rc = validate(in, inb, 4, out, outb, 3, B, H, N, dk, dv, chunk, dtype, &empty);
-    if (rc != CHELA_OK || empty) return rc;
+    int rc = validate(in_v, inb, 6, out_v, outb, 4, B, H, N, dk, dv, chunk, dtype, &empty);
+    if (rc != CHELA_OK) return rc;
     const long BH = (long)B * H;
     hipStream_t st = (hipStream_t)stream;
+    if (empty) {
+        if (dS_in && BH > 0) {
+            hipError_t e = dS_out ? hipMemcpyAsync(dS_in, dS_out, sb, hipMemcpyDeviceToDevice, st)
+                                  : hipMemsetAsync(dS_in, 0, sb, st);
+            return e == hipSuccess ? CHELA_OK : CHELA_ERR_HIP;
+        }
+        return CHELA_OK;
+    }
     if (dtype == CHELA_DTYPE_BF16) {
-        Plan plan = make_plan(BH, N, dk, dv, bf16_bwd_effective_chunk(dk, dv, chunk), dtype, true);
+        Plan plan = make_plan(BH, N, dk, dv, bf16_bwd_effective_chunk(dk, dv, chunk), dtype, true,
+                              S_in != nullptr || dS_out != nullptr);
         float* ws = nullptr;
         rc = get_workspace(plan.ws_bytes, &ws);
         if (rc != CHELA_OK) return rc;
-        hipError_t e = launch_bf16_bwd(Q, K, V, dO, dQ, dK, dV, BH, N, dk, dv, plan, ws, st);
+        hipError_t e = launch_bf16_bwd(Q, K, V, dO, S_in, dS_out, dQ, dK, dV, dS_in, BH, N, dk, dv, plan, ws, st);
         return e == hipSuccess ? CHELA_OK : CHELA_ERR_HIP;
     }
     // fp32: the gradient is three instances of the forward map (time-reversal duality):
@@ -250,8 +280,8 @@ static int bwd_common(const void* Q, const void* K, const void* V, const void* d
     //   dK = LinAttn(query V,  key dO, value Q)            anti-causal
     const int c1 = f32_effective_chunk(dv, dk, chunk);   // query/key width dv, value width dk
     const int c2 = f32_effective_chunk(dk, dv, chunk);
-    Plan p1 = make_plan(BH, N, dv, dk, c1, dtype, true);
-    Plan p2 = make_plan(BH, N, dk, dv, c2, dtype, true);
+    Plan p1 = make_plan(BH, N, dv, dk, c1, dtype, true, false);
+    Plan p2 = make_plan(BH, N, dk, dv, c2, dtype, true, false);
     float* ws = nullptr;
     rc = get_workspace(p1.ws_bytes > p2.ws_bytes ? p1.ws_bytes : p2.ws_bytes, &ws);
     if (rc != CHELA_OK) return rc;
@@ -273,25 +303,55 @@ extern "C" {
 int chela_linattn_fwd(const void* Q, const void* K, const void* V, void* O, int B, int H, int N, int dk, int dv,
                       int chunk, void* stream)
 {
-    return fwd_common(Q, K, V, O, B, H, N, dk, dv, chunk, stream, CHELA_DTYPE_BF16);
+    return fwd_common(Q, K, V, O, nullptr, nullptr, B, H, N, dk, dv, chunk, stream, CHELA_DTYPE_BF16);
 }
 
 int chela_linattn_fwd_f32(const void* Q, const void* K, const void* V, void* O, int B, int H, int N, int dk,
                           int dv, int chunk, void* stream)
 {
-    return fwd_common(Q, K, V, O, B, H, N, dk, dv, chunk, stream, CHELA_DTYPE_F32);
+    return fwd_common(Q, K, V, O, nullptr, nullptr, B, H, N, dk, dv, chunk, stream, CHELA_DTYPE_F32);
 }
 
 int chela_linattn_bwd(const void* Q, const void* K, const void* V, const void* dO, void* dQ, void* dK, void* dV,
                       int B, int H, int N, int dk, int dv, int chunk, void* stream)
 {
-    return bwd_common(Q, K, V, dO, dQ, dK, dV, B, H, N, dk, dv, chunk, stream, CHELA_DTYPE_BF16);
+    return bwd_common(Q, K, V, dO, nullptr, nullptr, dQ, dK, dV, nullptr, B, H, N, dk, dv, chunk, stream, CHELA_DTYPE_BF16);
 }
 
 int chela_linattn_bwd_f32(const void* Q, const void* K, const void* V, const void* dO, void* dQ, void* dK,
                           void* dV, int B, int H, int N, int dk, int dv, int chunk, void* stream)
 {
-    return bwd_common(Q, K, V, dO, dQ, dK, dV, B, H, N, dk, dv, chunk, stream, CHELA_DTYPE_F32);
+    return bwd_common(Q, K, V, dO, nullptr, nullptr, dQ, dK, dV, nullptr, B, H, N, dk, dv, chunk, stream, CHELA_DTYPE_F32);
+}
+
+int chela_linattn_fwd_state(const void* Q, const void* K, const void* V, const float* S_in, void* O, float* S_out,
+                            int B, int H, int N, int dk, int dv, int chunk, void* stream)
+{
+    return fwd_common(Q, K, V, O, S_in, S_out, B, H, N, dk, dv, chunk, stream, CHELA_DTYPE_BF16);
+}
+
+int chela_linattn_bwd_state(const void* Q, const void* K, const void* V, const float* S_in, const void* dO,
+                            const float* dS_out, void* dQ, void* dK, void* dV, float* dS_in, int B, int H, int N,
+                            int dk, int dv, int chunk, void* stream)
+{
+    return bwd_common(Q, K, V, dO, S_in, dS_out, dQ, dK, dV, dS_in, B, H, N, dk, dv, chunk, stream, CHELA_DTYPE_BF16);
+}
+
+int chela_linattn_step(const void* q, const void* k, const void* v, float* S, void* o, int B, int H, int dk, int dv,
+                       void* stream)
+{
+    if (B < 0 || H < 0) return CHELA_ERR_BAD_SHAPE;
+    if (!((dk == 64 || dk == 128) && (dv == 64 || dv == 128))) return CHELA_ERR_UNSUPPORTED_DIM;
+    if ((unsigned long long)B * (unsigned long long)H > 0x7fffffffull) return CHELA_ERR_BAD_SHAPE;
+    if (B == 0 || H == 0) return CHELA_OK;
+    if (!q || !k || !v || !S || !o) return CHELA_ERR_NULL_POINTER;
+    if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)S | (uintptr_t)o) & 15u) return CHELA_ERR_MISALIGNED;
+    const size_t bh = (size_t)B * H;
+    const Range ro{(const char*)o, bh * dv * 2}, rs{(const char*)S, bh * dk * dv * 4};
+    const Range ri[3] = {{(const char*)q, bh * dk * 2}, {(const char*)k, bh * dk * 2}, {(const char*)v, bh * dv * 2}};
+    if (overlap(ro, rs)) return CHELA_ERR_ALIASING;
+    for (const Range& r : ri) if (overlap(ro, r) || overlap(rs, r)) return CHELA_ERR_ALIASING;
+    return launch_bf16_step(q, k, v, S, o, (long)bh, dk, dv, (hipStream_t)stream) == hipSuccess ? CHELA_OK : CHELA_ERR_HIP;
 }
 
 size_t chela_linattn_workspace_bytes(int B, int H, int N, int dk, int dv, int chunk, int is_bwd, int dtype)
@@ -301,13 +361,13 @@ size_t chela_linattn_workspace_bytes(int B, int H, int N, int dk, int dv, int ch
     if (dtype == CHELA_DTYPE_BF16) {
         if (!(chunk == 64 || chunk == 128)) return 0;
         if (is_bwd) chunk = bf16_bwd_effective_chunk(dk, dv, chunk);
-        return make_plan((long)B * H, N, dk, dv, chunk, dtype, is_bwd != 0).ws_bytes;
+        return make_plan((long)B * H, N, dk, dv, chunk, dtype, is_bwd != 0, true).ws_bytes;
     }
     if (dtype != CHELA_DTYPE_F32) return 0;
     if (!(chunk == 16 || chunk == 32 || chunk == 64)) return 0;
-    size_t a = make_plan((long)B * H, N, dk, dv, f32_effective_chunk(dk, dv, chunk), dtype, is_bwd != 0).ws_bytes;
+    size_t a = make_plan((long)B * H, N, dk, dv, f32_effective_chunk(dk, dv, chunk), dtype, is_bwd != 0, false).ws_bytes;
     if (is_bwd) {
-        size_t b = make_plan((long)B * H, N, dv, dk, f32_effective_chunk(dv, dk, chunk), dtype, true).ws_bytes;
+        size_t b = make_plan((long)B * H, N, dv, dk, f32_effective_chunk(dv, dk, chunk), dtype, true, false).ws_bytes;
         if (b > a) a = b;
     }
     return a;

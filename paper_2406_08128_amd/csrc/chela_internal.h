@@ -17,15 +17,17 @@ struct Plan {
     size_t ws_bytes;     // scratch bytes for the whole call
 };
 
-Plan make_plan(long BH, int N, int dk, int dv, int chunk, int dtype, bool is_bwd);
+Plan make_plan(long BH, int N, int dk, int dv, int chunk, int dtype, bool is_bwd, bool stateful);
 
 // scan modes for scan_states()
 enum { SCAN_EXCL_PREFIX = 0, SCAN_INCL_PREFIX = 1, SCAN_EXCL_SUFFIX = 2 };
 
 // In-place scan over the segment axis of n_arrays (1 or 2) arrays states[z][BH][n_seg][elems] (fp32), the arrays
-// `array_stride` floats apart, array z scanned in mode modes[z].  elems must be a multiple of 4.
-hipError_t scan_states(float* states, size_t array_stride, int n_arrays, const int* modes, long BH, int n_seg, int elems,
-                       hipStream_t st);
+// `array_stride` floats apart, array z scanned in mode modes[z].  elems must be a multiple of 4.  init (may be null,
+// entries may be null): per-head seeds [BH][elems] of the running sums; init_cols > 0 says the arrays hold the
+// transpose of what init holds and gives the arrays' row length.
+hipError_t scan_states(float* states, size_t array_stride, int n_arrays, const int* modes, const float* const* init,
+                       int init_cols, long BH, int n_seg, int elems, hipStream_t st);
 
 // Streaming copy used to calibrate byte counters.
 hipError_t launch_copy(const void* src, void* dst, size_t bytes, hipStream_t st);
@@ -35,15 +37,18 @@ hipError_t launch_copy(const void* src, void* dst, size_t bytes, hipStream_t st)
 hipError_t launch_f32(const float* Q, const float* K, const float* V, float* O, long BH, int N, int dk, int dv,
                       const Plan& plan, bool rev, float* ws, hipStream_t st);
 
-// bf16 path.
-hipError_t launch_bf16_fwd(const void* Q, const void* K, const void* V, void* O, long BH, int N, int dk, int dv,
-                           const Plan& plan, float* ws, hipStream_t st);
-hipError_t launch_bf16_bwd(const void* Q, const void* K, const void* V, const void* dO, void* dQ, void* dK,
-                           void* dV, long BH, int N, int dk, int dv, const Plan& plan, float* ws, hipStream_t st);
+// bf16 path.  S_in / S_out / dS_out / dS_in: optional carried states and their gradients, [BH][dk][dv] fp32.
+hipError_t launch_bf16_fwd(const void* Q, const void* K, const void* V, void* O, const float* S_in, float* S_out,
+                           long BH, int N, int dk, int dv, const Plan& plan, float* ws, hipStream_t st);
+hipError_t launch_bf16_bwd(const void* Q, const void* K, const void* V, const void* dO, const float* S_in,
+                           const float* dS_out, void* dQ, void* dK, void* dV, float* dS_in, long BH, int N, int dk,
+                           int dv, const Plan& plan, float* ws, hipStream_t st);
+hipError_t launch_bf16_step(const void* q, const void* k, const void* v, float* S, void* o, long BH, int dk, int dv,
+                            hipStream_t st);
 
 // Kernel classes for the per-kernel timing aid.
 enum { KID_SEG_STATE_BF16 = 0, KID_SCAN = 1, KID_FWD_SWEEP_BF16 = 2, KID_BWD_SWEEP_BF16 = 3, KID_SEG_STATE_F32 = 4,
-       KID_SWEEP_F32 = 5, KID_COPY = 6, KID_COUNT = 7 };
+       KID_SWEEP_F32 = 5, KID_COPY = 6, KID_STEP_BF16 = 7, KID_COUNT = 8 };
 
 // Brackets one kernel launch with HIP events on its stream while profiling is enabled; otherwise does nothing.
 struct ProfScope {

@@ -226,6 +226,38 @@ __device__ __forceinline__ void state_to_lds_T(bf16* dst, const f32x16* acc, int
     }
 }
 
+// Write a [DA][DB] state held as accumulator tiles to global memory, fp32, row-major [DA][DB].
+template <int DA, int DB>
+__device__ __forceinline__ void store_state(float* dst, const f32x16* acc, int w, int lane)
+{
+    constexpr int BB = DB / 32, NT = (DA / 32) * BB / 4;
+    const int r = lane & 31, h = lane >> 5;
+#pragma unroll
+    for (int n = 0; n < NT; ++n) {
+        const int id = w + 4 * n, ab = id / BB, bb = id % BB;
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+#pragma unroll
+            for (int b = 0; b < 4; ++b) dst[(ab * 32 + 8 * a + 4 * h + b) * DB + bb * 32 + r] = acc[n][4 * a + b];
+    }
+}
+
+// Same state written TRANSPOSED, as [DB][DA]: a lane owns 4 consecutive a for one b -> one 16-byte store.
+template <int DA, int DB>
+__device__ __forceinline__ void store_state_T(float* dst, const f32x16* acc, int w, int lane)
+{
+    constexpr int BB = DB / 32, NT = (DA / 32) * BB / 4;
+    const int r = lane & 31, h = lane >> 5;
+#pragma unroll
+    for (int n = 0; n < NT; ++n) {
+        const int id = w + 4 * n, ab = id / BB, bb = id % BB;
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+            *reinterpret_cast<float4*>(dst + (size_t)(bb * 32 + r) * DA + ab * 32 + 8 * a + 4 * h) =
+                make_float4(acc[n][4 * a + 0], acc[n][4 * a + 1], acc[n][4 * a + 2], acc[n][4 * a + 3]);
+    }
+}
+
 // =============================================================================================== pre-pass body
 // out[a][b] = sum over `ntok` tokens s of X[s][a] * Y[s][b]   (fp32, [DA][DB] row-major).  One workgroup; wave w owns
 // output tiles w, w+4, ...  LDS: 64 x (DA + PAD) + 64 x (DB + PAD) bf16.
@@ -307,8 +339,8 @@ struct FwdLds {
 template <int C, int DK, int DV>
 __device__ __forceinline__ void fwd_sweep_body(const bf16* __restrict__ Qb, const bf16* __restrict__ Kb,
                                                const bf16* __restrict__ Vb, bf16* __restrict__ Ob,
-                                               const float* __restrict__ S0, int ntok, unsigned char* lds, int tid,
-                                               int w, int lane)
+                                               const float* __restrict__ S0, float* __restrict__ S_final, int ntok,
+                                               unsigned char* lds, int tid, int w, int lane)
 {
     constexpr int LDK = DK + PAD, LDV = DV + PAD;
     constexpr int TB = C / 32, JB = DV / 32, IB = DK / 32;
@@ -380,8 +412,8 @@ __device__ __forceinline__ void fwd_sweep_body(const bf16* __restrict__ Qb, cons
 #pragma unroll
             for (int n = 0; n < NJ; ++n) store_tile_T(rows, DV, (jg * NJ + n) * 32, accO[n], valid, lane);
         }
-        // state update S += K^T V (not needed after the segment's last chunk)
-        if (more) {
+        // state update S += K^T V (after the segment's last chunk only if the final state is asked for)
+        if (more || S_final != nullptr) {
 #pragma unroll
             for (int n = 0; n < NS; ++n) {
                 const int id = w + 4 * n, ib = id / JB, jb = id % JB;
@@ -392,6 +424,7 @@ __device__ __forceinline__ void fwd_sweep_body(const bf16* __restrict__ Qb, cons
         }
         __syncthreads();
     }
+    if (S_final != nullptr) store_state<DK, DV>(S_final, accS, w, lane);
 }
 
 // =============================================================================================== backward sweep body
@@ -405,6 +438,7 @@ __device__ __forceinline__ void fwd_sweep_body(const bf16* __restrict__ Qb, cons
 // Per chunk:  dQ = dP K + dO S^T',  dK = dP^T Q + V R^T',  dV = P^T dO + K R,
 //             P = (Q K^T) o M,  dP = (dO V^T) o M, every output accumulated transposed.
 // Send == nullptr means the whole sequence is this one segment: S is then built here, R starts at zero.
+// R_final, if given, receives the state R after the segment's first chunk has been added ([dk][dv], fp32).
 template <int C, int DK, int DV>
 struct BwdLds {
     static constexpr int LDK = DK + PAD, LDV = DV + PAD;
@@ -416,7 +450,8 @@ __device__ __forceinline__ void bwd_sweep_body(const bf16* __restrict__ Qb, cons
                                                const bf16* __restrict__ Vb, const bf16* __restrict__ Gb,
                                                bf16* __restrict__ dQb, bf16* __restrict__ dKb, bf16* __restrict__ dVb,
                                                const float* __restrict__ Send, const float* __restrict__ Rnext,
-                                               int ntok, unsigned char* lds, int tid, int w, int lane)
+                                               float* __restrict__ R_final, int ntok, unsigned char* lds, int tid,
+                                               int w, int lane)
 {
     constexpr int LDK = DK + PAD, LDV = DV + PAD;
     constexpr int TB = C / 32, JB = DV / 32, IB = DK / 32;
@@ -604,8 +639,8 @@ __device__ __forceinline__ void bwd_sweep_body(const bf16* __restrict__ Qb, cons
 #pragma unroll
             for (int n = 0; n < NJ; ++n) store_tile_T(rows, DV, (cg * NJ + n) * 32, acc[n], valid, lane);
         }
-        // ---------------- R^T += dO^T Q (not needed after the segment's first chunk)
-        if (ci > 0) {
+        // ---------------- R^T += dO^T Q (after the segment's first chunk only if the final state is asked for)
+        if (ci > 0 || R_final != nullptr) {
 #pragma unroll
             for (int n = 0; n < NS; ++n) {
                 const int id = w + 4 * n, jb = id / IB, ib = id % IB;
@@ -616,6 +651,7 @@ __device__ __forceinline__ void bwd_sweep_body(const bf16* __restrict__ Qb, cons
         }
         __syncthreads();
     }
+    if (R_final != nullptr) store_state_T<DV, DK>(R_final, accRT, w, lane);
 }
 
 // =============================================================================================== kernels
@@ -643,7 +679,8 @@ __global__ __launch_bounds__(256) void bf16_seg_state_kernel(SegStateArgs args, 
 template <int C, int DK, int DV>
 __global__ __launch_bounds__(256) void bf16_fwd_sweep_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K,
                                                             const bf16* __restrict__ V, bf16* __restrict__ O,
-                                                            const float* __restrict__ S0, int N, int seg_len, int n_seg)
+                                                            const float* __restrict__ S0, float* __restrict__ S_out,
+                                                            int first_loads_state, int N, int seg_len, int n_seg)
 {
     __shared__ __attribute__((aligned(16))) unsigned char lds[FwdLds<C, DK, DV>::BYTES];
     const int seg = blockIdx.y;
@@ -652,9 +689,13 @@ __global__ __launch_bounds__(256) void bf16_fwd_sweep_kernel(const bf16* __restr
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int p0 = seg * seg_len, p1 = min(N, p0 + seg_len);
     const size_t rk = ((size_t)bh * N + p0) * DK, rv = ((size_t)bh * N + p0) * DV;
+    // S0: scanned start states (segment 0's slot holds the carried-in state, read only if there is one);
+    // S_out: final state of the whole sequence, written by the last segment's workgroup
+    const bool has_state = S0 != nullptr && (seg > 0 || first_loads_state);
     fwd_sweep_body<C, DK, DV>(Q + rk, K + rk, V + rv, O + rv,
-                                     (S0 != nullptr && seg > 0) ? S0 + ((size_t)bh * n_seg + seg) * DK * DV : nullptr,
-                                     p1 - p0, lds, tid, w, lane);
+                              has_state ? S0 + ((size_t)bh * n_seg + seg) * DK * DV : nullptr,
+                              (S_out != nullptr && seg == n_seg - 1) ? S_out + (size_t)bh * DK * DV : nullptr, p1 - p0,
+                              lds, tid, w, lane);
 }
 
 template <int C, int DK, int DV>
@@ -662,8 +703,8 @@ __global__ __launch_bounds__(256) void bf16_bwd_sweep_kernel(const bf16* __restr
                                                             const bf16* __restrict__ V, const bf16* __restrict__ dO,
                                                             bf16* __restrict__ dQ, bf16* __restrict__ dK,
                                                             bf16* __restrict__ dV, const float* __restrict__ Send,
-                                                            const float* __restrict__ Rnext, int N, int seg_len,
-                                                            int n_seg)
+                                                            const float* __restrict__ Rnext, float* __restrict__ dS_in,
+                                                            int N, int seg_len, int n_seg)
 {
     __shared__ __attribute__((aligned(16))) unsigned char lds[BwdLds<C, DK, DV>::BYTES];
     const int seg = blockIdx.y;
@@ -674,16 +715,65 @@ __global__ __launch_bounds__(256) void bf16_bwd_sweep_kernel(const bf16* __restr
     const size_t rk = ((size_t)bh * N + p0) * DK, rv = ((size_t)bh * N + p0) * DV;
     const size_t soff = ((size_t)bh * n_seg + seg) * DK * DV;
     // the scan leaves zeros in the last segment's R slot, so Rnext can be read for every segment
+    // dS_in: gradient with respect to the carried-in state = R after the very first chunk (segment 0's workgroup)
     bwd_sweep_body<C, DK, DV>(Q + rk, K + rk, V + rv, dO + rv, dQ + rk, dK + rk, dV + rv,
-                                     Send ? Send + soff : nullptr, Rnext ? Rnext + soff : nullptr, p1 - p0, lds, tid, w,
-                                     lane);
+                              Send ? Send + soff : nullptr, Rnext ? Rnext + soff : nullptr,
+                              (dS_in != nullptr && seg == 0) ? dS_in + (size_t)bh * DK * DV : nullptr, p1 - p0, lds, tid,
+                              w, lane);
+}
+
+// =============================================================================================== decode step
+// One token per (b,h): S += k v^T (fp32, in place), o = S^T q.  q, k: [BH][DK]; v, o: [BH][DV]; S: [BH][DK][DV].
+// The state is read and written once: 2 * DK * DV * 4 bytes per token-head, nothing else of note.
+template <int DK, int DV>
+__global__ __launch_bounds__(256) void bf16_step_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k,
+                                                       const bf16* __restrict__ v, float* __restrict__ S,
+                                                       bf16* __restrict__ o)
+{
+    constexpr int G = 256 / DV;          // row groups
+    constexpr int RPG = DK / G;          // rows of S per thread
+    __shared__ float part[G][DV];
+    const long bh = blockIdx.x;
+    const int tid = threadIdx.x, j = tid % DV, g = tid / DV;
+    float* s = S + (size_t)bh * DK * DV;
+    const float vj = (float)v[bh * DV + j];
+    float acc = 0.f;
+#pragma unroll 8
+    for (int r = 0; r < RPG; ++r) {
+        const int i = g * RPG + r;
+        const float sn = fmaf((float)k[bh * DK + i], vj, s[i * DV + j]);
+        s[i * DV + j] = sn;
+        acc = fmaf(sn, (float)q[bh * DK + i], acc);
+    }
+    part[g][j] = acc;
+    __syncthreads();
+    if (g == 0) {
+        float t = 0.f;
+#pragma unroll
+        for (int gg = 0; gg < G; ++gg) t += part[gg][j];
+        o[bh * DV + j] = (bf16)t;
+    }
+}
+
+hipError_t launch_bf16_step(const void* q, const void* k, const void* v, float* S, void* o, long BH, int dk, int dv,
+                            hipStream_t st)
+{
+    const bf16 *qq = (const bf16*)q, *kk = (const bf16*)k, *vv = (const bf16*)v;
+    bf16* oo = (bf16*)o;
+    ProfScope prof(KID_STEP_BF16, st);
+    if (dk == 64 && dv == 64) hipLaunchKernelGGL((bf16_step_kernel<64, 64>), dim3((unsigned)BH), dim3(256), 0, st, qq, kk, vv, S, oo);
+    else if (dk == 64 && dv == 128) hipLaunchKernelGGL((bf16_step_kernel<64, 128>), dim3((unsigned)BH), dim3(256), 0, st, qq, kk, vv, S, oo);
+    else if (dk == 128 && dv == 64) hipLaunchKernelGGL((bf16_step_kernel<128, 64>), dim3((unsigned)BH), dim3(256), 0, st, qq, kk, vv, S, oo);
+    else if (dk == 128 && dv == 128) hipLaunchKernelGGL((bf16_step_kernel<128, 128>), dim3((unsigned)BH), dim3(256), 0, st, qq, kk, vv, S, oo);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
 }
 
 // =============================================================================================== launchers
-// Pre-pass + scan over segments.
+// Pre-pass + scan over segments.  init[z] (optional, [dk][dv] fp32 per head) seeds the scan of array z.
 template <int DA, int DB>
-static hipError_t run_seg_state(const SegStateArgs& a, int npairs, const int* scan_modes, long BH, int N,
-                                const Plan& plan, hipStream_t st)
+static hipError_t run_seg_state(const SegStateArgs& a, int npairs, const int* scan_modes, const float* const* init,
+                                bool init_transposed, long BH, int N, const Plan& plan, hipStream_t st)
 {
     hipError_t e;
     {
@@ -693,79 +783,88 @@ static hipError_t run_seg_state(const SegStateArgs& a, int npairs, const int* sc
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     const size_t stride = npairs > 1 ? (size_t)(a.out[1] - a.out[0]) : 0;
-    return scan_states(a.out[0], stride, npairs, scan_modes, BH, plan.n_seg, DA * DB, st);
+    return scan_states(a.out[0], stride, npairs, scan_modes, init, init_transposed ? DB : 0, BH, plan.n_seg, DA * DB, st);
 }
 
+// `stateful`: a carried-in or carried-out state is involved; the three-launch path is then taken even for a single
+// segment, with the scan seeding segment 0's slot from S_in.
 template <int C, int DK, int DV>
-static hipError_t fwd_impl(const bf16* Q, const bf16* K, const bf16* V, bf16* O, long BH, int N, const Plan& plan,
-                           float* ws, hipStream_t st)
+static hipError_t fwd_impl(const bf16* Q, const bf16* K, const bf16* V, bf16* O, const float* S_in, float* S_out,
+                           long BH, int N, const Plan& plan, float* ws, hipStream_t st)
 {
     hipError_t e;
-    float* states = ws;
-    if (plan.n_seg > 1) {
+    const bool stateful = (S_in != nullptr || S_out != nullptr);
+    const bool use_ws = plan.n_seg > 1 || S_in != nullptr;
+    if (use_ws) {
         SegStateArgs a{};
-        a.X[0] = K; a.Y[0] = V; a.out[0] = states; a.skip_seg[0] = plan.n_seg - 1;
+        a.X[0] = K; a.Y[0] = V; a.out[0] = ws; a.skip_seg[0] = plan.n_seg - 1;
         const int mode = SCAN_EXCL_PREFIX;
-        if ((e = run_seg_state<DK, DV>(a, 1, &mode, BH, N, plan, st)) != hipSuccess) return e;
+        const float* init[2] = {S_in, nullptr};
+        if ((e = run_seg_state<DK, DV>(a, 1, &mode, init, false, BH, N, plan, st)) != hipSuccess) return e;
     }
+    (void)stateful;
     dim3 grid((unsigned)BH, plan.n_seg);
     ProfScope prof(KID_FWD_SWEEP_BF16, st);
-    hipLaunchKernelGGL((bf16_fwd_sweep_kernel<C, DK, DV>), grid, dim3(256), 0, st, Q, K, V, O,
-                       plan.n_seg > 1 ? states : nullptr, N, plan.seg_len, plan.n_seg);
+    hipLaunchKernelGGL((bf16_fwd_sweep_kernel<C, DK, DV>), grid, dim3(256), 0, st, Q, K, V, O, use_ws ? ws : nullptr,
+                       S_out, S_in != nullptr ? 1 : 0, N, plan.seg_len, plan.n_seg);
     return hipGetLastError();
 }
 
 template <int C, int DK, int DV>
-static hipError_t bwd_impl(const bf16* Q, const bf16* K, const bf16* V, const bf16* dO, bf16* dQ, bf16* dK, bf16* dV,
-                           long BH, int N, const Plan& plan, float* ws, hipStream_t st)
+static hipError_t bwd_impl(const bf16* Q, const bf16* K, const bf16* V, const bf16* dO, const float* S_in,
+                           const float* dS_out, bf16* dQ, bf16* dK, bf16* dV, float* dS_in, long BH, int N,
+                           const Plan& plan, float* ws, hipStream_t st)
 {
     hipError_t e;
     float* wsS = ws;
-    float* wsR = ws ? wsS + (size_t)BH * plan.n_seg * DK * DV : nullptr;
-    if (plan.n_seg > 1) {
+    float* wsR = ws ? ws + (size_t)BH * plan.n_seg * DK * DV : nullptr;
+    const bool use_ws = plan.n_seg > 1 || S_in != nullptr || dS_out != nullptr;
+    if (use_ws) {
         SegStateArgs a{};
         // S^T totals: every segment is needed (inclusive prefix); R^T totals: the first is never used (exclusive suffix)
         a.X[0] = V;  a.Y[0] = K; a.out[0] = wsS; a.skip_seg[0] = -1;
         a.X[1] = dO; a.Y[1] = Q; a.out[1] = wsR; a.skip_seg[1] = 0;
         const int modes[2] = {SCAN_INCL_PREFIX, SCAN_EXCL_SUFFIX};
-        if ((e = run_seg_state<DV, DK>(a, 2, modes, BH, N, plan, st)) != hipSuccess) return e;
+        const float* init[2] = {S_in, dS_out};   // given as [dk][dv]; the arrays are [dv][dk]
+        if ((e = run_seg_state<DV, DK>(a, 2, modes, init, true, BH, N, plan, st)) != hipSuccess) return e;
     }
     dim3 grid((unsigned)BH, plan.n_seg);
     ProfScope prof(KID_BWD_SWEEP_BF16, st);
     hipLaunchKernelGGL((bf16_bwd_sweep_kernel<C, DK, DV>), grid, dim3(256), 0, st, Q, K, V, dO, dQ, dK, dV,
-                       plan.n_seg > 1 ? wsS : nullptr, plan.n_seg > 1 ? wsR : nullptr, N, plan.seg_len, plan.n_seg);
+                       use_ws ? wsS : nullptr, use_ws ? wsR : nullptr, dS_in, N, plan.seg_len, plan.n_seg);
     return hipGetLastError();
 }
 
 #define CHELA_DISPATCH(C_, DK_, DV_, CALL)                                  \
     if (plan.chunk == C_ && dk == DK_ && dv == DV_) return CALL;
 
-hipError_t launch_bf16_fwd(const void* Q, const void* K, const void* V, void* O, long BH, int N, int dk, int dv,
-                           const Plan& plan, float* ws, hipStream_t st)
+hipError_t launch_bf16_fwd(const void* Q, const void* K, const void* V, void* O, const float* S_in, float* S_out,
+                           long BH, int N, int dk, int dv, const Plan& plan, float* ws, hipStream_t st)
 {
     const bf16 *q = (const bf16*)Q, *k = (const bf16*)K, *v = (const bf16*)V;
     bf16* o = (bf16*)O;
-    CHELA_DISPATCH(64, 64, 64, (fwd_impl<64, 64, 64>(q, k, v, o, BH, N, plan, ws, st)))
-    CHELA_DISPATCH(128, 64, 64, (fwd_impl<128, 64, 64>(q, k, v, o, BH, N, plan, ws, st)))
-    CHELA_DISPATCH(64, 64, 128, (fwd_impl<64, 64, 128>(q, k, v, o, BH, N, plan, ws, st)))
-    CHELA_DISPATCH(128, 64, 128, (fwd_impl<128, 64, 128>(q, k, v, o, BH, N, plan, ws, st)))
-    CHELA_DISPATCH(64, 128, 64, (fwd_impl<64, 128, 64>(q, k, v, o, BH, N, plan, ws, st)))
-    CHELA_DISPATCH(128, 128, 64, (fwd_impl<128, 128, 64>(q, k, v, o, BH, N, plan, ws, st)))
-    CHELA_DISPATCH(64, 128, 128, (fwd_impl<64, 128, 128>(q, k, v, o, BH, N, plan, ws, st)))
-    CHELA_DISPATCH(128, 128, 128, (fwd_impl<128, 128, 128>(q, k, v, o, BH, N, plan, ws, st)))
+    CHELA_DISPATCH(64, 64, 64, (fwd_impl<64, 64, 64>(q, k, v, o, S_in, S_out, BH, N, plan, ws, st)))
+    CHELA_DISPATCH(128, 64, 64, (fwd_impl<128, 64, 64>(q, k, v, o, S_in, S_out, BH, N, plan, ws, st)))
+    CHELA_DISPATCH(64, 64, 128, (fwd_impl<64, 64, 128>(q, k, v, o, S_in, S_out, BH, N, plan, ws, st)))
+    CHELA_DISPATCH(128, 64, 128, (fwd_impl<128, 64, 128>(q, k, v, o, S_in, S_out, BH, N, plan, ws, st)))
+    CHELA_DISPATCH(64, 128, 64, (fwd_impl<64, 128, 64>(q, k, v, o, S_in, S_out, BH, N, plan, ws, st)))
+    CHELA_DISPATCH(128, 128, 64, (fwd_impl<128, 128, 64>(q, k, v, o, S_in, S_out, BH, N, plan, ws, st)))
+    CHELA_DISPATCH(64, 128, 128, (fwd_impl<64, 128, 128>(q, k, v, o, S_in, S_out, BH, N, plan, ws, st)))
+    CHELA_DISPATCH(128, 128, 128, (fwd_impl<128, 128, 128>(q, k, v, o, S_in, S_out, BH, N, plan, ws, st)))
     return hipErrorInvalidValue;
 }
 
-hipError_t launch_bf16_bwd(const void* Q, const void* K, const void* V, const void* dO, void* dQ, void* dK,
-                           void* dV, long BH, int N, int dk, int dv, const Plan& plan, float* ws, hipStream_t st)
+hipError_t launch_bf16_bwd(const void* Q, const void* K, const void* V, const void* dO, const float* S_in,
+                           const float* dS_out, void* dQ, void* dK, void* dV, float* dS_in, long BH, int N, int dk,
+                           int dv, const Plan& plan, float* ws, hipStream_t st)
 {
     const bf16 *q = (const bf16*)Q, *k = (const bf16*)K, *v = (const bf16*)V, *g = (const bf16*)dO;
     bf16 *dq = (bf16*)dQ, *dkk = (bf16*)dK, *dvv = (bf16*)dV;
-    CHELA_DISPATCH(64, 64, 64, (bwd_impl<64, 64, 64>(q, k, v, g, dq, dkk, dvv, BH, N, plan, ws, st)))
-    CHELA_DISPATCH(128, 64, 64, (bwd_impl<128, 64, 64>(q, k, v, g, dq, dkk, dvv, BH, N, plan, ws, st)))
-    CHELA_DISPATCH(64, 64, 128, (bwd_impl<64, 64, 128>(q, k, v, g, dq, dkk, dvv, BH, N, plan, ws, st)))
-    CHELA_DISPATCH(64, 128, 64, (bwd_impl<64, 128, 64>(q, k, v, g, dq, dkk, dvv, BH, N, plan, ws, st)))
-    CHELA_DISPATCH(64, 128, 128, (bwd_impl<64, 128, 128>(q, k, v, g, dq, dkk, dvv, BH, N, plan, ws, st)))
+    CHELA_DISPATCH(64, 64, 64, (bwd_impl<64, 64, 64>(q, k, v, g, S_in, dS_out, dq, dkk, dvv, dS_in, BH, N, plan, ws, st)))
+    CHELA_DISPATCH(128, 64, 64, (bwd_impl<128, 64, 64>(q, k, v, g, S_in, dS_out, dq, dkk, dvv, dS_in, BH, N, plan, ws, st)))
+    CHELA_DISPATCH(64, 64, 128, (bwd_impl<64, 64, 128>(q, k, v, g, S_in, dS_out, dq, dkk, dvv, dS_in, BH, N, plan, ws, st)))
+    CHELA_DISPATCH(64, 128, 64, (bwd_impl<64, 128, 64>(q, k, v, g, S_in, dS_out, dq, dkk, dvv, dS_in, BH, N, plan, ws, st)))
+    CHELA_DISPATCH(64, 128, 128, (bwd_impl<64, 128, 128>(q, k, v, g, S_in, dS_out, dq, dkk, dvv, dS_in, BH, N, plan, ws, st)))
     return hipErrorInvalidValue;
 }
 

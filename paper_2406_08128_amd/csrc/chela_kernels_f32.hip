@@ -13,10 +13,13 @@ namespace chela {
 // states[z][bh][seg][e] (z = 0 .. n_arrays-1, arrays `array_stride` floats apart), one thread per (z, bh, 4 e's),
 // serial over the (few) segments, coalesced over e.  The loads of U segments are issued before the first add so that
 // one memory round trip serves U segments.
-struct ScanModes { int mode[2]; };
+// An optional carried-in state seeds the running sum of array z: init[z] is [rows][cols] fp32 per head; if
+// init_cols > 0 the array itself is stored transposed ([cols][rows], cols = init_cols... see below) and the seed is
+// read transposed: element e = a * init_cols + b of the array takes init[b * (elems / init_cols) + a].
+struct ScanModes { int mode[2]; const float* init[2]; };
 
 __global__ __launch_bounds__(256) void scan_states_kernel(float* __restrict__ st, size_t array_stride, int n_seg,
-                                                         int elems, ScanModes modes)
+                                                         int elems, ScanModes modes, int init_cols)
 {
     const long bh = blockIdx.x;     // heads on grid.x: its limit is 2^31-1, the others' 65535
     const int z = blockIdx.z;
@@ -25,6 +28,16 @@ __global__ __launch_bounds__(256) void scan_states_kernel(float* __restrict__ st
     if (e >= elems) return;
     float* p = st + (size_t)z * array_stride + (size_t)bh * n_seg * elems + e;
     float4 run = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (modes.init[z] != nullptr) {
+        const float* in = modes.init[z] + (size_t)bh * elems;
+        if (init_cols > 0) {
+            const int a = e / init_cols, b = e % init_cols, rows = elems / init_cols;   // 4 consecutive b, one a
+            run = make_float4(in[(size_t)b * rows + a], in[(size_t)(b + 1) * rows + a], in[(size_t)(b + 2) * rows + a],
+                              in[(size_t)(b + 3) * rows + a]);
+        } else {
+            run = *reinterpret_cast<const float4*>(in + e);
+        }
+    }
     constexpr int U = 16;                      // segments in flight per thread
     const bool suffix = (mode == SCAN_EXCL_SUFFIX);
     for (int s0 = 0; s0 < n_seg; s0 += U) {
@@ -53,14 +66,14 @@ __global__ __launch_bounds__(256) void scan_states_kernel(float* __restrict__ st
     }
 }
 
-hipError_t scan_states(float* states, size_t array_stride, int n_arrays, const int* modes, long BH, int n_seg, int elems,
-                       hipStream_t st)
+hipError_t scan_states(float* states, size_t array_stride, int n_arrays, const int* modes, const float* const* init,
+                       int init_cols, long BH, int n_seg, int elems, hipStream_t st)
 {
     ScanModes m{};
-    for (int z = 0; z < n_arrays && z < 2; ++z) m.mode[z] = modes[z];
+    for (int z = 0; z < n_arrays && z < 2; ++z) { m.mode[z] = modes[z]; m.init[z] = init ? init[z] : nullptr; }
     dim3 grid((unsigned)BH, (elems / 4 + 255) / 256, n_arrays);
     ProfScope prof(KID_SCAN, st);
-    hipLaunchKernelGGL(scan_states_kernel, grid, dim3(256), 0, st, states, array_stride, n_seg, elems, m);
+    hipLaunchKernelGGL(scan_states_kernel, grid, dim3(256), 0, st, states, array_stride, n_seg, elems, m, init_cols);
     return hipGetLastError();
 }
 
@@ -241,7 +254,7 @@ hipError_t launch_f32(const float* Q, const float* K, const float* V, float* O, 
         }
         if ((e = hipGetLastError()) != hipSuccess) return e;
         const int mode = SCAN_EXCL_PREFIX;
-        if ((e = scan_states(ws, 0, 1, &mode, BH, plan.n_seg, dk * dv, st)) != hipSuccess) return e;
+        if ((e = scan_states(ws, 0, 1, &mode, nullptr, 0, BH, plan.n_seg, dk * dv, st)) != hipSuccess) return e;
     }
     const size_t lds = f32_sweep_lds(dk, dv, C);
     e = hipFuncSetAttribute((const void*)f32_sweep_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);

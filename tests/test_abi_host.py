@@ -92,6 +92,26 @@ def test_bwd_argument_errors(L, name):
     assert _bwd(L, name, N=0) == 0
 
 
+def test_state_and_step_argument_errors(L):
+    f = L.chela_linattn_fwd_state
+    S = A + 8 * SZ
+    assert f(A, A + SZ, A + 2 * SZ, S + 4, A + 3 * SZ, None, 1, 1, 64, 64, 64, 64, None) == -5   # misaligned state
+    assert f(A, A + SZ, A + 2 * SZ, A + 3 * SZ, A + 3 * SZ, None, 1, 1, 64, 64, 64, 64, None) == -6   # O overlaps S_in
+    assert f(None, A + SZ, A + 2 * SZ, None, A + 3 * SZ, None, 1, 1, 64, 64, 64, 64, None) == -1
+    g = L.chela_linattn_bwd_state
+    assert g(A, A + SZ, A + 2 * SZ, None, A + 3 * SZ, None, A + 4 * SZ, A + 5 * SZ, A + 6 * SZ, A + 4 * SZ,
+             1, 1, 64, 64, 64, 64, None) == -6                                                     # dS_in overlaps dQ
+    assert g(A, A + SZ, A + 2 * SZ, None, A + 3 * SZ, None, A + 4 * SZ, A + 5 * SZ, A + 6 * SZ, None,
+             1, 1, 64, 48, 64, 64, None) == -3
+    st = L.chela_linattn_step
+    assert st(A, A + SZ, A + 2 * SZ, S, A + 3 * SZ, 0, 4, 64, 64, None) == 0
+    assert st(A, A + SZ, A + 2 * SZ, None, A + 3 * SZ, 1, 4, 64, 64, None) == -1
+    assert st(A, A + SZ, A + 2 * SZ, S, A + 3 * SZ, 1, 4, 64, 96, None) == -3
+    assert st(A, A + SZ, A + 2 * SZ, S, S, 1, 4, 64, 64, None) == -6
+    assert st(A, A + SZ, A + 2 * SZ, S + 4, A + 3 * SZ, 1, 4, 64, 64, None) == -5
+    assert st(A, A + SZ, A + 2 * SZ, S, A + 3 * SZ, -1, 4, 64, 64, None) == -2
+
+
 def test_shape_overflow_is_rejected(L):
     assert _fwd(L, B=1 << 20, H=1 << 20, N=1 << 20) == -2
 
@@ -99,7 +119,7 @@ def test_shape_overflow_is_rejected(L):
 def test_workspace_bytes(L):
     w = L.chela_linattn_workspace_bytes
     assert w(0, 1, 64, 64, 64, 64, 0, 0) == 0
-    assert w(1, 1, 64, 64, 64, 64, 0, 0) == 0                     # one segment: no scratch
+    assert w(1, 1, 64, 64, 64, 64, 0, 0) == 64 * 64 * 4           # one segment: one slot, used only with a carried-in state
     assert w(1, 1, 64, 48, 64, 64, 0, 0) == 0                     # invalid -> 0
     state = 48 * 64 * 64 * 4                                      # one fp32 state for each of the 48 (b,h) pairs
     fwd = w(4, 12, 16384, 64, 64, 64, 0, 0)
@@ -107,8 +127,8 @@ def test_workspace_bytes(L):
     assert fwd > 0 and fwd % state == 0                           # forward: one state array (K^T V prefixes)
     assert bwd > 0 and bwd % (2 * state) == 0                     # backward: two (prefix of V^T K, suffix of dO^T Q)
     assert 2 <= fwd // state <= 64 and 2 <= bwd // (2 * state) <= 64
-    # 256 or more (b,h) pairs need no segmentation, hence no scratch
-    assert w(32, 8, 4096, 64, 64, 64, 0, 0) == 0
+    # 256 or more (b,h) pairs need no segmentation: one slot per pair, touched only when a state is carried in
+    assert w(32, 8, 4096, 64, 64, 64, 0, 0) == 256 * 64 * 64 * 4
     # fixed-memory property: the number of segments is set by the GPU, not by N, so the scratch stays bounded
     for n in (1 << 16, 1 << 18, 1 << 20):
         assert w(4, 12, n, 64, 64, 64, 0, 0) <= 64 * state

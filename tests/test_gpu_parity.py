@@ -257,3 +257,101 @@ def test_empty_inputs_on_device():
     z = torch.empty((2, 2, 0, 64), dtype=torch.bfloat16, device="cuda")
     O = binding.chela_linattn_fwd(z, z, z)
     assert O.shape == (2, 2, 0, 64)
+
+
+# ------------------------------------------------------------------------------------------ carried state, decode step
+STATE_SHAPES = [(1, 2, 64, 64, 64), (2, 2, 1000, 64, 64), (1, 3, 2048, 64, 64), (2, 1, 700, 64, 128),
+                (1, 2, 900, 128, 64), (1, 2, 1500, 128, 128), (1, 1, 1, 64, 64)]
+
+
+def _state(shape, seed, scale=1.0):
+    g = torch.Generator(device="cpu")
+    g.manual_seed(seed)
+    return (torch.randn(*shape, generator=g, dtype=torch.float32) * scale).contiguous()
+
+
+@pytest.mark.parametrize("shape", STATE_SHAPES)
+def test_state_carry_forward_and_backward(shape):
+    B, H, N, dk, dv = shape
+    w = shrink(WORKLOADS["lm_bf16"], B=B, H=H, N=N, dk=dk, dv=dv, seed=300 + N)
+    x = make_inputs(w)
+    S_in = _state((B, H, dk, dv), 11, 2.0)
+    dS_out = _state((B, H, dk, dv), 12, 0.5)
+    d = _dev(x)
+    O, S_out = binding.chela_linattn_fwd_state(d["Q"], d["K"], d["V"], S_in=S_in.cuda())
+    dQ, dK, dV, dS_in = binding.chela_linattn_bwd_state(d["Q"], d["K"], d["V"], d["dO"], S_in=S_in.cuda(),
+                                                        dS_out=dS_out.cuda())
+    torch.cuda.synchronize()
+    Qn, Kn, Vn, Gn = (to_f64_numpy(x[n]) for n in ("Q", "K", "V", "dO"))
+    rO, rS = oracle.fwd_state(Qn, Kn, Vn, S_in=S_in.double().numpy())
+    rdQ, rdK, rdV, rdS = oracle.bwd_state(Qn, Kn, Vn, Gn, S_in=S_in.double().numpy(), dS_out=dS_out.double().numpy())
+    print("\nstate case", shape, flush=True)
+    _check("O", O, rO, "bf16")
+    for name, got, ref in (("dQ", dQ, rdQ), ("dK", dK, rdK), ("dV", dV, rdV)):
+        _check(name, got, ref, "bf16")
+    # the states themselves are fp32 sums of exact bf16 products: fp32-level agreement
+    for name, got, ref in (("S_out", S_out, rS), ("dS_in", dS_in, rdS)):
+        err = oracle.rel_l2(to_f64_numpy(got), ref)
+        print("   rel-L2 %-5s = %.3e" % (name, err), flush=True)
+        assert err <= 1e-5, (name, err)
+
+
+def test_state_outputs_without_state_inputs():
+    # S_out and dS_in alone (no carried-in state): the stateless kernels with one extra store
+    w = shrink(WORKLOADS["lm_bf16"], B=1, H=2, N=1300, seed=77)
+    x = make_inputs(w)
+    d = _dev(x)
+    O, S_out = binding.chela_linattn_fwd_state(d["Q"], d["K"], d["V"])
+    dQ, dK, dV, dS_in = binding.chela_linattn_bwd_state(d["Q"], d["K"], d["V"], d["dO"])
+    assert torch.equal(O, binding.chela_linattn_fwd(d["Q"], d["K"], d["V"]))
+    for a, b in zip((dQ, dK, dV), binding.chela_linattn_bwd(d["Q"], d["K"], d["V"], d["dO"])):
+        assert torch.equal(a, b)
+    Kd, Vd, Qd, Gd = (d[n].double()[0] for n in ("K", "V", "Q", "dO"))
+    assert float((S_out[0].double() - Kd.transpose(1, 2) @ Vd).norm() / S_out.double().norm()) < 1e-5
+    assert float((dS_in[0].double() - Qd.transpose(1, 2) @ Gd).norm() / dS_in.double().norm()) < 1e-5
+
+
+def test_two_segments_with_carry_equal_one_pass():
+    w = shrink(WORKLOADS["lm_bf16"], B=2, H=2, N=2048, seed=55)
+    d = _dev(make_inputs(w))
+    whole = binding.chela_linattn_fwd(d["Q"], d["K"], d["V"]).double()
+    cut = 1100
+    a = {k: v[:, :, :cut].contiguous() for k, v in d.items()}
+    b = {k: v[:, :, cut:].contiguous() for k, v in d.items()}
+    O1, S = binding.chela_linattn_fwd_state(a["Q"], a["K"], a["V"])
+    O2, S = binding.chela_linattn_fwd_state(b["Q"], b["K"], b["V"], S_in=S, S_out=S)     # state updated in place
+    both = torch.cat([O1, O2], dim=2).double()
+    assert float((both - whole).norm() / whole.norm()) < 6e-3
+    K, V = d["K"].double(), d["V"].double()
+    assert float((S.double() - K.transpose(2, 3) @ V).norm() / S.double().norm()) < 1e-5
+
+
+@pytest.mark.parametrize("dims", [(64, 64), (64, 128), (128, 64), (128, 128)])
+def test_decode_step(dims):
+    dk, dv = dims
+    B, H, T = 2, 3, 40
+    g = torch.Generator(device="cpu")
+    g.manual_seed(9)
+    q = (torch.randn(T, B, H, dk, generator=g) / 8).to(torch.bfloat16)
+    k = (torch.randn(T, B, H, dk, generator=g) / 8).to(torch.bfloat16)
+    v = torch.randn(T, B, H, dv, generator=g).to(torch.bfloat16)
+    S0 = _state((B, H, dk, dv), 3)
+    S = S0.clone().cuda()
+    ref_S = S0.double().numpy()
+    outs, refs = [], []
+    for t in range(T):
+        outs.append(binding.chela_linattn_step(q[t].cuda(), k[t].cuda(), v[t].cuda(), S))
+        ro, ref_S = oracle.step(to_f64_numpy(q[t]), to_f64_numpy(k[t]), to_f64_numpy(v[t]), ref_S)
+        refs.append(ro)
+    torch.cuda.synchronize()
+    err_o = oracle.rel_l2(np.stack([to_f64_numpy(o) for o in outs]), np.stack(refs))
+    err_S = oracle.rel_l2(to_f64_numpy(S), ref_S)
+    print("\ndecode dk%d dv%d: rel-L2 o %.3e  S %.3e" % (dk, dv, err_o, err_S), flush=True)
+    assert err_o <= 2e-2 and err_o <= 6e-3
+    assert err_S <= 1e-5
+    # T decode steps == one forward call over the T tokens, started from the same state
+    tok = lambda x: x.permute(1, 2, 0, 3).contiguous().cuda()
+    O, S_seq = binding.chela_linattn_fwd_state(tok(q), tok(k), tok(v), S_in=S0.cuda())
+    O_steps = torch.stack(outs, dim=2).double()
+    assert float((O.double() - O_steps).norm() / O_steps.norm()) < 6e-3
+    assert float((S_seq.double() - S.double()).norm() / S.double().norm()) < 1e-5
