@@ -43,6 +43,47 @@ def read_traffic(path):
     return float(m.group(1)) if m else None
 
 
+def bench_decode(args, w, torch, binding):
+    """Single-token decode steps (S += k v^T; o = S^T q) for `decode_batch` sequences x H heads of the workload's width."""
+    B, H, dk, dv = args.decode_batch, w.H, w.dk, w.dv
+    g = torch.Generator(device="cuda")
+    g.manual_seed(3)
+    q = (torch.randn(B, H, dk, device="cuda", generator=g) / 8).to(torch.bfloat16)
+    k = (torch.randn(B, H, dk, device="cuda", generator=g) / 8).to(torch.bfloat16)
+    v = torch.randn(B, H, dv, device="cuda", generator=g).to(torch.bfloat16)
+    S = torch.zeros(B, H, dk, dv, device="cuda")
+    o = torch.empty(B, H, dv, device="cuda", dtype=torch.bfloat16)
+    for _ in range(args.warmup):
+        binding.chela_linattn_step(q, k, v, S, o=o)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        binding.chela_linattn_step(q, k, v, S, o=o)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    binding.chela_profile_reset()
+    binding.chela_profile_enable(True)
+    for _ in range(args.steps):
+        binding.chela_linattn_step(q, k, v, S, o=o)
+    torch.cuda.synchronize()
+    prof = binding.chela_profile_read()
+    binding.chela_profile_enable(False)
+    binding.chela_profile_reset()
+    n, tot = prof["bf16_step_kernel"]
+    us = tot * 1e3 / n
+    alg = B * H * (2 * dk * dv * 4 + 2 * (2 * dk + 2 * dv))     # state read + written in fp32, q,k,v,o in bf16
+    achieved = alg / (us * 1e-6) / 1e9
+    print(json.dumps({
+        "metric": "causal linear-attn decode tokens/s", "value": round(B / (ms * 1e-3), 1), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 5), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "decode: %d sequences x H%d dk%d dv%d, one token each per step, fp32 state" % (B, H, dk, dv)},
+        "roofline": {"bound": "hbm", "kernel": "bf16_step_kernel", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "algorithmic_bytes_per_launch": alg, "avg_launch_us": round(us, 2)},
+        "cpu_baseline": None}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -50,6 +91,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="lm_bf16")
     ap.add_argument("--chunk", type=int, default=64)
+    ap.add_argument("--mode", default="train", choices=["train", "train_state", "decode"],
+                    help="train: fwd+bwd (the headline); train_state: the same through the carried-state entry points "
+                         "(S_in, S_out, dS_out, dS_in all live); decode: single-token steps of the recurrent form")
+    ap.add_argument("--decode-batch", type=int, default=256, help="sequences decoded together in --mode decode")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also run the library's plain copy kernel on a buffer of this many MiB (3 launches): the "
@@ -67,17 +112,35 @@ def main():
     from paper_2406_08128_amd.workloads import WORKLOADS, make_inputs, to_f64_numpy
 
     w = WORKLOADS[args.workload]
-    assert w.dtype == "bf16", "bench.py times the bf16 path"
     torch.cuda.set_device(0)
-    x = make_inputs(w, with_dO=True)
+    if args.mode == "decode":
+        return bench_decode(args, w, torch, binding)
+    has_bwd = w.backward          # the headline workload runs forward + backward; forward-only workloads time the forward
+    es = 2 if w.dtype == "bf16" else 4
+    x = make_inputs(w, with_dO=has_bwd)
     d = {k: v.cuda() for k, v in x.items()}
     O = torch.empty_like(d["V"])
-    dQ, dK, dV = torch.empty_like(d["Q"]), torch.empty_like(d["K"]), torch.empty_like(d["V"])
+    dQ, dK, dV = (torch.empty_like(d["Q"]), torch.empty_like(d["K"]), torch.empty_like(d["V"])) if has_bwd else (None,) * 3
     chunk = args.chunk
 
-    def step():
-        binding.chela_linattn_fwd(d["Q"], d["K"], d["V"], O=O, chunk=chunk)
-        binding.chela_linattn_bwd(d["Q"], d["K"], d["V"], d["dO"], dQ=dQ, dK=dK, dV=dV, chunk=chunk)
+    if args.mode == "train_state":
+        assert has_bwd and w.dtype == "bf16", "--mode train_state needs a bf16 forward+backward workload"
+        g = torch.Generator(device="cuda")
+        g.manual_seed(7)
+        S_in = torch.randn(w.B, w.H, w.dk, w.dv, device="cuda", generator=g)
+        dS_out = torch.randn(w.B, w.H, w.dk, w.dv, device="cuda", generator=g)
+        S_out = torch.empty_like(S_in)
+
+        def step():
+            binding.chela_linattn_fwd_state(d["Q"], d["K"], d["V"], S_in=S_in, O=O, S_out=S_out, chunk=chunk)
+            binding.chela_linattn_bwd_state(d["Q"], d["K"], d["V"], d["dO"], S_in=S_in, dS_out=dS_out, chunk=chunk)
+    elif has_bwd:
+        def step():
+            binding.chela_linattn_fwd(d["Q"], d["K"], d["V"], O=O, chunk=chunk)
+            binding.chela_linattn_bwd(d["Q"], d["K"], d["V"], d["dO"], dQ=dQ, dK=dK, dV=dV, chunk=chunk)
+    else:
+        def step():
+            binding.chela_linattn_fwd(d["Q"], d["K"], d["V"], O=O, chunk=chunk)
 
     if args.copy_probe_mib > 0:
         src = torch.zeros(args.copy_probe_mib << 20, dtype=torch.uint8, device="cuda")
@@ -110,18 +173,23 @@ def main():
     binding.chela_profile_reset()
     kernels = {k: {"launches": n, "avg_us": ms * 1e3 / n} for k, (n, ms) in prof.items()}
 
-    fwd_b, bwd_b = algorithmic_bytes_per_token_head(w.dk, w.dv)
+    fwd_b, bwd_b = algorithmic_bytes_per_token_head(w.dk, w.dv, es)
     fwd_f, bwd_f = flops_per_token_head(w.dk, w.dv, chunk)
     th = w.token_heads
-    dom = "bf16_bwd_sweep_kernel"
+    if w.dtype != "bf16":
+        dom, dom_b = "f32_sweep_kernel", fwd_b
+    elif has_bwd:
+        dom, dom_b = "bf16_bwd_sweep_kernel", bwd_b
+    else:
+        dom, dom_b = "bf16_fwd_sweep_kernel", fwd_b
     dom_us = kernels[dom]["avg_us"]
-    achieved = bwd_b * th / (dom_us * 1e-6) / 1e9
-    traffic = read_traffic(args.traffic_file) if args.workload == "lm_bf16" else None
+    achieved = dom_b * th / (dom_us * 1e-6) / 1e9
+    traffic = read_traffic(args.traffic_file) if (args.workload == "lm_bf16" and chunk == 64) else None
     roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
-                "algorithmic_bytes_per_launch": bwd_b * th, "avg_launch_us": round(dom_us, 2)}
-    step_bytes = (fwd_b + bwd_b) * th
-    step_flops = (fwd_f + bwd_f) * th
+                "algorithmic_bytes_per_launch": dom_b * th, "avg_launch_us": round(dom_us, 2)}
+    step_bytes = (fwd_b + (bwd_b if has_bwd else 0)) * th
+    step_flops = (fwd_f + (bwd_f if has_bwd else 0)) * th
     whole = {"hbm_GBs_algorithmic": round(step_bytes / (ms_per_step * 1e-3) / 1e9, 1),
              "hbm_frac": round(step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
              "mfma_TFLOPs_full_tile_model": round(step_flops / (ms_per_step * 1e-3) / 1e12, 1),
@@ -130,18 +198,21 @@ def main():
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
-        Qn, Kn, Vn, Gn = (to_f64_numpy(x[n]) for n in ("Q", "K", "V", "dO"))
+        Qn, Kn, Vn = (to_f64_numpy(x[n]) for n in ("Q", "K", "V"))
+        Gn = to_f64_numpy(x["dO"]) if has_bwd else None
         c0 = time.perf_counter()
         oracle.fwd_recurrent(Qn, Kn, Vn)
-        oracle.bwd_recurrent(Qn, Kn, Vn, Gn)
+        if has_bwd:
+            oracle.bwd_recurrent(Qn, Kn, Vn, Gn)
         c1 = time.perf_counter()
         cpu = {"value": round(w.tokens / (c1 - c0), 1), "unit": "tokens/s", "cores": oracle.num_threads(),
                "kind": "oracle", "seconds": round(c1 - c0, 3),
-               "sample": "fp64 recurrent-form oracle, fwd+bwd, all %d (b,h) pairs of the workload, one repetition"
-                         % (w.B * w.H)}
+               "sample": "fp64 recurrent-form oracle, %s, all %d (b,h) pairs of the workload, one repetition"
+                         % ("fwd+bwd" if has_bwd else "fwd", w.B * w.H)}
 
     out = {
-        "metric": "causal linear-attn fwd+bwd tokens/s",
+        "metric": "causal linear-attn %s tokens/s" % ("fwd+bwd" if has_bwd else "fwd")
+                  + (" (carried-state entry points)" if args.mode == "train_state" else ""),
         "value": round(tokens_per_s, 1),
         "unit": "tokens/s",
         "n_gpus": 1,
@@ -151,10 +222,12 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "bf16",
+        "dtype": w.dtype,
         "data": "synthetic",
-        "config": {"workload": "%s: B%d H%d N%d dk%d dv%d bf16 I/O fp32 accumulate, fwd+bwd, chunk %d"
-                               % (w.name, w.B, w.H, w.N, w.dk, w.dv, chunk),
+        "config": {"workload": "%s: B%d H%d N%d dk%d dv%d %s, %s, chunk %d"
+                               % (w.name, w.B, w.H, w.N, w.dk, w.dv,
+                                  "bf16 I/O fp32 accumulate" if w.dtype == "bf16" else "fp32 I/O",
+                                  "fwd+bwd" if has_bwd else "fwd", chunk),
                    "tokens_per_step": w.tokens, "token_heads_per_step": th},
         "roofline": roofline,
         "whole_step": whole,

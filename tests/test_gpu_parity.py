@@ -253,6 +253,12 @@ def test_more_heads_than_a_grid_dimension_holds():
         _check(name, sel(got), ref, "bf16")
 
 
+def test_one_very_long_ragged_sequence():
+    # a single (b,h) pair, 200 003 tokens: hundreds of segments, a ragged tail, a long scan
+    w = shrink(WORKLOADS["lm_bf16"], B=1, H=1, N=200003, seed=71)
+    _run_case(w, 64, True)
+
+
 def test_empty_inputs_on_device():
     z = torch.empty((2, 2, 0, 64), dtype=torch.bfloat16, device="cuda")
     O = binding.chela_linattn_fwd(z, z, z)
