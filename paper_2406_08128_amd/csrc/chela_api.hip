@@ -181,15 +181,13 @@ static int validate(const void* const* in, const size_t* in_bytes, int n_in,
     return CHELA_OK;
 }
 
+// The fp32 kernels tile with the chunk that fits LDS next to the fp32 state: 64 tokens, 32 when both head widths
+// are 128.  The `chunk` argument (validated, {16, 32, 64}) is a hint and, like every chunking, cannot change the result
+// beyond re-association.
 static int f32_effective_chunk(int dk, int dv, int chunk)
 {
-    // The fp32 kernel keeps Q, K, V tiles, the score tile and the whole state in LDS (160 KB per workgroup).
-    auto lds = [&](int c) {
-        return sizeof(float) * ((size_t)2 * c * (dk + 1) + (size_t)c * (dv + 1) + (size_t)c * (c + 1) +
-                                (size_t)dk * (dv + 1));
-    };
-    while (chunk > 16 && lds(chunk) > 150 * 1024) chunk /= 2;
-    return chunk;
+    (void)chunk;
+    return (dk == 128 && dv == 128) ? 32 : 64;
 }
 
 // The backward sweep keeps four input tiles and two states in LDS; 128-token chunks only fit with 64-wide heads.

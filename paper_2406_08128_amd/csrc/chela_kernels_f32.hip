@@ -1,10 +1,16 @@
-// fp32 kernels: causal linear attention with fp32 I/O and fp32 arithmetic (plain FMA, no matrix cores:
-// the fp32 path exists for accuracy, the bf16 path for speed).  Also the state scan shared by both paths.
+// fp32 kernels: causal linear attention with fp32 I/O and fp32 arithmetic on the fp32 matrix instruction
+// v_mfma_f32_32x32x2_f32 (products and sums in IEEE fp32; the path exists for accuracy, the bf16 path for speed).
+// Also the state scan and the copy probe shared by both paths.
 //
 // Structure (Sec. 4.1): a (b,h) sequence is cut into segments; within a segment one workgroup walks the
-// chunks in order, holding the d_k x d_v state S in LDS.  Per chunk: masked left product P = (Q K^T) o M,
-// O = P V + Q S (both parts summed on chip), then S += K^T V.  Segment start states come from a pre-pass
-// (segment totals of K^T V) and a scan over segments.
+// chunks in order with the d_k x d_v state S in accumulator registers.  Per chunk: masked left product
+// P = (Q K^T) o M, O = P V + Q S (both parts summed in the same accumulators), then S += K^T V.  Segment start
+// states come from a pre-pass (segment totals of K^T V) and a scan over segments.
+//
+// Operand plumbing is simpler than in the bf16 kernels: with k = 2 per instruction a lane supplies ONE float of A
+// (row lane%32, k = lane/32) and ONE of B, so every operand is a 4-byte LDS read -- along a row of a row-major tile
+// (stride = leading dimension, kept odd so the 32 rows fall into 32 different banks) or along its columns
+// (contiguous).  Nothing is ever transposed.
 #include "chela_internal.h"
 
 namespace chela {
@@ -95,175 +101,237 @@ hipError_t launch_copy(const void* src, void* dst, size_t bytes, hipStream_t st)
     return hipGetLastError();
 }
 
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+__device__ __forceinline__ f32x16 mfma_f32(float a, float b, f32x16 c)
+{
+    return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ f32x16 zero16f()
+{
+    f32x16 z;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) z[i] = 0.f;
+    return z;
+}
+
 // Logical position p (0 = first token the causal sum sees) to physical row of the [N, d] matrix.
 __device__ __forceinline__ int phys_row(int p, int N, bool rev) { return rev ? (N - 1 - p) : p; }
 
-// ------------------------------------------------------------------------------------------------ segment totals
-// out[bh][seg][i*dv + j] = sum over the segment's tokens of K[t][i] * V[t][j].  The last segment's total is never
-// used by an exclusive prefix, so its workgroups leave at once.
-__global__ __launch_bounds__(256) void f32_seg_state_kernel(const float* __restrict__ K, const float* __restrict__ V,
-                                                           float* __restrict__ out, int N, int dk, int dv,
-                                                           int seg_len, int n_seg, int rev)
+// acc[32x32] += A B over K2 values of k.
+//   A element (m, k): a_base[(m) * a_rs + (k) * a_ks]   B element (k, n): b_base[(k) * b_ks + (n) * b_ns]
+// with m = lane%32 (+ tile offset folded into the base), n = lane%32, k = k0 + lane/32, k0 stepping by 2.
+__device__ __forceinline__ f32x16 gemm_tile(f32x16 acc, const float* a_base, int a_rs, int a_ks, const float* b_base,
+                                            int b_ks, int b_ns, int K2, int lane)
 {
-    extern __shared__ float lds[];
+    const int r = lane & 31, h = lane >> 5;
+    const float* pa = a_base + r * a_rs + h * a_ks;
+    const float* pb = b_base + h * b_ks + r * b_ns;
+#pragma unroll 8
+    for (int k0 = 0; k0 < K2; k0 += 2) acc = mfma_f32(pa[k0 * a_ks], pb[k0 * b_ks], acc);
+    return acc;
+}
+
+// C rows of a row-major [N][D] fp32 matrix, starting at logical position c0 -> LDS tile with leading dimension D+1.
+// Rows at or beyond p_end read as zero.
+template <int C, int D>
+__device__ __forceinline__ void load_tile_f32(float* lds, const float* base, int c0, int p_end, int N, bool rev, int tid)
+{
+    constexpr int V4 = D / 4;   // float4 per row
+#pragma unroll
+    for (int n = 0; n < C * V4 / 256; ++n) {
+        const int x = tid + 256 * n, row = x / V4, c4 = x % V4, p = c0 + row;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (p < p_end) v = *reinterpret_cast<const float4*>(base + (size_t)phys_row(p, N, rev) * D + c4 * 4);
+        float* d = lds + row * (D + 1) + c4 * 4;
+        d[0] = v.x; d[1] = v.y; d[2] = v.z; d[3] = v.w;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------ segment totals
+// out[bh][seg][i*DV + j] = sum over the segment's tokens of K[t][i] * V[t][j].  The last segment's total is never
+// used by an exclusive prefix, so its workgroups leave at once.  Wave w owns output tiles w, w+4, ...
+template <int DK, int DV>
+__global__ __launch_bounds__(256) void f32_seg_state_kernel(const float* __restrict__ K, const float* __restrict__ V,
+                                                           float* __restrict__ out, int N, int seg_len, int n_seg,
+                                                           int rev)
+{
+    constexpr int R = 32;                         // tokens staged per step
+    constexpr int LDK = DK + 1, LDV = DV + 1;
+    __shared__ float sK[R * LDK];
+    __shared__ float sV[R * LDV];
     const int seg = blockIdx.y;
     const long bh = blockIdx.x;
     if (seg == n_seg - 1) return;
-    constexpr int R = 16;                         // rows staged per step
-    float* sK = lds;                              // [R][dk]
-    float* sV = lds + R * dk;                     // [R][dv]
-    const int tid = threadIdx.x;
-    const float* Kb = K + (size_t)bh * N * dk;
-    const float* Vb = V + (size_t)bh * N * dv;
-    const int p0 = seg * seg_len;
-    const int p1 = min(N, p0 + seg_len);
-    const int per_thread = dk * dv / 256;         // 16, 32 or 64
-    float acc[64];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const float* Kb = K + (size_t)bh * N * DK;
+    const float* Vb = V + (size_t)bh * N * DV;
+    const int p0 = seg * seg_len, p1 = min(N, p0 + seg_len);
+    constexpr int JB = DV / 32, NT = (DK / 32) * JB / 4;
+    f32x16 acc[NT];
 #pragma unroll
-    for (int n = 0; n < 64; ++n) acc[n] = 0.f;
+    for (int n = 0; n < NT; ++n) acc[n] = zero16f();
     for (int c0 = p0; c0 < p1; c0 += R) {
-        for (int x = tid; x < R * dk; x += 256) {
-            int r = x / dk, c = x - r * dk, p = c0 + r;
-            sK[x] = p < p1 ? Kb[(size_t)phys_row(p, N, rev) * dk + c] : 0.f;
-        }
-        for (int x = tid; x < R * dv; x += 256) {
-            int r = x / dv, c = x - r * dv, p = c0 + r;
-            sV[x] = p < p1 ? Vb[(size_t)phys_row(p, N, rev) * dv + c] : 0.f;
-        }
+        __syncthreads();
+        load_tile_f32<R, DK>(sK, Kb, c0, p1, N, rev, tid);
+        load_tile_f32<R, DV>(sV, Vb, c0, p1, N, rev, tid);
         __syncthreads();
 #pragma unroll
-        for (int n = 0; n < 64; ++n) {
-            if (n < per_thread) {
-                const int e = tid + 256 * n, i = e / dv, j = e - i * dv;
-                float a = acc[n];
-                for (int r = 0; r < R; ++r) a = fmaf(sK[r * dk + i], sV[r * dv + j], a);
-                acc[n] = a;
-            }
+        for (int n = 0; n < NT; ++n) {
+            const int id = w + 4 * n, ib = id / JB, jb = id % JB;
+            // A[m=i][k=s] = K[s][i]: contiguous in i;  B[k=s][n=j] = V[s][j]: contiguous in j
+            acc[n] = gemm_tile(acc[n], sK + ib * 32, 1, LDK, sV + jb * 32, LDV, 1, R, lane);
         }
-        __syncthreads();
     }
-    float* o = out + ((size_t)bh * n_seg + seg) * dk * dv;
+    float* o = out + ((size_t)bh * n_seg + seg) * DK * DV;
+    const int r = lane & 31, h = lane >> 5;
 #pragma unroll
-    for (int n = 0; n < 64; ++n)
-        if (n < per_thread) o[tid + 256 * n] = acc[n];
+    for (int n = 0; n < NT; ++n) {
+        const int id = w + 4 * n, ib = id / JB, jb = id % JB;
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+#pragma unroll
+            for (int b = 0; b < 4; ++b) o[(ib * 32 + 8 * a + 4 * h + b) * DV + jb * 32 + r] = acc[n][4 * a + b];
+    }
 }
 
 // ------------------------------------------------------------------------------------------------ main sweep
-// One workgroup per (segment, bh).  LDS: Q, K [C][dk+1]; V [C][dv+1]; P [C][C+1]; S [dk][dv+1] (the +1 keeps
-// column walks off a single bank).
+// One workgroup (4 waves) per (segment, bh).  Wave w owns output rows [32*tb, +32) with tb = w % WT and NJ column
+// tiles, and the state tiles w, w+4, ...  LDS: Q, K [C][DK+1]; V [C][DV+1]; S [DK][DV+1]; P [C][C+1].
+template <int C, int DK, int DV>
 __global__ __launch_bounds__(256) void f32_sweep_kernel(const float* __restrict__ Q, const float* __restrict__ K,
                                                        const float* __restrict__ V, float* __restrict__ O,
-                                                       const float* __restrict__ S0, int N, int dk, int dv, int C,
-                                                       int seg_len, int n_seg, int rev)
+                                                       const float* __restrict__ S0, int N, int seg_len, int n_seg,
+                                                       int rev)
 {
-    extern __shared__ float lds[];
-    const int ldk = dk + 1, ldv = dv + 1, ldp = C + 1;
-    float* sQ = lds;
-    float* sK = sQ + C * ldk;
-    float* sV = sK + C * ldk;
-    float* sP = sV + C * ldv;
-    float* sS = sP + C * ldp;
+    constexpr int LDK = DK + 1, LDV = DV + 1, LDP = C + 1;
+    constexpr int TB = C / 32, JB = DV / 32, IB = DK / 32;
+    constexpr int WT = TB < 4 ? TB : 4, WJ = 4 / WT, NJ = JB / WJ;
+    constexpr int NS = IB * JB / 4;
+    static_assert(JB % WJ == 0, "unsupported tile shape");
+    __shared__ float sQ[C * LDK];
+    __shared__ float sK[C * LDK];
+    __shared__ float sV[C * LDV];
+    __shared__ float sS[DK * LDV];
+    __shared__ float sP[C * LDP];
     const int seg = blockIdx.y;
     const long bh = blockIdx.x;
-    const int tid = threadIdx.x;
-    const float* Qb = Q + (size_t)bh * N * dk;
-    const float* Kb = K + (size_t)bh * N * dk;
-    const float* Vb = V + (size_t)bh * N * dv;
-    float* Ob = O + (size_t)bh * N * dv;
-    const int p0 = seg * seg_len;
-    const int p1 = min(N, p0 + seg_len);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int tb = w % WT, jg = w / WT;
+    const int r = lane & 31, h = lane >> 5;
+    const float* Qb = Q + (size_t)bh * N * DK;
+    const float* Kb = K + (size_t)bh * N * DK;
+    const float* Vb = V + (size_t)bh * N * DV;
+    float* Ob = O + (size_t)bh * N * DV;
+    const int p0 = seg * seg_len, p1 = min(N, p0 + seg_len);
 
-    // start state of this segment: exclusive prefix over earlier segments, zero for the first
-    const float* s0 = (S0 != nullptr && seg > 0) ? S0 + ((size_t)bh * n_seg + seg) * dk * dv : nullptr;
-    for (int e = tid; e < dk * dv; e += 256) {
-        int i = e / dv, j = e - i * dv;
-        sS[i * ldv + j] = s0 ? s0[e] : 0.f;
+    // start state of this segment (exclusive prefix over earlier segments, zero for the first), as accumulator tiles
+    f32x16 accS[NS];
+    const float* s0 = (S0 != nullptr && seg > 0) ? S0 + ((size_t)bh * n_seg + seg) * DK * DV : nullptr;
+#pragma unroll
+    for (int n = 0; n < NS; ++n) {
+        const int id = w + 4 * n, ib = id / JB, jb = id % JB;
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+#pragma unroll
+            for (int b = 0; b < 4; ++b)
+                accS[n][4 * a + b] = s0 ? s0[(ib * 32 + 8 * a + 4 * h + b) * DV + jb * 32 + r] : 0.f;
     }
 
     for (int c0 = p0; c0 < p1; c0 += C) {
-        __syncthreads();     // previous chunk fully consumed, state visible
-        for (int x = tid; x < C * dk; x += 256) {
-            int r = x / dk, c = x - r * dk, p = c0 + r;
-            bool ok = p < p1;
-            size_t g = ok ? (size_t)phys_row(p, N, rev) * dk + c : 0;
-            sQ[r * ldk + c] = ok ? Qb[g] : 0.f;
-            sK[r * ldk + c] = ok ? Kb[g] : 0.f;
-        }
-        for (int x = tid; x < C * dv; x += 256) {
-            int r = x / dv, c = x - r * dv, p = c0 + r;
-            sV[r * ldv + c] = p < p1 ? Vb[(size_t)phys_row(p, N, rev) * dv + c] : 0.f;
-        }
-        __syncthreads();
-        // P[t][s] = q_t . k_s for s <= t (the mask includes the diagonal), else 0
-        for (int x = tid; x < C * C; x += 256) {
-            int t = x / C, s = x - t * C;
-            float a = 0.f;
-            if (s <= t) {
-                const float* q = sQ + t * ldk;
-                const float* k = sK + s * ldk;
-                for (int i = 0; i < dk; ++i) a = fmaf(q[i], k[i], a);
-            }
-            sP[t * ldp + s] = a;
+        __syncthreads();   // previous chunk fully consumed
+        load_tile_f32<C, DK>(sQ, Qb, c0, p1, N, rev, tid);
+        load_tile_f32<C, DK>(sK, Kb, c0, p1, N, rev, tid);
+        load_tile_f32<C, DV>(sV, Vb, c0, p1, N, rev, tid);
+        // publish the state before this chunk, [i][j]
+#pragma unroll
+        for (int n = 0; n < NS; ++n) {
+            const int id = w + 4 * n, ib = id / JB, jb = id % JB;
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+#pragma unroll
+                for (int b = 0; b < 4; ++b) sS[(ib * 32 + 8 * a + 4 * h + b) * LDV + jb * 32 + r] = accS[n][4 * a + b];
         }
         __syncthreads();
-        // O[t][j] = sum_{s<=t} P[t][s] V[s][j] + sum_i Q[t][i] S[i][j]   (inner and outer parts summed on chip)
-        for (int x = tid; x < C * dv; x += 256) {
-            int t = x / dv, j = x - t * dv;
-            int p = c0 + t;
-            if (p < p1) {
-                float a = 0.f;
-                const float* pr = sP + t * ldp;
-                for (int s = 0; s <= t; ++s) a = fmaf(pr[s], sV[s * ldv + j], a);
-                float b = 0.f;
-                const float* q = sQ + t * ldk;
-                for (int i = 0; i < dk; ++i) b = fmaf(q[i], sS[i * ldv + j], b);
-                Ob[(size_t)phys_row(p, N, rev) * dv + j] = a + b;
+        // masked scores of this wave's row block: P[t][s] = q_t . k_s for s <= t, written to LDS (rows of tb only)
+#pragma unroll
+        for (int sb = 0; sb < TB; ++sb) {
+            if (sb <= tb) {
+                // A[m=t][k=i] = Q[t][i] (row walk), B[k=i][n=s] = K[s][i] (row walk)
+                f32x16 p = gemm_tile(zero16f(), sQ + tb * 32 * LDK, LDK, 1, sK + sb * 32 * LDK, 1, LDK, DK, lane);
+#pragma unroll
+                for (int a = 0; a < 4; ++a)
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) {
+                        const int row = 8 * a + 4 * h + b;   // query within the block; r = key within the block
+                        const float v = (sb == tb && r > row) ? 0.f : p[4 * a + b];
+                        sP[(tb * 32 + row) * LDP + sb * 32 + r] = v;
+                    }
             }
         }
-        __syncthreads();
-        // S[i][j] += sum_s K[s][i] V[s][j]
+        __syncthreads();   // both waves of a row block wrote the same values; now every wave may read them
+        f32x16 accO[NJ];
+#pragma unroll
+        for (int n = 0; n < NJ; ++n) {
+            const int j0 = (jg * NJ + n) * 32;
+            // inter-chunk part Q S_prev: A = Q rows (row walk), B[k=i][n=j] = S[i][j] (contiguous)
+            accO[n] = gemm_tile(zero16f(), sQ + tb * 32 * LDK, LDK, 1, sS + j0, LDV, 1, DK, lane);
+            // intra-chunk part P V over the key blocks sb <= tb: A = P rows (row walk), B[k=s][n=j] = V[s][j]
+            accO[n] = gemm_tile(accO[n], sP + tb * 32 * LDP, LDP, 1, sV + j0, LDV, 1, (tb + 1) * 32, lane);
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    const int pp = c0 + tb * 32 + 8 * a + 4 * h + b;
+                    if (pp < p1) Ob[(size_t)phys_row(pp, N, rev) * DV + j0 + r] = accO[n][4 * a + b];
+                }
+        }
+        // state update S += K^T V (not needed after the segment's last chunk)
         if (c0 + C < p1) {
-            for (int e = tid; e < dk * dv; e += 256) {
-                int i = e / dv, j = e - i * dv;
-                float a = sS[i * ldv + j];
-                for (int s = 0; s < C; ++s) a = fmaf(sK[s * ldk + i], sV[s * ldv + j], a);
-                sS[i * ldv + j] = a;
+#pragma unroll
+            for (int n = 0; n < NS; ++n) {
+                const int id = w + 4 * n, ib = id / JB, jb = id % JB;
+                accS[n] = gemm_tile(accS[n], sK + ib * 32, 1, LDK, sV + jb * 32, LDV, 1, C, lane);
             }
         }
     }
 }
 
-static size_t f32_sweep_lds(int dk, int dv, int C)
+template <int DK, int DV>
+static hipError_t launch_f32_impl(const float* Q, const float* K, const float* V, float* O, long BH, int N,
+                                  const Plan& plan, bool rev, float* ws, hipStream_t st)
 {
-    return sizeof(float) * ((size_t)2 * C * (dk + 1) + (size_t)C * (dv + 1) + (size_t)C * (C + 1) +
-                            (size_t)dk * (dv + 1));
+    hipError_t e;
+    constexpr int C = (DK == 128 && DV == 128) ? 32 : 64;   // what fits 160 KB of LDS
+    if (plan.n_seg > 1) {
+        dim3 grid((unsigned)BH, plan.n_seg);
+        {
+            ProfScope prof(KID_SEG_STATE_F32, st);
+            hipLaunchKernelGGL((f32_seg_state_kernel<DK, DV>), grid, dim3(256), 0, st, K, V, ws, N, plan.seg_len,
+                               plan.n_seg, (int)rev);
+        }
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+        const int mode = SCAN_EXCL_PREFIX;
+        if ((e = scan_states(ws, 0, 1, &mode, nullptr, 0, BH, plan.n_seg, DK * DV, st)) != hipSuccess) return e;
+    }
+    dim3 grid((unsigned)BH, plan.n_seg);
+    ProfScope prof(KID_SWEEP_F32, st);
+    hipLaunchKernelGGL((f32_sweep_kernel<C, DK, DV>), grid, dim3(256), 0, st, Q, K, V, O, plan.n_seg > 1 ? ws : nullptr,
+                       N, plan.seg_len, plan.n_seg, (int)rev);
+    return hipGetLastError();
 }
 
 hipError_t launch_f32(const float* Q, const float* K, const float* V, float* O, long BH, int N, int dk, int dv,
                       const Plan& plan, bool rev, float* ws, hipStream_t st)
 {
-    hipError_t e;
-    const int C = plan.chunk;
-    if (plan.n_seg > 1) {
-        dim3 grid((unsigned)BH, plan.n_seg);
-        size_t lds1 = sizeof(float) * 16 * (size_t)(dk + dv);
-        {
-            ProfScope prof(KID_SEG_STATE_F32, st);
-            hipLaunchKernelGGL(f32_seg_state_kernel, grid, dim3(256), lds1, st, K, V, ws, N, dk, dv, plan.seg_len,
-                               plan.n_seg, (int)rev);
-        }
-        if ((e = hipGetLastError()) != hipSuccess) return e;
-        const int mode = SCAN_EXCL_PREFIX;
-        if ((e = scan_states(ws, 0, 1, &mode, nullptr, 0, BH, plan.n_seg, dk * dv, st)) != hipSuccess) return e;
-    }
-    const size_t lds = f32_sweep_lds(dk, dv, C);
-    e = hipFuncSetAttribute((const void*)f32_sweep_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-    dim3 grid((unsigned)BH, plan.n_seg);
-    ProfScope prof(KID_SWEEP_F32, st);
-    hipLaunchKernelGGL(f32_sweep_kernel, grid, dim3(256), lds, st, Q, K, V, O, plan.n_seg > 1 ? ws : nullptr, N, dk,
-                       dv, C, plan.seg_len, plan.n_seg, (int)rev);
-    return hipGetLastError();
+    if (dk == 64 && dv == 64) return launch_f32_impl<64, 64>(Q, K, V, O, BH, N, plan, rev, ws, st);
+    if (dk == 64 && dv == 128) return launch_f32_impl<64, 128>(Q, K, V, O, BH, N, plan, rev, ws, st);
+    if (dk == 128 && dv == 64) return launch_f32_impl<128, 64>(Q, K, V, O, BH, N, plan, rev, ws, st);
+    if (dk == 128 && dv == 128) return launch_f32_impl<128, 128>(Q, K, V, O, BH, N, plan, rev, ws, st);
+    return hipErrorInvalidValue;
 }
 
 }  // namespace chela
