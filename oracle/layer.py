@@ -1,0 +1,49 @@
+"""fp64 CPU oracle for the pieces of the CHELA layer that sit directly around the attention kernel
+-- TEST INFRASTRUCTURE ONLY (same rules as the rest of this package).
+
+Sec. 4.3, Eq. 11-12: queries and keys are not separate projections but two per-feature affine maps of ONE tensor Z,
+
+        Q = alpha_q * Z + beta_q ,     K = alpha_k * Z + beta_k ,
+
+with learnable alpha, beta in R^d.  With d split over H heads of width dk, each head owns its slice of the four
+vectors: `affine` is a [4, H, dk] array holding (alpha_q, beta_q, alpha_k, beta_k), broadcast over batch and tokens.
+
+Everything here is plain numpy in float64; the attention itself is the pinned C oracle.
+"""
+import numpy as np
+
+from . import fwd_quadratic, bwd_quadratic
+
+
+def _check(Z, affine):
+    Z = np.asarray(Z, dtype=np.float64)
+    affine = np.asarray(affine, dtype=np.float64)
+    if Z.ndim != 4 or affine.shape != (4, Z.shape[1], Z.shape[3]):
+        raise ValueError("Z must be [B,H,N,dk] and affine [4,H,dk]")
+    return Z, affine
+
+
+def qk_from_z(Z, affine):
+    """(Q, K) of Eq. 11-12 for Z [B,H,N,dk] and affine [4,H,dk]."""
+    Z, a = _check(Z, affine)
+    Q = a[0][None, :, None, :] * Z + a[1][None, :, None, :]
+    K = a[2][None, :, None, :] * Z + a[3][None, :, None, :]
+    return Q, K
+
+
+def zqk_fwd(Z, affine, V):
+    """O_t = sum_{s<=t} (q_t . k_s) v_s with q, k from Eq. 11-12."""
+    Q, K = qk_from_z(Z, affine)
+    return fwd_quadratic(Q, K, V)
+
+
+def zqk_bwd(Z, affine, V, dO):
+    """(dZ, d_affine, dV) of zqk_fwd: the chain rule through Eq. 11-12.
+
+    dZ = alpha_q * dQ + alpha_k * dK;  d_alpha_q = sum_{b,t} dQ * Z;  d_beta_q = sum_{b,t} dQ;  same for k."""
+    Z, a = _check(Z, affine)
+    Q, K = qk_from_z(Z, a)
+    dQ, dK, dV = bwd_quadratic(Q, K, V, dO)
+    dZ = a[0][None, :, None, :] * dQ + a[2][None, :, None, :] * dK
+    d_aff = np.stack([(dQ * Z).sum(axis=(0, 2)), dQ.sum(axis=(0, 2)), (dK * Z).sum(axis=(0, 2)), dK.sum(axis=(0, 2))])
+    return dZ, d_aff, dV

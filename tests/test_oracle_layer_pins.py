@@ -1,0 +1,115 @@
+"""Pins for the layer-level oracle (no GPU): queries and keys as affine maps of one tensor Z (CHELA Sec. 4.3,
+Eq. 11-12) around the causal linear attention.
+
+Checked against scalar brute force, closed forms, the special case that reduces to the plain attention oracle, and
+finite differences of a scalar loss -- never against a retyped copy of the oracle's own array expressions.
+"""
+import numpy as np
+import pytest
+
+import oracle
+from oracle import layer
+
+
+def _rand(rng, B, H, N, dk, dv):
+    Z = rng.standard_normal((B, H, N, dk))
+    aff = rng.standard_normal((4, H, dk))
+    V = rng.standard_normal((B, H, N, dv))
+    dO = rng.standard_normal((B, H, N, dv))
+    return Z, aff, V, dO
+
+
+def _brute_fwd(Z, aff, V):
+    B, H, N, dk = Z.shape
+    dv = V.shape[3]
+    O = np.zeros((B, H, N, dv))
+    for b in range(B):
+        for h in range(H):
+            for t in range(N):
+                for s in range(t + 1):
+                    dot = 0.0
+                    for i in range(dk):
+                        q = aff[0, h, i] * Z[b, h, t, i] + aff[1, h, i]
+                        k = aff[2, h, i] * Z[b, h, s, i] + aff[3, h, i]
+                        dot += q * k
+                    for j in range(dv):
+                        O[b, h, t, j] += dot * V[b, h, s, j]
+    return O
+
+
+def test_zqk_forward_brute_force():
+    rng = np.random.default_rng(11)
+    Z, aff, V, _ = _rand(rng, 2, 2, 6, 3, 2)
+    np.testing.assert_allclose(layer.zqk_fwd(Z, aff, V), _brute_fwd(Z, aff, V), rtol=1e-12, atol=1e-12)
+
+
+def test_zqk_identity_affine_is_plain_attention_of_z():
+    rng = np.random.default_rng(12)
+    Z, aff, V, dO = _rand(rng, 1, 3, 17, 4, 5)
+    aff[0] = 1.0; aff[1] = 0.0; aff[2] = 1.0; aff[3] = 0.0
+    np.testing.assert_allclose(layer.zqk_fwd(Z, aff, V), oracle.fwd_recurrent(Z, Z, V), rtol=1e-12, atol=1e-12)
+    dZ, _, dV = layer.zqk_bwd(Z, aff, V, dO)
+    dQ, dK, dV2 = oracle.bwd_recurrent(Z, Z, V, dO)
+    np.testing.assert_allclose(dZ, dQ + dK, rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(dV, dV2, rtol=1e-12, atol=1e-12)
+
+
+def test_zqk_offsets_only_is_scaled_cumsum():
+    # alpha = 0: q and k are the constant vectors beta_q, beta_k, so O_t = (beta_q . beta_k) * sum_{s<=t} v_s
+    rng = np.random.default_rng(13)
+    Z, aff, V, _ = _rand(rng, 2, 2, 9, 4, 3)
+    aff[0] = 0.0
+    aff[2] = 0.0
+    c = (aff[1] * aff[3]).sum(axis=1)                       # [H]
+    want = c[None, :, None, None] * np.cumsum(V, axis=2)
+    np.testing.assert_allclose(layer.zqk_fwd(Z, aff, V), want, rtol=1e-12, atol=1e-12)
+
+
+def test_zqk_gradient_finite_differences():
+    rng = np.random.default_rng(14)
+    Z, aff, V, dO = _rand(rng, 2, 2, 5, 3, 2)
+    dZ, d_aff, dV = layer.zqk_bwd(Z, aff, V, dO)
+
+    def loss(Z_, aff_, V_):
+        return float((layer.zqk_fwd(Z_, aff_, V_) * dO).sum())
+
+    h = 1e-5
+    for arr, grad, which in ((Z, dZ, 0), (aff, d_aff, 1), (V, dV, 2)):
+        it = np.nditer(arr, flags=["multi_index"])
+        for _ in it:
+            idx = it.multi_index
+            args = [Z.copy(), aff.copy(), V.copy()]
+            args[which][idx] += h
+            up = loss(*args)
+            args[which][idx] -= 2 * h
+            dn = loss(*args)
+            fd = (up - dn) / (2 * h)
+            assert abs(fd - grad[idx]) <= 1e-6 * max(1.0, abs(fd)), (which, idx, fd, grad[idx])
+
+
+def test_zqk_affine_gradient_sums_over_batch_only_within_head():
+    # the parameters of head h see every batch entry of head h and nothing of the other heads
+    rng = np.random.default_rng(15)
+    Z, aff, V, dO = _rand(rng, 3, 2, 7, 4, 3)
+    _, d_aff, _ = layer.zqk_bwd(Z, aff, V, dO)
+    acc = np.zeros_like(d_aff)
+    for b in range(3):
+        for h in range(2):
+            _, d1, _ = layer.zqk_bwd(Z[b:b + 1, h:h + 1], aff[:, h:h + 1], V[b:b + 1, h:h + 1], dO[b:b + 1, h:h + 1])
+            acc[:, h] += d1[:, 0]
+    np.testing.assert_allclose(d_aff, acc, rtol=1e-12, atol=1e-12)
+
+
+def test_zqk_adjoint_in_v():
+    # for fixed Z and affine the map V -> O is linear; dV is its adjoint applied to dO
+    rng = np.random.default_rng(16)
+    Z, aff, V, dO = _rand(rng, 1, 2, 12, 4, 3)
+    _, _, dV = layer.zqk_bwd(Z, aff, V, dO)
+    lhs = float((layer.zqk_fwd(Z, aff, V) * dO).sum())
+    rhs = float((V * dV).sum())
+    assert abs(lhs - rhs) <= 1e-10 * max(1.0, abs(lhs))
+
+
+def test_zqk_shape_errors():
+    with pytest.raises(ValueError):
+        layer.qk_from_z(np.zeros((1, 2, 3, 4)), np.zeros((4, 1, 4)))
