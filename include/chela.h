@@ -107,6 +107,28 @@ int chela_linattn_bwd_state(const void *Q, const void *K, const void *V, const f
                             void *dQ, void *dK, void *dV, float *dS_in,
                             int B, int H, int N, int dk, int dv, int chunk, void *stream);
 
+/* ---- queries and keys from one tensor (Sec. 4.3, Eq. 11-12: Q = alpha_q * Z + beta_q, K = alpha_k * Z + beta_k,
+ * learnable per-feature scales and offsets) --------------------------------------------------------------------
+ * Same map as chela_linattn_fwd / _bwd, bf16 I/O, but the library reads Z once and forms Q and K on chip, so the
+ * forward moves three tensors instead of four and the backward five instead of seven.
+ *   Z        : [B,H,N,dk] bf16 in.
+ *   affine   : [4,H,dk] fp32 in, rows alpha_q, beta_q, alpha_k, beta_k: head h owns its dk-slice of the four
+ *              d-vectors; broadcast over batch and tokens.  Q and K are computed in fp32 and rounded to bf16 once,
+ *              as matrix-core operands.
+ *   forward  : O[b,h,t,:] = sum_{s<=t} (q_t . k_s) v_s.
+ *   backward : dZ = alpha_q * dQ + alpha_k * dK ([B,H,N,dk] bf16 out), dV as before, and
+ *              d_affine ([4,H,dk] fp32 out, overwritten) = (sum dQ*Z, sum dQ, sum dK*Z, sum dK), sums over batch and
+ *              tokens, accumulated in fp32 from the fp32 dQ, dK (deterministic: fixed summation order).
+ * The kernels use 64-token chunks; `chunk` is validated ({64, 128}) and otherwise ignored.  Scratch:
+ * chela_linattn_z_workspace_bytes().  With B*H*N = 0 nothing is done, except that d_affine is zeroed if H > 0.
+ * Everything else (pointers, alignment, aliasing, stream, errors) as for the calls above. */
+int chela_linattn_zfwd(const void *Z, const float *affine, const void *V, void *O,
+                       int B, int H, int N, int dk, int dv, int chunk, void *stream);
+int chela_linattn_zbwd(const void *Z, const float *affine, const void *V, const void *dO,
+                       void *dZ, float *d_affine, void *dV,
+                       int B, int H, int N, int dk, int dv, int chunk, void *stream);
+size_t chela_linattn_z_workspace_bytes(int B, int H, int N, int dk, int dv, int chunk, int is_bwd);
+
 /* One decode step of autoregressive inference (the recurrent form, one token per (b,h)):
  *     S += k v^T  (in place, fp32) ;  o = S^T q.
  * q, k: [B, H, dk] bf16; v, o: [B, H, dv] bf16; S: [B, H, dk, dv] fp32.  Needs no scratch. */

@@ -47,6 +47,12 @@ def lib() -> ctypes.CDLL:
     L.chela_linattn_fwd_state.restype = i
     L.chela_linattn_bwd_state.argtypes = [vp] * 10 + [i, i, i, i, i, i, vp]
     L.chela_linattn_bwd_state.restype = i
+    L.chela_linattn_zfwd.argtypes = [vp, vp, vp, vp, i, i, i, i, i, i, vp]
+    L.chela_linattn_zfwd.restype = i
+    L.chela_linattn_zbwd.argtypes = [vp] * 7 + [i, i, i, i, i, i, vp]
+    L.chela_linattn_zbwd.restype = i
+    L.chela_linattn_z_workspace_bytes.argtypes = [i, i, i, i, i, i, i]
+    L.chela_linattn_z_workspace_bytes.restype = sz
     L.chela_linattn_step.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, vp]
     L.chela_linattn_step.restype = i
     L.chela_linattn_workspace_bytes.argtypes = [i, i, i, i, i, i, i, i]
@@ -177,6 +183,48 @@ def chela_linattn_bwd_state(Q, K, V, dO, S_in=None, dS_out=None, chunk: int = 64
                                              dV.data_ptr(), dS_in.data_ptr(), B, H, N, dk, dv, int(chunk),
                                              _stream_ptr(stream)))
     return dQ, dK, dV, dS_in
+
+
+def _zdims(Z, affine, V):
+    if Z.dim() != 4 or V.dim() != 4 or V.shape[:3] != Z.shape[:3]:
+        raise ValueError("expected Z: [B,H,N,dk] and V: [B,H,N,dv]")
+    B, H, N, dk = Z.shape
+    for t in (Z, V):
+        if t.dtype != torch.bfloat16 or not t.is_cuda or not t.is_contiguous():
+            raise ValueError("Z and V must be contiguous bf16 device tensors")
+    if (affine.dtype != torch.float32 or tuple(affine.shape) != (4, H, dk) or not affine.is_cuda
+            or not affine.is_contiguous()):
+        raise ValueError("affine must be a contiguous float32 device tensor [4,H,dk]")
+    return B, H, N, dk, V.shape[3]
+
+
+def chela_linattn_zfwd(Z, affine, V, O=None, chunk: int = 64, stream=None):
+    """O for Q = affine[0]*Z + affine[1], K = affine[2]*Z + affine[3], formed on chip (Z is read once)."""
+    B, H, N, dk, dv = _zdims(Z, affine, V)
+    if O is None:
+        O = torch.empty((B, H, N, dv), dtype=Z.dtype, device=Z.device)
+    with torch.cuda.device(Z.device):
+        _check(lib().chela_linattn_zfwd(Z.data_ptr(), affine.data_ptr(), V.data_ptr(), O.data_ptr(), B, H, N, dk, dv,
+                                        int(chunk), _stream_ptr(stream)))
+    return O
+
+
+def chela_linattn_zbwd(Z, affine, V, dO, chunk: int = 64, stream=None):
+    """(dZ, d_affine, dV) of chela_linattn_zfwd for upstream gradient dO."""
+    B, H, N, dk, dv = _zdims(Z, affine, V)
+    if dO.shape != V.shape or dO.dtype != V.dtype or not dO.is_contiguous():
+        raise ValueError("dO must match V")
+    dZ, dV = torch.empty_like(Z), torch.empty_like(V)
+    d_aff = torch.empty_like(affine)
+    with torch.cuda.device(Z.device):
+        _check(lib().chela_linattn_zbwd(Z.data_ptr(), affine.data_ptr(), V.data_ptr(), dO.data_ptr(), dZ.data_ptr(),
+                                        d_aff.data_ptr(), dV.data_ptr(), B, H, N, dk, dv, int(chunk),
+                                        _stream_ptr(stream)))
+    return dZ, d_aff, dV
+
+
+def chela_linattn_z_workspace_bytes(B, H, N, dk, dv, chunk, is_bwd) -> int:
+    return int(lib().chela_linattn_z_workspace_bytes(B, H, N, dk, dv, chunk, int(bool(is_bwd))))
 
 
 def chela_linattn_step(q, k, v, S, o=None, stream=None):

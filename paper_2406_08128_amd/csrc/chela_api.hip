@@ -94,7 +94,7 @@ static std::vector<ProfRec> g_prof;          // records in use
 static std::vector<ProfRec> g_prof_free;     // event pairs to re-use
 static const char* const kKernelNames[KID_COUNT] = {
     "bf16_seg_state_kernel", "scan_states_kernel", "bf16_fwd_sweep_kernel", "bf16_bwd_sweep_kernel",
-    "f32_seg_state_kernel", "f32_sweep_kernel", "copy_probe_kernel", "bf16_step_kernel"};
+    "f32_seg_state_kernel", "f32_sweep_kernel", "copy_probe_kernel", "bf16_step_kernel", "affine_grad_kernel"};
 
 ProfScope::ProfScope(int id, hipStream_t s) : slot(-1), st(s)
 {
@@ -292,6 +292,54 @@ static int bwd_common(const void* Q, const void* K, const void* V, const void* d
     return e == hipSuccess ? CHELA_OK : CHELA_ERR_HIP;
 }
 
+// Eq. 11-12 variants.  The kernels tile with 64-token chunks whatever the (validated) hint says.
+static int zfwd_common(const void* Z, const float* aff, const void* V, void* O, int B, int H, int N, int dk, int dv,
+                       int chunk, void* stream)
+{
+    const size_t th = (B > 0 && H > 0 && N > 0) ? (size_t)B * H * N : 0;
+    const size_t ab = th ? (size_t)4 * H * dk * sizeof(float) : 0;
+    const void* in_v[3] = {Z, aff, V};
+    const size_t inb[3] = {th * dk * 2, ab, th * dv * 2};
+    void* out_v[1] = {O};
+    const size_t outb[1] = {th * dv * 2};
+    bool empty = false;
+    int rc = validate(in_v, inb, 3, out_v, outb, 1, B, H, N, dk, dv, chunk, CHELA_DTYPE_BF16, &empty);
+    if (rc != CHELA_OK || empty) return rc;
+    const long BH = (long)B * H;
+    Plan plan = make_plan(BH, N, dk, dv, 64, CHELA_DTYPE_BF16, false, false);
+    float* ws = nullptr;
+    rc = get_workspace(plan.ws_bytes, &ws);
+    if (rc != CHELA_OK) return rc;
+    return launch_bf16_zfwd(Z, aff, V, O, B, H, N, dk, dv, plan, ws, (hipStream_t)stream) == hipSuccess ? CHELA_OK
+                                                                                                         : CHELA_ERR_HIP;
+}
+
+static int zbwd_common(const void* Z, const float* aff, const void* V, const void* dO, void* dZ, float* d_aff,
+                       void* dV, int B, int H, int N, int dk, int dv, int chunk, void* stream)
+{
+    const size_t th = (B > 0 && H > 0 && N > 0) ? (size_t)B * H * N : 0;
+    const size_t ab = (H > 0) ? (size_t)4 * H * dk * sizeof(float) : 0;
+    const void* in_v[4] = {Z, aff, V, dO};
+    const size_t inb[4] = {th * dk * 2, th ? ab : 0, th * dv * 2, th * dv * 2};
+    void* out_v[3] = {dZ, d_aff, dV};
+    const size_t outb[3] = {th * dk * 2, th ? ab : 0, th * dv * 2};
+    bool empty = false;
+    int rc = validate(in_v, inb, 4, out_v, outb, 3, B, H, N, dk, dv, chunk, CHELA_DTYPE_BF16, &empty);
+    if (rc != CHELA_OK) return rc;
+    if (empty) {
+        // no tokens: the parameters received no gradient
+        if (d_aff && ab) return hipMemsetAsync(d_aff, 0, ab, (hipStream_t)stream) == hipSuccess ? CHELA_OK : CHELA_ERR_HIP;
+        return CHELA_OK;
+    }
+    const long BH = (long)B * H;
+    Plan plan = make_plan(BH, N, dk, dv, 64, CHELA_DTYPE_BF16, true, false);
+    float* ws = nullptr;
+    rc = get_workspace(plan.ws_bytes + zbwd_extra_ws_bytes(BH, plan, dk), &ws);
+    if (rc != CHELA_OK) return rc;
+    return launch_bf16_zbwd(Z, aff, V, dO, dZ, d_aff, dV, B, H, N, dk, dv, plan, ws, (hipStream_t)stream) == hipSuccess
+               ? CHELA_OK : CHELA_ERR_HIP;
+}
+
 }  // namespace chela
 
 using namespace chela;
@@ -333,6 +381,28 @@ int chela_linattn_bwd_state(const void* Q, const void* K, const void* V, const f
                             int dk, int dv, int chunk, void* stream)
 {
     return bwd_common(Q, K, V, dO, S_in, dS_out, dQ, dK, dV, dS_in, B, H, N, dk, dv, chunk, stream, CHELA_DTYPE_BF16);
+}
+
+int chela_linattn_zfwd(const void* Z, const float* affine, const void* V, void* O, int B, int H, int N, int dk,
+                       int dv, int chunk, void* stream)
+{
+    return zfwd_common(Z, affine, V, O, B, H, N, dk, dv, chunk, stream);
+}
+
+int chela_linattn_zbwd(const void* Z, const float* affine, const void* V, const void* dO, void* dZ, float* d_affine,
+                       void* dV, int B, int H, int N, int dk, int dv, int chunk, void* stream)
+{
+    return zbwd_common(Z, affine, V, dO, dZ, d_affine, dV, B, H, N, dk, dv, chunk, stream);
+}
+
+size_t chela_linattn_z_workspace_bytes(int B, int H, int N, int dk, int dv, int chunk, int is_bwd)
+{
+    if (B <= 0 || H <= 0 || N <= 0) return 0;
+    if (!((dk == 64 || dk == 128) && (dv == 64 || dv == 128))) return 0;
+    if (!(chunk == 64 || chunk == 128)) return 0;
+    const long BH = (long)B * H;
+    Plan plan = make_plan(BH, N, dk, dv, 64, CHELA_DTYPE_BF16, is_bwd != 0, false);
+    return plan.ws_bytes + (is_bwd ? zbwd_extra_ws_bytes(BH, plan, dk) : 0);
 }
 
 int chela_linattn_step(const void* q, const void* k, const void* v, float* S, void* o, int B, int H, int dk, int dv,

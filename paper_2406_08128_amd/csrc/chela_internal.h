@@ -43,12 +43,22 @@ hipError_t launch_bf16_fwd(const void* Q, const void* K, const void* V, void* O,
 hipError_t launch_bf16_bwd(const void* Q, const void* K, const void* V, const void* dO, const float* S_in,
                            const float* dS_out, void* dQ, void* dK, void* dV, float* dS_in, long BH, int N, int dk,
                            int dv, const Plan& plan, float* ws, hipStream_t st);
+// Eq. 11-12 variants: Z [BH][N][dk] stands in for Q and K, aff = [4][H][dk] fp32 (alpha_q, beta_q, alpha_k, beta_k).
+// plan.chunk must be 64.  The backward needs zbwd_extra_ws_bytes() of workspace behind plan.ws_bytes.
+hipError_t launch_bf16_zfwd(const void* Z, const float* aff, const void* V, void* O, int B, int H, int N, int dk,
+                            int dv, const Plan& plan, float* ws, hipStream_t st);
+hipError_t launch_bf16_zbwd(const void* Z, const float* aff, const void* V, const void* dO, void* dZ, float* d_aff,
+                            void* dV, int B, int H, int N, int dk, int dv, const Plan& plan, float* ws, hipStream_t st);
+inline size_t zbwd_extra_ws_bytes(long BH, const Plan& plan, int dk)
+{
+    return (size_t)BH * plan.n_seg * 4 * dk * sizeof(float);
+}
 hipError_t launch_bf16_step(const void* q, const void* k, const void* v, float* S, void* o, long BH, int dk, int dv,
                             hipStream_t st);
 
 // Kernel classes for the per-kernel timing aid.
 enum { KID_SEG_STATE_BF16 = 0, KID_SCAN = 1, KID_FWD_SWEEP_BF16 = 2, KID_BWD_SWEEP_BF16 = 3, KID_SEG_STATE_F32 = 4,
-       KID_SWEEP_F32 = 5, KID_COPY = 6, KID_STEP_BF16 = 7, KID_COUNT = 8 };
+       KID_SWEEP_F32 = 5, KID_COPY = 6, KID_STEP_BF16 = 7, KID_AFFINE_GRAD = 8, KID_COUNT = 9 };
 
 // Brackets one kernel launch with HIP events on its stream while profiling is enabled; otherwise does nothing.
 struct ProfScope {

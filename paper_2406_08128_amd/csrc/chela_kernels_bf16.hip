@@ -135,6 +135,30 @@ __device__ __forceinline__ void cvt_tile_masked(const f32x16& p, const unsigned 
     a1 = __builtin_bit_cast(bf16x8, hi);
 }
 
+// Eq. 11-12: queries and keys are per-feature affine maps of one tensor Z.  Eight consecutive features of one
+// map, kept in registers: apply() turns 8 bf16 z into 8 bf16 (alpha * z + beta).
+__device__ __forceinline__ float bf16_lo(unsigned u) { return __builtin_bit_cast(float, u << 16); }
+__device__ __forceinline__ float bf16_hi(unsigned u) { return __builtin_bit_cast(float, u & 0xffff0000u); }
+
+struct AffineCols {
+    float a[8], b[8];
+    __device__ __forceinline__ AffineCols(const float* alpha, const float* beta, int col0)
+    {
+        const float4 a0 = *reinterpret_cast<const float4*>(alpha + col0), a1 = *reinterpret_cast<const float4*>(alpha + col0 + 4);
+        const float4 b0 = *reinterpret_cast<const float4*>(beta + col0), b1 = *reinterpret_cast<const float4*>(beta + col0 + 4);
+        a[0] = a0.x; a[1] = a0.y; a[2] = a0.z; a[3] = a0.w; a[4] = a1.x; a[5] = a1.y; a[6] = a1.z; a[7] = a1.w;
+        b[0] = b0.x; b[1] = b0.y; b[2] = b0.z; b[3] = b0.w; b[4] = b1.x; b[5] = b1.y; b[6] = b1.z; b[7] = b1.w;
+    }
+    __device__ __forceinline__ unsigned two(unsigned z, int c) const
+    {
+        return pack2(fmaf(a[c], bf16_lo(z), b[c]), fmaf(a[c + 1], bf16_hi(z), b[c + 1]));
+    }
+    __device__ __forceinline__ uint4 apply(uint4 z) const
+    {
+        return make_uint4(two(z.x, 0), two(z.y, 2), two(z.z, 4), two(z.w, 6));
+    }
+};
+
 // A C x D bf16 tile (C consecutive rows of a row-major [N][D] matrix, i.e. one contiguous block of memory) travels
 // HBM -> registers (16-byte vectors, NV per thread) -> LDS (row stride D + PAD).
 template <int C, int D>
@@ -164,6 +188,17 @@ struct TileRegs {
         for (int n = 0; n < NV; ++n) {
             const int x = tid + 256 * n, row = x / VPR, cv = x % VPR;
             *reinterpret_cast<uint4*>(lds + row * (D + PAD) + cv * 8) = v[n];
+        }
+    }
+    // The tile holds Z; write alpha * Z + beta (per feature, fp32 arithmetic, rounded once to bf16) instead.
+    // A thread's vectors all sit in the same 8 columns because 256 is a multiple of VPR.
+    __device__ __forceinline__ void store_affine(bf16* lds, const float* alpha, const float* beta, int tid) const
+    {
+        const AffineCols ac(alpha, beta, (tid % VPR) * 8);
+#pragma unroll
+        for (int n = 0; n < NV; ++n) {
+            const int x = tid + 256 * n, row = x / VPR, cv = x % VPR;
+            *reinterpret_cast<uint4*>(lds + row * (D + PAD) + cv * 8) = ac.apply(v[n]);
         }
     }
 };
@@ -261,22 +296,28 @@ __device__ __forceinline__ void store_state_T(float* dst, const f32x16* acc, int
 // =============================================================================================== pre-pass body
 // out[a][b] = sum over `ntok` tokens s of X[s][a] * Y[s][b]   (fp32, [DA][DB] row-major).  One workgroup; wave w owns
 // output tiles w, w+4, ...  LDS: 64 x (DA + PAD) + 64 x (DB + PAD) bf16.
-template <int DA, int DB>
+// AFF = 1 (2): the X (Y) tensor is Z and the operand is alpha * Z + beta (Eq. 11-12), alpha and beta being this
+// head's DA (DB) floats.
+template <int DA, int DB, int AFF = 0>
 struct PrepassLds {
     static constexpr int R = 64;
-    static constexpr int BYTES = (R * (DA + PAD) + R * (DB + PAD)) * 2;
+    static constexpr int TILES = (R * (DA + PAD) + R * (DB + PAD)) * 2;
+    static constexpr int BYTES = TILES + (AFF == 1 ? 2 * DA * 4 : AFF == 2 ? 2 * DB * 4 : 0);
 };
 
-template <int DA, int DB>
+template <int DA, int DB, int AFF>
 __device__ __forceinline__ void prepass_body(const bf16* __restrict__ X, const bf16* __restrict__ Y,
-                                             float* __restrict__ out, int ntok, unsigned char* lds, int tid, int w,
-                                             int lane)
+                                             float* __restrict__ out, const float* __restrict__ alpha,
+                                             const float* __restrict__ beta, int ntok, unsigned char* lds, int tid,
+                                             int w, int lane)
 {
     constexpr int R = 64;
     constexpr int PF = 2;          // 64-token blocks in flight per workgroup: this kernel only reads, so it lives
                                    // off memory-level parallelism
     bf16* sX = reinterpret_cast<bf16*>(lds);
     bf16* sY = sX + R * (DA + PAD);
+    float* sAff = reinterpret_cast<float*>(lds + PrepassLds<DA, DB, 0>::TILES);
+    constexpr int DAFF = AFF == 1 ? DA : DB;
     constexpr int BB = DB / 32, NT = (DA / 32) * BB / 4;
     f32x16 acc[NT];
 #pragma unroll
@@ -289,13 +330,19 @@ __device__ __forceinline__ void prepass_body(const bf16* __restrict__ X, const b
             rx[u].load(X + (size_t)(u * R) * DA, ntok - u * R, tid);
             ry[u].load(Y + (size_t)(u * R) * DB, ntok - u * R, tid);
         }
+    if (AFF != 0) {
+        if (tid < DAFF) { sAff[tid] = alpha[tid]; sAff[DAFF + tid] = beta[tid]; }
+        __syncthreads();
+    }
     for (int c0 = 0; c0 < ntok; c0 += PF * R) {
 #pragma unroll
         for (int u = 0; u < PF; ++u) {
             const int c = c0 + u * R;
             if (c < ntok) {
-                rx[u].store(sX, tid);
-                ry[u].store(sY, tid);
+                if (AFF == 1) rx[u].store_affine(sX, sAff, sAff + DAFF, tid);
+                else rx[u].store(sX, tid);
+                if (AFF == 2) ry[u].store_affine(sY, sAff, sAff + DAFF, tid);
+                else ry[u].store(sY, tid);
                 __syncthreads();
                 if (c + PF * R < ntok) {
                     rx[u].load(X + (size_t)(c + PF * R) * DA, ntok - c - PF * R, tid);
@@ -330,16 +377,20 @@ __device__ __forceinline__ void prepass_body(const bf16* __restrict__ X, const b
 //   P^T = K Q^T (masked), O^T = V^T P^T + S_prev^T Q^T, store O, S += K^T V.
 // Wave w owns output rows [32*tb, 32*tb+32) with tb = w % WT and NJ column tiles; it recomputes the score
 // tiles of its row block itself (matrix-core time is cheap here, LDS round trips and barriers are not).
-template <int C, int DK, int DV>
+// ZQK: Qb points at Z, Kb is unused, and `aff` at this head's alpha_q row of the [4][H][DK] parameter array
+// (rows alpha_q, beta_q, alpha_k, beta_k, `aff_stride` floats apart): Q and K tiles are formed on the way into LDS.
+template <int C, int DK, int DV, bool ZQK = false>
 struct FwdLds {
     static constexpr int LDK = DK + PAD, LDV = DV + PAD;
-    static constexpr int BYTES = (2 * C * LDK + C * LDV + DV * LDK) * 2;
+    static constexpr int TILES = (2 * C * LDK + C * LDV + DV * LDK) * 2;
+    static constexpr int BYTES = TILES + (ZQK ? 4 * DK * 4 : 0);
 };
 
-template <int C, int DK, int DV>
+template <int C, int DK, int DV, bool ZQK>
 __device__ __forceinline__ void fwd_sweep_body(const bf16* __restrict__ Qb, const bf16* __restrict__ Kb,
                                                const bf16* __restrict__ Vb, bf16* __restrict__ Ob,
-                                               const float* __restrict__ S0, float* __restrict__ S_final, int ntok,
+                                               const float* __restrict__ S0, float* __restrict__ S_final,
+                                               const float* __restrict__ aff, size_t aff_stride, int ntok,
                                                unsigned char* lds, int tid, int w, int lane)
 {
     constexpr int LDK = DK + PAD, LDV = DV + PAD;
@@ -356,25 +407,35 @@ __device__ __forceinline__ void fwd_sweep_body(const bf16* __restrict__ Qb, cons
     unsigned maskK[8];
     make_masks<true>(maskK, lane);
 
-    TileRegs<C, DK> rq, rk;
+    TileRegs<C, DK> rq, rk;   // with ZQK only rq is used: it holds Z
     TileRegs<C, DV> rv;
     rq.load(Qb, ntok, tid);
-    rk.load(Kb, ntok, tid);
+    if (!ZQK) rk.load(Kb, ntok, tid);
     rv.load(Vb, ntok, tid);
+    float* sAff = reinterpret_cast<float*>(lds + FwdLds<C, DK, DV, false>::TILES);
+    if (ZQK) {
+        for (int x = tid; x < 4 * DK; x += 256) sAff[x] = aff[(size_t)(x / DK) * aff_stride + x % DK];
+        __syncthreads();
+    }
 
     f32x16 accS[NS];
     load_state<DK, DV, false>(accS, S0, w, lane);
 
     for (int c0 = 0; c0 < ntok; c0 += C) {
-        rq.store(sQ, tid);
-        rk.store(sK, tid);
+        if (ZQK) {
+            rq.store_affine(sQ, sAff, sAff + DK, tid);
+            rq.store_affine(sK, sAff + 2 * DK, sAff + 3 * DK, tid);
+        } else {
+            rq.store(sQ, tid);
+            rk.store(sK, tid);
+        }
         rv.store(sV, tid);
         state_to_lds_T<DK, DV, false>(sST, accS, w, lane);
         __syncthreads();
         const bool more = c0 + C < ntok;
         if (more) {
             rq.load(Qb + (size_t)(c0 + C) * DK, ntok - c0 - C, tid);
-            rk.load(Kb + (size_t)(c0 + C) * DK, ntok - c0 - C, tid);
+            if (!ZQK) rk.load(Kb + (size_t)(c0 + C) * DK, ntok - c0 - C, tid);
             rv.load(Vb + (size_t)(c0 + C) * DV, ntok - c0 - C, tid);
         }
         bf16x8 bQ[DK / 16];   // Q rows of this wave's token block: the B operand (n = token, k = feature i)
@@ -439,19 +500,43 @@ __device__ __forceinline__ void fwd_sweep_body(const bf16* __restrict__ Qb, cons
 //             P = (Q K^T) o M,  dP = (dO V^T) o M, every output accumulated transposed.
 // Send == nullptr means the whole sequence is this one segment: S is then built here, R starts at zero.
 // R_final, if given, receives the state R after the segment's first chunk has been added ([dk][dv], fp32).
-template <int C, int DK, int DV>
+//
+// ZQK (Eq. 11-12, Q = alpha_q Z + beta_q, K = alpha_k Z + beta_k): Qb points at Z, Kb is unused, dQb receives
+// dZ = alpha_q dQ + alpha_k dK and dKb is unused.  The parameter gradients are sums over tokens,
+//   d_alpha_q = sum dQ * Z, d_beta_q = sum dQ, d_alpha_k = sum dK * Z, d_beta_k = sum dK;
+// each workgroup writes its share of the four as [4][DK] floats to `part`, a later kernel adds the shares up.
+template <int C, int DK, int DV, bool ZQK = false>
 struct BwdLds {
     static constexpr int LDK = DK + PAD, LDV = DV + PAD;
-    static constexpr int BYTES = (2 * C * LDK + 2 * C * LDV + 2 * DK * LDV) * 2;
+    static constexpr int TILES = (2 * C * LDK + 2 * C * LDV + 2 * DK * LDV) * 2;
+    static constexpr int BYTES = TILES + (ZQK ? C * LDK * 2 + 4 * DK * 4 : 0);
 };
 
-template <int C, int DK, int DV>
+// x holds, per lane, 16 values of one token (the token is lane % 32).  Returns the sum over the 32 tokens of a wave
+// half of ONE of them: value index 8*b16 + 4*b8 + 2*b4 + b2, b_m = bit m of the lane number.  Each exchange step
+// halves the number of live values, so the whole reduction costs 16 lane exchanges instead of 80.
+__device__ __forceinline__ float sum_tokens16(const f32x16& x, int lane)
+{
+    float y8[8], y4[4], y2[2];
+    const bool u16 = lane & 16, u8 = lane & 8, u4 = lane & 4, u2 = lane & 2;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) y8[j] = (u16 ? x[j + 8] : x[j]) + __shfl_xor(u16 ? x[j] : x[j + 8], 16);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) y4[j] = (u8 ? y8[j + 4] : y8[j]) + __shfl_xor(u8 ? y8[j] : y8[j + 4], 8);
+#pragma unroll
+    for (int j = 0; j < 2; ++j) y2[j] = (u4 ? y4[j + 2] : y4[j]) + __shfl_xor(u4 ? y4[j] : y4[j + 2], 4);
+    float y = (u2 ? y2[1] : y2[0]) + __shfl_xor(u2 ? y2[0] : y2[1], 2);
+    return y + __shfl_xor(y, 1);
+}
+
+template <int C, int DK, int DV, bool ZQK>
 __device__ __forceinline__ void bwd_sweep_body(const bf16* __restrict__ Qb, const bf16* __restrict__ Kb,
                                                const bf16* __restrict__ Vb, const bf16* __restrict__ Gb,
                                                bf16* __restrict__ dQb, bf16* __restrict__ dKb, bf16* __restrict__ dVb,
                                                const float* __restrict__ Send, const float* __restrict__ Rnext,
-                                               float* __restrict__ R_final, int ntok, unsigned char* lds, int tid,
-                                               int w, int lane)
+                                               float* __restrict__ R_final, const float* __restrict__ aff,
+                                               size_t aff_stride, float* __restrict__ part, int ntok,
+                                               unsigned char* lds, int tid, int w, int lane)
 {
     constexpr int LDK = DK + PAD, LDV = DV + PAD;
     constexpr int TB = C / 32, JB = DV / 32, IB = DK / 32;
@@ -471,9 +556,20 @@ __device__ __forceinline__ void bwd_sweep_body(const bf16* __restrict__ Qb, cons
     make_masks<true>(maskK, lane);
     make_masks<false>(maskQ, lane);
 
-    TileRegs<C, DK> rq, rk;
+    TileRegs<C, DK> rq, rk;            // with ZQK only rq is used in the main loop: it holds Z
     TileRegs<C, DV> rv, rg;
     f32x16 accNS[NS], accRT[NS];       // states, transposed: [DV][DK]; accNS holds MINUS S^T
+    bf16* sZ = reinterpret_cast<bf16*>(lds + BwdLds<C, DK, DV, false>::TILES);
+    float* sAff = reinterpret_cast<float*>(sZ + C * LDK);
+    float pg[4][NI];                   // this lane's running share of the four parameter gradients
+    if (ZQK) {
+        for (int x = tid; x < 4 * DK; x += 256) sAff[x] = aff[(size_t)(x / DK) * aff_stride + x % DK];
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int n = 0; n < NI; ++n) pg[q][n] = 0.f;
+        __syncthreads();
+    }
 
     if (Send == nullptr) {
         // single segment: no pre-pass ran, build -S^T = -sum V^T K over the whole sequence here
@@ -481,10 +577,11 @@ __device__ __forceinline__ void bwd_sweep_body(const bf16* __restrict__ Qb, cons
         for (int n = 0; n < NS; ++n) { accNS[n] = zero16(); accRT[n] = zero16(); }
         for (int ci = 0; ci < n_ch; ++ci) {
             const int c0 = ci * C;
-            rk.load(Kb + (size_t)c0 * DK, ntok - c0, tid);
+            rk.load((ZQK ? Qb : Kb) + (size_t)c0 * DK, ntok - c0, tid);
             rv.load(Vb + (size_t)c0 * DV, ntok - c0, tid);
             __syncthreads();
-            rk.store(sK, tid);
+            if (ZQK) rk.store_affine(sK, sAff + 2 * DK, sAff + 3 * DK, tid);
+            else rk.store(sK, tid);
             rv.store(sV, tid);
             __syncthreads();
 #pragma unroll
@@ -504,7 +601,7 @@ __device__ __forceinline__ void bwd_sweep_body(const bf16* __restrict__ Qb, cons
     {
         const int c0 = (n_ch - 1) * C;
         rq.load(Qb + (size_t)c0 * DK, ntok - c0, tid);
-        rk.load(Kb + (size_t)c0 * DK, ntok - c0, tid);
+        if (!ZQK) rk.load(Kb + (size_t)c0 * DK, ntok - c0, tid);
         rv.load(Vb + (size_t)c0 * DV, ntok - c0, tid);
         rg.load(Gb + (size_t)c0 * DV, ntok - c0, tid);
     }
@@ -515,8 +612,14 @@ __device__ __forceinline__ void bwd_sweep_body(const bf16* __restrict__ Qb, cons
 
     for (int ci = n_ch - 1; ci >= 0; --ci) {
         const int c0 = ci * C;
-        rq.store(sQ, tid);
-        rk.store(sK, tid);
+        if (ZQK) {
+            rq.store_affine(sQ, sAff, sAff + DK, tid);
+            rq.store_affine(sK, sAff + 2 * DK, sAff + 3 * DK, tid);
+            rq.store(sZ, tid);
+        } else {
+            rq.store(sQ, tid);
+            rk.store(sK, tid);
+        }
         rv.store(sV, tid);
         rg.store(sG, tid);
         // R (state after this chunk) is already final: publish it as bf16 [i][j]
@@ -524,7 +627,7 @@ __device__ __forceinline__ void bwd_sweep_body(const bf16* __restrict__ Qb, cons
         __syncthreads();
         if (ci > 0) {   // every chunk but a segment's last is complete
             rq.load(Qb + (size_t)(c0 - C) * DK, C, tid);
-            rk.load(Kb + (size_t)(c0 - C) * DK, C, tid);
+            if (!ZQK) rk.load(Kb + (size_t)(c0 - C) * DK, C, tid);
             rv.load(Vb + (size_t)(c0 - C) * DV, C, tid);
             rg.load(Gb + (size_t)(c0 - C) * DV, C, tid);
         }
@@ -541,11 +644,12 @@ __device__ __forceinline__ void bwd_sweep_body(const bf16* __restrict__ Qb, cons
 
         const int valid = ntok - (c0 + rb * 32);   // rows of this wave's 32-token block that exist
         // ---------------- dQ^T for token block tb = rb:  dQ^T = K^T dP^T + S dO^T
+        f32x16 accQ[NI];
         {
+            f32x16 (&acc)[NI] = accQ;
             bf16x8 bG[DV / 16];
 #pragma unroll
             for (int kk = 0; kk < DV / 16; ++kk) bG[kk] = ld_nat(sG, LDV, rb * 32, kk * 16, lane);
-            f32x16 acc[NI];
 #pragma unroll
             for (int n = 0; n < NI; ++n) acc[n] = zero16();
 #pragma unroll
@@ -569,9 +673,11 @@ __device__ __forceinline__ void bwd_sweep_body(const bf16* __restrict__ Qb, cons
                     }
                 }
             }
-            bf16* rows = dQb + (size_t)(c0 + rb * 32) * DK;
+            if (!ZQK) {
+                bf16* rows = dQb + (size_t)(c0 + rb * 32) * DK;
 #pragma unroll
-            for (int n = 0; n < NI; ++n) store_tile_T(rows, DK, (cg * NI + n) * 32, acc[n], valid, lane);
+                for (int n = 0; n < NI; ++n) store_tile_T(rows, DK, (cg * NI + n) * 32, acc[n], valid, lane);
+            }
         }
         // ---------------- dK^T for key block sb = rb:  dK^T = Q^T dP + R V^T
         {
@@ -602,9 +708,41 @@ __device__ __forceinline__ void bwd_sweep_body(const bf16* __restrict__ Qb, cons
                     }
                 }
             }
-            bf16* rows = dKb + (size_t)(c0 + rb * 32) * DK;
+            if (!ZQK) {
+                bf16* rows = dKb + (size_t)(c0 + rb * 32) * DK;
 #pragma unroll
-            for (int n = 0; n < NI; ++n) store_tile_T(rows, DK, (cg * NI + n) * 32, acc[n], valid, lane);
+                for (int n = 0; n < NI; ++n) store_tile_T(rows, DK, (cg * NI + n) * 32, acc[n], valid, lane);
+            } else {
+                // dZ = alpha_q dQ + alpha_k dK; the lane owns features f0 + 8a + 4h + b of token rb*32 + r
+                const int r = lane & 31, h = lane >> 5;
+                bf16* rows = dQb + (size_t)(c0 + rb * 32) * DK;
+#pragma unroll
+                for (int n = 0; n < NI; ++n) {
+                    const int f0 = (cg * NI + n) * 32;
+                    f32x16 dz, qz, kz;
+#pragma unroll
+                    for (int a = 0; a < 4; ++a) {
+                        const int f = f0 + 8 * a + 4 * h;
+                        const u32x2 zz = *reinterpret_cast<const u32x2*>(sZ + (rb * 32 + r) * LDK + f);
+                        const float z[4] = {bf16_lo(zz[0]), bf16_hi(zz[0]), bf16_lo(zz[1]), bf16_hi(zz[1])};
+                        const float4 aq = *reinterpret_cast<const float4*>(sAff + f);
+                        const float4 ak = *reinterpret_cast<const float4*>(sAff + 2 * DK + f);
+                        const float aqv[4] = {aq.x, aq.y, aq.z, aq.w}, akv[4] = {ak.x, ak.y, ak.z, ak.w};
+#pragma unroll
+                        for (int b = 0; b < 4; ++b) {
+                            const int e = 4 * a + b;
+                            dz[e] = fmaf(aqv[b], accQ[n][e], akv[b] * acc[n][e]);
+                            qz[e] = accQ[n][e] * z[b];
+                            kz[e] = acc[n][e] * z[b];
+                        }
+                    }
+                    store_tile_T(rows, DK, f0, dz, valid, lane);
+                    pg[0][n] += sum_tokens16(qz, lane);
+                    pg[1][n] += sum_tokens16(accQ[n], lane);
+                    pg[2][n] += sum_tokens16(kz, lane);
+                    pg[3][n] += sum_tokens16(acc[n], lane);
+                }
+            }
         }
         // ---------------- dV^T for key block sb = rb:  dV^T = dO^T P + R^T K^T
         {
@@ -652,6 +790,28 @@ __device__ __forceinline__ void bwd_sweep_body(const bf16* __restrict__ Qb, cons
         __syncthreads();
     }
     if (R_final != nullptr) store_state_T<DV, DK>(R_final, accRT, w, lane);
+    if (ZQK) {
+        // The loop's last barrier has passed: the tile area is free.  Even lanes hold the sums (odd ones a copy) of
+        // feature 32*(cg*NI+n) + 8*(e/4) + 4*h + e%4 with e = 8*b16 + 4*b8 + 2*b4 + b2; the WT waves that share
+        // a column group each cover their own tokens, so their shares are added up here.
+        float* sP = reinterpret_cast<float*>(lds);          // [WT][4][DK]
+        const int r = lane & 31, h = lane >> 5;
+        const int e = ((r >> 4) & 1) * 8 + ((r >> 3) & 1) * 4 + ((r >> 2) & 1) * 2 + ((r >> 1) & 1);
+        if ((r & 1) == 0) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int n = 0; n < NI; ++n)
+                    sP[(rb * 4 + q) * DK + (cg * NI + n) * 32 + 8 * (e >> 2) + 4 * h + (e & 3)] = pg[q][n];
+        }
+        __syncthreads();
+        for (int x = tid; x < 4 * DK; x += 256) {
+            float t = 0.f;
+#pragma unroll
+            for (int v = 0; v < WT; ++v) t += sP[v * 4 * DK + x];
+            part[x] = t;
+        }
+    }
 }
 
 // =============================================================================================== kernels
@@ -660,29 +820,40 @@ struct SegStateArgs {
     const bf16* Y[2];
     float* out[2];
     int skip_seg[2];   // a segment whose total the scan never uses (-1: none)
+    // AFF != 0: per pair, the [H][D] rows of alpha and beta that map Z to the affine operand
+    const float* alpha[2];
+    const float* beta[2];
+    int H;
 };
 
-template <int DA, int DB>
+template <int DA, int DB, int AFF>
 __global__ __launch_bounds__(256) void bf16_seg_state_kernel(SegStateArgs args, int N, int seg_len, int n_seg)
 {
-    __shared__ __attribute__((aligned(16))) unsigned char lds[PrepassLds<DA, DB>::BYTES];
+    __shared__ __attribute__((aligned(16))) unsigned char lds[PrepassLds<DA, DB, AFF>::BYTES];
     const int z = blockIdx.z, seg = blockIdx.y;   // heads on grid.x: its limit is 2^31-1, the others' 65535
     const long bh = blockIdx.x;
     if (seg == args.skip_seg[z]) return;
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int p0 = seg * seg_len, p1 = min(N, p0 + seg_len);
-    prepass_body<DA, DB>(args.X[z] + ((size_t)bh * N + p0) * DA, args.Y[z] + ((size_t)bh * N + p0) * DB,
-                                args.out[z] + ((size_t)bh * n_seg + seg) * DA * DB, p1 - p0, lds, tid, w, lane);
+    const float *al = nullptr, *be = nullptr;
+    if (AFF != 0) {
+        const size_t hoff = (size_t)(bh % args.H) * (AFF == 1 ? DA : DB);
+        al = args.alpha[z] + hoff;
+        be = args.beta[z] + hoff;
+    }
+    prepass_body<DA, DB, AFF>(args.X[z] + ((size_t)bh * N + p0) * DA, args.Y[z] + ((size_t)bh * N + p0) * DB,
+                              args.out[z] + ((size_t)bh * n_seg + seg) * DA * DB, al, be, p1 - p0, lds, tid, w, lane);
 }
 
-template <int C, int DK, int DV>
+template <int C, int DK, int DV, bool ZQK>
 __global__ __launch_bounds__(256) void bf16_fwd_sweep_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K,
                                                             const bf16* __restrict__ V, bf16* __restrict__ O,
                                                             const float* __restrict__ S0, float* __restrict__ S_out,
+                                                            const float* __restrict__ aff, int H,
                                                             int first_loads_state, int N, int seg_len, int n_seg)
 {
-    __shared__ __attribute__((aligned(16))) unsigned char lds[FwdLds<C, DK, DV>::BYTES];
+    __shared__ __attribute__((aligned(16))) unsigned char lds[FwdLds<C, DK, DV, ZQK>::BYTES];
     const int seg = blockIdx.y;
     const long bh = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63;
@@ -692,21 +863,23 @@ __global__ __launch_bounds__(256) void bf16_fwd_sweep_kernel(const bf16* __restr
     // S0: scanned start states (segment 0's slot holds the carried-in state, read only if there is one);
     // S_out: final state of the whole sequence, written by the last segment's workgroup
     const bool has_state = S0 != nullptr && (seg > 0 || first_loads_state);
-    fwd_sweep_body<C, DK, DV>(Q + rk, K + rk, V + rv, O + rv,
-                              has_state ? S0 + ((size_t)bh * n_seg + seg) * DK * DV : nullptr,
-                              (S_out != nullptr && seg == n_seg - 1) ? S_out + (size_t)bh * DK * DV : nullptr, p1 - p0,
-                              lds, tid, w, lane);
+    fwd_sweep_body<C, DK, DV, ZQK>(Q + rk, ZQK ? nullptr : K + rk, V + rv, O + rv,
+                                   has_state ? S0 + ((size_t)bh * n_seg + seg) * DK * DV : nullptr,
+                                   (S_out != nullptr && seg == n_seg - 1) ? S_out + (size_t)bh * DK * DV : nullptr,
+                                   ZQK ? aff + (size_t)(bh % H) * DK : nullptr, (size_t)H * DK, p1 - p0, lds, tid, w,
+                                   lane);
 }
 
-template <int C, int DK, int DV>
+template <int C, int DK, int DV, bool ZQK>
 __global__ __launch_bounds__(256) void bf16_bwd_sweep_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K,
                                                             const bf16* __restrict__ V, const bf16* __restrict__ dO,
                                                             bf16* __restrict__ dQ, bf16* __restrict__ dK,
                                                             bf16* __restrict__ dV, const float* __restrict__ Send,
                                                             const float* __restrict__ Rnext, float* __restrict__ dS_in,
-                                                            int N, int seg_len, int n_seg)
+                                                            const float* __restrict__ aff, int H,
+                                                            float* __restrict__ part, int N, int seg_len, int n_seg)
 {
-    __shared__ __attribute__((aligned(16))) unsigned char lds[BwdLds<C, DK, DV>::BYTES];
+    __shared__ __attribute__((aligned(16))) unsigned char lds[BwdLds<C, DK, DV, ZQK>::BYTES];
     const int seg = blockIdx.y;
     const long bh = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63;
@@ -716,10 +889,37 @@ __global__ __launch_bounds__(256) void bf16_bwd_sweep_kernel(const bf16* __restr
     const size_t soff = ((size_t)bh * n_seg + seg) * DK * DV;
     // the scan leaves zeros in the last segment's R slot, so Rnext can be read for every segment
     // dS_in: gradient with respect to the carried-in state = R after the very first chunk (segment 0's workgroup)
-    bwd_sweep_body<C, DK, DV>(Q + rk, K + rk, V + rv, dO + rv, dQ + rk, dK + rk, dV + rv,
-                              Send ? Send + soff : nullptr, Rnext ? Rnext + soff : nullptr,
-                              (dS_in != nullptr && seg == 0) ? dS_in + (size_t)bh * DK * DV : nullptr, p1 - p0, lds, tid,
-                              w, lane);
+    bwd_sweep_body<C, DK, DV, ZQK>(Q + rk, ZQK ? nullptr : K + rk, V + rv, dO + rv, dQ + rk, ZQK ? nullptr : dK + rk,
+                                   dV + rv, Send ? Send + soff : nullptr, Rnext ? Rnext + soff : nullptr,
+                                   (dS_in != nullptr && seg == 0) ? dS_in + (size_t)bh * DK * DV : nullptr,
+                                   ZQK ? aff + (size_t)(bh % H) * DK : nullptr, (size_t)H * DK,
+                                   ZQK ? part + ((size_t)bh * n_seg + seg) * 4 * DK : nullptr, p1 - p0, lds, tid, w,
+                                   lane);
+}
+
+// Adds up the workgroups' shares of the parameter gradients: part is [B][H][n_seg][4][DK], out is [4][H][DK].
+// One workgroup per (head, quantity); thread = (slice of the B * n_seg shares, feature).
+template <int DK>
+__global__ __launch_bounds__(256) void affine_grad_kernel(const float* __restrict__ part, float* __restrict__ out,
+                                                         int B, int H, int n_seg)
+{
+    constexpr int SL = 256 / DK;
+    __shared__ float red[SL][DK];
+    const int hq = blockIdx.x, hd = hq / 4, q = hq % 4;
+    const int i = threadIdx.x % DK, sl = threadIdx.x / DK;
+    const long n_sh = (long)B * n_seg;
+    float t = 0.f;
+    for (long x = sl; x < n_sh; x += SL) {
+        const long b = x / n_seg, seg = x % n_seg;
+        t += part[((((size_t)b * H + hd) * n_seg + seg) * 4 + q) * DK + i];
+    }
+    red[sl][i] = t;
+    __syncthreads();
+    if (sl == 0) {
+#pragma unroll
+        for (int v = 1; v < SL; ++v) t += red[v][i];
+        out[((size_t)q * H + hd) * DK + i] = t;
+    }
 }
 
 // =============================================================================================== decode step
@@ -771,7 +971,7 @@ hipError_t launch_bf16_step(const void* q, const void* k, const void* v, float* 
 
 // =============================================================================================== launchers
 // Pre-pass + scan over segments.  init[z] (optional, [dk][dv] fp32 per head) seeds the scan of array z.
-template <int DA, int DB>
+template <int DA, int DB, int AFF = 0>
 static hipError_t run_seg_state(const SegStateArgs& a, int npairs, const int* scan_modes, const float* const* init,
                                 bool init_transposed, long BH, int N, const Plan& plan, hipStream_t st)
 {
@@ -779,60 +979,79 @@ static hipError_t run_seg_state(const SegStateArgs& a, int npairs, const int* sc
     {
         dim3 grid((unsigned)BH, plan.n_seg, npairs);
         ProfScope prof(KID_SEG_STATE_BF16, st);
-        hipLaunchKernelGGL((bf16_seg_state_kernel<DA, DB>), grid, dim3(256), 0, st, a, N, plan.seg_len, plan.n_seg);
+        hipLaunchKernelGGL((bf16_seg_state_kernel<DA, DB, AFF>), grid, dim3(256), 0, st, a, N, plan.seg_len, plan.n_seg);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     const size_t stride = npairs > 1 ? (size_t)(a.out[1] - a.out[0]) : 0;
     return scan_states(a.out[0], stride, npairs, scan_modes, init, init_transposed ? DB : 0, BH, plan.n_seg, DA * DB, st);
 }
 
-// `stateful`: a carried-in or carried-out state is involved; the three-launch path is then taken even for a single
-// segment, with the scan seeding segment 0's slot from S_in.
-template <int C, int DK, int DV>
+// `aff` (Eq. 11-12): non-null selects the kernels that take Z in place of Q and K; it points at the [4][H][DK] fp32
+// parameters (alpha_q, beta_q, alpha_k, beta_k).  A carried-in state goes through the scan even when there is a
+// single segment.
+template <int C, int DK, int DV, bool ZQK>
 static hipError_t fwd_impl(const bf16* Q, const bf16* K, const bf16* V, bf16* O, const float* S_in, float* S_out,
-                           long BH, int N, const Plan& plan, float* ws, hipStream_t st)
+                           const float* aff, int H, long BH, int N, const Plan& plan, float* ws, hipStream_t st)
 {
     hipError_t e;
-    const bool stateful = (S_in != nullptr || S_out != nullptr);
     const bool use_ws = plan.n_seg > 1 || S_in != nullptr;
     if (use_ws) {
         SegStateArgs a{};
-        a.X[0] = K; a.Y[0] = V; a.out[0] = ws; a.skip_seg[0] = plan.n_seg - 1;
+        a.X[0] = ZQK ? Q : K; a.Y[0] = V; a.out[0] = ws; a.skip_seg[0] = plan.n_seg - 1;
+        if (ZQK) { a.alpha[0] = aff + 2 * (size_t)H * DK; a.beta[0] = aff + 3 * (size_t)H * DK; a.H = H; }
         const int mode = SCAN_EXCL_PREFIX;
         const float* init[2] = {S_in, nullptr};
-        if ((e = run_seg_state<DK, DV>(a, 1, &mode, init, false, BH, N, plan, st)) != hipSuccess) return e;
+        if ((e = run_seg_state<DK, DV, ZQK ? 1 : 0>(a, 1, &mode, init, false, BH, N, plan, st)) != hipSuccess) return e;
     }
-    (void)stateful;
     dim3 grid((unsigned)BH, plan.n_seg);
     ProfScope prof(KID_FWD_SWEEP_BF16, st);
-    hipLaunchKernelGGL((bf16_fwd_sweep_kernel<C, DK, DV>), grid, dim3(256), 0, st, Q, K, V, O, use_ws ? ws : nullptr,
-                       S_out, S_in != nullptr ? 1 : 0, N, plan.seg_len, plan.n_seg);
+    hipLaunchKernelGGL((bf16_fwd_sweep_kernel<C, DK, DV, ZQK>), grid, dim3(256), 0, st, Q, K, V, O,
+                       use_ws ? ws : nullptr, S_out, aff, H, S_in != nullptr ? 1 : 0, N, plan.seg_len, plan.n_seg);
     return hipGetLastError();
 }
 
-template <int C, int DK, int DV>
+// With ZQK, dQ receives dZ, dK is unused and d_aff ([4][H][DK]) the parameter gradients; the workgroups' shares of
+// those live behind the two state arrays in the workspace.
+template <int C, int DK, int DV, bool ZQK>
 static hipError_t bwd_impl(const bf16* Q, const bf16* K, const bf16* V, const bf16* dO, const float* S_in,
-                           const float* dS_out, bf16* dQ, bf16* dK, bf16* dV, float* dS_in, long BH, int N,
-                           const Plan& plan, float* ws, hipStream_t st)
+                           const float* dS_out, bf16* dQ, bf16* dK, bf16* dV, float* dS_in, const float* aff,
+                           float* d_aff, int B, int H, int N, const Plan& plan, float* ws, hipStream_t st)
 {
     hipError_t e;
-    float* wsS = ws;
-    float* wsR = ws ? ws + (size_t)BH * plan.n_seg * DK * DV : nullptr;
+    const long BH = (long)B * H;
     const bool use_ws = plan.n_seg > 1 || S_in != nullptr || dS_out != nullptr;
+    const size_t state_floats = use_ws ? (size_t)BH * plan.n_seg * DK * DV : 0;
+    float* wsS = ws;
+    float* wsR = ws ? ws + state_floats : nullptr;
+    float* wsP = ZQK ? ws + 2 * state_floats : nullptr;
     if (use_ws) {
         SegStateArgs a{};
         // S^T totals: every segment is needed (inclusive prefix); R^T totals: the first is never used (exclusive suffix)
-        a.X[0] = V;  a.Y[0] = K; a.out[0] = wsS; a.skip_seg[0] = -1;
-        a.X[1] = dO; a.Y[1] = Q; a.out[1] = wsR; a.skip_seg[1] = 0;
+        a.X[0] = V;  a.Y[0] = ZQK ? Q : K; a.out[0] = wsS; a.skip_seg[0] = -1;
+        a.X[1] = dO; a.Y[1] = Q;           a.out[1] = wsR; a.skip_seg[1] = 0;
+        if (ZQK) {
+            a.alpha[0] = aff + 2 * (size_t)H * DK; a.beta[0] = aff + 3 * (size_t)H * DK;   // K
+            a.alpha[1] = aff;                      a.beta[1] = aff + (size_t)H * DK;       // Q
+            a.H = H;
+        }
         const int modes[2] = {SCAN_INCL_PREFIX, SCAN_EXCL_SUFFIX};
         const float* init[2] = {S_in, dS_out};   // given as [dk][dv]; the arrays are [dv][dk]
-        if ((e = run_seg_state<DV, DK>(a, 2, modes, init, true, BH, N, plan, st)) != hipSuccess) return e;
+        if ((e = run_seg_state<DV, DK, ZQK ? 2 : 0>(a, 2, modes, init, true, BH, N, plan, st)) != hipSuccess) return e;
     }
-    dim3 grid((unsigned)BH, plan.n_seg);
-    ProfScope prof(KID_BWD_SWEEP_BF16, st);
-    hipLaunchKernelGGL((bf16_bwd_sweep_kernel<C, DK, DV>), grid, dim3(256), 0, st, Q, K, V, dO, dQ, dK, dV,
-                       use_ws ? wsS : nullptr, use_ws ? wsR : nullptr, dS_in, N, plan.seg_len, plan.n_seg);
-    return hipGetLastError();
+    {
+        dim3 grid((unsigned)BH, plan.n_seg);
+        ProfScope prof(KID_BWD_SWEEP_BF16, st);
+        hipLaunchKernelGGL((bf16_bwd_sweep_kernel<C, DK, DV, ZQK>), grid, dim3(256), 0, st, Q, K, V, dO, dQ, dK, dV,
+                           use_ws ? wsS : nullptr, use_ws ? wsR : nullptr, dS_in, aff, H, wsP, N, plan.seg_len,
+                           plan.n_seg);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+    if (ZQK) {
+        ProfScope prof(KID_AFFINE_GRAD, st);
+        hipLaunchKernelGGL((affine_grad_kernel<DK>), dim3(4 * H), dim3(256), 0, st, wsP, d_aff, B, H, plan.n_seg);
+        e = hipGetLastError();
+    }
+    return e;
 }
 
 #define CHELA_DISPATCH(C_, DK_, DV_, CALL)                                  \
@@ -843,14 +1062,11 @@ hipError_t launch_bf16_fwd(const void* Q, const void* K, const void* V, void* O,
 {
     const bf16 *q = (const bf16*)Q, *k = (const bf16*)K, *v = (const bf16*)V;
     bf16* o = (bf16*)O;
-    CHELA_DISPATCH(64, 64, 64, (fwd_impl<64, 64, 64>(q, k, v, o, S_in, S_out, BH, N, plan, ws, st)))
-    CHELA_DISPATCH(128, 64, 64, (fwd_impl<128, 64, 64>(q, k, v, o, S_in, S_out, BH, N, plan, ws, st)))
-    CHELA_DISPATCH(64, 64, 128, (fwd_impl<64, 64, 128>(q, k, v, o, S_in, S_out, BH, N, plan, ws, st)))
-    CHELA_DISPATCH(128, 64, 128, (fwd_impl<128, 64, 128>(q, k, v, o, S_in, S_out, BH, N, plan, ws, st)))
-    CHELA_DISPATCH(64, 128, 64, (fwd_impl<64, 128, 64>(q, k, v, o, S_in, S_out, BH, N, plan, ws, st)))
-    CHELA_DISPATCH(128, 128, 64, (fwd_impl<128, 128, 64>(q, k, v, o, S_in, S_out, BH, N, plan, ws, st)))
-    CHELA_DISPATCH(64, 128, 128, (fwd_impl<64, 128, 128>(q, k, v, o, S_in, S_out, BH, N, plan, ws, st)))
-    CHELA_DISPATCH(128, 128, 128, (fwd_impl<128, 128, 128>(q, k, v, o, S_in, S_out, BH, N, plan, ws, st)))
+#define CHELA_FWD(C_, DK_, DV_) \
+    CHELA_DISPATCH(C_, DK_, DV_, (fwd_impl<C_, DK_, DV_, false>(q, k, v, o, S_in, S_out, nullptr, 1, BH, N, plan, ws, st)))
+    CHELA_FWD(64, 64, 64) CHELA_FWD(128, 64, 64) CHELA_FWD(64, 64, 128) CHELA_FWD(128, 64, 128)
+    CHELA_FWD(64, 128, 64) CHELA_FWD(128, 128, 64) CHELA_FWD(64, 128, 128) CHELA_FWD(128, 128, 128)
+#undef CHELA_FWD
     return hipErrorInvalidValue;
 }
 
@@ -860,11 +1076,38 @@ hipError_t launch_bf16_bwd(const void* Q, const void* K, const void* V, const vo
 {
     const bf16 *q = (const bf16*)Q, *k = (const bf16*)K, *v = (const bf16*)V, *g = (const bf16*)dO;
     bf16 *dq = (bf16*)dQ, *dkk = (bf16*)dK, *dvv = (bf16*)dV;
-    CHELA_DISPATCH(64, 64, 64, (bwd_impl<64, 64, 64>(q, k, v, g, S_in, dS_out, dq, dkk, dvv, dS_in, BH, N, plan, ws, st)))
-    CHELA_DISPATCH(128, 64, 64, (bwd_impl<128, 64, 64>(q, k, v, g, S_in, dS_out, dq, dkk, dvv, dS_in, BH, N, plan, ws, st)))
-    CHELA_DISPATCH(64, 64, 128, (bwd_impl<64, 64, 128>(q, k, v, g, S_in, dS_out, dq, dkk, dvv, dS_in, BH, N, plan, ws, st)))
-    CHELA_DISPATCH(64, 128, 64, (bwd_impl<64, 128, 64>(q, k, v, g, S_in, dS_out, dq, dkk, dvv, dS_in, BH, N, plan, ws, st)))
-    CHELA_DISPATCH(64, 128, 128, (bwd_impl<64, 128, 128>(q, k, v, g, S_in, dS_out, dq, dkk, dvv, dS_in, BH, N, plan, ws, st)))
+#define CHELA_BWD(C_, DK_, DV_)                                                                                       \
+    CHELA_DISPATCH(C_, DK_, DV_, (bwd_impl<C_, DK_, DV_, false>(q, k, v, g, S_in, dS_out, dq, dkk, dvv, dS_in, nullptr, \
+                                                                nullptr, (int)BH, 1, N, plan, ws, st)))
+    CHELA_BWD(64, 64, 64) CHELA_BWD(128, 64, 64) CHELA_BWD(64, 64, 128) CHELA_BWD(64, 128, 64) CHELA_BWD(64, 128, 128)
+#undef CHELA_BWD
+    return hipErrorInvalidValue;
+}
+
+// Eq. 11-12 variants: Z in place of Q and K, 64-token chunks.
+hipError_t launch_bf16_zfwd(const void* Z, const float* aff, const void* V, void* O, int B, int H, int N, int dk,
+                            int dv, const Plan& plan, float* ws, hipStream_t st)
+{
+    const bf16 *z = (const bf16*)Z, *v = (const bf16*)V;
+    bf16* o = (bf16*)O;
+    const long BH = (long)B * H;
+#define CHELA_ZFWD(DK_, DV_) \
+    CHELA_DISPATCH(64, DK_, DV_, (fwd_impl<64, DK_, DV_, true>(z, nullptr, v, o, nullptr, nullptr, aff, H, BH, N, plan, ws, st)))
+    CHELA_ZFWD(64, 64) CHELA_ZFWD(64, 128) CHELA_ZFWD(128, 64) CHELA_ZFWD(128, 128)
+#undef CHELA_ZFWD
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_bf16_zbwd(const void* Z, const float* aff, const void* V, const void* dO, void* dZ, float* d_aff,
+                            void* dV, int B, int H, int N, int dk, int dv, const Plan& plan, float* ws, hipStream_t st)
+{
+    const bf16 *z = (const bf16*)Z, *v = (const bf16*)V, *g = (const bf16*)dO;
+    bf16 *dz = (bf16*)dZ, *dvv = (bf16*)dV;
+#define CHELA_ZBWD(DK_, DV_)                                                                                       \
+    CHELA_DISPATCH(64, DK_, DV_, (bwd_impl<64, DK_, DV_, true>(z, nullptr, v, g, nullptr, nullptr, dz, nullptr, dvv, \
+                                                               nullptr, aff, d_aff, B, H, N, plan, ws, st)))
+    CHELA_ZBWD(64, 64) CHELA_ZBWD(64, 128) CHELA_ZBWD(128, 64) CHELA_ZBWD(128, 128)
+#undef CHELA_ZBWD
     return hipErrorInvalidValue;
 }
 

@@ -89,6 +89,29 @@ def make_inputs(w: Workload, with_dO: Optional[bool] = None) -> Dict[str, torch.
     return out
 
 
+def make_z_inputs(w: Workload, with_dO: Optional[bool] = None) -> Dict[str, torch.Tensor]:
+    """Inputs for the entry points that form queries and keys from one tensor: {"Z","affine","V"[,"dO"]}.
+
+    Recipe: generator seeded with seed + 1000; torch.randn in fp32 in the order Z [B,H,N,dk], n [4,H,dk],
+    V [B,H,N,dv], dO; affine rows (scale_q, offset_q, scale_k, offset_k) = ((1 + n0/4)/8, n1/32, (1 + n2/4)/8, n3/32),
+    so that queries and keys have the spread of the plain workloads (about 1/8) plus a per-feature offset;
+    Z, V, dO are cast to the I/O dtype last, affine stays fp32."""
+    if with_dO is None:
+        with_dO = w.backward
+    g = torch.Generator(device="cpu")
+    g.manual_seed(w.seed + 1000)
+    z = torch.randn(w.B, w.H, w.N, w.dk, generator=g, dtype=torch.float32)
+    n = torch.randn(4, w.H, w.dk, generator=g, dtype=torch.float32)
+    v = torch.randn(w.B, w.H, w.N, w.dv, generator=g, dtype=torch.float32)
+    affine = torch.stack([(1.0 + n[0] / 4.0) / 8.0, n[1] / 32.0, (1.0 + n[2] / 4.0) / 8.0, n[3] / 32.0]).contiguous()
+    dt = _torch_dtype(w.dtype)
+    out = {"Z": z.to(dt).contiguous(), "affine": affine, "V": v.to(dt).contiguous()}
+    if with_dO:
+        dO = torch.randn(w.B, w.H, w.N, w.dv, generator=g, dtype=torch.float32)
+        out["dO"] = dO.to(dt).contiguous()
+    return out
+
+
 def to_f64_numpy(t: torch.Tensor):
     """Exact up-cast of an fp32/bf16 tensor to a float64 numpy array (oracle input)."""
     return t.detach().to("cpu").to(torch.float64).numpy()

@@ -112,6 +112,30 @@ def test_state_and_step_argument_errors(L):
     assert st(A, A + SZ, A + 2 * SZ, S, A + 3 * SZ, -1, 4, 64, 64, None) == -2
 
 
+def test_z_entry_point_argument_errors(L):
+    f, g, w = L.chela_linattn_zfwd, L.chela_linattn_zbwd, L.chela_linattn_z_workspace_bytes
+    Z, AF, V, O = A, A + SZ, A + 2 * SZ, A + 3 * SZ
+    assert f(None, AF, V, O, 1, 2, 64, 64, 64, 64, None) == -1
+    assert f(Z, None, V, O, 1, 2, 64, 64, 64, 64, None) == -1
+    assert f(Z, AF + 4, V, O, 1, 2, 64, 64, 64, 64, None) == -5
+    assert f(Z, AF, V, AF, 1, 2, 64, 64, 64, 64, None) == -6          # O on top of the parameters
+    assert f(Z, AF, V, O, 1, 2, 64, 96, 64, 64, None) == -3
+    assert f(Z, AF, V, O, 1, 2, 64, 64, 64, 32, None) == -4
+    assert f(None, None, None, None, 1, 2, 0, 64, 64, 64, None) == 0
+    dZ, dA, dV, dO = A + 4 * SZ, A + 5 * SZ, A + 6 * SZ, A + 7 * SZ
+    assert g(Z, AF, V, dO, dZ, None, dV, 1, 2, 64, 64, 64, 64, None) == -1
+    assert g(Z, AF, V, dO, dZ, AF, dV, 1, 2, 64, 64, 64, 64, None) == -6   # d_affine on top of affine
+    assert g(Z, AF, V, dO, dZ, dA, dZ, 1, 2, 64, 64, 64, 64, None) == -6   # dV on top of dZ
+    assert g(Z, AF, V, dO, dZ, dA, dV, -1, 2, 64, 64, 64, 64, None) == -2
+    assert w(1, 2, 0, 64, 64, 64, 0) == 0 and w(1, 2, 64, 64, 48, 64, 0) == 0
+    # one segment, forward: nothing; backward: the workgroups' shares of the parameter gradients, [B*H][4][dk] fp32
+    assert w(1, 2, 64, 64, 64, 64, 0) == 0
+    assert w(1, 2, 64, 64, 64, 64, 1) == 2 * 4 * 64 * 4
+    big = w(4, 12, 16384, 64, 64, 64, 1)
+    plain = L.chela_linattn_workspace_bytes(4, 12, 16384, 64, 64, 64, 1, 0)
+    assert big > plain and (big - plain) % (48 * 4 * 64 * 4) == 0
+
+
 def test_shape_overflow_is_rejected(L):
     assert _fwd(L, B=1 << 20, H=1 << 20, N=1 << 20) == -2
 

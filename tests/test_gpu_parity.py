@@ -11,7 +11,8 @@ import torch
 
 import oracle
 from paper_2406_08128_amd import binding
-from paper_2406_08128_amd.workloads import WORKLOADS, make_inputs, shrink, to_f64_numpy
+from oracle import layer as oracle_layer
+from paper_2406_08128_amd.workloads import WORKLOADS, make_inputs, make_z_inputs, shrink, to_f64_numpy
 
 pytestmark = pytest.mark.gpu
 
@@ -361,3 +362,89 @@ def test_decode_step(dims):
     O_steps = torch.stack(outs, dim=2).double()
     assert float((O.double() - O_steps).norm() / O_steps.norm()) < 6e-3
     assert float((S_seq.double() - S.double()).norm() / S.double().norm()) < 1e-5
+
+
+# ------------------------------------------------------------------------------------------ Q, K from one tensor Z
+def _run_z_case(w, heads_of_batch0=None):
+    """zfwd / zbwd against the layer oracle.  d_affine sums over the whole batch, so a sampled comparison at full
+    size restricts the INPUT to batch entry 0 and some heads instead of slicing outputs."""
+    print("\nz-case %s B%d H%d N%d dk%d dv%d" % (w.name, w.B, w.H, w.N, w.dk, w.dv), flush=True)
+    x = make_z_inputs(w, with_dO=True)
+    d = _dev(x)
+    O = binding.chela_linattn_zfwd(d["Z"], d["affine"], d["V"])
+    dZ, dA, dV = binding.chela_linattn_zbwd(d["Z"], d["affine"], d["V"], d["dO"])
+    torch.cuda.synchronize()
+    Zn, An, Vn, Gn = (to_f64_numpy(x[n]) for n in ("Z", "affine", "V", "dO"))
+    _check("O", O, oracle_layer.zqk_fwd(Zn, An, Vn), "bf16")
+    rZ, rA, rV = oracle_layer.zqk_bwd(Zn, An, Vn, Gn)
+    _check("dZ", dZ, rZ, "bf16")
+    _check("dV", dV, rV, "bf16")
+    # the parameter gradients leave in fp32, but they are sums of products of bf16-rounded operands' results
+    for q, name in enumerate(("d_alpha_q", "d_beta_q", "d_alpha_k", "d_beta_k")):
+        _check(name, dA[q], rA[q], "bf16")
+    return dA
+
+
+Z_SHAPES = [(1, 1, 64, 64, 64), (2, 3, 1000, 64, 64), (1, 2, 1, 64, 64), (3, 2, 1100, 64, 128), (1, 2, 1300, 128, 64),
+            (2, 1, 700, 128, 128), (1, 2, 9000, 64, 64)]
+
+
+@pytest.mark.parametrize("shape", Z_SHAPES)
+def test_zqk_fwd_bwd_small(shape):
+    B, H, N, dk, dv = shape
+    _run_z_case(shrink(WORKLOADS["lm_bf16"], B=B, H=H, N=N, dk=dk, dv=dv, seed=50 + N))
+
+
+def test_zqk_equals_unfused_call_on_materialised_q_k():
+    # the fused call must agree with the plain entry points fed Q, K computed by torch in fp32 and rounded to bf16
+    # (same operand rounding; only fp32 contraction of alpha*z+beta may differ in the last bit before rounding)
+    w = shrink(WORKLOADS["lm_bf16"], B=2, H=3, N=3000, seed=77)
+    x = _dev(make_z_inputs(w, with_dO=True))
+    a = x["affine"]
+    Zf = x["Z"].float()
+    Q = (a[0][None, :, None, :] * Zf + a[1][None, :, None, :]).bfloat16()
+    K = (a[2][None, :, None, :] * Zf + a[3][None, :, None, :]).bfloat16()
+    O1 = binding.chela_linattn_zfwd(x["Z"], a, x["V"])
+    O2 = binding.chela_linattn_fwd(Q, K, x["V"])
+    dZ, dA, dV1 = binding.chela_linattn_zbwd(x["Z"], a, x["V"], x["dO"])
+    dQ, dK, dV2 = binding.chela_linattn_bwd(Q, K, x["V"], x["dO"])
+    torch.cuda.synchronize()
+    assert oracle.rel_l2(to_f64_numpy(O1), to_f64_numpy(O2)) <= 1e-3
+    assert oracle.rel_l2(to_f64_numpy(dV1), to_f64_numpy(dV2)) <= 1e-3
+    dZ2 = a[0][None, :, None, :] * dQ.float() + a[2][None, :, None, :] * dK.float()
+    assert oracle.rel_l2(to_f64_numpy(dZ), to_f64_numpy(dZ2)) <= 6e-3
+
+
+def test_zqk_lm_full_size_sampled():
+    # full-size launch configuration (B4 H12 N16384): outputs of sampled heads against the oracle; the parameter
+    # gradients of the full call against the oracle run on the whole batch for those heads only
+    w = WORKLOADS["lm_bf16"]
+    x = make_z_inputs(w, with_dO=True)
+    d = _dev(x)
+    O = binding.chela_linattn_zfwd(d["Z"], d["affine"], d["V"])
+    dZ, dA, dV = binding.chela_linattn_zbwd(d["Z"], d["affine"], d["V"], d["dO"])
+    torch.cuda.synchronize()
+    for hd in (0, 7, 11):
+        Zn, Vn, Gn = (to_f64_numpy(x[n][:, hd:hd + 1]) for n in ("Z", "V", "dO"))
+        An = to_f64_numpy(x["affine"][:, hd:hd + 1])
+        print("head", hd, flush=True)
+        _check("O", O[:, hd:hd + 1], oracle_layer.zqk_fwd(Zn, An, Vn), "bf16")
+        rZ, rA, rV = oracle_layer.zqk_bwd(Zn, An, Vn, Gn)
+        _check("dZ", dZ[:, hd:hd + 1], rZ, "bf16")
+        _check("dV", dV[:, hd:hd + 1], rV, "bf16")
+        for q in range(4):
+            _check("d_affine[%d]" % q, dA[q, hd:hd + 1], rA[q], "bf16")
+
+
+def test_zqk_two_runs_are_bit_identical_and_empty_input():
+    w = shrink(WORKLOADS["lm_bf16"], B=2, H=2, N=5000, seed=78)
+    x = _dev(make_z_inputs(w, with_dO=True))
+    r1 = binding.chela_linattn_zbwd(x["Z"], x["affine"], x["V"], x["dO"])
+    r2 = binding.chela_linattn_zbwd(x["Z"], x["affine"], x["V"], x["dO"])
+    torch.cuda.synchronize()
+    for a, b in zip(r1, r2):
+        assert torch.equal(a, b)
+    e = torch.empty((2, 2, 0, 64), dtype=torch.bfloat16, device="cuda")
+    dZ, dA, dV = binding.chela_linattn_zbwd(e, x["affine"], e, e)
+    torch.cuda.synchronize()
+    assert dZ.numel() == 0 and float(dA.abs().max()) == 0.0
