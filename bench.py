@@ -91,9 +91,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="lm_bf16")
     ap.add_argument("--chunk", type=int, default=64)
-    ap.add_argument("--mode", default="train", choices=["train", "train_state", "decode"],
+    ap.add_argument("--mode", default="train", choices=["train", "train_state", "train_z", "decode"],
                     help="train: fwd+bwd (the headline); train_state: the same through the carried-state entry points "
-                         "(S_in, S_out, dS_out, dS_in all live); decode: single-token steps of the recurrent form")
+                         "(S_in, S_out, dS_out, dS_in all live); train_z: queries and keys formed on chip from one tensor Z "
+                         "(chela_linattn_zfwd / zbwd: three forward and five backward HBM streams); decode: single-token steps of the recurrent form")
     ap.add_argument("--decode-batch", type=int, default=256, help="sequences decoded together in --mode decode")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
@@ -109,7 +110,7 @@ def main():
 
     import torch
     from paper_2406_08128_amd import binding
-    from paper_2406_08128_amd.workloads import WORKLOADS, make_inputs, to_f64_numpy
+    from paper_2406_08128_amd.workloads import WORKLOADS, make_inputs, make_z_inputs, to_f64_numpy
 
     w = WORKLOADS[args.workload]
     torch.cuda.set_device(0)
@@ -134,6 +135,17 @@ def main():
         def step():
             binding.chela_linattn_fwd_state(d["Q"], d["K"], d["V"], S_in=S_in, O=O, S_out=S_out, chunk=chunk)
             binding.chela_linattn_bwd_state(d["Q"], d["K"], d["V"], d["dO"], S_in=S_in, dS_out=dS_out, chunk=chunk)
+    elif args.mode == "train_z":
+        assert w.dtype == "bf16", "--mode train_z needs a bf16 workload"
+        xz = make_z_inputs(w, with_dO=has_bwd)
+        dz = {k: v.cuda() for k, v in xz.items()}
+        if has_bwd:
+            def step():
+                binding.chela_linattn_zfwd(dz["Z"], dz["affine"], dz["V"], O=O)
+                binding.chela_linattn_zbwd(dz["Z"], dz["affine"], dz["V"], dz["dO"])
+        else:
+            def step():
+                binding.chela_linattn_zfwd(dz["Z"], dz["affine"], dz["V"], O=O)
     elif has_bwd:
         def step():
             binding.chela_linattn_fwd(d["Q"], d["K"], d["V"], O=O, chunk=chunk)
@@ -174,6 +186,8 @@ def main():
     kernels = {k: {"launches": n, "avg_us": ms * 1e3 / n} for k, (n, ms) in prof.items()}
 
     fwd_b, bwd_b = algorithmic_bytes_per_token_head(w.dk, w.dv, es)
+    if args.mode == "train_z":     # Z replaces Q and K on the way in, dZ replaces dQ and dK on the way out
+        fwd_b, bwd_b = es * (w.dk + 2 * w.dv), es * (w.dk + 2 * w.dv + w.dk + w.dv)
     fwd_f, bwd_f = flops_per_token_head(w.dk, w.dv, chunk)
     th = w.token_heads
     if w.dtype != "bf16":
@@ -184,7 +198,8 @@ def main():
         dom, dom_b = "bf16_fwd_sweep_kernel", fwd_b
     dom_us = kernels[dom]["avg_us"]
     achieved = dom_b * th / (dom_us * 1e-6) / 1e9
-    traffic = read_traffic(args.traffic_file) if (args.workload == "lm_bf16" and chunk == 64) else None
+    traffic = read_traffic(args.traffic_file) if (args.workload == "lm_bf16" and chunk == 64
+                                                  and args.mode == "train") else None
     roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "algorithmic_bytes_per_launch": dom_b * th, "avg_launch_us": round(dom_us, 2)}
@@ -198,13 +213,23 @@ def main():
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
-        Qn, Kn, Vn = (to_f64_numpy(x[n]) for n in ("Q", "K", "V"))
-        Gn = to_f64_numpy(x["dO"]) if has_bwd else None
-        c0 = time.perf_counter()
-        oracle.fwd_recurrent(Qn, Kn, Vn)
-        if has_bwd:
-            oracle.bwd_recurrent(Qn, Kn, Vn, Gn)
-        c1 = time.perf_counter()
+        if args.mode == "train_z":
+            from oracle import layer as oracle_layer
+            Zn, An, Vn = (to_f64_numpy(xz[n]) for n in ("Z", "affine", "V"))
+            Gn = to_f64_numpy(xz["dO"]) if has_bwd else None
+            c0 = time.perf_counter()
+            oracle_layer.zqk_fwd(Zn, An, Vn)
+            if has_bwd:
+                oracle_layer.zqk_bwd(Zn, An, Vn, Gn)
+            c1 = time.perf_counter()
+        else:
+            Qn, Kn, Vn = (to_f64_numpy(x[n]) for n in ("Q", "K", "V"))
+            Gn = to_f64_numpy(x["dO"]) if has_bwd else None
+            c0 = time.perf_counter()
+            oracle.fwd_recurrent(Qn, Kn, Vn)
+            if has_bwd:
+                oracle.bwd_recurrent(Qn, Kn, Vn, Gn)
+            c1 = time.perf_counter()
         cpu = {"value": round(w.tokens / (c1 - c0), 1), "unit": "tokens/s", "cores": oracle.num_threads(),
                "kind": "oracle", "seconds": round(c1 - c0, 3),
                "sample": "fp64 recurrent-form oracle, %s, all %d (b,h) pairs of the workload, one repetition"
@@ -212,7 +237,8 @@ def main():
 
     out = {
         "metric": "causal linear-attn %s tokens/s" % ("fwd+bwd" if has_bwd else "fwd")
-                  + (" (carried-state entry points)" if args.mode == "train_state" else ""),
+                  + (" (carried-state entry points)" if args.mode == "train_state" else "")
+                  + (" (Q, K formed on chip from Z)" if args.mode == "train_z" else ""),
         "value": round(tokens_per_s, 1),
         "unit": "tokens/s",
         "n_gpus": 1,

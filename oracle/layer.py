@@ -12,7 +12,7 @@ Everything here is plain numpy in float64; the attention itself is the pinned C 
 """
 import numpy as np
 
-from . import fwd_quadratic, bwd_quadratic
+from . import fwd_recurrent, bwd_recurrent
 
 
 def _check(Z, affine):
@@ -34,7 +34,7 @@ def qk_from_z(Z, affine):
 def zqk_fwd(Z, affine, V):
     """O_t = sum_{s<=t} (q_t . k_s) v_s with q, k from Eq. 11-12."""
     Q, K = qk_from_z(Z, affine)
-    return fwd_quadratic(Q, K, V)
+    return fwd_recurrent(Q, K, V)
 
 
 def zqk_bwd(Z, affine, V, dO):
@@ -43,7 +43,7 @@ def zqk_bwd(Z, affine, V, dO):
     dZ = alpha_q * dQ + alpha_k * dK;  d_alpha_q = sum_{b,t} dQ * Z;  d_beta_q = sum_{b,t} dQ;  same for k."""
     Z, a = _check(Z, affine)
     Q, K = qk_from_z(Z, a)
-    dQ, dK, dV = bwd_quadratic(Q, K, V, dO)
+    dQ, dK, dV = bwd_recurrent(Q, K, V, dO)
     dZ = a[0][None, :, None, :] * dQ + a[2][None, :, None, :] * dK
     d_aff = np.stack([(dQ * Z).sum(axis=(0, 2)), dQ.sum(axis=(0, 2)), (dK * Z).sum(axis=(0, 2)), dK.sum(axis=(0, 2))])
     return dZ, d_aff, dV

@@ -512,21 +512,42 @@ struct BwdLds {
     static constexpr int BYTES = TILES + (ZQK ? C * LDK * 2 + 4 * DK * 4 : 0);
 };
 
-// x holds, per lane, 16 values of one token (the token is lane % 32).  Returns the sum over the 32 tokens of a wave
-// half of ONE of them: value index 8*b16 + 4*b8 + 2*b4 + b2, b_m = bit m of the lane number.  Each exchange step
-// halves the number of live values, so the whole reduction costs 16 lane exchanges instead of 80.
+// Sum over the tokens of a wave half for the parameter gradients.  x holds, per lane, 16 values of one token (the
+// token is lane % 32, the value index e = 4a + b stands for feature 8a + 4h + b, h = lane / 32).  Every exchange step
+// pairs each lane with a partner, the two keep opposite halves of the live values and add the partner's copy of
+// theirs, so the reduction costs 16 exchanges instead of 80; the lane ends with the total of value
+// e = 8*b16 + 4*b8 + 2*b4 + b2 (b_m = bit m of the lane number).  All exchanges are register-to-register:
+//   16: v_permlane16_swap (odd 16-lane rows of the first operand trade places with even rows of the second), which
+//       also needs no per-lane choice between x[j] and x[j+8] (the compiler would turn that choice into a
+//       dynamically indexed vector);
+//    8: DPP row rotate by 8;   4: DPP half-row mirror (partner = lane ^ 7: differs in bit 4's place, and the two
+//       steps after it still cover all eight lanes);   2, 1: DPP quad permutes.
+template <int CTRL>
+__device__ __forceinline__ float dpp_get(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, false));
+}
+
 __device__ __forceinline__ float sum_tokens16(const f32x16& x, int lane)
 {
+    constexpr int ROW_ROR8 = 0x128, HALF_MIRROR = 0x141, QUAD_XOR2 = 0x4E, QUAD_XOR1 = 0xB1;
     float y8[8], y4[4], y2[2];
-    const bool u16 = lane & 16, u8 = lane & 8, u4 = lane & 4, u2 = lane & 2;
+    const bool u8 = lane & 8, u4 = lane & 4, u2 = lane & 2;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) y8[j] = (u16 ? x[j + 8] : x[j]) + __shfl_xor(u16 ? x[j] : x[j + 8], 16);
+    for (int j = 0; j < 8; ++j) {
+        // (bit casts go through named scalars: applied to a vector element they read element 0)
+        const float lo = x[j], hi = x[j + 8];
+        const u32x2 s = __builtin_amdgcn_permlane16_swap(__builtin_bit_cast(unsigned, lo),
+                                                         __builtin_bit_cast(unsigned, hi), false, false);
+        const unsigned s0 = s[0], s1 = s[1];
+        y8[j] = __builtin_bit_cast(float, s0) + __builtin_bit_cast(float, s1);
+    }
 #pragma unroll
-    for (int j = 0; j < 4; ++j) y4[j] = (u8 ? y8[j + 4] : y8[j]) + __shfl_xor(u8 ? y8[j] : y8[j + 4], 8);
+    for (int j = 0; j < 4; ++j) y4[j] = (u8 ? y8[j + 4] : y8[j]) + dpp_get<ROW_ROR8>(u8 ? y8[j] : y8[j + 4]);
 #pragma unroll
-    for (int j = 0; j < 2; ++j) y2[j] = (u4 ? y4[j + 2] : y4[j]) + __shfl_xor(u4 ? y4[j] : y4[j + 2], 4);
-    float y = (u2 ? y2[1] : y2[0]) + __shfl_xor(u2 ? y2[0] : y2[1], 2);
-    return y + __shfl_xor(y, 1);
+    for (int j = 0; j < 2; ++j) y2[j] = (u4 ? y4[j + 2] : y4[j]) + dpp_get<HALF_MIRROR>(u4 ? y4[j] : y4[j + 2]);
+    const float y = (u2 ? y2[1] : y2[0]) + dpp_get<QUAD_XOR2>(u2 ? y2[0] : y2[1]);
+    return y + dpp_get<QUAD_XOR1>(y);
 }
 
 template <int C, int DK, int DV, bool ZQK>
