@@ -47,3 +47,21 @@ def zqk_bwd(Z, affine, V, dO):
     dZ = a[0][None, :, None, :] * dQ + a[2][None, :, None, :] * dK
     d_aff = np.stack([(dQ * Z).sum(axis=(0, 2)), dQ.sum(axis=(0, 2)), (dK * Z).sum(axis=(0, 2)), dK.sum(axis=(0, 2))])
     return dZ, d_aff, dV
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# Sec. 2.1 Eq. 2 as written (no mask): O = Q (K^T V), what the paper's classification models (LRA, speech, pixel
+# sequences) run.  Norm is left to the caller, as in the causal case.  numpy matmul is the library step.
+def noncausal_fwd(Q, K, V):
+    """O[b,h] = Q[b,h] @ (K[b,h]^T @ V[b,h]): right-product linear attention without a mask."""
+    Q, K, V = (np.asarray(x, dtype=np.float64) for x in (Q, K, V))
+    S = np.matmul(np.swapaxes(K, -1, -2), V)            # [B,H,dk,dv]
+    return np.matmul(Q, S)
+
+
+def noncausal_bwd(Q, K, V, dO):
+    """(dQ, dK, dV) of noncausal_fwd: with S = K^T V and R = Q^T dO,  dQ = dO S^T, dK = V R^T, dV = K R."""
+    Q, K, V, dO = (np.asarray(x, dtype=np.float64) for x in (Q, K, V, dO))
+    S = np.matmul(np.swapaxes(K, -1, -2), V)
+    R = np.matmul(np.swapaxes(Q, -1, -2), dO)
+    return np.matmul(dO, np.swapaxes(S, -1, -2)), np.matmul(V, np.swapaxes(R, -1, -2)), np.matmul(K, R)

@@ -113,3 +113,76 @@ def test_zqk_adjoint_in_v():
 def test_zqk_shape_errors():
     with pytest.raises(ValueError):
         layer.qk_from_z(np.zeros((1, 2, 3, 4)), np.zeros((4, 1, 4)))
+
+
+# --------------------------------------------------------------------------- non-causal form (Sec. 2.1, Eq. 2)
+def _qkv(rng, B, H, N, dk, dv):
+    return (rng.standard_normal((B, H, N, dk)), rng.standard_normal((B, H, N, dk)),
+            rng.standard_normal((B, H, N, dv)), rng.standard_normal((B, H, N, dv)))
+
+
+def test_noncausal_brute_force():
+    rng = np.random.default_rng(21)
+    Q, K, V, _ = _qkv(rng, 2, 2, 5, 3, 2)
+    want = np.zeros_like(V)
+    for b in range(2):
+        for h in range(2):
+            for t in range(5):
+                for s in range(5):
+                    dot = sum(Q[b, h, t, i] * K[b, h, s, i] for i in range(3))
+                    for j in range(2):
+                        want[b, h, t, j] += dot * V[b, h, s, j]
+    np.testing.assert_allclose(layer.noncausal_fwd(Q, K, V), want, rtol=1e-12, atol=1e-12)
+
+
+def test_noncausal_right_product_equals_left_product():
+    # Eq. 2's point: Q (K^T V) = (Q K^T) V; the oracle takes the first, this is the second
+    rng = np.random.default_rng(22)
+    Q, K, V, _ = _qkv(rng, 1, 3, 40, 8, 6)
+    want = np.einsum("bhts,bhsj->bhtj", np.einsum("bhti,bhsi->bhts", Q, K), V)
+    np.testing.assert_allclose(layer.noncausal_fwd(Q, K, V), want, rtol=1e-11, atol=1e-11)
+
+
+def test_noncausal_is_causal_plus_anticausal_minus_diagonal():
+    # sum over all s = sum over s <= t  +  sum over s >= t  -  the s = t term; both one-sided sums come from the
+    # pinned causal oracle (the second on the time-reversed sequence)
+    rng = np.random.default_rng(23)
+    Q, K, V, _ = _qkv(rng, 2, 2, 33, 4, 5)
+    fwd = oracle.fwd_recurrent(Q, K, V)
+    rev = oracle.fwd_recurrent(Q[:, :, ::-1], K[:, :, ::-1], V[:, :, ::-1])[:, :, ::-1]
+    diag = (Q * K).sum(-1, keepdims=True) * V
+    np.testing.assert_allclose(layer.noncausal_fwd(Q, K, V), fwd + rev - diag, rtol=1e-11, atol=1e-11)
+    # and the last token of the causal form sees everything
+    np.testing.assert_allclose(layer.noncausal_fwd(Q, K, V)[:, :, -1], fwd[:, :, -1], rtol=1e-11, atol=1e-11)
+
+
+def test_noncausal_gradient_adjoint_and_finite_differences():
+    rng = np.random.default_rng(24)
+    Q, K, V, dO = _qkv(rng, 1, 2, 6, 3, 2)
+    dQ, dK, dV = layer.noncausal_bwd(Q, K, V, dO)
+    # linear in V: <O, dO> = <V, dV>; linear in Q: <O, dO> = <Q, dQ>; linear in K likewise
+    lhs = float((layer.noncausal_fwd(Q, K, V) * dO).sum())
+    for x, g in ((Q, dQ), (K, dK), (V, dV)):
+        assert abs(lhs - float((x * g).sum())) <= 1e-10 * max(1.0, abs(lhs))
+    h = 1e-5
+    for which, grad in enumerate((dQ, dK, dV)):
+        base = [Q, K, V]
+        it = np.nditer(base[which], flags=["multi_index"])
+        for _ in it:
+            idx = it.multi_index
+            args = [a.copy() for a in base]
+            args[which][idx] += h
+            up = float((layer.noncausal_fwd(*args) * dO).sum())
+            args[which][idx] -= 2 * h
+            dn = float((layer.noncausal_fwd(*args) * dO).sum())
+            fd = (up - dn) / (2 * h)
+            assert abs(fd - grad[idx]) <= 1e-6 * max(1.0, abs(fd))
+
+
+def test_noncausal_permutation_of_keys_changes_nothing():
+    # without a mask the order of the (key, value) pairs is irrelevant -- the property the causal form lacks
+    rng = np.random.default_rng(25)
+    Q, K, V, _ = _qkv(rng, 1, 1, 20, 4, 4)
+    perm = rng.permutation(20)
+    np.testing.assert_allclose(layer.noncausal_fwd(Q, K[:, :, perm], V[:, :, perm]), layer.noncausal_fwd(Q, K, V),
+                               rtol=1e-11, atol=1e-11)
