@@ -91,10 +91,11 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="lm_bf16")
     ap.add_argument("--chunk", type=int, default=64)
-    ap.add_argument("--mode", default="train", choices=["train", "train_state", "train_z", "decode"],
+    ap.add_argument("--mode", default="train", choices=["train", "train_state", "train_z", "noncausal", "decode"],
                     help="train: fwd+bwd (the headline); train_state: the same through the carried-state entry points "
                          "(S_in, S_out, dS_out, dS_in all live); train_z: queries and keys formed on chip from one tensor Z "
-                         "(chela_linattn_zfwd / zbwd: three forward and five backward HBM streams); decode: single-token steps of the recurrent form")
+                         "(chela_linattn_zfwd / zbwd: three forward and five backward HBM streams); noncausal: O = Q (K^T V) "
+                         "without a mask (the classification models' form); decode: single-token steps of the recurrent form")
     ap.add_argument("--decode-batch", type=int, default=256, help="sequences decoded together in --mode decode")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
@@ -135,6 +136,15 @@ def main():
         def step():
             binding.chela_linattn_fwd_state(d["Q"], d["K"], d["V"], S_in=S_in, O=O, S_out=S_out, chunk=chunk)
             binding.chela_linattn_bwd_state(d["Q"], d["K"], d["V"], d["dO"], S_in=S_in, dS_out=dS_out, chunk=chunk)
+    elif args.mode == "noncausal":
+        assert w.dtype == "bf16", "--mode noncausal needs a bf16 workload"
+        if has_bwd:
+            def step():
+                binding.chela_linattn_noncausal_fwd(d["Q"], d["K"], d["V"], O=O)
+                binding.chela_linattn_noncausal_bwd(d["Q"], d["K"], d["V"], d["dO"])
+        else:
+            def step():
+                binding.chela_linattn_noncausal_fwd(d["Q"], d["K"], d["V"], O=O)
     elif args.mode == "train_z":
         assert w.dtype == "bf16", "--mode train_z needs a bf16 workload"
         xz = make_z_inputs(w, with_dO=has_bwd)
@@ -190,7 +200,9 @@ def main():
         fwd_b, bwd_b = es * (w.dk + 2 * w.dv), es * (w.dk + 2 * w.dv + w.dk + w.dv)
     fwd_f, bwd_f = flops_per_token_head(w.dk, w.dv, chunk)
     th = w.token_heads
-    if w.dtype != "bf16":
+    if args.mode == "noncausal":    # the apply kernel reads one tensor and writes one; forward: Q in, O out
+        dom, dom_b = "bf16_apply_state_kernel", es * (w.dk + w.dv)
+    elif w.dtype != "bf16":
         dom, dom_b = "f32_sweep_kernel", fwd_b
     elif has_bwd:
         dom, dom_b = "bf16_bwd_sweep_kernel", bwd_b
@@ -213,7 +225,16 @@ def main():
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
-        if args.mode == "train_z":
+        if args.mode == "noncausal":
+            from oracle import layer as oracle_layer
+            Qn, Kn, Vn = (to_f64_numpy(x[n]) for n in ("Q", "K", "V"))
+            Gn = to_f64_numpy(x["dO"]) if has_bwd else None
+            c0 = time.perf_counter()
+            oracle_layer.noncausal_fwd(Qn, Kn, Vn)
+            if has_bwd:
+                oracle_layer.noncausal_bwd(Qn, Kn, Vn, Gn)
+            c1 = time.perf_counter()
+        elif args.mode == "train_z":
             from oracle import layer as oracle_layer
             Zn, An, Vn = (to_f64_numpy(xz[n]) for n in ("Z", "affine", "V"))
             Gn = to_f64_numpy(xz["dO"]) if has_bwd else None
@@ -232,11 +253,12 @@ def main():
             c1 = time.perf_counter()
         cpu = {"value": round(w.tokens / (c1 - c0), 1), "unit": "tokens/s", "cores": oracle.num_threads(),
                "kind": "oracle", "seconds": round(c1 - c0, 3),
-               "sample": "fp64 recurrent-form oracle, %s, all %d (b,h) pairs of the workload, one repetition"
+               "sample": "fp64 oracle, %s, all %d (b,h) pairs of the workload, one repetition"
                          % ("fwd+bwd" if has_bwd else "fwd", w.B * w.H)}
 
     out = {
-        "metric": "causal linear-attn %s tokens/s" % ("fwd+bwd" if has_bwd else "fwd")
+        "metric": "%s linear-attn %s tokens/s" % ("non-causal" if args.mode == "noncausal" else "causal",
+                                                  "fwd+bwd" if has_bwd else "fwd")
                   + (" (carried-state entry points)" if args.mode == "train_state" else "")
                   + (" (Q, K formed on chip from Z)" if args.mode == "train_z" else ""),
         "value": round(tokens_per_s, 1),

@@ -129,6 +129,20 @@ int chela_linattn_zbwd(const void *Z, const float *affine, const void *V, const 
                        int B, int H, int N, int dk, int dv, int chunk, void *stream);
 size_t chela_linattn_z_workspace_bytes(int B, int H, int N, int dk, int dv, int chunk, int is_bwd);
 
+/* ---- non-causal form (Sec. 2.1, Eq. 2 as written, without Norm): O = Q (K^T V), every token sees every token.
+ * This is what the paper's sequence classifiers run (no mask); bf16 I/O, fp32 accumulation, the d_k x d_v matrix
+ * K^T V rounded to bf16 once as a matrix-core operand.  Two passes: K^T V summed over the sequence, then O = Q S for
+ * independent blocks of tokens.  The backward returns, with S = K^T V and R = Q^T dO,
+ *     dQ = dO S^T,  dK = V R^T,  dV = K R.
+ * Tensors, layout, alignment, aliasing rules, stream and errors as for chela_linattn_fwd / _bwd (there is no chunk
+ * argument: nothing here is sequential).  Scratch: chela_linattn_noncausal_workspace_bytes(). */
+int chela_linattn_noncausal_fwd(const void *Q, const void *K, const void *V, void *O,
+                                int B, int H, int N, int dk, int dv, void *stream);
+int chela_linattn_noncausal_bwd(const void *Q, const void *K, const void *V, const void *dO,
+                                void *dQ, void *dK, void *dV,
+                                int B, int H, int N, int dk, int dv, void *stream);
+size_t chela_linattn_noncausal_workspace_bytes(int B, int H, int N, int dk, int dv, int is_bwd);
+
 /* One decode step of autoregressive inference (the recurrent form, one token per (b,h)):
  *     S += k v^T  (in place, fp32) ;  o = S^T q.
  * q, k: [B, H, dk] bf16; v, o: [B, H, dv] bf16; S: [B, H, dk, dv] fp32.  Needs no scratch. */

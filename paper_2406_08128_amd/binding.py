@@ -53,6 +53,12 @@ def lib() -> ctypes.CDLL:
     L.chela_linattn_zbwd.restype = i
     L.chela_linattn_z_workspace_bytes.argtypes = [i, i, i, i, i, i, i]
     L.chela_linattn_z_workspace_bytes.restype = sz
+    L.chela_linattn_noncausal_fwd.argtypes = [vp, vp, vp, vp, i, i, i, i, i, vp]
+    L.chela_linattn_noncausal_fwd.restype = i
+    L.chela_linattn_noncausal_bwd.argtypes = [vp] * 7 + [i, i, i, i, i, vp]
+    L.chela_linattn_noncausal_bwd.restype = i
+    L.chela_linattn_noncausal_workspace_bytes.argtypes = [i, i, i, i, i, i]
+    L.chela_linattn_noncausal_workspace_bytes.restype = sz
     L.chela_linattn_step.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, vp]
     L.chela_linattn_step.restype = i
     L.chela_linattn_workspace_bytes.argtypes = [i, i, i, i, i, i, i, i]
@@ -183,6 +189,41 @@ def chela_linattn_bwd_state(Q, K, V, dO, S_in=None, dS_out=None, chunk: int = 64
                                              dV.data_ptr(), dS_in.data_ptr(), B, H, N, dk, dv, int(chunk),
                                              _stream_ptr(stream)))
     return dQ, dK, dV, dS_in
+
+
+def _bf16_only(Q, what):
+    if Q.dtype != torch.bfloat16:
+        raise TypeError("%s is bf16 only" % what)
+
+
+def chela_linattn_noncausal_fwd(Q, K, V, O=None, stream=None):
+    """O = Q (K^T V) per (b,h): linear attention without a mask."""
+    B, H, N, dk, dv = _dims(Q, K, V)
+    _bf16_only(Q, "the non-causal form")
+    if O is None:
+        O = torch.empty((B, H, N, dv), dtype=Q.dtype, device=Q.device)
+    with torch.cuda.device(Q.device):
+        _check(lib().chela_linattn_noncausal_fwd(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), B, H, N, dk,
+                                                 dv, _stream_ptr(stream)))
+    return O
+
+
+def chela_linattn_noncausal_bwd(Q, K, V, dO, stream=None):
+    """(dQ, dK, dV) of chela_linattn_noncausal_fwd."""
+    B, H, N, dk, dv = _dims(Q, K, V)
+    _bf16_only(Q, "the non-causal form")
+    if dO.shape != V.shape or dO.dtype != Q.dtype or not dO.is_contiguous():
+        raise ValueError("dO must match V")
+    dQ, dK, dV = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
+    with torch.cuda.device(Q.device):
+        _check(lib().chela_linattn_noncausal_bwd(Q.data_ptr(), K.data_ptr(), V.data_ptr(), dO.data_ptr(),
+                                                 dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(), B, H, N, dk, dv,
+                                                 _stream_ptr(stream)))
+    return dQ, dK, dV
+
+
+def chela_linattn_noncausal_workspace_bytes(B, H, N, dk, dv, is_bwd) -> int:
+    return int(lib().chela_linattn_noncausal_workspace_bytes(B, H, N, dk, dv, int(bool(is_bwd))))
 
 
 def _zdims(Z, affine, V):

@@ -87,6 +87,28 @@ Plan make_plan(long BH, int N, int dk, int dv, int chunk, int dtype, bool is_bwd
     return p;
 }
 
+// Non-causal form: the pre-pass is the only part that is split, and only to fill the GPU (about four workgroups per
+// compute unit), in pieces of at least 256 tokens.
+Plan make_noncausal_plan(long BH, int N, int dk, int dv, bool is_bwd)
+{
+    Plan p{};
+    p.chunk = 64;
+    p.state_elems = (size_t)dk * dv;
+    if (BH <= 0 || N <= 0) { p.seg_len = 64; p.n_seg = 0; p.ws_bytes = 0; return p; }
+    const int pairs = is_bwd ? 2 : 1;
+    long n_seg = (1024 + BH * pairs - 1) / (BH * pairs);
+    const long max_seg = N / 256 > 0 ? N / 256 : 1;
+    const int forced = env_int("CHELA_NC_SEGS", 0);     // tuning aid: segments per (b,h) of the non-causal pre-pass
+    if (forced > 0) n_seg = forced;
+    if (n_seg > max_seg) n_seg = max_seg;
+    if (n_seg < 1) n_seg = 1;
+    long seg_len = (((long)N + n_seg - 1) / n_seg + 63) / 64 * 64;
+    p.seg_len = (int)seg_len;
+    p.n_seg = (int)(((long)N + seg_len - 1) / seg_len);
+    p.ws_bytes = (size_t)BH * p.n_seg * p.state_elems * sizeof(float) * pairs;
+    return p;
+}
+
 // ------------------------------------------------------------------ per-kernel timing aid
 struct ProfRec { int id; hipEvent_t a, b; };
 static bool g_prof_on = false;
@@ -94,7 +116,8 @@ static std::vector<ProfRec> g_prof;          // records in use
 static std::vector<ProfRec> g_prof_free;     // event pairs to re-use
 static const char* const kKernelNames[KID_COUNT] = {
     "bf16_seg_state_kernel", "scan_states_kernel", "bf16_fwd_sweep_kernel", "bf16_bwd_sweep_kernel",
-    "f32_seg_state_kernel", "f32_sweep_kernel", "copy_probe_kernel", "bf16_step_kernel", "affine_grad_kernel"};
+    "f32_seg_state_kernel", "f32_sweep_kernel", "copy_probe_kernel", "bf16_step_kernel", "affine_grad_kernel",
+    "bf16_apply_state_kernel"};
 
 ProfScope::ProfScope(int id, hipStream_t s) : slot(-1), st(s)
 {
@@ -340,6 +363,28 @@ static int zbwd_common(const void* Z, const float* aff, const void* V, const voi
                ? CHELA_OK : CHELA_ERR_HIP;
 }
 
+static int noncausal_common(const void* Q, const void* K, const void* V, const void* dO, void* O_or_dQ, void* dK,
+                            void* dV, bool is_bwd, int B, int H, int N, int dk, int dv, void* stream)
+{
+    const size_t th = (B > 0 && H > 0 && N > 0) ? (size_t)B * H * N : 0;
+    const void* in_v[4] = {Q, K, V, is_bwd ? dO : Q};
+    const size_t inb[4] = {th * dk * 2, th * dk * 2, th * dv * 2, is_bwd ? th * dv * 2 : 0};
+    void* out_v[3] = {O_or_dQ, is_bwd ? dK : O_or_dQ, is_bwd ? dV : O_or_dQ};
+    const size_t outb[3] = {th * (is_bwd ? dk : dv) * 2, is_bwd ? th * dk * 2 : 0, is_bwd ? th * dv * 2 : 0};
+    bool empty = false;
+    int rc = validate(in_v, inb, 4, out_v, outb, 3, B, H, N, dk, dv, 64, CHELA_DTYPE_BF16, &empty);
+    if (rc != CHELA_OK || empty) return rc;
+    const long BH = (long)B * H;
+    Plan plan = make_noncausal_plan(BH, N, dk, dv, is_bwd);
+    float* ws = nullptr;
+    rc = get_workspace(plan.ws_bytes, &ws);
+    if (rc != CHELA_OK) return rc;
+    hipError_t e = is_bwd ? launch_bf16_noncausal_bwd(Q, K, V, dO, O_or_dQ, dK, dV, BH, N, dk, dv, plan, ws,
+                                                      (hipStream_t)stream)
+                          : launch_bf16_noncausal_fwd(Q, K, V, O_or_dQ, BH, N, dk, dv, plan, ws, (hipStream_t)stream);
+    return e == hipSuccess ? CHELA_OK : CHELA_ERR_HIP;
+}
+
 }  // namespace chela
 
 using namespace chela;
@@ -403,6 +448,25 @@ size_t chela_linattn_z_workspace_bytes(int B, int H, int N, int dk, int dv, int 
     const long BH = (long)B * H;
     Plan plan = make_plan(BH, N, dk, dv, 64, CHELA_DTYPE_BF16, is_bwd != 0, false);
     return plan.ws_bytes + (is_bwd ? zbwd_extra_ws_bytes(BH, plan, dk) : 0);
+}
+
+int chela_linattn_noncausal_fwd(const void* Q, const void* K, const void* V, void* O, int B, int H, int N, int dk,
+                                int dv, void* stream)
+{
+    return noncausal_common(Q, K, V, nullptr, O, nullptr, nullptr, false, B, H, N, dk, dv, stream);
+}
+
+int chela_linattn_noncausal_bwd(const void* Q, const void* K, const void* V, const void* dO, void* dQ, void* dK,
+                                void* dV, int B, int H, int N, int dk, int dv, void* stream)
+{
+    return noncausal_common(Q, K, V, dO, dQ, dK, dV, true, B, H, N, dk, dv, stream);
+}
+
+size_t chela_linattn_noncausal_workspace_bytes(int B, int H, int N, int dk, int dv, int is_bwd)
+{
+    if (B <= 0 || H <= 0 || N <= 0) return 0;
+    if (!((dk == 64 || dk == 128) && (dv == 64 || dv == 128))) return 0;
+    return make_noncausal_plan((long)B * H, N, dk, dv, is_bwd != 0).ws_bytes;
 }
 
 int chela_linattn_step(const void* q, const void* k, const void* v, float* S, void* o, int B, int H, int dk, int dv,

@@ -53,12 +53,20 @@ inline size_t zbwd_extra_ws_bytes(long BH, const Plan& plan, int dk)
 {
     return (size_t)BH * plan.n_seg * 4 * dk * sizeof(float);
 }
+// Non-causal form O = Q (K^T V) and its gradient.  `plan` comes from make_noncausal_plan(): n_seg / seg_len split
+// the pre-pass, ws holds one (forward) or two (backward) arrays of BH * n_seg states.
+Plan make_noncausal_plan(long BH, int N, int dk, int dv, bool is_bwd);
+hipError_t launch_bf16_noncausal_fwd(const void* Q, const void* K, const void* V, void* O, long BH, int N, int dk,
+                                     int dv, const Plan& plan, float* ws, hipStream_t st);
+hipError_t launch_bf16_noncausal_bwd(const void* Q, const void* K, const void* V, const void* dO, void* dQ, void* dK,
+                                     void* dV, long BH, int N, int dk, int dv, const Plan& plan, float* ws,
+                                     hipStream_t st);
 hipError_t launch_bf16_step(const void* q, const void* k, const void* v, float* S, void* o, long BH, int dk, int dv,
                             hipStream_t st);
 
 // Kernel classes for the per-kernel timing aid.
 enum { KID_SEG_STATE_BF16 = 0, KID_SCAN = 1, KID_FWD_SWEEP_BF16 = 2, KID_BWD_SWEEP_BF16 = 3, KID_SEG_STATE_F32 = 4,
-       KID_SWEEP_F32 = 5, KID_COPY = 6, KID_STEP_BF16 = 7, KID_AFFINE_GRAD = 8, KID_COUNT = 9 };
+       KID_SWEEP_F32 = 5, KID_COPY = 6, KID_STEP_BF16 = 7, KID_AFFINE_GRAD = 8, KID_APPLY_BF16 = 9, KID_COUNT = 10 };
 
 // Brackets one kernel launch with HIP events on its stream while profiling is enabled; otherwise does nothing.
 struct ProfScope {

@@ -182,6 +182,14 @@ struct TileRegs {
             }
         }
     }
+    // All C rows exist: no predicate, so the loads are issued unconditionally and the compiler can count them
+    // (s_waitcnt vmcnt(n) with the exact n instead of 0 wherever younger loads are meant to stay in flight).
+    __device__ __forceinline__ void load_full(const bf16* tile, int tid)
+    {
+        const uint4* src = reinterpret_cast<const uint4*>(tile);
+#pragma unroll
+        for (int n = 0; n < NV; ++n) v[n] = src[tid + 256 * n];
+    }
     __device__ __forceinline__ void store(bf16* lds, int tid) const
     {
 #pragma unroll
@@ -324,38 +332,67 @@ __device__ __forceinline__ void prepass_body(const bf16* __restrict__ X, const b
     for (int n = 0; n < NT; ++n) acc[n] = zero16();
     TileRegs<R, DA> rx[PF];
     TileRegs<R, DB> ry[PF];
-#pragma unroll
-    for (int u = 0; u < PF; ++u)
-        if (u * R < ntok) {
-            rx[u].load(X + (size_t)(u * R) * DA, ntok - u * R, tid);
-            ry[u].load(Y + (size_t)(u * R) * DB, ntok - u * R, tid);
-        }
     if (AFF != 0) {
         if (tid < DAFF) { sAff[tid] = alpha[tid]; sAff[DAFF + tid] = beta[tid]; }
         __syncthreads();
     }
-    for (int c0 = 0; c0 < ntok; c0 += PF * R) {
+    auto consume = [&](int u) __attribute__((always_inline)) {   // registers of set u -> LDS -> accumulators
+        if (AFF == 1) rx[u].store_affine(sX, sAff, sAff + DAFF, tid);
+        else rx[u].store(sX, tid);
+        if (AFF == 2) ry[u].store_affine(sY, sAff, sAff + DAFF, tid);
+        else ry[u].store(sY, tid);
+    };
+    auto multiply = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int n = 0; n < NT; ++n) {
+            const int id = w + 4 * n, ab = id / BB, bb = id % BB;
+#pragma unroll
+            for (int s0 = 0; s0 < R; s0 += 16)
+                acc[n] = mfma(ld_tr(sX, DA + PAD, s0, ab * 32, lane), ld_tr(sY, DB + PAD, s0, bb * 32, lane), acc[n]);
+        }
+    };
+    int c0 = 0;
+    if (ntok >= 2 * PF * R) {
+        // Steady state: the PF blocks being consumed and the PF blocks being fetched are all complete, so every load
+        // is unconditional and the wait before a set is consumed leaves the younger set's loads in flight.
+#pragma unroll
+        for (int u = 0; u < PF; ++u) {
+            rx[u].load_full(X + (size_t)(u * R) * DA, tid);
+            ry[u].load_full(Y + (size_t)(u * R) * DB, tid);
+            __builtin_amdgcn_sched_barrier(0);   // keep the sets in issue order: the wait for set 0 must not cover set 1
+        }
+        for (; c0 + 2 * PF * R <= ntok; c0 += PF * R) {
+#pragma unroll
+            for (int u = 0; u < PF; ++u) {
+                consume(u);
+                __syncthreads();
+                rx[u].load_full(X + (size_t)(c0 + (PF + u) * R) * DA, tid);
+                ry[u].load_full(Y + (size_t)(c0 + (PF + u) * R) * DB, tid);
+                multiply();
+                __syncthreads();
+            }
+        }
+    } else {
+#pragma unroll
+        for (int u = 0; u < PF; ++u)
+            if (u * R < ntok) {
+                rx[u].load(X + (size_t)(u * R) * DA, ntok - u * R, tid);
+                ry[u].load(Y + (size_t)(u * R) * DB, ntok - u * R, tid);
+            }
+    }
+    // The rest (at most 2 PF blocks, the last one possibly ragged): set u holds block c0 + u R if that block exists.
+    for (; c0 < ntok; c0 += PF * R) {
 #pragma unroll
         for (int u = 0; u < PF; ++u) {
             const int c = c0 + u * R;
             if (c < ntok) {
-                if (AFF == 1) rx[u].store_affine(sX, sAff, sAff + DAFF, tid);
-                else rx[u].store(sX, tid);
-                if (AFF == 2) ry[u].store_affine(sY, sAff, sAff + DAFF, tid);
-                else ry[u].store(sY, tid);
+                consume(u);
                 __syncthreads();
                 if (c + PF * R < ntok) {
                     rx[u].load(X + (size_t)(c + PF * R) * DA, ntok - c - PF * R, tid);
                     ry[u].load(Y + (size_t)(c + PF * R) * DB, ntok - c - PF * R, tid);
                 }
-#pragma unroll
-                for (int n = 0; n < NT; ++n) {
-                    const int id = w + 4 * n, ab = id / BB, bb = id % BB;
-#pragma unroll
-                    for (int s0 = 0; s0 < R; s0 += 16)
-                        acc[n] = mfma(ld_tr(sX, DA + PAD, s0, ab * 32, lane), ld_tr(sY, DB + PAD, s0, bb * 32, lane),
-                                      acc[n]);
-                }
+                multiply();
                 __syncthreads();
             }
         }
@@ -994,7 +1031,8 @@ hipError_t launch_bf16_step(const void* q, const void* k, const void* v, float* 
 // Pre-pass + scan over segments.  init[z] (optional, [dk][dv] fp32 per head) seeds the scan of array z.
 template <int DA, int DB, int AFF = 0>
 static hipError_t run_seg_state(const SegStateArgs& a, int npairs, const int* scan_modes, const float* const* init,
-                                bool init_transposed, long BH, int N, const Plan& plan, hipStream_t st)
+                                bool init_transposed, long BH, int N, const Plan& plan, hipStream_t st,
+                                bool do_scan = true)
 {
     hipError_t e;
     {
@@ -1003,6 +1041,7 @@ static hipError_t run_seg_state(const SegStateArgs& a, int npairs, const int* sc
         hipLaunchKernelGGL((bf16_seg_state_kernel<DA, DB, AFF>), grid, dim3(256), 0, st, a, N, plan.seg_len, plan.n_seg);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
+    if (!do_scan) return hipSuccess;
     const size_t stride = npairs > 1 ? (size_t)(a.out[1] - a.out[0]) : 0;
     return scan_states(a.out[0], stride, npairs, scan_modes, init, init_transposed ? DB : 0, BH, plan.n_seg, DA * DB, st);
 }
@@ -1073,6 +1112,155 @@ static hipError_t bwd_impl(const bf16* Q, const bf16* K, const bf16* V, const bf
         e = hipGetLastError();
     }
     return e;
+}
+
+// =============================================================================================== non-causal form
+// Eq. 2 as written, O = Q (K^T V): no mask, so the state is one matrix per (b,h) -- the total of the pre-pass -- and
+// every block of tokens is independent.  Y[t][:] = X[t][:] M for the tokens of one workgroup, M a [DA][DB] fp32
+// matrix per head, given either as it is (M_IS_T = false) or transposed, [DB][DA] (true).  The matrix becomes the
+// A operand (M^T, bf16, read from LDS once and kept in registers), a 64-token tile of X the B operand, the result
+// tile is Y^T and leaves through 16-byte stores.  The X tile is double-buffered in LDS: one barrier per chunk.
+template <int DA, int DB>
+struct ApplyLds {
+    static constexpr int LDA = DA + PAD;
+    static constexpr int BYTES = (2 * 64 * LDA + DB * LDA) * 2;
+};
+
+template <int DA, int DB, bool M_IS_T>
+__global__ __launch_bounds__(256) void bf16_apply_state_kernel(const bf16* __restrict__ X, bf16* __restrict__ Y,
+                                                              const float* __restrict__ M, size_t m_stride, int N,
+                                                              int rows_per_wg)
+{
+    constexpr int C = 64, LDA = DA + PAD;
+    constexpr int JB = DB / 32, NJ = JB / 2;
+    __shared__ __attribute__((aligned(16))) unsigned char lds[ApplyLds<DA, DB>::BYTES];
+    bf16* sX = reinterpret_cast<bf16*>(lds);          // two buffers of C x LDA
+    bf16* sMT = sX + 2 * C * LDA;                      // M^T: [DB][LDA]
+    const long bh = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int tb = w % 2, jg = w / 2;
+    const int p0 = blockIdx.y * rows_per_wg, p1 = min(N, p0 + rows_per_wg), ntok = p1 - p0;
+    const bf16* Xb = X + ((size_t)bh * N + p0) * DA;
+    bf16* Yb = Y + ((size_t)bh * N + p0) * DB;
+    const float4* M4 = reinterpret_cast<const float4*>(M + (size_t)bh * m_stride);
+
+    TileRegs<C, DA> rx;
+    rx.load(Xb, ntok, tid);
+    for (int x = tid; x < DA * DB / 4; x += 256) {
+        const float4 v = M4[x];
+        if (M_IS_T) {
+            const int j = (4 * x) / DA, i = (4 * x) % DA;
+            u32x2 pk;
+            pk[0] = pack2(v.x, v.y);
+            pk[1] = pack2(v.z, v.w);
+            *reinterpret_cast<u32x2*>(sMT + j * LDA + i) = pk;
+        } else {
+            const int i = (4 * x) / DB, j = (4 * x) % DB;
+            sMT[(j + 0) * LDA + i] = (bf16)v.x;
+            sMT[(j + 1) * LDA + i] = (bf16)v.y;
+            sMT[(j + 2) * LDA + i] = (bf16)v.z;
+            sMT[(j + 3) * LDA + i] = (bf16)v.w;
+        }
+    }
+    __syncthreads();
+    bf16x8 aM[NJ][DA / 16];
+#pragma unroll
+    for (int n = 0; n < NJ; ++n)
+#pragma unroll
+        for (int kk = 0; kk < DA / 16; ++kk) aM[n][kk] = ld_nat(sMT, LDA, (jg * NJ + n) * 32, kk * 16, lane);
+
+    int buf = 0;
+    for (int c0 = 0; c0 < ntok; c0 += C, buf ^= 1) {
+        bf16* sXb = sX + buf * C * LDA;
+        rx.store(sXb, tid);
+        __syncthreads();
+        if (c0 + C < ntok) rx.load(Xb + (size_t)(c0 + C) * DA, ntok - c0 - C, tid);
+        f32x16 acc[NJ];
+#pragma unroll
+        for (int n = 0; n < NJ; ++n) acc[n] = zero16();
+#pragma unroll
+        for (int kk = 0; kk < DA / 16; ++kk) {
+            const bf16x8 bX = ld_nat(sXb, LDA, tb * 32, kk * 16, lane);
+#pragma unroll
+            for (int n = 0; n < NJ; ++n) acc[n] = mfma(aM[n][kk], bX, acc[n]);
+        }
+        bf16* rows = Yb + (size_t)(c0 + tb * 32) * DB;
+        const int valid = ntok - (c0 + tb * 32);
+#pragma unroll
+        for (int n = 0; n < NJ; ++n) store_tile_T(rows, DB, (jg * NJ + n) * 32, acc[n], valid, lane);
+    }
+}
+
+constexpr int kApplyRows = 512;   // tokens per workgroup of the apply kernel
+
+template <int DA, int DB, bool M_IS_T>
+static hipError_t run_apply(const bf16* X, bf16* Y, const float* M, size_t m_stride, long BH, int N, hipStream_t st)
+{
+    dim3 grid((unsigned)BH, (N + kApplyRows - 1) / kApplyRows);
+    ProfScope prof(KID_APPLY_BF16, st);
+    hipLaunchKernelGGL((bf16_apply_state_kernel<DA, DB, M_IS_T>), grid, dim3(256), 0, st, X, Y, M, m_stride, N,
+                       kApplyRows);
+    return hipGetLastError();
+}
+
+// plan.n_seg / seg_len describe the pre-pass split here; the totals end up in the last segment's slot.
+template <int DK, int DV>
+static hipError_t noncausal_fwd_impl(const bf16* Q, const bf16* K, const bf16* V, bf16* O, long BH, int N,
+                                     const Plan& plan, float* ws, hipStream_t st)
+{
+    hipError_t e;
+    SegStateArgs a{};
+    a.X[0] = V; a.Y[0] = K; a.out[0] = ws; a.skip_seg[0] = -1;       // S^T = V^T K, [dv][dk]
+    const int mode = SCAN_INCL_PREFIX;
+    if ((e = run_seg_state<DV, DK>(a, 1, &mode, nullptr, false, BH, N, plan, st, plan.n_seg > 1)) != hipSuccess) return e;
+    const size_t el = (size_t)DK * DV;
+    return run_apply<DK, DV, true>(Q, O, ws + (size_t)(plan.n_seg - 1) * el, plan.n_seg * el, BH, N, st);
+}
+
+template <int DK, int DV>
+static hipError_t noncausal_bwd_impl(const bf16* Q, const bf16* K, const bf16* V, const bf16* dO, bf16* dQ, bf16* dK,
+                                     bf16* dV, long BH, int N, const Plan& plan, float* ws, hipStream_t st)
+{
+    hipError_t e;
+    const size_t el = (size_t)DK * DV, arr = (size_t)BH * plan.n_seg * el;
+    float* wsS = ws;            // S^T = V^T K   [dv][dk]
+    float* wsR = ws + arr;      // R^T = dO^T Q  [dv][dk]
+    SegStateArgs a{};
+    a.X[0] = V;  a.Y[0] = K; a.out[0] = wsS; a.skip_seg[0] = -1;
+    a.X[1] = dO; a.Y[1] = Q; a.out[1] = wsR; a.skip_seg[1] = -1;
+    const int modes[2] = {SCAN_INCL_PREFIX, SCAN_INCL_PREFIX};
+    if ((e = run_seg_state<DV, DK>(a, 2, modes, nullptr, false, BH, N, plan, st, plan.n_seg > 1)) != hipSuccess) return e;
+    const size_t last = (size_t)(plan.n_seg - 1) * el, stride = plan.n_seg * el;
+    // dQ = dO S^T, dK = V R^T, dV = K R
+    if ((e = run_apply<DV, DK, false>(dO, dQ, wsS + last, stride, BH, N, st)) != hipSuccess) return e;
+    if ((e = run_apply<DV, DK, false>(V, dK, wsR + last, stride, BH, N, st)) != hipSuccess) return e;
+    return run_apply<DK, DV, true>(K, dV, wsR + last, stride, BH, N, st);
+}
+
+hipError_t launch_bf16_noncausal_fwd(const void* Q, const void* K, const void* V, void* O, long BH, int N, int dk,
+                                     int dv, const Plan& plan, float* ws, hipStream_t st)
+{
+    const bf16 *q = (const bf16*)Q, *k = (const bf16*)K, *v = (const bf16*)V;
+    bf16* o = (bf16*)O;
+    if (dk == 64 && dv == 64) return noncausal_fwd_impl<64, 64>(q, k, v, o, BH, N, plan, ws, st);
+    if (dk == 64 && dv == 128) return noncausal_fwd_impl<64, 128>(q, k, v, o, BH, N, plan, ws, st);
+    if (dk == 128 && dv == 64) return noncausal_fwd_impl<128, 64>(q, k, v, o, BH, N, plan, ws, st);
+    if (dk == 128 && dv == 128) return noncausal_fwd_impl<128, 128>(q, k, v, o, BH, N, plan, ws, st);
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_bf16_noncausal_bwd(const void* Q, const void* K, const void* V, const void* dO, void* dQ, void* dK,
+                                     void* dV, long BH, int N, int dk, int dv, const Plan& plan, float* ws,
+                                     hipStream_t st)
+{
+    const bf16 *q = (const bf16*)Q, *k = (const bf16*)K, *v = (const bf16*)V, *g = (const bf16*)dO;
+    bf16 *dq = (bf16*)dQ, *dkk = (bf16*)dK, *dvv = (bf16*)dV;
+    if (dk == 64 && dv == 64) return noncausal_bwd_impl<64, 64>(q, k, v, g, dq, dkk, dvv, BH, N, plan, ws, st);
+    if (dk == 64 && dv == 128) return noncausal_bwd_impl<64, 128>(q, k, v, g, dq, dkk, dvv, BH, N, plan, ws, st);
+    if (dk == 128 && dv == 64) return noncausal_bwd_impl<128, 64>(q, k, v, g, dq, dkk, dvv, BH, N, plan, ws, st);
+    if (dk == 128 && dv == 128) return noncausal_bwd_impl<128, 128>(q, k, v, g, dq, dkk, dvv, BH, N, plan, ws, st);
+    return hipErrorInvalidValue;
 }
 
 #define CHELA_DISPATCH(C_, DK_, DV_, CALL)                                  \

@@ -136,6 +136,26 @@ def test_z_entry_point_argument_errors(L):
     assert big > plain and (big - plain) % (48 * 4 * 64 * 4) == 0
 
 
+def test_noncausal_argument_errors(L):
+    f, g, w = L.chela_linattn_noncausal_fwd, L.chela_linattn_noncausal_bwd, L.chela_linattn_noncausal_workspace_bytes
+    Q, K, V, O = A, A + SZ, A + 2 * SZ, A + 3 * SZ
+    assert f(None, K, V, O, 1, 1, 64, 64, 64, None) == -1
+    assert f(Q, K, V, None, 1, 1, 64, 64, 64, None) == -1
+    assert f(Q, K, V, O + 2, 1, 1, 64, 64, 64, None) == -5
+    assert f(Q, K, V, K, 1, 1, 64, 64, 64, None) == -6
+    assert f(Q, K, V, O, 1, 1, 64, 64, 80, None) == -3
+    assert f(Q, K, V, O, 1, -1, 64, 64, 64, None) == -2
+    assert f(None, None, None, None, 1, 1, 0, 64, 64, None) == 0
+    dO, dQ, dK, dV = A + 3 * SZ, A + 4 * SZ, A + 5 * SZ, A + 6 * SZ
+    assert g(Q, K, V, None, dQ, dK, dV, 1, 1, 64, 64, 64, None) == -1
+    assert g(Q, K, V, dO, dQ, dQ, dV, 1, 1, 64, 64, 64, None) == -6
+    assert g(Q, K, V, dO, dQ, dK, dV, 0, 1, 64, 64, 64, None) == 0
+    assert w(1, 1, 64, 64, 64, 0) == 64 * 64 * 4 and w(1, 1, 64, 64, 64, 1) == 2 * 64 * 64 * 4
+    assert w(1, 1, 0, 64, 64, 0) == 0 and w(1, 1, 64, 64, 72, 0) == 0
+    # the scratch is bounded by the GPU's size, not by N
+    assert w(4, 12, 1 << 20, 64, 64, 0) <= 1100 * 64 * 64 * 4
+
+
 def test_shape_overflow_is_rejected(L):
     assert _fwd(L, B=1 << 20, H=1 << 20, N=1 << 20) == -2
 

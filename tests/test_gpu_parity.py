@@ -448,3 +448,50 @@ def test_zqk_two_runs_are_bit_identical_and_empty_input():
     dZ, dA, dV = binding.chela_linattn_zbwd(e, x["affine"], e, e)
     torch.cuda.synchronize()
     assert dZ.numel() == 0 and float(dA.abs().max()) == 0.0
+
+
+# ------------------------------------------------------------------------------------------ non-causal form
+NC_SHAPES = [(1, 1, 64, 64, 64), (2, 3, 1000, 64, 64), (1, 2, 1, 64, 64), (3, 2, 1100, 64, 128), (1, 2, 1300, 128, 64),
+             (2, 1, 700, 128, 128), (1, 2, 9000, 64, 64), (1, 1, 513, 128, 128)]
+
+
+def _run_nc_case(w, heads=None):
+    print("\nnon-causal %s B%d H%d N%d dk%d dv%d" % (w.name, w.B, w.H, w.N, w.dk, w.dv), flush=True)
+    x = make_inputs(w, with_dO=True)
+    d = _dev(x)
+    O = binding.chela_linattn_noncausal_fwd(d["Q"], d["K"], d["V"])
+    dQ, dK, dV = binding.chela_linattn_noncausal_bwd(d["Q"], d["K"], d["V"], d["dO"])
+    torch.cuda.synchronize()
+    if heads is None:
+        sel = lambda t: t
+    else:
+        idx = torch.tensor(heads)
+        sel = lambda t: t.reshape(1, w.B * w.H, w.N, -1)[:, idx.to(t.device)]
+    Qn, Kn, Vn, Gn = (to_f64_numpy(sel(x[n])) for n in ("Q", "K", "V", "dO"))
+    _check("O", sel(O), oracle_layer.noncausal_fwd(Qn, Kn, Vn), "bf16")
+    for name, got, r in zip(("dQ", "dK", "dV"), (dQ, dK, dV), oracle_layer.noncausal_bwd(Qn, Kn, Vn, Gn)):
+        _check(name, sel(got), r, "bf16")
+
+
+@pytest.mark.parametrize("shape", NC_SHAPES)
+def test_noncausal_fwd_bwd_small(shape):
+    B, H, N, dk, dv = shape
+    _run_nc_case(shrink(WORKLOADS["lra_bf16"], B=B, H=H, N=N, dk=dk, dv=dv, seed=90 + N))
+
+
+def test_noncausal_lra_full_size_sampled():
+    w = WORKLOADS["lra_bf16"]       # the shape of the paper's byte-level classification runs, where no mask is used
+    _run_nc_case(w, heads=_sample_heads(w))
+
+
+def test_noncausal_last_token_equals_causal_last_token_and_determinism():
+    w = shrink(WORKLOADS["lra_bf16"], B=2, H=2, N=3000, seed=91)
+    d = _dev(make_inputs(w))
+    O1 = binding.chela_linattn_noncausal_fwd(d["Q"], d["K"], d["V"])
+    O2 = binding.chela_linattn_noncausal_fwd(d["Q"], d["K"], d["V"])
+    Oc = binding.chela_linattn_fwd(d["Q"], d["K"], d["V"])
+    torch.cuda.synchronize()
+    assert torch.equal(O1, O2)
+    assert oracle.rel_l2(to_f64_numpy(O1[:, :, -1]), to_f64_numpy(Oc[:, :, -1])) <= 1e-2
+    e = torch.empty((2, 2, 0, 64), dtype=torch.bfloat16, device="cuda")
+    assert binding.chela_linattn_noncausal_fwd(e, e, e).numel() == 0
