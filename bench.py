@@ -91,8 +91,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="lm_bf16")
     ap.add_argument("--chunk", type=int, default=64)
-    ap.add_argument("--mode", default="train", choices=["train", "train_state", "train_z", "noncausal", "decode"],
-                    help="train: fwd+bwd (the headline); train_state: the same through the carried-state entry points "
+    ap.add_argument("--mode", default="train", choices=["train", "train_saved", "train_state", "train_z", "noncausal", "decode"],
+                    help="train: fwd+bwd (the headline); train_saved: the same step through chela_linattn_fwd_save / "
+                         "_bwd_saved (the forward leaves the boundary states, the backward skips its pass over K, V); "
+                         "train_state: the same through the carried-state entry points "
                          "(S_in, S_out, dS_out, dS_in all live); train_z: queries and keys formed on chip from one tensor Z "
                          "(chela_linattn_zfwd / zbwd: three forward and five backward HBM streams); noncausal: O = Q (K^T V) "
                          "without a mask (the classification models' form); decode: single-token steps of the recurrent form")
@@ -136,6 +138,14 @@ def main():
         def step():
             binding.chela_linattn_fwd_state(d["Q"], d["K"], d["V"], S_in=S_in, O=O, S_out=S_out, chunk=chunk)
             binding.chela_linattn_bwd_state(d["Q"], d["K"], d["V"], d["dO"], S_in=S_in, dS_out=dS_out, chunk=chunk)
+    elif args.mode == "train_saved":
+        assert has_bwd and w.dtype == "bf16", "--mode train_saved needs a bf16 forward+backward workload"
+        saved = torch.empty(max(binding.chela_linattn_saved_bytes(w.B, w.H, w.N, w.dk, w.dv, chunk), 16) // 4,
+                            dtype=torch.float32, device="cuda")
+
+        def step():
+            binding.chela_linattn_fwd_save(d["Q"], d["K"], d["V"], O=O, saved=saved, chunk=chunk)
+            binding.chela_linattn_bwd_saved(d["Q"], d["K"], d["V"], d["dO"], saved, dQ=dQ, dK=dK, dV=dV, chunk=chunk)
     elif args.mode == "noncausal":
         assert w.dtype == "bf16", "--mode noncausal needs a bf16 workload"
         if has_bwd:
@@ -260,6 +270,7 @@ def main():
         "metric": "%s linear-attn %s tokens/s" % ("non-causal" if args.mode == "noncausal" else "causal",
                                                   "fwd+bwd" if has_bwd else "fwd")
                   + (" (carried-state entry points)" if args.mode == "train_state" else "")
+                  + (" (forward saves the boundary states)" if args.mode == "train_saved" else "")
                   + (" (Q, K formed on chip from Z)" if args.mode == "train_z" else ""),
         "value": round(tokens_per_s, 1),
         "unit": "tokens/s",

@@ -129,6 +129,21 @@ int chela_linattn_zbwd(const void *Z, const float *affine, const void *V, const 
                        int B, int H, int N, int dk, int dv, int chunk, void *stream);
 size_t chela_linattn_z_workspace_bytes(int B, int H, int N, int dk, int dv, int chunk, int is_bwd);
 
+/* ---- training pair: forward that leaves the running state for the backward ------------------------------------
+ * chela_linattn_bwd rebuilds the state at its segment boundaries from K and V (one extra pass over both).  In a
+ * training step the forward call has just walked those states: chela_linattn_fwd_save writes them (fp32, at the
+ * boundaries the backward will use) into `saved`, a caller-owned device buffer of chela_linattn_saved_bytes() bytes
+ * (16-byte aligned, opaque), and chela_linattn_bwd_saved reads them back instead of re-reading K and V.  Same
+ * results as chela_linattn_fwd / _bwd up to floating-point re-association (the segment split may differ).
+ * `saved` must reach the backward call unchanged, with the same B, H, N, dk, dv and chunk, in the same process (its
+ * layout follows the library's work split for the current GPU).  bf16 I/O; everything else as for the plain calls. */
+int chela_linattn_fwd_save(const void *Q, const void *K, const void *V, void *O, void *saved,
+                           int B, int H, int N, int dk, int dv, int chunk, void *stream);
+int chela_linattn_bwd_saved(const void *Q, const void *K, const void *V, const void *dO, const void *saved,
+                            void *dQ, void *dK, void *dV,
+                            int B, int H, int N, int dk, int dv, int chunk, void *stream);
+size_t chela_linattn_saved_bytes(int B, int H, int N, int dk, int dv, int chunk);
+
 /* ---- non-causal form (Sec. 2.1, Eq. 2 as written, without Norm): O = Q (K^T V), every token sees every token.
  * This is what the paper's sequence classifiers run (no mask); bf16 I/O, fp32 accumulation, the d_k x d_v matrix
  * K^T V rounded to bf16 once as a matrix-core operand.  Two passes: K^T V summed over the sequence, then O = Q S for

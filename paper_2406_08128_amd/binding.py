@@ -53,6 +53,12 @@ def lib() -> ctypes.CDLL:
     L.chela_linattn_zbwd.restype = i
     L.chela_linattn_z_workspace_bytes.argtypes = [i, i, i, i, i, i, i]
     L.chela_linattn_z_workspace_bytes.restype = sz
+    L.chela_linattn_fwd_save.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, i, vp]
+    L.chela_linattn_fwd_save.restype = i
+    L.chela_linattn_bwd_saved.argtypes = [vp] * 8 + [i, i, i, i, i, i, vp]
+    L.chela_linattn_bwd_saved.restype = i
+    L.chela_linattn_saved_bytes.argtypes = [i, i, i, i, i, i]
+    L.chela_linattn_saved_bytes.restype = sz
     L.chela_linattn_noncausal_fwd.argtypes = [vp, vp, vp, vp, i, i, i, i, i, vp]
     L.chela_linattn_noncausal_fwd.restype = i
     L.chela_linattn_noncausal_bwd.argtypes = [vp] * 7 + [i, i, i, i, i, vp]
@@ -189,6 +195,43 @@ def chela_linattn_bwd_state(Q, K, V, dO, S_in=None, dS_out=None, chunk: int = 64
                                              dV.data_ptr(), dS_in.data_ptr(), B, H, N, dk, dv, int(chunk),
                                              _stream_ptr(stream)))
     return dQ, dK, dV, dS_in
+
+
+def chela_linattn_saved_bytes(B, H, N, dk, dv, chunk=64) -> int:
+    return int(lib().chela_linattn_saved_bytes(B, H, N, dk, dv, int(chunk)))
+
+
+def chela_linattn_fwd_save(Q, K, V, O=None, saved=None, chunk: int = 64, stream=None):
+    """(O, saved): forward that also leaves the running state at the backward's segment boundaries in `saved`."""
+    B, H, N, dk, dv = _dims(Q, K, V)
+    _bf16_only(Q, "the training pair")
+    if O is None:
+        O = torch.empty((B, H, N, dv), dtype=Q.dtype, device=Q.device)
+    need = chela_linattn_saved_bytes(B, H, N, dk, dv, chunk)
+    if saved is None:
+        saved = torch.empty(max(need, 16) // 4, dtype=torch.float32, device=Q.device)
+    elif saved.numel() * saved.element_size() < need or not saved.is_contiguous():
+        raise ValueError("saved must be a contiguous device buffer of at least %d bytes" % need)
+    with torch.cuda.device(Q.device):
+        _check(lib().chela_linattn_fwd_save(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), saved.data_ptr(),
+                                            B, H, N, dk, dv, int(chunk), _stream_ptr(stream)))
+    return O, saved
+
+
+def chela_linattn_bwd_saved(Q, K, V, dO, saved, dQ=None, dK=None, dV=None, chunk: int = 64, stream=None):
+    """(dQ, dK, dV) using the states chela_linattn_fwd_save left for the same inputs."""
+    B, H, N, dk, dv = _dims(Q, K, V)
+    _bf16_only(Q, "the training pair")
+    if dO.shape != V.shape or dO.dtype != Q.dtype or not dO.is_contiguous():
+        raise ValueError("dO must match V")
+    dQ = torch.empty_like(Q) if dQ is None else dQ
+    dK = torch.empty_like(K) if dK is None else dK
+    dV = torch.empty_like(V) if dV is None else dV
+    with torch.cuda.device(Q.device):
+        _check(lib().chela_linattn_bwd_saved(Q.data_ptr(), K.data_ptr(), V.data_ptr(), dO.data_ptr(),
+                                             saved.data_ptr(), dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(), B, H, N,
+                                             dk, dv, int(chunk), _stream_ptr(stream)))
+    return dQ, dK, dV
 
 
 def _bf16_only(Q, what):

@@ -87,6 +87,36 @@ Plan make_plan(long BH, int N, int dk, int dv, int chunk, int dtype, bool is_bwd
     return p;
 }
 
+// Training pair.  The backward's segments are fixed first (its sweep is the dominant kernel); the forward then cuts
+// each of them into save_every equal pieces, as close as the chunk grid allows to the split it would have chosen
+// for itself, so that every backward boundary is also a forward boundary.
+TrainPlans make_train_plans(long BH, int N, int dk, int dv, int chunk)
+{
+    TrainPlans t{};
+    const int cb = (chunk == 128 && dk == 64 && dv == 64) ? 128 : 64;      // the backward's chunk
+    t.bwd = make_plan(BH, N, dk, dv, cb, CHELA_DTYPE_BF16, true, false);
+    t.fwd = make_plan(BH, N, dk, dv, cb, CHELA_DTYPE_BF16, false, false);   // both calls tile with the same chunk
+    t.save_every = 1;
+    if (BH <= 0 || N <= 0) return t;
+    const long cps_b = t.bwd.seg_len / cb;             // chunks per backward segment
+    const double want = (double)t.fwd.n_seg / (double)t.bwd.n_seg;
+    long best = 1;
+    double best_d = 1e300;
+    for (long m = 1; m <= cps_b; ++m) {
+        if (cps_b % m) continue;
+        if (((long)N + t.bwd.seg_len / m - 1) / (t.bwd.seg_len / m) > 32768) break;   // segments ride on grid.y
+        const double d = want > (double)m ? want - (double)m : (double)m - want;
+        if (d < best_d) { best_d = d; best = m; }
+    }
+    t.save_every = (int)best;
+    t.fwd.seg_len = (int)(t.bwd.seg_len / best);
+    t.fwd.n_seg = (int)(((long)N + t.fwd.seg_len - 1) / t.fwd.seg_len);
+    t.fwd.ws_bytes = t.fwd.n_seg > 1 ? (size_t)BH * t.fwd.n_seg * t.fwd.state_elems * sizeof(float) : 0;
+    // the backward only needs the suffix array now
+    t.bwd.ws_bytes = t.bwd.n_seg > 1 ? (size_t)BH * t.bwd.n_seg * t.bwd.state_elems * sizeof(float) : 0;
+    return t;
+}
+
 // Non-causal form: the pre-pass is the only part that is split, and only to fill the GPU (about four workgroups per
 // compute unit), in pieces of at least 256 tokens.
 Plan make_noncausal_plan(long BH, int N, int dk, int dv, bool is_bwd)
@@ -254,7 +284,7 @@ static int fwd_common(const void* Q, const void* K, const void* V, void* O, cons
     rc = get_workspace(plan.ws_bytes, &ws);
     if (rc != CHELA_OK) return rc;
     hipError_t e = dtype == CHELA_DTYPE_BF16
-        ? launch_bf16_fwd(Q, K, V, O, S_in, S_out, BH, N, dk, dv, plan, ws, (hipStream_t)stream)
+        ? launch_bf16_fwd(Q, K, V, O, S_in, S_out, nullptr, 1, BH, N, dk, dv, plan, ws, (hipStream_t)stream)
         : launch_f32((const float*)Q, (const float*)K, (const float*)V, (float*)O, BH, N, dk, dv, plan, false, ws,
                      (hipStream_t)stream);
     return e == hipSuccess ? CHELA_OK : CHELA_ERR_HIP;
@@ -292,7 +322,7 @@ static int bwd_common(const void* Q, const void* K, const void* V, const void* d
         float* ws = nullptr;
         rc = get_workspace(plan.ws_bytes, &ws);
         if (rc != CHELA_OK) return rc;
-        hipError_t e = launch_bf16_bwd(Q, K, V, dO, S_in, dS_out, dQ, dK, dV, dS_in, BH, N, dk, dv, plan, ws, st);
+        hipError_t e = launch_bf16_bwd(Q, K, V, dO, S_in, dS_out, dQ, dK, dV, dS_in, nullptr, BH, N, dk, dv, plan, ws, st);
         return e == hipSuccess ? CHELA_OK : CHELA_ERR_HIP;
     }
     // fp32: the gradient is three instances of the forward map (time-reversal duality):
@@ -361,6 +391,52 @@ static int zbwd_common(const void* Z, const float* aff, const void* V, const voi
     if (rc != CHELA_OK) return rc;
     return launch_bf16_zbwd(Z, aff, V, dO, dZ, d_aff, dV, B, H, N, dk, dv, plan, ws, (hipStream_t)stream) == hipSuccess
                ? CHELA_OK : CHELA_ERR_HIP;
+}
+
+static size_t saved_bytes(long BH, const TrainPlans& t) { return (size_t)BH * t.bwd.n_seg * t.bwd.state_elems * sizeof(float); }
+
+static int fwd_save_common(const void* Q, const void* K, const void* V, void* O, void* saved, int B, int H, int N,
+                           int dk, int dv, int chunk, void* stream)
+{
+    const size_t th = (B > 0 && H > 0 && N > 0) ? (size_t)B * H * N : 0;
+    const long BH = (long)B * H;
+    TrainPlans t{};
+    if (th && (dk == 64 || dk == 128) && (dv == 64 || dv == 128) && (chunk == 64 || chunk == 128))
+        t = make_train_plans(BH, N, dk, dv, chunk);
+    const void* in_v[3] = {Q, K, V};
+    const size_t inb[3] = {th * dk * 2, th * dk * 2, th * dv * 2};
+    void* out_v[2] = {O, saved};
+    const size_t outb[2] = {th * dv * 2, th ? saved_bytes(BH, t) : 0};
+    bool empty = false;
+    int rc = validate(in_v, inb, 3, out_v, outb, 2, B, H, N, dk, dv, chunk, CHELA_DTYPE_BF16, &empty);
+    if (rc != CHELA_OK || empty) return rc;
+    float* ws = nullptr;
+    rc = get_workspace(t.fwd.ws_bytes, &ws);
+    if (rc != CHELA_OK) return rc;
+    return launch_bf16_fwd(Q, K, V, O, nullptr, nullptr, (float*)saved, t.save_every, BH, N, dk, dv, t.fwd, ws,
+                           (hipStream_t)stream) == hipSuccess ? CHELA_OK : CHELA_ERR_HIP;
+}
+
+static int bwd_saved_common(const void* Q, const void* K, const void* V, const void* dO, const void* saved, void* dQ,
+                            void* dK, void* dV, int B, int H, int N, int dk, int dv, int chunk, void* stream)
+{
+    const size_t th = (B > 0 && H > 0 && N > 0) ? (size_t)B * H * N : 0;
+    const long BH = (long)B * H;
+    TrainPlans t{};
+    if (th && (dk == 64 || dk == 128) && (dv == 64 || dv == 128) && (chunk == 64 || chunk == 128))
+        t = make_train_plans(BH, N, dk, dv, chunk);
+    const void* in_v[5] = {Q, K, V, dO, saved};
+    const size_t inb[5] = {th * dk * 2, th * dk * 2, th * dv * 2, th * dv * 2, th ? saved_bytes(BH, t) : 0};
+    void* out_v[3] = {dQ, dK, dV};
+    const size_t outb[3] = {th * dk * 2, th * dk * 2, th * dv * 2};
+    bool empty = false;
+    int rc = validate(in_v, inb, 5, out_v, outb, 3, B, H, N, dk, dv, chunk, CHELA_DTYPE_BF16, &empty);
+    if (rc != CHELA_OK || empty) return rc;
+    float* ws = nullptr;
+    rc = get_workspace(t.bwd.ws_bytes, &ws);
+    if (rc != CHELA_OK) return rc;
+    return launch_bf16_bwd(Q, K, V, dO, nullptr, nullptr, dQ, dK, dV, nullptr, (const float*)saved, BH, N, dk, dv,
+                           t.bwd, ws, (hipStream_t)stream) == hipSuccess ? CHELA_OK : CHELA_ERR_HIP;
 }
 
 static int noncausal_common(const void* Q, const void* K, const void* V, const void* dO, void* O_or_dQ, void* dK,
@@ -448,6 +524,26 @@ size_t chela_linattn_z_workspace_bytes(int B, int H, int N, int dk, int dv, int 
     const long BH = (long)B * H;
     Plan plan = make_plan(BH, N, dk, dv, 64, CHELA_DTYPE_BF16, is_bwd != 0, false);
     return plan.ws_bytes + (is_bwd ? zbwd_extra_ws_bytes(BH, plan, dk) : 0);
+}
+
+int chela_linattn_fwd_save(const void* Q, const void* K, const void* V, void* O, void* saved, int B, int H, int N,
+                           int dk, int dv, int chunk, void* stream)
+{
+    return fwd_save_common(Q, K, V, O, saved, B, H, N, dk, dv, chunk, stream);
+}
+
+int chela_linattn_bwd_saved(const void* Q, const void* K, const void* V, const void* dO, const void* saved, void* dQ,
+                            void* dK, void* dV, int B, int H, int N, int dk, int dv, int chunk, void* stream)
+{
+    return bwd_saved_common(Q, K, V, dO, saved, dQ, dK, dV, B, H, N, dk, dv, chunk, stream);
+}
+
+size_t chela_linattn_saved_bytes(int B, int H, int N, int dk, int dv, int chunk)
+{
+    if (B <= 0 || H <= 0 || N <= 0) return 0;
+    if (!((dk == 64 || dk == 128) && (dv == 64 || dv == 128))) return 0;
+    if (!(chunk == 64 || chunk == 128)) return 0;
+    return saved_bytes((long)B * H, make_train_plans((long)B * H, N, dk, dv, chunk));
 }
 
 int chela_linattn_noncausal_fwd(const void* Q, const void* K, const void* V, void* O, int B, int H, int N, int dk,

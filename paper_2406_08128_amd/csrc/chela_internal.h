@@ -38,11 +38,19 @@ hipError_t launch_f32(const float* Q, const float* K, const float* V, float* O, 
                       const Plan& plan, bool rev, float* ws, hipStream_t st);
 
 // bf16 path.  S_in / S_out / dS_out / dS_in: optional carried states and their gradients, [BH][dk][dv] fp32.
+// saved (optional): the forward writes the running state at the end of every save_every-th of its segments and of
+// the last one, [BH][ceil(n_seg / save_every)][dv][dk] fp32; given to the backward (whose plan must have exactly
+// those segments) it replaces the pre-pass over K and V.
 hipError_t launch_bf16_fwd(const void* Q, const void* K, const void* V, void* O, const float* S_in, float* S_out,
-                           long BH, int N, int dk, int dv, const Plan& plan, float* ws, hipStream_t st);
+                           float* saved, int save_every, long BH, int N, int dk, int dv, const Plan& plan, float* ws,
+                           hipStream_t st);
 hipError_t launch_bf16_bwd(const void* Q, const void* K, const void* V, const void* dO, const float* S_in,
-                           const float* dS_out, void* dQ, void* dK, void* dV, float* dS_in, long BH, int N, int dk,
-                           int dv, const Plan& plan, float* ws, hipStream_t st);
+                           const float* dS_out, void* dQ, void* dK, void* dV, float* dS_in, const float* saved,
+                           long BH, int N, int dk, int dv, const Plan& plan, float* ws, hipStream_t st);
+// The two plans of a forward call that saves states and the backward call that uses them: the backward's segment
+// length is save_every times the forward's.
+struct TrainPlans { Plan fwd, bwd; int save_every; };
+TrainPlans make_train_plans(long BH, int N, int dk, int dv, int chunk);
 // Eq. 11-12 variants: Z [BH][N][dk] stands in for Q and K, aff = [4][H][dk] fp32 (alpha_q, beta_q, alpha_k, beta_k).
 // plan.chunk must be 64.  The backward needs zbwd_extra_ws_bytes() of workspace behind plan.ws_bytes.
 hipError_t launch_bf16_zfwd(const void* Z, const float* aff, const void* V, void* O, int B, int H, int N, int dk,

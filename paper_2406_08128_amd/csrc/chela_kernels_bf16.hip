@@ -427,8 +427,9 @@ template <int C, int DK, int DV, bool ZQK>
 __device__ __forceinline__ void fwd_sweep_body(const bf16* __restrict__ Qb, const bf16* __restrict__ Kb,
                                                const bf16* __restrict__ Vb, bf16* __restrict__ Ob,
                                                const float* __restrict__ S0, float* __restrict__ S_final,
-                                               const float* __restrict__ aff, size_t aff_stride, int ntok,
-                                               unsigned char* lds, int tid, int w, int lane)
+                                               float* __restrict__ S_final_T, const float* __restrict__ aff,
+                                               size_t aff_stride, int ntok, unsigned char* lds, int tid, int w,
+                                               int lane)
 {
     constexpr int LDK = DK + PAD, LDV = DV + PAD;
     constexpr int TB = C / 32, JB = DV / 32, IB = DK / 32;
@@ -511,7 +512,7 @@ __device__ __forceinline__ void fwd_sweep_body(const bf16* __restrict__ Qb, cons
             for (int n = 0; n < NJ; ++n) store_tile_T(rows, DV, (jg * NJ + n) * 32, accO[n], valid, lane);
         }
         // state update S += K^T V (after the segment's last chunk only if the final state is asked for)
-        if (more || S_final != nullptr) {
+        if (more || S_final != nullptr || S_final_T != nullptr) {
 #pragma unroll
             for (int n = 0; n < NS; ++n) {
                 const int id = w + 4 * n, ib = id / JB, jb = id % JB;
@@ -523,6 +524,7 @@ __device__ __forceinline__ void fwd_sweep_body(const bf16* __restrict__ Qb, cons
         __syncthreads();
     }
     if (S_final != nullptr) store_state<DK, DV>(S_final, accS, w, lane);
+    if (S_final_T != nullptr) store_state_T<DK, DV>(S_final_T, accS, w, lane);   // [dv][dk], as the backward reads it
 }
 
 // =============================================================================================== backward sweep body
@@ -909,6 +911,7 @@ __global__ __launch_bounds__(256) void bf16_fwd_sweep_kernel(const bf16* __restr
                                                             const bf16* __restrict__ V, bf16* __restrict__ O,
                                                             const float* __restrict__ S0, float* __restrict__ S_out,
                                                             const float* __restrict__ aff, int H,
+                                                            float* __restrict__ saved, int save_every,
                                                             int first_loads_state, int N, int seg_len, int n_seg)
 {
     __shared__ __attribute__((aligned(16))) unsigned char lds[FwdLds<C, DK, DV, ZQK>::BYTES];
@@ -921,10 +924,17 @@ __global__ __launch_bounds__(256) void bf16_fwd_sweep_kernel(const bf16* __restr
     // S0: scanned start states (segment 0's slot holds the carried-in state, read only if there is one);
     // S_out: final state of the whole sequence, written by the last segment's workgroup
     const bool has_state = S0 != nullptr && (seg > 0 || first_loads_state);
+    // saved: the running state at the end of every save_every-th segment (and of the last one), transposed, for a
+    // backward call that walks segments save_every times as long: [bh][ceil(n_seg / save_every)][dv][dk]
+    float* save_to = nullptr;
+    if (saved != nullptr && ((seg + 1) % save_every == 0 || seg == n_seg - 1)) {
+        const int n_slots = (n_seg + save_every - 1) / save_every, slot = (seg + save_every) / save_every - 1;
+        save_to = saved + ((size_t)bh * n_slots + slot) * DK * DV;
+    }
     fwd_sweep_body<C, DK, DV, ZQK>(Q + rk, ZQK ? nullptr : K + rk, V + rv, O + rv,
                                    has_state ? S0 + ((size_t)bh * n_seg + seg) * DK * DV : nullptr,
                                    (S_out != nullptr && seg == n_seg - 1) ? S_out + (size_t)bh * DK * DV : nullptr,
-                                   ZQK ? aff + (size_t)(bh % H) * DK : nullptr, (size_t)H * DK, p1 - p0, lds, tid, w,
+                                   save_to, ZQK ? aff + (size_t)(bh % H) * DK : nullptr, (size_t)H * DK, p1 - p0, lds, tid, w,
                                    lane);
 }
 
@@ -1051,7 +1061,8 @@ static hipError_t run_seg_state(const SegStateArgs& a, int npairs, const int* sc
 // single segment.
 template <int C, int DK, int DV, bool ZQK>
 static hipError_t fwd_impl(const bf16* Q, const bf16* K, const bf16* V, bf16* O, const float* S_in, float* S_out,
-                           const float* aff, int H, long BH, int N, const Plan& plan, float* ws, hipStream_t st)
+                           const float* aff, int H, float* saved, int save_every, long BH, int N, const Plan& plan,
+                           float* ws, hipStream_t st)
 {
     hipError_t e;
     const bool use_ws = plan.n_seg > 1 || S_in != nullptr;
@@ -1066,7 +1077,8 @@ static hipError_t fwd_impl(const bf16* Q, const bf16* K, const bf16* V, bf16* O,
     dim3 grid((unsigned)BH, plan.n_seg);
     ProfScope prof(KID_FWD_SWEEP_BF16, st);
     hipLaunchKernelGGL((bf16_fwd_sweep_kernel<C, DK, DV, ZQK>), grid, dim3(256), 0, st, Q, K, V, O,
-                       use_ws ? ws : nullptr, S_out, aff, H, S_in != nullptr ? 1 : 0, N, plan.seg_len, plan.n_seg);
+                       use_ws ? ws : nullptr, S_out, aff, H, saved, save_every, S_in != nullptr ? 1 : 0, N,
+                       plan.seg_len, plan.n_seg);
     return hipGetLastError();
 }
 
@@ -1075,10 +1087,28 @@ static hipError_t fwd_impl(const bf16* Q, const bf16* K, const bf16* V, bf16* O,
 template <int C, int DK, int DV, bool ZQK>
 static hipError_t bwd_impl(const bf16* Q, const bf16* K, const bf16* V, const bf16* dO, const float* S_in,
                            const float* dS_out, bf16* dQ, bf16* dK, bf16* dV, float* dS_in, const float* aff,
-                           float* d_aff, int B, int H, int N, const Plan& plan, float* ws, hipStream_t st)
+                           float* d_aff, const float* saved, int B, int H, int N, const Plan& plan, float* ws,
+                           hipStream_t st)
 {
     hipError_t e;
     const long BH = (long)B * H;
+    if (saved != nullptr) {
+        // The forward call left the state at the end of every segment of THIS plan ([bh][seg][dv][dk]): only the
+        // suffix sums of dO^T Q remain to be built, from dO and Q alone.
+        float* wsR = ws;
+        if (plan.n_seg > 1) {
+            SegStateArgs a{};
+            a.X[0] = dO; a.Y[0] = Q; a.out[0] = wsR; a.skip_seg[0] = 0;
+            const int mode = SCAN_EXCL_SUFFIX;
+            if ((e = run_seg_state<DV, DK>(a, 1, &mode, nullptr, false, BH, N, plan, st)) != hipSuccess) return e;
+        }
+        dim3 grid((unsigned)BH, plan.n_seg);
+        ProfScope prof(KID_BWD_SWEEP_BF16, st);
+        hipLaunchKernelGGL((bf16_bwd_sweep_kernel<C, DK, DV, ZQK>), grid, dim3(256), 0, st, Q, K, V, dO, dQ, dK, dV,
+                           saved, plan.n_seg > 1 ? wsR : nullptr, dS_in, aff, H, (float*)nullptr, N, plan.seg_len,
+                           plan.n_seg);
+        return hipGetLastError();
+    }
     const bool use_ws = plan.n_seg > 1 || S_in != nullptr || dS_out != nullptr;
     const size_t state_floats = use_ws ? (size_t)BH * plan.n_seg * DK * DV : 0;
     float* wsS = ws;
@@ -1267,12 +1297,14 @@ hipError_t launch_bf16_noncausal_bwd(const void* Q, const void* K, const void* V
     if (plan.chunk == C_ && dk == DK_ && dv == DV_) return CALL;
 
 hipError_t launch_bf16_fwd(const void* Q, const void* K, const void* V, void* O, const float* S_in, float* S_out,
-                           long BH, int N, int dk, int dv, const Plan& plan, float* ws, hipStream_t st)
+                           float* saved, int save_every, long BH, int N, int dk, int dv, const Plan& plan, float* ws,
+                           hipStream_t st)
 {
     const bf16 *q = (const bf16*)Q, *k = (const bf16*)K, *v = (const bf16*)V;
     bf16* o = (bf16*)O;
-#define CHELA_FWD(C_, DK_, DV_) \
-    CHELA_DISPATCH(C_, DK_, DV_, (fwd_impl<C_, DK_, DV_, false>(q, k, v, o, S_in, S_out, nullptr, 1, BH, N, plan, ws, st)))
+#define CHELA_FWD(C_, DK_, DV_)                                                                                       \
+    CHELA_DISPATCH(C_, DK_, DV_, (fwd_impl<C_, DK_, DV_, false>(q, k, v, o, S_in, S_out, nullptr, 1, saved, save_every, \
+                                                                BH, N, plan, ws, st)))
     CHELA_FWD(64, 64, 64) CHELA_FWD(128, 64, 64) CHELA_FWD(64, 64, 128) CHELA_FWD(128, 64, 128)
     CHELA_FWD(64, 128, 64) CHELA_FWD(128, 128, 64) CHELA_FWD(64, 128, 128) CHELA_FWD(128, 128, 128)
 #undef CHELA_FWD
@@ -1280,14 +1312,14 @@ hipError_t launch_bf16_fwd(const void* Q, const void* K, const void* V, void* O,
 }
 
 hipError_t launch_bf16_bwd(const void* Q, const void* K, const void* V, const void* dO, const float* S_in,
-                           const float* dS_out, void* dQ, void* dK, void* dV, float* dS_in, long BH, int N, int dk,
-                           int dv, const Plan& plan, float* ws, hipStream_t st)
+                           const float* dS_out, void* dQ, void* dK, void* dV, float* dS_in, const float* saved,
+                           long BH, int N, int dk, int dv, const Plan& plan, float* ws, hipStream_t st)
 {
     const bf16 *q = (const bf16*)Q, *k = (const bf16*)K, *v = (const bf16*)V, *g = (const bf16*)dO;
     bf16 *dq = (bf16*)dQ, *dkk = (bf16*)dK, *dvv = (bf16*)dV;
 #define CHELA_BWD(C_, DK_, DV_)                                                                                       \
     CHELA_DISPATCH(C_, DK_, DV_, (bwd_impl<C_, DK_, DV_, false>(q, k, v, g, S_in, dS_out, dq, dkk, dvv, dS_in, nullptr, \
-                                                                nullptr, (int)BH, 1, N, plan, ws, st)))
+                                                                nullptr, saved, (int)BH, 1, N, plan, ws, st)))
     CHELA_BWD(64, 64, 64) CHELA_BWD(128, 64, 64) CHELA_BWD(64, 64, 128) CHELA_BWD(64, 128, 64) CHELA_BWD(64, 128, 128)
 #undef CHELA_BWD
     return hipErrorInvalidValue;
@@ -1301,7 +1333,7 @@ hipError_t launch_bf16_zfwd(const void* Z, const float* aff, const void* V, void
     bf16* o = (bf16*)O;
     const long BH = (long)B * H;
 #define CHELA_ZFWD(DK_, DV_) \
-    CHELA_DISPATCH(64, DK_, DV_, (fwd_impl<64, DK_, DV_, true>(z, nullptr, v, o, nullptr, nullptr, aff, H, BH, N, plan, ws, st)))
+    CHELA_DISPATCH(64, DK_, DV_, (fwd_impl<64, DK_, DV_, true>(z, nullptr, v, o, nullptr, nullptr, aff, H, nullptr, 1, BH, N, plan, ws, st)))
     CHELA_ZFWD(64, 64) CHELA_ZFWD(64, 128) CHELA_ZFWD(128, 64) CHELA_ZFWD(128, 128)
 #undef CHELA_ZFWD
     return hipErrorInvalidValue;
@@ -1314,7 +1346,7 @@ hipError_t launch_bf16_zbwd(const void* Z, const float* aff, const void* V, cons
     bf16 *dz = (bf16*)dZ, *dvv = (bf16*)dV;
 #define CHELA_ZBWD(DK_, DV_)                                                                                       \
     CHELA_DISPATCH(64, DK_, DV_, (bwd_impl<64, DK_, DV_, true>(z, nullptr, v, g, nullptr, nullptr, dz, nullptr, dvv, \
-                                                               nullptr, aff, d_aff, B, H, N, plan, ws, st)))
+                                                               nullptr, aff, d_aff, nullptr, B, H, N, plan, ws, st)))
     CHELA_ZBWD(64, 64) CHELA_ZBWD(64, 128) CHELA_ZBWD(128, 64) CHELA_ZBWD(128, 128)
 #undef CHELA_ZBWD
     return hipErrorInvalidValue;

@@ -136,6 +136,24 @@ def test_z_entry_point_argument_errors(L):
     assert big > plain and (big - plain) % (48 * 4 * 64 * 4) == 0
 
 
+def test_training_pair_argument_errors(L):
+    f, g, sb = L.chela_linattn_fwd_save, L.chela_linattn_bwd_saved, L.chela_linattn_saved_bytes
+    Q, K, V, O, SV = A, A + SZ, A + 2 * SZ, A + 3 * SZ, A + 8 * SZ
+    assert sb(1, 1, 64, 64, 64, 64) == 64 * 64 * 4              # one segment: the state at the end of the sequence
+    assert sb(0, 1, 64, 64, 64, 64) == 0 and sb(1, 1, 64, 64, 96, 64) == 0 and sb(1, 1, 64, 64, 64, 32) == 0
+    big = sb(4, 12, 16384, 64, 64, 64)
+    assert big > 0 and big % (48 * 64 * 64 * 4) == 0 and big // (48 * 64 * 64 * 4) <= 64
+    assert f(Q, K, V, O, None, 1, 1, 64, 64, 64, 64, None) == -1
+    assert f(Q, K, V, O, SV + 4, 1, 1, 64, 64, 64, 64, None) == -5
+    assert f(Q, K, V, O, O, 1, 1, 64, 64, 64, 64, None) == -6
+    assert f(Q, K, V, O, SV, 1, 1, 64, 64, 64, 16, None) == -4
+    assert f(None, None, None, None, None, 1, 1, 0, 64, 64, 64, None) == 0
+    dO, dQ, dK, dV = A + 3 * SZ, A + 4 * SZ, A + 5 * SZ, A + 6 * SZ
+    assert g(Q, K, V, dO, None, dQ, dK, dV, 1, 1, 64, 64, 64, 64, None) == -1
+    assert g(Q, K, V, dO, SV, dQ, SV, dV, 1, 1, 64, 64, 64, 64, None) == -6      # dK on top of the saved states
+    assert g(Q, K, V, dO, SV, dQ, dK, dV, 1, 1, 64, 128, 256, 64, None) == -3
+
+
 def test_noncausal_argument_errors(L):
     f, g, w = L.chela_linattn_noncausal_fwd, L.chela_linattn_noncausal_bwd, L.chela_linattn_noncausal_workspace_bytes
     Q, K, V, O = A, A + SZ, A + 2 * SZ, A + 3 * SZ

@@ -495,3 +495,60 @@ def test_noncausal_last_token_equals_causal_last_token_and_determinism():
     assert oracle.rel_l2(to_f64_numpy(O1[:, :, -1]), to_f64_numpy(Oc[:, :, -1])) <= 1e-2
     e = torch.empty((2, 2, 0, 64), dtype=torch.bfloat16, device="cuda")
     assert binding.chela_linattn_noncausal_fwd(e, e, e).numel() == 0
+
+
+# ------------------------------------------------------------------------------------------ training pair
+TRAIN_SHAPES = [(1, 1, 64, 64, 64, 64), (2, 3, 1000, 64, 64, 64), (1, 2, 9000, 64, 64, 64), (1, 2, 9000, 64, 64, 128),
+                (3, 2, 1100, 64, 128, 64), (1, 2, 5000, 128, 64, 64), (2, 1, 4100, 128, 128, 128), (1, 1, 1, 64, 64, 64)]
+
+
+@pytest.mark.parametrize("shape", TRAIN_SHAPES)
+def test_fwd_save_bwd_saved_small(shape):
+    B, H, N, dk, dv, chunk = shape
+    w = shrink(WORKLOADS["lm_bf16"], B=B, H=H, N=N, dk=dk, dv=dv, seed=120 + N)
+    x = make_inputs(w, with_dO=True)
+    d = _dev(x)
+    O, saved = binding.chela_linattn_fwd_save(d["Q"], d["K"], d["V"], chunk=chunk)
+    dQ, dK, dV = binding.chela_linattn_bwd_saved(d["Q"], d["K"], d["V"], d["dO"], saved, chunk=chunk)
+    torch.cuda.synchronize()
+    Qn, Kn, Vn, Gn = (to_f64_numpy(x[n]) for n in ("Q", "K", "V", "dO"))
+    _check("O", O, oracle.fwd_recurrent(Qn, Kn, Vn), "bf16")
+    for name, got, r in zip(("dQ", "dK", "dV"), (dQ, dK, dV), oracle.bwd_recurrent(Qn, Kn, Vn, Gn)):
+        _check(name, got, r, "bf16")
+
+
+def test_training_pair_lm_full_size_sampled():
+    w = WORKLOADS["lm_bf16"]
+    x = make_inputs(w, with_dO=True)
+    d = _dev(x)
+    O, saved = binding.chela_linattn_fwd_save(d["Q"], d["K"], d["V"])
+    dQ, dK, dV = binding.chela_linattn_bwd_saved(d["Q"], d["K"], d["V"], d["dO"], saved)
+    torch.cuda.synchronize()
+    idx = torch.tensor(_sample_heads(w))
+    sel = lambda t: t.reshape(1, w.B * w.H, w.N, -1)[:, idx.to(t.device)]
+    Qn, Kn, Vn, Gn = (to_f64_numpy(sel(x[n])) for n in ("Q", "K", "V", "dO"))
+    _check("O", sel(O), oracle.fwd_recurrent(Qn, Kn, Vn), "bf16")
+    for name, got, r in zip(("dQ", "dK", "dV"), (dQ, dK, dV), oracle.bwd_recurrent(Qn, Kn, Vn, Gn)):
+        _check(name, sel(got), r, "bf16")
+    # the saved states are the oracle's running state K^T V at the backward's segment ends (last slot = whole sequence)
+    n_slots = saved.numel() // (w.B * w.H * w.dk * w.dv)
+    sv = saved.view(w.B * w.H, n_slots, w.dv, w.dk)
+    last = to_f64_numpy(sv[idx.to(sv.device), n_slots - 1])
+    want = np.einsum("hsi,hsj->hji", Kn[0], Vn[0])
+    assert oracle.rel_l2(last, want) <= 1e-3
+
+
+def test_training_pair_many_heads_single_segment():
+    # 256 or more (b,h) pairs: one segment per pair, the backward then reads nothing but the end state
+    w = shrink(WORKLOADS["lra_bf16"], B=32, H=8, N=700, seed=131)
+    x = make_inputs(w, with_dO=True)
+    d = _dev(x)
+    O, saved = binding.chela_linattn_fwd_save(d["Q"], d["K"], d["V"])
+    dQ, dK, dV = binding.chela_linattn_bwd_saved(d["Q"], d["K"], d["V"], d["dO"], saved)
+    torch.cuda.synchronize()
+    idx = torch.tensor([0, 100, 255])
+    sel = lambda t: t.reshape(1, w.B * w.H, w.N, -1)[:, idx.to(t.device)]
+    Qn, Kn, Vn, Gn = (to_f64_numpy(sel(x[n])) for n in ("Q", "K", "V", "dO"))
+    _check("O", sel(O), oracle.fwd_recurrent(Qn, Kn, Vn), "bf16")
+    for name, got, r in zip(("dQ", "dK", "dV"), (dQ, dK, dV), oracle.bwd_recurrent(Qn, Kn, Vn, Gn)):
+        _check(name, sel(got), r, "bf16")
