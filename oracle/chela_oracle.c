@@ -278,3 +278,52 @@ void chela_oracle_step(const double *q, const double *k, const double *v, double
         }
     }
 }
+
+/* ======================================================================================================
+ * Short-long convolutions, CHELA Sec. 4.2 Eq. 8:  Z = K_l( silu( K_s(X) ) ).
+ * Depthwise (one kernel per channel), causal, zero history; tensors are [B][d][L] (time fastest).
+ *   K_s : short kernel w[c][0..m-1]   (the paper's two parallel short kernels, of size 3 and 2 log10(L) + 1,
+ *         summed tap by tap into one -- the structural re-parameterisation the section describes);
+ *   silu: x / (1 + exp(-x));
+ *   K_l : long kernel k[c][0..L-1], as long as the sequence (Sec. 2.3, "Long convolution").
+ * Eq. 7 evaluates K_l by FFT; what it evaluates is the convolution sum, which is written out here:
+ *   y[t] = sum_{s=0..t} k[s] * v[t-s].
+ * O(L^2) per channel on purpose.
+ * ====================================================================================================== */
+#include <math.h>
+
+/* V[b][c][t] = act( sum_{j=0..min(m-1,t)} w[c][j] * X[b][c][t-j] ),  act = silu if apply_silu else identity */
+void chela_oracle_short_conv(const double *X, const double *w, double *V, int B, int d, int L, int m,
+                             int apply_silu)
+{
+    const long BD = (long)B * d;
+#pragma omp parallel for schedule(static)
+    for (long bc = 0; bc < BD; ++bc) {
+        const int c = (int)(bc % d);
+        const double *x = X + bc * (long)L;
+        double *v = V + bc * (long)L;
+        for (int t = 0; t < L; ++t) {
+            double a = 0.0;
+            for (int j = 0; j < m && j <= t; ++j) a += w[(long)c * m + j] * x[t - j];
+            v[t] = apply_silu ? a / (1.0 + exp(-a)) : a;
+        }
+    }
+}
+
+/* Y[b][c][t] = sum_{s=0..t} k[c][s] * V[b][c][t-s] */
+void chela_oracle_long_conv(const double *V, const double *k, double *Y, int B, int d, int L)
+{
+    const long BD = (long)B * d;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long bc = 0; bc < BD; ++bc) {
+        const int c = (int)(bc % d);
+        const double *v = V + bc * (long)L;
+        const double *kc = k + (long)c * L;
+        double *y = Y + bc * (long)L;
+        for (int t = 0; t < L; ++t) {
+            double a = 0.0;
+            for (int s = 0; s <= t; ++s) a += kc[s] * v[t - s];
+            y[t] = a;
+        }
+    }
+}
