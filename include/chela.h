@@ -158,6 +158,27 @@ int chela_linattn_noncausal_bwd(const void *Q, const void *K, const void *V, con
                                 int B, int H, int N, int dk, int dv, void *stream);
 size_t chela_linattn_noncausal_workspace_bytes(int B, int H, int N, int dk, int dv, int is_bwd);
 
+/* ---- short-long convolutions (Sec. 4.2, Eq. 8): Z = K_l( silu( K_s(X) ) ), the other half of the token mixer -----
+ * Depthwise (one kernel per channel) and causal with zero history:
+ *     v[b,c,t] = silu( sum_{j<m, j<=t} w_short[c,j] * X[b,c,t-j] ),   Z[b,c,t] = sum_{s<=t} k_long[c,s] * v[b,c,t-s].
+ *   X, Z     : [B, d, L] (time fastest), bf16 (plain name) or fp32 (_f32); fp32 arithmetic throughout.
+ *   w_short  : [d, m] fp32, 1 <= m <= 32: the paper's two parallel short kernels (sizes 3 and 2 log10(L) + 1) summed
+ *              tap by tap into one, i.e. after the structural re-parameterisation of Sec. 4.2.  NULL: no short kernel
+ *              and no activation (v = X), a plain long convolution.
+ *   k_long   : [d, L] fp32, as long as the sequence.  It enters through its spectrum (Eq. 7: y = F^-1 D_K F u):
+ *              chela_longconv_spectrum() turns k_long into `spectrum`, an opaque device buffer of
+ *              chela_longconv_spectrum_bytes(d, L) bytes that is valid for this d and L and is reused for every batch
+ *              until the kernel's weights change.
+ * Sequences are zero-padded on chip to twice a transform length M >= L (M in {256, 1024, 4096, 16384}), which makes
+ * the circular product of Eq. 7 equal the causal sum; L > 16384 is rejected (CHELA_ERR_BAD_SHAPE).  Forward only.
+ * No scratch.  Pointers 16-byte aligned; Z must not overlap an input.  Everything else as for the calls above. */
+size_t chela_longconv_spectrum_bytes(int d, int L);
+int chela_longconv_spectrum(const float *k_long, void *spectrum, int d, int L, void *stream);
+int chela_shortlong_conv_fwd(const void *X, const float *w_short, int m, const void *spectrum, void *Z,
+                             int B, int d, int L, void *stream);
+int chela_shortlong_conv_fwd_f32(const void *X, const float *w_short, int m, const void *spectrum, void *Z,
+                                 int B, int d, int L, void *stream);
+
 /* One decode step of autoregressive inference (the recurrent form, one token per (b,h)):
  *     S += k v^T  (in place, fp32) ;  o = S^T q.
  * q, k: [B, H, dk] bf16; v, o: [B, H, dv] bf16; S: [B, H, dk, dv] fp32.  Needs no scratch. */

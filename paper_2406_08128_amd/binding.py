@@ -65,6 +65,14 @@ def lib() -> ctypes.CDLL:
     L.chela_linattn_noncausal_bwd.restype = i
     L.chela_linattn_noncausal_workspace_bytes.argtypes = [i, i, i, i, i, i]
     L.chela_linattn_noncausal_workspace_bytes.restype = sz
+    L.chela_longconv_spectrum_bytes.argtypes = [i, i]
+    L.chela_longconv_spectrum_bytes.restype = sz
+    L.chela_longconv_spectrum.argtypes = [vp, vp, i, i, vp]
+    L.chela_longconv_spectrum.restype = i
+    for name in ("chela_shortlong_conv_fwd", "chela_shortlong_conv_fwd_f32"):
+        f = getattr(L, name)
+        f.argtypes = [vp, vp, i, vp, vp, i, i, i, vp]
+        f.restype = i
     L.chela_linattn_step.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, vp]
     L.chela_linattn_step.restype = i
     L.chela_linattn_workspace_bytes.argtypes = [i, i, i, i, i, i, i, i]
@@ -309,6 +317,41 @@ def chela_linattn_zbwd(Z, affine, V, dO, chunk: int = 64, stream=None):
 
 def chela_linattn_z_workspace_bytes(B, H, N, dk, dv, chunk, is_bwd) -> int:
     return int(lib().chela_linattn_z_workspace_bytes(B, H, N, dk, dv, chunk, int(bool(is_bwd))))
+
+
+def chela_longconv_spectrum(k_long, stream=None):
+    """Spectrum buffer of a long kernel k_long [d, L] (float32): computed once, reused for every batch."""
+    if k_long.dim() != 2 or k_long.dtype != torch.float32 or not k_long.is_cuda or not k_long.is_contiguous():
+        raise ValueError("k_long must be a contiguous float32 device tensor [d, L]")
+    d, Lseq = k_long.shape
+    nbytes = int(lib().chela_longconv_spectrum_bytes(d, Lseq))
+    if nbytes == 0 and d * Lseq > 0:
+        raise ValueError("sequence length %d is not supported by the long convolution" % Lseq)
+    spec = torch.empty(max(nbytes, 16) // 4, dtype=torch.float32, device=k_long.device)
+    with torch.cuda.device(k_long.device):
+        _check(lib().chela_longconv_spectrum(k_long.data_ptr(), spec.data_ptr(), d, Lseq, _stream_ptr(stream)))
+    return spec
+
+
+def chela_shortlong_conv_fwd(X, w_short, spectrum, Z=None, stream=None):
+    """Z = K_l(silu(K_s(X))) for X [B, d, L] (bf16 or float32); w_short [d, m] float32 or None; spectrum from
+    chela_longconv_spectrum for the same d and L."""
+    if X.dim() != 3 or not X.is_cuda or not X.is_contiguous():
+        raise ValueError("X must be a contiguous device tensor [B, d, L]")
+    sfx, _ = _suffix(X)
+    B, d, Lseq = X.shape
+    m, wp = 0, None
+    if w_short is not None:
+        if (w_short.dim() != 2 or w_short.shape[0] != d or w_short.dtype != torch.float32 or not w_short.is_cuda
+                or not w_short.is_contiguous()):
+            raise ValueError("w_short must be a contiguous float32 device tensor [d, m]")
+        m, wp = w_short.shape[1], w_short.data_ptr()
+    if Z is None:
+        Z = torch.empty_like(X)
+    f = getattr(lib(), "chela_shortlong_conv_fwd" + sfx)
+    with torch.cuda.device(X.device):
+        _check(f(X.data_ptr(), wp, m, spectrum.data_ptr(), Z.data_ptr(), B, d, Lseq, _stream_ptr(stream)))
+    return Z
 
 
 def chela_linattn_step(q, k, v, S, o=None, stream=None):

@@ -147,7 +147,7 @@ static std::vector<ProfRec> g_prof_free;     // event pairs to re-use
 static const char* const kKernelNames[KID_COUNT] = {
     "bf16_seg_state_kernel", "scan_states_kernel", "bf16_fwd_sweep_kernel", "bf16_bwd_sweep_kernel",
     "f32_seg_state_kernel", "f32_sweep_kernel", "copy_probe_kernel", "bf16_step_kernel", "affine_grad_kernel",
-    "bf16_apply_state_kernel"};
+    "bf16_apply_state_kernel", "longconv_spectrum_kernel", "shortlong_conv_kernel"};
 
 ProfScope::ProfScope(int id, hipStream_t s) : slot(-1), st(s)
 {
@@ -563,6 +563,55 @@ size_t chela_linattn_noncausal_workspace_bytes(int B, int H, int N, int dk, int 
     if (B <= 0 || H <= 0 || N <= 0) return 0;
     if (!((dk == 64 || dk == 128) && (dv == 64 || dv == 128))) return 0;
     return make_noncausal_plan((long)B * H, N, dk, dv, is_bwd != 0).ws_bytes;
+}
+
+size_t chela_longconv_spectrum_bytes(int d, int L)
+{
+    const int M = (d > 0 && L > 0) ? conv_fft_size(L) : 0;
+    return M ? (size_t)d * (size_t)(M + 1) * 2 * sizeof(float) : 0;
+}
+
+int chela_longconv_spectrum(const float* k_long, void* spectrum, int d, int L, void* stream)
+{
+    if (d < 0 || L < 0) return CHELA_ERR_BAD_SHAPE;
+    if (d == 0 || L == 0) return CHELA_OK;
+    if (conv_fft_size(L) == 0) return CHELA_ERR_BAD_SHAPE;
+    if (!k_long || !spectrum) return CHELA_ERR_NULL_POINTER;
+    if (((uintptr_t)k_long | (uintptr_t)spectrum) & 15u) return CHELA_ERR_MISALIGNED;
+    if (overlap(Range{(const char*)k_long, (size_t)d * L * 4}, Range{(const char*)spectrum, chela_longconv_spectrum_bytes(d, L)}))
+        return CHELA_ERR_ALIASING;
+    return launch_longconv_spectrum(k_long, spectrum, d, L, (hipStream_t)stream) == hipSuccess ? CHELA_OK : CHELA_ERR_HIP;
+}
+
+static int shortlong_common(const void* X, const float* w_short, int m, const void* spectrum, void* Y, int B, int d,
+                            int L, int dtype, void* stream)
+{
+    if (B < 0 || d < 0 || L < 0) return CHELA_ERR_BAD_SHAPE;
+    if (w_short != nullptr && (m < 1 || m > 32)) return CHELA_ERR_BAD_SHAPE;
+    if ((unsigned long long)B * (unsigned long long)d > 0x7fffffffull) return CHELA_ERR_BAD_SHAPE;
+    if (B == 0 || d == 0 || L == 0) return CHELA_OK;
+    if (conv_fft_size(L) == 0) return CHELA_ERR_BAD_SHAPE;
+    if (!X || !spectrum || !Y) return CHELA_ERR_NULL_POINTER;
+    if (((uintptr_t)X | (uintptr_t)spectrum | (uintptr_t)Y | (uintptr_t)w_short) & 15u) return CHELA_ERR_MISALIGNED;
+    const size_t es = dtype == CHELA_DTYPE_BF16 ? 2 : 4, tb = (size_t)B * d * L * es;
+    const Range ry{(const char*)Y, tb};
+    if (overlap(ry, Range{(const char*)X, tb}) || overlap(ry, Range{(const char*)spectrum, chela_longconv_spectrum_bytes(d, L)}) ||
+        (w_short && overlap(ry, Range{(const char*)w_short, (size_t)d * m * 4})))
+        return CHELA_ERR_ALIASING;
+    return launch_shortlong_conv(X, w_short, m, spectrum, Y, (long)B * d, d, L, dtype == CHELA_DTYPE_BF16 ? 0 : 1,
+                                 (hipStream_t)stream) == hipSuccess ? CHELA_OK : CHELA_ERR_HIP;
+}
+
+int chela_shortlong_conv_fwd(const void* X, const float* w_short, int m, const void* spectrum, void* Y, int B, int d,
+                             int L, void* stream)
+{
+    return shortlong_common(X, w_short, m, spectrum, Y, B, d, L, CHELA_DTYPE_BF16, stream);
+}
+
+int chela_shortlong_conv_fwd_f32(const void* X, const float* w_short, int m, const void* spectrum, void* Y, int B,
+                                 int d, int L, void* stream)
+{
+    return shortlong_common(X, w_short, m, spectrum, Y, B, d, L, CHELA_DTYPE_F32, stream);
 }
 
 int chela_linattn_step(const void* q, const void* k, const void* v, float* S, void* o, int B, int H, int dk, int dv,

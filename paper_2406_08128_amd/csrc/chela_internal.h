@@ -72,9 +72,16 @@ hipError_t launch_bf16_noncausal_bwd(const void* Q, const void* K, const void* V
 hipError_t launch_bf16_step(const void* q, const void* k, const void* v, float* S, void* o, long BH, int dk, int dv,
                             hipStream_t st);
 
+// Short-long convolutions (Sec. 4.2).  conv_fft_size(L): length M of the complex transform used for sequences of
+// L steps (0: L too long); the kernel spectrum is [d][M + 1] complex fp32.  dtype 0: bf16 I/O, 1: fp32 I/O.
+int conv_fft_size(int L);
+hipError_t launch_longconv_spectrum(const float* k, void* Kf, int d, int L, hipStream_t st);
+hipError_t launch_shortlong_conv(const void* X, const float* w_short, int m, const void* Kf, void* Y, long BD, int d,
+                                 int L, int dtype, hipStream_t st);
+
 // Kernel classes for the per-kernel timing aid.
 enum { KID_SEG_STATE_BF16 = 0, KID_SCAN = 1, KID_FWD_SWEEP_BF16 = 2, KID_BWD_SWEEP_BF16 = 3, KID_SEG_STATE_F32 = 4,
-       KID_SWEEP_F32 = 5, KID_COPY = 6, KID_STEP_BF16 = 7, KID_AFFINE_GRAD = 8, KID_APPLY_BF16 = 9, KID_COUNT = 10 };
+       KID_SWEEP_F32 = 5, KID_COPY = 6, KID_STEP_BF16 = 7, KID_AFFINE_GRAD = 8, KID_APPLY_BF16 = 9, KID_CONV_SPECTRUM = 10, KID_CONV_FWD = 11, KID_COUNT = 12 };
 
 // Brackets one kernel launch with HIP events on its stream while profiling is enabled; otherwise does nothing.
 struct ProfScope {

@@ -1,0 +1,403 @@
+// Short-long convolutions (Sec. 4.2, Eq. 8): Z = K_l( silu( K_s(X) ) ), depthwise and causal, tensors [B][d][L].
+//
+// The long kernel is as long as the sequence, so K_l goes through the Fourier domain (Eq. 7).  One workgroup
+// owns one (batch, channel) sequence and never leaves the chip between load and store:
+//   load x, short kernel + silu  ->  real sequence v, zero-padded to N = 2M >= 2L (so that the circular product of
+//   Eq. 7 equals the causal sum), packed as M complex numbers z[n] = v[2n] + i v[2n+1]  ->  complex FFT of length M
+//   in LDS  ->  untangle to the spectrum of v, multiply by the kernel's spectrum, tangle back  ->  inverse FFT
+//   ->  y[2n], y[2n+1] = Re, Im.
+// FFT: in place, decimation in frequency forward (natural order in, digit-reversed out) and the exact inverse of
+// every pass in reverse order (digit-reversed in, natural out), so no reordering pass exists; the point-wise
+// stage addresses the spectrum through the digit reversal.  M = 4^a 16^b: an optional leading radix-4 pass, then
+// radix-16 passes with one 16-point transform per thread held in registers (two layers of radix 4).  The LDS
+// array carries one complex of padding per 16, which makes the stride-1 and stride-16 passes conflict-free.
+// Arithmetic is fp32 on the vector ALU: with one kernel per channel there is no operand shared across channels
+// except the DFT matrix itself, and fp32 matrix instructions are no faster than the ALU on this chip.
+#include "chela_internal.h"
+
+namespace chela {
+
+typedef __bf16 bf16;
+
+struct cplx { float x, y; };
+__device__ __forceinline__ cplx mk(float x, float y) { cplx c; c.x = x; c.y = y; return c; }
+__device__ __forceinline__ cplx cadd(cplx a, cplx b) { return mk(a.x + b.x, a.y + b.y); }
+__device__ __forceinline__ cplx csub(cplx a, cplx b) { return mk(a.x - b.x, a.y - b.y); }
+__device__ __forceinline__ cplx cmul(cplx a, cplx b) { return mk(a.x * b.x - a.y * b.y, a.x * b.y + a.y * b.x); }
+__device__ __forceinline__ cplx conj(cplx a) { return mk(a.x, -a.y); }
+__device__ __forceinline__ cplx mul_neg_i(cplx a) { return mk(a.y, -a.x); }   // a * (-i)
+__device__ __forceinline__ cplx mul_pos_i(cplx a) { return mk(-a.y, a.x); }   // a * (+i)
+
+// 4-point DFT, kernel exp(-2 pi i p q / 4) (INV: the conjugate kernel), in place: (a,b,c,d) = x_0..x_3 -> X_0..X_3.
+template <bool INV>
+__device__ __forceinline__ void dft4(cplx& a, cplx& b, cplx& c, cplx& d)
+{
+    const cplx s0 = cadd(a, c), d0 = csub(a, c), s1 = cadd(b, d), d1 = csub(b, d);
+    const cplx r = INV ? mul_pos_i(d1) : mul_neg_i(d1);
+    a = cadd(s0, s1);
+    c = csub(s0, s1);
+    b = cadd(d0, r);
+    d = csub(d0, r);
+}
+
+// 16-point DFT in registers.  In: v[q] = x_q.  Out: X_p sits in slot (p >> 2) + 4 * (p & 3).
+// q = q0 + 4 q1, p = p1 + 4 p0:  X_p = sum_q0 w4^(p0 q0) w16^(p1 q0) [ sum_q1 x_(q0 + 4 q1) w4^(p1 q1) ].
+template <bool INV>
+__device__ __forceinline__ void dft16(cplx (&v)[16])
+{
+#pragma unroll
+    for (int q0 = 0; q0 < 4; ++q0) dft4<INV>(v[q0], v[q0 + 4], v[q0 + 8], v[q0 + 12]);     // slot q0 + 4 p1
+    constexpr float C1 = 0.92387953251128674f, S1 = 0.38268343236508977f, R2 = 0.70710678118654752f;
+    // w16^k = exp(-2 pi i k / 16) for the products q0 * p1 in {1, 2, 3, 4, 6, 9}
+    const cplx w1 = mk(C1, INV ? S1 : -S1), w2 = mk(R2, INV ? R2 : -R2), w3 = mk(S1, INV ? C1 : -C1);
+    const cplx w6 = mk(-R2, INV ? R2 : -R2), w9 = mk(-C1, INV ? -S1 : S1);
+    v[1 + 4 * 1] = cmul(v[1 + 4 * 1], w1);
+    v[2 + 4 * 1] = cmul(v[2 + 4 * 1], w2);
+    v[3 + 4 * 1] = cmul(v[3 + 4 * 1], w3);
+    v[1 + 4 * 2] = cmul(v[1 + 4 * 2], w2);
+    v[2 + 4 * 2] = INV ? mul_pos_i(v[2 + 4 * 2]) : mul_neg_i(v[2 + 4 * 2]);                 // w16^4 = -i
+    v[3 + 4 * 2] = cmul(v[3 + 4 * 2], w6);
+    v[1 + 4 * 3] = cmul(v[1 + 4 * 3], w3);
+    v[2 + 4 * 3] = cmul(v[2 + 4 * 3], w6);
+    v[3 + 4 * 3] = cmul(v[3 + 4 * 3], w9);
+#pragma unroll
+    for (int p1 = 0; p1 < 4; ++p1) dft4<INV>(v[4 * p1], v[4 * p1 + 1], v[4 * p1 + 2], v[4 * p1 + 3]);   // slot p0 + 4 p1
+}
+
+__host__ __device__ constexpr int conv_threads(int M) { return M / 16 < 64 ? 64 : M / 16; }
+__host__ __device__ constexpr bool conv_lead4(int M) { return M == 1024 || M == 16384; }
+__host__ __device__ constexpr int conv_pad(int i) { return i + (i >> 4); }
+
+template <int M>
+struct ConvLds {
+    static constexpr int DATA = conv_pad(M);                 // complex slots
+    static constexpr int BYTES = DATA * 8 + 2 * 128 * 8;     // + two twiddle tables of 128
+};
+
+// exp(-2 pi i e / M) for 0 <= e < M from two tables of 128: lo[x] = W^x, hi[y] = W^(128 y).
+template <int M>
+__device__ __forceinline__ cplx twiddle(const cplx* lo, const cplx* hi, int e)
+{
+    if (M <= 128) return lo[e];
+    return cmul(lo[e & 127], hi[e >> 7]);
+}
+
+// Storage position of spectrum bin k (0 <= k < M) after the forward passes.
+template <int M>
+__device__ __forceinline__ int spectrum_pos(int k)
+{
+    int pos = 0, span = M;
+    if (conv_lead4(M)) { span /= 4; pos += (k & 3) * span; k >>= 2; }
+#pragma unroll
+    for (int s = span; s > 1; s /= 16) { pos += (k & 15) * (s / 16); k >>= 4; }
+    return pos;
+}
+
+// All forward passes (INV = false) or all inverse passes in reverse order (INV = true) over a[] in LDS.
+// A __syncthreads() separates the passes; the caller synchronises before and after.
+template <int M, bool INV>
+__device__ __forceinline__ void fft_passes(cplx* a, const cplx* lo, const cplx* hi, int tid)
+{
+    constexpr int T = conv_threads(M);
+    constexpr int M16 = conv_lead4(M) ? M / 4 : M;     // what the radix-16 passes transform (blocks of this length)
+    auto lead4 = [&]() __attribute__((always_inline)) {
+        constexpr int s = M / 4;
+        for (int g = tid; g < s; g += T) {
+            cplx v0 = a[conv_pad(g)], v1 = a[conv_pad(g + s)], v2 = a[conv_pad(g + 2 * s)], v3 = a[conv_pad(g + 3 * s)];
+            const cplx w1 = twiddle<M>(lo, hi, g);
+            const cplx t1 = INV ? conj(w1) : w1, t2 = cmul(t1, t1), t3 = cmul(t2, t1);
+            if (INV) { v1 = cmul(v1, t1); v2 = cmul(v2, t2); v3 = cmul(v3, t3); }
+            dft4<INV>(v0, v1, v2, v3);
+            if (!INV) { v1 = cmul(v1, t1); v2 = cmul(v2, t2); v3 = cmul(v3, t3); }
+            a[conv_pad(g)] = v0; a[conv_pad(g + s)] = v1; a[conv_pad(g + 2 * s)] = v2; a[conv_pad(g + 3 * s)] = v3;
+        }
+    };
+    auto pass16 = [&](int n) __attribute__((always_inline)) {     // n: current sub-transform length, stride n / 16
+        const int s = n / 16;
+        for (int g = tid; g < M / 16; g += T) {
+            const int block = g / s, j = g - block * s, base = block * n + j;
+            cplx v[16];
+            // twiddles W_n^(j p) = (W_M^(j M / n))^p
+            const cplx w1f = twiddle<M>(lo, hi, j * (M / n));
+            const cplx w1 = INV ? conj(w1f) : w1f;
+            if (INV) {
+                // undo the forward pass: strip the twiddles, then the conjugate 16-point transform (the factor
+                // 1/16 is left to the final scaling); inputs X_p in natural order p, outputs x_q in slot order
+                cplx w = w1;
+                v[0] = a[conv_pad(base)];
+#pragma unroll
+                for (int p = 1; p < 16; ++p) {
+                    v[p] = cmul(a[conv_pad(base + p * s)], w);
+                    w = cmul(w, w1);
+                }
+                dft16<true>(v);
+#pragma unroll
+                for (int q = 0; q < 16; ++q) a[conv_pad(base + q * s)] = v[(q >> 2) + 4 * (q & 3)];
+            } else {
+#pragma unroll
+                for (int q = 0; q < 16; ++q) v[q] = a[conv_pad(base + q * s)];
+                dft16<false>(v);
+                cplx w = w1;
+                a[conv_pad(base)] = v[0];
+#pragma unroll
+                for (int p = 1; p < 16; ++p) {
+                    a[conv_pad(base + p * s)] = cmul(v[(p >> 2) + 4 * (p & 3)], w);
+                    w = cmul(w, w1);
+                }
+            }
+        }
+    };
+    if (!INV) {
+        if (conv_lead4(M)) { lead4(); __syncthreads(); }
+        for (int n = M16; n >= 16; n /= 16) {
+            pass16(n);
+            if (n > 16) __syncthreads();
+        }
+    } else {
+        for (int n = 16; n <= M16; n *= 16) {
+            pass16(n);
+            if (n < M16 || conv_lead4(M)) __syncthreads();
+        }
+        if (conv_lead4(M)) lead4();
+    }
+}
+
+template <typename T> struct IoPair;
+template <> struct IoPair<float> {
+    static __device__ __forceinline__ void load2(const float* p, float& a, float& b) { const float2 v = *reinterpret_cast<const float2*>(p); a = v.x; b = v.y; }
+    static __device__ __forceinline__ void store2(float* p, float a, float b) { *reinterpret_cast<float2*>(p) = make_float2(a, b); }
+};
+template <> struct IoPair<bf16> {
+    static __device__ __forceinline__ void load2(const bf16* p, float& a, float& b)
+    {
+        const unsigned u = *reinterpret_cast<const unsigned*>(p);
+        a = __builtin_bit_cast(float, u << 16);
+        b = __builtin_bit_cast(float, u & 0xffff0000u);
+    }
+    static __device__ __forceinline__ void store2(bf16* p, float a, float b)
+    {
+        typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+        bf16x2 v;
+        v[0] = (bf16)a;
+        v[1] = (bf16)b;
+        *reinterpret_cast<bf16x2*>(p) = v;
+    }
+};
+
+template <int M>
+__device__ __forceinline__ void build_tables(cplx* lo, cplx* hi, int tid)
+{
+    for (int t = tid; t < 128; t += conv_threads(M)) {
+        float s, c;
+        sincospif(-2.0f * (float)t / (float)M, &s, &c);
+        lo[t] = mk(c, s);
+        sincospif(-2.0f * (float)(t * 128 % M) / (float)M, &s, &c);
+        hi[t] = mk(c, s);
+    }
+}
+
+// Spectrum of a real sequence of length 2M from the length-M transform Z of its even/odd packing:
+//   X[k] = (Z[k] + conj Z[M-k]) / 2 + W_2M^k (Z[k] - conj Z[M-k]) / (2i),  k = 0 .. M  (Z[M] = Z[0]).
+// Kernel spectrum of one channel: K[c][0 .. M], complex fp32.
+template <int M>
+__global__ __launch_bounds__(conv_threads(M)) void longconv_spectrum_kernel(const float* __restrict__ k,
+                                                                           float2* __restrict__ Kf, int L)
+{
+    constexpr int T = conv_threads(M);
+    __shared__ __attribute__((aligned(16))) unsigned char lds[ConvLds<M>::BYTES];
+    cplx* a = reinterpret_cast<cplx*>(lds);
+    cplx* lo = a + ConvLds<M>::DATA;
+    cplx* hi = lo + 128;
+    const int tid = threadIdx.x;
+    const long c = blockIdx.x;
+    const float* kc = k + c * (long)L;
+    build_tables<M>(lo, hi, tid);
+    for (int n = tid; n < M; n += T) {
+        const int t = 2 * n;
+        a[conv_pad(n)] = mk(t < L ? kc[t] : 0.f, t + 1 < L ? kc[t + 1] : 0.f);
+    }
+    __syncthreads();
+    fft_passes<M, false>(a, lo, hi, tid);
+    __syncthreads();
+    float2* out = Kf + c * (long)(M + 1);
+    for (int kk = tid; kk <= M / 2; kk += T) {
+        const cplx A = a[conv_pad(spectrum_pos<M>(kk))];
+        const cplx Bc = conj(a[conv_pad(spectrum_pos<M>((M - kk) & (M - 1)))]);
+        const cplx xe = mk(0.5f * (A.x + Bc.x), 0.5f * (A.y + Bc.y));
+        const cplx xo = mul_neg_i(mk(0.5f * (A.x - Bc.x), 0.5f * (A.y - Bc.y)));
+        float s, co;
+        sincospif(-(float)kk / (float)M, &s, &co);
+        const cplx wx = cmul(mk(co, s), xo);
+        const cplx Xk = cadd(xe, wx), Xmk = conj(csub(xe, wx));
+        out[kk] = make_float2(Xk.x, Xk.y);
+        out[M - kk] = make_float2(Xmk.x, Xmk.y);
+    }
+}
+
+// One workgroup per (b, c).  w_short == nullptr: no short kernel and no activation (plain long convolution).
+template <int M, typename IO>
+__global__ __launch_bounds__(conv_threads(M)) void shortlong_conv_kernel(const IO* __restrict__ X,
+                                                                        const float* __restrict__ w_short, int m,
+                                                                        const float2* __restrict__ Kf,
+                                                                        IO* __restrict__ Y, int d, int L)
+{
+    constexpr int T = conv_threads(M);
+    __shared__ __attribute__((aligned(16))) unsigned char lds[ConvLds<M>::BYTES];
+    cplx* a = reinterpret_cast<cplx*>(lds);
+    cplx* lo = a + ConvLds<M>::DATA;
+    cplx* hi = lo + 128;
+    const int tid = threadIdx.x;
+    const long bc = blockIdx.x;
+    const int c = (int)(bc % d);
+    const IO* x = X + bc * (long)L;
+    IO* y = Y + bc * (long)L;
+    const bool vec_ok = (L & 1) == 0;        // rows start on a pair boundary
+    build_tables<M>(lo, hi, tid);
+
+    // ---- load, short kernel, activation, packing
+    if (w_short != nullptr) {
+        float* sx = reinterpret_cast<float*>(a);           // raw x, one float per time step (L <= M floats)
+        for (int n = tid; n < M; n += T) {
+            const int t = 2 * n;
+            if (t < L) {
+                float v0, v1 = 0.f;
+                if (vec_ok) IoPair<IO>::load2(x + t, v0, v1);
+                else { v0 = (float)x[t]; if (t + 1 < L) v1 = (float)x[t + 1]; }
+                sx[t] = v0;
+                sx[t + 1] = v1;
+            }
+        }
+        __syncthreads();
+        constexpr int PER = M / T;
+        cplx z[PER];
+        const float* wc = w_short + (long)c * m;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int t = 2 * (tid + T * i);
+            float acc0 = 0.f, acc1 = 0.f;
+            if (t < L) {
+                for (int j = 0; j < m; ++j) {
+                    const float wj = wc[j];
+                    if (t - j >= 0) acc0 = fmaf(wj, sx[t - j], acc0);
+                    if (t + 1 - j >= 0 && t + 1 < L) acc1 = fmaf(wj, sx[t + 1 - j], acc1);
+                }
+                acc0 = acc0 / (1.f + __expf(-acc0));
+                acc1 = acc1 / (1.f + __expf(-acc1));
+            }
+            z[i] = mk(acc0, acc1);
+        }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < PER; ++i) a[conv_pad(tid + T * i)] = z[i];
+    } else {
+        for (int n = tid; n < M; n += T) {
+            const int t = 2 * n;
+            float v0 = 0.f, v1 = 0.f;
+            if (t < L) {
+                if (vec_ok) IoPair<IO>::load2(x + t, v0, v1);
+                else { v0 = (float)x[t]; if (t + 1 < L) v1 = (float)x[t + 1]; }
+            }
+            a[conv_pad(n)] = mk(v0, v1);
+        }
+    }
+    __syncthreads();
+
+    fft_passes<M, false>(a, lo, hi, tid);
+    __syncthreads();
+
+    // ---- spectrum of v times spectrum of the kernel, re-packed for the inverse transform (pairs k, M - k)
+    const float2* Kc = Kf + (long)c * (M + 1);
+    for (int kk = tid; kk <= M / 2; kk += T) {
+        const int p1 = conv_pad(spectrum_pos<M>(kk)), p2 = conv_pad(spectrum_pos<M>((M - kk) & (M - 1)));
+        const cplx A = a[p1], Bc = conj(a[p2]);
+        const cplx xe = mk(0.5f * (A.x + Bc.x), 0.5f * (A.y + Bc.y));
+        const cplx xo = mul_neg_i(mk(0.5f * (A.x - Bc.x), 0.5f * (A.y - Bc.y)));
+        float s, co;
+        sincospif(-(float)kk / (float)M, &s, &co);
+        const cplx w = mk(co, s);                       // W_2M^k
+        const cplx wx = cmul(w, xo);
+        const float2 k1 = Kc[kk], k2 = Kc[M - kk];
+        const cplx Yk = cmul(cadd(xe, wx), mk(k1.x, k1.y));               // Y[k]
+        const cplx Ymk = cmul(conj(csub(xe, wx)), mk(k2.x, k2.y));        // Y[M-k]
+        // Zy[k] = Ye + i Yo, Zy[M-k] = conj(Ye) + i conj(Yo);  Ye = (Y[k] + conj Y[M-k]) / 2,
+        // Yo = (Y[k] - conj Y[M-k]) / 2 * conj(W_2M^k)
+        const cplx Yc = conj(Ymk);
+        const cplx ye = mk(0.5f * (Yk.x + Yc.x), 0.5f * (Yk.y + Yc.y));
+        const cplx yo = cmul(mk(0.5f * (Yk.x - Yc.x), 0.5f * (Yk.y - Yc.y)), conj(w));
+        const cplx Zk = cadd(ye, mul_pos_i(yo));
+        const cplx Zmk = cadd(conj(ye), mul_pos_i(conj(yo)));
+        if (kk == 0) {
+            // bins 0 and M are real: X[0] = Re + Im, X[M] = Re - Im of Z[0]; they share storage slot 0
+            const float x0 = (A.x + A.y) * k1.x, xm = (A.x - A.y) * k2.x;
+            a[p1] = mk(0.5f * (x0 + xm), 0.5f * (x0 - xm));
+        } else {
+            a[p1] = Zk;
+            if (p2 != p1) a[p2] = Zmk;
+        }
+    }
+    __syncthreads();
+
+    fft_passes<M, true>(a, lo, hi, tid);
+    __syncthreads();
+
+    // ---- unpack, scale, store
+    const float scale = 1.0f / (float)M;
+    for (int n = tid; n < M; n += T) {
+        const int t = 2 * n;
+        if (t < L) {
+            const cplx v = a[conv_pad(n)];
+            if (vec_ok) IoPair<IO>::store2(y + t, v.x * scale, v.y * scale);
+            else { y[t] = (IO)(v.x * scale); if (t + 1 < L) y[t + 1] = (IO)(v.y * scale); }
+        }
+    }
+}
+
+int conv_fft_size(int L)
+{
+    if (L <= 256) return 256;
+    if (L <= 1024) return 1024;
+    if (L <= 4096) return 4096;
+    if (L <= 16384) return 16384;
+    return 0;
+}
+
+hipError_t launch_longconv_spectrum(const float* k, void* Kf, int d, int L, hipStream_t st)
+{
+    const int M = conv_fft_size(L);
+    ProfScope prof(KID_CONV_SPECTRUM, st);
+    float2* out = (float2*)Kf;
+    switch (M) {
+        case 256: hipLaunchKernelGGL((longconv_spectrum_kernel<256>), dim3(d), dim3(conv_threads(256)), 0, st, k, out, L); break;
+        case 1024: hipLaunchKernelGGL((longconv_spectrum_kernel<1024>), dim3(d), dim3(conv_threads(1024)), 0, st, k, out, L); break;
+        case 4096: hipLaunchKernelGGL((longconv_spectrum_kernel<4096>), dim3(d), dim3(conv_threads(4096)), 0, st, k, out, L); break;
+        case 16384: hipLaunchKernelGGL((longconv_spectrum_kernel<16384>), dim3(d), dim3(conv_threads(16384)), 0, st, k, out, L); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+template <typename IO>
+static hipError_t conv_dispatch(const IO* X, const float* w, int m, const float2* Kf, IO* Y, long BD, int d, int L,
+                                hipStream_t st)
+{
+    const int M = conv_fft_size(L);
+    ProfScope prof(KID_CONV_FWD, st);
+    const dim3 grid((unsigned)BD);
+    switch (M) {
+        case 256: hipLaunchKernelGGL((shortlong_conv_kernel<256, IO>), grid, dim3(conv_threads(256)), 0, st, X, w, m, Kf, Y, d, L); break;
+        case 1024: hipLaunchKernelGGL((shortlong_conv_kernel<1024, IO>), grid, dim3(conv_threads(1024)), 0, st, X, w, m, Kf, Y, d, L); break;
+        case 4096: hipLaunchKernelGGL((shortlong_conv_kernel<4096, IO>), grid, dim3(conv_threads(4096)), 0, st, X, w, m, Kf, Y, d, L); break;
+        case 16384: hipLaunchKernelGGL((shortlong_conv_kernel<16384, IO>), grid, dim3(conv_threads(16384)), 0, st, X, w, m, Kf, Y, d, L); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_shortlong_conv(const void* X, const float* w_short, int m, const void* Kf, void* Y, long BD, int d,
+                                 int L, int dtype, hipStream_t st)
+{
+    if (dtype == 0) return conv_dispatch<bf16>((const bf16*)X, w_short, m, (const float2*)Kf, (bf16*)Y, BD, d, L, st);
+    return conv_dispatch<float>((const float*)X, w_short, m, (const float2*)Kf, (float*)Y, BD, d, L, st);
+}
+
+}  // namespace chela

@@ -112,6 +112,22 @@ def make_z_inputs(w: Workload, with_dO: Optional[bool] = None) -> Dict[str, torc
     return out
 
 
+def make_conv_inputs(B: int, d: int, L: int, m: int, seed: int, dtype: str = "bf16") -> Dict[str, torch.Tensor]:
+    """Inputs for the short-long convolution: {"X" [B,d,L], "w_short" [d,m], "k_long" [d,L]}.
+
+    Recipe: generator seeded with seed + 2000; torch.randn in fp32 in the order X, n_w [d,m], n_k [d,L];
+    w_short = n_w / m; k_long[c,t] = n_k[c,t] * exp(-4 t / L) * sqrt(8 / L): a decaying kernel as long as the sequence
+    with unit energy, so that outputs stay of order one; X is cast to the I/O dtype last, the kernels stay fp32."""
+    g = torch.Generator(device="cpu")
+    g.manual_seed(seed + 2000)
+    x = torch.randn(B, d, L, generator=g, dtype=torch.float32)
+    nw = torch.randn(d, m, generator=g, dtype=torch.float32)
+    nk = torch.randn(d, L, generator=g, dtype=torch.float32)
+    t = torch.arange(L, dtype=torch.float32)
+    k_long = (nk * torch.exp(-4.0 * t / L)[None, :] * (8.0 / L) ** 0.5).contiguous()
+    return {"X": x.to(_torch_dtype(dtype)).contiguous(), "w_short": (nw / m).contiguous(), "k_long": k_long}
+
+
 def to_f64_numpy(t: torch.Tensor):
     """Exact up-cast of an fp32/bf16 tensor to a float64 numpy array (oracle input)."""
     return t.detach().to("cpu").to(torch.float64).numpy()

@@ -174,6 +174,25 @@ def test_noncausal_argument_errors(L):
     assert w(4, 12, 1 << 20, 64, 64, 0) <= 1100 * 64 * 64 * 4
 
 
+def test_conv_argument_errors(L):
+    sb, sp, f = L.chela_longconv_spectrum_bytes, L.chela_longconv_spectrum, L.chela_shortlong_conv_fwd
+    assert sb(3, 16384) == 3 * 16385 * 8 and sb(3, 16385) == 0 and sb(0, 64) == 0
+    assert sb(2, 257) == 2 * 1025 * 8 and sb(2, 256) == 2 * 257 * 8 and sb(1, 1) == 257 * 8
+    K, S, X, W, Y = A, A + SZ, A + 2 * SZ, A + 3 * SZ, A + 4 * SZ
+    assert sp(None, S, 4, 100, None) == -1
+    assert sp(K, S + 8, 4, 100, None) == -5
+    assert sp(K, S, 4, 20000, None) == -2
+    assert sp(K, K, 4, 100, None) == -6
+    assert sp(K, S, 0, 100, None) == 0
+    assert f(None, W, 9, S, Y, 2, 4, 100, None) == -1
+    assert f(X, W, 0, S, Y, 2, 4, 100, None) == -2
+    assert f(X, W, 33, S, Y, 2, 4, 100, None) == -2
+    assert f(X, W, 9, S, Y, 2, 4, 16385, None) == -2
+    assert f(X, W, 9, S, X, 2, 4, 100, None) == -6
+    assert f(X, W, 9, S, Y + 6, 2, 4, 100, None) == -5
+    assert f(X, None, 0, S, Y, 0, 4, 100, None) == 0
+
+
 def test_shape_overflow_is_rejected(L):
     assert _fwd(L, B=1 << 20, H=1 << 20, N=1 << 20) == -2
 

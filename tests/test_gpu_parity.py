@@ -12,7 +12,8 @@ import torch
 import oracle
 from paper_2406_08128_amd import binding
 from oracle import layer as oracle_layer
-from paper_2406_08128_amd.workloads import WORKLOADS, make_inputs, make_z_inputs, shrink, to_f64_numpy
+from oracle import conv as oracle_conv
+from paper_2406_08128_amd.workloads import WORKLOADS, make_conv_inputs, make_inputs, make_z_inputs, shrink, to_f64_numpy
 
 pytestmark = pytest.mark.gpu
 
@@ -552,3 +553,67 @@ def test_training_pair_many_heads_single_segment():
     _check("O", sel(O), oracle.fwd_recurrent(Qn, Kn, Vn), "bf16")
     for name, got, r in zip(("dQ", "dK", "dV"), (dQ, dK, dV), oracle.bwd_recurrent(Qn, Kn, Vn, Gn)):
         _check(name, sel(got), r, "bf16")
+
+
+# ------------------------------------------------------------------------------------------ short-long convolution
+def _run_conv_case(B, d, L, m, dtype, seed=0, short=True):
+    print("\nconv B%d d%d L%d m%d %s short=%s" % (B, d, L, m, dtype, short), flush=True)
+    x = make_conv_inputs(B, d, L, m, seed, dtype)
+    dev = _dev(x)
+    spec = binding.chela_longconv_spectrum(dev["k_long"])
+    Z = binding.chela_shortlong_conv_fwd(dev["X"], dev["w_short"] if short else None, spec)
+    torch.cuda.synchronize()
+    ref = oracle_conv.short_long_conv(to_f64_numpy(x["X"]), to_f64_numpy(x["w_short"]) if short else None,
+                                      to_f64_numpy(x["k_long"]))
+    return _check("Z", Z, ref, dtype)
+
+
+CONV_F32 = [(1, 1, 1, 1), (2, 3, 2, 3), (1, 2, 7, 3), (1, 3, 255, 9), (2, 2, 256, 9), (1, 2, 257, 5), (1, 3, 1000, 9),
+            (2, 2, 1024, 3), (1, 2, 1025, 9), (1, 2, 3000, 9), (1, 2, 4096, 9), (1, 2, 9001, 9), (1, 2, 16384, 9)]
+
+
+@pytest.mark.parametrize("shape", CONV_F32)
+def test_shortlong_conv_f32(shape):
+    B, d, L, m = shape
+    _run_conv_case(B, d, L, m, "f32", seed=L)
+
+
+@pytest.mark.parametrize("shape", [(2, 3, 1000, 9), (1, 4, 4096, 9), (2, 2, 16384, 9), (1, 2, 777, 32)])
+def test_shortlong_conv_bf16(shape):
+    B, d, L, m = shape
+    _run_conv_case(B, d, L, m, "bf16", seed=L + 1)
+
+
+@pytest.mark.parametrize("L", [300, 4096, 16384])
+def test_long_conv_alone(L):
+    _run_conv_case(1, 3, L, 3, "f32", seed=L + 2, short=False)
+
+
+def test_conv_identity_kernel_delay_and_determinism():
+    # a unit impulse at lag 5 as the long kernel delays the activated short-conv output by 5 steps
+    x = make_conv_inputs(2, 4, 2000, 9, 7, "f32")
+    dev = _dev(x)
+    k = torch.zeros_like(dev["k_long"])
+    k[:, 5] = 1.0
+    spec = binding.chela_longconv_spectrum(k)
+    Z1 = binding.chela_shortlong_conv_fwd(dev["X"], dev["w_short"], spec)
+    Z2 = binding.chela_shortlong_conv_fwd(dev["X"], dev["w_short"], spec)
+    torch.cuda.synchronize()
+    assert torch.equal(Z1, Z2)
+    v = oracle_conv.short_conv(to_f64_numpy(x["X"]), to_f64_numpy(x["w_short"]))
+    want = np.zeros_like(v)
+    want[..., 5:] = v[..., :-5]
+    assert oracle.rel_l2(to_f64_numpy(Z1), want) <= 1e-5
+
+
+def test_conv_lm_width_sampled_channels():
+    # the LM-shaped width (B4, d768, L16384) in the launch configuration the benchmark times; a few channels checked
+    x = make_conv_inputs(4, 768, 16384, 9, 3, "bf16")
+    dev = _dev(x)
+    spec = binding.chela_longconv_spectrum(dev["k_long"])
+    Z = binding.chela_shortlong_conv_fwd(dev["X"], dev["w_short"], spec)
+    torch.cuda.synchronize()
+    for c in (0, 383, 767):
+        ref = oracle_conv.short_long_conv(to_f64_numpy(x["X"][:, c:c + 1]), to_f64_numpy(x["w_short"][c:c + 1]),
+                                          to_f64_numpy(x["k_long"][c:c + 1]))
+        _check("Z[c=%d]" % c, Z[:, c:c + 1], ref, "bf16")
