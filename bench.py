@@ -84,6 +84,70 @@ def bench_decode(args, w, torch, binding):
         "cpu_baseline": None}))
 
 
+def bench_conv(args, w, torch, binding):
+    """Short-long convolution Z = K_l(silu(K_s(X))) at the workload's width: B sequences x (H*dk) channels x N steps."""
+    from paper_2406_08128_amd.workloads import make_conv_inputs, to_f64_numpy
+    B, d, L, m = w.B, w.H * w.dk, w.N, 9
+    dt = "bf16" if w.dtype == "bf16" else "f32"
+    es = 2 if dt == "bf16" else 4
+    x = make_conv_inputs(B, d, L, m, w.seed, dt)
+    dev = {k: v.cuda() for k, v in x.items()}
+    spec = binding.chela_longconv_spectrum(dev["k_long"])
+    Z = torch.empty_like(dev["X"])
+
+    def step():
+        binding.chela_shortlong_conv_fwd(dev["X"], dev["w_short"], spec, Z=Z)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    binding.chela_profile_reset()
+    binding.chela_profile_enable(True)
+    for _ in range(args.steps):
+        step()
+    binding.chela_longconv_spectrum(dev["k_long"])
+    torch.cuda.synchronize()
+    prof = binding.chela_profile_read()
+    binding.chela_profile_enable(False)
+    binding.chela_profile_reset()
+    kernels = {k: {"launches": n, "avg_us": round(t * 1e3 / n, 2)} for k, (n, t) in prof.items()}
+    us = kernels["shortlong_conv_kernel"]["avg_us"]
+    M = 256 if L <= 256 else 1024 if L <= 1024 else 4096 if L <= 4096 else 16384
+    # ALU model per sequence: two complex FFTs of length M at 5 M log2 M flops + 20 flops per spectrum pair + short kernel
+    import math
+    flops = B * d * (2 * 5 * M * math.log2(M) + 20 * M / 2 + 2 * m * L)
+    alg = B * d * L * es * 2 + d * (M + 1) * 8          # X in, Z out, the kernel spectrum once
+    achieved = flops / (us * 1e-6) / 1e12
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import conv as oracle_conv
+        nch = min(d, 512)                                # bounded sample: the direct sum is O(L^2) per sequence
+        Xn = to_f64_numpy(x["X"][:1, :nch]); wn = to_f64_numpy(x["w_short"][:nch]); kn = to_f64_numpy(x["k_long"][:nch])
+        import oracle
+        c0 = time.perf_counter()
+        oracle_conv.short_long_conv(Xn, wn, kn)
+        c1 = time.perf_counter()
+        cpu = {"value": round(L * nch / d / (c1 - c0), 2), "unit": "tokens/s", "cores": min(oracle.num_threads(), nch),
+               "kind": "oracle", "seconds": round(c1 - c0, 3),
+               "sample": "fp64 direct-sum oracle on %d of the %d (batch, channel) sequences; tokens/s = L / (seconds "
+                         "scaled to all %d channels of one batch entry)" % (nch, B * d, d)}
+    print(json.dumps({
+        "metric": "short-long convolution fwd tokens/s", "value": round(B * L / (ms * 1e-3), 1), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "conv at %s width: B%d d%d L%d, short kernel %d taps + silu + long kernel of L taps, %s I/O, "
+                               "fp32 arithmetic" % (w.name, B, d, L, m, dt)},
+        "roofline": {"bound": "alu", "kernel": "shortlong_conv_kernel", "achieved": round(achieved, 2), "peak": 157.3,
+                     "unit": "TFLOP/s", "frac": round(achieved / 157.3, 4), "traffic": None,
+                     "flop_model_per_launch": flops, "avg_launch_us": us,
+                     "hbm_GBs_algorithmic": round(alg / (us * 1e-6) / 1e9, 1)},
+        "kernels": kernels, "cpu_baseline": cpu}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -91,13 +155,14 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="lm_bf16")
     ap.add_argument("--chunk", type=int, default=64)
-    ap.add_argument("--mode", default="train", choices=["train", "train_saved", "train_state", "train_z", "noncausal", "decode"],
+    ap.add_argument("--mode", default="train", choices=["train", "train_saved", "train_state", "train_z", "noncausal", "decode", "conv"],
                     help="train: fwd+bwd (the headline); train_saved: the same step through chela_linattn_fwd_save / "
                          "_bwd_saved (the forward leaves the boundary states, the backward skips its pass over K, V); "
                          "train_state: the same through the carried-state entry points "
                          "(S_in, S_out, dS_out, dS_in all live); train_z: queries and keys formed on chip from one tensor Z "
                          "(chela_linattn_zfwd / zbwd: three forward and five backward HBM streams); noncausal: O = Q (K^T V) "
-                         "without a mask (the classification models' form); decode: single-token steps of the recurrent form")
+                         "without a mask (the classification models' form); conv: the short-long convolution of "
+                         "Sec. 4.2 at the workload's width (B x H*dk channels x N steps); decode: single-token steps of the recurrent form")
     ap.add_argument("--decode-batch", type=int, default=256, help="sequences decoded together in --mode decode")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
@@ -119,6 +184,8 @@ def main():
     torch.cuda.set_device(0)
     if args.mode == "decode":
         return bench_decode(args, w, torch, binding)
+    if args.mode == "conv":
+        return bench_conv(args, w, torch, binding)
     has_bwd = w.backward          # the headline workload runs forward + backward; forward-only workloads time the forward
     es = 2 if w.dtype == "bf16" else 4
     x = make_inputs(w, with_dO=has_bwd)

@@ -93,6 +93,51 @@ __device__ __forceinline__ int spectrum_pos(int k)
     return pos;
 }
 
+// One radix-16 pass over sub-transforms of length N16 (stride N16 / 16), forward or inverse, one 16-point transform
+// per thread.  With the length fixed at compile time the 16 LDS addresses are one base plus constants (the padding
+// of a multiple of 16 is itself a constant), and the last pass (N16 = 16) has no twiddles at all.
+template <int M, int N16, bool INV>
+__device__ __forceinline__ void pass16(cplx* a, const cplx* lo, const cplx* hi, int tid)
+{
+    constexpr int T = conv_threads(M), S = N16 / 16;
+    constexpr int STEP = S >= 16 ? S + S / 16 : 1;                 // padded distance between the transform's points
+    for (int g = tid; g < M / 16; g += T) {
+        const int block = g / S, j = g - block * S;
+        cplx* p0 = a + (S >= 16 ? conv_pad(block * N16 + j) : 17 * g);
+        cplx v[16];
+        cplx w1 = mk(1.f, 0.f);
+        if (S > 1) {
+            const cplx w1f = twiddle<M>(lo, hi, j * (M / N16));   // W_N16^j
+            w1 = INV ? conj(w1f) : w1f;
+        }
+        if (INV) {
+            // undo the forward pass: strip the twiddles, then the conjugate 16-point transform (the factor 1/16 is
+            // left to the final scaling); inputs X_p in natural order p, outputs x_q in slot order
+            cplx w = w1;
+            v[0] = p0[0];
+#pragma unroll
+            for (int p = 1; p < 16; ++p) {
+                v[p] = S > 1 ? cmul(p0[p * STEP], w) : p0[p * STEP];
+                if (S > 1) w = cmul(w, w1);
+            }
+            dft16<true>(v);
+#pragma unroll
+            for (int q = 0; q < 16; ++q) p0[q * STEP] = v[(q >> 2) + 4 * (q & 3)];
+        } else {
+#pragma unroll
+            for (int q = 0; q < 16; ++q) v[q] = p0[q * STEP];
+            dft16<false>(v);
+            cplx w = w1;
+            p0[0] = v[0];
+#pragma unroll
+            for (int p = 1; p < 16; ++p) {
+                p0[p * STEP] = S > 1 ? cmul(v[(p >> 2) + 4 * (p & 3)], w) : v[(p >> 2) + 4 * (p & 3)];
+                if (S > 1) w = cmul(w, w1);
+            }
+        }
+    }
+}
+
 // All forward passes (INV = false) or all inverse passes in reverse order (INV = true) over a[] in LDS.
 // A __syncthreads() separates the passes; the caller synchronises before and after.
 template <int M, bool INV>
@@ -100,65 +145,32 @@ __device__ __forceinline__ void fft_passes(cplx* a, const cplx* lo, const cplx* 
 {
     constexpr int T = conv_threads(M);
     constexpr int M16 = conv_lead4(M) ? M / 4 : M;     // what the radix-16 passes transform (blocks of this length)
+    static_assert(M16 == 256 || M16 == 4096, "radix-16 part must be 16^2 or 16^3");
     auto lead4 = [&]() __attribute__((always_inline)) {
-        constexpr int s = M / 4;
+        constexpr int s = M / 4, sp = s + s / 16;
         for (int g = tid; g < s; g += T) {
-            cplx v0 = a[conv_pad(g)], v1 = a[conv_pad(g + s)], v2 = a[conv_pad(g + 2 * s)], v3 = a[conv_pad(g + 3 * s)];
+            cplx* p0 = a + conv_pad(g);
+            cplx v0 = p0[0], v1 = p0[sp], v2 = p0[2 * sp], v3 = p0[3 * sp];
             const cplx w1 = twiddle<M>(lo, hi, g);
             const cplx t1 = INV ? conj(w1) : w1, t2 = cmul(t1, t1), t3 = cmul(t2, t1);
             if (INV) { v1 = cmul(v1, t1); v2 = cmul(v2, t2); v3 = cmul(v3, t3); }
             dft4<INV>(v0, v1, v2, v3);
             if (!INV) { v1 = cmul(v1, t1); v2 = cmul(v2, t2); v3 = cmul(v3, t3); }
-            a[conv_pad(g)] = v0; a[conv_pad(g + s)] = v1; a[conv_pad(g + 2 * s)] = v2; a[conv_pad(g + 3 * s)] = v3;
-        }
-    };
-    auto pass16 = [&](int n) __attribute__((always_inline)) {     // n: current sub-transform length, stride n / 16
-        const int s = n / 16;
-        for (int g = tid; g < M / 16; g += T) {
-            const int block = g / s, j = g - block * s, base = block * n + j;
-            cplx v[16];
-            // twiddles W_n^(j p) = (W_M^(j M / n))^p
-            const cplx w1f = twiddle<M>(lo, hi, j * (M / n));
-            const cplx w1 = INV ? conj(w1f) : w1f;
-            if (INV) {
-                // undo the forward pass: strip the twiddles, then the conjugate 16-point transform (the factor
-                // 1/16 is left to the final scaling); inputs X_p in natural order p, outputs x_q in slot order
-                cplx w = w1;
-                v[0] = a[conv_pad(base)];
-#pragma unroll
-                for (int p = 1; p < 16; ++p) {
-                    v[p] = cmul(a[conv_pad(base + p * s)], w);
-                    w = cmul(w, w1);
-                }
-                dft16<true>(v);
-#pragma unroll
-                for (int q = 0; q < 16; ++q) a[conv_pad(base + q * s)] = v[(q >> 2) + 4 * (q & 3)];
-            } else {
-#pragma unroll
-                for (int q = 0; q < 16; ++q) v[q] = a[conv_pad(base + q * s)];
-                dft16<false>(v);
-                cplx w = w1;
-                a[conv_pad(base)] = v[0];
-#pragma unroll
-                for (int p = 1; p < 16; ++p) {
-                    a[conv_pad(base + p * s)] = cmul(v[(p >> 2) + 4 * (p & 3)], w);
-                    w = cmul(w, w1);
-                }
-            }
+            p0[0] = v0; p0[sp] = v1; p0[2 * sp] = v2; p0[3 * sp] = v3;
         }
     };
     if (!INV) {
         if (conv_lead4(M)) { lead4(); __syncthreads(); }
-        for (int n = M16; n >= 16; n /= 16) {
-            pass16(n);
-            if (n > 16) __syncthreads();
-        }
+        if (M16 == 4096) { pass16<M, 4096, false>(a, lo, hi, tid); __syncthreads(); }
+        pass16<M, 256, false>(a, lo, hi, tid);
+        __syncthreads();
+        pass16<M, 16, false>(a, lo, hi, tid);
     } else {
-        for (int n = 16; n <= M16; n *= 16) {
-            pass16(n);
-            if (n < M16 || conv_lead4(M)) __syncthreads();
-        }
-        if (conv_lead4(M)) lead4();
+        pass16<M, 16, true>(a, lo, hi, tid);
+        __syncthreads();
+        pass16<M, 256, true>(a, lo, hi, tid);
+        if (M16 == 4096) { __syncthreads(); pass16<M, 4096, true>(a, lo, hi, tid); }
+        if (conv_lead4(M)) { __syncthreads(); lead4(); }
     }
 }
 
@@ -256,15 +268,18 @@ __global__ __launch_bounds__(conv_threads(M)) void shortlong_conv_kernel(const I
 
     // ---- load, short kernel, activation, packing
     if (w_short != nullptr) {
-        float* sx = reinterpret_cast<float*>(a);           // raw x, one float per time step (L <= M floats)
+        // raw x as floats behind 32 zeros (the zero history), so that no tap needs a bounds check
+        float* sx = reinterpret_cast<float*>(a);
+        constexpr int ZP = 32;
+        if (tid < ZP) sx[tid] = 0.f;
         for (int n = tid; n < M; n += T) {
             const int t = 2 * n;
             if (t < L) {
                 float v0, v1 = 0.f;
                 if (vec_ok) IoPair<IO>::load2(x + t, v0, v1);
                 else { v0 = (float)x[t]; if (t + 1 < L) v1 = (float)x[t + 1]; }
-                sx[t] = v0;
-                sx[t + 1] = v1;
+                sx[ZP + t] = v0;
+                sx[ZP + t + 1] = v1;
             }
         }
         __syncthreads();
@@ -272,19 +287,25 @@ __global__ __launch_bounds__(conv_threads(M)) void shortlong_conv_kernel(const I
         cplx z[PER];
         const float* wc = w_short + (long)c * m;
 #pragma unroll
+        for (int i = 0; i < PER; ++i) z[i] = mk(0.f, 0.f);
+        // outputs t and t+1 share all but one of their inputs: x[t+1-j], j = 0..m, are read once
+        for (int j = 0; j <= m; ++j) {
+            const float wj = j < m ? wc[j] : 0.f, wjm1 = j > 0 ? wc[j - 1] : 0.f;
+#pragma unroll
+            for (int i = 0; i < PER; ++i) {
+                const int t = 2 * (tid + T * i);
+                if (t < L) {
+                    const float xv = sx[ZP + t + 1 - j];      // feeds output t+1 with tap j and output t with tap j-1
+                    z[i].y = fmaf(wj, xv, z[i].y);
+                    z[i].x = fmaf(wjm1, xv, z[i].x);
+                }
+            }
+        }
+#pragma unroll
         for (int i = 0; i < PER; ++i) {
             const int t = 2 * (tid + T * i);
-            float acc0 = 0.f, acc1 = 0.f;
-            if (t < L) {
-                for (int j = 0; j < m; ++j) {
-                    const float wj = wc[j];
-                    if (t - j >= 0) acc0 = fmaf(wj, sx[t - j], acc0);
-                    if (t + 1 - j >= 0 && t + 1 < L) acc1 = fmaf(wj, sx[t + 1 - j], acc1);
-                }
-                acc0 = acc0 / (1.f + __expf(-acc0));
-                acc1 = acc1 / (1.f + __expf(-acc1));
-            }
-            z[i] = mk(acc0, acc1);
+            z[i].x = z[i].x * __builtin_amdgcn_rcpf(1.f + __expf(-z[i].x));
+            z[i].y = (t + 1 < L) ? z[i].y * __builtin_amdgcn_rcpf(1.f + __expf(-z[i].y)) : 0.f;
         }
         __syncthreads();
 #pragma unroll
