@@ -423,7 +423,7 @@ struct FwdLds {
     static constexpr int BYTES = TILES + (ZQK ? 4 * DK * 4 : 0);
 };
 
-template <int C, int DK, int DV, bool ZQK>
+template <int C, int DK, int DV, bool ZQK, bool SAVE>
 __device__ __forceinline__ void fwd_sweep_body(const bf16* __restrict__ Qb, const bf16* __restrict__ Kb,
                                                const bf16* __restrict__ Vb, bf16* __restrict__ Ob,
                                                const float* __restrict__ S0, float* __restrict__ S_final,
@@ -512,7 +512,7 @@ __device__ __forceinline__ void fwd_sweep_body(const bf16* __restrict__ Qb, cons
             for (int n = 0; n < NJ; ++n) store_tile_T(rows, DV, (jg * NJ + n) * 32, accO[n], valid, lane);
         }
         // state update S += K^T V (after the segment's last chunk only if the final state is asked for)
-        if (more || S_final != nullptr || S_final_T != nullptr) {
+        if (more || S_final != nullptr || (SAVE && S_final_T != nullptr)) {
 #pragma unroll
             for (int n = 0; n < NS; ++n) {
                 const int id = w + 4 * n, ib = id / JB, jb = id % JB;
@@ -524,7 +524,7 @@ __device__ __forceinline__ void fwd_sweep_body(const bf16* __restrict__ Qb, cons
         __syncthreads();
     }
     if (S_final != nullptr) store_state<DK, DV>(S_final, accS, w, lane);
-    if (S_final_T != nullptr) store_state_T<DK, DV>(S_final_T, accS, w, lane);   // [dv][dk], as the backward reads it
+    if (SAVE && S_final_T != nullptr) store_state_T<DK, DV>(S_final_T, accS, w, lane);   // [dv][dk], as the backward reads it
 }
 
 // =============================================================================================== backward sweep body
@@ -887,7 +887,8 @@ struct SegStateArgs {
 };
 
 template <int DA, int DB, int AFF>
-__global__ __launch_bounds__(256) void bf16_seg_state_kernel(SegStateArgs args, int N, int seg_len, int n_seg)
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((DA == 64 && DB == 64) ? (AFF == 0 ? 6 : 5) : 1)))
+void bf16_seg_state_kernel(SegStateArgs args, int N, int seg_len, int n_seg)
 {
     __shared__ __attribute__((aligned(16))) unsigned char lds[PrepassLds<DA, DB, AFF>::BYTES];
     const int z = blockIdx.z, seg = blockIdx.y;   // heads on grid.x: its limit is 2^31-1, the others' 65535
@@ -906,8 +907,10 @@ __global__ __launch_bounds__(256) void bf16_seg_state_kernel(SegStateArgs args, 
                               args.out[z] + ((size_t)bh * n_seg + seg) * DA * DB, al, be, p1 - p0, lds, tid, w, lane);
 }
 
-template <int C, int DK, int DV, bool ZQK>
-__global__ __launch_bounds__(256) void bf16_fwd_sweep_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K,
+// (the narrowest shape is asked to stay within the 128 registers that let four workgroups share a compute unit)
+template <int C, int DK, int DV, bool ZQK, bool SAVE>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((C == 64 && DK == 64 && DV == 64) ? 4 : 1)))
+void bf16_fwd_sweep_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K,
                                                             const bf16* __restrict__ V, bf16* __restrict__ O,
                                                             const float* __restrict__ S0, float* __restrict__ S_out,
                                                             const float* __restrict__ aff, int H,
@@ -927,11 +930,11 @@ __global__ __launch_bounds__(256) void bf16_fwd_sweep_kernel(const bf16* __restr
     // saved: the running state at the end of every save_every-th segment (and of the last one), transposed, for a
     // backward call that walks segments save_every times as long: [bh][ceil(n_seg / save_every)][dv][dk]
     float* save_to = nullptr;
-    if (saved != nullptr && ((seg + 1) % save_every == 0 || seg == n_seg - 1)) {
+    if (SAVE && saved != nullptr && ((seg + 1) % save_every == 0 || seg == n_seg - 1)) {
         const int n_slots = (n_seg + save_every - 1) / save_every, slot = (seg + save_every) / save_every - 1;
         save_to = saved + ((size_t)bh * n_slots + slot) * DK * DV;
     }
-    fwd_sweep_body<C, DK, DV, ZQK>(Q + rk, ZQK ? nullptr : K + rk, V + rv, O + rv,
+    fwd_sweep_body<C, DK, DV, ZQK, SAVE>(Q + rk, ZQK ? nullptr : K + rk, V + rv, O + rv,
                                    has_state ? S0 + ((size_t)bh * n_seg + seg) * DK * DV : nullptr,
                                    (S_out != nullptr && seg == n_seg - 1) ? S_out + (size_t)bh * DK * DV : nullptr,
                                    save_to, ZQK ? aff + (size_t)(bh % H) * DK : nullptr, (size_t)H * DK, p1 - p0, lds, tid, w,
@@ -1076,9 +1079,15 @@ static hipError_t fwd_impl(const bf16* Q, const bf16* K, const bf16* V, bf16* O,
     }
     dim3 grid((unsigned)BH, plan.n_seg);
     ProfScope prof(KID_FWD_SWEEP_BF16, st);
-    hipLaunchKernelGGL((bf16_fwd_sweep_kernel<C, DK, DV, ZQK>), grid, dim3(256), 0, st, Q, K, V, O,
-                       use_ws ? ws : nullptr, S_out, aff, H, saved, save_every, S_in != nullptr ? 1 : 0, N,
-                       plan.seg_len, plan.n_seg);
+    // the variant that can save boundary states needs a few more registers; the plain call keeps its own kernel
+    if (saved != nullptr)
+        hipLaunchKernelGGL((bf16_fwd_sweep_kernel<C, DK, DV, ZQK, !ZQK>), grid, dim3(256), 0, st, Q, K, V, O,
+                           use_ws ? ws : nullptr, S_out, aff, H, saved, save_every, S_in != nullptr ? 1 : 0, N,
+                           plan.seg_len, plan.n_seg);
+    else
+        hipLaunchKernelGGL((bf16_fwd_sweep_kernel<C, DK, DV, ZQK, false>), grid, dim3(256), 0, st, Q, K, V, O,
+                           use_ws ? ws : nullptr, S_out, aff, H, (float*)nullptr, 1, S_in != nullptr ? 1 : 0, N,
+                           plan.seg_len, plan.n_seg);
     return hipGetLastError();
 }
 
