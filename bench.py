@@ -155,7 +155,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="lm_bf16")
     ap.add_argument("--chunk", type=int, default=64)
-    ap.add_argument("--mode", default="train", choices=["train", "train_saved", "train_state", "train_z", "noncausal", "decode", "conv"],
+    ap.add_argument("--mode", default="train", choices=["train", "train_saved", "train_state", "train_z", "train_z_saved", "noncausal", "decode", "conv"],
                     help="train: fwd+bwd (the headline); train_saved: the same step through chela_linattn_fwd_save / "
                          "_bwd_saved (the forward leaves the boundary states, the backward skips its pass over K, V); "
                          "train_state: the same through the carried-state entry points "
@@ -222,11 +222,19 @@ def main():
         else:
             def step():
                 binding.chela_linattn_noncausal_fwd(d["Q"], d["K"], d["V"], O=O)
-    elif args.mode == "train_z":
+    elif args.mode in ("train_z", "train_z_saved"):
         assert w.dtype == "bf16", "--mode train_z needs a bf16 workload"
         xz = make_z_inputs(w, with_dO=has_bwd)
         dz = {k: v.cuda() for k, v in xz.items()}
-        if has_bwd:
+        if args.mode == "train_z_saved":
+            assert has_bwd, "--mode train_z_saved needs a forward+backward workload"
+            saved = torch.empty(max(binding.chela_linattn_saved_bytes(w.B, w.H, w.N, w.dk, w.dv, 64), 16) // 4,
+                                dtype=torch.float32, device="cuda")
+
+            def step():
+                binding.chela_linattn_zfwd_save(dz["Z"], dz["affine"], dz["V"], O=O, saved=saved)
+                binding.chela_linattn_zbwd_saved(dz["Z"], dz["affine"], dz["V"], dz["dO"], saved)
+        elif has_bwd:
             def step():
                 binding.chela_linattn_zfwd(dz["Z"], dz["affine"], dz["V"], O=O)
                 binding.chela_linattn_zbwd(dz["Z"], dz["affine"], dz["V"], dz["dO"])
@@ -273,7 +281,7 @@ def main():
     kernels = {k: {"launches": n, "avg_us": ms * 1e3 / n} for k, (n, ms) in prof.items()}
 
     fwd_b, bwd_b = algorithmic_bytes_per_token_head(w.dk, w.dv, es)
-    if args.mode == "train_z":     # Z replaces Q and K on the way in, dZ replaces dQ and dK on the way out
+    if args.mode in ("train_z", "train_z_saved"):     # Z replaces Q and K on the way in, dZ replaces dQ and dK on the way out
         fwd_b, bwd_b = es * (w.dk + 2 * w.dv), es * (w.dk + 2 * w.dv + w.dk + w.dv)
     fwd_f, bwd_f = flops_per_token_head(w.dk, w.dv, chunk)
     th = w.token_heads
@@ -311,7 +319,7 @@ def main():
             if has_bwd:
                 oracle_layer.noncausal_bwd(Qn, Kn, Vn, Gn)
             c1 = time.perf_counter()
-        elif args.mode == "train_z":
+        elif args.mode in ("train_z", "train_z_saved"):
             from oracle import layer as oracle_layer
             Zn, An, Vn = (to_f64_numpy(xz[n]) for n in ("Z", "affine", "V"))
             Gn = to_f64_numpy(xz["dO"]) if has_bwd else None
@@ -338,7 +346,8 @@ def main():
                                                   "fwd+bwd" if has_bwd else "fwd")
                   + (" (carried-state entry points)" if args.mode == "train_state" else "")
                   + (" (forward saves the boundary states)" if args.mode == "train_saved" else "")
-                  + (" (Q, K formed on chip from Z)" if args.mode == "train_z" else ""),
+                  + (" (Q, K formed on chip from Z)" if args.mode == "train_z" else "")
+                  + (" (Q, K formed on chip from Z; forward saves the boundary states)" if args.mode == "train_z_saved" else ""),
         "value": round(tokens_per_s, 1),
         "unit": "tokens/s",
         "n_gpus": 1,

@@ -128,6 +128,14 @@ int chela_linattn_zbwd(const void *Z, const float *affine, const void *V, const 
                        void *dZ, float *d_affine, void *dV,
                        int B, int H, int N, int dk, int dv, int chunk, void *stream);
 size_t chela_linattn_z_workspace_bytes(int B, int H, int N, int dk, int dv, int chunk, int is_bwd);
+/* The same two calls as a training pair (see chela_linattn_fwd_save below): `saved` is a caller-owned buffer of
+ * chela_linattn_saved_bytes(B, H, N, dk, dv, 64) bytes that carries the boundary states from the forward to the
+ * backward call, which then needs no pass over K(Z), V to rebuild them. */
+int chela_linattn_zfwd_save(const void *Z, const float *affine, const void *V, void *O, void *saved,
+                            int B, int H, int N, int dk, int dv, int chunk, void *stream);
+int chela_linattn_zbwd_saved(const void *Z, const float *affine, const void *V, const void *dO, const void *saved,
+                             void *dZ, float *d_affine, void *dV,
+                             int B, int H, int N, int dk, int dv, int chunk, void *stream);
 
 /* ---- training pair: forward that leaves the running state for the backward ------------------------------------
  * chela_linattn_bwd rebuilds the state at its segment boundaries from K and V (one extra pass over both).  In a

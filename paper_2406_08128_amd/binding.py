@@ -51,6 +51,10 @@ def lib() -> ctypes.CDLL:
     L.chela_linattn_zfwd.restype = i
     L.chela_linattn_zbwd.argtypes = [vp] * 7 + [i, i, i, i, i, i, vp]
     L.chela_linattn_zbwd.restype = i
+    L.chela_linattn_zfwd_save.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, i, vp]
+    L.chela_linattn_zfwd_save.restype = i
+    L.chela_linattn_zbwd_saved.argtypes = [vp] * 8 + [i, i, i, i, i, i, vp]
+    L.chela_linattn_zbwd_saved.restype = i
     L.chela_linattn_z_workspace_bytes.argtypes = [i, i, i, i, i, i, i]
     L.chela_linattn_z_workspace_bytes.restype = sz
     L.chela_linattn_fwd_save.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, i, vp]
@@ -312,6 +316,36 @@ def chela_linattn_zbwd(Z, affine, V, dO, chunk: int = 64, stream=None):
         _check(lib().chela_linattn_zbwd(Z.data_ptr(), affine.data_ptr(), V.data_ptr(), dO.data_ptr(), dZ.data_ptr(),
                                         d_aff.data_ptr(), dV.data_ptr(), B, H, N, dk, dv, int(chunk),
                                         _stream_ptr(stream)))
+    return dZ, d_aff, dV
+
+
+def chela_linattn_zfwd_save(Z, affine, V, O=None, saved=None, stream=None):
+    """(O, saved): chela_linattn_zfwd that also leaves the boundary states for chela_linattn_zbwd_saved."""
+    B, H, N, dk, dv = _zdims(Z, affine, V)
+    if O is None:
+        O = torch.empty((B, H, N, dv), dtype=Z.dtype, device=Z.device)
+    need = chela_linattn_saved_bytes(B, H, N, dk, dv, 64)
+    if saved is None:
+        saved = torch.empty(max(need, 16) // 4, dtype=torch.float32, device=Z.device)
+    elif saved.numel() * saved.element_size() < need or not saved.is_contiguous():
+        raise ValueError("saved must be a contiguous device buffer of at least %d bytes" % need)
+    with torch.cuda.device(Z.device):
+        _check(lib().chela_linattn_zfwd_save(Z.data_ptr(), affine.data_ptr(), V.data_ptr(), O.data_ptr(),
+                                             saved.data_ptr(), B, H, N, dk, dv, 64, _stream_ptr(stream)))
+    return O, saved
+
+
+def chela_linattn_zbwd_saved(Z, affine, V, dO, saved, stream=None):
+    """(dZ, d_affine, dV) using the states chela_linattn_zfwd_save left for the same inputs."""
+    B, H, N, dk, dv = _zdims(Z, affine, V)
+    if dO.shape != V.shape or dO.dtype != V.dtype or not dO.is_contiguous():
+        raise ValueError("dO must match V")
+    dZ, dV = torch.empty_like(Z), torch.empty_like(V)
+    d_aff = torch.empty_like(affine)
+    with torch.cuda.device(Z.device):
+        _check(lib().chela_linattn_zbwd_saved(Z.data_ptr(), affine.data_ptr(), V.data_ptr(), dO.data_ptr(),
+                                              saved.data_ptr(), dZ.data_ptr(), d_aff.data_ptr(), dV.data_ptr(), B, H,
+                                              N, dk, dv, 64, _stream_ptr(stream)))
     return dZ, d_aff, dV
 
 

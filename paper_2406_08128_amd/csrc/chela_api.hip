@@ -345,55 +345,64 @@ static int bwd_common(const void* Q, const void* K, const void* V, const void* d
     return e == hipSuccess ? CHELA_OK : CHELA_ERR_HIP;
 }
 
-// Eq. 11-12 variants.  The kernels tile with 64-token chunks whatever the (validated) hint says.
-static int zfwd_common(const void* Z, const float* aff, const void* V, void* O, int B, int H, int N, int dk, int dv,
-                       int chunk, void* stream)
+static size_t saved_bytes(long BH, const TrainPlans& t) { return (size_t)BH * t.bwd.n_seg * t.bwd.state_elems * sizeof(float); }
+
+// Eq. 11-12 variants.  The kernels tile with 64-token chunks whatever the (validated) hint says.  `saved` (optional,
+// with want_saved): the training-pair hand-over of boundary states, as for the plain pair.
+static int zfwd_common(const void* Z, const float* aff, const void* V, void* O, void* saved, bool want_saved, int B,
+                       int H, int N, int dk, int dv, int chunk, void* stream)
 {
     const size_t th = (B > 0 && H > 0 && N > 0) ? (size_t)B * H * N : 0;
     const size_t ab = th ? (size_t)4 * H * dk * sizeof(float) : 0;
+    const long BH = (long)B * H;
+    TrainPlans t{};
+    const bool dims_ok = (dk == 64 || dk == 128) && (dv == 64 || dv == 128);
+    if (want_saved && th && dims_ok) t = make_train_plans(BH, N, dk, dv, 64);
     const void* in_v[3] = {Z, aff, V};
     const size_t inb[3] = {th * dk * 2, ab, th * dv * 2};
-    void* out_v[1] = {O};
-    const size_t outb[1] = {th * dv * 2};
+    void* out_v[2] = {O, want_saved ? saved : O};
+    const size_t outb[2] = {th * dv * 2, (want_saved && th && dims_ok) ? saved_bytes(BH, t) : 0};
     bool empty = false;
-    int rc = validate(in_v, inb, 3, out_v, outb, 1, B, H, N, dk, dv, chunk, CHELA_DTYPE_BF16, &empty);
+    int rc = validate(in_v, inb, 3, out_v, outb, 2, B, H, N, dk, dv, chunk, CHELA_DTYPE_BF16, &empty);
     if (rc != CHELA_OK || empty) return rc;
-    const long BH = (long)B * H;
-    Plan plan = make_plan(BH, N, dk, dv, 64, CHELA_DTYPE_BF16, false, false);
+    Plan plan = want_saved ? t.fwd : make_plan(BH, N, dk, dv, 64, CHELA_DTYPE_BF16, false, false);
     float* ws = nullptr;
     rc = get_workspace(plan.ws_bytes, &ws);
     if (rc != CHELA_OK) return rc;
-    return launch_bf16_zfwd(Z, aff, V, O, B, H, N, dk, dv, plan, ws, (hipStream_t)stream) == hipSuccess ? CHELA_OK
-                                                                                                         : CHELA_ERR_HIP;
+    return launch_bf16_zfwd(Z, aff, V, O, want_saved ? (float*)saved : nullptr, want_saved ? t.save_every : 1, B, H, N,
+                            dk, dv, plan, ws, (hipStream_t)stream) == hipSuccess ? CHELA_OK : CHELA_ERR_HIP;
 }
 
 static int zbwd_common(const void* Z, const float* aff, const void* V, const void* dO, void* dZ, float* d_aff,
-                       void* dV, int B, int H, int N, int dk, int dv, int chunk, void* stream)
+                       void* dV, const void* saved, bool want_saved, int B, int H, int N, int dk, int dv, int chunk,
+                       void* stream)
 {
     const size_t th = (B > 0 && H > 0 && N > 0) ? (size_t)B * H * N : 0;
     const size_t ab = (H > 0) ? (size_t)4 * H * dk * sizeof(float) : 0;
-    const void* in_v[4] = {Z, aff, V, dO};
-    const size_t inb[4] = {th * dk * 2, th ? ab : 0, th * dv * 2, th * dv * 2};
+    const long BH = (long)B * H;
+    TrainPlans t{};
+    const bool dims_ok = (dk == 64 || dk == 128) && (dv == 64 || dv == 128);
+    if (want_saved && th && dims_ok) t = make_train_plans(BH, N, dk, dv, 64);
+    const void* in_v[5] = {Z, aff, V, dO, want_saved ? saved : Z};
+    const size_t inb[5] = {th * dk * 2, th ? ab : 0, th * dv * 2, th * dv * 2,
+                           (want_saved && th && dims_ok) ? saved_bytes(BH, t) : 0};
     void* out_v[3] = {dZ, d_aff, dV};
     const size_t outb[3] = {th * dk * 2, th ? ab : 0, th * dv * 2};
     bool empty = false;
-    int rc = validate(in_v, inb, 4, out_v, outb, 3, B, H, N, dk, dv, chunk, CHELA_DTYPE_BF16, &empty);
+    int rc = validate(in_v, inb, 5, out_v, outb, 3, B, H, N, dk, dv, chunk, CHELA_DTYPE_BF16, &empty);
     if (rc != CHELA_OK) return rc;
     if (empty) {
         // no tokens: the parameters received no gradient
         if (d_aff && ab) return hipMemsetAsync(d_aff, 0, ab, (hipStream_t)stream) == hipSuccess ? CHELA_OK : CHELA_ERR_HIP;
         return CHELA_OK;
     }
-    const long BH = (long)B * H;
-    Plan plan = make_plan(BH, N, dk, dv, 64, CHELA_DTYPE_BF16, true, false);
+    Plan plan = want_saved ? t.bwd : make_plan(BH, N, dk, dv, 64, CHELA_DTYPE_BF16, true, false);
     float* ws = nullptr;
     rc = get_workspace(plan.ws_bytes + zbwd_extra_ws_bytes(BH, plan, dk), &ws);
     if (rc != CHELA_OK) return rc;
-    return launch_bf16_zbwd(Z, aff, V, dO, dZ, d_aff, dV, B, H, N, dk, dv, plan, ws, (hipStream_t)stream) == hipSuccess
-               ? CHELA_OK : CHELA_ERR_HIP;
+    return launch_bf16_zbwd(Z, aff, V, dO, dZ, d_aff, dV, want_saved ? (const float*)saved : nullptr, B, H, N, dk, dv,
+                            plan, ws, (hipStream_t)stream) == hipSuccess ? CHELA_OK : CHELA_ERR_HIP;
 }
-
-static size_t saved_bytes(long BH, const TrainPlans& t) { return (size_t)BH * t.bwd.n_seg * t.bwd.state_elems * sizeof(float); }
 
 static int fwd_save_common(const void* Q, const void* K, const void* V, void* O, void* saved, int B, int H, int N,
                            int dk, int dv, int chunk, void* stream)
@@ -507,13 +516,26 @@ int chela_linattn_bwd_state(const void* Q, const void* K, const void* V, const f
 int chela_linattn_zfwd(const void* Z, const float* affine, const void* V, void* O, int B, int H, int N, int dk,
                        int dv, int chunk, void* stream)
 {
-    return zfwd_common(Z, affine, V, O, B, H, N, dk, dv, chunk, stream);
+    return zfwd_common(Z, affine, V, O, nullptr, false, B, H, N, dk, dv, chunk, stream);
 }
 
 int chela_linattn_zbwd(const void* Z, const float* affine, const void* V, const void* dO, void* dZ, float* d_affine,
                        void* dV, int B, int H, int N, int dk, int dv, int chunk, void* stream)
 {
-    return zbwd_common(Z, affine, V, dO, dZ, d_affine, dV, B, H, N, dk, dv, chunk, stream);
+    return zbwd_common(Z, affine, V, dO, dZ, d_affine, dV, nullptr, false, B, H, N, dk, dv, chunk, stream);
+}
+
+int chela_linattn_zfwd_save(const void* Z, const float* affine, const void* V, void* O, void* saved, int B, int H,
+                            int N, int dk, int dv, int chunk, void* stream)
+{
+    return zfwd_common(Z, affine, V, O, saved, true, B, H, N, dk, dv, chunk, stream);
+}
+
+int chela_linattn_zbwd_saved(const void* Z, const float* affine, const void* V, const void* dO, const void* saved,
+                             void* dZ, float* d_affine, void* dV, int B, int H, int N, int dk, int dv, int chunk,
+                             void* stream)
+{
+    return zbwd_common(Z, affine, V, dO, dZ, d_affine, dV, saved, true, B, H, N, dk, dv, chunk, stream);
 }
 
 size_t chela_linattn_z_workspace_bytes(int B, int H, int N, int dk, int dv, int chunk, int is_bwd)

@@ -53,10 +53,12 @@ struct TrainPlans { Plan fwd, bwd; int save_every; };
 TrainPlans make_train_plans(long BH, int N, int dk, int dv, int chunk);
 // Eq. 11-12 variants: Z [BH][N][dk] stands in for Q and K, aff = [4][H][dk] fp32 (alpha_q, beta_q, alpha_k, beta_k).
 // plan.chunk must be 64.  The backward needs zbwd_extra_ws_bytes() of workspace behind plan.ws_bytes.
-hipError_t launch_bf16_zfwd(const void* Z, const float* aff, const void* V, void* O, int B, int H, int N, int dk,
-                            int dv, const Plan& plan, float* ws, hipStream_t st);
+// `saved` as for launch_bf16_fwd / launch_bf16_bwd (optional).
+hipError_t launch_bf16_zfwd(const void* Z, const float* aff, const void* V, void* O, float* saved, int save_every,
+                            int B, int H, int N, int dk, int dv, const Plan& plan, float* ws, hipStream_t st);
 hipError_t launch_bf16_zbwd(const void* Z, const float* aff, const void* V, const void* dO, void* dZ, float* d_aff,
-                            void* dV, int B, int H, int N, int dk, int dv, const Plan& plan, float* ws, hipStream_t st);
+                            void* dV, const float* saved, int B, int H, int N, int dk, int dv, const Plan& plan,
+                            float* ws, hipStream_t st);
 inline size_t zbwd_extra_ws_bytes(long BH, const Plan& plan, int dk)
 {
     return (size_t)BH * plan.n_seg * 4 * dk * sizeof(float);

@@ -1081,7 +1081,7 @@ static hipError_t fwd_impl(const bf16* Q, const bf16* K, const bf16* V, bf16* O,
     ProfScope prof(KID_FWD_SWEEP_BF16, st);
     // the variant that can save boundary states needs a few more registers; the plain call keeps its own kernel
     if (saved != nullptr)
-        hipLaunchKernelGGL((bf16_fwd_sweep_kernel<C, DK, DV, ZQK, !ZQK>), grid, dim3(256), 0, st, Q, K, V, O,
+        hipLaunchKernelGGL((bf16_fwd_sweep_kernel<C, DK, DV, ZQK, true>), grid, dim3(256), 0, st, Q, K, V, O,
                            use_ws ? ws : nullptr, S_out, aff, H, saved, save_every, S_in != nullptr ? 1 : 0, N,
                            plan.seg_len, plan.n_seg);
     else
@@ -1103,20 +1103,31 @@ static hipError_t bwd_impl(const bf16* Q, const bf16* K, const bf16* V, const bf
     const long BH = (long)B * H;
     if (saved != nullptr) {
         // The forward call left the state at the end of every segment of THIS plan ([bh][seg][dv][dk]): only the
-        // suffix sums of dO^T Q remain to be built, from dO and Q alone.
+        // suffix sums of dO^T Q remain to be built, from dO and Q (or Z) alone.
         float* wsR = ws;
+        float* wsP = ZQK ? ws + (plan.n_seg > 1 ? (size_t)BH * plan.n_seg * DK * DV : 0) : nullptr;
         if (plan.n_seg > 1) {
             SegStateArgs a{};
             a.X[0] = dO; a.Y[0] = Q; a.out[0] = wsR; a.skip_seg[0] = 0;
+            if (ZQK) { a.alpha[0] = aff; a.beta[0] = aff + (size_t)H * DK; a.H = H; }
             const int mode = SCAN_EXCL_SUFFIX;
-            if ((e = run_seg_state<DV, DK>(a, 1, &mode, nullptr, false, BH, N, plan, st)) != hipSuccess) return e;
+            if ((e = run_seg_state<DV, DK, ZQK ? 2 : 0>(a, 1, &mode, nullptr, false, BH, N, plan, st)) != hipSuccess)
+                return e;
         }
-        dim3 grid((unsigned)BH, plan.n_seg);
-        ProfScope prof(KID_BWD_SWEEP_BF16, st);
-        hipLaunchKernelGGL((bf16_bwd_sweep_kernel<C, DK, DV, ZQK>), grid, dim3(256), 0, st, Q, K, V, dO, dQ, dK, dV,
-                           saved, plan.n_seg > 1 ? wsR : nullptr, dS_in, aff, H, (float*)nullptr, N, plan.seg_len,
-                           plan.n_seg);
-        return hipGetLastError();
+        {
+            dim3 grid((unsigned)BH, plan.n_seg);
+            ProfScope prof(KID_BWD_SWEEP_BF16, st);
+            hipLaunchKernelGGL((bf16_bwd_sweep_kernel<C, DK, DV, ZQK>), grid, dim3(256), 0, st, Q, K, V, dO, dQ, dK,
+                               dV, saved, plan.n_seg > 1 ? wsR : nullptr, dS_in, aff, H, wsP, N, plan.seg_len,
+                               plan.n_seg);
+            if ((e = hipGetLastError()) != hipSuccess) return e;
+        }
+        if (ZQK) {
+            ProfScope prof(KID_AFFINE_GRAD, st);
+            hipLaunchKernelGGL((affine_grad_kernel<DK>), dim3(4 * H), dim3(256), 0, st, wsP, d_aff, B, H, plan.n_seg);
+            e = hipGetLastError();
+        }
+        return e;
     }
     const bool use_ws = plan.n_seg > 1 || S_in != nullptr || dS_out != nullptr;
     const size_t state_floats = use_ws ? (size_t)BH * plan.n_seg * DK * DV : 0;
@@ -1335,27 +1346,28 @@ hipError_t launch_bf16_bwd(const void* Q, const void* K, const void* V, const vo
 }
 
 // Eq. 11-12 variants: Z in place of Q and K, 64-token chunks.
-hipError_t launch_bf16_zfwd(const void* Z, const float* aff, const void* V, void* O, int B, int H, int N, int dk,
-                            int dv, const Plan& plan, float* ws, hipStream_t st)
+hipError_t launch_bf16_zfwd(const void* Z, const float* aff, const void* V, void* O, float* saved, int save_every,
+                            int B, int H, int N, int dk, int dv, const Plan& plan, float* ws, hipStream_t st)
 {
     const bf16 *z = (const bf16*)Z, *v = (const bf16*)V;
     bf16* o = (bf16*)O;
     const long BH = (long)B * H;
 #define CHELA_ZFWD(DK_, DV_) \
-    CHELA_DISPATCH(64, DK_, DV_, (fwd_impl<64, DK_, DV_, true>(z, nullptr, v, o, nullptr, nullptr, aff, H, nullptr, 1, BH, N, plan, ws, st)))
+    CHELA_DISPATCH(64, DK_, DV_, (fwd_impl<64, DK_, DV_, true>(z, nullptr, v, o, nullptr, nullptr, aff, H, saved, save_every, BH, N, plan, ws, st)))
     CHELA_ZFWD(64, 64) CHELA_ZFWD(64, 128) CHELA_ZFWD(128, 64) CHELA_ZFWD(128, 128)
 #undef CHELA_ZFWD
     return hipErrorInvalidValue;
 }
 
 hipError_t launch_bf16_zbwd(const void* Z, const float* aff, const void* V, const void* dO, void* dZ, float* d_aff,
-                            void* dV, int B, int H, int N, int dk, int dv, const Plan& plan, float* ws, hipStream_t st)
+                            void* dV, const float* saved, int B, int H, int N, int dk, int dv, const Plan& plan,
+                            float* ws, hipStream_t st)
 {
     const bf16 *z = (const bf16*)Z, *v = (const bf16*)V, *g = (const bf16*)dO;
     bf16 *dz = (bf16*)dZ, *dvv = (bf16*)dV;
 #define CHELA_ZBWD(DK_, DV_)                                                                                       \
     CHELA_DISPATCH(64, DK_, DV_, (bwd_impl<64, DK_, DV_, true>(z, nullptr, v, g, nullptr, nullptr, dz, nullptr, dvv, \
-                                                               nullptr, aff, d_aff, nullptr, B, H, N, plan, ws, st)))
+                                                               nullptr, aff, d_aff, saved, B, H, N, plan, ws, st)))
     CHELA_ZBWD(64, 64) CHELA_ZBWD(64, 128) CHELA_ZBWD(128, 64) CHELA_ZBWD(128, 128)
 #undef CHELA_ZBWD
     return hipErrorInvalidValue;

@@ -131,6 +131,13 @@ def test_z_entry_point_argument_errors(L):
     # one segment, forward: nothing; backward: the workgroups' shares of the parameter gradients, [B*H][4][dk] fp32
     assert w(1, 2, 64, 64, 64, 64, 0) == 0
     assert w(1, 2, 64, 64, 64, 64, 1) == 2 * 4 * 64 * 4
+    SV = A + 9 * SZ
+    fs, gs = L.chela_linattn_zfwd_save, L.chela_linattn_zbwd_saved
+    assert fs(Z, AF, V, O, None, 1, 2, 64, 64, 64, 64, None) == -1
+    assert fs(Z, AF, V, O, SV + 8, 1, 2, 64, 64, 64, 64, None) == -5
+    assert fs(Z, AF, V, O, V, 1, 2, 64, 64, 64, 64, None) == -6
+    assert gs(Z, AF, V, dO, None, dZ, dA, dV, 1, 2, 64, 64, 64, 64, None) == -1
+    assert gs(Z, AF, V, dO, SV, dZ, SV, dV, 1, 2, 64, 64, 64, 64, None) == -6
     big = w(4, 12, 16384, 64, 64, 64, 1)
     plain = L.chela_linattn_workspace_bytes(4, 12, 16384, 64, 64, 64, 1, 0)
     assert big > plain and (big - plain) % (48 * 4 * 64 * 4) == 0

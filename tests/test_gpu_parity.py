@@ -617,3 +617,41 @@ def test_conv_lm_width_sampled_channels():
         ref = oracle_conv.short_long_conv(to_f64_numpy(x["X"][:, c:c + 1]), to_f64_numpy(x["w_short"][c:c + 1]),
                                           to_f64_numpy(x["k_long"][c:c + 1]))
         _check("Z[c=%d]" % c, Z[:, c:c + 1], ref, "bf16")
+
+
+# ------------------------------------------------------------------------------------------ Z entry points as a training pair
+@pytest.mark.parametrize("shape", [(2, 3, 1000, 64, 64), (1, 2, 9000, 64, 64), (3, 2, 1100, 64, 128), (1, 2, 5000, 128, 64),
+                                   (2, 1, 4100, 128, 128), (1, 1, 1, 64, 64)])
+def test_zqk_training_pair_small(shape):
+    B, H, N, dk, dv = shape
+    w = shrink(WORKLOADS["lm_bf16"], B=B, H=H, N=N, dk=dk, dv=dv, seed=150 + N)
+    x = make_z_inputs(w, with_dO=True)
+    d = _dev(x)
+    O, saved = binding.chela_linattn_zfwd_save(d["Z"], d["affine"], d["V"])
+    dZ, dA, dV = binding.chela_linattn_zbwd_saved(d["Z"], d["affine"], d["V"], d["dO"], saved)
+    torch.cuda.synchronize()
+    Zn, An, Vn, Gn = (to_f64_numpy(x[n]) for n in ("Z", "affine", "V", "dO"))
+    _check("O", O, oracle_layer.zqk_fwd(Zn, An, Vn), "bf16")
+    rZ, rA, rV = oracle_layer.zqk_bwd(Zn, An, Vn, Gn)
+    _check("dZ", dZ, rZ, "bf16")
+    _check("dV", dV, rV, "bf16")
+    for q in range(4):
+        _check("d_affine[%d]" % q, dA[q], rA[q], "bf16")
+
+
+def test_zqk_training_pair_lm_full_size_sampled():
+    w = WORKLOADS["lm_bf16"]
+    x = make_z_inputs(w, with_dO=True)
+    d = _dev(x)
+    O, saved = binding.chela_linattn_zfwd_save(d["Z"], d["affine"], d["V"])
+    dZ, dA, dV = binding.chela_linattn_zbwd_saved(d["Z"], d["affine"], d["V"], d["dO"], saved)
+    torch.cuda.synchronize()
+    for hd in (0, 5, 11):
+        Zn, Vn, Gn = (to_f64_numpy(x[n][:, hd:hd + 1]) for n in ("Z", "V", "dO"))
+        An = to_f64_numpy(x["affine"][:, hd:hd + 1])
+        _check("O", O[:, hd:hd + 1], oracle_layer.zqk_fwd(Zn, An, Vn), "bf16")
+        rZ, rA, rV = oracle_layer.zqk_bwd(Zn, An, Vn, Gn)
+        _check("dZ", dZ[:, hd:hd + 1], rZ, "bf16")
+        _check("dV", dV[:, hd:hd + 1], rV, "bf16")
+        for q in range(4):
+            _check("d_affine[%d]" % q, dA[q, hd:hd + 1], rA[q], "bf16")
