@@ -327,3 +327,67 @@ void chela_oracle_long_conv(const double *V, const double *k, double *Y, int B, 
         }
     }
 }
+
+/* Gradient of Z = K_l( silu( K_s(X) ) ) for an upstream gradient dZ (the paper gives no backward; this is the
+ * exact gradient of the two sums above).  U = K_s(X) before the activation, V = silu(U).
+ *   dV[b,c,t] = sum_{s>=t} k[c][s-t] dZ[b,c,s]
+ *   dk[c][s]  = sum_b sum_{t>=s} dZ[b,c,t] V[b,c,t-s]
+ *   dU        = dV * silu'(U),  silu'(u) = sig(u) (1 + u (1 - sig(u)))      (dU = dV if there is no short stage)
+ *   dX[b,c,t] = sum_{j<m, t+j<L} w[c][j] dU[b,c,t+j]
+ *   dw[c][j]  = sum_b sum_{t>=j} dU[b,c,t] X[b,c,t-j]
+ * w == NULL: no short stage (V = X, dX = dV, dw untouched). */
+void chela_oracle_short_long_conv_bwd(const double *X, const double *w, int m, const double *k, const double *dZ,
+                                      double *dX, double *dw, double *dk, int B, int d, int L)
+{
+    for (long i = 0; i < (long)d * L; ++i) dk[i] = 0.0;
+    if (w) for (long i = 0; i < (long)d * m; ++i) dw[i] = 0.0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int c = 0; c < d; ++c) {
+        double *U = (double *)malloc(sizeof(double) * (size_t)L * 4);
+        double *V = U + L, *dV = V + L, *dU = dV + L;
+        for (int b = 0; b < B; ++b) {
+            const double *x = X + ((long)b * d + c) * L;
+            const double *dz = dZ + ((long)b * d + c) * L;
+            double *dx = dX + ((long)b * d + c) * L;
+            for (int t = 0; t < L; ++t) {
+                if (w) {
+                    double a = 0.0;
+                    for (int j = 0; j < m && j <= t; ++j) a += w[(long)c * m + j] * x[t - j];
+                    U[t] = a;
+                    V[t] = a / (1.0 + exp(-a));
+                } else {
+                    U[t] = V[t] = x[t];
+                }
+            }
+            for (int t = 0; t < L; ++t) {
+                double a = 0.0;
+                for (int s = t; s < L; ++s) a += k[(long)c * L + (s - t)] * dz[s];
+                dV[t] = a;
+            }
+            for (int s = 0; s < L; ++s) {
+                double a = 0.0;
+                for (int t = s; t < L; ++t) a += dz[t] * V[t - s];
+                dk[(long)c * L + s] += a;
+            }
+            if (!w) {
+                for (int t = 0; t < L; ++t) dx[t] = dV[t];
+                continue;
+            }
+            for (int t = 0; t < L; ++t) {
+                const double sg = 1.0 / (1.0 + exp(-U[t]));
+                dU[t] = dV[t] * sg * (1.0 + U[t] * (1.0 - sg));
+            }
+            for (int t = 0; t < L; ++t) {
+                double a = 0.0;
+                for (int j = 0; j < m && t + j < L; ++j) a += w[(long)c * m + j] * dU[t + j];
+                dx[t] = a;
+            }
+            for (int j = 0; j < m; ++j) {
+                double a = 0.0;
+                for (int t = j; t < L; ++t) a += dU[t] * x[t - j];
+                dw[(long)c * m + j] += a;
+            }
+        }
+        free(U);
+    }
+}

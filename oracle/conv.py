@@ -56,3 +56,23 @@ def short_long_conv(X, w_short, k_long):
     """Z = K_l(silu(K_s(X))) (Eq. 8); w_short None skips the short stage and the activation (plain long convolution)."""
     V = _c(X) if w_short is None else short_conv(X, w_short, silu=True)
     return long_conv(V, k_long)
+
+
+def short_long_conv_bwd(X, w_short, k_long, dZ):
+    """(dX, dw_short, dk_long) of short_long_conv for the upstream gradient dZ; dw_short is None if w_short is."""
+    X, k, dZ = _c(X), _c(k_long), _c(dZ)
+    B, d, L = X.shape
+    if k.shape != (d, L) or dZ.shape != X.shape:
+        raise ValueError("shapes: X, dZ [B,d,L]; k_long [d,L]")
+    dX, dk = np.empty_like(X), np.empty_like(k)
+    lib = _load()
+    lib.chela_oracle_short_long_conv_bwd.restype = None
+    if w_short is None:
+        lib.chela_oracle_short_long_conv_bwd(_p(X), None, ctypes.c_int(0), _p(k), _p(dZ), _p(dX), None, _p(dk),
+                                             ctypes.c_int(B), ctypes.c_int(d), ctypes.c_int(L))
+        return dX, None, dk
+    w = _c(w_short)
+    dw = np.empty_like(w)
+    lib.chela_oracle_short_long_conv_bwd(_p(X), _p(w), ctypes.c_int(w.shape[1]), _p(k), _p(dZ), _p(dX), _p(dw), _p(dk),
+                                         ctypes.c_int(B), ctypes.c_int(d), ctypes.c_int(L))
+    return dX, dw, dk

@@ -103,3 +103,62 @@ def test_shape_errors():
         conv.long_conv(np.zeros((1, 2, 8)), np.zeros((2, 7)))
     with pytest.raises(ValueError):
         conv.short_conv(np.zeros((1, 2, 8)), np.zeros((3, 3)))
+
+
+# --------------------------------------------------------------------------- gradient
+def test_conv_gradient_finite_differences():
+    rng = np.random.default_rng(7)
+    X, w, k = _rand(rng, 2, 2, 12, 4)
+    dZ = rng.standard_normal(X.shape)
+    dX, dw, dk = conv.short_long_conv_bwd(X, w, k, dZ)
+
+    def loss(X_, w_, k_):
+        return float((conv.short_long_conv(X_, w_, k_) * dZ).sum())
+
+    h = 1e-6
+    for which, grad in enumerate((dX, dw, dk)):
+        base = [X, w, k]
+        it = np.nditer(base[which], flags=["multi_index"])
+        for _ in it:
+            idx = it.multi_index
+            args = [a.copy() for a in base]
+            args[which][idx] += h
+            up = loss(*args)
+            args[which][idx] -= 2 * h
+            dn = loss(*args)
+            fd = (up - dn) / (2 * h)
+            assert abs(fd - grad[idx]) <= 2e-6 * max(1.0, abs(fd)), (which, idx, fd, grad[idx])
+
+
+def test_long_conv_gradient_is_the_adjoint():
+    # without the short stage Z is bilinear in (X, k): <Z, dZ> = <X, dX> = <k, dk>
+    rng = np.random.default_rng(8)
+    X, _, k = _rand(rng, 3, 2, 33, 3)
+    dZ = rng.standard_normal(X.shape)
+    dX, dw, dk = conv.short_long_conv_bwd(X, None, k, dZ)
+    assert dw is None
+    lhs = float((conv.long_conv(X, k) * dZ).sum())
+    assert abs(lhs - float((X * dX).sum())) <= 1e-10 * max(1.0, abs(lhs))
+    assert abs(lhs - float((k * dk).sum())) <= 1e-10 * max(1.0, abs(lhs))
+    # the correlation with the kernel, by the library's correlate
+    want = np.stack([[np.correlate(dZ[b, c], k[c], mode="full")[33 - 1:] for c in range(2)] for b in range(3)])
+    np.testing.assert_allclose(dX, want, rtol=1e-11, atol=1e-12)
+
+
+def test_conv_gradient_identity_kernel_reduces_to_short_stage():
+    # long kernel = unit impulse: Z = silu(K_s X), so dX is the short correlation of dZ * silu'(U)
+    rng = np.random.default_rng(9)
+    X, w, k = _rand(rng, 1, 2, 20, 3)
+    k[:] = 0.0
+    k[:, 0] = 1.0
+    dZ = rng.standard_normal(X.shape)
+    dX, dw, dk = conv.short_long_conv_bwd(X, w, k, dZ)
+    U = conv.short_conv(X, w, silu=False)
+    sg = 1.0 / (1.0 + np.exp(-U))
+    dU = dZ * sg * (1.0 + U * (1.0 - sg))
+    want = np.zeros_like(X)
+    for t in range(20):
+        for j in range(3):
+            if t + j < 20:
+                want[..., t] += w[None, :, j] * dU[..., t + j]
+    np.testing.assert_allclose(dX, want, rtol=1e-12, atol=1e-12)
