@@ -178,14 +178,28 @@ size_t chela_linattn_noncausal_workspace_bytes(int B, int H, int N, int dk, int 
  *              chela_longconv_spectrum_bytes(d, L) bytes that is valid for this d and L and is reused for every batch
  *              until the kernel's weights change.
  * Sequences are zero-padded on chip to twice a transform length M >= L (M in {256, 1024, 4096, 16384}), which makes
- * the circular product of Eq. 7 equal the causal sum; L > 16384 is rejected (CHELA_ERR_BAD_SHAPE).  Forward only.
- * No scratch.  Pointers 16-byte aligned; Z must not overlap an input.  Everything else as for the calls above. */
+ * the circular product of Eq. 7 equal the causal sum; L > 16384 is rejected (CHELA_ERR_BAD_SHAPE).  The forward
+ * needs no scratch.  Pointers 16-byte aligned; Z must not overlap an input.  Everything else as for the calls above. */
 size_t chela_longconv_spectrum_bytes(int d, int L);
 int chela_longconv_spectrum(const float *k_long, void *spectrum, int d, int L, void *stream);
 int chela_shortlong_conv_fwd(const void *X, const float *w_short, int m, const void *spectrum, void *Z,
                              int B, int d, int L, void *stream);
 int chela_shortlong_conv_fwd_f32(const void *X, const float *w_short, int m, const void *spectrum, void *Z,
                                  int B, int d, int L, void *stream);
+/* Gradient of the map above for an upstream gradient dZ [B,d,L] (the paper gives no backward: this is the exact
+ * gradient of the two sums).  With u = K_s(X), v = silu(u):
+ *     dv[t] = sum_{s>=t} k_long[s-t] dZ[s]              (correlation with the long kernel: its conjugate spectrum)
+ *     d_k_long[c,s] = sum_b sum_{t>=s} dZ[b,c,t] v[b,c,t-s]         ([d,L] fp32 out, overwritten)
+ *     du = dv * silu'(u),  dX[t] = sum_j w_short[j] du[t+j]         ([B,d,L] out, I/O dtype)
+ *     d_w_short[c,j] = sum_b sum_t du[b,c,t] X[b,c,t-j]             ([d,m] fp32 out, overwritten)
+ * Nothing is saved by the forward call: u and v are recomputed from X.  With w_short = NULL (no short stage) dX = dv,
+ * v = X and d_w_short is ignored.  The backward supports m <= 16 taps.  Scratch (library workspace):
+ * chela_shortlong_conv_bwd_workspace_bytes().  Sums over batch and time are taken in a fixed order (deterministic). */
+int chela_shortlong_conv_bwd(const void *X, const float *w_short, int m, const void *spectrum, const void *dZ,
+                             void *dX, float *d_w_short, float *d_k_long, int B, int d, int L, void *stream);
+int chela_shortlong_conv_bwd_f32(const void *X, const float *w_short, int m, const void *spectrum, const void *dZ,
+                                 void *dX, float *d_w_short, float *d_k_long, int B, int d, int L, void *stream);
+size_t chela_shortlong_conv_bwd_workspace_bytes(int B, int d, int L, int has_short_kernel, int dtype);
 
 /* One decode step of autoregressive inference (the recurrent form, one token per (b,h)):
  *     S += k v^T  (in place, fp32) ;  o = S^T q.

@@ -77,6 +77,12 @@ def lib() -> ctypes.CDLL:
         f = getattr(L, name)
         f.argtypes = [vp, vp, i, vp, vp, i, i, i, vp]
         f.restype = i
+    for name in ("chela_shortlong_conv_bwd", "chela_shortlong_conv_bwd_f32"):
+        f = getattr(L, name)
+        f.argtypes = [vp, vp, i, vp, vp, vp, vp, vp, i, i, i, vp]
+        f.restype = i
+    L.chela_shortlong_conv_bwd_workspace_bytes.argtypes = [i, i, i, i, i]
+    L.chela_shortlong_conv_bwd_workspace_bytes.restype = sz
     L.chela_linattn_step.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, vp]
     L.chela_linattn_step.restype = i
     L.chela_linattn_workspace_bytes.argtypes = [i, i, i, i, i, i, i, i]
@@ -386,6 +392,28 @@ def chela_shortlong_conv_fwd(X, w_short, spectrum, Z=None, stream=None):
     with torch.cuda.device(X.device):
         _check(f(X.data_ptr(), wp, m, spectrum.data_ptr(), Z.data_ptr(), B, d, Lseq, _stream_ptr(stream)))
     return Z
+
+
+def chela_shortlong_conv_bwd(X, w_short, spectrum, dZ, stream=None):
+    """(dX, d_w_short, d_k_long) of chela_shortlong_conv_fwd for the upstream gradient dZ (d_w_short is None
+    without a short kernel)."""
+    if X.dim() != 3 or not X.is_cuda or not X.is_contiguous() or dZ.shape != X.shape or dZ.dtype != X.dtype \
+            or not dZ.is_contiguous():
+        raise ValueError("X and dZ must be contiguous device tensors [B, d, L] of one dtype")
+    sfx, _ = _suffix(X)
+    B, d, Lseq = X.shape
+    m, wp, dwp, dw = 0, None, None, None
+    if w_short is not None:
+        m, wp = w_short.shape[1], w_short.data_ptr()
+        dw = torch.empty_like(w_short)
+        dwp = dw.data_ptr()
+    dX = torch.empty_like(X)
+    dk = torch.empty((d, Lseq), dtype=torch.float32, device=X.device)
+    f = getattr(lib(), "chela_shortlong_conv_bwd" + sfx)
+    with torch.cuda.device(X.device):
+        _check(f(X.data_ptr(), wp, m, spectrum.data_ptr(), dZ.data_ptr(), dX.data_ptr(), dwp, dk.data_ptr(), B, d, Lseq,
+                 _stream_ptr(stream)))
+    return dX, dw, dk
 
 
 def chela_linattn_step(q, k, v, S, o=None, stream=None):

@@ -147,7 +147,8 @@ static std::vector<ProfRec> g_prof_free;     // event pairs to re-use
 static const char* const kKernelNames[KID_COUNT] = {
     "bf16_seg_state_kernel", "scan_states_kernel", "bf16_fwd_sweep_kernel", "bf16_bwd_sweep_kernel",
     "f32_seg_state_kernel", "f32_sweep_kernel", "copy_probe_kernel", "bf16_step_kernel", "affine_grad_kernel",
-    "bf16_apply_state_kernel", "longconv_spectrum_kernel", "shortlong_conv_kernel"};
+    "bf16_apply_state_kernel", "longconv_spectrum_kernel", "shortlong_conv_kernel",
+    "shortconv_bwd_kernel", "longconv_dk_kernel"};
 
 ProfScope::ProfScope(int id, hipStream_t s) : slot(-1), st(s)
 {
@@ -634,6 +635,69 @@ int chela_shortlong_conv_fwd_f32(const void* X, const float* w_short, int m, con
                                  int d, int L, void* stream)
 {
     return shortlong_common(X, w_short, m, spectrum, Y, B, d, L, CHELA_DTYPE_F32, stream);
+}
+
+static size_t conv_bwd_ws_bytes(int B, int d, int L, int dtype, bool has_short)
+{
+    if (!has_short || B <= 0 || d <= 0 || L <= 0) return 0;
+    const size_t n = (size_t)B * d * L;
+    return n * sizeof(float) + n * (dtype == CHELA_DTYPE_BF16 ? 2 : 4);
+}
+
+size_t chela_shortlong_conv_bwd_workspace_bytes(int B, int d, int L, int has_short_kernel, int dtype)
+{
+    if (dtype != CHELA_DTYPE_BF16 && dtype != CHELA_DTYPE_F32) return 0;
+    return conv_bwd_ws_bytes(B, d, L, dtype, has_short_kernel != 0);
+}
+
+static int shortlong_bwd_common(const void* X, const float* w_short, int m, const void* spectrum, const void* dZ,
+                                void* dX, float* d_w_short, float* d_k_long, int B, int d, int L, int dtype,
+                                void* stream)
+{
+    if (B < 0 || d < 0 || L < 0) return CHELA_ERR_BAD_SHAPE;
+    if (w_short != nullptr && (m < 1 || m > 16)) return CHELA_ERR_BAD_SHAPE;      // the backward keeps <= 16 tap sums
+    if ((unsigned long long)B * (unsigned long long)d > 0x7fffffffull) return CHELA_ERR_BAD_SHAPE;
+    if (d == 0 || L == 0) return CHELA_OK;
+    if (conv_fft_size(L) == 0) return CHELA_ERR_BAD_SHAPE;
+    hipStream_t st = (hipStream_t)stream;
+    if (B == 0) {
+        // no data: the kernels received no gradient
+        if (!d_k_long || (w_short && !d_w_short)) return CHELA_ERR_NULL_POINTER;
+        hipError_t e = hipMemsetAsync(d_k_long, 0, (size_t)d * L * 4, st);
+        if (e == hipSuccess && w_short) e = hipMemsetAsync(d_w_short, 0, (size_t)d * m * 4, st);
+        return e == hipSuccess ? CHELA_OK : CHELA_ERR_HIP;
+    }
+    if (!X || !spectrum || !dZ || !dX || !d_k_long || (w_short && !d_w_short)) return CHELA_ERR_NULL_POINTER;
+    if (((uintptr_t)X | (uintptr_t)spectrum | (uintptr_t)dZ | (uintptr_t)dX | (uintptr_t)d_k_long | (uintptr_t)w_short |
+         (uintptr_t)d_w_short) & 15u)
+        return CHELA_ERR_MISALIGNED;
+    const size_t es = dtype == CHELA_DTYPE_BF16 ? 2 : 4, tb = (size_t)B * d * L * es;
+    const Range in[4] = {{(const char*)X, tb}, {(const char*)dZ, tb},
+                         {(const char*)spectrum, chela_longconv_spectrum_bytes(d, L)},
+                         {(const char*)w_short, w_short ? (size_t)d * m * 4 : 0}};
+    const Range out[3] = {{(const char*)dX, tb}, {(const char*)d_k_long, (size_t)d * L * 4},
+                          {(const char*)d_w_short, w_short ? (size_t)d * m * 4 : 0}};
+    for (int o = 0; o < 3; ++o) {
+        for (const Range& r : in) if (overlap(out[o], r)) return CHELA_ERR_ALIASING;
+        for (int o2 = o + 1; o2 < 3; ++o2) if (overlap(out[o], out[o2])) return CHELA_ERR_ALIASING;
+    }
+    float* ws = nullptr;
+    int rc = get_workspace(conv_bwd_ws_bytes(B, d, L, dtype, w_short != nullptr), &ws);
+    if (rc != CHELA_OK) return rc;
+    return launch_shortlong_conv_bwd(X, w_short, m, spectrum, dZ, dX, d_w_short, d_k_long, ws, B, d, L,
+                                     dtype == CHELA_DTYPE_BF16 ? 0 : 1, st) == hipSuccess ? CHELA_OK : CHELA_ERR_HIP;
+}
+
+int chela_shortlong_conv_bwd(const void* X, const float* w_short, int m, const void* spectrum, const void* dZ,
+                             void* dX, float* d_w_short, float* d_k_long, int B, int d, int L, void* stream)
+{
+    return shortlong_bwd_common(X, w_short, m, spectrum, dZ, dX, d_w_short, d_k_long, B, d, L, CHELA_DTYPE_BF16, stream);
+}
+
+int chela_shortlong_conv_bwd_f32(const void* X, const float* w_short, int m, const void* spectrum, const void* dZ,
+                                 void* dX, float* d_w_short, float* d_k_long, int B, int d, int L, void* stream)
+{
+    return shortlong_bwd_common(X, w_short, m, spectrum, dZ, dX, d_w_short, d_k_long, B, d, L, CHELA_DTYPE_F32, stream);
 }
 
 int chela_linattn_step(const void* q, const void* k, const void* v, float* S, void* o, int B, int H, int dk, int dv,

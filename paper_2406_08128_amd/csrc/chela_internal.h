@@ -80,10 +80,15 @@ int conv_fft_size(int L);
 hipError_t launch_longconv_spectrum(const float* k, void* Kf, int d, int L, hipStream_t st);
 hipError_t launch_shortlong_conv(const void* X, const float* w_short, int m, const void* Kf, void* Y, long BD, int d,
                                  int L, int dtype, hipStream_t st);
+// Gradient: dX [B][d][L] (I/O dtype), dw [d][m] (only with a short kernel, m <= 16), dk [d][L] fp32.
+// ws_dV: B*d*L floats of scratch when there is a short kernel.
+hipError_t launch_shortlong_conv_bwd(const void* X, const float* w_short, int m, const void* Kf, const void* dZ,
+                                     void* dX, float* dw, float* dk, float* ws_dV, int B, int d, int L, int dtype,
+                                     hipStream_t st);
 
 // Kernel classes for the per-kernel timing aid.
 enum { KID_SEG_STATE_BF16 = 0, KID_SCAN = 1, KID_FWD_SWEEP_BF16 = 2, KID_BWD_SWEEP_BF16 = 3, KID_SEG_STATE_F32 = 4,
-       KID_SWEEP_F32 = 5, KID_COPY = 6, KID_STEP_BF16 = 7, KID_AFFINE_GRAD = 8, KID_APPLY_BF16 = 9, KID_CONV_SPECTRUM = 10, KID_CONV_FWD = 11, KID_COUNT = 12 };
+       KID_SWEEP_F32 = 5, KID_COPY = 6, KID_STEP_BF16 = 7, KID_AFFINE_GRAD = 8, KID_APPLY_BF16 = 9, KID_CONV_SPECTRUM = 10, KID_CONV_FWD = 11, KID_CONV_SHORT_BWD = 12, KID_CONV_DK = 13, KID_COUNT = 14 };
 
 // Brackets one kernel launch with HIP events on its stream while profiling is enabled; otherwise does nothing.
 struct ProfScope {

@@ -65,6 +65,8 @@ __device__ __forceinline__ void dft16(cplx (&v)[16])
 }
 
 __host__ __device__ constexpr int conv_threads(int M) { return M / 16 < 64 ? 64 : M / 16; }
+// the kernel-gradient kernel keeps two spectra in registers besides the transform in flight: half as many threads
+__host__ __device__ constexpr int conv_threads_dk(int M) { return M / 32 < 64 ? 64 : M / 32; }
 __host__ __device__ constexpr bool conv_lead4(int M) { return M == 1024 || M == 16384; }
 __host__ __device__ constexpr int conv_pad(int i) { return i + (i >> 4); }
 
@@ -93,13 +95,13 @@ __device__ __forceinline__ int spectrum_pos(int k)
     return pos;
 }
 
-// One radix-16 pass over sub-transforms of length N16 (stride N16 / 16), forward or inverse, one 16-point transform
-// per thread.  With the length fixed at compile time the 16 LDS addresses are one base plus constants (the padding
-// of a multiple of 16 is itself a constant), and the last pass (N16 = 16) has no twiddles at all.
-template <int M, int N16, bool INV>
+// One radix-16 pass over sub-transforms of length N16 (stride N16 / 16), forward or inverse, 16-point transforms
+// in registers, T threads.  With the length fixed at compile time the 16 LDS addresses are one base plus constants
+// (the padding of a multiple of 16 is itself a constant), and the last pass (N16 = 16) has no twiddles at all.
+template <int M, int T, int N16, bool INV>
 __device__ __forceinline__ void pass16(cplx* a, const cplx* lo, const cplx* hi, int tid)
 {
-    constexpr int T = conv_threads(M), S = N16 / 16;
+    constexpr int S = N16 / 16;
     constexpr int STEP = S >= 16 ? S + S / 16 : 1;                 // padded distance between the transform's points
     for (int g = tid; g < M / 16; g += T) {
         const int block = g / S, j = g - block * S;
@@ -140,10 +142,9 @@ __device__ __forceinline__ void pass16(cplx* a, const cplx* lo, const cplx* hi, 
 
 // All forward passes (INV = false) or all inverse passes in reverse order (INV = true) over a[] in LDS.
 // A __syncthreads() separates the passes; the caller synchronises before and after.
-template <int M, bool INV>
+template <int M, int T, bool INV>
 __device__ __forceinline__ void fft_passes(cplx* a, const cplx* lo, const cplx* hi, int tid)
 {
-    constexpr int T = conv_threads(M);
     constexpr int M16 = conv_lead4(M) ? M / 4 : M;     // what the radix-16 passes transform (blocks of this length)
     static_assert(M16 == 256 || M16 == 4096, "radix-16 part must be 16^2 or 16^3");
     auto lead4 = [&]() __attribute__((always_inline)) {
@@ -161,15 +162,15 @@ __device__ __forceinline__ void fft_passes(cplx* a, const cplx* lo, const cplx* 
     };
     if (!INV) {
         if (conv_lead4(M)) { lead4(); __syncthreads(); }
-        if (M16 == 4096) { pass16<M, 4096, false>(a, lo, hi, tid); __syncthreads(); }
-        pass16<M, 256, false>(a, lo, hi, tid);
+        if (M16 == 4096) { pass16<M, T, 4096, false>(a, lo, hi, tid); __syncthreads(); }
+        pass16<M, T, 256, false>(a, lo, hi, tid);
         __syncthreads();
-        pass16<M, 16, false>(a, lo, hi, tid);
+        pass16<M, T, 16, false>(a, lo, hi, tid);
     } else {
-        pass16<M, 16, true>(a, lo, hi, tid);
+        pass16<M, T, 16, true>(a, lo, hi, tid);
         __syncthreads();
-        pass16<M, 256, true>(a, lo, hi, tid);
-        if (M16 == 4096) { __syncthreads(); pass16<M, 4096, true>(a, lo, hi, tid); }
+        pass16<M, T, 256, true>(a, lo, hi, tid);
+        if (M16 == 4096) { __syncthreads(); pass16<M, T, 4096, true>(a, lo, hi, tid); }
         if (conv_lead4(M)) { __syncthreads(); lead4(); }
     }
 }
@@ -196,10 +197,10 @@ template <> struct IoPair<bf16> {
     }
 };
 
-template <int M>
+template <int M, int T>
 __device__ __forceinline__ void build_tables(cplx* lo, cplx* hi, int tid)
 {
-    for (int t = tid; t < 128; t += conv_threads(M)) {
+    for (int t = tid; t < 128; t += T) {
         float s, c;
         sincospif(-2.0f * (float)t / (float)M, &s, &c);
         lo[t] = mk(c, s);
@@ -208,66 +209,45 @@ __device__ __forceinline__ void build_tables(cplx* lo, cplx* hi, int tid)
     }
 }
 
-// Spectrum of a real sequence of length 2M from the length-M transform Z of its even/odd packing:
-//   X[k] = (Z[k] + conj Z[M-k]) / 2 + W_2M^k (Z[k] - conj Z[M-k]) / (2i),  k = 0 .. M  (Z[M] = Z[0]).
-// Kernel spectrum of one channel: K[c][0 .. M], complex fp32.
-template <int M>
-__global__ __launch_bounds__(conv_threads(M)) void longconv_spectrum_kernel(const float* __restrict__ k,
-                                                                           float2* __restrict__ Kf, int L)
+// Bins k and M - k of the spectrum of a real sequence of length 2M from the length-M transform Z of its even/odd
+// packing:  X[k] = (Z[k] + conj Z[M-k]) / 2 + W_2M^k (Z[k] - conj Z[M-k]) / (2i),  k = 0 .. M  (Z[M] = Z[0]).
+// A = Z[k], Bc = conj Z[M-k], w = W_2M^k.  For k = 0 this gives X[0] and X[M] (both real).
+__device__ __forceinline__ void untangle(cplx A, cplx Bc, cplx w, cplx& Xk, cplx& Xmk)
 {
-    constexpr int T = conv_threads(M);
-    __shared__ __attribute__((aligned(16))) unsigned char lds[ConvLds<M>::BYTES];
-    cplx* a = reinterpret_cast<cplx*>(lds);
-    cplx* lo = a + ConvLds<M>::DATA;
-    cplx* hi = lo + 128;
-    const int tid = threadIdx.x;
-    const long c = blockIdx.x;
-    const float* kc = k + c * (long)L;
-    build_tables<M>(lo, hi, tid);
-    for (int n = tid; n < M; n += T) {
-        const int t = 2 * n;
-        a[conv_pad(n)] = mk(t < L ? kc[t] : 0.f, t + 1 < L ? kc[t + 1] : 0.f);
-    }
-    __syncthreads();
-    fft_passes<M, false>(a, lo, hi, tid);
-    __syncthreads();
-    float2* out = Kf + c * (long)(M + 1);
-    for (int kk = tid; kk <= M / 2; kk += T) {
-        const cplx A = a[conv_pad(spectrum_pos<M>(kk))];
-        const cplx Bc = conj(a[conv_pad(spectrum_pos<M>((M - kk) & (M - 1)))]);
-        const cplx xe = mk(0.5f * (A.x + Bc.x), 0.5f * (A.y + Bc.y));
-        const cplx xo = mul_neg_i(mk(0.5f * (A.x - Bc.x), 0.5f * (A.y - Bc.y)));
-        float s, co;
-        sincospif(-(float)kk / (float)M, &s, &co);
-        const cplx wx = cmul(mk(co, s), xo);
-        const cplx Xk = cadd(xe, wx), Xmk = conj(csub(xe, wx));
-        out[kk] = make_float2(Xk.x, Xk.y);
-        out[M - kk] = make_float2(Xmk.x, Xmk.y);
-    }
+    const cplx xe = mk(0.5f * (A.x + Bc.x), 0.5f * (A.y + Bc.y));
+    const cplx xo = mul_neg_i(mk(0.5f * (A.x - Bc.x), 0.5f * (A.y - Bc.y)));
+    const cplx wx = cmul(w, xo);
+    Xk = cadd(xe, wx);
+    Xmk = conj(csub(xe, wx));
 }
 
-// One workgroup per (b, c).  w_short == nullptr: no short kernel and no activation (plain long convolution).
-template <int M, typename IO>
-__global__ __launch_bounds__(conv_threads(M)) void shortlong_conv_kernel(const IO* __restrict__ X,
-                                                                        const float* __restrict__ w_short, int m,
-                                                                        const float2* __restrict__ Kf,
-                                                                        IO* __restrict__ Y, int d, int L)
+// The inverse: from bins Y[k], Y[M-k] of a real sequence's spectrum to Z[k], Z[M-k] of its packing.
+//   Ye = (Y[k] + conj Y[M-k]) / 2, Yo = (Y[k] - conj Y[M-k]) / 2 * conj(W_2M^k); Z[k] = Ye + i Yo,
+//   Z[M-k] = conj(Ye) + i conj(Yo).  For k = 0 (Y[0], Y[M] real) Z[0] = (Y0 + YM)/2 + i (Y0 - YM)/2.
+__device__ __forceinline__ void tangle(cplx Yk, cplx Ymk, cplx w, cplx& Zk, cplx& Zmk)
 {
-    constexpr int T = conv_threads(M);
-    __shared__ __attribute__((aligned(16))) unsigned char lds[ConvLds<M>::BYTES];
-    cplx* a = reinterpret_cast<cplx*>(lds);
-    cplx* lo = a + ConvLds<M>::DATA;
-    cplx* hi = lo + 128;
-    const int tid = threadIdx.x;
-    const long bc = blockIdx.x;
-    const int c = (int)(bc % d);
-    const IO* x = X + bc * (long)L;
-    IO* y = Y + bc * (long)L;
-    const bool vec_ok = (L & 1) == 0;        // rows start on a pair boundary
-    build_tables<M>(lo, hi, tid);
+    const cplx Yc = conj(Ymk);
+    const cplx ye = mk(0.5f * (Yk.x + Yc.x), 0.5f * (Yk.y + Yc.y));
+    const cplx yo = cmul(mk(0.5f * (Yk.x - Yc.x), 0.5f * (Yk.y - Yc.y)), conj(w));
+    Zk = cadd(ye, mul_pos_i(yo));
+    Zmk = cadd(conj(ye), mul_pos_i(conj(yo)));
+}
 
-    // ---- load, short kernel, activation, packing
-    if (w_short != nullptr) {
+__device__ __forceinline__ cplx w2m(int k, int M)      // W_2M^k = exp(-i pi k / M)
+{
+    float s, c;
+    sincospif(-(float)k / (float)M, &s, &c);
+    return mk(c, s);
+}
+
+// x (one sequence of L steps) -> optional short kernel and activation -> packed complex z[n] = v[2n] + i v[2n+1]
+// in a[], zero beyond L.  Ends with the data in place but NOT synchronised.
+template <int M, int T, typename IO>
+__device__ __forceinline__ void stage_input(const IO* __restrict__ x, const float* __restrict__ wc, int m, int L,
+                                            cplx* a, int tid)
+{
+    const bool vec_ok = (L & 1) == 0;        // rows start on a pair boundary
+    if (wc != nullptr) {
         // raw x as floats behind 32 zeros (the zero history), so that no tap needs a bounds check
         float* sx = reinterpret_cast<float*>(a);
         constexpr int ZP = 32;
@@ -285,7 +265,6 @@ __global__ __launch_bounds__(conv_threads(M)) void shortlong_conv_kernel(const I
         __syncthreads();
         constexpr int PER = M / T;
         cplx z[PER];
-        const float* wc = w_short + (long)c * m;
 #pragma unroll
         for (int i = 0; i < PER; ++i) z[i] = mk(0.f, 0.f);
         // outputs t and t+1 share all but one of their inputs: x[t+1-j], j = 0..m, are read once
@@ -321,56 +300,249 @@ __global__ __launch_bounds__(conv_threads(M)) void shortlong_conv_kernel(const I
             a[conv_pad(n)] = mk(v0, v1);
         }
     }
+}
+
+// Kernel spectrum of one channel: K[c][0 .. M], complex fp32.
+template <int M>
+__global__ __launch_bounds__(conv_threads(M)) void longconv_spectrum_kernel(const float* __restrict__ k,
+                                                                           float2* __restrict__ Kf, int L)
+{
+    constexpr int T = conv_threads(M);
+    __shared__ __attribute__((aligned(16))) unsigned char lds[ConvLds<M>::BYTES];
+    cplx* a = reinterpret_cast<cplx*>(lds);
+    cplx* lo = a + ConvLds<M>::DATA;
+    cplx* hi = lo + 128;
+    const int tid = threadIdx.x;
+    const long c = blockIdx.x;
+    build_tables<M, T>(lo, hi, tid);
+    stage_input<M, T, float>(k + c * (long)L, nullptr, 0, L, a, tid);
+    __syncthreads();
+    fft_passes<M, T, false>(a, lo, hi, tid);
+    __syncthreads();
+    float2* out = Kf + c * (long)(M + 1);
+    for (int kk = tid; kk <= M / 2; kk += T) {
+        cplx Xk, Xmk;
+        untangle(a[conv_pad(spectrum_pos<M>(kk))], conj(a[conv_pad(spectrum_pos<M>((M - kk) & (M - 1)))]), w2m(kk, M), Xk,
+                 Xmk);
+        out[kk] = make_float2(Xk.x, Xk.y);
+        out[M - kk] = make_float2(Xmk.x, Xmk.y);
+    }
+}
+
+// One workgroup per (b, c).  w_short == nullptr: no short kernel and no activation (plain long convolution).
+// CONJ: multiply by the conjugate kernel spectrum, i.e. correlate with the kernel instead of convolving,
+// y[t] = sum_{s >= t} k[s - t] x[s] (the gradient with respect to the long kernel's input).
+template <int M, typename IN, typename OUT, bool CONJ>
+__global__ __launch_bounds__(conv_threads(M)) void shortlong_conv_kernel(const IN* __restrict__ X,
+                                                                        const float* __restrict__ w_short, int m,
+                                                                        const float2* __restrict__ Kf,
+                                                                        OUT* __restrict__ Y, int d, int L)
+{
+    constexpr int T = conv_threads(M);
+    __shared__ __attribute__((aligned(16))) unsigned char lds[ConvLds<M>::BYTES];
+    cplx* a = reinterpret_cast<cplx*>(lds);
+    cplx* lo = a + ConvLds<M>::DATA;
+    cplx* hi = lo + 128;
+    const int tid = threadIdx.x;
+    const long bc = blockIdx.x;
+    const int c = (int)(bc % d);
+    OUT* y = Y + bc * (long)L;
+    build_tables<M, T>(lo, hi, tid);
+    stage_input<M, T, IN>(X + bc * (long)L, w_short ? w_short + (long)c * m : nullptr, m, L, a, tid);
     __syncthreads();
 
-    fft_passes<M, false>(a, lo, hi, tid);
+    fft_passes<M, T, false>(a, lo, hi, tid);
     __syncthreads();
 
     // ---- spectrum of v times spectrum of the kernel, re-packed for the inverse transform (pairs k, M - k)
     const float2* Kc = Kf + (long)c * (M + 1);
     for (int kk = tid; kk <= M / 2; kk += T) {
         const int p1 = conv_pad(spectrum_pos<M>(kk)), p2 = conv_pad(spectrum_pos<M>((M - kk) & (M - 1)));
-        const cplx A = a[p1], Bc = conj(a[p2]);
-        const cplx xe = mk(0.5f * (A.x + Bc.x), 0.5f * (A.y + Bc.y));
-        const cplx xo = mul_neg_i(mk(0.5f * (A.x - Bc.x), 0.5f * (A.y - Bc.y)));
-        float s, co;
-        sincospif(-(float)kk / (float)M, &s, &co);
-        const cplx w = mk(co, s);                       // W_2M^k
-        const cplx wx = cmul(w, xo);
+        const cplx w = w2m(kk, M);
+        cplx Xk, Xmk, Zk, Zmk;
+        untangle(a[p1], conj(a[p2]), w, Xk, Xmk);
         const float2 k1 = Kc[kk], k2 = Kc[M - kk];
-        const cplx Yk = cmul(cadd(xe, wx), mk(k1.x, k1.y));               // Y[k]
-        const cplx Ymk = cmul(conj(csub(xe, wx)), mk(k2.x, k2.y));        // Y[M-k]
-        // Zy[k] = Ye + i Yo, Zy[M-k] = conj(Ye) + i conj(Yo);  Ye = (Y[k] + conj Y[M-k]) / 2,
-        // Yo = (Y[k] - conj Y[M-k]) / 2 * conj(W_2M^k)
-        const cplx Yc = conj(Ymk);
-        const cplx ye = mk(0.5f * (Yk.x + Yc.x), 0.5f * (Yk.y + Yc.y));
-        const cplx yo = cmul(mk(0.5f * (Yk.x - Yc.x), 0.5f * (Yk.y - Yc.y)), conj(w));
-        const cplx Zk = cadd(ye, mul_pos_i(yo));
-        const cplx Zmk = cadd(conj(ye), mul_pos_i(conj(yo)));
+        const cplx K1 = mk(k1.x, CONJ ? -k1.y : k1.y), K2 = mk(k2.x, CONJ ? -k2.y : k2.y);
         if (kk == 0) {
-            // bins 0 and M are real: X[0] = Re + Im, X[M] = Re - Im of Z[0]; they share storage slot 0
-            const float x0 = (A.x + A.y) * k1.x, xm = (A.x - A.y) * k2.x;
-            a[p1] = mk(0.5f * (x0 + xm), 0.5f * (x0 - xm));
+            // bins 0 and M are real and share storage slot 0
+            const float y0 = Xk.x * K1.x, ym = Xmk.x * K2.x;
+            a[p1] = mk(0.5f * (y0 + ym), 0.5f * (y0 - ym));
         } else {
+            tangle(cmul(Xk, K1), cmul(Xmk, K2), w, Zk, Zmk);
             a[p1] = Zk;
             if (p2 != p1) a[p2] = Zmk;
         }
     }
     __syncthreads();
 
-    fft_passes<M, true>(a, lo, hi, tid);
+    fft_passes<M, T, true>(a, lo, hi, tid);
     __syncthreads();
 
     // ---- unpack, scale, store
+    const bool vec_ok = (L & 1) == 0;
     const float scale = 1.0f / (float)M;
     for (int n = tid; n < M; n += T) {
         const int t = 2 * n;
         if (t < L) {
             const cplx v = a[conv_pad(n)];
-            if (vec_ok) IoPair<IO>::store2(y + t, v.x * scale, v.y * scale);
-            else { y[t] = (IO)(v.x * scale); if (t + 1 < L) y[t + 1] = (IO)(v.y * scale); }
+            if (vec_ok) IoPair<OUT>::store2(y + t, v.x * scale, v.y * scale);
+            else { y[t] = (OUT)(v.x * scale); if (t + 1 < L) y[t + 1] = (OUT)(v.y * scale); }
         }
     }
+}
+
+// Gradient with respect to the long kernel: dk[c][s] = sum_b sum_{t >= s} dZ[b,c,t] v[b,c,t-s], v = silu(K_s x)
+// (given as a tensor: the short-stage kernel below writes it out, without a short stage it is x itself).
+// In the Fourier domain the correlation is DZ conj(V); the products of all batch entries are added up in
+// registers (each thread owns the bin pairs k, M - k it would handle in the point-wise stage) and transformed back
+// once.  One workgroup per channel.
+template <int M, typename IO>
+__global__ __launch_bounds__(conv_threads_dk(M)) void longconv_dk_kernel(const IO* __restrict__ V,
+                                                                        const IO* __restrict__ dZ,
+                                                                        float* __restrict__ dk, int B, int d, int L)
+{
+    constexpr int T = conv_threads_dk(M);
+    constexpr int NP = (M / 2) / T + 1;                  // bin pairs per thread
+    __shared__ __attribute__((aligned(16))) unsigned char lds[ConvLds<M>::BYTES];
+    cplx* a = reinterpret_cast<cplx*>(lds);
+    cplx* lo = a + ConvLds<M>::DATA;
+    cplx* hi = lo + 128;
+    const int tid = threadIdx.x;
+    const int c = blockIdx.x;
+    build_tables<M, T>(lo, hi, tid);
+    cplx accK[NP], accMK[NP], Vk[NP], Vmk[NP];
+#pragma unroll
+    for (int i = 0; i < NP; ++i) { accK[i] = mk(0.f, 0.f); accMK[i] = mk(0.f, 0.f); }
+
+    for (int b = 0; b < B; ++b) {
+        const long row = ((long)b * d + c) * L;
+        stage_input<M, T, IO>(V + row, nullptr, 0, L, a, tid);
+        __syncthreads();
+        fft_passes<M, T, false>(a, lo, hi, tid);
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < NP; ++i) {
+            const int kk = tid + T * i;
+            if (kk <= M / 2)
+                untangle(a[conv_pad(spectrum_pos<M>(kk))], conj(a[conv_pad(spectrum_pos<M>((M - kk) & (M - 1)))]),
+                         w2m(kk, M), Vk[i], Vmk[i]);
+        }
+        __syncthreads();
+        stage_input<M, T, IO>(dZ + row, nullptr, 0, L, a, tid);
+        __syncthreads();
+        fft_passes<M, T, false>(a, lo, hi, tid);
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < NP; ++i) {
+            const int kk = tid + T * i;
+            if (kk <= M / 2) {
+                cplx Gk, Gmk;
+                untangle(a[conv_pad(spectrum_pos<M>(kk))], conj(a[conv_pad(spectrum_pos<M>((M - kk) & (M - 1)))]),
+                         w2m(kk, M), Gk, Gmk);
+                accK[i] = cadd(accK[i], cmul(Gk, conj(Vk[i])));
+                accMK[i] = cadd(accMK[i], cmul(Gmk, conj(Vmk[i])));
+            }
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int i = 0; i < NP; ++i) {
+        const int kk = tid + T * i;
+        if (kk <= M / 2) {
+            const int p1 = conv_pad(spectrum_pos<M>(kk)), p2 = conv_pad(spectrum_pos<M>((M - kk) & (M - 1)));
+            if (kk == 0) {
+                a[p1] = mk(0.5f * (accK[i].x + accMK[i].x), 0.5f * (accK[i].x - accMK[i].x));
+            } else {
+                cplx Zk, Zmk;
+                tangle(accK[i], accMK[i], w2m(kk, M), Zk, Zmk);
+                a[p1] = Zk;
+                if (p2 != p1) a[p2] = Zmk;
+            }
+        }
+    }
+    __syncthreads();
+    fft_passes<M, T, true>(a, lo, hi, tid);
+    __syncthreads();
+    float* out = dk + (long)c * L;
+    const float scale = 1.0f / (float)M;
+    for (int n = tid; n < M; n += T) {
+        const int t = 2 * n;
+        if (t < L) {
+            const cplx v = a[conv_pad(n)];
+            out[t] = v.x * scale;
+            if (t + 1 < L) out[t + 1] = v.y * scale;
+        }
+    }
+}
+
+// Gradient through the activation and the short kernel.  dV is the gradient with respect to v = silu(u), u = K_s x:
+//   dU = dV silu'(u),  dX[t] = sum_j w[j] dU[t+j],  dw[c][j] = sum_b sum_t dU[b,c,t] x[b,c,t-j].
+// It also writes v = silu(u) out.  One workgroup per channel walks the batch entries in tiles of TL steps; x is staged with m-1 steps of history and
+// dU with m-1 steps of look-ahead; the tap sums stay in registers (MT >= m) until one reduction at the very end.
+constexpr int kShortTile = 2048, kShortMaxTaps = 16;
+
+template <typename IO>
+__global__ __launch_bounds__(256) void shortconv_bwd_kernel(const IO* __restrict__ X, const float* __restrict__ w_short,
+                                                           int m, const float* __restrict__ dV, IO* __restrict__ dX,
+                                                           float* __restrict__ dw, IO* __restrict__ Vout, int B, int d,
+                                                           int L)
+{
+    constexpr int TL = kShortTile, MT = kShortMaxTaps, H = MT;       // H: halo on either side
+    __shared__ float sx[TL + 2 * H];      // x[t0 - H .. t0 + TL + H)
+    __shared__ float su[TL + H];          // dU[t0 .. t0 + TL + H)
+    __shared__ float red[MT][4];
+    const int tid = threadIdx.x, c = blockIdx.x;
+    float wreg[MT], acc[MT];
+#pragma unroll
+    for (int j = 0; j < MT; ++j) { wreg[j] = j < m ? w_short[(long)c * m + j] : 0.f; acc[j] = 0.f; }
+    for (int b = 0; b < B; ++b) {
+        const long row = ((long)b * d + c) * L;
+        for (int t0 = 0; t0 < L; t0 += TL) {
+            __syncthreads();
+            for (int i = tid; i < TL + 2 * H; i += 256) {
+                const int t = t0 - H + i;
+                sx[i] = (t >= 0 && t < L) ? (float)X[row + t] : 0.f;
+            }
+            __syncthreads();
+            for (int i = tid; i < TL + H; i += 256) {
+                const int t = t0 + i;
+                float du = 0.f;
+                if (t < L) {
+                    float u = 0.f;
+#pragma unroll
+                    for (int j = 0; j < MT; ++j) u = fmaf(wreg[j], sx[H + i - j], u);
+                    const float sg = __builtin_amdgcn_rcpf(1.f + __expf(-u));
+                    du = dV[row + t] * sg * (1.f + u * (1.f - sg));
+                    if (i < TL) Vout[row + t] = (IO)(u * sg);       // v = silu(u), for the long kernel's gradient
+                }
+                su[i] = du;
+            }
+            __syncthreads();
+            for (int i = tid; i < TL; i += 256) {
+                const int t = t0 + i;
+                if (t < L) {
+                    float dx = 0.f;
+                    const float du = su[i];
+#pragma unroll
+                    for (int j = 0; j < MT; ++j) {
+                        dx = fmaf(wreg[j], su[i + j], dx);
+                        acc[j] = fmaf(du, sx[H + i - j], acc[j]);
+                    }
+                    dX[row + t] = (IO)dx;
+                }
+            }
+        }
+    }
+    // the taps' sums over this channel: wave reduction, then across the four waves
+#pragma unroll
+    for (int j = 0; j < MT; ++j) {
+        float v = acc[j];
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+        if ((tid & 63) == 0) red[j][tid >> 6] = v;
+    }
+    __syncthreads();
+    if (tid < m) dw[(long)c * m + tid] = red[tid][0] + red[tid][1] + red[tid][2] + red[tid][3];
 }
 
 int conv_fft_size(int L)
@@ -397,18 +569,18 @@ hipError_t launch_longconv_spectrum(const float* k, void* Kf, int d, int L, hipS
     return hipGetLastError();
 }
 
-template <typename IO>
-static hipError_t conv_dispatch(const IO* X, const float* w, int m, const float2* Kf, IO* Y, long BD, int d, int L,
+template <typename IN, typename OUT, bool CONJ>
+static hipError_t conv_dispatch(const IN* X, const float* w, int m, const float2* Kf, OUT* Y, long BD, int d, int L,
                                 hipStream_t st)
 {
     const int M = conv_fft_size(L);
     ProfScope prof(KID_CONV_FWD, st);
     const dim3 grid((unsigned)BD);
     switch (M) {
-        case 256: hipLaunchKernelGGL((shortlong_conv_kernel<256, IO>), grid, dim3(conv_threads(256)), 0, st, X, w, m, Kf, Y, d, L); break;
-        case 1024: hipLaunchKernelGGL((shortlong_conv_kernel<1024, IO>), grid, dim3(conv_threads(1024)), 0, st, X, w, m, Kf, Y, d, L); break;
-        case 4096: hipLaunchKernelGGL((shortlong_conv_kernel<4096, IO>), grid, dim3(conv_threads(4096)), 0, st, X, w, m, Kf, Y, d, L); break;
-        case 16384: hipLaunchKernelGGL((shortlong_conv_kernel<16384, IO>), grid, dim3(conv_threads(16384)), 0, st, X, w, m, Kf, Y, d, L); break;
+        case 256: hipLaunchKernelGGL((shortlong_conv_kernel<256, IN, OUT, CONJ>), grid, dim3(conv_threads(256)), 0, st, X, w, m, Kf, Y, d, L); break;
+        case 1024: hipLaunchKernelGGL((shortlong_conv_kernel<1024, IN, OUT, CONJ>), grid, dim3(conv_threads(1024)), 0, st, X, w, m, Kf, Y, d, L); break;
+        case 4096: hipLaunchKernelGGL((shortlong_conv_kernel<4096, IN, OUT, CONJ>), grid, dim3(conv_threads(4096)), 0, st, X, w, m, Kf, Y, d, L); break;
+        case 16384: hipLaunchKernelGGL((shortlong_conv_kernel<16384, IN, OUT, CONJ>), grid, dim3(conv_threads(16384)), 0, st, X, w, m, Kf, Y, d, L); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -417,8 +589,59 @@ static hipError_t conv_dispatch(const IO* X, const float* w, int m, const float2
 hipError_t launch_shortlong_conv(const void* X, const float* w_short, int m, const void* Kf, void* Y, long BD, int d,
                                  int L, int dtype, hipStream_t st)
 {
-    if (dtype == 0) return conv_dispatch<bf16>((const bf16*)X, w_short, m, (const float2*)Kf, (bf16*)Y, BD, d, L, st);
-    return conv_dispatch<float>((const float*)X, w_short, m, (const float2*)Kf, (float*)Y, BD, d, L, st);
+    if (dtype == 0)
+        return conv_dispatch<bf16, bf16, false>((const bf16*)X, w_short, m, (const float2*)Kf, (bf16*)Y, BD, d, L, st);
+    return conv_dispatch<float, float, false>((const float*)X, w_short, m, (const float2*)Kf, (float*)Y, BD, d, L, st);
+}
+
+template <typename IO>
+static hipError_t conv_dk_dispatch(const IO* V, const IO* dZ, float* dk, int B, int d, int L, hipStream_t st)
+{
+    const int M = conv_fft_size(L);
+    ProfScope prof(KID_CONV_DK, st);
+    switch (M) {
+        case 256: hipLaunchKernelGGL((longconv_dk_kernel<256, IO>), dim3(d), dim3(conv_threads_dk(256)), 0, st, V, dZ, dk, B, d, L); break;
+        case 1024: hipLaunchKernelGGL((longconv_dk_kernel<1024, IO>), dim3(d), dim3(conv_threads_dk(1024)), 0, st, V, dZ, dk, B, d, L); break;
+        case 4096: hipLaunchKernelGGL((longconv_dk_kernel<4096, IO>), dim3(d), dim3(conv_threads_dk(4096)), 0, st, V, dZ, dk, B, d, L); break;
+        case 16384: hipLaunchKernelGGL((longconv_dk_kernel<16384, IO>), dim3(d), dim3(conv_threads_dk(16384)), 0, st, V, dZ, dk, B, d, L); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+// ws: scratch, used only with a short kernel: B*d*L floats (dV) followed by B*d*L elements of the I/O type (v).
+template <typename IO>
+static hipError_t conv_bwd_impl(const IO* X, const float* w_short, int m, const float2* Kf, const IO* dZ, IO* dX,
+                                float* dw, float* dk, float* ws, int B, int d, int L, hipStream_t st)
+{
+    hipError_t e;
+    const long BD = (long)B * d;
+    if (w_short == nullptr) {
+        // no short stage: v = x and dX is the correlation of dZ with the long kernel itself
+        if ((e = conv_dispatch<IO, IO, true>(dZ, nullptr, 0, Kf, dX, BD, d, L, st)) != hipSuccess) return e;
+        return conv_dk_dispatch<IO>(X, dZ, dk, B, d, L, st);
+    }
+    float* ws_dV = ws;
+    IO* ws_V = reinterpret_cast<IO*>(ws + (size_t)BD * L);
+    if ((e = conv_dispatch<IO, float, true>(dZ, nullptr, 0, Kf, ws_dV, BD, d, L, st)) != hipSuccess) return e;
+    {
+        ProfScope prof(KID_CONV_SHORT_BWD, st);
+        hipLaunchKernelGGL((shortconv_bwd_kernel<IO>), dim3(d), dim3(256), 0, st, X, w_short, m, ws_dV, dX, dw, ws_V, B, d,
+                           L);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+    return conv_dk_dispatch<IO>(ws_V, dZ, dk, B, d, L, st);
+}
+
+// Backward of Z = K_l(silu(K_s X)): dX (I/O dtype), dw [d][m] (with a short kernel, m <= 16), dk [d][L] fp32.
+hipError_t launch_shortlong_conv_bwd(const void* X, const float* w_short, int m, const void* Kf, const void* dZ,
+                                     void* dX, float* dw, float* dk, float* ws, int B, int d, int L, int dtype,
+                                     hipStream_t st)
+{
+    const float2* K = (const float2*)Kf;
+    if (dtype == 0)
+        return conv_bwd_impl<bf16>((const bf16*)X, w_short, m, K, (const bf16*)dZ, (bf16*)dX, dw, dk, ws, B, d, L, st);
+    return conv_bwd_impl<float>((const float*)X, w_short, m, K, (const float*)dZ, (float*)dX, dw, dk, ws, B, d, L, st);
 }
 
 }  // namespace chela

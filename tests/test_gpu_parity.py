@@ -655,3 +655,41 @@ def test_zqk_training_pair_lm_full_size_sampled():
         _check("dV", dV[:, hd:hd + 1], rV, "bf16")
         for q in range(4):
             _check("d_affine[%d]" % q, dA[q, hd:hd + 1], rA[q], "bf16")
+
+
+# ------------------------------------------------------------------------------------------ short-long convolution, gradient
+def _run_conv_bwd_case(B, d, L, m, dtype, seed, short=True):
+    print("\nconv bwd B%d d%d L%d m%d %s short=%s" % (B, d, L, m, dtype, short), flush=True)
+    x = make_conv_inputs(B, d, L, m, seed, dtype)
+    g = torch.Generator(device="cpu")
+    g.manual_seed(seed + 3000)
+    dZ = torch.randn(B, d, L, generator=g, dtype=torch.float32).to(x["X"].dtype)
+    dev = _dev(x)
+    spec = binding.chela_longconv_spectrum(dev["k_long"])
+    dX, dw, dk = binding.chela_shortlong_conv_bwd(dev["X"], dev["w_short"] if short else None, spec, dZ.cuda())
+    torch.cuda.synchronize()
+    rX, rw, rk = oracle_conv.short_long_conv_bwd(to_f64_numpy(x["X"]), to_f64_numpy(x["w_short"]) if short else None,
+                                                 to_f64_numpy(x["k_long"]), to_f64_numpy(dZ))
+    _check("dX", dX, rX, dtype)
+    # the kernels' gradients leave in fp32; with bf16 I/O they inherit the rounding of v to bf16 (bar of the I/O type)
+    _check("dk", dk, rk, dtype)
+    if short:
+        _check("dw", dw, rw, dtype)
+
+
+@pytest.mark.parametrize("shape", [(1, 1, 1, 1), (2, 3, 7, 3), (1, 2, 255, 9), (2, 2, 257, 5), (3, 2, 1000, 9),
+                                   (1, 2, 2049, 16), (2, 2, 4096, 9), (1, 2, 5000, 9), (2, 1, 16384, 9)])
+def test_shortlong_conv_bwd_f32(shape):
+    B, d, L, m = shape
+    _run_conv_bwd_case(B, d, L, m, "f32", seed=L + 10)
+
+
+@pytest.mark.parametrize("shape", [(2, 3, 1000, 9), (4, 2, 4096, 9), (2, 2, 16384, 9)])
+def test_shortlong_conv_bwd_bf16(shape):
+    B, d, L, m = shape
+    _run_conv_bwd_case(B, d, L, m, "bf16", seed=L + 11)
+
+
+@pytest.mark.parametrize("L", [300, 4096])
+def test_long_conv_alone_bwd(L):
+    _run_conv_bwd_case(2, 3, L, 3, "f32", seed=L + 12, short=False)
