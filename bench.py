@@ -95,8 +95,18 @@ def bench_conv(args, w, torch, binding):
     spec = binding.chela_longconv_spectrum(dev["k_long"])
     Z = torch.empty_like(dev["X"])
 
-    def step():
-        binding.chela_shortlong_conv_fwd(dev["X"], dev["w_short"], spec, Z=Z)
+    train = args.mode == "conv_train"
+    if train:
+        g = torch.Generator(device="cuda")
+        g.manual_seed(11)
+        dZ = torch.randn(B, d, L, device="cuda", generator=g).to(dev["X"].dtype)
+
+        def step():
+            binding.chela_shortlong_conv_fwd(dev["X"], dev["w_short"], spec, Z=Z)
+            binding.chela_shortlong_conv_bwd(dev["X"], dev["w_short"], spec, dZ)
+    else:
+        def step():
+            binding.chela_shortlong_conv_fwd(dev["X"], dev["w_short"], spec, Z=Z)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -115,11 +125,11 @@ def bench_conv(args, w, torch, binding):
     binding.chela_profile_enable(False)
     binding.chela_profile_reset()
     kernels = {k: {"launches": n, "avg_us": round(t * 1e3 / n, 2)} for k, (n, t) in prof.items()}
-    us = kernels["shortlong_conv_kernel"]["avg_us"]
+    us = kernels["shortlong_conv_kernel"]["avg_us"]      # (with the backward: mean over its two kinds of launch)
     M = 256 if L <= 256 else 1024 if L <= 1024 else 4096 if L <= 4096 else 16384
     # ALU model per sequence: two complex FFTs of length M at 5 M log2 M flops + 20 flops per spectrum pair + short kernel
     import math
-    flops = B * d * (2 * 5 * M * math.log2(M) + 20 * M / 2 + 2 * m * L)
+    flops = B * d * (2 * 5 * M * math.log2(M) + 20 * M / 2 + 2 * m * L)       # one launch of the forward kernel
     alg = B * d * L * es * 2 + d * (M + 1) * 8          # X in, Z out, the kernel spectrum once
     achieved = flops / (us * 1e-6) / 1e12
     cpu = None
@@ -130,13 +140,15 @@ def bench_conv(args, w, torch, binding):
         import oracle
         c0 = time.perf_counter()
         oracle_conv.short_long_conv(Xn, wn, kn)
+        if train:
+            oracle_conv.short_long_conv_bwd(Xn, wn, kn, to_f64_numpy(dZ[:1, :nch]))
         c1 = time.perf_counter()
         cpu = {"value": round(L * nch / d / (c1 - c0), 2), "unit": "tokens/s", "cores": min(oracle.num_threads(), nch),
                "kind": "oracle", "seconds": round(c1 - c0, 3),
                "sample": "fp64 direct-sum oracle on %d of the %d (batch, channel) sequences; tokens/s = L / (seconds "
                          "scaled to all %d channels of one batch entry)" % (nch, B * d, d)}
     print(json.dumps({
-        "metric": "short-long convolution fwd tokens/s", "value": round(B * L / (ms * 1e-3), 1), "unit": "tokens/s",
+        "metric": "short-long convolution %s tokens/s" % ("fwd+bwd" if train else "fwd"), "value": round(B * L / (ms * 1e-3), 1), "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": "conv at %s width: B%d d%d L%d, short kernel %d taps + silu + long kernel of L taps, %s I/O, "
@@ -155,7 +167,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="lm_bf16")
     ap.add_argument("--chunk", type=int, default=64)
-    ap.add_argument("--mode", default="train", choices=["train", "train_saved", "train_state", "train_z", "train_z_saved", "noncausal", "decode", "conv"],
+    ap.add_argument("--mode", default="train", choices=["train", "train_saved", "train_state", "train_z", "train_z_saved", "noncausal", "decode", "conv", "conv_train"],
                     help="train: fwd+bwd (the headline); train_saved: the same step through chela_linattn_fwd_save / "
                          "_bwd_saved (the forward leaves the boundary states, the backward skips its pass over K, V); "
                          "train_state: the same through the carried-state entry points "
@@ -184,7 +196,7 @@ def main():
     torch.cuda.set_device(0)
     if args.mode == "decode":
         return bench_decode(args, w, torch, binding)
-    if args.mode == "conv":
+    if args.mode in ("conv", "conv_train"):
         return bench_conv(args, w, torch, binding)
     has_bwd = w.backward          # the headline workload runs forward + backward; forward-only workloads time the forward
     es = 2 if w.dtype == "bf16" else 4

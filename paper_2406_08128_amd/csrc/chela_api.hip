@@ -640,8 +640,8 @@ int chela_shortlong_conv_fwd_f32(const void* X, const float* w_short, int m, con
 static size_t conv_bwd_ws_bytes(int B, int d, int L, int dtype, bool has_short)
 {
     if (!has_short || B <= 0 || d <= 0 || L <= 0) return 0;
-    const size_t n = (size_t)B * d * L;
-    return n * sizeof(float) + n * (dtype == CHELA_DTYPE_BF16 ? 2 : 4);
+    const size_t n = (size_t)B * d * L, tiles = ((size_t)L + 2047) / 2048;
+    return n * sizeof(float) + (size_t)B * d * tiles * 16 * sizeof(float) + n * (dtype == CHELA_DTYPE_BF16 ? 2 : 4);
 }
 
 size_t chela_shortlong_conv_bwd_workspace_bytes(int B, int d, int L, int has_short_kernel, int dtype)
@@ -656,6 +656,7 @@ static int shortlong_bwd_common(const void* X, const float* w_short, int m, cons
 {
     if (B < 0 || d < 0 || L < 0) return CHELA_ERR_BAD_SHAPE;
     if (w_short != nullptr && (m < 1 || m > 16)) return CHELA_ERR_BAD_SHAPE;      // the backward keeps <= 16 tap sums
+    if (B > 65535) return CHELA_ERR_BAD_SHAPE;                                    // batch entries ride on grid.y
     if ((unsigned long long)B * (unsigned long long)d > 0x7fffffffull) return CHELA_ERR_BAD_SHAPE;
     if (d == 0 || L == 0) return CHELA_OK;
     if (conv_fft_size(L) == 0) return CHELA_ERR_BAD_SHAPE;

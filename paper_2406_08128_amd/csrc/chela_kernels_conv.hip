@@ -477,63 +477,60 @@ __global__ __launch_bounds__(conv_threads_dk(M)) void longconv_dk_kernel(const I
 
 // Gradient through the activation and the short kernel.  dV is the gradient with respect to v = silu(u), u = K_s x:
 //   dU = dV silu'(u),  dX[t] = sum_j w[j] dU[t+j],  dw[c][j] = sum_b sum_t dU[b,c,t] x[b,c,t-j].
-// It also writes v = silu(u) out.  One workgroup per channel walks the batch entries in tiles of TL steps; x is staged with m-1 steps of history and
-// dU with m-1 steps of look-ahead; the tap sums stay in registers (MT >= m) until one reduction at the very end.
+// It also writes v = silu(u) out.  One workgroup per (channel, batch entry, tile of TL steps); x is staged with MT
+// steps of history and dU with MT steps of look-ahead.  Each workgroup leaves its share of the tap sums in `part`
+// ([d][B * tiles][MT]); shortconv_dw_kernel adds the shares of a channel in a fixed order.
 constexpr int kShortTile = 2048, kShortMaxTaps = 16;
 
 template <typename IO>
 __global__ __launch_bounds__(256) void shortconv_bwd_kernel(const IO* __restrict__ X, const float* __restrict__ w_short,
                                                            int m, const float* __restrict__ dV, IO* __restrict__ dX,
-                                                           float* __restrict__ dw, IO* __restrict__ Vout, int B, int d,
-                                                           int L)
+                                                           float* __restrict__ part, IO* __restrict__ Vout, int d, int L)
 {
     constexpr int TL = kShortTile, MT = kShortMaxTaps, H = MT;       // H: halo on either side
     __shared__ float sx[TL + 2 * H];      // x[t0 - H .. t0 + TL + H)
     __shared__ float su[TL + H];          // dU[t0 .. t0 + TL + H)
     __shared__ float red[MT][4];
-    const int tid = threadIdx.x, c = blockIdx.x;
+    const int tid = threadIdx.x, c = blockIdx.x, b = blockIdx.y, tile = blockIdx.z;
+    const int n_share = gridDim.y * gridDim.z, share = b * gridDim.z + tile;
     float wreg[MT], acc[MT];
 #pragma unroll
     for (int j = 0; j < MT; ++j) { wreg[j] = j < m ? w_short[(long)c * m + j] : 0.f; acc[j] = 0.f; }
-    for (int b = 0; b < B; ++b) {
-        const long row = ((long)b * d + c) * L;
-        for (int t0 = 0; t0 < L; t0 += TL) {
-            __syncthreads();
-            for (int i = tid; i < TL + 2 * H; i += 256) {
-                const int t = t0 - H + i;
-                sx[i] = (t >= 0 && t < L) ? (float)X[row + t] : 0.f;
-            }
-            __syncthreads();
-            for (int i = tid; i < TL + H; i += 256) {
-                const int t = t0 + i;
-                float du = 0.f;
-                if (t < L) {
-                    float u = 0.f;
+    const long row = ((long)b * d + c) * L;
+    const int t0 = tile * TL;
+    for (int i = tid; i < TL + 2 * H; i += 256) {
+        const int t = t0 - H + i;
+        sx[i] = (t >= 0 && t < L) ? (float)X[row + t] : 0.f;
+    }
+    __syncthreads();
+    for (int i = tid; i < TL + H; i += 256) {
+        const int t = t0 + i;
+        float du = 0.f;
+        if (t < L) {
+            float u = 0.f;
 #pragma unroll
-                    for (int j = 0; j < MT; ++j) u = fmaf(wreg[j], sx[H + i - j], u);
-                    const float sg = __builtin_amdgcn_rcpf(1.f + __expf(-u));
-                    du = dV[row + t] * sg * (1.f + u * (1.f - sg));
-                    if (i < TL) Vout[row + t] = (IO)(u * sg);       // v = silu(u), for the long kernel's gradient
-                }
-                su[i] = du;
-            }
-            __syncthreads();
-            for (int i = tid; i < TL; i += 256) {
-                const int t = t0 + i;
-                if (t < L) {
-                    float dx = 0.f;
-                    const float du = su[i];
+            for (int j = 0; j < MT; ++j) u = fmaf(wreg[j], sx[H + i - j], u);
+            const float sg = __builtin_amdgcn_rcpf(1.f + __expf(-u));
+            du = dV[row + t] * sg * (1.f + u * (1.f - sg));
+            if (i < TL) Vout[row + t] = (IO)(u * sg);       // v = silu(u), for the long kernel's gradient
+        }
+        su[i] = du;
+    }
+    __syncthreads();
+    for (int i = tid; i < TL; i += 256) {
+        const int t = t0 + i;
+        if (t < L) {
+            float dx = 0.f;
+            const float du = su[i];
 #pragma unroll
-                    for (int j = 0; j < MT; ++j) {
-                        dx = fmaf(wreg[j], su[i + j], dx);
-                        acc[j] = fmaf(du, sx[H + i - j], acc[j]);
-                    }
-                    dX[row + t] = (IO)dx;
-                }
+            for (int j = 0; j < MT; ++j) {
+                dx = fmaf(wreg[j], su[i + j], dx);
+                acc[j] = fmaf(du, sx[H + i - j], acc[j]);
             }
+            dX[row + t] = (IO)dx;
         }
     }
-    // the taps' sums over this channel: wave reduction, then across the four waves
+    // this workgroup's tap sums: wave reduction, then across the four waves
 #pragma unroll
     for (int j = 0; j < MT; ++j) {
         float v = acc[j];
@@ -542,7 +539,17 @@ __global__ __launch_bounds__(256) void shortconv_bwd_kernel(const IO* __restrict
         if ((tid & 63) == 0) red[j][tid >> 6] = v;
     }
     __syncthreads();
-    if (tid < m) dw[(long)c * m + tid] = red[tid][0] + red[tid][1] + red[tid][2] + red[tid][3];
+    if (tid < MT) part[((long)c * n_share + share) * MT + tid] = red[tid][0] + red[tid][1] + red[tid][2] + red[tid][3];
+}
+
+__global__ __launch_bounds__(64) void shortconv_dw_kernel(const float* __restrict__ part, float* __restrict__ dw, int m,
+                                                         int n_share)
+{
+    const int c = blockIdx.x, j = threadIdx.x;
+    if (j >= m) return;
+    float t = 0.f;
+    for (int s = 0; s < n_share; ++s) t += part[((long)c * n_share + s) * kShortMaxTaps + j];
+    dw[(long)c * m + j] = t;
 }
 
 int conv_fft_size(int L)
@@ -609,7 +616,8 @@ static hipError_t conv_dk_dispatch(const IO* V, const IO* dZ, float* dk, int B, 
     return hipGetLastError();
 }
 
-// ws: scratch, used only with a short kernel: B*d*L floats (dV) followed by B*d*L elements of the I/O type (v).
+// ws: scratch, used only with a short kernel: B*d*L floats (dV), the workgroups' tap sums, then B*d*L elements of
+// the I/O type (v).
 template <typename IO>
 static hipError_t conv_bwd_impl(const IO* X, const float* w_short, int m, const float2* Kf, const IO* dZ, IO* dX,
                                 float* dw, float* dk, float* ws, int B, int d, int L, hipStream_t st)
@@ -622,12 +630,16 @@ static hipError_t conv_bwd_impl(const IO* X, const float* w_short, int m, const 
         return conv_dk_dispatch<IO>(X, dZ, dk, B, d, L, st);
     }
     float* ws_dV = ws;
-    IO* ws_V = reinterpret_cast<IO*>(ws + (size_t)BD * L);
+    const int tiles = (L + kShortTile - 1) / kShortTile;
+    float* ws_part = ws + (size_t)BD * L;                                   // [d][B * tiles][16]
+    IO* ws_V = reinterpret_cast<IO*>(ws_part + (size_t)BD * tiles * kShortMaxTaps);
     if ((e = conv_dispatch<IO, float, true>(dZ, nullptr, 0, Kf, ws_dV, BD, d, L, st)) != hipSuccess) return e;
     {
         ProfScope prof(KID_CONV_SHORT_BWD, st);
-        hipLaunchKernelGGL((shortconv_bwd_kernel<IO>), dim3(d), dim3(256), 0, st, X, w_short, m, ws_dV, dX, dw, ws_V, B, d,
-                           L);
+        hipLaunchKernelGGL((shortconv_bwd_kernel<IO>), dim3(d, B, tiles), dim3(256), 0, st, X, w_short, m, ws_dV, dX,
+                           ws_part, ws_V, d, L);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+        hipLaunchKernelGGL(shortconv_dw_kernel, dim3(d), dim3(64), 0, st, ws_part, dw, m, B * tiles);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     return conv_dk_dispatch<IO>(ws_V, dZ, dk, B, d, L, st);
