@@ -130,7 +130,7 @@ def bench_conv(args, w, torch, binding):
     # ALU model per sequence: two complex FFTs of length M at 5 M log2 M flops + 20 flops per spectrum pair + short kernel
     import math
     flops = B * d * (2 * 5 * M * math.log2(M) + 20 * M / 2 + 2 * m * L)       # one launch of the forward kernel
-    alg = B * d * L * es * 2 + d * (M + 1) * 8          # X in, Z out, the kernel spectrum once
+    alg = B * d * L * es * 2 + d * (M // 2 + 1) * 16   # X in, Z out, the kernel spectrum once
     achieved = flops / (us * 1e-6) / 1e12
     cpu = None
     if not args.no_cpu_baseline:

@@ -591,7 +591,7 @@ size_t chela_linattn_noncausal_workspace_bytes(int B, int H, int N, int dk, int 
 size_t chela_longconv_spectrum_bytes(int d, int L)
 {
     const int M = (d > 0 && L > 0) ? conv_fft_size(L) : 0;
-    return M ? (size_t)d * (size_t)(M + 1) * 2 * sizeof(float) : 0;
+    return M ? (size_t)d * (size_t)(M / 2 + 1) * 4 * sizeof(float) : 0;     // one (K[k], K[M-k]) pair per 16 bytes
 }
 
 int chela_longconv_spectrum(const float* k_long, void* spectrum, int d, int L, void* stream)

@@ -75,7 +75,7 @@ hipError_t launch_bf16_step(const void* q, const void* k, const void* v, float* 
                             hipStream_t st);
 
 // Short-long convolutions (Sec. 4.2).  conv_fft_size(L): length M of the complex transform used for sequences of
-// L steps (0: L too long); the kernel spectrum is [d][M + 1] complex fp32.  dtype 0: bf16 I/O, 1: fp32 I/O.
+// L steps (0: L too long); the kernel spectrum is [d][M/2 + 1] pairs of complex fp32.  dtype 0: bf16 I/O, 1: fp32 I/O.
 int conv_fft_size(int L);
 hipError_t launch_longconv_spectrum(const float* k, void* Kf, int d, int L, hipStream_t st);
 hipError_t launch_shortlong_conv(const void* X, const float* w_short, int m, const void* Kf, void* Y, long BD, int d,

@@ -233,6 +233,21 @@ __device__ __forceinline__ void tangle(cplx Yk, cplx Ymk, cplx w, cplx& Zk, cplx
     Zmk = cadd(conj(ye), mul_pos_i(conj(yo)));
 }
 
+// Order in which the point-wise stages walk the bin pairs (k, M - k), 0 <= k <= M/2.  The forward passes leave
+// bin k at a digit-reversed position, so lanes that took consecutive k would all hit the same LDS banks (strides of
+// M/4 and M/64 complex).  Pair l takes k = ((l & 63) << HB) | (l >> 6) instead: the 64 lanes of a wave then differ
+// in the HIGH bits of k, i.e. in the low digits of the storage position.  l = M/2 stands for the self-paired bin
+// M/2.  The kernel spectrum is stored in the same order, one float4 (K[k], K[M-k]) per pair, so its loads coalesce.
+template <int M>
+__device__ __forceinline__ int pair_bin(int l)
+{
+    constexpr int HALF = M / 2;
+    int hb = 0;
+#pragma unroll
+    for (int x = HALF / 64; x > 1; x >>= 1) ++hb;
+    return l >= HALF ? HALF : (((l & 63) << hb) | (l >> 6));
+}
+
 __device__ __forceinline__ cplx w2m(int k, int M)      // W_2M^k = exp(-i pi k / M)
 {
     float s, c;
@@ -267,16 +282,18 @@ __device__ __forceinline__ void stage_input(const IO* __restrict__ x, const floa
         cplx z[PER];
 #pragma unroll
         for (int i = 0; i < PER; ++i) z[i] = mk(0.f, 0.f);
-        // outputs t and t+1 share all but one of their inputs: x[t+1-j], j = 0..m, are read once
-        for (int j = 0; j <= m; ++j) {
-            const float wj = j < m ? wc[j] : 0.f, wjm1 = j > 0 ? wc[j - 1] : 0.f;
+        // outputs t and t+1 share all but one of their inputs; x is read in aligned pairs (x[t-2p], x[t-2p+1]):
+        // x[t-2p+1] meets taps 2p (for t+1) and 2p-1 (for t), x[t-2p] meets taps 2p+1 (for t+1) and 2p (for t)
+        for (int p = 0; 2 * p <= m; ++p) {
+            const float w2p = 2 * p < m ? wc[2 * p] : 0.f, w2pm1 = p > 0 ? wc[2 * p - 1] : 0.f;
+            const float w2pp1 = 2 * p + 1 < m ? wc[2 * p + 1] : 0.f;
 #pragma unroll
             for (int i = 0; i < PER; ++i) {
                 const int t = 2 * (tid + T * i);
                 if (t < L) {
-                    const float xv = sx[ZP + t + 1 - j];      // feeds output t+1 with tap j and output t with tap j-1
-                    z[i].y = fmaf(wj, xv, z[i].y);
-                    z[i].x = fmaf(wjm1, xv, z[i].x);
+                    const float2 xv = *reinterpret_cast<const float2*>(sx + ZP + t - 2 * p);
+                    z[i].y = fmaf(w2p, xv.y, fmaf(w2pp1, xv.x, z[i].y));
+                    z[i].x = fmaf(w2pm1, xv.y, fmaf(w2p, xv.x, z[i].x));
                 }
             }
         }
@@ -302,10 +319,10 @@ __device__ __forceinline__ void stage_input(const IO* __restrict__ x, const floa
     }
 }
 
-// Kernel spectrum of one channel: K[c][0 .. M], complex fp32.
+// Kernel spectrum of one channel: (K[k], K[M-k]) for the M/2 + 1 bin pairs in pair order, complex fp32.
 template <int M>
 __global__ __launch_bounds__(conv_threads(M)) void longconv_spectrum_kernel(const float* __restrict__ k,
-                                                                           float2* __restrict__ Kf, int L)
+                                                                           float4* __restrict__ Kf, int L)
 {
     constexpr int T = conv_threads(M);
     __shared__ __attribute__((aligned(16))) unsigned char lds[ConvLds<M>::BYTES];
@@ -319,13 +336,13 @@ __global__ __launch_bounds__(conv_threads(M)) void longconv_spectrum_kernel(cons
     __syncthreads();
     fft_passes<M, T, false>(a, lo, hi, tid);
     __syncthreads();
-    float2* out = Kf + c * (long)(M + 1);
-    for (int kk = tid; kk <= M / 2; kk += T) {
+    float4* out = Kf + c * (long)(M / 2 + 1);
+    for (int l = tid; l <= M / 2; l += T) {
+        const int kk = pair_bin<M>(l);
         cplx Xk, Xmk;
         untangle(a[conv_pad(spectrum_pos<M>(kk))], conj(a[conv_pad(spectrum_pos<M>((M - kk) & (M - 1)))]), w2m(kk, M), Xk,
                  Xmk);
-        out[kk] = make_float2(Xk.x, Xk.y);
-        out[M - kk] = make_float2(Xmk.x, Xmk.y);
+        out[l] = make_float4(Xk.x, Xk.y, Xmk.x, Xmk.y);
     }
 }
 
@@ -335,7 +352,7 @@ __global__ __launch_bounds__(conv_threads(M)) void longconv_spectrum_kernel(cons
 template <int M, typename IN, typename OUT, bool CONJ>
 __global__ __launch_bounds__(conv_threads(M)) void shortlong_conv_kernel(const IN* __restrict__ X,
                                                                         const float* __restrict__ w_short, int m,
-                                                                        const float2* __restrict__ Kf,
+                                                                        const float4* __restrict__ Kf,
                                                                         OUT* __restrict__ Y, int d, int L)
 {
     constexpr int T = conv_threads(M);
@@ -355,14 +372,15 @@ __global__ __launch_bounds__(conv_threads(M)) void shortlong_conv_kernel(const I
     __syncthreads();
 
     // ---- spectrum of v times spectrum of the kernel, re-packed for the inverse transform (pairs k, M - k)
-    const float2* Kc = Kf + (long)c * (M + 1);
-    for (int kk = tid; kk <= M / 2; kk += T) {
+    const float4* Kc = Kf + (long)c * (M / 2 + 1);
+    for (int l = tid; l <= M / 2; l += T) {
+        const int kk = pair_bin<M>(l);
         const int p1 = conv_pad(spectrum_pos<M>(kk)), p2 = conv_pad(spectrum_pos<M>((M - kk) & (M - 1)));
         const cplx w = w2m(kk, M);
         cplx Xk, Xmk, Zk, Zmk;
         untangle(a[p1], conj(a[p2]), w, Xk, Xmk);
-        const float2 k1 = Kc[kk], k2 = Kc[M - kk];
-        const cplx K1 = mk(k1.x, CONJ ? -k1.y : k1.y), K2 = mk(k2.x, CONJ ? -k2.y : k2.y);
+        const float4 kq = Kc[l];
+        const cplx K1 = mk(kq.x, CONJ ? -kq.y : kq.y), K2 = mk(kq.z, CONJ ? -kq.w : kq.w);
         if (kk == 0) {
             // bins 0 and M are real and share storage slot 0
             const float y0 = Xk.x * K1.x, ym = Xmk.x * K2.x;
@@ -422,8 +440,8 @@ __global__ __launch_bounds__(conv_threads_dk(M)) void longconv_dk_kernel(const I
         __syncthreads();
 #pragma unroll
         for (int i = 0; i < NP; ++i) {
-            const int kk = tid + T * i;
-            if (kk <= M / 2)
+            const int l = tid + T * i, kk = pair_bin<M>(l);
+            if (l <= M / 2)
                 untangle(a[conv_pad(spectrum_pos<M>(kk))], conj(a[conv_pad(spectrum_pos<M>((M - kk) & (M - 1)))]),
                          w2m(kk, M), Vk[i], Vmk[i]);
         }
@@ -434,8 +452,8 @@ __global__ __launch_bounds__(conv_threads_dk(M)) void longconv_dk_kernel(const I
         __syncthreads();
 #pragma unroll
         for (int i = 0; i < NP; ++i) {
-            const int kk = tid + T * i;
-            if (kk <= M / 2) {
+            const int l = tid + T * i, kk = pair_bin<M>(l);
+            if (l <= M / 2) {
                 cplx Gk, Gmk;
                 untangle(a[conv_pad(spectrum_pos<M>(kk))], conj(a[conv_pad(spectrum_pos<M>((M - kk) & (M - 1)))]),
                          w2m(kk, M), Gk, Gmk);
@@ -447,8 +465,8 @@ __global__ __launch_bounds__(conv_threads_dk(M)) void longconv_dk_kernel(const I
     }
 #pragma unroll
     for (int i = 0; i < NP; ++i) {
-        const int kk = tid + T * i;
-        if (kk <= M / 2) {
+        const int l = tid + T * i, kk = pair_bin<M>(l);
+        if (l <= M / 2) {
             const int p1 = conv_pad(spectrum_pos<M>(kk)), p2 = conv_pad(spectrum_pos<M>((M - kk) & (M - 1)));
             if (kk == 0) {
                 a[p1] = mk(0.5f * (accK[i].x + accMK[i].x), 0.5f * (accK[i].x - accMK[i].x));
@@ -565,7 +583,7 @@ hipError_t launch_longconv_spectrum(const float* k, void* Kf, int d, int L, hipS
 {
     const int M = conv_fft_size(L);
     ProfScope prof(KID_CONV_SPECTRUM, st);
-    float2* out = (float2*)Kf;
+    float4* out = (float4*)Kf;
     switch (M) {
         case 256: hipLaunchKernelGGL((longconv_spectrum_kernel<256>), dim3(d), dim3(conv_threads(256)), 0, st, k, out, L); break;
         case 1024: hipLaunchKernelGGL((longconv_spectrum_kernel<1024>), dim3(d), dim3(conv_threads(1024)), 0, st, k, out, L); break;
@@ -577,7 +595,7 @@ hipError_t launch_longconv_spectrum(const float* k, void* Kf, int d, int L, hipS
 }
 
 template <typename IN, typename OUT, bool CONJ>
-static hipError_t conv_dispatch(const IN* X, const float* w, int m, const float2* Kf, OUT* Y, long BD, int d, int L,
+static hipError_t conv_dispatch(const IN* X, const float* w, int m, const float4* Kf, OUT* Y, long BD, int d, int L,
                                 hipStream_t st)
 {
     const int M = conv_fft_size(L);
@@ -597,8 +615,8 @@ hipError_t launch_shortlong_conv(const void* X, const float* w_short, int m, con
                                  int L, int dtype, hipStream_t st)
 {
     if (dtype == 0)
-        return conv_dispatch<bf16, bf16, false>((const bf16*)X, w_short, m, (const float2*)Kf, (bf16*)Y, BD, d, L, st);
-    return conv_dispatch<float, float, false>((const float*)X, w_short, m, (const float2*)Kf, (float*)Y, BD, d, L, st);
+        return conv_dispatch<bf16, bf16, false>((const bf16*)X, w_short, m, (const float4*)Kf, (bf16*)Y, BD, d, L, st);
+    return conv_dispatch<float, float, false>((const float*)X, w_short, m, (const float4*)Kf, (float*)Y, BD, d, L, st);
 }
 
 template <typename IO>
@@ -619,7 +637,7 @@ static hipError_t conv_dk_dispatch(const IO* V, const IO* dZ, float* dk, int B, 
 // ws: scratch, used only with a short kernel: B*d*L floats (dV), the workgroups' tap sums, then B*d*L elements of
 // the I/O type (v).
 template <typename IO>
-static hipError_t conv_bwd_impl(const IO* X, const float* w_short, int m, const float2* Kf, const IO* dZ, IO* dX,
+static hipError_t conv_bwd_impl(const IO* X, const float* w_short, int m, const float4* Kf, const IO* dZ, IO* dX,
                                 float* dw, float* dk, float* ws, int B, int d, int L, hipStream_t st)
 {
     hipError_t e;
@@ -650,7 +668,7 @@ hipError_t launch_shortlong_conv_bwd(const void* X, const float* w_short, int m,
                                      void* dX, float* dw, float* dk, float* ws, int B, int d, int L, int dtype,
                                      hipStream_t st)
 {
-    const float2* K = (const float2*)Kf;
+    const float4* K = (const float4*)Kf;
     if (dtype == 0)
         return conv_bwd_impl<bf16>((const bf16*)X, w_short, m, K, (const bf16*)dZ, (bf16*)dX, dw, dk, ws, B, d, L, st);
     return conv_bwd_impl<float>((const float*)X, w_short, m, K, (const float*)dZ, (float*)dX, dw, dk, ws, B, d, L, st);

@@ -183,8 +183,8 @@ def test_noncausal_argument_errors(L):
 
 def test_conv_argument_errors(L):
     sb, sp, f = L.chela_longconv_spectrum_bytes, L.chela_longconv_spectrum, L.chela_shortlong_conv_fwd
-    assert sb(3, 16384) == 3 * 16385 * 8 and sb(3, 16385) == 0 and sb(0, 64) == 0
-    assert sb(2, 257) == 2 * 1025 * 8 and sb(2, 256) == 2 * 257 * 8 and sb(1, 1) == 257 * 8
+    assert sb(3, 16384) == 3 * 8193 * 16 and sb(3, 16385) == 0 and sb(0, 64) == 0
+    assert sb(2, 257) == 2 * 513 * 16 and sb(2, 256) == 2 * 129 * 16 and sb(1, 1) == 129 * 16
     K, S, X, W, Y = A, A + SZ, A + 2 * SZ, A + 3 * SZ, A + 4 * SZ
     assert sp(None, S, 4, 100, None) == -1
     assert sp(K, S + 8, 4, 100, None) == -5
