@@ -197,6 +197,21 @@ template <> struct IoPair<bf16> {
     }
 };
 
+// Eight consecutive elements at a 16-byte aligned position.
+__device__ __forceinline__ void store8(float* p, const float (&v)[8])
+{
+    *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+    *reinterpret_cast<float4*>(p + 4) = make_float4(v[4], v[5], v[6], v[7]);
+}
+__device__ __forceinline__ void store8(bf16* p, const float (&v)[8])
+{
+    typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+    bf16x8 o;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] = (bf16)v[e];
+    *reinterpret_cast<bf16x8*>(p) = o;
+}
+
 template <int M, int T>
 __device__ __forceinline__ void build_tables(cplx* lo, cplx* hi, int tid)
 {
@@ -498,7 +513,7 @@ __global__ __launch_bounds__(conv_threads_dk(M)) void longconv_dk_kernel(const I
 // It also writes v = silu(u) out.  One workgroup per (channel, batch entry, tile of TL steps); x is staged with MT
 // steps of history and dU with MT steps of look-ahead.  Each workgroup leaves its share of the tap sums in `part`
 // ([d][B * tiles][MT]); shortconv_dw_kernel adds the shares of a channel in a fixed order.
-constexpr int kShortTile = 2048, kShortMaxTaps = 16;
+constexpr int kShortTile = 2048, kShortMaxTaps = 16, kShortTilesPerWg = 4;
 
 template <typename IO>
 __global__ __launch_bounds__(256) void shortconv_bwd_kernel(const IO* __restrict__ X, const float* __restrict__ w_short,
@@ -506,47 +521,91 @@ __global__ __launch_bounds__(256) void shortconv_bwd_kernel(const IO* __restrict
                                                            float* __restrict__ part, IO* __restrict__ Vout, int d, int L)
 {
     constexpr int TL = kShortTile, MT = kShortMaxTaps, H = MT;       // H: halo on either side
-    __shared__ float sx[TL + 2 * H];      // x[t0 - H .. t0 + TL + H)
-    __shared__ float su[TL + H];          // dU[t0 .. t0 + TL + H)
+    __shared__ __attribute__((aligned(16))) float sx[TL + 2 * H];      // x[t0 - H .. t0 + TL + H)
+    __shared__ __attribute__((aligned(16))) float su[TL + H + 8];      // dU[t0 .. t0 + TL + H) (+ slack for 16-byte reads)
     __shared__ float red[MT][4];
-    const int tid = threadIdx.x, c = blockIdx.x, b = blockIdx.y, tile = blockIdx.z;
-    const int n_share = gridDim.y * gridDim.z, share = b * gridDim.z + tile;
+    const int tid = threadIdx.x, c = blockIdx.x, b = blockIdx.y;
+    const int n_share = gridDim.y * gridDim.z, share = b * gridDim.z + blockIdx.z;
     float wreg[MT], acc[MT];
 #pragma unroll
     for (int j = 0; j < MT; ++j) { wreg[j] = j < m ? w_short[(long)c * m + j] : 0.f; acc[j] = 0.f; }
     const long row = ((long)b * d + c) * L;
+    const bool vec8 = (L & 7) == 0;       // every row starts 16-byte aligned
+    for (int tile = blockIdx.z * kShortTilesPerWg; tile < (blockIdx.z + 1) * kShortTilesPerWg && tile * TL < L; ++tile) {
     const int t0 = tile * TL;
+    __syncthreads();
     for (int i = tid; i < TL + 2 * H; i += 256) {
         const int t = t0 - H + i;
         sx[i] = (t >= 0 && t < L) ? (float)X[row + t] : 0.f;
     }
     __syncthreads();
-    for (int i = tid; i < TL + H; i += 256) {
-        const int t = t0 + i;
-        float du = 0.f;
-        if (t < L) {
+    // each thread takes 8 consecutive steps: the 24 inputs they need are read once, as six 16-byte LDS reads
+    for (int ch = tid; ch < (TL + H) / 8; ch += 256) {
+        const int i0 = 8 * ch;
+        float xs[24];                                   // x[t0 + i0 - 16 .. t0 + i0 + 8)
+#pragma unroll
+        for (int r = 0; r < 6; ++r) {
+            const float4 v = *reinterpret_cast<const float4*>(sx + i0 + 4 * r);      // sx index of x[t0 + i] is H + i
+            xs[4 * r] = v.x; xs[4 * r + 1] = v.y; xs[4 * r + 2] = v.z; xs[4 * r + 3] = v.w;
+        }
+        float du8[8], v8[8], g8[8];
+        const int tc = t0 + i0;
+        const bool whole = vec8 && tc + 8 <= L;         // eight steps in range at a 16-byte aligned address
+        if (whole) {
+            const float4 a0 = *reinterpret_cast<const float4*>(dV + row + tc), a1 = *reinterpret_cast<const float4*>(dV + row + tc + 4);
+            g8[0] = a0.x; g8[1] = a0.y; g8[2] = a0.z; g8[3] = a0.w; g8[4] = a1.x; g8[5] = a1.y; g8[6] = a1.z; g8[7] = a1.w;
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) g8[e] = tc + e < L ? dV[row + tc + e] : 0.f;
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
             float u = 0.f;
 #pragma unroll
-            for (int j = 0; j < MT; ++j) u = fmaf(wreg[j], sx[H + i - j], u);
+            for (int j = 0; j < MT; ++j) u = fmaf(wreg[j], xs[16 + e - j], u);
             const float sg = __builtin_amdgcn_rcpf(1.f + __expf(-u));
-            du = dV[row + t] * sg * (1.f + u * (1.f - sg));
-            if (i < TL) Vout[row + t] = (IO)(u * sg);       // v = silu(u), for the long kernel's gradient
+            du8[e] = tc + e < L ? g8[e] * sg * (1.f + u * (1.f - sg)) : 0.f;
+            v8[e] = u * sg;                             // v = silu(u), for the long kernel's gradient
         }
-        su[i] = du;
+        if (i0 < TL) {
+            if (whole) store8(Vout + row + tc, v8);
+            else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) if (tc + e < L) Vout[row + tc + e] = (IO)v8[e];
+            }
+        }
+        *reinterpret_cast<float4*>(su + i0) = make_float4(du8[0], du8[1], du8[2], du8[3]);
+        *reinterpret_cast<float4*>(su + i0 + 4) = make_float4(du8[4], du8[5], du8[6], du8[7]);
     }
     __syncthreads();
-    for (int i = tid; i < TL; i += 256) {
-        const int t = t0 + i;
-        if (t < L) {
+    {
+        const int i0 = 8 * tid;                         // TL = 8 * 256
+        float xs[24], ds[24];                           // x as above; dU[t0 + i0 .. t0 + i0 + 24)
+#pragma unroll
+        for (int r = 0; r < 6; ++r) {
+            const float4 v = *reinterpret_cast<const float4*>(sx + i0 + 4 * r);
+            xs[4 * r] = v.x; xs[4 * r + 1] = v.y; xs[4 * r + 2] = v.z; xs[4 * r + 3] = v.w;
+            const float4 g = *reinterpret_cast<const float4*>(su + i0 + 4 * r);
+            ds[4 * r] = g.x; ds[4 * r + 1] = g.y; ds[4 * r + 2] = g.z; ds[4 * r + 3] = g.w;
+        }
+        float dx8[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
             float dx = 0.f;
-            const float du = su[i];
 #pragma unroll
             for (int j = 0; j < MT; ++j) {
-                dx = fmaf(wreg[j], su[i + j], dx);
-                acc[j] = fmaf(du, sx[H + i - j], acc[j]);
+                dx = fmaf(wreg[j], ds[e + j], dx);
+                acc[j] = fmaf(ds[e], xs[16 + e - j], acc[j]);
             }
-            dX[row + t] = (IO)dx;
+            dx8[e] = dx;
         }
+        const int tc = t0 + i0;
+        if (vec8 && tc + 8 <= L) store8(dX + row + tc, dx8);
+        else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) if (tc + e < L) dX[row + tc + e] = (IO)dx8[e];
+        }
+    }
     }
     // this workgroup's tap sums: wave reduction, then across the four waves
 #pragma unroll
@@ -648,7 +707,7 @@ static hipError_t conv_bwd_impl(const IO* X, const float* w_short, int m, const 
         return conv_dk_dispatch<IO>(X, dZ, dk, B, d, L, st);
     }
     float* ws_dV = ws;
-    const int tiles = (L + kShortTile - 1) / kShortTile;
+    const int tiles = ((L + kShortTile - 1) / kShortTile + kShortTilesPerWg - 1) / kShortTilesPerWg;   // tile groups
     float* ws_part = ws + (size_t)BD * L;                                   // [d][B * tiles][16]
     IO* ws_V = reinterpret_cast<IO*>(ws_part + (size_t)BD * tiles * kShortMaxTaps);
     if ((e = conv_dispatch<IO, float, true>(dZ, nullptr, 0, Kf, ws_dV, BD, d, L, st)) != hipSuccess) return e;
