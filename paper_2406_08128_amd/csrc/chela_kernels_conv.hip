@@ -147,17 +147,26 @@ __device__ __forceinline__ void fft_passes(cplx* a, const cplx* lo, const cplx* 
 {
     constexpr int M16 = conv_lead4(M) ? M / 4 : M;     // what the radix-16 passes transform (blocks of this length)
     static_assert(M16 == 256 || M16 == 4096, "radix-16 part must be 16^2 or 16^3");
+    // The packed sequence has at most M/2 non-zero entries (L <= M real steps) and only its first M/2 entries are
+    // ever read back: the leading radix-4 pass sees two zero inputs going forward and owes only two outputs coming back.
     auto lead4 = [&]() __attribute__((always_inline)) {
         constexpr int s = M / 4, sp = s + s / 16;
         for (int g = tid; g < s; g += T) {
             cplx* p0 = a + conv_pad(g);
-            cplx v0 = p0[0], v1 = p0[sp], v2 = p0[2 * sp], v3 = p0[3 * sp];
             const cplx w1 = twiddle<M>(lo, hi, g);
             const cplx t1 = INV ? conj(w1) : w1, t2 = cmul(t1, t1), t3 = cmul(t2, t1);
-            if (INV) { v1 = cmul(v1, t1); v2 = cmul(v2, t2); v3 = cmul(v3, t3); }
-            dft4<INV>(v0, v1, v2, v3);
-            if (!INV) { v1 = cmul(v1, t1); v2 = cmul(v2, t2); v3 = cmul(v3, t3); }
-            p0[0] = v0; p0[sp] = v1; p0[2 * sp] = v2; p0[3 * sp] = v3;
+            if (!INV) {
+                const cplx v0 = p0[0], v1 = p0[sp], r = mul_neg_i(v1);
+                p0[0] = cadd(v0, v1);
+                p0[sp] = cmul(cadd(v0, r), t1);
+                p0[2 * sp] = cmul(csub(v0, v1), t2);
+                p0[3 * sp] = cmul(csub(v0, r), t3);
+            } else {
+                const cplx v0 = p0[0], v1 = cmul(p0[sp], t1), v2 = cmul(p0[2 * sp], t2), v3 = cmul(p0[3 * sp], t3);
+                const cplx s02 = cadd(v0, v2), d02 = csub(v0, v2), s13 = cadd(v1, v3), d13 = csub(v1, v3);
+                p0[0] = cadd(s02, s13);
+                p0[sp] = cadd(d02, mul_pos_i(d13));
+            }
         }
     };
     if (!INV) {
@@ -224,6 +233,47 @@ __device__ __forceinline__ void build_tables(cplx* lo, cplx* hi, int tid)
     }
 }
 
+// Order in which the point-wise stages walk the bin pairs (k, M - k), 0 <= k <= M/2.  The forward passes leave
+// bin k at a digit-reversed position, so lanes that took consecutive k would all hit the same LDS banks (strides of
+// M/4 and M/64 complex).  Pair l takes k = ((l & 63) << HB) | (l >> 6) instead: the 64 lanes of a wave then differ
+// in the HIGH bits of k, i.e. in the low digits of the storage position.  l = M/2 stands for the self-paired bin
+// M/2.  The kernel spectrum is stored in the same order, one float4 (K[k], K[M-k]) per pair, so its loads coalesce.
+template <int M>
+__device__ __forceinline__ int pair_bin(int l)
+{
+    constexpr int HALF = M / 2;
+    int hb = 0;
+#pragma unroll
+    for (int x = HALF / 64; x > 1; x >>= 1) ++hb;
+    return l >= HALF ? HALF : (((l & 63) << hb) | (l >> 6));
+}
+
+__device__ __forceinline__ cplx w2m(int k, int M)      // W_2M^k = exp(-i pi k / M)
+{
+    float s, c;
+    sincospif(-(float)k / (float)M, &s, &c);
+    return mk(c, s);
+}
+
+// W_2M^k for the bins a thread meets when it walks the pairs l = tid, tid + T, ... in pair order: k = (lane << HB) |
+// (l >> 6), so W^k = W^(lane << HB) * W^(tid >> 6) * (W^(T/64))^i: two sincospi per thread and one rotation per pair
+// instead of one sincospi per pair.  The self-paired bin M/2 (l = M/2) is -i.
+template <int M, int T>
+struct PairTwiddle {
+    cplx cur, step;
+    __device__ __forceinline__ PairTwiddle(int tid)
+    {
+        cur = w2m(pair_bin<M>(tid < M / 2 ? tid : 0), M);
+        step = w2m(T / 64, M);
+    }
+    __device__ __forceinline__ cplx next(int l)
+    {
+        const cplx w = l >= M / 2 ? mk(0.f, -1.f) : cur;
+        cur = cmul(cur, step);
+        return w;
+    }
+};
+
 // Bins k and M - k of the spectrum of a real sequence of length 2M from the length-M transform Z of its even/odd
 // packing:  X[k] = (Z[k] + conj Z[M-k]) / 2 + W_2M^k (Z[k] - conj Z[M-k]) / (2i),  k = 0 .. M  (Z[M] = Z[0]).
 // A = Z[k], Bc = conj Z[M-k], w = W_2M^k.  For k = 0 this gives X[0] and X[M] (both real).
@@ -248,27 +298,6 @@ __device__ __forceinline__ void tangle(cplx Yk, cplx Ymk, cplx w, cplx& Zk, cplx
     Zmk = cadd(conj(ye), mul_pos_i(conj(yo)));
 }
 
-// Order in which the point-wise stages walk the bin pairs (k, M - k), 0 <= k <= M/2.  The forward passes leave
-// bin k at a digit-reversed position, so lanes that took consecutive k would all hit the same LDS banks (strides of
-// M/4 and M/64 complex).  Pair l takes k = ((l & 63) << HB) | (l >> 6) instead: the 64 lanes of a wave then differ
-// in the HIGH bits of k, i.e. in the low digits of the storage position.  l = M/2 stands for the self-paired bin
-// M/2.  The kernel spectrum is stored in the same order, one float4 (K[k], K[M-k]) per pair, so its loads coalesce.
-template <int M>
-__device__ __forceinline__ int pair_bin(int l)
-{
-    constexpr int HALF = M / 2;
-    int hb = 0;
-#pragma unroll
-    for (int x = HALF / 64; x > 1; x >>= 1) ++hb;
-    return l >= HALF ? HALF : (((l & 63) << hb) | (l >> 6));
-}
-
-__device__ __forceinline__ cplx w2m(int k, int M)      // W_2M^k = exp(-i pi k / M)
-{
-    float s, c;
-    sincospif(-(float)k / (float)M, &s, &c);
-    return mk(c, s);
-}
 
 // x (one sequence of L steps) -> optional short kernel and activation -> packed complex z[n] = v[2n] + i v[2n+1]
 // in a[], zero beyond L.  Ends with the data in place but NOT synchronised.
@@ -388,10 +417,11 @@ __global__ __launch_bounds__(conv_threads(M)) void shortlong_conv_kernel(const I
 
     // ---- spectrum of v times spectrum of the kernel, re-packed for the inverse transform (pairs k, M - k)
     const float4* Kc = Kf + (long)c * (M / 2 + 1);
+    PairTwiddle<M, T> pw(tid);
     for (int l = tid; l <= M / 2; l += T) {
         const int kk = pair_bin<M>(l);
         const int p1 = conv_pad(spectrum_pos<M>(kk)), p2 = conv_pad(spectrum_pos<M>((M - kk) & (M - 1)));
-        const cplx w = w2m(kk, M);
+        const cplx w = pw.next(l);
         cplx Xk, Xmk, Zk, Zmk;
         untangle(a[p1], conj(a[p2]), w, Xk, Xmk);
         const float4 kq = Kc[l];
