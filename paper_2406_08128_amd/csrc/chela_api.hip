@@ -117,8 +117,8 @@ TrainPlans make_train_plans(long BH, int N, int dk, int dv, int chunk)
     return t;
 }
 
-// Non-causal form: the pre-pass is the only part that is split, and only to fill the GPU (about four workgroups per
-// compute unit), in pieces of at least 256 tokens.
+// Non-causal form: the pre-pass is the only part that is split, and only to fill the GPU (two workgroups per compute
+// unit measured best: every further segment is a state to write, scan and read), in pieces of at least 256 tokens.
 Plan make_noncausal_plan(long BH, int N, int dk, int dv, bool is_bwd)
 {
     Plan p{};
@@ -126,7 +126,7 @@ Plan make_noncausal_plan(long BH, int N, int dk, int dv, bool is_bwd)
     p.state_elems = (size_t)dk * dv;
     if (BH <= 0 || N <= 0) { p.seg_len = 64; p.n_seg = 0; p.ws_bytes = 0; return p; }
     const int pairs = is_bwd ? 2 : 1;
-    long n_seg = (1024 + BH * pairs - 1) / (BH * pairs);
+    long n_seg = (512 + BH * pairs - 1) / (BH * pairs);
     const long max_seg = N / 256 > 0 ? N / 256 : 1;
     const int forced = env_int("CHELA_NC_SEGS", 0);     // tuning aid: segments per (b,h) of the non-causal pre-pass
     if (forced > 0) n_seg = forced;
