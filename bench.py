@@ -167,7 +167,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="lm_bf16")
     ap.add_argument("--chunk", type=int, default=64)
-    ap.add_argument("--mode", default="train", choices=["train", "train_saved", "train_state", "train_z", "train_z_saved", "noncausal", "decode", "conv", "conv_train"],
+    ap.add_argument("--mode", default="train", choices=["train", "train_saved", "train_state", "train_bnhd", "train_z", "train_z_saved", "noncausal", "decode",
+                             "conv", "conv_train"],
                     help="train: fwd+bwd (the headline); train_saved: the same step through chela_linattn_fwd_save / "
                          "_bwd_saved (the forward leaves the boundary states, the backward skips its pass over K, V); "
                          "train_state: the same through the carried-state entry points "
@@ -225,6 +226,17 @@ def main():
         def step():
             binding.chela_linattn_fwd_save(d["Q"], d["K"], d["V"], O=O, saved=saved, chunk=chunk)
             binding.chela_linattn_bwd_saved(d["Q"], d["K"], d["V"], d["dO"], saved, dQ=dQ, dK=dK, dV=dV, chunk=chunk)
+    elif args.mode == "train_bnhd":
+        assert w.dtype == "bf16", "--mode train_bnhd needs a bf16 workload"
+        t = {k: v.transpose(1, 2).contiguous() for k, v in d.items()}          # [B,N,H,d]
+        Ot = torch.empty_like(t["V"])
+        if has_bwd:
+            def step():
+                binding.chela_linattn_fwd_bnhd(t["Q"], t["K"], t["V"], O=Ot)
+                binding.chela_linattn_bwd_bnhd(t["Q"], t["K"], t["V"], t["dO"])
+        else:
+            def step():
+                binding.chela_linattn_fwd_bnhd(t["Q"], t["K"], t["V"], O=Ot)
     elif args.mode == "noncausal":
         assert w.dtype == "bf16", "--mode noncausal needs a bf16 workload"
         if has_bwd:
@@ -358,6 +370,7 @@ def main():
                                                   "fwd+bwd" if has_bwd else "fwd")
                   + (" (carried-state entry points)" if args.mode == "train_state" else "")
                   + (" (forward saves the boundary states)" if args.mode == "train_saved" else "")
+                  + (" ([B,N,H,d] tensors)" if args.mode == "train_bnhd" else "")
                   + (" (Q, K formed on chip from Z)" if args.mode == "train_z" else "")
                   + (" (Q, K formed on chip from Z; forward saves the boundary states)" if args.mode == "train_z_saved" else ""),
         "value": round(tokens_per_s, 1),

@@ -91,6 +91,16 @@ int chela_linattn_bwd_f32(const void *Q, const void *K, const void *V, const voi
                           void *dQ, void *dK, void *dV,
                           int B, int H, int N, int dk, int dv, int chunk, void *stream);
 
+/* ---- the same two maps for tensors laid out [B, N, H, d] (all heads of a token next to each other, which is how
+ * a projection `X W` leaves them: no transposition pass is needed before or after).  bf16 I/O; Q, K, dQ, dK are
+ * [B,N,H,dk], V, O, dO, dV are [B,N,H,dv], contiguous.  64-token chunks (`chunk` is validated, {64, 128}, and
+ * otherwise ignored).  Scratch as for chela_linattn_fwd / _bwd with chunk 64.  Everything else as above. */
+int chela_linattn_fwd_bnhd(const void *Q, const void *K, const void *V, void *O,
+                           int B, int H, int N, int dk, int dv, int chunk, void *stream);
+int chela_linattn_bwd_bnhd(const void *Q, const void *K, const void *V, const void *dO,
+                           void *dQ, void *dK, void *dV,
+                           int B, int H, int N, int dk, int dv, int chunk, void *stream);
+
 /* ---- carried state (segment-wise processing, Sec. 5.2 / App. A: sequences are cut into segments that are
  * processed one after the other; the running d_k x d_v state is all one segment hands to the next) ------------
  * Same maps as above, bf16 I/O, with the state made explicit.  States are fp32, [B, H, dk, dv], 16-byte aligned.

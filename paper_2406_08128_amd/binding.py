@@ -43,6 +43,10 @@ def lib() -> ctypes.CDLL:
         f = getattr(L, name)
         f.argtypes = [vp, vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, vp]
         f.restype = i
+    L.chela_linattn_fwd_bnhd.argtypes = [vp, vp, vp, vp, i, i, i, i, i, i, vp]
+    L.chela_linattn_fwd_bnhd.restype = i
+    L.chela_linattn_bwd_bnhd.argtypes = [vp, vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, vp]
+    L.chela_linattn_bwd_bnhd.restype = i
     L.chela_linattn_fwd_state.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, vp]
     L.chela_linattn_fwd_state.restype = i
     L.chela_linattn_bwd_state.argtypes = [vp] * 10 + [i, i, i, i, i, i, vp]
@@ -171,6 +175,39 @@ def chela_linattn_bwd(Q, K, V, dO, dQ=None, dK=None, dV=None, chunk: int = 64, s
     with torch.cuda.device(Q.device):
         _check(f(Q.data_ptr(), K.data_ptr(), V.data_ptr(), dO.data_ptr(), dQ.data_ptr(), dK.data_ptr(),
                  dV.data_ptr(), B, H, N, dk, dv, int(chunk), _stream_ptr(stream)))
+    return dQ, dK, dV
+
+
+def _dims_bnhd(Q, K, V):
+    if Q.dim() != 4 or K.shape != Q.shape or V.dim() != 4 or V.shape[:3] != Q.shape[:3]:
+        raise ValueError("expected Q, K: [B,N,H,dk] and V: [B,N,H,dv]")
+    for t in (Q, K, V):
+        if t.dtype != torch.bfloat16 or not t.is_cuda or not t.is_contiguous():
+            raise ValueError("tensors must be contiguous bf16 device tensors")
+    B, N, H, dk = Q.shape
+    return B, H, N, dk, V.shape[3]
+
+
+def chela_linattn_fwd_bnhd(Q, K, V, O=None, stream=None):
+    """O for Q, K [B,N,H,dk] and V [B,N,H,dv] (heads inside the token row); O is [B,N,H,dv]."""
+    B, H, N, dk, dv = _dims_bnhd(Q, K, V)
+    if O is None:
+        O = torch.empty_like(V)
+    with torch.cuda.device(Q.device):
+        _check(lib().chela_linattn_fwd_bnhd(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), B, H, N, dk, dv, 64,
+                                            _stream_ptr(stream)))
+    return O
+
+
+def chela_linattn_bwd_bnhd(Q, K, V, dO, stream=None):
+    """(dQ, dK, dV) in the [B,N,H,d] layout."""
+    B, H, N, dk, dv = _dims_bnhd(Q, K, V)
+    if dO.shape != V.shape or dO.dtype != V.dtype or not dO.is_contiguous():
+        raise ValueError("dO must match V")
+    dQ, dK, dV = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
+    with torch.cuda.device(Q.device):
+        _check(lib().chela_linattn_bwd_bnhd(Q.data_ptr(), K.data_ptr(), V.data_ptr(), dO.data_ptr(), dQ.data_ptr(),
+                                            dK.data_ptr(), dV.data_ptr(), B, H, N, dk, dv, 64, _stream_ptr(stream)))
     return dQ, dK, dV
 
 

@@ -449,6 +449,27 @@ static int bwd_saved_common(const void* Q, const void* K, const void* V, const v
                            t.bwd, ws, (hipStream_t)stream) == hipSuccess ? CHELA_OK : CHELA_ERR_HIP;
 }
 
+// [B,N,H,d] tensors: same extents and aliasing rules as the [B,H,N,d] calls, 64-token chunks.
+static int bnhd_common(const void* Q, const void* K, const void* V, const void* dO, void* O_or_dQ, void* dK, void* dV,
+                       bool is_bwd, int B, int H, int N, int dk, int dv, int chunk, void* stream)
+{
+    const size_t th = (B > 0 && H > 0 && N > 0) ? (size_t)B * H * N : 0;
+    const void* in_v[4] = {Q, K, V, is_bwd ? dO : Q};
+    const size_t inb[4] = {th * dk * 2, th * dk * 2, th * dv * 2, is_bwd ? th * dv * 2 : 0};
+    void* out_v[3] = {O_or_dQ, is_bwd ? dK : O_or_dQ, is_bwd ? dV : O_or_dQ};
+    const size_t outb[3] = {th * (is_bwd ? dk : dv) * 2, is_bwd ? th * dk * 2 : 0, is_bwd ? th * dv * 2 : 0};
+    bool empty = false;
+    int rc = validate(in_v, inb, 4, out_v, outb, 3, B, H, N, dk, dv, chunk, CHELA_DTYPE_BF16, &empty);
+    if (rc != CHELA_OK || empty) return rc;
+    Plan plan = make_plan((long)B * H, N, dk, dv, 64, CHELA_DTYPE_BF16, is_bwd, false);
+    float* ws = nullptr;
+    rc = get_workspace(plan.ws_bytes, &ws);
+    if (rc != CHELA_OK) return rc;
+    hipError_t e = is_bwd ? launch_bf16_bwd_nh(Q, K, V, dO, O_or_dQ, dK, dV, B, H, N, dk, dv, plan, ws, (hipStream_t)stream)
+                          : launch_bf16_fwd_nh(Q, K, V, O_or_dQ, B, H, N, dk, dv, plan, ws, (hipStream_t)stream);
+    return e == hipSuccess ? CHELA_OK : CHELA_ERR_HIP;
+}
+
 static int noncausal_common(const void* Q, const void* K, const void* V, const void* dO, void* O_or_dQ, void* dK,
                             void* dV, bool is_bwd, int B, int H, int N, int dk, int dv, void* stream)
 {
@@ -567,6 +588,18 @@ size_t chela_linattn_saved_bytes(int B, int H, int N, int dk, int dv, int chunk)
     if (!((dk == 64 || dk == 128) && (dv == 64 || dv == 128))) return 0;
     if (!(chunk == 64 || chunk == 128)) return 0;
     return saved_bytes((long)B * H, make_train_plans((long)B * H, N, dk, dv, chunk));
+}
+
+int chela_linattn_fwd_bnhd(const void* Q, const void* K, const void* V, void* O, int B, int H, int N, int dk, int dv,
+                           int chunk, void* stream)
+{
+    return bnhd_common(Q, K, V, nullptr, O, nullptr, nullptr, false, B, H, N, dk, dv, chunk, stream);
+}
+
+int chela_linattn_bwd_bnhd(const void* Q, const void* K, const void* V, const void* dO, void* dQ, void* dK, void* dV,
+                           int B, int H, int N, int dk, int dv, int chunk, void* stream)
+{
+    return bnhd_common(Q, K, V, dO, dQ, dK, dV, true, B, H, N, dk, dv, chunk, stream);
 }
 
 int chela_linattn_noncausal_fwd(const void* Q, const void* K, const void* V, void* O, int B, int H, int N, int dk,

@@ -51,6 +51,11 @@ hipError_t launch_bf16_bwd(const void* Q, const void* K, const void* V, const vo
 // length is save_every times the forward's.
 struct TrainPlans { Plan fwd, bwd; int save_every; };
 TrainPlans make_train_plans(long BH, int N, int dk, int dv, int chunk);
+// The same two maps for [B,N,H,d] tensors; plan.chunk must be 64.
+hipError_t launch_bf16_fwd_nh(const void* Q, const void* K, const void* V, void* O, int B, int H, int N, int dk, int dv,
+                              const Plan& plan, float* ws, hipStream_t st);
+hipError_t launch_bf16_bwd_nh(const void* Q, const void* K, const void* V, const void* dO, void* dQ, void* dK, void* dV,
+                              int B, int H, int N, int dk, int dv, const Plan& plan, float* ws, hipStream_t st);
 // Eq. 11-12 variants: Z [BH][N][dk] stands in for Q and K, aff = [4][H][dk] fp32 (alpha_q, beta_q, alpha_k, beta_k).
 // plan.chunk must be 64.  The backward needs zbwd_extra_ws_bytes() of workspace behind plan.ws_bytes.
 // `saved` as for launch_bf16_fwd / launch_bf16_bwd (optional).

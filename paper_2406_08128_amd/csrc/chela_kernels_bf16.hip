@@ -167,28 +167,33 @@ struct TileRegs {
     static constexpr int NV = C * D / 8 / 256;     // vectors per thread
     uint4 v[NV];
     // `tile` points at the first row; rows >= valid_rows read as zero.
-    __device__ __forceinline__ void load(const bf16* tile, int valid_rows, int tid)
+    // `ld` is the distance between rows in elements: D for [B,H,N,d] tensors (the tile is then one contiguous block
+    // and the address below folds to 16 * x), H * D for [B,N,H,d] ones.
+    static __device__ __forceinline__ const uint4* at(const bf16* tile, int ld, int x)
     {
-        const uint4* src = reinterpret_cast<const uint4*>(tile);
+        if (ld == D) return reinterpret_cast<const uint4*>(tile) + x;      // (decided at compile time for [B,H,N,d])
+        return reinterpret_cast<const uint4*>(tile + (x / VPR) * ld + (x % VPR) * 8);
+    }
+    __device__ __forceinline__ void load(const bf16* tile, int ld, int valid_rows, int tid)
+    {
         if (valid_rows >= C) {
 #pragma unroll
-            for (int n = 0; n < NV; ++n) v[n] = src[tid + 256 * n];
+            for (int n = 0; n < NV; ++n) v[n] = *at(tile, ld, tid + 256 * n);
         } else {
             const int lim = valid_rows * VPR;
 #pragma unroll
             for (int n = 0; n < NV; ++n) {
                 const int x = tid + 256 * n;
-                v[n] = x < lim ? src[x] : make_uint4(0, 0, 0, 0);
+                v[n] = x < lim ? *at(tile, ld, x) : make_uint4(0, 0, 0, 0);
             }
         }
     }
     // All C rows exist: no predicate, so the loads are issued unconditionally and the compiler can count them
     // (s_waitcnt vmcnt(n) with the exact n instead of 0 wherever younger loads are meant to stay in flight).
-    __device__ __forceinline__ void load_full(const bf16* tile, int tid)
+    __device__ __forceinline__ void load_full(const bf16* tile, int ld, int tid)
     {
-        const uint4* src = reinterpret_cast<const uint4*>(tile);
 #pragma unroll
-        for (int n = 0; n < NV; ++n) v[n] = src[tid + 256 * n];
+        for (int n = 0; n < NV; ++n) v[n] = *at(tile, ld, tid + 256 * n);
     }
     __device__ __forceinline__ void store(bf16* lds, int tid) const
     {
@@ -316,8 +321,8 @@ struct PrepassLds {
 template <int DA, int DB, int AFF>
 __device__ __forceinline__ void prepass_body(const bf16* __restrict__ X, const bf16* __restrict__ Y,
                                              float* __restrict__ out, const float* __restrict__ alpha,
-                                             const float* __restrict__ beta, int ntok, unsigned char* lds, int tid,
-                                             int w, int lane)
+                                             const float* __restrict__ beta, int lda, int ldb, int ntok,
+                                             unsigned char* lds, int tid, int w, int lane)
 {
     constexpr int R = 64;
     constexpr int PF = 2;          // 64-token blocks in flight per workgroup: this kernel only reads, so it lives
@@ -357,8 +362,8 @@ __device__ __forceinline__ void prepass_body(const bf16* __restrict__ X, const b
         // is unconditional and the wait before a set is consumed leaves the younger set's loads in flight.
 #pragma unroll
         for (int u = 0; u < PF; ++u) {
-            rx[u].load_full(X + (size_t)(u * R) * DA, tid);
-            ry[u].load_full(Y + (size_t)(u * R) * DB, tid);
+            rx[u].load_full(X + (size_t)(u * R) * lda, lda, tid);
+            ry[u].load_full(Y + (size_t)(u * R) * ldb, ldb, tid);
             __builtin_amdgcn_sched_barrier(0);   // keep the sets in issue order: the wait for set 0 must not cover set 1
         }
         for (; c0 + 2 * PF * R <= ntok; c0 += PF * R) {
@@ -366,8 +371,8 @@ __device__ __forceinline__ void prepass_body(const bf16* __restrict__ X, const b
             for (int u = 0; u < PF; ++u) {
                 consume(u);
                 __syncthreads();
-                rx[u].load_full(X + (size_t)(c0 + (PF + u) * R) * DA, tid);
-                ry[u].load_full(Y + (size_t)(c0 + (PF + u) * R) * DB, tid);
+                rx[u].load_full(X + (size_t)(c0 + (PF + u) * R) * lda, lda, tid);
+                ry[u].load_full(Y + (size_t)(c0 + (PF + u) * R) * ldb, ldb, tid);
                 multiply();
                 __syncthreads();
             }
@@ -376,8 +381,8 @@ __device__ __forceinline__ void prepass_body(const bf16* __restrict__ X, const b
 #pragma unroll
         for (int u = 0; u < PF; ++u)
             if (u * R < ntok) {
-                rx[u].load(X + (size_t)(u * R) * DA, ntok - u * R, tid);
-                ry[u].load(Y + (size_t)(u * R) * DB, ntok - u * R, tid);
+                rx[u].load(X + (size_t)(u * R) * lda, lda, ntok - u * R, tid);
+                ry[u].load(Y + (size_t)(u * R) * ldb, ldb, ntok - u * R, tid);
             }
     }
     // The rest (at most 2 PF blocks, the last one possibly ragged): set u holds block c0 + u R if that block exists.
@@ -389,8 +394,8 @@ __device__ __forceinline__ void prepass_body(const bf16* __restrict__ X, const b
                 consume(u);
                 __syncthreads();
                 if (c + PF * R < ntok) {
-                    rx[u].load(X + (size_t)(c + PF * R) * DA, ntok - c - PF * R, tid);
-                    ry[u].load(Y + (size_t)(c + PF * R) * DB, ntok - c - PF * R, tid);
+                    rx[u].load(X + (size_t)(c + PF * R) * lda, lda, ntok - c - PF * R, tid);
+                    ry[u].load(Y + (size_t)(c + PF * R) * ldb, ldb, ntok - c - PF * R, tid);
                 }
                 multiply();
                 __syncthreads();
@@ -428,8 +433,8 @@ __device__ __forceinline__ void fwd_sweep_body(const bf16* __restrict__ Qb, cons
                                                const bf16* __restrict__ Vb, bf16* __restrict__ Ob,
                                                const float* __restrict__ S0, float* __restrict__ S_final,
                                                float* __restrict__ S_final_T, const float* __restrict__ aff,
-                                               size_t aff_stride, int ntok, unsigned char* lds, int tid, int w,
-                                               int lane)
+                                               size_t aff_stride, int ldk, int ldv, int ntok, unsigned char* lds,
+                                               int tid, int w, int lane)
 {
     constexpr int LDK = DK + PAD, LDV = DV + PAD;
     constexpr int TB = C / 32, JB = DV / 32, IB = DK / 32;
@@ -447,9 +452,9 @@ __device__ __forceinline__ void fwd_sweep_body(const bf16* __restrict__ Qb, cons
 
     TileRegs<C, DK> rq, rk;   // with ZQK only rq is used: it holds Z
     TileRegs<C, DV> rv;
-    rq.load(Qb, ntok, tid);
-    if (!ZQK) rk.load(Kb, ntok, tid);
-    rv.load(Vb, ntok, tid);
+    rq.load(Qb, ldk, ntok, tid);
+    if (!ZQK) rk.load(Kb, ldk, ntok, tid);
+    rv.load(Vb, ldv, ntok, tid);
     float* sAff = reinterpret_cast<float*>(lds + FwdLds<C, DK, DV, false>::TILES);
     if (ZQK) {
         for (int x = tid; x < 4 * DK; x += 256) sAff[x] = aff[(size_t)(x / DK) * aff_stride + x % DK];
@@ -472,9 +477,9 @@ __device__ __forceinline__ void fwd_sweep_body(const bf16* __restrict__ Qb, cons
         __syncthreads();
         const bool more = c0 + C < ntok;
         if (more) {
-            rq.load(Qb + (size_t)(c0 + C) * DK, ntok - c0 - C, tid);
-            if (!ZQK) rk.load(Kb + (size_t)(c0 + C) * DK, ntok - c0 - C, tid);
-            rv.load(Vb + (size_t)(c0 + C) * DV, ntok - c0 - C, tid);
+            rq.load(Qb + (size_t)(c0 + C) * ldk, ldk, ntok - c0 - C, tid);
+            if (!ZQK) rk.load(Kb + (size_t)(c0 + C) * ldk, ldk, ntok - c0 - C, tid);
+            rv.load(Vb + (size_t)(c0 + C) * ldv, ldv, ntok - c0 - C, tid);
         }
         bf16x8 bQ[DK / 16];   // Q rows of this wave's token block: the B operand (n = token, k = feature i)
 #pragma unroll
@@ -506,10 +511,10 @@ __device__ __forceinline__ void fwd_sweep_body(const bf16* __restrict__ Qb, cons
             }
         }
         {
-            bf16* rows = Ob + (size_t)(c0 + tb * 32) * DV;
+            bf16* rows = Ob + (size_t)(c0 + tb * 32) * ldv;
             const int valid = ntok - (c0 + tb * 32);
 #pragma unroll
-            for (int n = 0; n < NJ; ++n) store_tile_T(rows, DV, (jg * NJ + n) * 32, accO[n], valid, lane);
+            for (int n = 0; n < NJ; ++n) store_tile_T(rows, ldv, (jg * NJ + n) * 32, accO[n], valid, lane);
         }
         // state update S += K^T V (after the segment's last chunk only if the final state is asked for)
         if (more || S_final != nullptr || (SAVE && S_final_T != nullptr)) {
@@ -595,8 +600,8 @@ __device__ __forceinline__ void bwd_sweep_body(const bf16* __restrict__ Qb, cons
                                                bf16* __restrict__ dQb, bf16* __restrict__ dKb, bf16* __restrict__ dVb,
                                                const float* __restrict__ Send, const float* __restrict__ Rnext,
                                                float* __restrict__ R_final, const float* __restrict__ aff,
-                                               size_t aff_stride, float* __restrict__ part, int ntok,
-                                               unsigned char* lds, int tid, int w, int lane)
+                                               size_t aff_stride, float* __restrict__ part, int ldk, int ldv,
+                                               int ntok, unsigned char* lds, int tid, int w, int lane)
 {
     constexpr int LDK = DK + PAD, LDV = DV + PAD;
     constexpr int TB = C / 32, JB = DV / 32, IB = DK / 32;
@@ -637,8 +642,8 @@ __device__ __forceinline__ void bwd_sweep_body(const bf16* __restrict__ Qb, cons
         for (int n = 0; n < NS; ++n) { accNS[n] = zero16(); accRT[n] = zero16(); }
         for (int ci = 0; ci < n_ch; ++ci) {
             const int c0 = ci * C;
-            rk.load((ZQK ? Qb : Kb) + (size_t)c0 * DK, ntok - c0, tid);
-            rv.load(Vb + (size_t)c0 * DV, ntok - c0, tid);
+            rk.load((ZQK ? Qb : Kb) + (size_t)c0 * ldk, ldk, ntok - c0, tid);
+            rv.load(Vb + (size_t)c0 * ldv, ldv, ntok - c0, tid);
             __syncthreads();
             if (ZQK) rk.store_affine(sK, sAff + 2 * DK, sAff + 3 * DK, tid);
             else rk.store(sK, tid);
@@ -660,10 +665,10 @@ __device__ __forceinline__ void bwd_sweep_body(const bf16* __restrict__ Qb, cons
 
     {
         const int c0 = (n_ch - 1) * C;
-        rq.load(Qb + (size_t)c0 * DK, ntok - c0, tid);
-        if (!ZQK) rk.load(Kb + (size_t)c0 * DK, ntok - c0, tid);
-        rv.load(Vb + (size_t)c0 * DV, ntok - c0, tid);
-        rg.load(Gb + (size_t)c0 * DV, ntok - c0, tid);
+        rq.load(Qb + (size_t)c0 * ldk, ldk, ntok - c0, tid);
+        if (!ZQK) rk.load(Kb + (size_t)c0 * ldk, ldk, ntok - c0, tid);
+        rv.load(Vb + (size_t)c0 * ldv, ldv, ntok - c0, tid);
+        rg.load(Gb + (size_t)c0 * ldv, ldv, ntok - c0, tid);
     }
     if (Send != nullptr) {
         load_state<DV, DK, true>(accNS, Send, w, lane);
@@ -686,10 +691,10 @@ __device__ __forceinline__ void bwd_sweep_body(const bf16* __restrict__ Qb, cons
         state_to_lds_T<DV, DK, false>(sR, accRT, w, lane);
         __syncthreads();
         if (ci > 0) {   // every chunk but a segment's last is complete
-            rq.load(Qb + (size_t)(c0 - C) * DK, C, tid);
-            if (!ZQK) rk.load(Kb + (size_t)(c0 - C) * DK, C, tid);
-            rv.load(Vb + (size_t)(c0 - C) * DV, C, tid);
-            rg.load(Gb + (size_t)(c0 - C) * DV, C, tid);
+            rq.load(Qb + (size_t)(c0 - C) * ldk, ldk, C, tid);
+            if (!ZQK) rk.load(Kb + (size_t)(c0 - C) * ldk, ldk, C, tid);
+            rv.load(Vb + (size_t)(c0 - C) * ldv, ldv, C, tid);
+            rg.load(Gb + (size_t)(c0 - C) * ldv, ldv, C, tid);
         }
         // roll S back over this chunk: (-S^T) += V^T K, then publish S (state before this chunk)
 #pragma unroll
@@ -734,9 +739,9 @@ __device__ __forceinline__ void bwd_sweep_body(const bf16* __restrict__ Qb, cons
                 }
             }
             if (!ZQK) {
-                bf16* rows = dQb + (size_t)(c0 + rb * 32) * DK;
+                bf16* rows = dQb + (size_t)(c0 + rb * 32) * ldk;
 #pragma unroll
-                for (int n = 0; n < NI; ++n) store_tile_T(rows, DK, (cg * NI + n) * 32, acc[n], valid, lane);
+                for (int n = 0; n < NI; ++n) store_tile_T(rows, ldk, (cg * NI + n) * 32, acc[n], valid, lane);
             }
         }
         // ---------------- dK^T for key block sb = rb:  dK^T = Q^T dP + R V^T
@@ -769,13 +774,13 @@ __device__ __forceinline__ void bwd_sweep_body(const bf16* __restrict__ Qb, cons
                 }
             }
             if (!ZQK) {
-                bf16* rows = dKb + (size_t)(c0 + rb * 32) * DK;
+                bf16* rows = dKb + (size_t)(c0 + rb * 32) * ldk;
 #pragma unroll
-                for (int n = 0; n < NI; ++n) store_tile_T(rows, DK, (cg * NI + n) * 32, acc[n], valid, lane);
+                for (int n = 0; n < NI; ++n) store_tile_T(rows, ldk, (cg * NI + n) * 32, acc[n], valid, lane);
             } else {
                 // dZ = alpha_q dQ + alpha_k dK; the lane owns features f0 + 8a + 4h + b of token rb*32 + r
                 const int r = lane & 31, h = lane >> 5;
-                bf16* rows = dQb + (size_t)(c0 + rb * 32) * DK;
+                bf16* rows = dQb + (size_t)(c0 + rb * 32) * ldk;
 #pragma unroll
                 for (int n = 0; n < NI; ++n) {
                     const int f0 = (cg * NI + n) * 32;
@@ -796,7 +801,7 @@ __device__ __forceinline__ void bwd_sweep_body(const bf16* __restrict__ Qb, cons
                             kz[e] = acc[n][e] * z[b];
                         }
                     }
-                    store_tile_T(rows, DK, f0, dz, valid, lane);
+                    store_tile_T(rows, ldk, f0, dz, valid, lane);
                     pg[0][n] += sum_tokens16(qz, lane);
                     pg[1][n] += sum_tokens16(accQ[n], lane);
                     pg[2][n] += sum_tokens16(kz, lane);
@@ -833,9 +838,9 @@ __device__ __forceinline__ void bwd_sweep_body(const bf16* __restrict__ Qb, cons
                     }
                 }
             }
-            bf16* rows = dVb + (size_t)(c0 + rb * 32) * DV;
+            bf16* rows = dVb + (size_t)(c0 + rb * 32) * ldv;
 #pragma unroll
-            for (int n = 0; n < NJ; ++n) store_tile_T(rows, DV, (cg * NJ + n) * 32, acc[n], valid, lane);
+            for (int n = 0; n < NJ; ++n) store_tile_T(rows, ldv, (cg * NJ + n) * 32, acc[n], valid, lane);
         }
         // ---------------- R^T += dO^T Q (after the segment's first chunk only if the final state is asked for)
         if (ci > 0 || R_final != nullptr) {
@@ -886,8 +891,15 @@ struct SegStateArgs {
     int H;
 };
 
-template <int DA, int DB, int AFF>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((DA == 64 && DB == 64) ? (AFF == 0 ? 6 : 5) : 1)))
+// NH: the tensors are [B,N,H,d] (token rows H * d apart) instead of [B,H,N,d]; args.H is then the head count.
+template <int D>
+__device__ __forceinline__ size_t row_offset(bool nh, long bh, int H, int N, int p0)
+{
+    return nh ? ((size_t)(bh / H) * N + p0) * H * D + (size_t)(bh % H) * D : ((size_t)bh * N + p0) * D;
+}
+
+template <int DA, int DB, int AFF, bool NH>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((DA == 64 && DB == 64) ? ((AFF == 0 && !NH) ? 6 : 5) : 1)))
 void bf16_seg_state_kernel(SegStateArgs args, int N, int seg_len, int n_seg)
 {
     __shared__ __attribute__((aligned(16))) unsigned char lds[PrepassLds<DA, DB, AFF>::BYTES];
@@ -903,13 +915,15 @@ void bf16_seg_state_kernel(SegStateArgs args, int N, int seg_len, int n_seg)
         al = args.alpha[z] + hoff;
         be = args.beta[z] + hoff;
     }
-    prepass_body<DA, DB, AFF>(args.X[z] + ((size_t)bh * N + p0) * DA, args.Y[z] + ((size_t)bh * N + p0) * DB,
-                              args.out[z] + ((size_t)bh * n_seg + seg) * DA * DB, al, be, p1 - p0, lds, tid, w, lane);
+    prepass_body<DA, DB, AFF>(args.X[z] + row_offset<DA>(NH, bh, args.H, N, p0),
+                              args.Y[z] + row_offset<DB>(NH, bh, args.H, N, p0),
+                              args.out[z] + ((size_t)bh * n_seg + seg) * DA * DB, al, be, NH ? args.H * DA : DA,
+                              NH ? args.H * DB : DB, p1 - p0, lds, tid, w, lane);
 }
 
 // (the narrowest shape is asked to stay within the 128 registers that let four workgroups share a compute unit)
-template <int C, int DK, int DV, bool ZQK, bool SAVE>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((C == 64 && DK == 64 && DV == 64) ? 4 : 1)))
+template <int C, int DK, int DV, bool ZQK, bool SAVE, bool NH>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((C == 64 && DK == 64 && DV == 64) ? (NH ? 3 : 4) : 1)))
 void bf16_fwd_sweep_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K,
                                                             const bf16* __restrict__ V, bf16* __restrict__ O,
                                                             const float* __restrict__ S0, float* __restrict__ S_out,
@@ -923,7 +937,7 @@ void bf16_fwd_sweep_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ 
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int p0 = seg * seg_len, p1 = min(N, p0 + seg_len);
-    const size_t rk = ((size_t)bh * N + p0) * DK, rv = ((size_t)bh * N + p0) * DV;
+    const size_t rk = row_offset<DK>(NH, bh, H, N, p0), rv = row_offset<DV>(NH, bh, H, N, p0);
     // S0: scanned start states (segment 0's slot holds the carried-in state, read only if there is one);
     // S_out: final state of the whole sequence, written by the last segment's workgroup
     const bool has_state = S0 != nullptr && (seg > 0 || first_loads_state);
@@ -937,11 +951,11 @@ void bf16_fwd_sweep_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ 
     fwd_sweep_body<C, DK, DV, ZQK, SAVE>(Q + rk, ZQK ? nullptr : K + rk, V + rv, O + rv,
                                    has_state ? S0 + ((size_t)bh * n_seg + seg) * DK * DV : nullptr,
                                    (S_out != nullptr && seg == n_seg - 1) ? S_out + (size_t)bh * DK * DV : nullptr,
-                                   save_to, ZQK ? aff + (size_t)(bh % H) * DK : nullptr, (size_t)H * DK, p1 - p0, lds, tid, w,
-                                   lane);
+                                   save_to, ZQK ? aff + (size_t)(bh % H) * DK : nullptr, (size_t)H * DK,
+                                   NH ? H * DK : DK, NH ? H * DV : DV, p1 - p0, lds, tid, w, lane);
 }
 
-template <int C, int DK, int DV, bool ZQK>
+template <int C, int DK, int DV, bool ZQK, bool NH>
 __global__ __launch_bounds__(256) void bf16_bwd_sweep_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K,
                                                             const bf16* __restrict__ V, const bf16* __restrict__ dO,
                                                             bf16* __restrict__ dQ, bf16* __restrict__ dK,
@@ -956,7 +970,7 @@ __global__ __launch_bounds__(256) void bf16_bwd_sweep_kernel(const bf16* __restr
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int p0 = seg * seg_len, p1 = min(N, p0 + seg_len);
-    const size_t rk = ((size_t)bh * N + p0) * DK, rv = ((size_t)bh * N + p0) * DV;
+    const size_t rk = row_offset<DK>(NH, bh, H, N, p0), rv = row_offset<DV>(NH, bh, H, N, p0);
     const size_t soff = ((size_t)bh * n_seg + seg) * DK * DV;
     // the scan leaves zeros in the last segment's R slot, so Rnext can be read for every segment
     // dS_in: gradient with respect to the carried-in state = R after the very first chunk (segment 0's workgroup)
@@ -964,8 +978,8 @@ __global__ __launch_bounds__(256) void bf16_bwd_sweep_kernel(const bf16* __restr
                                    dV + rv, Send ? Send + soff : nullptr, Rnext ? Rnext + soff : nullptr,
                                    (dS_in != nullptr && seg == 0) ? dS_in + (size_t)bh * DK * DV : nullptr,
                                    ZQK ? aff + (size_t)(bh % H) * DK : nullptr, (size_t)H * DK,
-                                   ZQK ? part + ((size_t)bh * n_seg + seg) * 4 * DK : nullptr, p1 - p0, lds, tid, w,
-                                   lane);
+                                   ZQK ? part + ((size_t)bh * n_seg + seg) * 4 * DK : nullptr, NH ? H * DK : DK,
+                                   NH ? H * DV : DV, p1 - p0, lds, tid, w, lane);
 }
 
 // Adds up the workgroups' shares of the parameter gradients: part is [B][H][n_seg][4][DK], out is [4][H][DK].
@@ -1042,7 +1056,7 @@ hipError_t launch_bf16_step(const void* q, const void* k, const void* v, float* 
 
 // =============================================================================================== launchers
 // Pre-pass + scan over segments.  init[z] (optional, [dk][dv] fp32 per head) seeds the scan of array z.
-template <int DA, int DB, int AFF = 0>
+template <int DA, int DB, int AFF = 0, bool NH = false>
 static hipError_t run_seg_state(const SegStateArgs& a, int npairs, const int* scan_modes, const float* const* init,
                                 bool init_transposed, long BH, int N, const Plan& plan, hipStream_t st,
                                 bool do_scan = true)
@@ -1051,7 +1065,7 @@ static hipError_t run_seg_state(const SegStateArgs& a, int npairs, const int* sc
     {
         dim3 grid((unsigned)BH, plan.n_seg, npairs);
         ProfScope prof(KID_SEG_STATE_BF16, st);
-        hipLaunchKernelGGL((bf16_seg_state_kernel<DA, DB, AFF>), grid, dim3(256), 0, st, a, N, plan.seg_len, plan.n_seg);
+        hipLaunchKernelGGL((bf16_seg_state_kernel<DA, DB, AFF, NH>), grid, dim3(256), 0, st, a, N, plan.seg_len, plan.n_seg);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     if (!do_scan) return hipSuccess;
@@ -1062,7 +1076,7 @@ static hipError_t run_seg_state(const SegStateArgs& a, int npairs, const int* sc
 // `aff` (Eq. 11-12): non-null selects the kernels that take Z in place of Q and K; it points at the [4][H][DK] fp32
 // parameters (alpha_q, beta_q, alpha_k, beta_k).  A carried-in state goes through the scan even when there is a
 // single segment.
-template <int C, int DK, int DV, bool ZQK>
+template <int C, int DK, int DV, bool ZQK, bool NH = false>
 static hipError_t fwd_impl(const bf16* Q, const bf16* K, const bf16* V, bf16* O, const float* S_in, float* S_out,
                            const float* aff, int H, float* saved, int save_every, long BH, int N, const Plan& plan,
                            float* ws, hipStream_t st)
@@ -1072,20 +1086,21 @@ static hipError_t fwd_impl(const bf16* Q, const bf16* K, const bf16* V, bf16* O,
     if (use_ws) {
         SegStateArgs a{};
         a.X[0] = ZQK ? Q : K; a.Y[0] = V; a.out[0] = ws; a.skip_seg[0] = plan.n_seg - 1;
-        if (ZQK) { a.alpha[0] = aff + 2 * (size_t)H * DK; a.beta[0] = aff + 3 * (size_t)H * DK; a.H = H; }
+        a.H = H;
+        if (ZQK) { a.alpha[0] = aff + 2 * (size_t)H * DK; a.beta[0] = aff + 3 * (size_t)H * DK; }
         const int mode = SCAN_EXCL_PREFIX;
         const float* init[2] = {S_in, nullptr};
-        if ((e = run_seg_state<DK, DV, ZQK ? 1 : 0>(a, 1, &mode, init, false, BH, N, plan, st)) != hipSuccess) return e;
+        if ((e = run_seg_state<DK, DV, ZQK ? 1 : 0, NH>(a, 1, &mode, init, false, BH, N, plan, st)) != hipSuccess) return e;
     }
     dim3 grid((unsigned)BH, plan.n_seg);
     ProfScope prof(KID_FWD_SWEEP_BF16, st);
     // the variant that can save boundary states needs a few more registers; the plain call keeps its own kernel
     if (saved != nullptr)
-        hipLaunchKernelGGL((bf16_fwd_sweep_kernel<C, DK, DV, ZQK, true>), grid, dim3(256), 0, st, Q, K, V, O,
+        hipLaunchKernelGGL((bf16_fwd_sweep_kernel<C, DK, DV, ZQK, true, NH>), grid, dim3(256), 0, st, Q, K, V, O,
                            use_ws ? ws : nullptr, S_out, aff, H, saved, save_every, S_in != nullptr ? 1 : 0, N,
                            plan.seg_len, plan.n_seg);
     else
-        hipLaunchKernelGGL((bf16_fwd_sweep_kernel<C, DK, DV, ZQK, false>), grid, dim3(256), 0, st, Q, K, V, O,
+        hipLaunchKernelGGL((bf16_fwd_sweep_kernel<C, DK, DV, ZQK, false, NH>), grid, dim3(256), 0, st, Q, K, V, O,
                            use_ws ? ws : nullptr, S_out, aff, H, (float*)nullptr, 1, S_in != nullptr ? 1 : 0, N,
                            plan.seg_len, plan.n_seg);
     return hipGetLastError();
@@ -1093,7 +1108,7 @@ static hipError_t fwd_impl(const bf16* Q, const bf16* K, const bf16* V, bf16* O,
 
 // With ZQK, dQ receives dZ, dK is unused and d_aff ([4][H][DK]) the parameter gradients; the workgroups' shares of
 // those live behind the two state arrays in the workspace.
-template <int C, int DK, int DV, bool ZQK>
+template <int C, int DK, int DV, bool ZQK, bool NH = false>
 static hipError_t bwd_impl(const bf16* Q, const bf16* K, const bf16* V, const bf16* dO, const float* S_in,
                            const float* dS_out, bf16* dQ, bf16* dK, bf16* dV, float* dS_in, const float* aff,
                            float* d_aff, const float* saved, int B, int H, int N, const Plan& plan, float* ws,
@@ -1109,15 +1124,16 @@ static hipError_t bwd_impl(const bf16* Q, const bf16* K, const bf16* V, const bf
         if (plan.n_seg > 1) {
             SegStateArgs a{};
             a.X[0] = dO; a.Y[0] = Q; a.out[0] = wsR; a.skip_seg[0] = 0;
-            if (ZQK) { a.alpha[0] = aff; a.beta[0] = aff + (size_t)H * DK; a.H = H; }
+            a.H = H;
+            if (ZQK) { a.alpha[0] = aff; a.beta[0] = aff + (size_t)H * DK; }
             const int mode = SCAN_EXCL_SUFFIX;
-            if ((e = run_seg_state<DV, DK, ZQK ? 2 : 0>(a, 1, &mode, nullptr, false, BH, N, plan, st)) != hipSuccess)
+            if ((e = run_seg_state<DV, DK, ZQK ? 2 : 0, NH>(a, 1, &mode, nullptr, false, BH, N, plan, st)) != hipSuccess)
                 return e;
         }
         {
             dim3 grid((unsigned)BH, plan.n_seg);
             ProfScope prof(KID_BWD_SWEEP_BF16, st);
-            hipLaunchKernelGGL((bf16_bwd_sweep_kernel<C, DK, DV, ZQK>), grid, dim3(256), 0, st, Q, K, V, dO, dQ, dK,
+            hipLaunchKernelGGL((bf16_bwd_sweep_kernel<C, DK, DV, ZQK, NH>), grid, dim3(256), 0, st, Q, K, V, dO, dQ, dK,
                                dV, saved, plan.n_seg > 1 ? wsR : nullptr, dS_in, aff, H, wsP, N, plan.seg_len,
                                plan.n_seg);
             if ((e = hipGetLastError()) != hipSuccess) return e;
@@ -1139,19 +1155,19 @@ static hipError_t bwd_impl(const bf16* Q, const bf16* K, const bf16* V, const bf
         // S^T totals: every segment is needed (inclusive prefix); R^T totals: the first is never used (exclusive suffix)
         a.X[0] = V;  a.Y[0] = ZQK ? Q : K; a.out[0] = wsS; a.skip_seg[0] = -1;
         a.X[1] = dO; a.Y[1] = Q;           a.out[1] = wsR; a.skip_seg[1] = 0;
+        a.H = H;
         if (ZQK) {
             a.alpha[0] = aff + 2 * (size_t)H * DK; a.beta[0] = aff + 3 * (size_t)H * DK;   // K
             a.alpha[1] = aff;                      a.beta[1] = aff + (size_t)H * DK;       // Q
-            a.H = H;
         }
         const int modes[2] = {SCAN_INCL_PREFIX, SCAN_EXCL_SUFFIX};
         const float* init[2] = {S_in, dS_out};   // given as [dk][dv]; the arrays are [dv][dk]
-        if ((e = run_seg_state<DV, DK, ZQK ? 2 : 0>(a, 2, modes, init, true, BH, N, plan, st)) != hipSuccess) return e;
+        if ((e = run_seg_state<DV, DK, ZQK ? 2 : 0, NH>(a, 2, modes, init, true, BH, N, plan, st)) != hipSuccess) return e;
     }
     {
         dim3 grid((unsigned)BH, plan.n_seg);
         ProfScope prof(KID_BWD_SWEEP_BF16, st);
-        hipLaunchKernelGGL((bf16_bwd_sweep_kernel<C, DK, DV, ZQK>), grid, dim3(256), 0, st, Q, K, V, dO, dQ, dK, dV,
+        hipLaunchKernelGGL((bf16_bwd_sweep_kernel<C, DK, DV, ZQK, NH>), grid, dim3(256), 0, st, Q, K, V, dO, dQ, dK, dV,
                            use_ws ? wsS : nullptr, use_ws ? wsR : nullptr, dS_in, aff, H, wsP, N, plan.seg_len,
                            plan.n_seg);
         if ((e = hipGetLastError()) != hipSuccess) return e;
@@ -1196,7 +1212,7 @@ __global__ __launch_bounds__(256) void bf16_apply_state_kernel(const bf16* __res
     const float4* M4 = reinterpret_cast<const float4*>(M + (size_t)bh * m_stride);
 
     TileRegs<C, DA> rx;
-    rx.load(Xb, ntok, tid);
+    rx.load(Xb, DA, ntok, tid);
     for (int x = tid; x < DA * DB / 4; x += 256) {
         const float4 v = M4[x];
         if (M_IS_T) {
@@ -1225,7 +1241,7 @@ __global__ __launch_bounds__(256) void bf16_apply_state_kernel(const bf16* __res
         bf16* sXb = sX + buf * C * LDA;
         rx.store(sXb, tid);
         __syncthreads();
-        if (c0 + C < ntok) rx.load(Xb + (size_t)(c0 + C) * DA, ntok - c0 - C, tid);
+        if (c0 + C < ntok) rx.load(Xb + (size_t)(c0 + C) * DA, DA, ntok - c0 - C, tid);
         f32x16 acc[NJ];
 #pragma unroll
         for (int n = 0; n < NJ; ++n) acc[n] = zero16();
@@ -1342,6 +1358,34 @@ hipError_t launch_bf16_bwd(const void* Q, const void* K, const void* V, const vo
                                                                 nullptr, saved, (int)BH, 1, N, plan, ws, st)))
     CHELA_BWD(64, 64, 64) CHELA_BWD(128, 64, 64) CHELA_BWD(64, 64, 128) CHELA_BWD(64, 128, 64) CHELA_BWD(64, 128, 128)
 #undef CHELA_BWD
+    return hipErrorInvalidValue;
+}
+
+// [B,N,H,d] tensors (heads next to each other inside a token row), 64-token chunks, no carried or saved states.
+hipError_t launch_bf16_fwd_nh(const void* Q, const void* K, const void* V, void* O, int B, int H, int N, int dk, int dv,
+                              const Plan& plan, float* ws, hipStream_t st)
+{
+    const bf16 *q = (const bf16*)Q, *k = (const bf16*)K, *v = (const bf16*)V;
+    bf16* o = (bf16*)O;
+    const long BH = (long)B * H;
+#define CHELA_FWD_NH(DK_, DV_)                                                                                        \
+    CHELA_DISPATCH(64, DK_, DV_, (fwd_impl<64, DK_, DV_, false, true>(q, k, v, o, nullptr, nullptr, nullptr, H, nullptr, \
+                                                                      1, BH, N, plan, ws, st)))
+    CHELA_FWD_NH(64, 64) CHELA_FWD_NH(64, 128) CHELA_FWD_NH(128, 64) CHELA_FWD_NH(128, 128)
+#undef CHELA_FWD_NH
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_bf16_bwd_nh(const void* Q, const void* K, const void* V, const void* dO, void* dQ, void* dK, void* dV,
+                              int B, int H, int N, int dk, int dv, const Plan& plan, float* ws, hipStream_t st)
+{
+    const bf16 *q = (const bf16*)Q, *k = (const bf16*)K, *v = (const bf16*)V, *g = (const bf16*)dO;
+    bf16 *dq = (bf16*)dQ, *dkk = (bf16*)dK, *dvv = (bf16*)dV;
+#define CHELA_BWD_NH(DK_, DV_)                                                                                         \
+    CHELA_DISPATCH(64, DK_, DV_, (bwd_impl<64, DK_, DV_, false, true>(q, k, v, g, nullptr, nullptr, dq, dkk, dvv, nullptr, \
+                                                                      nullptr, nullptr, nullptr, B, H, N, plan, ws, st)))
+    CHELA_BWD_NH(64, 64) CHELA_BWD_NH(64, 128) CHELA_BWD_NH(128, 64) CHELA_BWD_NH(128, 128)
+#undef CHELA_BWD_NH
     return hipErrorInvalidValue;
 }
 

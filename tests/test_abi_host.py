@@ -54,7 +54,7 @@ def _bwd(L, name="chela_linattn_bwd", Q=A, K=A + SZ, V=A + 2 * SZ, dO=A + 3 * SZ
     return getattr(L, name)(Q, K, V, dO, dQ, dK, dV, B, H, N, dk, dv, chunk, None)
 
 
-@pytest.mark.parametrize("name", ["chela_linattn_fwd", "chela_linattn_fwd_f32"])
+@pytest.mark.parametrize("name", ["chela_linattn_fwd", "chela_linattn_fwd_f32", "chela_linattn_fwd_bnhd"])
 def test_fwd_argument_errors(L, name):
     assert _fwd(L, name, Q=None) == -1
     assert _fwd(L, name, O=None) == -1
@@ -79,7 +79,7 @@ def test_chunk_sets_differ_by_dtype(L):
     assert _fwd(L, "chela_linattn_fwd_f32", chunk=128) == -4
 
 
-@pytest.mark.parametrize("name", ["chela_linattn_bwd", "chela_linattn_bwd_f32"])
+@pytest.mark.parametrize("name", ["chela_linattn_bwd", "chela_linattn_bwd_f32", "chela_linattn_bwd_bnhd"])
 def test_bwd_argument_errors(L, name):
     assert _bwd(L, name, dO=None) == -1
     assert _bwd(L, name, dV=None) == -1

@@ -693,3 +693,41 @@ def test_shortlong_conv_bwd_bf16(shape):
 @pytest.mark.parametrize("L", [300, 4096])
 def test_long_conv_alone_bwd(L):
     _run_conv_bwd_case(2, 3, L, 3, "f32", seed=L + 12, short=False)
+
+
+# ------------------------------------------------------------------------------------------ [B,N,H,d] layout
+@pytest.mark.parametrize("shape", [(1, 1, 64, 64, 64), (2, 3, 1000, 64, 64), (1, 5, 9000, 64, 64), (3, 2, 1100, 64, 128),
+                                   (1, 3, 1300, 128, 64), (2, 2, 700, 128, 128), (1, 2, 1, 64, 64)])
+def test_bnhd_layout_is_the_same_map(shape):
+    # the token-major layout must give, bit for bit, the head-major results transposed (same kernels, same split)
+    B, H, N, dk, dv = shape
+    w = shrink(WORKLOADS["lm_bf16"], B=B, H=H, N=N, dk=dk, dv=dv, seed=170 + N)
+    x = make_inputs(w, with_dO=True)
+    d = _dev(x)
+    t = {k: v.transpose(1, 2).contiguous() for k, v in d.items()}           # [B,N,H,d]
+    O = binding.chela_linattn_fwd_bnhd(t["Q"], t["K"], t["V"])
+    dQ, dK, dV = binding.chela_linattn_bwd_bnhd(t["Q"], t["K"], t["V"], t["dO"])
+    O2 = binding.chela_linattn_fwd(d["Q"], d["K"], d["V"])
+    dQ2, dK2, dV2 = binding.chela_linattn_bwd(d["Q"], d["K"], d["V"], d["dO"])
+    torch.cuda.synchronize()
+    for a, b in ((O, O2), (dQ, dQ2), (dK, dK2), (dV, dV2)):
+        assert torch.equal(a.transpose(1, 2), b)
+    Qn, Kn, Vn, Gn = (to_f64_numpy(x[n]) for n in ("Q", "K", "V", "dO"))
+    _check("O", O.transpose(1, 2), oracle.fwd_recurrent(Qn, Kn, Vn), "bf16")
+    for name, got, r in zip(("dQ", "dK", "dV"), (dQ, dK, dV), oracle.bwd_recurrent(Qn, Kn, Vn, Gn)):
+        _check(name, got.transpose(1, 2), r, "bf16")
+
+
+def test_bnhd_lm_full_size_sampled():
+    w = WORKLOADS["lm_bf16"]
+    x = make_inputs(w, with_dO=True)
+    t = {k: v.cuda().transpose(1, 2).contiguous() for k, v in x.items()}
+    O = binding.chela_linattn_fwd_bnhd(t["Q"], t["K"], t["V"])
+    dQ, dK, dV = binding.chela_linattn_bwd_bnhd(t["Q"], t["K"], t["V"], t["dO"])
+    torch.cuda.synchronize()
+    for b, h in ((0, 0), (1, 7), (3, 11)):
+        Qn, Kn, Vn, Gn = (to_f64_numpy(x[n][b:b + 1, h:h + 1]) for n in ("Q", "K", "V", "dO"))
+        sel = lambda z: z[b:b + 1, :, h:h + 1].transpose(1, 2)
+        _check("O", sel(O), oracle.fwd_recurrent(Qn, Kn, Vn), "bf16")
+        for name, got, r in zip(("dQ", "dK", "dV"), (dQ, dK, dV), oracle.bwd_recurrent(Qn, Kn, Vn, Gn)):
+            _check(name, sel(got), r, "bf16")
