@@ -65,3 +65,51 @@ def noncausal_bwd(Q, K, V, dO):
     S = np.matmul(np.swapaxes(K, -1, -2), V)
     R = np.matmul(np.swapaxes(Q, -1, -2), dO)
     return np.matmul(dO, np.swapaxes(S, -1, -2)), np.matmul(V, np.swapaxes(R, -1, -2)), np.matmul(K, R)
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# Sec. 4.3, Eq. 9: the layer's output is Norm(Q (K^T V)) * G_a, G_a a gate with the shape of the attention output.
+# The paper never writes Norm out; Sec. 2.1 attributes it to the TransNormer line of work, whose attention-output
+# normalisation is a root-mean-square normalisation with no learnable gain.  Reading taken here: per token and per
+# head, over that head's dv features,
+#
+#       Norm(o) = o / sqrt(mean_j o_j^2 + eps),        Y = Norm(O) * G,
+#
+# eps >= 0 a small constant the caller passes (with one head this is the normalisation over the whole feature
+# dimension).  The gate is an input: Eq. 10 forms it with a dense projection, which is not part of this path.
+def gate_norm_fwd(O, G, eps):
+    """Y = Norm(O) * G for O, G [..., dv]; Norm as defined above."""
+    O, G = np.asarray(O, dtype=np.float64), np.asarray(G, dtype=np.float64)
+    if O.shape != G.shape:
+        raise ValueError("O and G must have the same shape")
+    ms = np.mean(O * O, axis=-1, keepdims=True)
+    return O / np.sqrt(ms + eps) * G
+
+
+def gate_norm_bwd(O, G, dY, eps):
+    """(dO, dG) of gate_norm_fwd.
+
+    With r = (mean_j o_j^2 + eps)^(-1/2), n = r o and u = dY * G:   dG = dY * n,
+    dO_j = sum_k u_k d(n_k)/d(o_j) = r (u_j - n_j mean_k(u_k n_k))   (d r / d o_j = -r^3 o_j / dv)."""
+    O, G, dY = (np.asarray(x, dtype=np.float64) for x in (O, G, dY))
+    if O.shape != G.shape or O.shape != dY.shape:
+        raise ValueError("O, G and dY must have the same shape")
+    r = 1.0 / np.sqrt(np.mean(O * O, axis=-1, keepdims=True) + eps)
+    n = r * O
+    u = dY * G
+    dO = r * (u - n * np.mean(u * n, axis=-1, keepdims=True))
+    return dO, dY * n
+
+
+def gated_fwd(Q, K, V, G, eps):
+    """Eq. 9 under the causal mask: (O, Y) with O the un-normalised attention output and Y = Norm(O) * G."""
+    O = fwd_recurrent(Q, K, V)
+    return O, gate_norm_fwd(O, G, eps)
+
+
+def gated_bwd(Q, K, V, G, dY, eps):
+    """(dQ, dK, dV, dG) of Y = Norm(O(Q,K,V)) * G."""
+    O = fwd_recurrent(Q, K, V)
+    dO, dG = gate_norm_bwd(O, G, dY, eps)
+    dQ, dK, dV = bwd_recurrent(Q, K, V, dO)
+    return dQ, dK, dV, dG

@@ -186,3 +186,98 @@ def test_noncausal_permutation_of_keys_changes_nothing():
     perm = rng.permutation(20)
     np.testing.assert_allclose(layer.noncausal_fwd(Q, K[:, :, perm], V[:, :, perm]), layer.noncausal_fwd(Q, K, V),
                                rtol=1e-11, atol=1e-11)
+
+
+# ------------------------------------------------------------------------------------------ Eq. 9 epilogue
+# Norm(O) * G with Norm the gain-free root-mean-square normalisation over a head's features.
+def test_gate_norm_hand_values():
+    # one row (3, 4): mean square 12.5, so Norm = (3, 4) / sqrt(12.5); gate (2, -1)
+    Y = layer.gate_norm_fwd([[3.0, 4.0]], [[2.0, -1.0]], 0.0)
+    np.testing.assert_allclose(Y, [[6.0 / 12.5 ** 0.5, -4.0 / 12.5 ** 0.5]], rtol=1e-15)
+    # a constant row c normalises to sign(c); eps enters under the root: row (1,1,1,1), eps = 3 -> 1/2
+    np.testing.assert_allclose(layer.gate_norm_fwd([[-5.0] * 7], [[1.0] * 7], 0.0), [[-1.0] * 7], rtol=1e-15)
+    np.testing.assert_allclose(layer.gate_norm_fwd([[1.0] * 4], [[1.0] * 4], 3.0), [[0.5] * 4], rtol=1e-15)
+
+
+def test_gate_norm_rows_have_unit_rms_and_ignore_scale():
+    rng = np.random.default_rng(5)
+    O = rng.standard_normal((2, 3, 5, 8))
+    ones = np.ones_like(O)
+    Y = layer.gate_norm_fwd(O, ones, 0.0)
+    for row in Y.reshape(-1, 8):
+        assert abs(sum(x * x for x in row) / 8 - 1.0) < 1e-12
+    # positive rescaling of a row changes nothing, rows do not talk to each other
+    scale = rng.uniform(0.1, 10.0, size=(2, 3, 5, 1))
+    np.testing.assert_allclose(layer.gate_norm_fwd(O * scale, ones, 0.0), Y, rtol=1e-12)
+    O2 = O.copy()
+    O2[1, 2, 3] += 1.0
+    Y2 = layer.gate_norm_fwd(O2, ones, 0.0)
+    changed = np.argwhere(np.abs(Y2 - Y).max(axis=-1) > 0)
+    assert changed.tolist() == [[1, 2, 3]]
+    # the gate multiplies feature by feature
+    G = rng.standard_normal(O.shape)
+    np.testing.assert_allclose(layer.gate_norm_fwd(O, G, 0.0), Y * G, rtol=1e-15)
+    with pytest.raises(ValueError):
+        layer.gate_norm_fwd(O, G[..., :4], 0.0)
+
+
+def test_gate_norm_gradient_finite_differences_and_invariants():
+    rng = np.random.default_rng(6)
+    O = rng.standard_normal((2, 2, 3, 6))
+    G = rng.standard_normal(O.shape)
+    dY = rng.standard_normal(O.shape)
+    eps = 0.05
+    dO, dG = layer.gate_norm_bwd(O, G, dY, eps)
+
+    def loss(o, g):
+        return float(np.sum(layer.gate_norm_fwd(o, g, eps) * dY))
+
+    h = 1e-6
+    for idx in [(0, 0, 0, 0), (1, 1, 2, 5), (0, 1, 1, 3), (1, 0, 2, 2)]:
+        E = np.zeros_like(O)
+        E[idx] = h
+        assert abs((loss(O + E, G) - loss(O - E, G)) / (2 * h) - dO[idx]) < 1e-8
+        assert abs((loss(O, G + E) - loss(O, G - E)) / (2 * h) - dG[idx]) < 1e-8
+    # without eps the map ignores the length of a row, so the gradient has no component along the row
+    dO0, dG0 = layer.gate_norm_bwd(O, G, dY, 0.0)
+    for o, d in zip(O.reshape(-1, 6), dO0.reshape(-1, 6)):
+        assert abs(float(np.dot(o, d))) < 1e-12
+    # the map is linear in the gate: <dG, G> is the loss itself
+    assert abs(float(np.sum(dG * G)) - loss(O, G)) < 1e-12
+
+
+def test_gated_attention_composes_and_differentiates():
+    rng = np.random.default_rng(7)
+    B, H, N, dk, dv = 1, 2, 5, 3, 4
+    Q, K = rng.standard_normal((2, B, H, N, dk))
+    V, G, dY = rng.standard_normal((3, B, H, N, dv))
+    eps = 1e-3
+    O, Y = layer.gated_fwd(Q, K, V, G, eps)
+    np.testing.assert_allclose(O, oracle.fwd_quadratic(Q, K, V), rtol=1e-12, atol=1e-12)
+    # first token: O_0 = (q_0 . k_0) v_0, so Y_0 = sign(q_0 . k_0) v_0 / sqrt(mean v_0^2 + eps / (q_0.k_0)^2) * g_0
+    for h_ in range(H):
+        a = float(np.dot(Q[0, h_, 0], K[0, h_, 0]))
+        v = V[0, h_, 0]
+        want = np.sign(a) * v / np.sqrt(np.mean(v * v) + eps / a ** 2) * G[0, h_, 0]
+        np.testing.assert_allclose(Y[0, h_, 0], want, rtol=1e-12)
+    dQ, dK, dV, dG = layer.gated_bwd(Q, K, V, G, dY, eps)
+
+    def loss(q, k, v, g):
+        return float(np.sum(layer.gated_fwd(q, k, v, g, eps)[1] * dY))
+
+    h = 1e-6
+    for name, X, dX in (("Q", Q, dQ), ("K", K, dK), ("V", V, dV), ("G", G, dG)):
+        for idx in [(0, 0, 0, 0), (0, 1, 4, 2), (0, 1, 2, 1)]:
+            E = np.zeros_like(X)
+            E[idx] = h
+            args_p = [Q, K, V, G]
+            args_m = [Q, K, V, G]
+            pos = "QKVG".index(name)
+            args_p[pos] = X + E
+            args_m[pos] = X - E
+            fd = (loss(*args_p) - loss(*args_m)) / (2 * h)
+            assert abs(fd - dX[idx]) < 1e-7, (name, idx, fd, dX[idx])
+    # causality survives the epilogue: the future does not move earlier outputs
+    Q2, K2, V2 = Q.copy(), K.copy(), V.copy()
+    Q2[:, :, 3:] += 1.0; K2[:, :, 3:] -= 2.0; V2[:, :, 3:] *= 3.0
+    np.testing.assert_array_equal(layer.gated_fwd(Q2, K2, V2, G, eps)[1][:, :, :3], Y[:, :, :3])
