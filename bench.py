@@ -168,7 +168,7 @@ def main():
     ap.add_argument("--workload", default="lm_bf16")
     ap.add_argument("--chunk", type=int, default=64)
     ap.add_argument("--mode", default="train", choices=["train", "train_saved", "train_state", "train_bnhd", "train_z", "train_z_saved", "noncausal", "decode",
-                             "conv", "conv_train"],
+                             "conv", "conv_train", "gated", "gated_unfused", "train_layer", "train_layer_unfused"],
                     help="train: fwd+bwd (the headline); train_saved: the same step through chela_linattn_fwd_save / "
                          "_bwd_saved (the forward leaves the boundary states, the backward skips its pass over K, V); "
                          "train_state: the same through the carried-state entry points "
@@ -191,7 +191,7 @@ def main():
 
     import torch
     from paper_2406_08128_amd import binding
-    from paper_2406_08128_amd.workloads import WORKLOADS, make_inputs, make_z_inputs, to_f64_numpy
+    from paper_2406_08128_amd.workloads import WORKLOADS, make_gate_inputs, make_inputs, make_z_inputs, to_f64_numpy
 
     w = WORKLOADS[args.workload]
     torch.cuda.set_device(0)
@@ -200,6 +200,10 @@ def main():
     if args.mode in ("conv", "conv_train"):
         return bench_conv(args, w, torch, binding)
     has_bwd = w.backward          # the headline workload runs forward + backward; forward-only workloads time the forward
+    if args.mode in ("gated", "gated_unfused"):
+        has_bwd = False           # Eq. 9 at inference
+    elif args.mode in ("train_layer", "train_layer_unfused"):
+        has_bwd = True
     es = 2 if w.dtype == "bf16" else 4
     x = make_inputs(w, with_dO=has_bwd)
     d = {k: v.cuda() for k, v in x.items()}
@@ -246,6 +250,37 @@ def main():
         else:
             def step():
                 binding.chela_linattn_noncausal_fwd(d["Q"], d["K"], d["V"], O=O)
+    elif args.mode in ("gated", "gated_unfused"):
+        # Eq. 9 at inference: Y = Norm(O) * G; fused into the forward, or as a second pass over a stored O
+        assert w.dtype == "bf16", "--mode gated needs a bf16 workload"
+        gate = make_gate_inputs(w)["G"].cuda()
+        Y = torch.empty_like(O)
+        if args.mode == "gated":
+            def step():
+                binding.chela_linattn_fwd_gated(d["Q"], d["K"], d["V"], gate, 1e-5, Y=Y)
+        else:
+            def step():
+                binding.chela_linattn_fwd(d["Q"], d["K"], d["V"], O=O, chunk=chunk)
+                binding.chela_gate_norm_fwd(O, gate, 1e-5, Y=Y)
+    elif args.mode in ("train_layer", "train_layer_unfused"):
+        # the layer's attention core in training: Z, V, G -> Y, then dY -> dZ, d_affine, dV, dG
+        assert w.dtype == "bf16", "--mode train_layer needs a bf16 workload"
+        dz = {k: v.cuda() for k, v in make_z_inputs(w, with_dO=False).items()}
+        gi = {k: v.cuda() for k, v in make_gate_inputs(w).items()}
+        Y, dOb, dG = torch.empty_like(O), torch.empty_like(O), torch.empty_like(O)
+        saved = torch.empty(max(binding.chela_linattn_saved_bytes(w.B, w.H, w.N, w.dk, w.dv, 64), 16) // 4,
+                            dtype=torch.float32, device="cuda")
+        if args.mode == "train_layer":
+            def step():
+                binding.chela_linattn_zfwd_gated(dz["Z"], dz["affine"], dz["V"], gi["G"], 1e-5, Y=Y, O=O, saved=saved)
+                binding.chela_gate_norm_bwd(O, gi["G"], gi["dY"], 1e-5, dO=dOb, dG=dG)
+                binding.chela_linattn_zbwd_saved(dz["Z"], dz["affine"], dz["V"], dOb, saved)
+        else:
+            def step():
+                binding.chela_linattn_zfwd_save(dz["Z"], dz["affine"], dz["V"], O=O, saved=saved)
+                binding.chela_gate_norm_fwd(O, gi["G"], 1e-5, Y=Y)
+                binding.chela_gate_norm_bwd(O, gi["G"], gi["dY"], 1e-5, dO=dOb, dG=dG)
+                binding.chela_linattn_zbwd_saved(dz["Z"], dz["affine"], dz["V"], dOb, saved)
     elif args.mode in ("train_z", "train_z_saved"):
         assert w.dtype == "bf16", "--mode train_z needs a bf16 workload"
         xz = make_z_inputs(w, with_dO=has_bwd)
@@ -307,12 +342,22 @@ def main():
     fwd_b, bwd_b = algorithmic_bytes_per_token_head(w.dk, w.dv, es)
     if args.mode in ("train_z", "train_z_saved"):     # Z replaces Q and K on the way in, dZ replaces dQ and dK on the way out
         fwd_b, bwd_b = es * (w.dk + 2 * w.dv), es * (w.dk + 2 * w.dv + w.dk + w.dv)
+    elif args.mode in ("gated", "gated_unfused"):     # the gate comes in as a fifth tensor; unfused: O out, O and G in, Y out
+        fwd_b = es * (2 * w.dk + 3 * w.dv) if args.mode == "gated" else es * (2 * w.dk + 5 * w.dv)
+    elif args.mode in ("train_layer", "train_layer_unfused"):
+        # forward Z,V,G -> Y,O; epilogue gradient O,G,dY -> dO,dG; backward Z,V,dO -> dZ,dV
+        fwd_b = es * (w.dk + 4 * w.dv) + (0 if args.mode == "train_layer" else es * 2 * w.dv)
+        bwd_b = es * (5 * w.dv) + es * (2 * w.dk + 3 * w.dv)
     fwd_f, bwd_f = flops_per_token_head(w.dk, w.dv, chunk)
     th = w.token_heads
     if args.mode == "noncausal":    # the apply kernel reads one tensor and writes one; forward: Q in, O out
         dom, dom_b = "bf16_apply_state_kernel", es * (w.dk + w.dv)
     elif w.dtype != "bf16":
         dom, dom_b = "f32_sweep_kernel", fwd_b
+    elif args.mode in ("train_layer", "train_layer_unfused"):
+        dom, dom_b = "bf16_bwd_sweep_kernel", es * (2 * w.dk + 3 * w.dv)
+    elif args.mode == "gated_unfused":
+        dom, dom_b = "bf16_fwd_sweep_kernel", es * (2 * w.dk + 2 * w.dv)
     elif has_bwd:
         dom, dom_b = "bf16_bwd_sweep_kernel", bwd_b
     else:
@@ -343,6 +388,21 @@ def main():
             if has_bwd:
                 oracle_layer.noncausal_bwd(Qn, Kn, Vn, Gn)
             c1 = time.perf_counter()
+        elif args.mode in ("gated", "gated_unfused"):
+            from oracle import layer as oracle_layer
+            Qn, Kn, Vn, Gg = (to_f64_numpy(t) for t in (x["Q"], x["K"], x["V"], gate))
+            c0 = time.perf_counter()
+            oracle_layer.gated_fwd(Qn, Kn, Vn, Gg, 1e-5)
+            c1 = time.perf_counter()
+        elif args.mode in ("train_layer", "train_layer_unfused"):
+            from oracle import layer as oracle_layer
+            Zn, An, Vn, Gg, dYn = (to_f64_numpy(t) for t in (dz["Z"], dz["affine"], dz["V"], gi["G"], gi["dY"]))
+            c0 = time.perf_counter()
+            Qn, Kn = oracle_layer.qk_from_z(Zn, An)
+            On, _ = oracle_layer.gated_fwd(Qn, Kn, Vn, Gg, 1e-5)
+            dOn, _ = oracle_layer.gate_norm_bwd(On, Gg, dYn, 1e-5)
+            oracle_layer.zqk_bwd(Zn, An, Vn, dOn)
+            c1 = time.perf_counter()
         elif args.mode in ("train_z", "train_z_saved"):
             from oracle import layer as oracle_layer
             Zn, An, Vn = (to_f64_numpy(xz[n]) for n in ("Z", "affine", "V"))
@@ -372,7 +432,11 @@ def main():
                   + (" (forward saves the boundary states)" if args.mode == "train_saved" else "")
                   + (" ([B,N,H,d] tensors)" if args.mode == "train_bnhd" else "")
                   + (" (Q, K formed on chip from Z)" if args.mode == "train_z" else "")
-                  + (" (Q, K formed on chip from Z; forward saves the boundary states)" if args.mode == "train_z_saved" else ""),
+                  + (" (Q, K formed on chip from Z; forward saves the boundary states)" if args.mode == "train_z_saved" else "")
+                  + (" (Y = Norm(O) * G inside the forward)" if args.mode == "gated" else "")
+                  + (" (Y = Norm(O) * G as a second pass)" if args.mode == "gated_unfused" else "")
+                  + (" (layer core: Z, V, G -> Y and all gradients, prologue and epilogue fused)" if args.mode == "train_layer" else "")
+                  + (" (layer core: Z, V, G -> Y and all gradients, epilogue as a separate pass)" if args.mode == "train_layer_unfused" else ""),
         "value": round(tokens_per_s, 1),
         "unit": "tokens/s",
         "n_gpus": 1,

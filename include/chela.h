@@ -176,6 +176,33 @@ int chela_linattn_noncausal_bwd(const void *Q, const void *K, const void *V, con
                                 int B, int H, int N, int dk, int dv, void *stream);
 size_t chela_linattn_noncausal_workspace_bytes(int B, int H, int N, int dk, int dv, int is_bwd);
 
+/* ---- gated, normalised output (Sec. 4.3, Eq. 9: M = Norm(Q (K^T V)) * G_a) ---------------------------------------
+ * The paper attributes Norm to the TransNormer line of work (Sec. 2.1) and does not write it out; this library takes
+ * the root-mean-square normalisation without learnable gain, per token and per head over that head's dv features:
+ *        Norm(o) = o / sqrt(mean_j o_j^2 + eps),      Y = Norm(O) * G            (eps >= 0, a finite constant;
+ * with eps = 0 an all-zero row of O gives NaN, as the formula does).  The gate G ([B,H,N,dv] bf16) is an input: the
+ * projection and activation that produce it (Eq. 10) are dense layers outside this library.
+ *   chela_linattn_fwd_gated : O as chela_linattn_fwd computes it, then Y, in one pass: the sum of squares is taken
+ *       from the fp32 accumulators, so Y is rounded once.  Y [B,H,N,dv] bf16 out.  O: bf16 out or NULL (a backward
+ *       pass needs O, inference does not: with NULL the call moves the same five tensors as the plain forward plus
+ *       the gate).  saved: NULL, or the buffer of the training pair below (chela_linattn_saved_bytes(..., 64)
+ *       bytes), filled for chela_linattn_bwd_saved / _zbwd_saved.
+ *   chela_linattn_zfwd_gated: the same with the Eq. 11-12 prologue (Z, affine as for chela_linattn_zfwd).
+ *   chela_gate_norm_fwd     : the epilogue alone on `rows` rows of dv features (any [..., dv] tensor, contiguous),
+ *       e.g. behind the non-causal call.  rows >= 0; dv in {64, 128}.
+ *   chela_gate_norm_bwd     : its gradient,  dG = dY * Norm(O),  dO = r (u - n mean_j(u_j n_j))  with
+ *       r = 1 / sqrt(mean_j o_j^2 + eps), n = r o, u = dY * G.  dO is what the attention backward calls take as their
+ *       dO.  dO may be the same buffer as dY (exactly the same pointer); no other overlap is allowed.
+ * 64-token chunks (`chunk` validated and otherwise ignored); scratch as for chela_linattn_fwd / _zfwd; a negative or
+ * non-finite eps gives CHELA_ERR_BAD_SHAPE.  Everything else as for the calls above. */
+int chela_linattn_fwd_gated(const void *Q, const void *K, const void *V, const void *G, void *O, void *Y, void *saved,
+                            float eps, int B, int H, int N, int dk, int dv, int chunk, void *stream);
+int chela_linattn_zfwd_gated(const void *Z, const float *affine, const void *V, const void *G, void *O, void *Y,
+                             void *saved, float eps, int B, int H, int N, int dk, int dv, int chunk, void *stream);
+int chela_gate_norm_fwd(const void *O, const void *G, void *Y, float eps, long long rows, int dv, void *stream);
+int chela_gate_norm_bwd(const void *O, const void *G, const void *dY, void *dO, void *dG, float eps, long long rows,
+                        int dv, void *stream);
+
 /* ---- short-long convolutions (Sec. 4.2, Eq. 8): Z = K_l( silu( K_s(X) ) ), the other half of the token mixer -----
  * Depthwise (one kernel per channel) and causal with zero history:
  *     v[b,c,t] = silu( sum_{j<m, j<=t} w_short[c,j] * X[b,c,t-j] ),   Z[b,c,t] = sum_{s<=t} k_long[c,s] * v[b,c,t-s].

@@ -67,6 +67,15 @@ def lib() -> ctypes.CDLL:
     L.chela_linattn_bwd_saved.restype = i
     L.chela_linattn_saved_bytes.argtypes = [i, i, i, i, i, i]
     L.chela_linattn_saved_bytes.restype = sz
+    f32 = ctypes.c_float
+    L.chela_linattn_fwd_gated.argtypes = [vp] * 7 + [f32, i, i, i, i, i, i, vp]
+    L.chela_linattn_fwd_gated.restype = i
+    L.chela_linattn_zfwd_gated.argtypes = [vp] * 7 + [f32, i, i, i, i, i, i, vp]
+    L.chela_linattn_zfwd_gated.restype = i
+    L.chela_gate_norm_fwd.argtypes = [vp, vp, vp, f32, ctypes.c_longlong, i, vp]
+    L.chela_gate_norm_fwd.restype = i
+    L.chela_gate_norm_bwd.argtypes = [vp] * 5 + [f32, ctypes.c_longlong, i, vp]
+    L.chela_gate_norm_bwd.restype = i
     L.chela_linattn_noncausal_fwd.argtypes = [vp, vp, vp, vp, i, i, i, i, i, vp]
     L.chela_linattn_noncausal_fwd.restype = i
     L.chela_linattn_noncausal_bwd.argtypes = [vp] * 7 + [i, i, i, i, i, vp]
@@ -390,6 +399,98 @@ def chela_linattn_zbwd_saved(Z, affine, V, dO, saved, stream=None):
                                               saved.data_ptr(), dZ.data_ptr(), d_aff.data_ptr(), dV.data_ptr(), B, H,
                                               N, dk, dv, 64, _stream_ptr(stream)))
     return dZ, d_aff, dV
+
+
+def _gated_outputs(V, G, want_O, want_saved, dk, Y, O, saved):
+    if G.shape != V.shape or G.dtype != V.dtype or not G.is_cuda or not G.is_contiguous():
+        raise ValueError("G must be a contiguous device tensor shaped like V")
+    for t in (Y, O):
+        if t is not None and (t.shape != V.shape or t.dtype != V.dtype or not t.is_cuda or not t.is_contiguous()):
+            raise ValueError("Y and O must be contiguous device tensors shaped like V")
+    B, H, N, dv = V.shape
+    if Y is None:
+        Y = torch.empty_like(V)
+    if O is None and want_O:
+        O = torch.empty_like(V)
+    if saved is not None or want_saved:
+        need = chela_linattn_saved_bytes(B, H, N, dk, dv, 64)
+        if saved is None:
+            saved = torch.empty(max(need, 16) // 4, dtype=torch.float32, device=V.device)
+        elif saved.numel() * saved.element_size() < need or not saved.is_contiguous():
+            raise ValueError("saved must be a contiguous device buffer of at least %d bytes" % need)
+    return Y, O, saved
+
+
+def _ptr(t):
+    return t.data_ptr() if t is not None else None
+
+
+def chela_linattn_fwd_gated(Q, K, V, G, eps, want_O=False, want_saved=False, Y=None, O=None, saved=None, stream=None):
+    """(Y, O, saved) with Y = Norm(O) * G (Eq. 9) formed inside the forward.  O and saved are produced when asked for
+    (want_*) or when a buffer for them is passed; otherwise they come back as None."""
+    B, H, N, dk, dv = _dims(Q, K, V)
+    _bf16_only(Q, "the gated forward")
+    Y, O, saved = _gated_outputs(V, G, want_O, want_saved, dk, Y, O, saved)
+    with torch.cuda.device(Q.device):
+        _check(lib().chela_linattn_fwd_gated(Q.data_ptr(), K.data_ptr(), V.data_ptr(), G.data_ptr(), _ptr(O),
+                                             Y.data_ptr(), _ptr(saved), float(eps), B, H, N, dk, dv, 64,
+                                             _stream_ptr(stream)))
+    return Y, O, saved
+
+
+def chela_linattn_zfwd_gated(Z, affine, V, G, eps, want_O=False, want_saved=False, Y=None, O=None, saved=None,
+                             stream=None):
+    """chela_linattn_fwd_gated with Q and K formed from Z (Eq. 11-12)."""
+    B, H, N, dk, dv = _zdims(Z, affine, V)
+    Y, O, saved = _gated_outputs(V, G, want_O, want_saved, dk, Y, O, saved)
+    with torch.cuda.device(Z.device):
+        _check(lib().chela_linattn_zfwd_gated(Z.data_ptr(), affine.data_ptr(), V.data_ptr(), G.data_ptr(), _ptr(O),
+                                              Y.data_ptr(), _ptr(saved), float(eps), B, H, N, dk, dv, 64,
+                                              _stream_ptr(stream)))
+    return Y, O, saved
+
+
+def _gate_rows(O, G):
+    if O.dim() < 1 or G.shape != O.shape:
+        raise ValueError("O and G must have the same shape [..., dv]")
+    for t in (O, G):
+        if t.dtype != torch.bfloat16 or not t.is_cuda or not t.is_contiguous():
+            raise ValueError("tensors must be contiguous bf16 device tensors")
+    dv = O.shape[-1]
+    return (O.numel() // dv if dv else 0), dv
+
+
+def chela_gate_norm_fwd(O, G, eps, Y=None, stream=None):
+    """Y = Norm(O) * G over the last dimension (Eq. 9 without the attention)."""
+    rows, dv = _gate_rows(O, G)
+    if Y is None:
+        Y = torch.empty_like(O)
+    elif Y.shape != O.shape or Y.dtype != O.dtype or not Y.is_cuda or not Y.is_contiguous():
+        raise ValueError("Y must match O")
+    with torch.cuda.device(O.device):
+        _check(lib().chela_gate_norm_fwd(O.data_ptr(), G.data_ptr(), Y.data_ptr(), float(eps), rows, dv,
+                                         _stream_ptr(stream)))
+    return Y
+
+
+def chela_gate_norm_bwd(O, G, dY, eps, in_place=False, dO=None, dG=None, stream=None):
+    """(dO, dG) of chela_gate_norm_fwd; in_place=True writes dO over dY."""
+    rows, dv = _gate_rows(O, G)
+    if dY.shape != O.shape or dY.dtype != O.dtype or not dY.is_cuda or not dY.is_contiguous():
+        raise ValueError("dY must match O")
+    if in_place:
+        dO = dY
+    elif dO is None:
+        dO = torch.empty_like(O)
+    if dG is None:
+        dG = torch.empty_like(O)
+    for t in (dO, dG):
+        if t.shape != O.shape or t.dtype != O.dtype or not t.is_cuda or not t.is_contiguous():
+            raise ValueError("dO and dG must match O")
+    with torch.cuda.device(O.device):
+        _check(lib().chela_gate_norm_bwd(O.data_ptr(), G.data_ptr(), dY.data_ptr(), dO.data_ptr(), dG.data_ptr(),
+                                         float(eps), rows, dv, _stream_ptr(stream)))
+    return dO, dG
 
 
 def chela_linattn_z_workspace_bytes(B, H, N, dk, dv, chunk, is_bwd) -> int:

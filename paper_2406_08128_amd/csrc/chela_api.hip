@@ -2,6 +2,7 @@
 // Every check below runs before the first HIP call so that a rejected call has touched nothing.
 #include "../../include/chela.h"
 #include "chela_internal.h"
+#include <cmath>
 
 #include <cstdlib>
 #include <mutex>
@@ -148,7 +149,7 @@ static const char* const kKernelNames[KID_COUNT] = {
     "bf16_seg_state_kernel", "scan_states_kernel", "bf16_fwd_sweep_kernel", "bf16_bwd_sweep_kernel",
     "f32_seg_state_kernel", "f32_sweep_kernel", "copy_probe_kernel", "bf16_step_kernel", "affine_grad_kernel",
     "bf16_apply_state_kernel", "longconv_spectrum_kernel", "shortlong_conv_kernel",
-    "shortconv_bwd_kernel", "longconv_dk_kernel"};
+    "shortconv_bwd_kernel", "longconv_dk_kernel", "gate_norm_kernel"};
 
 ProfScope::ProfScope(int id, hipStream_t s) : slot(-1), st(s)
 {
@@ -449,6 +450,61 @@ static int bwd_saved_common(const void* Q, const void* K, const void* V, const v
                            t.bwd, ws, (hipStream_t)stream) == hipSuccess ? CHELA_OK : CHELA_ERR_HIP;
 }
 
+// Forward with the Eq. 9 epilogue; aff non-null: Z in place of Q and K.  O and saved are optional outputs.
+static int fwd_gated_common(const void* Q, const void* K, const float* aff, bool zqk, const void* V, const void* G,
+                            void* O, void* Y, void* saved, float eps, int B, int H, int N, int dk, int dv, int chunk,
+                            void* stream)
+{
+    if (!(eps >= 0.f) || !std::isfinite(eps)) return CHELA_ERR_BAD_SHAPE;
+    const size_t th = (B > 0 && H > 0 && N > 0) ? (size_t)B * H * N : 0;
+    const size_t ab = (zqk && th) ? (size_t)4 * H * dk * sizeof(float) : 0;
+    const long BH = (long)B * H;
+    const bool dims_ok = (dk == 64 || dk == 128) && (dv == 64 || dv == 128);
+    TrainPlans t{};
+    if (saved && th && dims_ok) t = make_train_plans(BH, N, dk, dv, 64);
+    // optional pointers stand in as copies of required ones so that the null / alignment / overlap checks skip them
+    const void* in_v[4] = {Q, zqk ? (const void*)aff : K, V, G};
+    const size_t inb[4] = {th * dk * 2, zqk ? ab : th * dk * 2, th * dv * 2, th * dv * 2};
+    void* out_v[3] = {Y, O ? O : Y, saved ? saved : Y};
+    const size_t outb[3] = {th * dv * 2, O ? th * dv * 2 : 0, (saved && th && dims_ok) ? saved_bytes(BH, t) : 0};
+    bool empty = false;
+    int rc = validate(in_v, inb, 4, out_v, outb, 3, B, H, N, dk, dv, chunk, CHELA_DTYPE_BF16, &empty);
+    if (rc != CHELA_OK || empty) return rc;
+    Plan plan = saved ? t.fwd : make_plan(BH, N, dk, dv, 64, CHELA_DTYPE_BF16, false, false);
+    float* ws = nullptr;
+    rc = get_workspace(plan.ws_bytes, &ws);
+    if (rc != CHELA_OK) return rc;
+    return launch_bf16_fwd_gated(Q, K, V, G, O, Y, eps, zqk ? aff : nullptr, (float*)saved, saved ? t.save_every : 1, B,
+                                 H, N, dk, dv, plan, ws, (hipStream_t)stream) == hipSuccess ? CHELA_OK : CHELA_ERR_HIP;
+}
+
+static int gate_norm_common(const void* O, const void* G, const void* dY, void* out0, void* out1, bool bwd, float eps,
+                            long long rows, int dv, void* stream)
+{
+    if (!(eps >= 0.f) || !std::isfinite(eps)) return CHELA_ERR_BAD_SHAPE;
+    if (rows < 0 || rows > (1ll << 37)) return CHELA_ERR_BAD_SHAPE;   // keeps the grid below 2^31 workgroups
+    if (!(dv == 64 || dv == 128)) return CHELA_ERR_UNSUPPORTED_DIM;
+    if (rows == 0) return CHELA_OK;
+    const size_t nb = (size_t)rows * dv * 2;
+    const void* in_v[3] = {O, G, bwd ? dY : O};
+    void* out_v[2] = {out0, bwd ? out1 : out0};
+    for (int i = 0; i < 3; ++i) if (!in_v[i]) return CHELA_ERR_NULL_POINTER;
+    for (int i = 0; i < 2; ++i) if (!out_v[i]) return CHELA_ERR_NULL_POINTER;
+    for (int i = 0; i < 3; ++i) if ((uintptr_t)in_v[i] & 15u) return CHELA_ERR_MISALIGNED;
+    for (int i = 0; i < 2; ++i) if ((uintptr_t)out_v[i] & 15u) return CHELA_ERR_MISALIGNED;
+    const int n_out = bwd ? 2 : 1;
+    for (int o = 0; o < n_out; ++o) {
+        const Range ro{(const char*)out_v[o], nb};
+        for (int i = 0; i < (bwd ? 3 : 2); ++i) {
+            if (bwd && o == 0 && i == 2 && out_v[0] == dY) continue;   // dO written over dY, element for element
+            if (overlap(ro, Range{(const char*)in_v[i], nb})) return CHELA_ERR_ALIASING;
+        }
+    }
+    if (bwd && overlap(Range{(const char*)out0, nb}, Range{(const char*)out1, nb})) return CHELA_ERR_ALIASING;
+    return launch_gate_norm(O, G, bwd ? dY : nullptr, out0, bwd ? out1 : nullptr, eps, (long)rows, dv,
+                            (hipStream_t)stream) == hipSuccess ? CHELA_OK : CHELA_ERR_HIP;
+}
+
 // [B,N,H,d] tensors: same extents and aliasing rules as the [B,H,N,d] calls, 64-token chunks.
 static int bnhd_common(const void* Q, const void* K, const void* V, const void* dO, void* O_or_dQ, void* dK, void* dV,
                        bool is_bwd, int B, int H, int N, int dk, int dv, int chunk, void* stream)
@@ -580,6 +636,29 @@ int chela_linattn_bwd_saved(const void* Q, const void* K, const void* V, const v
                             void* dK, void* dV, int B, int H, int N, int dk, int dv, int chunk, void* stream)
 {
     return bwd_saved_common(Q, K, V, dO, saved, dQ, dK, dV, B, H, N, dk, dv, chunk, stream);
+}
+
+int chela_linattn_fwd_gated(const void* Q, const void* K, const void* V, const void* G, void* O, void* Y, void* saved,
+                            float eps, int B, int H, int N, int dk, int dv, int chunk, void* stream)
+{
+    return fwd_gated_common(Q, K, nullptr, false, V, G, O, Y, saved, eps, B, H, N, dk, dv, chunk, stream);
+}
+
+int chela_linattn_zfwd_gated(const void* Z, const float* affine, const void* V, const void* G, void* O, void* Y,
+                             void* saved, float eps, int B, int H, int N, int dk, int dv, int chunk, void* stream)
+{
+    return fwd_gated_common(Z, nullptr, affine, true, V, G, O, Y, saved, eps, B, H, N, dk, dv, chunk, stream);
+}
+
+int chela_gate_norm_fwd(const void* O, const void* G, void* Y, float eps, long long rows, int dv, void* stream)
+{
+    return gate_norm_common(O, G, nullptr, Y, nullptr, false, eps, rows, dv, stream);
+}
+
+int chela_gate_norm_bwd(const void* O, const void* G, const void* dY, void* dO, void* dG, float eps, long long rows,
+                        int dv, void* stream)
+{
+    return gate_norm_common(O, G, dY, dO, dG, true, eps, rows, dv, stream);
 }
 
 size_t chela_linattn_saved_bytes(int B, int H, int N, int dk, int dv, int chunk)

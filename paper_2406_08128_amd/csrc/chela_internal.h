@@ -64,6 +64,15 @@ hipError_t launch_bf16_zfwd(const void* Z, const float* aff, const void* V, void
 hipError_t launch_bf16_zbwd(const void* Z, const float* aff, const void* V, const void* dO, void* dZ, float* d_aff,
                             void* dV, const float* saved, int B, int H, int N, int dk, int dv, const Plan& plan,
                             float* ws, hipStream_t st);
+// Eq. 9 epilogue Y = Norm(O) * G (Norm: x / sqrt(mean x^2 + eps) over a head's dv features).
+// launch_bf16_fwd_gated: the causal forward with the epilogue fused; O optional, aff optional (Eq. 11-12 prologue),
+// saved as for launch_bf16_fwd.  launch_gate_norm: the epilogue alone on [rows][dv]; dY null: out0 = Y; dY given:
+// out0 = dO, out1 = dG.
+hipError_t launch_bf16_fwd_gated(const void* Q, const void* K, const void* V, const void* G, void* O, void* Y, float eps,
+                                 const float* aff, float* saved, int save_every, int B, int H, int N, int dk, int dv,
+                                 const Plan& plan, float* ws, hipStream_t st);
+hipError_t launch_gate_norm(const void* O, const void* G, const void* dY, void* out0, void* out1, float eps, long rows,
+                            int dv, hipStream_t st);
 inline size_t zbwd_extra_ws_bytes(long BH, const Plan& plan, int dk)
 {
     return (size_t)BH * plan.n_seg * 4 * dk * sizeof(float);
@@ -93,7 +102,7 @@ hipError_t launch_shortlong_conv_bwd(const void* X, const float* w_short, int m,
 
 // Kernel classes for the per-kernel timing aid.
 enum { KID_SEG_STATE_BF16 = 0, KID_SCAN = 1, KID_FWD_SWEEP_BF16 = 2, KID_BWD_SWEEP_BF16 = 3, KID_SEG_STATE_F32 = 4,
-       KID_SWEEP_F32 = 5, KID_COPY = 6, KID_STEP_BF16 = 7, KID_AFFINE_GRAD = 8, KID_APPLY_BF16 = 9, KID_CONV_SPECTRUM = 10, KID_CONV_FWD = 11, KID_CONV_SHORT_BWD = 12, KID_CONV_DK = 13, KID_COUNT = 14 };
+       KID_SWEEP_F32 = 5, KID_COPY = 6, KID_STEP_BF16 = 7, KID_AFFINE_GRAD = 8, KID_APPLY_BF16 = 9, KID_CONV_SPECTRUM = 10, KID_CONV_FWD = 11, KID_CONV_SHORT_BWD = 12, KID_CONV_DK = 13, KID_GATE_NORM = 14, KID_COUNT = 15 };
 
 // Brackets one kernel launch with HIP events on its stream while profiling is enabled; otherwise does nothing.
 struct ProfScope {

@@ -234,6 +234,29 @@ __device__ __forceinline__ void store_tile_T(bf16* rows, int ld, int col0, const
     }
 }
 
+// Eq. 9 epilogue on a transposed accumulator tile: every value times `scale` (the token's 1/rms) times its gate.
+// g[ap] holds the gate as store_tile_T would have stored it (8 consecutive features of this lane's token at
+// col0 + 8h + 16ap); the same half-wave exchange that produces that order also undoes it.
+__device__ __forceinline__ f32x16 gate_tile(const f32x16& acc, const uint4 (&g)[2], float scale)
+{
+    f32x16 out;
+#pragma unroll
+    for (int ap = 0; ap < 2; ++ap) {
+        const u32x2 s0 = __builtin_amdgcn_permlane32_swap(g[ap].x, g[ap].z, false, false);
+        const u32x2 s1 = __builtin_amdgcn_permlane32_swap(g[ap].y, g[ap].w, false, false);
+        const unsigned x0 = s0[0], y0 = s0[1], x1 = s1[0], y1 = s1[1];
+        out[8 * ap + 0] = acc[8 * ap + 0] * scale * bf16_lo(x0);
+        out[8 * ap + 1] = acc[8 * ap + 1] * scale * bf16_hi(x0);
+        out[8 * ap + 2] = acc[8 * ap + 2] * scale * bf16_lo(x1);
+        out[8 * ap + 3] = acc[8 * ap + 3] * scale * bf16_hi(x1);
+        out[8 * ap + 4] = acc[8 * ap + 4] * scale * bf16_lo(y0);
+        out[8 * ap + 5] = acc[8 * ap + 5] * scale * bf16_hi(y0);
+        out[8 * ap + 6] = acc[8 * ap + 6] * scale * bf16_lo(y1);
+        out[8 * ap + 7] = acc[8 * ap + 7] * scale * bf16_hi(y1);
+    }
+    return out;
+}
+
 // =============================================================================================== shared pieces
 // Load a [DA][DB] fp32 state as accumulator tiles: tile id = w + 4n -> (ab, bb) = (id / BB, id % BB).
 template <int DA, int DB, bool NEG>
@@ -421,20 +444,26 @@ __device__ __forceinline__ void prepass_body(const bf16* __restrict__ X, const b
 // tiles of its row block itself (matrix-core time is cheap here, LDS round trips and barriers are not).
 // ZQK: Qb points at Z, Kb is unused, and `aff` at this head's alpha_q row of the [4][H][DK] parameter array
 // (rows alpha_q, beta_q, alpha_k, beta_k, `aff_stride` floats apart): Q and K tiles are formed on the way into LDS.
-template <int C, int DK, int DV, bool ZQK = false>
+template <int C, int DK, int DV, bool ZQK = false, bool GATE = false>
 struct FwdLds {
     static constexpr int LDK = DK + PAD, LDV = DV + PAD;
     static constexpr int TILES = (2 * C * LDK + C * LDV + DV * LDK) * 2;
-    static constexpr int BYTES = TILES + (ZQK ? 4 * DK * 4 : 0);
+    static constexpr int BYTES = TILES + (ZQK ? 4 * DK * 4 : 0) + (GATE ? 4 * C * 4 : 0);
 };
 
-template <int C, int DK, int DV, bool ZQK, bool SAVE>
+// GATE (Eq. 9, Y = Norm(O) * G with Norm(o) = o / sqrt(mean_j o_j^2 + eps) over the head's DV features): Gb and Yb
+// point at the gate and at the output rows of this segment; Ob may then be null (O itself is only needed by a
+// backward pass).  A token's features are spread over two half-waves and WJ waves: each wave leaves its share of
+// the sum of squares in LDS, and the gated store happens after the barrier that ends the chunk anyway -- it needs
+// nothing but registers by then -- so the epilogue costs no barrier of its own.
+template <int C, int DK, int DV, bool ZQK, bool SAVE, bool GATE = false>
 __device__ __forceinline__ void fwd_sweep_body(const bf16* __restrict__ Qb, const bf16* __restrict__ Kb,
                                                const bf16* __restrict__ Vb, bf16* __restrict__ Ob,
                                                const float* __restrict__ S0, float* __restrict__ S_final,
                                                float* __restrict__ S_final_T, const float* __restrict__ aff,
                                                size_t aff_stride, int ldk, int ldv, int ntok, unsigned char* lds,
-                                               int tid, int w, int lane)
+                                               int tid, int w, int lane, const bf16* __restrict__ Gb = nullptr,
+                                               bf16* __restrict__ Yb = nullptr, float eps = 0.f)
 {
     constexpr int LDK = DK + PAD, LDV = DV + PAD;
     constexpr int TB = C / 32, JB = DV / 32, IB = DK / 32;
@@ -456,6 +485,7 @@ __device__ __forceinline__ void fwd_sweep_body(const bf16* __restrict__ Qb, cons
     if (!ZQK) rk.load(Kb, ldk, ntok, tid);
     rv.load(Vb, ldv, ntok, tid);
     float* sAff = reinterpret_cast<float*>(lds + FwdLds<C, DK, DV, false>::TILES);
+    float* sSq = sAff + (ZQK ? 4 * DK : 0);   // GATE: [WJ][C] partial sums of squares
     if (ZQK) {
         for (int x = tid; x < 4 * DK; x += 256) sAff[x] = aff[(size_t)(x / DK) * aff_stride + x % DK];
         __syncthreads();
@@ -480,6 +510,17 @@ __device__ __forceinline__ void fwd_sweep_body(const bf16* __restrict__ Qb, cons
             rq.load(Qb + (size_t)(c0 + C) * ldk, ldk, ntok - c0 - C, tid);
             if (!ZQK) rk.load(Kb + (size_t)(c0 + C) * ldk, ldk, ntok - c0 - C, tid);
             rv.load(Vb + (size_t)(c0 + C) * ldv, ldv, ntok - c0 - C, tid);
+        }
+        uint4 gate[GATE ? NJ : 1][2];   // this chunk's gate, in the order the output tile is stored in
+        if (GATE) {
+            // rows past the end of the sequence read the last row instead (their results are never stored)
+            const int row = min(c0 + tb * 32 + (lane & 31), ntok - 1);
+            const bf16* g = Gb + (size_t)row * ldv + 8 * (lane >> 5);
+#pragma unroll
+            for (int n = 0; n < NJ; ++n)
+#pragma unroll
+                for (int ap = 0; ap < 2; ++ap)
+                    gate[n][ap] = *reinterpret_cast<const uint4*>(g + (jg * NJ + n) * 32 + 16 * ap);
         }
         bf16x8 bQ[DK / 16];   // Q rows of this wave's token block: the B operand (n = token, k = feature i)
 #pragma unroll
@@ -510,11 +551,23 @@ __device__ __forceinline__ void fwd_sweep_body(const bf16* __restrict__ Qb, cons
                 }
             }
         }
-        {
+        const int valid = ntok - (c0 + tb * 32);
+        if (!GATE || Ob != nullptr) {
             bf16* rows = Ob + (size_t)(c0 + tb * 32) * ldv;
-            const int valid = ntok - (c0 + tb * 32);
 #pragma unroll
             for (int n = 0; n < NJ; ++n) store_tile_T(rows, ldv, (jg * NJ + n) * 32, accO[n], valid, lane);
+        }
+        if (GATE) {
+            // this wave's share of sum_j O[t][j]^2: 16 features per tile and lane, the other 16 in lane ^ 32
+            float ss = 0.f;
+#pragma unroll
+            for (int n = 0; n < NJ; ++n)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) ss = fmaf(accO[n][e], accO[n][e], ss);
+            const unsigned sb = __builtin_bit_cast(unsigned, ss);
+            const u32x2 sw = __builtin_amdgcn_permlane32_swap(sb, sb, false, false);
+            const unsigned sw0 = sw[0], sw1 = sw[1];
+            if (lane < 32) sSq[jg * C + tb * 32 + lane] = __builtin_bit_cast(float, sw0) + __builtin_bit_cast(float, sw1);
         }
         // state update S += K^T V (after the segment's last chunk only if the final state is asked for)
         if (more || S_final != nullptr || (SAVE && S_final_T != nullptr)) {
@@ -527,6 +580,17 @@ __device__ __forceinline__ void fwd_sweep_body(const bf16* __restrict__ Qb, cons
             }
         }
         __syncthreads();
+        if (GATE) {
+            // (the next chunk writes sSq only after its own first barrier, which every wave reaches after this read)
+            float tot = 0.f;
+#pragma unroll
+            for (int g = 0; g < WJ; ++g) tot += sSq[g * C + tb * 32 + (lane & 31)];
+            const float rinv = __builtin_amdgcn_rsqf(fmaf(tot, 1.f / DV, eps));
+            bf16* rows = Yb + (size_t)(c0 + tb * 32) * ldv;
+#pragma unroll
+            for (int n = 0; n < NJ; ++n)
+                store_tile_T(rows, ldv, (jg * NJ + n) * 32, gate_tile(accO[n], gate[n], rinv), valid, lane);
+        }
     }
     if (S_final != nullptr) store_state<DK, DV>(S_final, accS, w, lane);
     if (SAVE && S_final_T != nullptr) store_state_T<DK, DV>(S_final_T, accS, w, lane);   // [dv][dk], as the backward reads it
@@ -955,6 +1019,33 @@ void bf16_fwd_sweep_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ 
                                    NH ? H * DK : DK, NH ? H * DV : DV, p1 - p0, lds, tid, w, lane);
 }
 
+// The forward sweep with the Eq. 9 epilogue: Y = Norm(O) * G; O is written too when it is given.
+template <int C, int DK, int DV, bool ZQK, bool SAVE>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((C == 64 && DK == 64 && DV == 64) ? 3 : 1)))
+void bf16_fwd_gated_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, const bf16* __restrict__ V,
+                           const bf16* __restrict__ G, bf16* __restrict__ O, bf16* __restrict__ Y, float eps,
+                           const float* __restrict__ S0, const float* __restrict__ aff, int H,
+                           float* __restrict__ saved, int save_every, int N, int seg_len, int n_seg)
+{
+    __shared__ __attribute__((aligned(16))) unsigned char lds[FwdLds<C, DK, DV, ZQK, true>::BYTES];
+    const int seg = blockIdx.y;
+    const long bh = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int p0 = seg * seg_len, p1 = min(N, p0 + seg_len);
+    const size_t rk = ((size_t)bh * N + p0) * DK, rv = ((size_t)bh * N + p0) * DV;
+    float* save_to = nullptr;
+    if (SAVE && saved != nullptr && ((seg + 1) % save_every == 0 || seg == n_seg - 1)) {
+        const int n_slots = (n_seg + save_every - 1) / save_every, slot = (seg + save_every) / save_every - 1;
+        save_to = saved + ((size_t)bh * n_slots + slot) * DK * DV;
+    }
+    fwd_sweep_body<C, DK, DV, ZQK, SAVE, true>(Q + rk, ZQK ? nullptr : K + rk, V + rv, O ? O + rv : nullptr,
+                                               (S0 != nullptr && seg > 0) ? S0 + ((size_t)bh * n_seg + seg) * DK * DV
+                                                                          : nullptr,
+                                               nullptr, save_to, ZQK ? aff + (size_t)(bh % H) * DK : nullptr,
+                                               (size_t)H * DK, DK, DV, p1 - p0, lds, tid, w, lane, G + rv, Y + rv, eps);
+}
+
 template <int C, int DK, int DV, bool ZQK, bool NH>
 __global__ __launch_bounds__(256) void bf16_bwd_sweep_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K,
                                                             const bf16* __restrict__ V, const bf16* __restrict__ dO,
@@ -1005,6 +1096,102 @@ __global__ __launch_bounds__(256) void affine_grad_kernel(const float* __restric
         for (int v = 1; v < SL; ++v) t += red[v][i];
         out[((size_t)q * H + hd) * DK + i] = t;
     }
+}
+
+// =============================================================================================== Eq. 9 epilogue alone
+// Y = Norm(O) * G and its gradient on [rows][DV] matrices, Norm(o) = o / sqrt(mean_j o_j^2 + eps): for outputs that
+// did not come from the fused forward (the non-causal form) and for every backward pass.  A lane owns 8 consecutive
+// features of a row (one 16-byte access per tensor), DV / 8 neighbouring lanes share a row and add up their shares
+// with butterfly exchanges; RPT rows per thread are in flight at once.  Streaming work: 3 tensors forward,
+// 5 backward, nothing is read twice.
+__device__ __forceinline__ void unpack8(const uint4& u, float (&x)[8])
+{
+    x[0] = bf16_lo(u.x); x[1] = bf16_hi(u.x); x[2] = bf16_lo(u.y); x[3] = bf16_hi(u.y);
+    x[4] = bf16_lo(u.z); x[5] = bf16_hi(u.z); x[6] = bf16_lo(u.w); x[7] = bf16_hi(u.w);
+}
+__device__ __forceinline__ uint4 pack8(const float (&x)[8])
+{
+    return make_uint4(pack2(x[0], x[1]), pack2(x[2], x[3]), pack2(x[4], x[5]), pack2(x[6], x[7]));
+}
+template <int LANES>
+__device__ __forceinline__ float row_sum(float v)
+{
+#pragma unroll
+    for (int m = 1; m < LANES; m <<= 1) v += __shfl_xor(v, m);
+    return v;
+}
+
+template <int DV, bool BWD>
+__global__ __launch_bounds__(256) void gate_norm_kernel(const bf16* __restrict__ O, const bf16* __restrict__ G,
+                                                       const bf16* __restrict__ dY, bf16* __restrict__ out0,
+                                                       bf16* __restrict__ out1, float eps, long rows)
+{
+    constexpr int LPR = DV / 8, RPP = 256 / LPR, RPT = 4;   // lanes per row, rows per pass, rows per thread
+    const int sub = threadIdx.x % LPR;
+    const long row0 = (long)blockIdx.x * (RPP * RPT) + threadIdx.x / LPR;
+    uint4 o[RPT], g[RPT], d[RPT];
+#pragma unroll
+    for (int i = 0; i < RPT; ++i) {
+        // rows past the end read the last row (butterflies need every lane); nothing is stored for them
+        const long r = min(row0 + (long)i * RPP, rows - 1);
+        const size_t off = (size_t)r * DV + 8 * sub;
+        o[i] = *reinterpret_cast<const uint4*>(O + off);
+        g[i] = *reinterpret_cast<const uint4*>(G + off);
+        if (BWD) d[i] = *reinterpret_cast<const uint4*>(dY + off);
+    }
+#pragma unroll
+    for (int i = 0; i < RPT; ++i) {
+        const long r = row0 + (long)i * RPP;
+        const size_t off = (size_t)r * DV + 8 * sub;
+        float x[8], gg[8], y[8];
+        unpack8(o[i], x);
+        unpack8(g[i], gg);
+        float ss = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) ss = fmaf(x[e], x[e], ss);
+        const float rinv = __builtin_amdgcn_rsqf(fmaf(row_sum<LPR>(ss), 1.f / DV, eps));
+        if (!BWD) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) y[e] = x[e] * rinv * gg[e];
+            if (r < rows) *reinterpret_cast<uint4*>(out0 + off) = pack8(y);
+        } else {
+            // n = r o, u = dY g:  dG = dY n,  dO = r (u - n mean(u n))
+            float dy[8], u[8], dg[8];
+            unpack8(d[i], dy);
+            float un = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                x[e] *= rinv;
+                u[e] = dy[e] * gg[e];
+                dg[e] = dy[e] * x[e];
+                un = fmaf(u[e], x[e], un);
+            }
+            const float m = row_sum<LPR>(un) * (1.f / DV);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) y[e] = rinv * fmaf(-x[e], m, u[e]);
+            if (r < rows) {
+                *reinterpret_cast<uint4*>(out0 + off) = pack8(y);
+                *reinterpret_cast<uint4*>(out1 + off) = pack8(dg);
+            }
+        }
+    }
+}
+
+hipError_t launch_gate_norm(const void* O, const void* G, const void* dY, void* out0, void* out1, float eps, long rows,
+                            int dv, hipStream_t st)
+{
+    const bf16 *o = (const bf16*)O, *g = (const bf16*)G, *d = (const bf16*)dY;
+    bf16 *a = (bf16*)out0, *b = (bf16*)out1;
+    const bool bwd = dY != nullptr;
+    const long rows_per_wg = (256 / (dv / 8)) * 4;
+    const dim3 grid((unsigned)((rows + rows_per_wg - 1) / rows_per_wg));
+    ProfScope prof(KID_GATE_NORM, st);
+    if (dv == 64 && !bwd) hipLaunchKernelGGL((gate_norm_kernel<64, false>), grid, dim3(256), 0, st, o, g, d, a, b, eps, rows);
+    else if (dv == 64) hipLaunchKernelGGL((gate_norm_kernel<64, true>), grid, dim3(256), 0, st, o, g, d, a, b, eps, rows);
+    else if (dv == 128 && !bwd) hipLaunchKernelGGL((gate_norm_kernel<128, false>), grid, dim3(256), 0, st, o, g, d, a, b, eps, rows);
+    else if (dv == 128) hipLaunchKernelGGL((gate_norm_kernel<128, true>), grid, dim3(256), 0, st, o, g, d, a, b, eps, rows);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
 }
 
 // =============================================================================================== decode step
@@ -1103,6 +1290,34 @@ static hipError_t fwd_impl(const bf16* Q, const bf16* K, const bf16* V, bf16* O,
         hipLaunchKernelGGL((bf16_fwd_sweep_kernel<C, DK, DV, ZQK, false, NH>), grid, dim3(256), 0, st, Q, K, V, O,
                            use_ws ? ws : nullptr, S_out, aff, H, (float*)nullptr, 1, S_in != nullptr ? 1 : 0, N,
                            plan.seg_len, plan.n_seg);
+    return hipGetLastError();
+}
+
+// Forward with the Eq. 9 epilogue (Y = Norm(O) * G; O optional).  aff non-null: Z stands in for Q and K.
+template <int DK, int DV, bool ZQK>
+static hipError_t fwd_gated_impl(const bf16* Q, const bf16* K, const bf16* V, const bf16* G, bf16* O, bf16* Y, float eps,
+                                 const float* aff, int H, float* saved, int save_every, long BH, int N,
+                                 const Plan& plan, float* ws, hipStream_t st)
+{
+    hipError_t e;
+    if (plan.n_seg > 1) {
+        SegStateArgs a{};
+        a.X[0] = ZQK ? Q : K; a.Y[0] = V; a.out[0] = ws; a.skip_seg[0] = plan.n_seg - 1;
+        a.H = H;
+        if (ZQK) { a.alpha[0] = aff + 2 * (size_t)H * DK; a.beta[0] = aff + 3 * (size_t)H * DK; }
+        const int mode = SCAN_EXCL_PREFIX;
+        const float* init[2] = {nullptr, nullptr};
+        if ((e = run_seg_state<DK, DV, ZQK ? 1 : 0, false>(a, 1, &mode, init, false, BH, N, plan, st)) != hipSuccess)
+            return e;
+    }
+    dim3 grid((unsigned)BH, plan.n_seg);
+    ProfScope prof(KID_FWD_SWEEP_BF16, st);
+    if (saved != nullptr)
+        hipLaunchKernelGGL((bf16_fwd_gated_kernel<64, DK, DV, ZQK, true>), grid, dim3(256), 0, st, Q, K, V, G, O, Y, eps,
+                           plan.n_seg > 1 ? ws : nullptr, aff, H, saved, save_every, N, plan.seg_len, plan.n_seg);
+    else
+        hipLaunchKernelGGL((bf16_fwd_gated_kernel<64, DK, DV, ZQK, false>), grid, dim3(256), 0, st, Q, K, V, G, O, Y,
+                           eps, plan.n_seg > 1 ? ws : nullptr, aff, H, (float*)nullptr, 1, N, plan.seg_len, plan.n_seg);
     return hipGetLastError();
 }
 
@@ -1386,6 +1601,20 @@ hipError_t launch_bf16_bwd_nh(const void* Q, const void* K, const void* V, const
                                                                       nullptr, nullptr, nullptr, B, H, N, plan, ws, st)))
     CHELA_BWD_NH(64, 64) CHELA_BWD_NH(64, 128) CHELA_BWD_NH(128, 64) CHELA_BWD_NH(128, 128)
 #undef CHELA_BWD_NH
+    return hipErrorInvalidValue;
+}
+
+// Eq. 9 epilogue fused into the forward; aff non-null selects the Eq. 11-12 prologue as well.  64-token chunks.
+hipError_t launch_bf16_fwd_gated(const void* Q, const void* K, const void* V, const void* G, void* O, void* Y, float eps,
+                                 const float* aff, float* saved, int save_every, int B, int H, int N, int dk, int dv,
+                                 const Plan& plan, float* ws, hipStream_t st)
+{
+    const bf16 *q = (const bf16*)Q, *k = (const bf16*)K, *v = (const bf16*)V, *g = (const bf16*)G;
+    bf16 *o = (bf16*)O, *y = (bf16*)Y;
+    const long BH = (long)B * H;
+#define CHELA_GFWD(DK_, DV_)                                                                                               if (dk == DK_ && dv == DV_)                                                                                                return aff ? fwd_gated_impl<DK_, DV_, true>(q, nullptr, v, g, o, y, eps, aff, H, saved, save_every, BH, N, plan,                                                     ws, st)                                                                               : fwd_gated_impl<DK_, DV_, false>(q, k, v, g, o, y, eps, nullptr, H, saved, save_every, BH, N, plan,                                                      ws, st);
+    CHELA_GFWD(64, 64) CHELA_GFWD(64, 128) CHELA_GFWD(128, 64) CHELA_GFWD(128, 128)
+#undef CHELA_GFWD
     return hipErrorInvalidValue;
 }
 

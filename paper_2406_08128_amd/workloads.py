@@ -112,6 +112,20 @@ def make_z_inputs(w: Workload, with_dO: Optional[bool] = None) -> Dict[str, torc
     return out
 
 
+def make_gate_inputs(w: Workload) -> Dict[str, torch.Tensor]:
+    """Gate and output gradient for the normalised, gated output: {"G", "dY"}, both [B,H,N,dv] in the I/O dtype.
+
+    Recipe: generator seeded with seed + 3000; torch.randn in fp32 in the order n_g, n_y; G = silu(n_g) -- the
+    activation a gate leaves its projection through, so values lie in [-0.28, inf) with many near zero -- and
+    dY = n_y; both cast to the I/O dtype last."""
+    g = torch.Generator(device="cpu")
+    g.manual_seed(w.seed + 3000)
+    n_g = torch.randn(w.B, w.H, w.N, w.dv, generator=g, dtype=torch.float32)
+    n_y = torch.randn(w.B, w.H, w.N, w.dv, generator=g, dtype=torch.float32)
+    dt = _torch_dtype(w.dtype)
+    return {"G": torch.nn.functional.silu(n_g).to(dt).contiguous(), "dY": n_y.to(dt).contiguous()}
+
+
 def make_conv_inputs(B: int, d: int, L: int, m: int, seed: int, dtype: str = "bf16") -> Dict[str, torch.Tensor]:
     """Inputs for the short-long convolution: {"X" [B,d,L], "w_short" [d,m], "k_long" [d,L]}.
 

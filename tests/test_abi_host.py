@@ -254,3 +254,50 @@ def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "nope.so"))
     with pytest.raises(FileNotFoundError):
         binding.lib()
+
+
+def test_gated_argument_errors(L):
+    f, z = L.chela_linattn_fwd_gated, L.chela_linattn_zfwd_gated
+    Q, K, V, G, O, Y, SV = (A + i * SZ for i in range(7))
+    dims = (1, 1, 64, 64, 64, 64, None)
+    assert f(None, K, V, G, O, Y, SV, 1e-5, *dims) == -1
+    assert f(Q, K, V, None, O, Y, SV, 1e-5, *dims) == -1
+    assert f(Q, K, V, G, O, None, SV, 1e-5, *dims) == -1              # Y is required, O and saved are not
+    assert f(Q, K, V, G, O, Y, SV, -1.0, *dims) == -2
+    assert f(Q, K, V, G, O, Y, SV, float("nan"), *dims) == -2
+    assert f(Q, K, V, G, O, Y, SV, float("inf"), *dims) == -2
+    assert f(Q, K, V, G, O, Y + 4, SV, 1e-5, *dims) == -5
+    assert f(Q, K, V, G, O, G, SV, 1e-5, *dims) == -6                 # Y on top of the gate
+    assert f(Q, K, V, G, Y, Y, SV, 1e-5, *dims) == -6                 # O and Y are two outputs
+    assert f(Q, K, V, G, O, Y, V, 1e-5, *dims) == -6                  # saved states over V
+    assert f(Q, K, V, G, O, Y, SV, 1e-5, 1, 1, 64, 64, 96, 64, None) == -3
+    assert f(Q, K, V, G, O, Y, SV, 1e-5, 1, 1, 64, 64, 64, 5, None) == -4
+    assert f(None, None, None, None, None, None, None, 1e-5, 0, 1, 64, 64, 64, 64, None) == 0
+    AF = A + 7 * SZ
+    assert z(Q, None, V, G, O, Y, SV, 1e-5, *dims) == -1
+    assert z(Q, AF + 4, V, G, O, Y, SV, 1e-5, *dims) == -5
+    assert z(Q, AF, V, G, O, AF, SV, 1e-5, *dims) == -6
+    assert z(Q, AF, V, G, O, Y, SV, -0.5, *dims) == -2
+    assert z(None, None, None, None, None, None, None, 0.0, 1, 1, 0, 64, 64, 64, None) == 0
+
+
+def test_gate_norm_argument_errors(L):
+    f, g = L.chela_gate_norm_fwd, L.chela_gate_norm_bwd
+    O, G, dY, dO, dG = (A + i * SZ for i in range(5))
+    assert f(None, G, dO, 1e-5, 10, 64, None) == -1
+    assert f(O, G, None, 1e-5, 10, 64, None) == -1
+    assert f(O, G, dO, 1e-5, -1, 64, None) == -2
+    assert f(O, G, dO, -1e-5, 10, 64, None) == -2
+    assert f(O, G, dO, 1e-5, 10, 32, None) == -3
+    assert f(O, G, dO + 2, 1e-5, 10, 64, None) == -5
+    assert f(O, G, O, 1e-5, 10, 64, None) == -6
+    assert f(O, G, O + 64, 1e-5, 10, 64, None) == -6
+    assert f(None, None, None, 1e-5, 0, 64, None) == 0
+    assert g(O, G, None, dO, dG, 1e-5, 10, 64, None) == -1
+    assert g(O, G, dY, dO, None, 1e-5, 10, 64, None) == -1
+    assert g(O, G, dY, dO, dO, 1e-5, 10, 64, None) == -6
+    assert g(O, G, dY, G, dG, 1e-5, 10, 64, None) == -6
+    assert g(O, G, dY, dY + 16, dG, 1e-5, 10, 64, None) == -6       # shifted overlap with dY is not the in-place case
+    assert g(O, G, dY, dO, dY, 1e-5, 10, 64, None) == -6            # only dO may sit on dY
+    assert g(O, G, dY, dO, dG, 1e-5, 10, 256, None) == -3
+    assert g(None, None, None, None, None, 1e-5, 0, 128, None) == 0

@@ -13,7 +13,8 @@ import oracle
 from paper_2406_08128_amd import binding
 from oracle import layer as oracle_layer
 from oracle import conv as oracle_conv
-from paper_2406_08128_amd.workloads import WORKLOADS, make_conv_inputs, make_inputs, make_z_inputs, shrink, to_f64_numpy
+from paper_2406_08128_amd.workloads import (WORKLOADS, make_conv_inputs, make_gate_inputs, make_inputs, make_z_inputs,
+                                            shrink, to_f64_numpy)
 
 pytestmark = pytest.mark.gpu
 
@@ -731,3 +732,111 @@ def test_bnhd_lm_full_size_sampled():
         _check("O", sel(O), oracle.fwd_recurrent(Qn, Kn, Vn), "bf16")
         for name, got, r in zip(("dQ", "dK", "dV"), (dQ, dK, dV), oracle.bwd_recurrent(Qn, Kn, Vn, Gn)):
             _check(name, sel(got), r, "bf16")
+
+
+# ------------------------------------------------------------------------------------------ Eq. 9: Norm(O) * G
+EPS = 1e-5
+
+
+@pytest.mark.parametrize("rows_dv", [(1, 64), (127, 64), (128, 64), (1000, 64), (5, 128), (4101, 128), (3 * 1024, 128)])
+def test_gate_norm_alone(rows_dv):
+    rows, dv = rows_dv
+    print("\ngate-norm rows %d dv %d" % (rows, dv), flush=True)
+    g = torch.Generator(device="cpu")
+    g.manual_seed(7000 + rows)
+    # rows of very different length: the normalisation must not care
+    O = (torch.randn(rows, dv, generator=g) * torch.exp(2.0 * torch.randn(rows, 1, generator=g))).bfloat16()
+    G = torch.nn.functional.silu(torch.randn(rows, dv, generator=g)).bfloat16()
+    dY = torch.randn(rows, dv, generator=g).bfloat16()
+    Od, Gd, dYd = O.cuda(), G.cuda(), dY.cuda()
+    Y = binding.chela_gate_norm_fwd(Od, Gd, EPS)
+    dO, dG = binding.chela_gate_norm_bwd(Od, Gd, dYd, EPS)
+    dY2 = dYd.clone()
+    dO2, dG2 = binding.chela_gate_norm_bwd(Od, Gd, dY2, EPS, in_place=True)
+    torch.cuda.synchronize()
+    On, Gn, dYn = (to_f64_numpy(t) for t in (O, G, dY))
+    _check("Y", Y, oracle_layer.gate_norm_fwd(On, Gn, EPS), "bf16")
+    rO, rG = oracle_layer.gate_norm_bwd(On, Gn, dYn, EPS)
+    _check("dO", dO, rO, "bf16")
+    _check("dG", dG, rG, "bf16")
+    assert dO2.data_ptr() == dY2.data_ptr() and torch.equal(dO2, dO) and torch.equal(dG2, dG)
+
+
+def test_gate_norm_eps_enters_under_the_root_and_empty_input():
+    O = torch.full((64, 64), 2.0, dtype=torch.bfloat16, device="cuda")
+    G = torch.ones_like(O)
+    Y0 = binding.chela_gate_norm_fwd(O, G, 0.0)
+    Y1 = binding.chela_gate_norm_fwd(O, G, 12.0)          # 2 / sqrt(4 + 12) = 1/2
+    e = torch.empty((0, 64), dtype=torch.bfloat16, device="cuda")
+    Ye = binding.chela_gate_norm_fwd(e, e, EPS)
+    torch.cuda.synchronize()
+    assert float((Y0.float() - 1.0).abs().max()) <= 2 ** -8
+    assert float((Y1.float() - 0.5).abs().max()) <= 2 ** -9
+    assert Ye.numel() == 0
+
+
+GATED_SHAPES = [(1, 1, 64, 64, 64), (2, 3, 1000, 64, 64), (1, 2, 1, 64, 64), (3, 2, 1100, 64, 128), (1, 2, 1300, 128, 64),
+                (2, 1, 700, 128, 128), (1, 2, 9000, 64, 64)]
+
+
+@pytest.mark.parametrize("shape", GATED_SHAPES)
+def test_fwd_gated_small(shape):
+    B, H, N, dk, dv = shape
+    w = shrink(WORKLOADS["lm_bf16"], B=B, H=H, N=N, dk=dk, dv=dv, seed=300 + N)
+    print("\ngated %s" % (shape,), flush=True)
+    x, gx = make_inputs(w, with_dO=False), make_gate_inputs(w)
+    d, gd = _dev(x), _dev(gx)
+    Y, O, _ = binding.chela_linattn_fwd_gated(d["Q"], d["K"], d["V"], gd["G"], EPS, want_O=True)
+    Y2, O2, _ = binding.chela_linattn_fwd_gated(d["Q"], d["K"], d["V"], gd["G"], EPS)
+    O_plain = binding.chela_linattn_fwd(d["Q"], d["K"], d["V"])
+    torch.cuda.synchronize()
+    Qn, Kn, Vn, Gn = (to_f64_numpy(t) for t in (x["Q"], x["K"], x["V"], gx["G"]))
+    rO, rY = oracle_layer.gated_fwd(Qn, Kn, Vn, Gn, EPS)
+    _check("Y", Y, rY, "bf16")
+    _check("O", O, rO, "bf16")
+    # the epilogue changes nothing about O, and leaving O out changes nothing about Y
+    assert O2 is None and torch.equal(Y2, Y) and torch.equal(O, O_plain)
+
+
+@pytest.mark.parametrize("shape", [(2, 3, 1000, 64, 64), (1, 2, 9000, 64, 64), (3, 2, 1100, 64, 128),
+                                   (1, 2, 5000, 128, 64), (2, 1, 4100, 128, 128)])
+def test_layer_core_training_chain(shape):
+    # Z, V, G -> Y (prologue and epilogue fused into the forward, states saved), then dY -> dO, dG -> dZ, d_affine, dV
+    B, H, N, dk, dv = shape
+    w = shrink(WORKLOADS["lm_bf16"], B=B, H=H, N=N, dk=dk, dv=dv, seed=400 + N)
+    print("\nlayer core %s" % (shape,), flush=True)
+    x, gx = make_z_inputs(w, with_dO=False), make_gate_inputs(w)
+    d, gd = _dev(x), _dev(gx)
+    Y, O, saved = binding.chela_linattn_zfwd_gated(d["Z"], d["affine"], d["V"], gd["G"], EPS, want_O=True, want_saved=True)
+    O_ref, saved_ref = binding.chela_linattn_zfwd_save(d["Z"], d["affine"], d["V"])
+    dO, dG = binding.chela_gate_norm_bwd(O, gd["G"], gd["dY"], EPS)
+    dZ, dA, dV = binding.chela_linattn_zbwd_saved(d["Z"], d["affine"], d["V"], dO, saved)
+    torch.cuda.synchronize()
+    assert torch.equal(O, O_ref) and torch.equal(saved, saved_ref)
+    Zn, An, Vn, Gn, dYn = (to_f64_numpy(t) for t in (x["Z"], x["affine"], x["V"], gx["G"], gx["dY"]))
+    Qn, Kn = oracle_layer.qk_from_z(Zn, An)
+    rO, rY = oracle_layer.gated_fwd(Qn, Kn, Vn, Gn, EPS)
+    _check("Y", Y, rY, "bf16")
+    rdO, rdG = oracle_layer.gate_norm_bwd(rO, Gn, dYn, EPS)
+    _check("dG", dG, rdG, "bf16")
+    _check("dO", dO, rdO, "bf16")
+    rZ, rA, rV = oracle_layer.zqk_bwd(Zn, An, Vn, rdO)
+    _check("dZ", dZ, rZ, "bf16")
+    _check("dV", dV, rV, "bf16")
+    for q in range(4):
+        _check("d_affine[%d]" % q, dA[q], rA[q], "bf16")
+
+
+def test_fwd_gated_lm_full_size_sampled():
+    w = WORKLOADS["lm_bf16"]
+    x, gx = make_inputs(w, with_dO=False), make_gate_inputs(w)
+    d, gd = _dev(x), _dev(gx)
+    Y, _, _ = binding.chela_linattn_fwd_gated(d["Q"], d["K"], d["V"], gd["G"], EPS)
+    Yb = binding.chela_gate_norm_fwd(binding.chela_linattn_fwd(d["Q"], d["K"], d["V"]), gd["G"], EPS)
+    torch.cuda.synchronize()
+    for b, hd in ((0, 0), (1, 7), (3, 11)):
+        print("b, head", b, hd, flush=True)
+        Qn, Kn, Vn, Gn = (to_f64_numpy(t[b:b + 1, hd:hd + 1]) for t in (x["Q"], x["K"], x["V"], gx["G"]))
+        _check("Y", Y[b:b + 1, hd:hd + 1], oracle_layer.gated_fwd(Qn, Kn, Vn, Gn, EPS)[1], "bf16")
+    # against the two-call route the only difference is one more rounding of O to bf16
+    assert oracle.rel_l2(to_f64_numpy(Y), to_f64_numpy(Yb)) <= 4e-3
