@@ -345,7 +345,7 @@ template <int DA, int DB, int AFF>
 __device__ __forceinline__ void prepass_body(const bf16* __restrict__ X, const bf16* __restrict__ Y,
                                              float* __restrict__ out, const float* __restrict__ alpha,
                                              const float* __restrict__ beta, int lda, int ldb, int ntok,
-                                             unsigned char* lds, int tid, int w, int lane)
+                                             unsigned char* lds, int tid, int w, int lane, bool rev = false)
 {
     constexpr int R = 64;
     constexpr int PF = 2;          // 64-token blocks in flight per workgroup: this kernel only reads, so it lives
@@ -379,14 +379,19 @@ __device__ __forceinline__ void prepass_body(const bf16* __restrict__ X, const b
                 acc[n] = mfma(ld_tr(sX, DA + PAD, s0, ab * 32, lane), ld_tr(sY, DB + PAD, s0, bb * 32, lane), acc[n]);
         }
     };
+    // The sum does not care about the order of its blocks.  `rev` (only taken when every block is complete) walks them
+    // from the segment's end to its start, so that a forward sweep that follows finds the blocks it needs first
+    // among the most recently read ones in the memory-side cache.
+    rev = rev && ntok % R == 0;
+    auto at = [&](int c) __attribute__((always_inline)) { return (size_t)(rev ? ntok - R - c : c); };
     int c0 = 0;
     if (ntok >= 2 * PF * R) {
         // Steady state: the PF blocks being consumed and the PF blocks being fetched are all complete, so every load
         // is unconditional and the wait before a set is consumed leaves the younger set's loads in flight.
 #pragma unroll
         for (int u = 0; u < PF; ++u) {
-            rx[u].load_full(X + (size_t)(u * R) * lda, lda, tid);
-            ry[u].load_full(Y + (size_t)(u * R) * ldb, ldb, tid);
+            rx[u].load_full(X + at(u * R) * lda, lda, tid);
+            ry[u].load_full(Y + at(u * R) * ldb, ldb, tid);
             __builtin_amdgcn_sched_barrier(0);   // keep the sets in issue order: the wait for set 0 must not cover set 1
         }
         for (; c0 + 2 * PF * R <= ntok; c0 += PF * R) {
@@ -394,8 +399,8 @@ __device__ __forceinline__ void prepass_body(const bf16* __restrict__ X, const b
             for (int u = 0; u < PF; ++u) {
                 consume(u);
                 __syncthreads();
-                rx[u].load_full(X + (size_t)(c0 + (PF + u) * R) * lda, lda, tid);
-                ry[u].load_full(Y + (size_t)(c0 + (PF + u) * R) * ldb, ldb, tid);
+                rx[u].load_full(X + at(c0 + (PF + u) * R) * lda, lda, tid);
+                ry[u].load_full(Y + at(c0 + (PF + u) * R) * ldb, ldb, tid);
                 multiply();
                 __syncthreads();
             }
@@ -404,8 +409,8 @@ __device__ __forceinline__ void prepass_body(const bf16* __restrict__ X, const b
 #pragma unroll
         for (int u = 0; u < PF; ++u)
             if (u * R < ntok) {
-                rx[u].load(X + (size_t)(u * R) * lda, lda, ntok - u * R, tid);
-                ry[u].load(Y + (size_t)(u * R) * ldb, ldb, ntok - u * R, tid);
+                rx[u].load(X + at(u * R) * lda, lda, rev ? R : ntok - u * R, tid);
+                ry[u].load(Y + at(u * R) * ldb, ldb, rev ? R : ntok - u * R, tid);
             }
     }
     // The rest (at most 2 PF blocks, the last one possibly ragged): set u holds block c0 + u R if that block exists.
@@ -417,8 +422,8 @@ __device__ __forceinline__ void prepass_body(const bf16* __restrict__ X, const b
                 consume(u);
                 __syncthreads();
                 if (c + PF * R < ntok) {
-                    rx[u].load(X + (size_t)(c + PF * R) * lda, lda, ntok - c - PF * R, tid);
-                    ry[u].load(Y + (size_t)(c + PF * R) * ldb, ldb, ntok - c - PF * R, tid);
+                    rx[u].load(X + at(c + PF * R) * lda, lda, rev ? R : ntok - c - PF * R, tid);
+                    ry[u].load(Y + at(c + PF * R) * ldb, ldb, rev ? R : ntok - c - PF * R, tid);
                 }
                 multiply();
                 __syncthreads();
@@ -953,6 +958,7 @@ struct SegStateArgs {
     const float* alpha[2];
     const float* beta[2];
     int H;
+    int reverse[2];    // walk the segment's blocks from its end to its start (same sum)
 };
 
 // NH: the tensors are [B,N,H,d] (token rows H * d apart) instead of [B,H,N,d]; args.H is then the head count.
@@ -982,7 +988,7 @@ void bf16_seg_state_kernel(SegStateArgs args, int N, int seg_len, int n_seg)
     prepass_body<DA, DB, AFF>(args.X[z] + row_offset<DA>(NH, bh, args.H, N, p0),
                               args.Y[z] + row_offset<DB>(NH, bh, args.H, N, p0),
                               args.out[z] + ((size_t)bh * n_seg + seg) * DA * DB, al, be, NH ? args.H * DA : DA,
-                              NH ? args.H * DB : DB, p1 - p0, lds, tid, w, lane);
+                              NH ? args.H * DB : DB, p1 - p0, lds, tid, w, lane, args.reverse[z] != 0);
 }
 
 // (the narrowest shape is asked to stay within the 128 registers that let four workgroups share a compute unit)
@@ -1243,6 +1249,12 @@ hipError_t launch_bf16_step(const void* q, const void* k, const void* v, float* 
 
 // =============================================================================================== launchers
 // Pre-pass + scan over segments.  init[z] (optional, [dk][dv] fp32 per head) seeds the scan of array z.
+static int prepass_reverse()
+{
+    static const int v = [] { const char* e = getenv("CHELA_PREPASS_REV"); return e ? atoi(e) : 1; }();
+    return v;
+}
+
 template <int DA, int DB, int AFF = 0, bool NH = false>
 static hipError_t run_seg_state(const SegStateArgs& a, int npairs, const int* scan_modes, const float* const* init,
                                 bool init_transposed, long BH, int N, const Plan& plan, hipStream_t st,
@@ -1274,6 +1286,7 @@ static hipError_t fwd_impl(const bf16* Q, const bf16* K, const bf16* V, bf16* O,
         SegStateArgs a{};
         a.X[0] = ZQK ? Q : K; a.Y[0] = V; a.out[0] = ws; a.skip_seg[0] = plan.n_seg - 1;
         a.H = H;
+        a.reverse[0] = prepass_reverse();
         if (ZQK) { a.alpha[0] = aff + 2 * (size_t)H * DK; a.beta[0] = aff + 3 * (size_t)H * DK; }
         const int mode = SCAN_EXCL_PREFIX;
         const float* init[2] = {S_in, nullptr};
@@ -1304,6 +1317,7 @@ static hipError_t fwd_gated_impl(const bf16* Q, const bf16* K, const bf16* V, co
         SegStateArgs a{};
         a.X[0] = ZQK ? Q : K; a.Y[0] = V; a.out[0] = ws; a.skip_seg[0] = plan.n_seg - 1;
         a.H = H;
+        a.reverse[0] = prepass_reverse();
         if (ZQK) { a.alpha[0] = aff + 2 * (size_t)H * DK; a.beta[0] = aff + 3 * (size_t)H * DK; }
         const int mode = SCAN_EXCL_PREFIX;
         const float* init[2] = {nullptr, nullptr};
