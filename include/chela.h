@@ -271,6 +271,14 @@ void chela_shutdown(void);
  * this GPU actually reaches; it is not part of the attention path. */
 int chela_copy_probe(const void *src, void *dst, size_t bytes, void *stream);
 
+/* The same for any mix of streams: `in` and `out` are HOST arrays of n_in (1..4) and n_out (1..4) device pointers,
+ * each to `bytes` bytes (a multiple of 16, pointers 16-byte aligned, outputs overlapping nothing).  Thread i reads
+ * 16 bytes of every input and writes 16 bytes (derived from what it read) to every output, at offset 16 i rotated by
+ * a different amount per array, so that equally spaced allocations do not meet on one memory channel.  What this reaches for, say, four streams in and three out is the bandwidth the GPU delivers for the mix
+ * that the backward sweep moves; benchmarks print it next to that kernel's own figure.  Not part of the attention
+ * path. */
+int chela_stream_probe(const void *const *in, int n_in, void *const *out, int n_out, size_t bytes, void *stream);
+
 /* ---- per-kernel timing aid (for benchmarks; off by default) -------------------------------------------
  * While enabled, every kernel the library launches is bracketed by two HIP events recorded on the stream
  * the kernel is launched on.  Kernel classes are numbered 0 .. chela_profile_num_kernels()-1.

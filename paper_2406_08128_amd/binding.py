@@ -110,6 +110,8 @@ def lib() -> ctypes.CDLL:
     L.chela_shutdown.restype = None
     L.chela_copy_probe.argtypes = [vp, vp, sz, vp]
     L.chela_copy_probe.restype = i
+    L.chela_stream_probe.argtypes = [ctypes.POINTER(vp), i, ctypes.POINTER(vp), i, sz, vp]
+    L.chela_stream_probe.restype = i
     L.chela_profile_enable.argtypes = [i]
     L.chela_profile_enable.restype = i
     L.chela_profile_num_kernels.argtypes = []
@@ -594,6 +596,19 @@ def chela_copy_probe(src: torch.Tensor, dst: torch.Tensor, stream=None) -> None:
     if dst.numel() * dst.element_size() != nbytes:
         raise ValueError("size mismatch")
     _check(lib().chela_copy_probe(src.data_ptr(), dst.data_ptr(), nbytes, _stream_ptr(stream)))
+
+
+def chela_stream_probe(inputs, outputs, stream=None) -> None:
+    """Plain streaming kernel that reads every tensor of `inputs` (1..4) and writes every tensor of `outputs` (1..4),
+    all of one byte size: the bandwidth yardstick for a given mix of read and write streams."""
+    ts = list(inputs) + list(outputs)
+    nbytes = ts[0].numel() * ts[0].element_size()
+    for t in ts:
+        if t.numel() * t.element_size() != nbytes or not t.is_cuda or not t.is_contiguous():
+            raise ValueError("all tensors must be contiguous device tensors of one byte size")
+    ins = (ctypes.c_void_p * max(len(inputs), 1))(*[t.data_ptr() for t in inputs])
+    outs = (ctypes.c_void_p * max(len(outputs), 1))(*[t.data_ptr() for t in outputs])
+    _check(lib().chela_stream_probe(ins, len(inputs), outs, len(outputs), nbytes, _stream_ptr(stream)))
 
 
 def chela_profile_enable(on: bool) -> None:

@@ -149,7 +149,7 @@ static const char* const kKernelNames[KID_COUNT] = {
     "bf16_seg_state_kernel", "scan_states_kernel", "bf16_fwd_sweep_kernel", "bf16_bwd_sweep_kernel",
     "f32_seg_state_kernel", "f32_sweep_kernel", "copy_probe_kernel", "bf16_step_kernel", "affine_grad_kernel",
     "bf16_apply_state_kernel", "longconv_spectrum_kernel", "shortlong_conv_kernel",
-    "shortconv_bwd_kernel", "longconv_dk_kernel", "gate_norm_kernel"};
+    "shortconv_bwd_kernel", "longconv_dk_kernel", "gate_norm_kernel", "stream_probe_kernel"};
 
 ProfScope::ProfScope(int id, hipStream_t s) : slot(-1), st(s)
 {
@@ -883,6 +883,28 @@ int chela_copy_probe(const void* src, void* dst, size_t bytes, void* stream)
     if (((uintptr_t)src | (uintptr_t)dst | (uintptr_t)bytes) & 15u) return CHELA_ERR_MISALIGNED;
     if (overlap(Range{(const char*)src, bytes}, Range{(const char*)dst, bytes})) return CHELA_ERR_ALIASING;
     return launch_copy(src, dst, bytes, (hipStream_t)stream) == hipSuccess ? CHELA_OK : CHELA_ERR_HIP;
+}
+
+int chela_stream_probe(const void* const* in, int n_in, void* const* out, int n_out, size_t bytes, void* stream)
+{
+    if (n_in < 1 || n_in > 4 || n_out < 1 || n_out > 4) return CHELA_ERR_BAD_SHAPE;
+    if (bytes == 0) return CHELA_OK;
+    if (!in || !out) return CHELA_ERR_NULL_POINTER;
+    if (bytes & 15u) return CHELA_ERR_MISALIGNED;
+    for (int k = 0; k < n_in; ++k) {
+        if (!in[k]) return CHELA_ERR_NULL_POINTER;
+        if ((uintptr_t)in[k] & 15u) return CHELA_ERR_MISALIGNED;
+    }
+    for (int k = 0; k < n_out; ++k) {
+        if (!out[k]) return CHELA_ERR_NULL_POINTER;
+        if ((uintptr_t)out[k] & 15u) return CHELA_ERR_MISALIGNED;
+        const Range ro{(const char*)out[k], bytes};
+        for (int i = 0; i < n_in; ++i)
+            if (overlap(ro, Range{(const char*)in[i], bytes})) return CHELA_ERR_ALIASING;
+        for (int j = k + 1; j < n_out; ++j)
+            if (overlap(ro, Range{(const char*)out[j], bytes})) return CHELA_ERR_ALIASING;
+    }
+    return launch_stream_probe(in, n_in, out, n_out, bytes, (hipStream_t)stream) == hipSuccess ? CHELA_OK : CHELA_ERR_HIP;
 }
 
 int chela_profile_enable(int on) { g_prof_on = (on != 0); return CHELA_OK; }

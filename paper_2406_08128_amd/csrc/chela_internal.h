@@ -31,6 +31,9 @@ hipError_t scan_states(float* states, size_t array_stride, int n_arrays, const i
 
 // Streaming copy used to calibrate byte counters.
 hipError_t launch_copy(const void* src, void* dst, size_t bytes, hipStream_t st);
+// n_in (1..4) arrays read, n_out (1..4) arrays written, `bytes` each, by a plain grid-stride kernel.
+hipError_t launch_stream_probe(const void* const* in, int n_in, void* const* out, int n_out, size_t bytes,
+                               hipStream_t st);
 
 // fp32 path.  `rev` runs the same map on the time-reversed sequence (anti-causal mask), which is what the
 // gradient with respect to K and V is (the backward is three calls of this launcher).
@@ -102,7 +105,7 @@ hipError_t launch_shortlong_conv_bwd(const void* X, const float* w_short, int m,
 
 // Kernel classes for the per-kernel timing aid.
 enum { KID_SEG_STATE_BF16 = 0, KID_SCAN = 1, KID_FWD_SWEEP_BF16 = 2, KID_BWD_SWEEP_BF16 = 3, KID_SEG_STATE_F32 = 4,
-       KID_SWEEP_F32 = 5, KID_COPY = 6, KID_STEP_BF16 = 7, KID_AFFINE_GRAD = 8, KID_APPLY_BF16 = 9, KID_CONV_SPECTRUM = 10, KID_CONV_FWD = 11, KID_CONV_SHORT_BWD = 12, KID_CONV_DK = 13, KID_GATE_NORM = 14, KID_COUNT = 15 };
+       KID_SWEEP_F32 = 5, KID_COPY = 6, KID_STEP_BF16 = 7, KID_AFFINE_GRAD = 8, KID_APPLY_BF16 = 9, KID_CONV_SPECTRUM = 10, KID_CONV_FWD = 11, KID_CONV_SHORT_BWD = 12, KID_CONV_DK = 13, KID_GATE_NORM = 14, KID_STREAM_PROBE = 15, KID_COUNT = 16 };
 
 // Brackets one kernel launch with HIP events on its stream while profiling is enabled; otherwise does nothing.
 struct ProfScope {

@@ -101,6 +101,75 @@ hipError_t launch_copy(const void* src, void* dst, size_t bytes, hipStream_t st)
     return hipGetLastError();
 }
 
+// ------------------------------------------------------------------------------------------------ stream probe
+// NI arrays read and NO arrays written, element i of every array by the same thread, grid-stride, 16 bytes per
+// access: the friendliest kernel there is for a given mix of read and write streams.  What it reaches is the
+// bandwidth this GPU actually delivers for that mix, the yardstick for kernels that move the same mix.
+struct StreamArgs {
+    const uint4* in[4];
+    uint4* out[4];
+};
+
+template <int NI, int NO>
+__global__ __launch_bounds__(256) void stream_probe_kernel(StreamArgs a, size_t n)
+{
+    // Array k is walked from a different starting point (wrapping round): arrays allocated at equal distances would
+    // otherwise put all streams of a thread on the same memory channel at the same time.
+    const size_t stride = (size_t)gridDim.x * 256;
+    const size_t rot = n > 65536 ? 4099 : 0;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) {
+        uint4 v[NI];
+#pragma unroll
+        for (int k = 0; k < NI; ++k) {
+            size_t j = i + k * rot;
+            if (j >= n) j -= n;
+            v[k] = a.in[k][j];
+        }
+        uint4 x = v[0];
+#pragma unroll
+        for (int k = 1; k < NI; ++k) { x.x ^= v[k].x; x.y ^= v[k].y; x.z ^= v[k].z; x.w ^= v[k].w; }
+#pragma unroll
+        for (int k = 0; k < NO; ++k) {
+            size_t j = i + (NI + k) * rot;
+            if (j >= n) j -= n;
+            a.out[k][j] = x;
+            x.x += 1u;
+        }
+    }
+}
+
+template <int NI>
+static hipError_t stream_dispatch(const StreamArgs& a, int n_out, size_t n, dim3 grid, hipStream_t st)
+{
+    switch (n_out) {
+    case 1: hipLaunchKernelGGL((stream_probe_kernel<NI, 1>), grid, dim3(256), 0, st, a, n); break;
+    case 2: hipLaunchKernelGGL((stream_probe_kernel<NI, 2>), grid, dim3(256), 0, st, a, n); break;
+    case 3: hipLaunchKernelGGL((stream_probe_kernel<NI, 3>), grid, dim3(256), 0, st, a, n); break;
+    case 4: hipLaunchKernelGGL((stream_probe_kernel<NI, 4>), grid, dim3(256), 0, st, a, n); break;
+    default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_stream_probe(const void* const* in, int n_in, void* const* out, int n_out, size_t bytes, hipStream_t st)
+{
+    StreamArgs a{};
+    for (int k = 0; k < n_in; ++k) a.in[k] = (const uint4*)in[k];
+    for (int k = 0; k < n_out; ++k) a.out[k] = (uint4*)out[k];
+    const size_t n = bytes / 16;
+    size_t blocks = (n + 255) / 256;
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    const dim3 grid((unsigned)blocks);
+    ProfScope prof(KID_STREAM_PROBE, st);
+    switch (n_in) {
+    case 1: return stream_dispatch<1>(a, n_out, n, grid, st);
+    case 2: return stream_dispatch<2>(a, n_out, n, grid, st);
+    case 3: return stream_dispatch<3>(a, n_out, n, grid, st);
+    case 4: return stream_dispatch<4>(a, n_out, n, grid, st);
+    default: return hipErrorInvalidValue;
+    }
+}
+
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 __device__ __forceinline__ f32x16 mfma_f32(float a, float b, f32x16 c)

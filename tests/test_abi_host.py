@@ -301,3 +301,20 @@ def test_gate_norm_argument_errors(L):
     assert g(O, G, dY, dO, dY, 1e-5, 10, 64, None) == -6            # only dO may sit on dY
     assert g(O, G, dY, dO, dG, 1e-5, 10, 256, None) == -3
     assert g(None, None, None, None, None, 1e-5, 0, 128, None) == 0
+
+
+def test_stream_probe_argument_errors(L):
+    f = L.chela_stream_probe
+    vp = ctypes.c_void_p
+    ins = (vp * 4)(A, A + SZ, A + 2 * SZ, A + 3 * SZ)
+    outs = (vp * 3)(A + 4 * SZ, A + 5 * SZ, A + 6 * SZ)
+    assert f(ins, 0, outs, 3, 1024, None) == -2
+    assert f(ins, 5, outs, 3, 1024, None) == -2
+    assert f(ins, 4, outs, 0, 1024, None) == -2
+    assert f(ins, 4, outs, 3, 0, None) == 0
+    assert f(None, 4, outs, 3, 1024, None) == -1
+    assert f(ins, 4, outs, 3, 1000, None) == -5
+    assert f((vp * 1)(None), 1, outs, 1, 1024, None) == -1
+    assert f((vp * 1)(A + 4), 1, outs, 1, 1024, None) == -5
+    assert f(ins, 4, (vp * 2)(A + 4 * SZ, A + 4 * SZ + 512), 2, 1024, None) == -6
+    assert f(ins, 4, (vp * 1)(A + SZ), 1, 1024, None) == -6
