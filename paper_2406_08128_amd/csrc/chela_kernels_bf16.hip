@@ -357,7 +357,7 @@ struct PrepassLds {
     static constexpr int BYTES = TILES + (AFF == 1 ? 2 * DA * 4 : AFF == 2 ? 2 * DB * 4 : 0);
 };
 
-template <int DA, int DB, int AFF>
+template <int DA, int DB, int AFF, bool NTL = false>
 __device__ __forceinline__ void prepass_body(const bf16* __restrict__ X, const bf16* __restrict__ Y,
                                              float* __restrict__ out, const float* __restrict__ alpha,
                                              const float* __restrict__ beta, int lda, int ldb, int ntok,
@@ -374,8 +374,8 @@ __device__ __forceinline__ void prepass_body(const bf16* __restrict__ X, const b
     f32x16 acc[NT];
 #pragma unroll
     for (int n = 0; n < NT; ++n) acc[n] = zero16();
-    TileRegs<R, DA> rx[PF];
-    TileRegs<R, DB> ry[PF];
+    TileRegs<R, DA, NTL> rx[PF];     // NTL: nobody reads these tensors again soon (the non-causal forward)
+    TileRegs<R, DB, NTL> ry[PF];
     if (AFF != 0) {
         if (tid < DAFF) { sAff[tid] = alpha[tid]; sAff[DAFF + tid] = beta[tid]; }
         __syncthreads();
@@ -985,7 +985,8 @@ __device__ __forceinline__ size_t row_offset(bool nh, long bh, int H, int N, int
     return nh ? ((size_t)(bh / H) * N + p0) * H * D + (size_t)(bh % H) * D : ((size_t)bh * N + p0) * D;
 }
 
-template <int DA, int DB, int AFF, bool NH>
+// NT: the two tensors are not read again after this kernel (streaming hint on their loads).
+template <int DA, int DB, int AFF, bool NH, bool NT>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((DA == 64 && DB == 64) ? ((AFF == 0 && !NH) ? 6 : 5) : 1)))
 void bf16_seg_state_kernel(SegStateArgs args, int N, int seg_len, int n_seg)
 {
@@ -1002,10 +1003,10 @@ void bf16_seg_state_kernel(SegStateArgs args, int N, int seg_len, int n_seg)
         al = args.alpha[z] + hoff;
         be = args.beta[z] + hoff;
     }
-    prepass_body<DA, DB, AFF>(args.X[z] + row_offset<DA>(NH, bh, args.H, N, p0),
-                              args.Y[z] + row_offset<DB>(NH, bh, args.H, N, p0),
-                              args.out[z] + ((size_t)bh * n_seg + seg) * DA * DB, al, be, NH ? args.H * DA : DA,
-                              NH ? args.H * DB : DB, p1 - p0, lds, tid, w, lane, args.reverse[z] != 0);
+    prepass_body<DA, DB, AFF, NT>(args.X[z] + row_offset<DA>(NH, bh, args.H, N, p0),
+                                  args.Y[z] + row_offset<DB>(NH, bh, args.H, N, p0),
+                                  args.out[z] + ((size_t)bh * n_seg + seg) * DA * DB, al, be, NH ? args.H * DA : DA,
+                                  NH ? args.H * DB : DB, p1 - p0, lds, tid, w, lane, args.reverse[z] != 0);
 }
 
 // (the narrowest shape is asked to stay within the 128 registers that let four workgroups share a compute unit)
@@ -1272,7 +1273,7 @@ static int prepass_reverse()
     return v;
 }
 
-template <int DA, int DB, int AFF = 0, bool NH = false>
+template <int DA, int DB, int AFF = 0, bool NH = false, bool NT = false>
 static hipError_t run_seg_state(const SegStateArgs& a, int npairs, const int* scan_modes, const float* const* init,
                                 bool init_transposed, long BH, int N, const Plan& plan, hipStream_t st,
                                 bool do_scan = true)
@@ -1281,7 +1282,8 @@ static hipError_t run_seg_state(const SegStateArgs& a, int npairs, const int* sc
     {
         dim3 grid((unsigned)BH, plan.n_seg, npairs);
         ProfScope prof(KID_SEG_STATE_BF16, st);
-        hipLaunchKernelGGL((bf16_seg_state_kernel<DA, DB, AFF, NH>), grid, dim3(256), 0, st, a, N, plan.seg_len, plan.n_seg);
+        hipLaunchKernelGGL((bf16_seg_state_kernel<DA, DB, AFF, NH, NT>), grid, dim3(256), 0, st, a, N, plan.seg_len,
+                           plan.n_seg);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     if (!do_scan) return hipSuccess;
@@ -1457,7 +1459,7 @@ __global__ __launch_bounds__(256) void bf16_apply_state_kernel(const bf16* __res
     bf16* Yb = Y + ((size_t)bh * N + p0) * DB;
     const float4* M4 = reinterpret_cast<const float4*>(M + (size_t)bh * m_stride);
 
-    TileRegs<C, DA> rx;
+    TileRegs<C, DA, true> rx;   // X is read here for the last time: streaming loads
     rx.load(Xb, DA, ntok, tid);
     for (int x = tid; x < DA * DB / 4; x += 256) {
         const float4 v = M4[x];
@@ -1525,7 +1527,9 @@ static hipError_t noncausal_fwd_impl(const bf16* Q, const bf16* K, const bf16* V
     SegStateArgs a{};
     a.X[0] = V; a.Y[0] = K; a.out[0] = ws; a.skip_seg[0] = -1;       // S^T = V^T K, [dv][dk]
     const int mode = SCAN_INCL_PREFIX;
-    if ((e = run_seg_state<DV, DK>(a, 1, &mode, nullptr, false, BH, N, plan, st, plan.n_seg > 1)) != hipSuccess) return e;
+    // (K and V are not read again in this call: streaming loads)
+    if ((e = run_seg_state<DV, DK, 0, false, true>(a, 1, &mode, nullptr, false, BH, N, plan, st, plan.n_seg > 1)) != hipSuccess)
+        return e;
     const size_t el = (size_t)DK * DV;
     return run_apply<DK, DV, true>(Q, O, ws + (size_t)(plan.n_seg - 1) * el, plan.n_seg * el, BH, N, st);
 }
