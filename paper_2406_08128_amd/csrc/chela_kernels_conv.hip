@@ -545,7 +545,8 @@ __global__ __launch_bounds__(conv_threads_dk(M)) void longconv_dk_kernel(const I
 // ([d][B * tiles][MT]); shortconv_dw_kernel adds the shares of a channel in a fixed order.
 constexpr int kShortTile = 2048, kShortMaxTaps = 16, kShortTilesPerWg = 4;
 
-template <typename IO>
+// TAPS: compile-time bound on the number of taps (m <= TAPS <= 16): the tap loops are as long as the kernel needs.
+template <typename IO, int TAPS>
 __global__ __launch_bounds__(256) void shortconv_bwd_kernel(const IO* __restrict__ X, const float* __restrict__ w_short,
                                                            int m, const float* __restrict__ dV, IO* __restrict__ dX,
                                                            float* __restrict__ part, IO* __restrict__ Vout, int d, int L)
@@ -556,9 +557,9 @@ __global__ __launch_bounds__(256) void shortconv_bwd_kernel(const IO* __restrict
     __shared__ float red[MT][4];
     const int tid = threadIdx.x, c = blockIdx.x, b = blockIdx.y;
     const int n_share = gridDim.y * gridDim.z, share = b * gridDim.z + blockIdx.z;
-    float wreg[MT], acc[MT];
+    float wreg[TAPS], acc[TAPS];
 #pragma unroll
-    for (int j = 0; j < MT; ++j) { wreg[j] = j < m ? w_short[(long)c * m + j] : 0.f; acc[j] = 0.f; }
+    for (int j = 0; j < TAPS; ++j) { wreg[j] = j < m ? w_short[(long)c * m + j] : 0.f; acc[j] = 0.f; }
     const long row = ((long)b * d + c) * L;
     const bool vec8 = (L & 7) == 0;       // every row starts 16-byte aligned
     for (int tile = blockIdx.z * kShortTilesPerWg; tile < (blockIdx.z + 1) * kShortTilesPerWg && tile * TL < L; ++tile) {
@@ -592,7 +593,7 @@ __global__ __launch_bounds__(256) void shortconv_bwd_kernel(const IO* __restrict
         for (int e = 0; e < 8; ++e) {
             float u = 0.f;
 #pragma unroll
-            for (int j = 0; j < MT; ++j) u = fmaf(wreg[j], xs[16 + e - j], u);
+            for (int j = 0; j < TAPS; ++j) u = fmaf(wreg[j], xs[16 + e - j], u);
             const float sg = __builtin_amdgcn_rcpf(1.f + __expf(-u));
             du8[e] = tc + e < L ? g8[e] * sg * (1.f + u * (1.f - sg)) : 0.f;
             v8[e] = u * sg;                             // v = silu(u), for the long kernel's gradient
@@ -623,7 +624,7 @@ __global__ __launch_bounds__(256) void shortconv_bwd_kernel(const IO* __restrict
         for (int e = 0; e < 8; ++e) {
             float dx = 0.f;
 #pragma unroll
-            for (int j = 0; j < MT; ++j) {
+            for (int j = 0; j < TAPS; ++j) {
                 dx = fmaf(wreg[j], ds[e + j], dx);
                 acc[j] = fmaf(ds[e], xs[16 + e - j], acc[j]);
             }
@@ -639,14 +640,14 @@ __global__ __launch_bounds__(256) void shortconv_bwd_kernel(const IO* __restrict
     }
     // this workgroup's tap sums: wave reduction, then across the four waves
 #pragma unroll
-    for (int j = 0; j < MT; ++j) {
+    for (int j = 0; j < TAPS; ++j) {
         float v = acc[j];
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
         if ((tid & 63) == 0) red[j][tid >> 6] = v;
     }
     __syncthreads();
-    if (tid < MT) part[((long)c * n_share + share) * MT + tid] = red[tid][0] + red[tid][1] + red[tid][2] + red[tid][3];
+    if (tid < TAPS) part[((long)c * n_share + share) * MT + tid] = red[tid][0] + red[tid][1] + red[tid][2] + red[tid][3];
 }
 
 __global__ __launch_bounds__(64) void shortconv_dw_kernel(const float* __restrict__ part, float* __restrict__ dw, int m,
@@ -743,8 +744,11 @@ static hipError_t conv_bwd_impl(const IO* X, const float* w_short, int m, const 
     if ((e = conv_dispatch<IO, float, true>(dZ, nullptr, 0, Kf, ws_dV, BD, d, L, st)) != hipSuccess) return e;
     {
         ProfScope prof(KID_CONV_SHORT_BWD, st);
-        hipLaunchKernelGGL((shortconv_bwd_kernel<IO>), dim3(d, B, tiles), dim3(256), 0, st, X, w_short, m, ws_dV, dX,
-                           ws_part, ws_V, d, L);
+        const dim3 grid(d, B, tiles);
+        if (m <= 4) hipLaunchKernelGGL((shortconv_bwd_kernel<IO, 4>), grid, dim3(256), 0, st, X, w_short, m, ws_dV, dX, ws_part, ws_V, d, L);
+        else if (m <= 8) hipLaunchKernelGGL((shortconv_bwd_kernel<IO, 8>), grid, dim3(256), 0, st, X, w_short, m, ws_dV, dX, ws_part, ws_V, d, L);
+        else if (m <= 12) hipLaunchKernelGGL((shortconv_bwd_kernel<IO, 12>), grid, dim3(256), 0, st, X, w_short, m, ws_dV, dX, ws_part, ws_V, d, L);
+        else hipLaunchKernelGGL((shortconv_bwd_kernel<IO, 16>), grid, dim3(256), 0, st, X, w_short, m, ws_dV, dX, ws_part, ws_V, d, L);
         if ((e = hipGetLastError()) != hipSuccess) return e;
         hipLaunchKernelGGL(shortconv_dw_kernel, dim3(d), dim3(64), 0, st, ws_part, dw, m, B * tiles);
         if ((e = hipGetLastError()) != hipSuccess) return e;
