@@ -378,21 +378,24 @@ def main():
     else:
         n_rd, n_wr = (4, 1) if args.mode == "gated" else (3, 1)
     each = (dom_b * th // (n_rd + n_wr)) // 16 * 16
-    bufs = [torch.empty(each, dtype=torch.uint8, device="cuda") for _ in range(n_rd + n_wr)]
-    for b in bufs[:n_rd]:
-        b.zero_()
-    for _ in range(3):
-        binding.chela_stream_probe(bufs[:n_rd], bufs[n_rd:])
+    # (enough sets of arrays, used in turn, that a launch never finds its arrays in the 256 MB memory-side cache)
+    n_sets = min(8, max(1, -(-(1 << 30) // max(1, each * (n_rd + n_wr)))))
+    sets = [[torch.empty(each, dtype=torch.uint8, device="cuda") for _ in range(n_rd + n_wr)] for _ in range(n_sets)]
+    for bufs in sets:
+        for b in bufs[:n_rd]:
+            b.zero_()
+    for i in range(3):
+        binding.chela_stream_probe(sets[i % n_sets][:n_rd], sets[i % n_sets][n_rd:])
     torch.cuda.synchronize()
     binding.chela_profile_reset()
     binding.chela_profile_enable(True)
-    for _ in range(20):
-        binding.chela_stream_probe(bufs[:n_rd], bufs[n_rd:])
+    for i in range(20):
+        binding.chela_stream_probe(sets[i % n_sets][:n_rd], sets[i % n_sets][n_rd:])
     torch.cuda.synchronize()
     sp = binding.chela_profile_read()["stream_probe_kernel"]
     binding.chela_profile_enable(False)
     binding.chela_profile_reset()
-    del bufs
+    del sets, bufs
     sp_us = sp[1] * 1e3 / sp[0]
     sp_gbs = each * (n_rd + n_wr) / (sp_us * 1e-6) / 1e9
     roofline["stream_mix"] = {"reads": n_rd, "writes": n_wr, "bytes_per_launch": each * (n_rd + n_wr),
