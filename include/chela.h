@@ -243,6 +243,10 @@ size_t chela_shortlong_conv_bwd_workspace_bytes(int B, int d, int L, int has_sho
  * q, k: [B, H, dk] bf16; v, o: [B, H, dv] bf16; S: [B, H, dk, dv] fp32.  Needs no scratch. */
 int chela_linattn_step(const void *q, const void *k, const void *v, float *S, void *o,
                        int B, int H, int dk, int dv, void *stream);
+/* The same step with the Eq. 9 epilogue of chela_linattn_fwd_gated:  y = Norm(S^T q) * g,  g, y: [B, H, dv] bf16,
+ * Norm and eps as defined there (the sum of squares is taken from the fp32 o, y is rounded once). */
+int chela_linattn_step_gated(const void *q, const void *k, const void *v, const void *g, float *S, void *y, float eps,
+                             int B, int H, int dk, int dv, void *stream);
 
 /* Bytes of device scratch one call with these arguments needs, with or without
  * carried states (0 if the arguments are invalid).  The size is O(B*H*dk*dv*segments)

@@ -76,6 +76,8 @@ def lib() -> ctypes.CDLL:
     L.chela_gate_norm_fwd.restype = i
     L.chela_gate_norm_bwd.argtypes = [vp] * 5 + [f32, ctypes.c_longlong, i, vp]
     L.chela_gate_norm_bwd.restype = i
+    L.chela_linattn_step_gated.argtypes = [vp, vp, vp, vp, vp, vp, f32, i, i, i, i, vp]
+    L.chela_linattn_step_gated.restype = i
     L.chela_linattn_noncausal_fwd.argtypes = [vp, vp, vp, vp, i, i, i, i, i, vp]
     L.chela_linattn_noncausal_fwd.restype = i
     L.chela_linattn_noncausal_bwd.argtypes = [vp] * 7 + [i, i, i, i, i, vp]
@@ -569,6 +571,24 @@ def chela_linattn_step(q, k, v, S, o=None, stream=None):
         _check(lib().chela_linattn_step(q.data_ptr(), k.data_ptr(), v.data_ptr(), _state_ptr(S, B, H, dk, dv, "S"),
                                         o.data_ptr(), B, H, dk, dv, _stream_ptr(stream)))
     return o
+
+
+def chela_linattn_step_gated(q, k, v, g, S, eps, y=None, stream=None):
+    """One decode step with the Eq. 9 epilogue: S += k v^T in place, returns y = Norm(S^T q) * g (g: [B,H,dv] bf16)."""
+    B, H, dk = q.shape
+    dv = v.shape[2]
+    if y is None:
+        y = torch.empty((B, H, dv), dtype=torch.bfloat16, device=q.device)
+    for t in (q, k, v, g, y):
+        if t.dtype != torch.bfloat16 or not t.is_cuda or not t.is_contiguous():
+            raise ValueError("q, k, v, g, y must be contiguous bf16 device tensors")
+    if g.shape != v.shape:
+        raise ValueError("g must be shaped like v")
+    with torch.cuda.device(q.device):
+        _check(lib().chela_linattn_step_gated(q.data_ptr(), k.data_ptr(), v.data_ptr(), g.data_ptr(),
+                                              _state_ptr(S, B, H, dk, dv, "S"), y.data_ptr(), float(eps), B, H, dk, dv,
+                                              _stream_ptr(stream)))
+    return y
 
 
 def chela_linattn_workspace_bytes(B, H, N, dk, dv, chunk, is_bwd, dtype) -> int:

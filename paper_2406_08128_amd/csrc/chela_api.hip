@@ -813,21 +813,37 @@ int chela_shortlong_conv_bwd_f32(const void* X, const float* w_short, int m, con
     return shortlong_bwd_common(X, w_short, m, spectrum, dZ, dX, d_w_short, d_k_long, B, d, L, CHELA_DTYPE_F32, stream);
 }
 
-int chela_linattn_step(const void* q, const void* k, const void* v, float* S, void* o, int B, int H, int dk, int dv,
-                       void* stream)
+static int step_common(const void* q, const void* k, const void* v, const void* g, bool gated, float eps, float* S,
+                       void* o, int B, int H, int dk, int dv, void* stream)
 {
+    if (gated && (!(eps >= 0.f) || !std::isfinite(eps))) return CHELA_ERR_BAD_SHAPE;
     if (B < 0 || H < 0) return CHELA_ERR_BAD_SHAPE;
     if (!((dk == 64 || dk == 128) && (dv == 64 || dv == 128))) return CHELA_ERR_UNSUPPORTED_DIM;
     if ((unsigned long long)B * (unsigned long long)H > 0x7fffffffull) return CHELA_ERR_BAD_SHAPE;
     if (B == 0 || H == 0) return CHELA_OK;
-    if (!q || !k || !v || !S || !o) return CHELA_ERR_NULL_POINTER;
-    if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)S | (uintptr_t)o) & 15u) return CHELA_ERR_MISALIGNED;
+    if (!q || !k || !v || !S || !o || (gated && !g)) return CHELA_ERR_NULL_POINTER;
+    if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)S | (uintptr_t)o | (uintptr_t)(gated ? g : q)) & 15u)
+        return CHELA_ERR_MISALIGNED;
     const size_t bh = (size_t)B * H;
     const Range ro{(const char*)o, bh * dv * 2}, rs{(const char*)S, bh * dk * dv * 4};
-    const Range ri[3] = {{(const char*)q, bh * dk * 2}, {(const char*)k, bh * dk * 2}, {(const char*)v, bh * dv * 2}};
+    const Range ri[4] = {{(const char*)q, bh * dk * 2}, {(const char*)k, bh * dk * 2}, {(const char*)v, bh * dv * 2},
+                         {(const char*)g, gated ? bh * dv * 2 : 0}};
     if (overlap(ro, rs)) return CHELA_ERR_ALIASING;
     for (const Range& r : ri) if (overlap(ro, r) || overlap(rs, r)) return CHELA_ERR_ALIASING;
-    return launch_bf16_step(q, k, v, S, o, (long)bh, dk, dv, (hipStream_t)stream) == hipSuccess ? CHELA_OK : CHELA_ERR_HIP;
+    return launch_bf16_step(q, k, v, S, o, gated ? g : nullptr, eps, (long)bh, dk, dv, (hipStream_t)stream) == hipSuccess
+               ? CHELA_OK : CHELA_ERR_HIP;
+}
+
+int chela_linattn_step(const void* q, const void* k, const void* v, float* S, void* o, int B, int H, int dk, int dv,
+                       void* stream)
+{
+    return step_common(q, k, v, nullptr, false, 0.f, S, o, B, H, dk, dv, stream);
+}
+
+int chela_linattn_step_gated(const void* q, const void* k, const void* v, const void* g, float* S, void* y, float eps,
+                             int B, int H, int dk, int dv, void* stream)
+{
+    return step_common(q, k, v, g, true, eps, S, y, B, H, dk, dv, stream);
 }
 
 size_t chela_linattn_workspace_bytes(int B, int H, int N, int dk, int dv, int chunk, int is_bwd, int dtype)

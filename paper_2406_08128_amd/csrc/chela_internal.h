@@ -88,8 +88,9 @@ hipError_t launch_bf16_noncausal_fwd(const void* Q, const void* K, const void* V
 hipError_t launch_bf16_noncausal_bwd(const void* Q, const void* K, const void* V, const void* dO, void* dQ, void* dK,
                                      void* dV, long BH, int N, int dk, int dv, const Plan& plan, float* ws,
                                      hipStream_t st);
-hipError_t launch_bf16_step(const void* q, const void* k, const void* v, float* S, void* o, long BH, int dk, int dv,
-                            hipStream_t st);
+// gate (optional, [BH][dv] bf16): o leaves as Norm(o) * gate with the given eps.
+hipError_t launch_bf16_step(const void* q, const void* k, const void* v, float* S, void* o, const void* gate, float eps,
+                            long BH, int dk, int dv, hipStream_t st);
 
 // Short-long convolutions (Sec. 4.2).  conv_fft_size(L): length M of the complex transform used for sequences of
 // L steps (0: L too long); the kernel spectrum is [d][M/2 + 1] pairs of complex fp32.  dtype 0: bf16 I/O, 1: fp32 I/O.

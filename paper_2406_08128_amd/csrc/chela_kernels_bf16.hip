@@ -1221,14 +1221,16 @@ hipError_t launch_gate_norm(const void* O, const void* G, const void* dY, void* 
 // =============================================================================================== decode step
 // One token per (b,h): S += k v^T (fp32, in place), o = S^T q.  q, k: [BH][DK]; v, o: [BH][DV]; S: [BH][DK][DV].
 // The state is read and written once: 2 * DK * DV * 4 bytes per token-head, nothing else of note.
-template <int DK, int DV>
+// GATE: o leaves as Norm(o) * g (Eq. 9, Norm(o) = o / sqrt(mean_j o_j^2 + eps)), g: [BH][DV].
+template <int DK, int DV, bool GATE>
 __global__ __launch_bounds__(256) void bf16_step_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k,
                                                        const bf16* __restrict__ v, float* __restrict__ S,
-                                                       bf16* __restrict__ o)
+                                                       bf16* __restrict__ o, const bf16* __restrict__ gate, float eps)
 {
     constexpr int G = 256 / DV;          // row groups
     constexpr int RPG = DK / G;          // rows of S per thread
     __shared__ float part[G][DV];
+    __shared__ float sq[DV / 64];
     const long bh = blockIdx.x;
     const int tid = threadIdx.x, j = tid % DV, g = tid / DV;
     float* s = S + (size_t)bh * DK * DV;
@@ -1243,26 +1245,44 @@ __global__ __launch_bounds__(256) void bf16_step_kernel(const bf16* __restrict__
     }
     part[g][j] = acc;
     __syncthreads();
-    if (g == 0) {
-        float t = 0.f;
+    float t = 0.f;
+    if (g == 0) {                        // the first DV threads (one or two whole waves) hold the output row
 #pragma unroll
         for (int gg = 0; gg < G; ++gg) t += part[gg][j];
-        o[bh * DV + j] = (bf16)t;
+        if (GATE) {
+            float ss = t * t;
+#pragma unroll
+            for (int m = 32; m > 0; m >>= 1) ss += __shfl_xor(ss, m);
+            if ((tid & 63) == 0) sq[tid >> 6] = ss;
+        }
     }
+    if (GATE) {
+        __syncthreads();
+        if (g == 0) {
+            float tot = 0.f;
+#pragma unroll
+            for (int x = 0; x < DV / 64; ++x) tot += sq[x];
+            t *= __builtin_amdgcn_rsqf(fmaf(tot, 1.f / DV, eps)) * (float)gate[bh * DV + j];
+        }
+    }
+    if (g == 0) o[bh * DV + j] = (bf16)t;
 }
 
-hipError_t launch_bf16_step(const void* q, const void* k, const void* v, float* S, void* o, long BH, int dk, int dv,
-                            hipStream_t st)
+hipError_t launch_bf16_step(const void* q, const void* k, const void* v, float* S, void* o, const void* gate, float eps,
+                            long BH, int dk, int dv, hipStream_t st)
 {
-    const bf16 *qq = (const bf16*)q, *kk = (const bf16*)k, *vv = (const bf16*)v;
+    const bf16 *qq = (const bf16*)q, *kk = (const bf16*)k, *vv = (const bf16*)v, *gg = (const bf16*)gate;
     bf16* oo = (bf16*)o;
     ProfScope prof(KID_STEP_BF16, st);
-    if (dk == 64 && dv == 64) hipLaunchKernelGGL((bf16_step_kernel<64, 64>), dim3((unsigned)BH), dim3(256), 0, st, qq, kk, vv, S, oo);
-    else if (dk == 64 && dv == 128) hipLaunchKernelGGL((bf16_step_kernel<64, 128>), dim3((unsigned)BH), dim3(256), 0, st, qq, kk, vv, S, oo);
-    else if (dk == 128 && dv == 64) hipLaunchKernelGGL((bf16_step_kernel<128, 64>), dim3((unsigned)BH), dim3(256), 0, st, qq, kk, vv, S, oo);
-    else if (dk == 128 && dv == 128) hipLaunchKernelGGL((bf16_step_kernel<128, 128>), dim3((unsigned)BH), dim3(256), 0, st, qq, kk, vv, S, oo);
-    else return hipErrorInvalidValue;
-    return hipGetLastError();
+#define CHELA_STEP(DK_, DV_)                                                                                          \
+    if (dk == DK_ && dv == DV_) {                                                                                     \
+        if (gate) hipLaunchKernelGGL((bf16_step_kernel<DK_, DV_, true>), dim3((unsigned)BH), dim3(256), 0, st, qq, kk, vv, S, oo, gg, eps); \
+        else hipLaunchKernelGGL((bf16_step_kernel<DK_, DV_, false>), dim3((unsigned)BH), dim3(256), 0, st, qq, kk, vv, S, oo, gg, eps);     \
+        return hipGetLastError();                                                                                     \
+    }
+    CHELA_STEP(64, 64) CHELA_STEP(64, 128) CHELA_STEP(128, 64) CHELA_STEP(128, 128)
+#undef CHELA_STEP
+    return hipErrorInvalidValue;
 }
 
 // =============================================================================================== launchers

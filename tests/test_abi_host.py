@@ -318,3 +318,16 @@ def test_stream_probe_argument_errors(L):
     assert f((vp * 1)(A + 4), 1, outs, 1, 1024, None) == -5
     assert f(ins, 4, (vp * 2)(A + 4 * SZ, A + 4 * SZ + 512), 2, 1024, None) == -6
     assert f(ins, 4, (vp * 1)(A + SZ), 1, 1024, None) == -6
+
+
+def test_step_gated_argument_errors(L):
+    f = L.chela_linattn_step_gated
+    q, k, v, g, S, y = (A + i * SZ for i in range(6))
+    assert f(q, k, v, None, S, y, 1e-5, 1, 1, 64, 64, None) == -1
+    assert f(q, k, v, g, None, y, 1e-5, 1, 1, 64, 64, None) == -1
+    assert f(q, k, v, g, S, y, -1.0, 1, 1, 64, 64, None) == -2
+    assert f(q, k, v, g, S, y, 1e-5, 1, 1, 64, 96, None) == -3
+    assert f(q, k, v, g + 2, S, y, 1e-5, 1, 1, 64, 64, None) == -5
+    assert f(q, k, v, g, S, g, 1e-5, 1, 1, 64, 64, None) == -6
+    assert f(q, k, v, g, g, y, 1e-5, 1, 1, 64, 64, None) == -6
+    assert f(None, None, None, None, None, None, 1e-5, 0, 4, 64, 64, None) == 0

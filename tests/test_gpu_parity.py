@@ -841,3 +841,35 @@ def test_fwd_gated_lm_full_size_sampled():
         _check("Y", Y[b:b + 1, hd:hd + 1], oracle_layer.gated_fwd(Qn, Kn, Vn, Gn, EPS)[1], "bf16")
     # against the two-call route the only difference is one more rounding of O to bf16
     assert oracle.rel_l2(to_f64_numpy(Y), to_f64_numpy(Yb)) <= 4e-3
+
+
+@pytest.mark.parametrize("dims", [(64, 64), (64, 128), (128, 64), (128, 128)])
+def test_decode_step_gated(dims):
+    # decode with the Eq. 9 epilogue: every step against the oracle's step followed by its Norm(.) * g, the state
+    # against the oracle's, and the whole run against the gated forward over the same tokens
+    dk, dv = dims
+    B, H, T = 2, 3, 24
+    gen = torch.Generator(device="cpu")
+    gen.manual_seed(19)
+    q = (torch.randn(T, B, H, dk, generator=gen) / 8).to(torch.bfloat16)
+    k = (torch.randn(T, B, H, dk, generator=gen) / 8).to(torch.bfloat16)
+    v = torch.randn(T, B, H, dv, generator=gen).to(torch.bfloat16)
+    g = torch.nn.functional.silu(torch.randn(T, B, H, dv, generator=gen)).to(torch.bfloat16)
+    S = torch.zeros(B, H, dk, dv, dtype=torch.float32, device="cuda")
+    S_plain = S.clone()
+    ref_S = np.zeros((B, H, dk, dv))
+    outs, refs = [], []
+    for t in range(T):
+        outs.append(binding.chela_linattn_step_gated(q[t].cuda(), k[t].cuda(), v[t].cuda(), g[t].cuda(), S, EPS))
+        binding.chela_linattn_step(q[t].cuda(), k[t].cuda(), v[t].cuda(), S_plain)
+        ro, ref_S = oracle.step(to_f64_numpy(q[t]), to_f64_numpy(k[t]), to_f64_numpy(v[t]), ref_S)
+        refs.append(oracle_layer.gate_norm_fwd(ro, to_f64_numpy(g[t]), EPS))
+    torch.cuda.synchronize()
+    err_y = oracle.rel_l2(np.stack([to_f64_numpy(o) for o in outs]), np.stack(refs))
+    print("\ngated decode dk%d dv%d: rel-L2 y %.3e" % (dk, dv, err_y), flush=True)
+    assert err_y <= 2e-2 and err_y <= 6e-3
+    assert torch.equal(S, S_plain)                      # the epilogue does not touch the state update
+    tok = lambda x: x.permute(1, 2, 0, 3).contiguous().cuda()
+    Y, _, _ = binding.chela_linattn_fwd_gated(tok(q), tok(k), tok(v), tok(g), EPS)
+    Y_steps = torch.stack(outs, dim=2).double()
+    assert float((Y.double() - Y_steps).norm() / Y_steps.norm()) < 6e-3
