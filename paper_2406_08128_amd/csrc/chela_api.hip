@@ -24,7 +24,7 @@ static long sweep_slots(int dk, int dv, int chunk, int dtype, bool is_bwd)
     if (dtype != CHELA_DTYPE_BF16) return 512;
     const bool narrow = (dk == 64 && dv == 64), wide = (dk == 128 && dv == 128);
     int per_cu;
-    if (is_bwd) per_cu = (narrow && chunk == 64) ? 2 : 1;
+    if (is_bwd) per_cu = (chunk == 64 && !wide) ? 2 : 1;      // (one width of 128: the two states share an LDS tile)
     else if (chunk == 64) per_cu = narrow ? 4 : (wide ? 1 : 2);
     else per_cu = narrow ? 2 : 1;
     return 256L * per_cu;

@@ -638,7 +638,10 @@ __device__ __forceinline__ void fwd_sweep_body(const bf16* __restrict__ Qb, cons
 template <int C, int DK, int DV, bool ZQK = false>
 struct BwdLds {
     static constexpr int LDK = DK + PAD, LDV = DV + PAD;
-    static constexpr int TILES = (2 * C * LDK + 2 * C * LDV + 2 * DK * LDV) * 2;
+    // With one head width of 128 the two published states share ONE tile (S while dQ is formed, then R for dK and dV,
+    // two more barriers per chunk): that brings the workgroup under 80 KB, so that two of them fit a compute unit.
+    static constexpr bool SHARE = (C == 64 && DK != DV);
+    static constexpr int TILES = (2 * C * LDK + 2 * C * LDV + (SHARE ? 1 : 2) * DK * LDV) * 2;
     static constexpr int BYTES = TILES + (ZQK ? C * LDK * 2 + 4 * DK * 4 : 0);
 };
 
@@ -698,8 +701,9 @@ __device__ __forceinline__ void bwd_sweep_body(const bf16* __restrict__ Qb, cons
     bf16* sK = sQ + C * LDK;
     bf16* sV = sK + C * LDK;
     bf16* sG = sV + C * LDV;           // dO
-    bf16* sS = sG + C * LDV;           // S  [i][j] bf16
-    bf16* sR = sS + DK * LDV;          // R  [i][j] bf16
+    constexpr bool SHARE = BwdLds<C, DK, DV, false>::SHARE;
+    bf16* sS = sG + C * LDV;                        // S  [i][j] bf16
+    bf16* sR = SHARE ? sS : sS + DK * LDV;          // R  [i][j] bf16 (the same tile, later in the chunk, with SHARE)
     const int rb = w % WT, cg = w / WT;
     const int n_ch = (ntok + C - 1) / C;
 
@@ -774,7 +778,7 @@ __device__ __forceinline__ void bwd_sweep_body(const bf16* __restrict__ Qb, cons
         rv.store(sV, tid);
         rg.store(sG, tid);
         // R (state after this chunk) is already final: publish it as bf16 [i][j]
-        state_to_lds_T<DV, DK, false>(sR, accRT, w, lane);
+        if (!SHARE) state_to_lds_T<DV, DK, false>(sR, accRT, w, lane);
         __syncthreads();
         if (ci > 0) {   // every chunk but a segment's last is complete
             rq.load(Qb + (size_t)(c0 - C) * ldk, ldk, C, tid);
@@ -829,6 +833,11 @@ __device__ __forceinline__ void bwd_sweep_body(const bf16* __restrict__ Qb, cons
 #pragma unroll
                 for (int n = 0; n < NI; ++n) store_tile_T(rows, ldk, (cg * NI + n) * 32, acc[n], valid, lane);
             }
+        }
+        if (SHARE) {
+            __syncthreads();            // every wave is done with S ...
+            state_to_lds_T<DV, DK, false>(sR, accRT, w, lane);
+            __syncthreads();            // ... and R has taken its place
         }
         // ---------------- dK^T for key block sb = rb:  dK^T = Q^T dP + R V^T
         {
@@ -1070,8 +1079,12 @@ void bf16_fwd_gated_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ 
                                                (size_t)H * DK, DK, DV, p1 - p0, lds, tid, w, lane, G + rv, Y + rv, eps);
 }
 
+// (shapes whose LDS footprint lets two workgroups share a compute unit are asked to keep to the 256 registers that
+// allows)
 template <int C, int DK, int DV, bool ZQK, bool NH>
-__global__ __launch_bounds__(256) void bf16_bwd_sweep_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K,
+__global__ __launch_bounds__(256)
+__attribute__((amdgpu_waves_per_eu((BwdLds<C, DK, DV, ZQK>::SHARE && BwdLds<C, DK, DV, ZQK>::BYTES <= 81920 && !NH) ? 2 : 1)))
+void bf16_bwd_sweep_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K,
                                                             const bf16* __restrict__ V, const bf16* __restrict__ dO,
                                                             bf16* __restrict__ dQ, bf16* __restrict__ dK,
                                                             bf16* __restrict__ dV, const float* __restrict__ Send,
