@@ -178,6 +178,9 @@ def main():
                          "Sec. 4.2 at the workload's width (B x H*dk channels x N steps); decode: single-token steps of the recurrent form")
     ap.add_argument("--decode-batch", type=int, default=256, help="sequences decoded together in --mode decode")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step into a HIP graph (caller-owned scratch) and time replays of it instead of "
+                         "eager launches")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also run the library's plain copy kernel on a buffer of this many MiB (3 launches): the "
                          "kernel of known size that rocprofv3 byte counters are calibrated against")
@@ -316,6 +319,22 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    eager_step = step
+    if args.graph:
+        # nothing may be allocated while capturing: hand the library a scratch buffer of the size a first eager step
+        # made it allocate, then record the step once
+        step()
+        torch.cuda.synchronize()
+        ws_buf = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
+        binding.chela_set_workspace(ws_buf)
+        cap_stream = torch.cuda.Stream()
+        with torch.cuda.stream(cap_stream):
+            step()
+        cap_stream.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=cap_stream):
+            step()
+        step = graph.replay
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -332,7 +351,7 @@ def main():
     binding.chela_profile_reset()
     binding.chela_profile_enable(True)
     for _ in range(args.steps):
-        step()
+        eager_step()
     torch.cuda.synchronize()
     prof = binding.chela_profile_read()
     binding.chela_profile_enable(False)

@@ -873,3 +873,48 @@ def test_decode_step_gated(dims):
     Y, _, _ = binding.chela_linattn_fwd_gated(tok(q), tok(k), tok(v), tok(g), EPS)
     Y_steps = torch.stack(outs, dim=2).double()
     assert float((Y.double() - Y_steps).norm() / Y_steps.norm()) < 6e-3
+
+
+# ------------------------------------------------------------------------------------------ HIP graph capture
+def test_training_step_replays_from_a_hip_graph():
+    # The calls only enqueue kernels (no allocation, no synchronisation, no memset once the scratch is there), so a
+    # step can be captured and replayed.  Every replay is checked against the eager result, with eager work of the
+    # library on other inputs between the replays.
+    w = _small("bf16", N=6000, B=2, H=3)
+    d = _dev(make_inputs(w))
+    other = _dev(make_inputs(shrink(w, seed=w.seed + 1)))
+    gx = _dev(make_gate_inputs(w))
+    O_ref = binding.chela_linattn_fwd(d["Q"], d["K"], d["V"])
+    g_ref = binding.chela_linattn_bwd(d["Q"], d["K"], d["V"], d["dO"])
+    Y_ref, _, _ = binding.chela_linattn_fwd_gated(d["Q"], d["K"], d["V"], gx["G"], EPS)
+    need = binding.chela_linattn_workspace_bytes(w.B, w.H, w.N, w.dk, w.dv, 64, True, binding.DTYPE_BF16)
+    buf = torch.empty(need, dtype=torch.uint8, device="cuda")
+    O, Y = torch.empty_like(O_ref), torch.empty_like(O_ref)
+    dQ, dK, dV = (torch.empty_like(t) for t in g_ref)
+    torch.cuda.synchronize()
+    try:
+        binding.chela_set_workspace(buf)                    # caller-owned scratch: nothing is allocated under capture
+        s = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(s):
+            binding.chela_linattn_fwd(d["Q"], d["K"], d["V"], O=O)      # warm-up on the capture stream
+        s.synchronize()
+        with torch.cuda.graph(graph, stream=s):
+            binding.chela_linattn_fwd(d["Q"], d["K"], d["V"], O=O)
+            binding.chela_linattn_bwd(d["Q"], d["K"], d["V"], d["dO"], dQ=dQ, dK=dK, dV=dV)
+            binding.chela_linattn_fwd_gated(d["Q"], d["K"], d["V"], gx["G"], EPS, Y=Y)
+        for rep in range(4):
+            for t in (O, Y, dQ, dK, dV):
+                t.fill_(float("nan"))
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(O, O_ref) and torch.equal(Y, Y_ref), rep
+            for a, b in zip((dQ, dK, dV), g_ref):
+                assert torch.equal(a, b), rep
+            # eager use of the same scratch in between
+            binding.chela_linattn_bwd(other["Q"], other["K"], other["V"], other["dO"])
+            torch.cuda.synchronize()
+    finally:
+        torch.cuda.synchronize()
+        binding.chela_set_workspace(None)
