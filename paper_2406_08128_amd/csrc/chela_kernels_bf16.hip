@@ -185,22 +185,27 @@ struct TileRegs {
     // `tile` points at the first row; rows >= valid_rows read as zero.
     // `ld` is the distance between rows in elements: D for [B,H,N,d] tensors (the tile is then one contiguous block
     // and the address below folds to 16 * x), H * D for [B,N,H,d] ones.
-    static __device__ __forceinline__ const uint4* at(const bf16* tile, int ld, int x)
+    // Vector n of thread tid is vector tid + 256 n of the tile.  In the strided case the address is split into a
+    // part that is the same for the whole workgroup (tile start + n * (256 / VPR) rows: scalar registers) and one
+    // 32-bit per-thread offset shared by all n, instead of one 64-bit address per vector.
+    static __device__ __forceinline__ const uint4* at(const bf16* tile, int ld, int tid, int n)
     {
-        if (ld == D) return reinterpret_cast<const uint4*>(tile) + x;      // (decided at compile time for [B,H,N,d])
-        return reinterpret_cast<const uint4*>(tile + (x / VPR) * ld + (x % VPR) * 8);
+        if (ld == D) return reinterpret_cast<const uint4*>(tile) + (tid + 256 * n);   // (decided at compile time for [B,H,N,d])
+        const bf16* rows = tile + (size_t)(n * (256 / VPR)) * (size_t)ld;
+        const unsigned off = (unsigned)(tid / VPR) * (unsigned)ld + (unsigned)(tid % VPR) * 8u;
+        return reinterpret_cast<const uint4*>(rows + off);
     }
     __device__ __forceinline__ void load(const bf16* tile, int ld, int valid_rows, int tid)
     {
         if (valid_rows >= C) {
 #pragma unroll
-            for (int n = 0; n < NV; ++n) v[n] = ldg16<NTL>(at(tile, ld, tid + 256 * n));
+            for (int n = 0; n < NV; ++n) v[n] = ldg16<NTL>(at(tile, ld, tid, n));
         } else {
             const int lim = valid_rows * VPR;
 #pragma unroll
             for (int n = 0; n < NV; ++n) {
                 const int x = tid + 256 * n;
-                v[n] = x < lim ? ldg16<NTL>(at(tile, ld, x)) : make_uint4(0, 0, 0, 0);
+                v[n] = x < lim ? ldg16<NTL>(at(tile, ld, tid, n)) : make_uint4(0, 0, 0, 0);
             }
         }
     }
@@ -209,7 +214,7 @@ struct TileRegs {
     __device__ __forceinline__ void load_full(const bf16* tile, int ld, int tid)
     {
 #pragma unroll
-        for (int n = 0; n < NV; ++n) v[n] = ldg16<NTL>(at(tile, ld, tid + 256 * n));
+        for (int n = 0; n < NV; ++n) v[n] = ldg16<NTL>(at(tile, ld, tid, n));
     }
     __device__ __forceinline__ void store(bf16* lds, int tid) const
     {
@@ -238,7 +243,7 @@ struct TileRegs {
 __device__ __forceinline__ void store_tile_T(bf16* rows, int ld, int col0, const f32x16& acc, int valid_rows, int lane)
 {
     const int r = lane & 31, h = lane >> 5;
-    bf16* dst = rows + (size_t)r * ld + col0 + 8 * h;
+    bf16* dst = rows + ((unsigned)r * (unsigned)ld + (unsigned)(col0 + 8 * h));   // uniform base + 32-bit lane offset
 #pragma unroll
     for (int ap = 0; ap < 2; ++ap) {
         const unsigned x0 = pack2(acc[8 * ap + 0], acc[8 * ap + 1]), x1 = pack2(acc[8 * ap + 2], acc[8 * ap + 3]);
@@ -996,7 +1001,7 @@ __device__ __forceinline__ size_t row_offset(bool nh, long bh, int H, int N, int
 
 // NT: the two tensors are not read again after this kernel (streaming hint on their loads).
 template <int DA, int DB, int AFF, bool NH, bool NT>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((DA == 64 && DB == 64) ? ((AFF == 0 && !NH) ? 6 : 5) : 1)))
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((DA == 64 && DB == 64) ? (AFF == 0 ? 6 : 5) : 1)))
 void bf16_seg_state_kernel(SegStateArgs args, int N, int seg_len, int n_seg)
 {
     __shared__ __attribute__((aligned(16))) unsigned char lds[PrepassLds<DA, DB, AFF>::BYTES];
