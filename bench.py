@@ -84,6 +84,43 @@ def bench_decode(args, w, torch, binding):
         "cpu_baseline": None}))
 
 
+def bench_n_sweep(args, w, torch, binding):
+    """The workload's shape at sequence lengths 2048 ... 65536 (B, H, widths fixed): time per token must not depend on
+    N once the GPU is full (the linear-cost claim of Sec. 1 and of the ablation on hardware efficiency)."""
+    from paper_2406_08128_amd.workloads import make_inputs, shrink
+    rows = []
+    for N in (2048, 4096, 8192, 16384, 32768, 65536):
+        wn = shrink(w, N=N)
+        d = {k: v.cuda() for k, v in make_inputs(wn, with_dO=True).items()}
+        O = torch.empty_like(d["V"])
+        dQ, dK, dV = torch.empty_like(d["Q"]), torch.empty_like(d["K"]), torch.empty_like(d["V"])
+
+        def step():
+            binding.chela_linattn_fwd(d["Q"], d["K"], d["V"], O=O, chunk=args.chunk)
+            binding.chela_linattn_bwd(d["Q"], d["K"], d["V"], d["dO"], dQ=dQ, dK=dK, dV=dV, chunk=args.chunk)
+        for _ in range(args.warmup):
+            step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        rows.append({"N": N, "ms_per_step": round(ms, 4), "ns_per_token_head": round(ms * 1e6 / (wn.B * wn.H * N), 4),
+                     "tokens_per_s": round(wn.B * N / (ms * 1e-3), 1)})
+        del d, O, dQ, dK, dV
+    ref = [r for r in rows if r["N"] == 16384][0]["ns_per_token_head"]
+    for r in rows:
+        r["vs_N16384"] = round(r["ns_per_token_head"] / ref, 3)
+    print(json.dumps({
+        "metric": "causal linear-attn fwd+bwd time per token-head over sequence length", "unit": "ns/token-head",
+        "value": ref, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "higher_is_better": False,
+        "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": "%s shape (B%d H%d dk%d dv%d), N swept, fwd+bwd, chunk %d"
+                               % (w.name, w.B, w.H, w.dk, w.dv, args.chunk)},
+        "sweep": rows, "cpu_baseline": None}))
+
+
 def bench_conv(args, w, torch, binding):
     """Short-long convolution Z = K_l(silu(K_s(X))) at the workload's width: B sequences x (H*dk) channels x N steps."""
     from paper_2406_08128_amd.workloads import make_conv_inputs, to_f64_numpy
@@ -168,7 +205,7 @@ def main():
     ap.add_argument("--workload", default="lm_bf16")
     ap.add_argument("--chunk", type=int, default=64)
     ap.add_argument("--mode", default="train", choices=["train", "train_saved", "train_state", "train_bnhd", "train_z", "train_z_saved", "noncausal", "decode",
-                             "conv", "conv_train", "gated", "gated_unfused", "train_layer", "train_layer_unfused"],
+                             "conv", "conv_train", "gated", "gated_unfused", "train_layer", "train_layer_unfused", "n_sweep"],
                     help="train: fwd+bwd (the headline); train_saved: the same step through chela_linattn_fwd_save / "
                          "_bwd_saved (the forward leaves the boundary states, the backward skips its pass over K, V); "
                          "train_state: the same through the carried-state entry points "
@@ -202,6 +239,8 @@ def main():
         return bench_decode(args, w, torch, binding)
     if args.mode in ("conv", "conv_train"):
         return bench_conv(args, w, torch, binding)
+    if args.mode == "n_sweep":
+        return bench_n_sweep(args, w, torch, binding)
     has_bwd = w.backward          # the headline workload runs forward + backward; forward-only workloads time the forward
     if args.mode in ("gated", "gated_unfused"):
         has_bwd = False           # Eq. 9 at inference
