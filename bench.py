@@ -205,7 +205,7 @@ def main():
     ap.add_argument("--workload", default="lm_bf16")
     ap.add_argument("--chunk", type=int, default=64)
     ap.add_argument("--mode", default="train", choices=["train", "train_saved", "train_state", "train_bnhd", "train_z", "train_z_saved", "noncausal", "decode",
-                             "conv", "conv_train", "gated", "gated_unfused", "train_layer", "train_layer_unfused", "n_sweep"],
+                             "conv", "conv_train", "gated", "gated_unfused", "train_layer", "train_layer_unfused", "n_sweep", "nc_gated", "nc_gated_unfused"],
                     help="train: fwd+bwd (the headline); train_saved: the same step through chela_linattn_fwd_save / "
                          "_bwd_saved (the forward leaves the boundary states, the backward skips its pass over K, V); "
                          "train_state: the same through the carried-state entry points "
@@ -242,7 +242,7 @@ def main():
     if args.mode == "n_sweep":
         return bench_n_sweep(args, w, torch, binding)
     has_bwd = w.backward          # the headline workload runs forward + backward; forward-only workloads time the forward
-    if args.mode in ("gated", "gated_unfused"):
+    if args.mode in ("gated", "gated_unfused", "nc_gated", "nc_gated_unfused"):
         has_bwd = False           # Eq. 9 at inference
     elif args.mode in ("train_layer", "train_layer_unfused"):
         has_bwd = True
@@ -292,6 +292,18 @@ def main():
         else:
             def step():
                 binding.chela_linattn_noncausal_fwd(d["Q"], d["K"], d["V"], O=O)
+    elif args.mode in ("nc_gated", "nc_gated_unfused"):
+        # the non-causal form with the Eq. 9 epilogue (what a classifier runs at inference)
+        assert w.dtype == "bf16", "--mode nc_gated needs a bf16 workload"
+        gate = make_gate_inputs(w)["G"].cuda()
+        Y = torch.empty_like(O)
+        if args.mode == "nc_gated":
+            def step():
+                binding.chela_linattn_noncausal_fwd_gated(d["Q"], d["K"], d["V"], gate, 1e-5, Y=Y)
+        else:
+            def step():
+                binding.chela_linattn_noncausal_fwd(d["Q"], d["K"], d["V"], O=O)
+                binding.chela_gate_norm_fwd(O, gate, 1e-5, Y=Y)
     elif args.mode in ("gated", "gated_unfused"):
         # Eq. 9 at inference: Y = Norm(O) * G; fused into the forward, or as a second pass over a stored O
         assert w.dtype == "bf16", "--mode gated needs a bf16 workload"
@@ -410,6 +422,9 @@ def main():
     th = w.token_heads
     if args.mode == "noncausal":    # the apply kernel reads one tensor and writes one; forward: Q in, O out
         dom, dom_b = "bf16_apply_state_kernel", es * (w.dk + w.dv)
+    elif args.mode in ("nc_gated", "nc_gated_unfused"):
+        dom, dom_b = "bf16_apply_state_kernel", es * (w.dk + (2 if args.mode == "nc_gated" else 1) * w.dv)
+        fwd_b = es * (2 * w.dk + (3 if args.mode == "nc_gated" else 5) * w.dv)
     elif w.dtype != "bf16":
         dom, dom_b = "f32_sweep_kernel", fwd_b
     elif args.mode in ("train_layer", "train_layer_unfused"):
@@ -432,7 +447,7 @@ def main():
     if dom == "bf16_bwd_sweep_kernel":
         n_rd, n_wr = (3, 2) if args.mode in ("train_z", "train_z_saved", "train_layer", "train_layer_unfused") else (4, 3)
     elif dom == "bf16_apply_state_kernel":
-        n_rd, n_wr = 1, 1
+        n_rd, n_wr = (2, 1) if args.mode == "nc_gated" else (1, 1)
     else:
         n_rd, n_wr = (4, 1) if args.mode == "gated" else (3, 1)
     each = (dom_b * th // (n_rd + n_wr)) // 16 * 16
@@ -470,7 +485,13 @@ def main():
     cpu_reps = 1
     if not args.no_cpu_baseline:
         import oracle
-        if args.mode == "noncausal":
+        if args.mode in ("nc_gated", "nc_gated_unfused"):
+            from oracle import layer as oracle_layer
+            Qn, Kn, Vn, Gg = (to_f64_numpy(t) for t in (x["Q"], x["K"], x["V"], gate))
+            c0 = time.perf_counter()
+            oracle_layer.gate_norm_fwd(oracle_layer.noncausal_fwd(Qn, Kn, Vn), Gg, 1e-5)
+            c1 = time.perf_counter()
+        elif args.mode == "noncausal":
             from oracle import layer as oracle_layer
             Qn, Kn, Vn = (to_f64_numpy(x[n]) for n in ("Q", "K", "V"))
             Gn = to_f64_numpy(x["dO"]) if has_bwd else None
@@ -522,14 +543,15 @@ def main():
                          % ("fwd+bwd" if has_bwd else "fwd", w.B * w.H, cpu_reps, "" if cpu_reps == 1 else "s")}
 
     out = {
-        "metric": "%s linear-attn %s tokens/s" % ("non-causal" if args.mode == "noncausal" else "causal",
+        "metric": "%s linear-attn %s tokens/s" % ("non-causal" if args.mode in ("noncausal", "nc_gated", "nc_gated_unfused") else "causal",
                                                   "fwd+bwd" if has_bwd else "fwd")
                   + (" (carried-state entry points)" if args.mode == "train_state" else "")
                   + (" (forward saves the boundary states)" if args.mode == "train_saved" else "")
                   + (" ([B,N,H,d] tensors)" if args.mode == "train_bnhd" else "")
                   + (" (Q, K formed on chip from Z)" if args.mode == "train_z" else "")
                   + (" (Q, K formed on chip from Z; forward saves the boundary states)" if args.mode == "train_z_saved" else "")
-                  + (" (Y = Norm(O) * G inside the forward)" if args.mode == "gated" else "")
+                  + (" (Y = Norm(O) * G inside the forward)" if args.mode in ("gated", "nc_gated") else "")
+                  + (" (Y = Norm(O) * G as a second pass)" if args.mode == "nc_gated_unfused" else "")
                   + (" (Y = Norm(O) * G as a second pass)" if args.mode == "gated_unfused" else "")
                   + (" (layer core: Z, V, G -> Y and all gradients, prologue and epilogue fused)" if args.mode == "train_layer" else "")
                   + (" (layer core: Z, V, G -> Y and all gradients, epilogue as a separate pass)" if args.mode == "train_layer_unfused" else ""),

@@ -199,6 +199,11 @@ int chela_linattn_fwd_gated(const void *Q, const void *K, const void *V, const v
                             float eps, int B, int H, int N, int dk, int dv, int chunk, void *stream);
 int chela_linattn_zfwd_gated(const void *Z, const float *affine, const void *V, const void *G, void *O, void *Y,
                              void *saved, float eps, int B, int H, int N, int dk, int dv, int chunk, void *stream);
+/* The non-causal form with the same epilogue, Y = Norm(Q (K^T V)) * G (what the paper's classifiers run): the second
+ * kernel of chela_linattn_noncausal_fwd normalises and gates its output tiles on the way out.  O: bf16 out or NULL.
+ * Scratch: chela_linattn_noncausal_workspace_bytes(..., 0). */
+int chela_linattn_noncausal_fwd_gated(const void *Q, const void *K, const void *V, const void *G, void *O, void *Y,
+                                      float eps, int B, int H, int N, int dk, int dv, void *stream);
 int chela_gate_norm_fwd(const void *O, const void *G, void *Y, float eps, long long rows, int dv, void *stream);
 int chela_gate_norm_bwd(const void *O, const void *G, const void *dY, void *dO, void *dG, float eps, long long rows,
                         int dv, void *stream);

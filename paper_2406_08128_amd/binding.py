@@ -76,6 +76,8 @@ def lib() -> ctypes.CDLL:
     L.chela_gate_norm_fwd.restype = i
     L.chela_gate_norm_bwd.argtypes = [vp] * 5 + [f32, ctypes.c_longlong, i, vp]
     L.chela_gate_norm_bwd.restype = i
+    L.chela_linattn_noncausal_fwd_gated.argtypes = [vp] * 6 + [f32, i, i, i, i, i, vp]
+    L.chela_linattn_noncausal_fwd_gated.restype = i
     L.chela_linattn_step_gated.argtypes = [vp, vp, vp, vp, vp, vp, f32, i, i, i, i, vp]
     L.chela_linattn_step_gated.restype = i
     L.chela_linattn_noncausal_fwd.argtypes = [vp, vp, vp, vp, i, i, i, i, i, vp]
@@ -452,6 +454,17 @@ def chela_linattn_zfwd_gated(Z, affine, V, G, eps, want_O=False, want_saved=Fals
                                               Y.data_ptr(), _ptr(saved), float(eps), B, H, N, dk, dv, 64,
                                               _stream_ptr(stream)))
     return Y, O, saved
+
+
+def chela_linattn_noncausal_fwd_gated(Q, K, V, G, eps, want_O=False, Y=None, O=None, stream=None):
+    """(Y, O) with Y = Norm(Q (K^T V)) * G, the non-causal form with the Eq. 9 epilogue; O is None unless asked for."""
+    B, H, N, dk, dv = _dims(Q, K, V)
+    _bf16_only(Q, "the gated non-causal forward")
+    Y, O, _ = _gated_outputs(V, G, want_O, False, dk, Y, O, None)
+    with torch.cuda.device(Q.device):
+        _check(lib().chela_linattn_noncausal_fwd_gated(Q.data_ptr(), K.data_ptr(), V.data_ptr(), G.data_ptr(), _ptr(O),
+                                                       Y.data_ptr(), float(eps), B, H, N, dk, dv, _stream_ptr(stream)))
+    return Y, O
 
 
 def _gate_rows(O, G):

@@ -548,6 +548,28 @@ static int noncausal_common(const void* Q, const void* K, const void* V, const v
     return e == hipSuccess ? CHELA_OK : CHELA_ERR_HIP;
 }
 
+// Non-causal forward with the Eq. 9 epilogue: Y = Norm(Q (K^T V)) * G; O optional.
+static int noncausal_gated_common(const void* Q, const void* K, const void* V, const void* G, void* O, void* Y,
+                                  float eps, int B, int H, int N, int dk, int dv, void* stream)
+{
+    if (!(eps >= 0.f) || !std::isfinite(eps)) return CHELA_ERR_BAD_SHAPE;
+    const size_t th = (B > 0 && H > 0 && N > 0) ? (size_t)B * H * N : 0;
+    const void* in_v[4] = {Q, K, V, G};
+    const size_t inb[4] = {th * dk * 2, th * dk * 2, th * dv * 2, th * dv * 2};
+    void* out_v[2] = {Y, O ? O : Y};
+    const size_t outb[2] = {th * dv * 2, O ? th * dv * 2 : 0};
+    bool empty = false;
+    int rc = validate(in_v, inb, 4, out_v, outb, 2, B, H, N, dk, dv, 64, CHELA_DTYPE_BF16, &empty);
+    if (rc != CHELA_OK || empty) return rc;
+    const long BH = (long)B * H;
+    Plan plan = make_noncausal_plan(BH, N, dk, dv, false);
+    float* ws = nullptr;
+    rc = get_workspace(plan.ws_bytes, &ws);
+    if (rc != CHELA_OK) return rc;
+    return launch_bf16_noncausal_fwd(Q, K, V, O, BH, N, dk, dv, plan, ws, (hipStream_t)stream, G, Y, eps) == hipSuccess
+               ? CHELA_OK : CHELA_ERR_HIP;
+}
+
 }  // namespace chela
 
 using namespace chela;
@@ -691,6 +713,12 @@ int chela_linattn_noncausal_bwd(const void* Q, const void* K, const void* V, con
                                 void* dV, int B, int H, int N, int dk, int dv, void* stream)
 {
     return noncausal_common(Q, K, V, dO, dQ, dK, dV, true, B, H, N, dk, dv, stream);
+}
+
+int chela_linattn_noncausal_fwd_gated(const void* Q, const void* K, const void* V, const void* G, void* O, void* Y,
+                                      float eps, int B, int H, int N, int dk, int dv, void* stream)
+{
+    return noncausal_gated_common(Q, K, V, G, O, Y, eps, B, H, N, dk, dv, stream);
 }
 
 size_t chela_linattn_noncausal_workspace_bytes(int B, int H, int N, int dk, int dv, int is_bwd)

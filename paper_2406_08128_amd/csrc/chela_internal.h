@@ -83,8 +83,10 @@ inline size_t zbwd_extra_ws_bytes(long BH, const Plan& plan, int dk)
 // Non-causal form O = Q (K^T V) and its gradient.  `plan` comes from make_noncausal_plan(): n_seg / seg_len split
 // the pre-pass, ws holds one (forward) or two (backward) arrays of BH * n_seg states.
 Plan make_noncausal_plan(long BH, int N, int dk, int dv, bool is_bwd);
+// G non-null: the Eq. 9 epilogue is applied on the way out, Y = Norm(O) * G; O may then be null.
 hipError_t launch_bf16_noncausal_fwd(const void* Q, const void* K, const void* V, void* O, long BH, int N, int dk,
-                                     int dv, const Plan& plan, float* ws, hipStream_t st);
+                                     int dv, const Plan& plan, float* ws, hipStream_t st, const void* G = nullptr,
+                                     void* Y = nullptr, float eps = 0.f);
 hipError_t launch_bf16_noncausal_bwd(const void* Q, const void* K, const void* V, const void* dO, void* dQ, void* dK,
                                      void* dV, long BH, int N, int dk, int dv, const Plan& plan, float* ws,
                                      hipStream_t st);

@@ -474,14 +474,17 @@ template <int C, int DK, int DV, bool ZQK = false, bool GATE = false>
 struct FwdLds {
     static constexpr int LDK = DK + PAD, LDV = DV + PAD;
     static constexpr int TILES = (2 * C * LDK + C * LDV + DV * LDK) * 2;
-    static constexpr int BYTES = TILES + (ZQK ? 4 * DK * 4 : 0) + (GATE ? 4 * C * 4 : 0);
+    static constexpr int SMALL = (ZQK ? 4 * DK * 4 : 0) + (GATE ? 4 * C * 4 : 0);      // affine parameters, sums of squares
+    static constexpr int BYTES = TILES + SMALL + (GATE ? C * LDV * 2 : 0);            // + the gate tile
 };
 
 // GATE (Eq. 9, Y = Norm(O) * G with Norm(o) = o / sqrt(mean_j o_j^2 + eps) over the head's DV features): Gb and Yb
 // point at the gate and at the output rows of this segment; Ob may then be null (O itself is only needed by a
 // backward pass).  A token's features are spread over two half-waves and WJ waves: each wave leaves its share of
 // the sum of squares in LDS, and the gated store happens after the barrier that ends the chunk anyway -- it needs
-// nothing but registers by then -- so the epilogue costs no barrier of its own.
+// nothing but registers by then -- so the epilogue costs no barrier of its own.  The gate tile comes in like V
+// (whole 128- or 256-byte rows, one chunk ahead, via LDS) and is picked up from LDS in the order the output tile is
+// stored in; fetching it from HBM in that order directly (32 bytes per row and instruction) cost 20 % more time.
 template <int C, int DK, int DV, bool ZQK, bool SAVE, bool GATE = false>
 __device__ __forceinline__ void fwd_sweep_body(const bf16* __restrict__ Qb, const bf16* __restrict__ Kb,
                                                const bf16* __restrict__ Vb, bf16* __restrict__ Ob,
@@ -508,11 +511,14 @@ __device__ __forceinline__ void fwd_sweep_body(const bf16* __restrict__ Qb, cons
     TileRegs<C, DK, !ZQK> rq;   // Q is read once: streaming hint; with ZQK it holds Z, which the pre-pass shares
     TileRegs<C, DK> rk;         // (unused with ZQK)
     TileRegs<C, DV> rv;
+    TileRegs<C, DV, true> rg;   // GATE: the gate tile travels like V (whole lines, one chunk ahead, through LDS)
     rq.load(Qb, ldk, ntok, tid);
     if (!ZQK) rk.load(Kb, ldk, ntok, tid);
     rv.load(Vb, ldv, ntok, tid);
+    if (GATE) rg.load(Gb, ldv, ntok, tid);
     float* sAff = reinterpret_cast<float*>(lds + FwdLds<C, DK, DV, false>::TILES);
     float* sSq = sAff + (ZQK ? 4 * DK : 0);   // GATE: [WJ][C] partial sums of squares
+    bf16* sG = reinterpret_cast<bf16*>(lds + FwdLds<C, DK, DV, false>::TILES + FwdLds<C, DK, DV, ZQK, true>::SMALL);
     if (ZQK) {
         for (int x = tid; x < 4 * DK; x += 256) sAff[x] = aff[(size_t)(x / DK) * aff_stride + x % DK];
         __syncthreads();
@@ -530,6 +536,7 @@ __device__ __forceinline__ void fwd_sweep_body(const bf16* __restrict__ Qb, cons
             rk.store(sK, tid);
         }
         rv.store(sV, tid);
+        if (GATE) rg.store(sG, tid);
         state_to_lds_T<DK, DV, false>(sST, accS, w, lane);
         __syncthreads();
         const bool more = c0 + C < ntok;
@@ -537,17 +544,7 @@ __device__ __forceinline__ void fwd_sweep_body(const bf16* __restrict__ Qb, cons
             rq.load(Qb + (size_t)(c0 + C) * ldk, ldk, ntok - c0 - C, tid);
             if (!ZQK) rk.load(Kb + (size_t)(c0 + C) * ldk, ldk, ntok - c0 - C, tid);
             rv.load(Vb + (size_t)(c0 + C) * ldv, ldv, ntok - c0 - C, tid);
-        }
-        uint4 gate[GATE ? NJ : 1][2];   // this chunk's gate, in the order the output tile is stored in
-        if (GATE) {
-            // rows past the end of the sequence read the last row instead (their results are never stored)
-            const int row = min(c0 + tb * 32 + (lane & 31), ntok - 1);
-            const bf16* g = Gb + (size_t)row * ldv + 8 * (lane >> 5);
-#pragma unroll
-            for (int n = 0; n < NJ; ++n)
-#pragma unroll
-                for (int ap = 0; ap < 2; ++ap)
-                    gate[n][ap] = ldg16<true>(reinterpret_cast<const uint4*>(g + (jg * NJ + n) * 32 + 16 * ap));
+            if (GATE) rg.load(Gb + (size_t)(c0 + C) * ldv, ldv, ntok - c0 - C, tid);
         }
         bf16x8 bQ[DK / 16];   // Q rows of this wave's token block: the B operand (n = token, k = feature i)
 #pragma unroll
@@ -584,7 +581,15 @@ __device__ __forceinline__ void fwd_sweep_body(const bf16* __restrict__ Qb, cons
 #pragma unroll
             for (int n = 0; n < NJ; ++n) store_tile_T(rows, ldv, (jg * NJ + n) * 32, accO[n], valid, lane);
         }
+        uint4 gate[GATE ? NJ : 1][2];   // this chunk's gate, in the order the output tile is stored in
         if (GATE) {
+            // (read before the barrier that ends the chunk: the next chunk's gate tile overwrites this one after it)
+            const bf16* g = sG + (tb * 32 + (lane & 31)) * LDV + 8 * (lane >> 5);
+#pragma unroll
+            for (int n = 0; n < NJ; ++n)
+#pragma unroll
+                for (int ap = 0; ap < 2; ++ap)
+                    gate[n][ap] = *reinterpret_cast<const uint4*>(g + (jg * NJ + n) * 32 + 16 * ap);
             // this wave's share of sum_j O[t][j]^2: 16 features per tile and lane, the other 16 in lane ^ 32
             float ss = 0.f;
 #pragma unroll
@@ -1472,33 +1477,47 @@ static hipError_t bwd_impl(const bf16* Q, const bf16* K, const bf16* V, const bf
 // matrix per head, given either as it is (M_IS_T = false) or transposed, [DB][DA] (true).  The matrix becomes the
 // A operand (M^T, bf16, read from LDS once and kept in registers), a 64-token tile of X the B operand, the result
 // tile is Y^T and leaves through 16-byte stores.  The X tile is double-buffered in LDS: one barrier per chunk.
-template <int DA, int DB>
+template <int DA, int DB, bool GATE = false>
 struct ApplyLds {
     static constexpr int LDA = DA + PAD;
-    static constexpr int BYTES = (2 * 64 * LDA + DB * LDA) * 2;
+    static constexpr int TILES = (2 * 64 * LDA + DB * LDA) * 2;
+    static constexpr int SUMS = GATE ? 2 * 2 * 64 * 4 : 0;                  // [2][2][64] floats
+    static constexpr int BYTES = TILES + SUMS + (GATE ? 2 * 64 * (DB + PAD) * 2 : 0);   // + two gate tiles
 };
 
-template <int DA, int DB, bool M_IS_T>
+// GATE (Eq. 9): Yg = Norm(Y) * G with Norm(y) = y / sqrt(mean_j y_j^2 + eps) over the DB features of a token; Y itself
+// is then optional.  The two waves that share a token block leave their shares of the sum of squares in LDS (two
+// sets, used in turn) and the gated tile of chunk c leaves after the barrier of chunk c + 1, so the kernel still
+// meets at one barrier per chunk.
+template <int DA, int DB, bool M_IS_T, bool GATE>
 __global__ __launch_bounds__(256) void bf16_apply_state_kernel(const bf16* __restrict__ X, bf16* __restrict__ Y,
                                                               const float* __restrict__ M, size_t m_stride, int N,
-                                                              int rows_per_wg)
+                                                              int rows_per_wg, const bf16* __restrict__ G,
+                                                              bf16* __restrict__ Yg, float eps)
 {
     constexpr int C = 64, LDA = DA + PAD;
     constexpr int JB = DB / 32, NJ = JB / 2;
-    __shared__ __attribute__((aligned(16))) unsigned char lds[ApplyLds<DA, DB>::BYTES];
+    __shared__ __attribute__((aligned(16))) unsigned char lds[ApplyLds<DA, DB, GATE>::BYTES];
     bf16* sX = reinterpret_cast<bf16*>(lds);          // two buffers of C x LDA
     bf16* sMT = sX + 2 * C * LDA;                      // M^T: [DB][LDA]
+    float* sSq = reinterpret_cast<float*>(lds + ApplyLds<DA, DB, false>::TILES);   // GATE: [2][2][C]
+    constexpr int LDB = DB + PAD;
+    bf16* sG = reinterpret_cast<bf16*>(lds + ApplyLds<DA, DB, false>::TILES + ApplyLds<DA, DB, true>::SUMS);   // [2][C][LDB]
     const long bh = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int tb = w % 2, jg = w / 2;
     const int p0 = blockIdx.y * rows_per_wg, p1 = min(N, p0 + rows_per_wg), ntok = p1 - p0;
     const bf16* Xb = X + ((size_t)bh * N + p0) * DA;
-    bf16* Yb = Y + ((size_t)bh * N + p0) * DB;
+    bf16* Yb = Y ? Y + ((size_t)bh * N + p0) * DB : nullptr;
+    const bf16* Gb = GATE ? G + ((size_t)bh * N + p0) * DB : nullptr;
+    bf16* Ygb = GATE ? Yg + ((size_t)bh * N + p0) * DB : nullptr;
     const float4* M4 = reinterpret_cast<const float4*>(M + (size_t)bh * m_stride);
 
     TileRegs<C, DA, true> rx;   // X is read here for the last time: streaming loads
+    TileRegs<C, DB, true> rg;   // GATE: the gate tile travels like X (full lines in, LDS, then the order the tile is stored in)
     rx.load(Xb, DA, ntok, tid);
+    if (GATE) rg.load(Gb, DB, ntok, tid);
     for (int x = tid; x < DA * DB / 4; x += 256) {
         const float4 v = M4[x];
         if (M_IS_T) {
@@ -1522,12 +1541,39 @@ __global__ __launch_bounds__(256) void bf16_apply_state_kernel(const bf16* __res
 #pragma unroll
         for (int kk = 0; kk < DA / 16; ++kk) aM[n][kk] = ld_nat(sMT, LDA, (jg * NJ + n) * 32, kk * 16, lane);
 
+    // GATE: the tile of the previous chunk, its gate and where it goes, waiting for that chunk's sums of squares
+    f32x16 held[GATE ? NJ : 1];
+    uint4 gate[GATE ? NJ : 1][2];
+    int held_c0 = -1;
+    auto flush = [&](int par) __attribute__((always_inline)) {
+        float tot = sSq[(par * 2 + 0) * C + tb * 32 + (lane & 31)] + sSq[(par * 2 + 1) * C + tb * 32 + (lane & 31)];
+        const float rinv = __builtin_amdgcn_rsqf(fmaf(tot, 1.f / DB, eps));
+        bf16* rows = Ygb + (size_t)(held_c0 + tb * 32) * DB;
+        const int valid = ntok - (held_c0 + tb * 32);
+#pragma unroll
+        for (int n = 0; n < NJ; ++n)
+            store_tile_T(rows, DB, (jg * NJ + n) * 32, gate_tile(held[n], gate[n], rinv), valid, lane);
+    };
+
     int buf = 0;
     for (int c0 = 0; c0 < ntok; c0 += C, buf ^= 1) {
         bf16* sXb = sX + buf * C * LDA;
         rx.store(sXb, tid);
+        if (GATE) rg.store(sG + buf * C * LDB, tid);
         __syncthreads();
-        if (c0 + C < ntok) rx.load(Xb + (size_t)(c0 + C) * DA, DA, ntok - c0 - C, tid);
+        if (GATE && held_c0 >= 0) flush(buf ^ 1);      // the previous chunk's sums are complete now
+        if (c0 + C < ntok) {
+            rx.load(Xb + (size_t)(c0 + C) * DA, DA, ntok - c0 - C, tid);
+            if (GATE) rg.load(Gb + (size_t)(c0 + C) * DB, DB, ntok - c0 - C, tid);
+        }
+        if (GATE) {
+            const bf16* g = sG + buf * C * LDB + (tb * 32 + (lane & 31)) * LDB + 8 * (lane >> 5);
+#pragma unroll
+            for (int n = 0; n < NJ; ++n)
+#pragma unroll
+                for (int ap = 0; ap < 2; ++ap)
+                    gate[n][ap] = *reinterpret_cast<const uint4*>(g + (jg * NJ + n) * 32 + 16 * ap);
+        }
         f32x16 acc[NJ];
 #pragma unroll
         for (int n = 0; n < NJ; ++n) acc[n] = zero16();
@@ -1537,29 +1583,56 @@ __global__ __launch_bounds__(256) void bf16_apply_state_kernel(const bf16* __res
 #pragma unroll
             for (int n = 0; n < NJ; ++n) acc[n] = mfma(aM[n][kk], bX, acc[n]);
         }
-        bf16* rows = Yb + (size_t)(c0 + tb * 32) * DB;
-        const int valid = ntok - (c0 + tb * 32);
+        if (!GATE || Yb != nullptr) {
+            bf16* rows = Yb + (size_t)(c0 + tb * 32) * DB;
+            const int valid = ntok - (c0 + tb * 32);
 #pragma unroll
-        for (int n = 0; n < NJ; ++n) store_tile_T(rows, DB, (jg * NJ + n) * 32, acc[n], valid, lane);
+            for (int n = 0; n < NJ; ++n) store_tile_T(rows, DB, (jg * NJ + n) * 32, acc[n], valid, lane);
+        }
+        if (GATE) {
+            float ss = 0.f;
+#pragma unroll
+            for (int n = 0; n < NJ; ++n) {
+                held[n] = acc[n];
+#pragma unroll
+                for (int e = 0; e < 16; ++e) ss = fmaf(acc[n][e], acc[n][e], ss);
+            }
+            const unsigned sb = __builtin_bit_cast(unsigned, ss);
+            const u32x2 sw = __builtin_amdgcn_permlane32_swap(sb, sb, false, false);
+            const unsigned sw0 = sw[0], sw1 = sw[1];
+            if (lane < 32)
+                sSq[(buf * 2 + jg) * C + tb * 32 + lane] = __builtin_bit_cast(float, sw0) + __builtin_bit_cast(float, sw1);
+            held_c0 = c0;
+        }
+    }
+    if (GATE && held_c0 >= 0) {
+        __syncthreads();
+        flush(buf ^ 1);
     }
 }
 
 constexpr int kApplyRows = 512;   // tokens per workgroup of the apply kernel
 
 template <int DA, int DB, bool M_IS_T>
-static hipError_t run_apply(const bf16* X, bf16* Y, const float* M, size_t m_stride, long BH, int N, hipStream_t st)
+static hipError_t run_apply(const bf16* X, bf16* Y, const float* M, size_t m_stride, long BH, int N, hipStream_t st,
+                            const bf16* G = nullptr, bf16* Yg = nullptr, float eps = 0.f)
 {
     dim3 grid((unsigned)BH, (N + kApplyRows - 1) / kApplyRows);
     ProfScope prof(KID_APPLY_BF16, st);
-    hipLaunchKernelGGL((bf16_apply_state_kernel<DA, DB, M_IS_T>), grid, dim3(256), 0, st, X, Y, M, m_stride, N,
-                       kApplyRows);
+    if (G != nullptr)
+        hipLaunchKernelGGL((bf16_apply_state_kernel<DA, DB, M_IS_T, true>), grid, dim3(256), 0, st, X, Y, M, m_stride, N,
+                           kApplyRows, G, Yg, eps);
+    else
+        hipLaunchKernelGGL((bf16_apply_state_kernel<DA, DB, M_IS_T, false>), grid, dim3(256), 0, st, X, Y, M, m_stride,
+                           N, kApplyRows, G, Yg, eps);
     return hipGetLastError();
 }
 
 // plan.n_seg / seg_len describe the pre-pass split here; the totals end up in the last segment's slot.
 template <int DK, int DV>
 static hipError_t noncausal_fwd_impl(const bf16* Q, const bf16* K, const bf16* V, bf16* O, long BH, int N,
-                                     const Plan& plan, float* ws, hipStream_t st)
+                                     const Plan& plan, float* ws, hipStream_t st, const bf16* G = nullptr,
+                                     bf16* Y = nullptr, float eps = 0.f)
 {
     hipError_t e;
     SegStateArgs a{};
@@ -1569,7 +1642,7 @@ static hipError_t noncausal_fwd_impl(const bf16* Q, const bf16* K, const bf16* V
     if ((e = run_seg_state<DV, DK, 0, false, true>(a, 1, &mode, nullptr, false, BH, N, plan, st, plan.n_seg > 1)) != hipSuccess)
         return e;
     const size_t el = (size_t)DK * DV;
-    return run_apply<DK, DV, true>(Q, O, ws + (size_t)(plan.n_seg - 1) * el, plan.n_seg * el, BH, N, st);
+    return run_apply<DK, DV, true>(Q, O, ws + (size_t)(plan.n_seg - 1) * el, plan.n_seg * el, BH, N, st, G, Y, eps);
 }
 
 template <int DK, int DV>
@@ -1593,14 +1666,15 @@ static hipError_t noncausal_bwd_impl(const bf16* Q, const bf16* K, const bf16* V
 }
 
 hipError_t launch_bf16_noncausal_fwd(const void* Q, const void* K, const void* V, void* O, long BH, int N, int dk,
-                                     int dv, const Plan& plan, float* ws, hipStream_t st)
+                                     int dv, const Plan& plan, float* ws, hipStream_t st, const void* G, void* Y,
+                                     float eps)
 {
-    const bf16 *q = (const bf16*)Q, *k = (const bf16*)K, *v = (const bf16*)V;
-    bf16* o = (bf16*)O;
-    if (dk == 64 && dv == 64) return noncausal_fwd_impl<64, 64>(q, k, v, o, BH, N, plan, ws, st);
-    if (dk == 64 && dv == 128) return noncausal_fwd_impl<64, 128>(q, k, v, o, BH, N, plan, ws, st);
-    if (dk == 128 && dv == 64) return noncausal_fwd_impl<128, 64>(q, k, v, o, BH, N, plan, ws, st);
-    if (dk == 128 && dv == 128) return noncausal_fwd_impl<128, 128>(q, k, v, o, BH, N, plan, ws, st);
+    const bf16 *q = (const bf16*)Q, *k = (const bf16*)K, *v = (const bf16*)V, *g = (const bf16*)G;
+    bf16 *o = (bf16*)O, *y = (bf16*)Y;
+    if (dk == 64 && dv == 64) return noncausal_fwd_impl<64, 64>(q, k, v, o, BH, N, plan, ws, st, g, y, eps);
+    if (dk == 64 && dv == 128) return noncausal_fwd_impl<64, 128>(q, k, v, o, BH, N, plan, ws, st, g, y, eps);
+    if (dk == 128 && dv == 64) return noncausal_fwd_impl<128, 64>(q, k, v, o, BH, N, plan, ws, st, g, y, eps);
+    if (dk == 128 && dv == 128) return noncausal_fwd_impl<128, 128>(q, k, v, o, BH, N, plan, ws, st, g, y, eps);
     return hipErrorInvalidValue;
 }
 

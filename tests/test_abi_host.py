@@ -331,3 +331,16 @@ def test_step_gated_argument_errors(L):
     assert f(q, k, v, g, S, g, 1e-5, 1, 1, 64, 64, None) == -6
     assert f(q, k, v, g, g, y, 1e-5, 1, 1, 64, 64, None) == -6
     assert f(None, None, None, None, None, None, 1e-5, 0, 4, 64, 64, None) == 0
+
+
+def test_noncausal_gated_argument_errors(L):
+    f = L.chela_linattn_noncausal_fwd_gated
+    Q, K, V, G, O, Y = (A + i * SZ for i in range(6))
+    assert f(Q, K, V, None, O, Y, 1e-5, 1, 1, 64, 64, 64, None) == -1
+    assert f(Q, K, V, G, O, None, 1e-5, 1, 1, 64, 64, 64, None) == -1
+    assert f(Q, K, V, G, None, Y + 8, 1e-5, 1, 1, 64, 64, 64, None) == -5
+    assert f(Q, K, V, G, Y, Y, 1e-5, 1, 1, 64, 64, 64, None) == -6
+    assert f(Q, K, V, G, O, Q, 1e-5, 1, 1, 64, 64, 64, None) == -6
+    assert f(Q, K, V, G, O, Y, float("nan"), 1, 1, 64, 64, 64, None) == -2
+    assert f(Q, K, V, G, O, Y, 1e-5, 1, 1, 64, 64, 100, None) == -3
+    assert f(None, None, None, None, None, None, 1e-5, 1, 0, 64, 64, 64, None) == 0

@@ -918,3 +918,32 @@ def test_training_step_replays_from_a_hip_graph():
     finally:
         torch.cuda.synchronize()
         binding.chela_set_workspace(None)
+
+
+@pytest.mark.parametrize("shape", NC_SHAPES)
+def test_noncausal_fwd_gated(shape):
+    B, H, N, dk, dv = shape
+    w = shrink(WORKLOADS["lra_bf16"], B=B, H=H, N=N, dk=dk, dv=dv, seed=500 + N)
+    print("\nnon-causal gated %s" % (shape,), flush=True)
+    x, gx = make_inputs(w, with_dO=False), make_gate_inputs(w)
+    d, gd = _dev(x), _dev(gx)
+    Y, O = binding.chela_linattn_noncausal_fwd_gated(d["Q"], d["K"], d["V"], gd["G"], EPS, want_O=True)
+    Y2, O2 = binding.chela_linattn_noncausal_fwd_gated(d["Q"], d["K"], d["V"], gd["G"], EPS)
+    O_plain = binding.chela_linattn_noncausal_fwd(d["Q"], d["K"], d["V"])
+    torch.cuda.synchronize()
+    Qn, Kn, Vn, Gn = (to_f64_numpy(t) for t in (x["Q"], x["K"], x["V"], gx["G"]))
+    rO = oracle_layer.noncausal_fwd(Qn, Kn, Vn)
+    _check("O", O, rO, "bf16")
+    _check("Y", Y, oracle_layer.gate_norm_fwd(rO, Gn, EPS), "bf16")
+    assert O2 is None and torch.equal(Y2, Y) and torch.equal(O, O_plain)
+
+
+def test_noncausal_fwd_gated_lra_full_size_sampled():
+    w = WORKLOADS["lra_bf16"]
+    x, gx = make_inputs(w, with_dO=False), make_gate_inputs(w)
+    d, gd = _dev(x), _dev(gx)
+    Y, _ = binding.chela_linattn_noncausal_fwd_gated(d["Q"], d["K"], d["V"], gd["G"], EPS)
+    torch.cuda.synchronize()
+    for b, hd in ((0, 0), (17, 3), (31, 7)):
+        Qn, Kn, Vn, Gn = (to_f64_numpy(t[b:b + 1, hd:hd + 1]) for t in (x["Q"], x["K"], x["V"], gx["G"]))
+        _check("Y", Y[b:b + 1, hd:hd + 1], oracle_layer.gate_norm_fwd(oracle_layer.noncausal_fwd(Qn, Kn, Vn), Gn, EPS), "bf16")
