@@ -255,6 +255,39 @@ __device__ __forceinline__ void store_tile_T(bf16* rows, int ld, int col0, const
     }
 }
 
+// The same tile into an LDS staging area instead (rows of 64 bf16 = 128 bytes, no padding: the 16-byte pieces of a
+// row are permuted by an XOR with bits 1..3 of the row number so that neither these writes nor the row reads below
+// pile up on banks), and the staging area out to memory as whole rows: eight neighbouring lanes write one 128-byte
+// line.  store_tile_T sends 32 bytes per row and instruction; a plain streaming kernel with that store pattern loses
+// a third of its bandwidth against whole-line stores on this GPU.
+__device__ __forceinline__ int stage_at(int row, int piece) { return row * 64 + ((piece ^ ((row >> 1) & 7)) << 3); }
+
+__device__ __forceinline__ void stage_tile_T(bf16* stage, int row0, int col0, const f32x16& acc, int lane)
+{
+    const int r = lane & 31, h = lane >> 5, row = row0 + r;
+#pragma unroll
+    for (int ap = 0; ap < 2; ++ap) {
+        const unsigned x0 = pack2(acc[8 * ap + 0], acc[8 * ap + 1]), x1 = pack2(acc[8 * ap + 2], acc[8 * ap + 3]);
+        const unsigned y0 = pack2(acc[8 * ap + 4], acc[8 * ap + 5]), y1 = pack2(acc[8 * ap + 6], acc[8 * ap + 7]);
+        const u32x2 s0 = __builtin_amdgcn_permlane32_swap(x0, y0, false, false);
+        const u32x2 s1 = __builtin_amdgcn_permlane32_swap(x1, y1, false, false);
+        *reinterpret_cast<uint4*>(stage + stage_at(row, (col0 >> 3) + h + 2 * ap)) = make_uint4(s0[0], s1[0], s0[1], s1[1]);
+    }
+}
+
+// ROWS x 64 staged tile -> rows of the row-major matrix at `out` (leading dimension ld), the first valid_rows of them.
+template <int ROWS>
+__device__ __forceinline__ void flush_stage(const bf16* stage, bf16* out, int ld, int valid_rows, int tid)
+{
+#pragma unroll
+    for (int n = 0; n < ROWS * 8 / 256; ++n) {
+        const int x = tid + 256 * n, row = x >> 3, piece = x & 7;
+        if (row < valid_rows)
+            *reinterpret_cast<uint4*>(out + ((unsigned)row * (unsigned)ld + (unsigned)piece * 8u)) =
+                *reinterpret_cast<const uint4*>(stage + stage_at(row, piece));
+    }
+}
+
 // Eq. 9 epilogue on a transposed accumulator tile: every value times `scale` (the token's 1/rms) times its gate.
 // g[ap] holds the gate as store_tile_T would have stored it (8 consecutive features of this lane's token at
 // col0 + 8h + 16ap); the same half-wave exchange that produces that order also undoes it.
@@ -476,6 +509,7 @@ struct FwdLds {
     static constexpr int TILES = (2 * C * LDK + C * LDV + DV * LDK) * 2;
     static constexpr int SMALL = (ZQK ? 4 * DK * 4 : 0) + (GATE ? 4 * C * 4 : 0);      // affine parameters, sums of squares
     static constexpr int BYTES = TILES + SMALL + (GATE ? C * LDV * 2 : 0);            // + the gate tile
+    static constexpr int STAGED = BYTES + C * 64 * 2;                                 // + a staging tile for the output
 };
 
 // GATE (Eq. 9, Y = Norm(O) * G with Norm(o) = o / sqrt(mean_j o_j^2 + eps) over the head's DV features): Gb and Yb
@@ -485,7 +519,9 @@ struct FwdLds {
 // nothing but registers by then -- so the epilogue costs no barrier of its own.  The gate tile comes in like V
 // (whole 128- or 256-byte rows, one chunk ahead, via LDS) and is picked up from LDS in the order the output tile is
 // stored in; fetching it from HBM in that order directly (32 bytes per row and instruction) cost 20 % more time.
-template <int C, int DK, int DV, bool ZQK, bool SAVE, bool GATE = false>
+// STAGE (DV = 64 only): the output tile leaves through an LDS staging tile as whole rows, after the barrier that ends
+// the chunk; worth its 8 KB where the rows are far apart in memory ([B,N,H,d] tensors).
+template <int C, int DK, int DV, bool ZQK, bool SAVE, bool GATE = false, bool STAGE = false>
 __device__ __forceinline__ void fwd_sweep_body(const bf16* __restrict__ Qb, const bf16* __restrict__ Kb,
                                                const bf16* __restrict__ Vb, bf16* __restrict__ Ob,
                                                const float* __restrict__ S0, float* __restrict__ S_final,
@@ -576,7 +612,11 @@ __device__ __forceinline__ void fwd_sweep_body(const bf16* __restrict__ Qb, cons
             }
         }
         const int valid = ntok - (c0 + tb * 32);
-        if (!GATE || Ob != nullptr) {
+        if (STAGE) {
+            bf16* sOut = reinterpret_cast<bf16*>(lds + FwdLds<C, DK, DV, ZQK, GATE>::BYTES);
+#pragma unroll
+            for (int n = 0; n < NJ; ++n) stage_tile_T(sOut, tb * 32, (jg * NJ + n) * 32, accO[n], lane);
+        } else if (!GATE || Ob != nullptr) {
             bf16* rows = Ob + (size_t)(c0 + tb * 32) * ldv;
 #pragma unroll
             for (int n = 0; n < NJ; ++n) store_tile_T(rows, ldv, (jg * NJ + n) * 32, accO[n], valid, lane);
@@ -612,6 +652,9 @@ __device__ __forceinline__ void fwd_sweep_body(const bf16* __restrict__ Qb, cons
             }
         }
         __syncthreads();
+        if (STAGE)   // (the staging tile is next written after the next chunk's first barrier)
+            flush_stage<C>(reinterpret_cast<const bf16*>(lds + FwdLds<C, DK, DV, ZQK, GATE>::BYTES),
+                           Ob + (size_t)c0 * ldv, ldv, ntok - c0, tid);
         if (GATE) {
             // (the next chunk writes sSq only after its own first barrier, which every wave reaches after this read)
             float tot = 0.f;
@@ -652,7 +695,10 @@ struct BwdLds {
     // two more barriers per chunk): that brings the workgroup under 80 KB, so that two of them fit a compute unit.
     static constexpr bool SHARE = (C == 64 && DK != DV);
     static constexpr int TILES = (2 * C * LDK + 2 * C * LDV + (SHARE ? 1 : 2) * DK * LDV) * 2;
-    static constexpr int BYTES = TILES + (ZQK ? C * LDK * 2 + 4 * DK * 4 : 0);
+    static constexpr int WORK = TILES + (ZQK ? C * LDK * 2 + 4 * DK * 4 : 0);
+    // 64-wide heads: the output tiles leave through unpadded staging tiles (whole-line stores), 8 KB each
+    static constexpr bool STAGE = (C == 64 && DK == 64 && DV == 64);
+    static constexpr int BYTES = WORK + (STAGE ? (ZQK ? 2 : 3) * C * 64 * 2 : 0);
 };
 
 // Sum over the tokens of a wave half for the parameter gradients.  x holds, per lane, 16 values of one token (the
@@ -712,6 +758,10 @@ __device__ __forceinline__ void bwd_sweep_body(const bf16* __restrict__ Qb, cons
     bf16* sV = sK + C * LDK;
     bf16* sG = sV + C * LDV;           // dO
     constexpr bool SHARE = BwdLds<C, DK, DV, false>::SHARE;
+    constexpr bool STAGE = BwdLds<C, DK, DV, false>::STAGE;
+    bf16* sOutQ = reinterpret_cast<bf16*>(lds + BwdLds<C, DK, DV, ZQK>::WORK);     // dQ (with ZQK: dZ)
+    bf16* sOutV = sOutQ + C * 64;
+    bf16* sOutK = sOutV + C * 64;                                                  // (not with ZQK)
     bf16* sS = sG + C * LDV;                        // S  [i][j] bf16
     bf16* sR = SHARE ? sS : sS + DK * LDV;          // R  [i][j] bf16 (the same tile, later in the chunk, with SHARE)
     const int rb = w % WT, cg = w / WT;
@@ -841,7 +891,10 @@ __device__ __forceinline__ void bwd_sweep_body(const bf16* __restrict__ Qb, cons
             if (!ZQK) {
                 bf16* rows = dQb + (size_t)(c0 + rb * 32) * ldk;
 #pragma unroll
-                for (int n = 0; n < NI; ++n) store_tile_T(rows, ldk, (cg * NI + n) * 32, acc[n], valid, lane);
+                for (int n = 0; n < NI; ++n) {
+                    if (STAGE) stage_tile_T(sOutQ, rb * 32, (cg * NI + n) * 32, acc[n], lane);
+                    else store_tile_T(rows, ldk, (cg * NI + n) * 32, acc[n], valid, lane);
+                }
             }
         }
         if (SHARE) {
@@ -881,7 +934,10 @@ __device__ __forceinline__ void bwd_sweep_body(const bf16* __restrict__ Qb, cons
             if (!ZQK) {
                 bf16* rows = dKb + (size_t)(c0 + rb * 32) * ldk;
 #pragma unroll
-                for (int n = 0; n < NI; ++n) store_tile_T(rows, ldk, (cg * NI + n) * 32, acc[n], valid, lane);
+                for (int n = 0; n < NI; ++n) {
+                    if (STAGE) stage_tile_T(sOutK, rb * 32, (cg * NI + n) * 32, acc[n], lane);
+                    else store_tile_T(rows, ldk, (cg * NI + n) * 32, acc[n], valid, lane);
+                }
             } else {
                 // dZ = alpha_q dQ + alpha_k dK; the lane owns features f0 + 8a + 4h + b of token rb*32 + r
                 const int r = lane & 31, h = lane >> 5;
@@ -906,7 +962,8 @@ __device__ __forceinline__ void bwd_sweep_body(const bf16* __restrict__ Qb, cons
                             kz[e] = acc[n][e] * z[b];
                         }
                     }
-                    store_tile_T(rows, ldk, f0, dz, valid, lane);
+                    if (STAGE) stage_tile_T(sOutQ, rb * 32, f0, dz, lane);
+                    else store_tile_T(rows, ldk, f0, dz, valid, lane);
                     pg[0][n] += sum_tokens16(qz, lane);
                     pg[1][n] += sum_tokens16(accQ[n], lane);
                     pg[2][n] += sum_tokens16(kz, lane);
@@ -945,7 +1002,10 @@ __device__ __forceinline__ void bwd_sweep_body(const bf16* __restrict__ Qb, cons
             }
             bf16* rows = dVb + (size_t)(c0 + rb * 32) * ldv;
 #pragma unroll
-            for (int n = 0; n < NJ; ++n) store_tile_T(rows, ldv, (cg * NJ + n) * 32, acc[n], valid, lane);
+            for (int n = 0; n < NJ; ++n) {
+                if (STAGE) stage_tile_T(sOutV, rb * 32, (cg * NJ + n) * 32, acc[n], lane);
+                else store_tile_T(rows, ldv, (cg * NJ + n) * 32, acc[n], valid, lane);
+            }
         }
         // ---------------- R^T += dO^T Q (after the segment's first chunk only if the final state is asked for)
         if (ci > 0 || R_final != nullptr) {
@@ -958,6 +1018,13 @@ __device__ __forceinline__ void bwd_sweep_body(const bf16* __restrict__ Qb, cons
             }
         }
         __syncthreads();
+        if (STAGE) {
+            // the chunk's output tiles are complete in their staging tiles (which are next written after two more
+            // barriers): out they go, as whole rows
+            flush_stage<C>(sOutQ, dQb + (size_t)c0 * ldk, ldk, ntok - c0, tid);
+            if (!ZQK) flush_stage<C>(sOutK, dKb + (size_t)c0 * ldk, ldk, ntok - c0, tid);
+            flush_stage<C>(sOutV, dVb + (size_t)c0 * ldv, ldv, ntok - c0, tid);
+        }
     }
     if (R_final != nullptr) store_state_T<DV, DK>(R_final, accRT, w, lane);
     if (ZQK) {
@@ -1038,7 +1105,9 @@ void bf16_fwd_sweep_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ 
                                                             float* __restrict__ saved, int save_every,
                                                             int first_loads_state, int N, int seg_len, int n_seg)
 {
-    __shared__ __attribute__((aligned(16))) unsigned char lds[FwdLds<C, DK, DV, ZQK>::BYTES];
+    constexpr bool STAGE = NH && DV == 64;     // rows H * d apart: whole-line stores through a staging tile
+    __shared__ __attribute__((aligned(16))) unsigned char
+        lds[STAGE ? FwdLds<C, DK, DV, ZQK>::STAGED : FwdLds<C, DK, DV, ZQK>::BYTES];
     const int seg = blockIdx.y;
     const long bh = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63;
@@ -1055,7 +1124,7 @@ void bf16_fwd_sweep_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ 
         const int n_slots = (n_seg + save_every - 1) / save_every, slot = (seg + save_every) / save_every - 1;
         save_to = saved + ((size_t)bh * n_slots + slot) * DK * DV;
     }
-    fwd_sweep_body<C, DK, DV, ZQK, SAVE>(Q + rk, ZQK ? nullptr : K + rk, V + rv, O + rv,
+    fwd_sweep_body<C, DK, DV, ZQK, SAVE, false, STAGE>(Q + rk, ZQK ? nullptr : K + rk, V + rv, O + rv,
                                    has_state ? S0 + ((size_t)bh * n_seg + seg) * DK * DV : nullptr,
                                    (S_out != nullptr && seg == n_seg - 1) ? S_out + (size_t)bh * DK * DV : nullptr,
                                    save_to, ZQK ? aff + (size_t)(bh % H) * DK : nullptr, (size_t)H * DK,
