@@ -1551,7 +1551,10 @@ struct ApplyLds {
     static constexpr int LDA = DA + PAD;
     static constexpr int TILES = (2 * 64 * LDA + DB * LDA) * 2;
     static constexpr int SUMS = GATE ? 2 * 2 * 64 * 4 : 0;                  // [2][2][64] floats
-    static constexpr int BYTES = TILES + SUMS + (GATE ? 2 * 64 * (DB + PAD) * 2 : 0);   // + two gate tiles
+    // not gated, 64 features out: the output leaves as whole rows through two staging tiles used in turn
+    static constexpr bool STAGE = !GATE && DB == 64;
+    static constexpr int BYTES = TILES + SUMS + (GATE ? 2 * 64 * (DB + PAD) * 2 : 0)    // + two gate tiles
+                                 + (STAGE ? 2 * 64 * 64 * 2 : 0);
 };
 
 // GATE (Eq. 9): Yg = Norm(Y) * G with Norm(y) = y / sqrt(mean_j y_j^2 + eps) over the DB features of a token; Y itself
@@ -1624,6 +1627,8 @@ __global__ __launch_bounds__(256) void bf16_apply_state_kernel(const bf16* __res
             store_tile_T(rows, DB, (jg * NJ + n) * 32, gate_tile(held[n], gate[n], rinv), valid, lane);
     };
 
+    constexpr bool STAGE = ApplyLds<DA, DB, GATE>::STAGE;
+    bf16* sOut = reinterpret_cast<bf16*>(lds + ApplyLds<DA, DB, false>::TILES);      // STAGE: [2][C][64]
     int buf = 0;
     for (int c0 = 0; c0 < ntok; c0 += C, buf ^= 1) {
         bf16* sXb = sX + buf * C * LDA;
@@ -1631,6 +1636,8 @@ __global__ __launch_bounds__(256) void bf16_apply_state_kernel(const bf16* __res
         if (GATE) rg.store(sG + buf * C * LDB, tid);
         __syncthreads();
         if (GATE && held_c0 >= 0) flush(buf ^ 1);      // the previous chunk's sums are complete now
+        if (STAGE && c0 > 0)                            // the previous chunk's tile is complete in its staging tile
+            flush_stage<C>(sOut + (buf ^ 1) * C * 64, Yb + (size_t)(c0 - C) * DB, DB, C, tid);
         if (c0 + C < ntok) {
             rx.load(Xb + (size_t)(c0 + C) * DA, DA, ntok - c0 - C, tid);
             if (GATE) rg.load(Gb + (size_t)(c0 + C) * DB, DB, ntok - c0 - C, tid);
@@ -1652,7 +1659,10 @@ __global__ __launch_bounds__(256) void bf16_apply_state_kernel(const bf16* __res
 #pragma unroll
             for (int n = 0; n < NJ; ++n) acc[n] = mfma(aM[n][kk], bX, acc[n]);
         }
-        if (!GATE || Yb != nullptr) {
+        if (STAGE) {
+#pragma unroll
+            for (int n = 0; n < NJ; ++n) stage_tile_T(sOut + buf * C * 64, tb * 32, (jg * NJ + n) * 32, acc[n], lane);
+        } else if (!GATE || Yb != nullptr) {
             bf16* rows = Yb + (size_t)(c0 + tb * 32) * DB;
             const int valid = ntok - (c0 + tb * 32);
 #pragma unroll
@@ -1677,6 +1687,11 @@ __global__ __launch_bounds__(256) void bf16_apply_state_kernel(const bf16* __res
     if (GATE && held_c0 >= 0) {
         __syncthreads();
         flush(buf ^ 1);
+    }
+    if (STAGE && ntok > 0) {
+        __syncthreads();
+        const int last = (ntok - 1) / C * C;
+        flush_stage<C>(sOut + (buf ^ 1) * C * 64, Yb + (size_t)last * DB, DB, ntok - last, tid);
     }
 }
 
