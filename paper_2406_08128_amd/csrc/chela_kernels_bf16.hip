@@ -255,13 +255,20 @@ __device__ __forceinline__ void store_tile_T(bf16* rows, int ld, int col0, const
     }
 }
 
-// The same tile into an LDS staging area instead (rows of 64 bf16 = 128 bytes, no padding: the 16-byte pieces of a
+// The same tile into an LDS staging area instead (rows of D = 64 or 128 bf16, no padding: the 16-byte pieces of a
 // row are permuted by an XOR with bits 1..3 of the row number so that neither these writes nor the row reads below
 // pile up on banks), and the staging area out to memory as whole rows: eight neighbouring lanes write one 128-byte
 // line.  store_tile_T sends 32 bytes per row and instruction; a plain streaming kernel with that store pattern loses
 // a third of its bandwidth against whole-line stores on this GPU.
-__device__ __forceinline__ int stage_at(int row, int piece) { return row * 64 + ((piece ^ ((row >> 1) & 7)) << 3); }
+template <int D>
+__device__ __forceinline__ int stage_at(int row, int piece)
+{
+    // rows of 128 bytes: neighbouring rows already differ by half the banks, so the row PAIR picks the permutation;
+    // rows of 256 bytes all start on bank 0: the row itself does
+    return row * D + ((piece ^ (D == 64 ? ((row >> 1) & 7) : (row & 15))) << 3);
+}
 
+template <int D>
 __device__ __forceinline__ void stage_tile_T(bf16* stage, int row0, int col0, const f32x16& acc, int lane)
 {
     const int r = lane & 31, h = lane >> 5, row = row0 + r;
@@ -271,20 +278,22 @@ __device__ __forceinline__ void stage_tile_T(bf16* stage, int row0, int col0, co
         const unsigned y0 = pack2(acc[8 * ap + 4], acc[8 * ap + 5]), y1 = pack2(acc[8 * ap + 6], acc[8 * ap + 7]);
         const u32x2 s0 = __builtin_amdgcn_permlane32_swap(x0, y0, false, false);
         const u32x2 s1 = __builtin_amdgcn_permlane32_swap(x1, y1, false, false);
-        *reinterpret_cast<uint4*>(stage + stage_at(row, (col0 >> 3) + h + 2 * ap)) = make_uint4(s0[0], s1[0], s0[1], s1[1]);
+        *reinterpret_cast<uint4*>(stage + stage_at<D>(row, (col0 >> 3) + h + 2 * ap)) =
+            make_uint4(s0[0], s1[0], s0[1], s1[1]);
     }
 }
 
-// ROWS x 64 staged tile -> rows of the row-major matrix at `out` (leading dimension ld), the first valid_rows of them.
-template <int ROWS>
+// ROWS x D staged tile -> rows of the row-major matrix at `out` (leading dimension ld), the first valid_rows of them.
+template <int ROWS, int D>
 __device__ __forceinline__ void flush_stage(const bf16* stage, bf16* out, int ld, int valid_rows, int tid)
 {
+    constexpr int PPR = D / 8;      // 16-byte pieces per row
 #pragma unroll
-    for (int n = 0; n < ROWS * 8 / 256; ++n) {
-        const int x = tid + 256 * n, row = x >> 3, piece = x & 7;
+    for (int n = 0; n < ROWS * PPR / 256; ++n) {
+        const int x = tid + 256 * n, row = x / PPR, piece = x % PPR;
         if (row < valid_rows)
             *reinterpret_cast<uint4*>(out + ((unsigned)row * (unsigned)ld + (unsigned)piece * 8u)) =
-                *reinterpret_cast<const uint4*>(stage + stage_at(row, piece));
+                *reinterpret_cast<const uint4*>(stage + stage_at<D>(row, piece));
     }
 }
 
@@ -509,7 +518,7 @@ struct FwdLds {
     static constexpr int TILES = (2 * C * LDK + C * LDV + DV * LDK) * 2;
     static constexpr int SMALL = (ZQK ? 4 * DK * 4 : 0) + (GATE ? 4 * C * 4 : 0);      // affine parameters, sums of squares
     static constexpr int BYTES = TILES + SMALL + (GATE ? C * LDV * 2 : 0);            // + the gate tile
-    static constexpr int STAGED = BYTES + C * 64 * 2;                                 // + a staging tile for the output
+    static constexpr int STAGED = BYTES + C * DV * 2;                                 // + a staging tile for the output
 };
 
 // GATE (Eq. 9, Y = Norm(O) * G with Norm(o) = o / sqrt(mean_j o_j^2 + eps) over the head's DV features): Gb and Yb
@@ -519,8 +528,7 @@ struct FwdLds {
 // nothing but registers by then -- so the epilogue costs no barrier of its own.  The gate tile comes in like V
 // (whole 128- or 256-byte rows, one chunk ahead, via LDS) and is picked up from LDS in the order the output tile is
 // stored in; fetching it from HBM in that order directly (32 bytes per row and instruction) cost 20 % more time.
-// STAGE (DV = 64 only): the output tile leaves through an LDS staging tile as whole rows, after the barrier that ends
-// the chunk; worth its 8 KB where the rows are far apart in memory ([B,N,H,d] tensors).
+// STAGE: the output tile leaves through an LDS staging tile as whole rows, after the barrier that ends the chunk.
 template <int C, int DK, int DV, bool ZQK, bool SAVE, bool GATE = false, bool STAGE = false>
 __device__ __forceinline__ void fwd_sweep_body(const bf16* __restrict__ Qb, const bf16* __restrict__ Kb,
                                                const bf16* __restrict__ Vb, bf16* __restrict__ Ob,
@@ -615,7 +623,7 @@ __device__ __forceinline__ void fwd_sweep_body(const bf16* __restrict__ Qb, cons
         if (STAGE) {
             bf16* sOut = reinterpret_cast<bf16*>(lds + FwdLds<C, DK, DV, ZQK, GATE>::BYTES);
 #pragma unroll
-            for (int n = 0; n < NJ; ++n) stage_tile_T(sOut, tb * 32, (jg * NJ + n) * 32, accO[n], lane);
+            for (int n = 0; n < NJ; ++n) stage_tile_T<DV>(sOut, tb * 32, (jg * NJ + n) * 32, accO[n], lane);
         } else if (!GATE || Ob != nullptr) {
             bf16* rows = Ob + (size_t)(c0 + tb * 32) * ldv;
 #pragma unroll
@@ -653,7 +661,7 @@ __device__ __forceinline__ void fwd_sweep_body(const bf16* __restrict__ Qb, cons
         }
         __syncthreads();
         if (STAGE)   // (the staging tile is next written after the next chunk's first barrier)
-            flush_stage<C>(reinterpret_cast<const bf16*>(lds + FwdLds<C, DK, DV, ZQK, GATE>::BYTES),
+            flush_stage<C, DV>(reinterpret_cast<const bf16*>(lds + FwdLds<C, DK, DV, ZQK, GATE>::BYTES),
                            Ob + (size_t)c0 * ldv, ldv, ntok - c0, tid);
         if (GATE) {
             // (the next chunk writes sSq only after its own first barrier, which every wave reaches after this read)
@@ -892,7 +900,7 @@ __device__ __forceinline__ void bwd_sweep_body(const bf16* __restrict__ Qb, cons
                 bf16* rows = dQb + (size_t)(c0 + rb * 32) * ldk;
 #pragma unroll
                 for (int n = 0; n < NI; ++n) {
-                    if (STAGE) stage_tile_T(sOutQ, rb * 32, (cg * NI + n) * 32, acc[n], lane);
+                    if (STAGE) stage_tile_T<64>(sOutQ, rb * 32, (cg * NI + n) * 32, acc[n], lane);
                     else store_tile_T(rows, ldk, (cg * NI + n) * 32, acc[n], valid, lane);
                 }
             }
@@ -935,7 +943,7 @@ __device__ __forceinline__ void bwd_sweep_body(const bf16* __restrict__ Qb, cons
                 bf16* rows = dKb + (size_t)(c0 + rb * 32) * ldk;
 #pragma unroll
                 for (int n = 0; n < NI; ++n) {
-                    if (STAGE) stage_tile_T(sOutK, rb * 32, (cg * NI + n) * 32, acc[n], lane);
+                    if (STAGE) stage_tile_T<64>(sOutK, rb * 32, (cg * NI + n) * 32, acc[n], lane);
                     else store_tile_T(rows, ldk, (cg * NI + n) * 32, acc[n], valid, lane);
                 }
             } else {
@@ -962,7 +970,7 @@ __device__ __forceinline__ void bwd_sweep_body(const bf16* __restrict__ Qb, cons
                             kz[e] = acc[n][e] * z[b];
                         }
                     }
-                    if (STAGE) stage_tile_T(sOutQ, rb * 32, f0, dz, lane);
+                    if (STAGE) stage_tile_T<64>(sOutQ, rb * 32, f0, dz, lane);
                     else store_tile_T(rows, ldk, f0, dz, valid, lane);
                     pg[0][n] += sum_tokens16(qz, lane);
                     pg[1][n] += sum_tokens16(accQ[n], lane);
@@ -1003,7 +1011,7 @@ __device__ __forceinline__ void bwd_sweep_body(const bf16* __restrict__ Qb, cons
             bf16* rows = dVb + (size_t)(c0 + rb * 32) * ldv;
 #pragma unroll
             for (int n = 0; n < NJ; ++n) {
-                if (STAGE) stage_tile_T(sOutV, rb * 32, (cg * NJ + n) * 32, acc[n], lane);
+                if (STAGE) stage_tile_T<64>(sOutV, rb * 32, (cg * NJ + n) * 32, acc[n], lane);
                 else store_tile_T(rows, ldv, (cg * NJ + n) * 32, acc[n], valid, lane);
             }
         }
@@ -1021,9 +1029,9 @@ __device__ __forceinline__ void bwd_sweep_body(const bf16* __restrict__ Qb, cons
         if (STAGE) {
             // the chunk's output tiles are complete in their staging tiles (which are next written after two more
             // barriers): out they go, as whole rows
-            flush_stage<C>(sOutQ, dQb + (size_t)c0 * ldk, ldk, ntok - c0, tid);
-            if (!ZQK) flush_stage<C>(sOutK, dKb + (size_t)c0 * ldk, ldk, ntok - c0, tid);
-            flush_stage<C>(sOutV, dVb + (size_t)c0 * ldv, ldv, ntok - c0, tid);
+            flush_stage<C, 64>(sOutQ, dQb + (size_t)c0 * ldk, ldk, ntok - c0, tid);
+            if (!ZQK) flush_stage<C, 64>(sOutK, dKb + (size_t)c0 * ldk, ldk, ntok - c0, tid);
+            flush_stage<C, 64>(sOutV, dVb + (size_t)c0 * ldv, ldv, ntok - c0, tid);
         }
     }
     if (R_final != nullptr) store_state_T<DV, DK>(R_final, accRT, w, lane);
@@ -1105,7 +1113,10 @@ void bf16_fwd_sweep_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ 
                                                             float* __restrict__ saved, int save_every,
                                                             int first_loads_state, int N, int seg_len, int n_seg)
 {
-    constexpr bool STAGE = NH && DV == 64;     // rows H * d apart: whole-line stores through a staging tile
+    // whole-row stores through a staging tile where its LDS and registers cost nothing that matters: not the
+    // contiguous 64-wide shape (it would lose its fourth workgroup per unit; with [B,N,H,d] rows, H * d apart, the
+    // tile pays for itself there too), not the 128 x 128 shape (out of registers: measured slower)
+    constexpr bool STAGE = C == 64 && !(DK == 128 && DV == 128) && (NH || DK != DV);
     __shared__ __attribute__((aligned(16))) unsigned char
         lds[STAGE ? FwdLds<C, DK, DV, ZQK>::STAGED : FwdLds<C, DK, DV, ZQK>::BYTES];
     const int seg = blockIdx.y;
@@ -1637,7 +1648,7 @@ __global__ __launch_bounds__(256) void bf16_apply_state_kernel(const bf16* __res
         __syncthreads();
         if (GATE && held_c0 >= 0) flush(buf ^ 1);      // the previous chunk's sums are complete now
         if (STAGE && c0 > 0)                            // the previous chunk's tile is complete in its staging tile
-            flush_stage<C>(sOut + (buf ^ 1) * C * 64, Yb + (size_t)(c0 - C) * DB, DB, C, tid);
+            flush_stage<C, 64>(sOut + (buf ^ 1) * C * 64, Yb + (size_t)(c0 - C) * DB, DB, C, tid);
         if (c0 + C < ntok) {
             rx.load(Xb + (size_t)(c0 + C) * DA, DA, ntok - c0 - C, tid);
             if (GATE) rg.load(Gb + (size_t)(c0 + C) * DB, DB, ntok - c0 - C, tid);
@@ -1661,7 +1672,7 @@ __global__ __launch_bounds__(256) void bf16_apply_state_kernel(const bf16* __res
         }
         if (STAGE) {
 #pragma unroll
-            for (int n = 0; n < NJ; ++n) stage_tile_T(sOut + buf * C * 64, tb * 32, (jg * NJ + n) * 32, acc[n], lane);
+            for (int n = 0; n < NJ; ++n) stage_tile_T<64>(sOut + buf * C * 64, tb * 32, (jg * NJ + n) * 32, acc[n], lane);
         } else if (!GATE || Yb != nullptr) {
             bf16* rows = Yb + (size_t)(c0 + tb * 32) * DB;
             const int valid = ntok - (c0 + tb * 32);
@@ -1691,7 +1702,7 @@ __global__ __launch_bounds__(256) void bf16_apply_state_kernel(const bf16* __res
     if (STAGE && ntok > 0) {
         __syncthreads();
         const int last = (ntok - 1) / C * C;
-        flush_stage<C>(sOut + (buf ^ 1) * C * 64, Yb + (size_t)last * DB, DB, ntok - last, tid);
+        flush_stage<C, 64>(sOut + (buf ^ 1) * C * 64, Yb + (size_t)last * DB, DB, ntok - last, tid);
     }
 }
 
