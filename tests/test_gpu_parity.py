@@ -947,3 +947,58 @@ def test_noncausal_fwd_gated_lra_full_size_sampled():
     for b, hd in ((0, 0), (17, 3), (31, 7)):
         Qn, Kn, Vn, Gn = (to_f64_numpy(t[b:b + 1, hd:hd + 1]) for t in (x["Q"], x["K"], x["V"], gx["G"]))
         _check("Y", Y[b:b + 1, hd:hd + 1], oracle_layer.gate_norm_fwd(oracle_layer.noncausal_fwd(Qn, Kn, Vn), Gn, EPS), "bf16")
+
+
+# ------------------------------------------------------------------------------------------ seeded shape sweep
+def _sweep_shapes():
+    rng = np.random.default_rng(20240611)
+    shapes = []
+    for _ in range(14):
+        dk, dv = (int(x) for x in rng.choice([64, 128], size=2))
+        B, H = int(rng.integers(1, 4)), int(rng.integers(1, 5))
+        N = int(rng.choice([1, 63, 64, 65, 127, 500, 1000, 2047, 2048, 3333, 5000, 7777]))
+        shapes.append((B, H, N, dk, dv))
+    return shapes
+
+
+@pytest.mark.parametrize("shape", _sweep_shapes())
+def test_seeded_shape_sweep_over_the_entry_points(shape):
+    # every family of entry points on the same odd shape: ragged lengths, both layouts, all width pairs
+    B, H, N, dk, dv = shape
+    w = shrink(WORKLOADS["lm_bf16"], B=B, H=H, N=N, dk=dk, dv=dv, seed=900 + N + dk + 2 * dv)
+    print("\nsweep %s" % (shape,), flush=True)
+    x, gx = make_inputs(w, with_dO=True), make_gate_inputs(w)
+    d, gd = _dev(x), _dev(gx)
+    Qn, Kn, Vn, dOn, Gn = (to_f64_numpy(t) for t in (x["Q"], x["K"], x["V"], x["dO"], gx["G"]))
+    rO = oracle.fwd_recurrent(Qn, Kn, Vn)
+    rg = oracle.bwd_recurrent(Qn, Kn, Vn, dOn)
+    # plain pair and training pair
+    O = binding.chela_linattn_fwd(d["Q"], d["K"], d["V"])
+    g1 = binding.chela_linattn_bwd(d["Q"], d["K"], d["V"], d["dO"])
+    O2, saved = binding.chela_linattn_fwd_save(d["Q"], d["K"], d["V"])
+    g2 = binding.chela_linattn_bwd_saved(d["Q"], d["K"], d["V"], d["dO"], saved)
+    # [B,N,H,d] layout
+    t = {k: v.transpose(1, 2).contiguous() for k, v in d.items()}
+    O3 = binding.chela_linattn_fwd_bnhd(t["Q"], t["K"], t["V"])
+    g3 = binding.chela_linattn_bwd_bnhd(t["Q"], t["K"], t["V"], t["dO"])
+    # gated forward, non-causal pair, non-causal gated forward
+    Y, Og, _ = binding.chela_linattn_fwd_gated(d["Q"], d["K"], d["V"], gd["G"], EPS, want_O=True)
+    On = binding.chela_linattn_noncausal_fwd(d["Q"], d["K"], d["V"])
+    gn = binding.chela_linattn_noncausal_bwd(d["Q"], d["K"], d["V"], d["dO"])
+    Yn, _ = binding.chela_linattn_noncausal_fwd_gated(d["Q"], d["K"], d["V"], gd["G"], EPS)
+    torch.cuda.synchronize()
+    _check("O", O, rO, "bf16")
+    for name, a, r in zip(("dQ", "dK", "dV"), g1, rg):
+        _check(name, a, r, "bf16")
+    assert torch.equal(O2, O) and torch.equal(Og, O)
+    for name, a, r in zip(("dQ", "dK", "dV"), g2, rg):
+        _check(name + "(saved)", a, r, "bf16")
+    assert torch.equal(O3.transpose(1, 2), O)
+    for a, b in zip(g3, g1):
+        assert torch.equal(a.transpose(1, 2), b)
+    _check("Y", Y, oracle_layer.gate_norm_fwd(rO, Gn, EPS), "bf16")
+    rOn = oracle_layer.noncausal_fwd(Qn, Kn, Vn)
+    _check("O(nc)", On, rOn, "bf16")
+    for name, a, r in zip(("dQ(nc)", "dK(nc)", "dV(nc)"), gn, oracle_layer.noncausal_bwd(Qn, Kn, Vn, dOn)):
+        _check(name, a, r, "bf16")
+    _check("Y(nc)", Yn, oracle_layer.gate_norm_fwd(rOn, Gn, EPS), "bf16")
