@@ -149,7 +149,7 @@ static const char* const kKernelNames[KID_COUNT] = {
     "bf16_seg_state_kernel", "scan_states_kernel", "bf16_fwd_sweep_kernel", "bf16_bwd_sweep_kernel",
     "f32_seg_state_kernel", "f32_sweep_kernel", "copy_probe_kernel", "bf16_step_kernel", "affine_grad_kernel",
     "bf16_apply_state_kernel", "longconv_spectrum_kernel", "shortlong_conv_kernel",
-    "shortconv_bwd_kernel", "longconv_dk_kernel", "gate_norm_kernel", "stream_probe_kernel"};
+    "shortconv_bwd_kernel", "longconv_bwd_kernel", "gate_norm_kernel", "stream_probe_kernel"};
 
 ProfScope::ProfScope(int id, hipStream_t s) : slot(-1), st(s)
 {
@@ -779,9 +779,12 @@ int chela_shortlong_conv_fwd_f32(const void* X, const float* w_short, int m, con
 
 static size_t conv_bwd_ws_bytes(int B, int d, int L, int dtype, bool has_short)
 {
-    if (!has_short || B <= 0 || d <= 0 || L <= 0) return 0;
+    if (B <= 0 || d <= 0 || L <= 0) return 0;
+    const size_t acc = conv_bwd_acc_floats(d, L) * sizeof(float);      // running sums of the long-kernel gradient
+    if (!has_short) return acc;
     const size_t n = (size_t)B * d * L, tiles = ((size_t)L + 2047) / 2048;
-    return n * sizeof(float) + (size_t)B * d * tiles * 16 * sizeof(float) + n * (dtype == CHELA_DTYPE_BF16 ? 2 : 4);
+    (void)dtype;
+    return acc + n * sizeof(float) + (size_t)B * d * tiles * 16 * sizeof(float);
 }
 
 size_t chela_shortlong_conv_bwd_workspace_bytes(int B, int d, int L, int has_short_kernel, int dtype)

@@ -101,14 +101,21 @@ hipError_t launch_longconv_spectrum(const float* k, void* Kf, int d, int L, hipS
 hipError_t launch_shortlong_conv(const void* X, const float* w_short, int m, const void* Kf, void* Y, long BD, int d,
                                  int L, int dtype, hipStream_t st);
 // Gradient: dX [B][d][L] (I/O dtype), dw [d][m] (only with a short kernel, m <= 16), dk [d][L] fp32.
-// ws_dV: B*d*L floats of scratch when there is a short kernel.
+// ws: conv_bwd_acc_floats(d, L) floats (running sums of the long-kernel gradient at the largest transform size: they
+// no longer fit the registers of 1024 threads), then, with a short kernel, B*d*L floats (dV) and the workgroups' tap
+// sums.
+inline size_t conv_bwd_acc_floats(int d, int L)
+{
+    const int M = conv_fft_size(L);
+    return M >= 16384 ? (size_t)d * (M / 2 + 1) * 4 : 0;
+}
 hipError_t launch_shortlong_conv_bwd(const void* X, const float* w_short, int m, const void* Kf, const void* dZ,
                                      void* dX, float* dw, float* dk, float* ws_dV, int B, int d, int L, int dtype,
                                      hipStream_t st);
 
 // Kernel classes for the per-kernel timing aid.
 enum { KID_SEG_STATE_BF16 = 0, KID_SCAN = 1, KID_FWD_SWEEP_BF16 = 2, KID_BWD_SWEEP_BF16 = 3, KID_SEG_STATE_F32 = 4,
-       KID_SWEEP_F32 = 5, KID_COPY = 6, KID_STEP_BF16 = 7, KID_AFFINE_GRAD = 8, KID_APPLY_BF16 = 9, KID_CONV_SPECTRUM = 10, KID_CONV_FWD = 11, KID_CONV_SHORT_BWD = 12, KID_CONV_DK = 13, KID_GATE_NORM = 14, KID_STREAM_PROBE = 15, KID_COUNT = 16 };
+       KID_SWEEP_F32 = 5, KID_COPY = 6, KID_STEP_BF16 = 7, KID_AFFINE_GRAD = 8, KID_APPLY_BF16 = 9, KID_CONV_SPECTRUM = 10, KID_CONV_FWD = 11, KID_CONV_SHORT_BWD = 12, KID_CONV_LONG_BWD = 13, KID_GATE_NORM = 14, KID_STREAM_PROBE = 15, KID_COUNT = 16 };
 
 // Brackets one kernel launch with HIP events on its stream while profiling is enabled; otherwise does nothing.
 struct ProfScope {

@@ -14,6 +14,7 @@
 // Arithmetic is fp32 on the vector ALU: with one kernel per channel there is no operand shared across channels
 // except the DFT matrix itself, and fp32 matrix instructions are no faster than the ALU on this chip.
 #include "chela_internal.h"
+#include <cstdlib>
 
 namespace chela {
 
@@ -66,7 +67,6 @@ __device__ __forceinline__ void dft16(cplx (&v)[16])
 
 __host__ __device__ constexpr int conv_threads(int M) { return M / 16 < 64 ? 64 : M / 16; }
 // the kernel-gradient kernel keeps two spectra in registers besides the transform in flight: half as many threads
-__host__ __device__ constexpr int conv_threads_dk(int M) { return M / 32 < 64 ? 64 : M / 32; }
 __host__ __device__ constexpr bool conv_lead4(int M) { return M == 1024 || M == 16384; }
 __host__ __device__ constexpr int conv_pad(int i) { return i + (i >> 4); }
 
@@ -391,9 +391,7 @@ __global__ __launch_bounds__(conv_threads(M)) void longconv_spectrum_kernel(cons
 }
 
 // One workgroup per (b, c).  w_short == nullptr: no short kernel and no activation (plain long convolution).
-// CONJ: multiply by the conjugate kernel spectrum, i.e. correlate with the kernel instead of convolving,
-// y[t] = sum_{s >= t} k[s - t] x[s] (the gradient with respect to the long kernel's input).
-template <int M, typename IN, typename OUT, bool CONJ>
+template <int M, typename IN, typename OUT>
 __global__ __launch_bounds__(conv_threads(M)) void shortlong_conv_kernel(const IN* __restrict__ X,
                                                                         const float* __restrict__ w_short, int m,
                                                                         const float4* __restrict__ Kf,
@@ -425,7 +423,7 @@ __global__ __launch_bounds__(conv_threads(M)) void shortlong_conv_kernel(const I
         cplx Xk, Xmk, Zk, Zmk;
         untangle(a[p1], conj(a[p2]), w, Xk, Xmk);
         const float4 kq = Kc[l];
-        const cplx K1 = mk(kq.x, CONJ ? -kq.y : kq.y), K2 = mk(kq.z, CONJ ? -kq.w : kq.w);
+        const cplx K1 = mk(kq.x, kq.y), K2 = mk(kq.z, kq.w);
         if (kk == 0) {
             // bins 0 and M are real and share storage slot 0
             const float y0 = Xk.x * K1.x, ym = Xmk.x * K2.x;
@@ -454,18 +452,28 @@ __global__ __launch_bounds__(conv_threads(M)) void shortlong_conv_kernel(const I
     }
 }
 
-// Gradient with respect to the long kernel: dk[c][s] = sum_b sum_{t >= s} dZ[b,c,t] v[b,c,t-s], v = silu(K_s x)
-// (given as a tensor: the short-stage kernel below writes it out, without a short stage it is x itself).
-// In the Fourier domain the correlation is DZ conj(V); the products of all batch entries are added up in
-// registers (each thread owns the bin pairs k, M - k it would handle in the point-wise stage) and transformed back
-// once.  One workgroup per channel.
-template <int M, typename IO>
-__global__ __launch_bounds__(conv_threads_dk(M)) void longconv_dk_kernel(const IO* __restrict__ V,
-                                                                        const IO* __restrict__ dZ,
-                                                                        float* __restrict__ dk, int B, int d, int L)
+// The two long-stage gradients in one kernel: they share the spectrum of dZ.  One workgroup per channel walks the
+// batch; per sequence it transforms dZ once, keeps the untangled bins of its own bin pairs in registers, multiplies
+// by the CONJUGATE kernel spectrum (correlation instead of convolution: dV[t] = sum_{s >= t} k[s - t] dZ[s]) and
+// transforms back (out as DVT: fp32 scratch for the
+// short-stage kernel, or dX itself when there is no short stage), then transforms v = silu(K_s x) (recomputed from x)
+// and adds DZ conj(V) to the running sums of its bin pairs, also in registers; after the last sequence the sums are
+// transformed back once (dk).  Three transforms per sequence instead of the four of the two separate kernels, at the
+// forward kernel's full thread count.
+template <int M, typename IO, typename DVT>
+__global__ __launch_bounds__(conv_threads(M)) void longconv_bwd_kernel(const IO* __restrict__ X,
+                                                                      const float* __restrict__ w_short, int m,
+                                                                      const float4* __restrict__ Kf,
+                                                                      const IO* __restrict__ dZ,
+                                                                      DVT* __restrict__ dV, float* __restrict__ dk,
+                                                                      float4* __restrict__ acc_ws, int B, int d, int L)
 {
-    constexpr int T = conv_threads_dk(M);
+    constexpr int T = conv_threads(M);
     constexpr int NP = (M / 2) / T + 1;                  // bin pairs per thread
+    // At the largest size 1024 threads share the register file: the running sums then live in a scratch array in
+    // memory ([d][M/2 + 1] pairs; every thread only ever touches its own pairs, between uses they sit in the caches).
+    constexpr bool ACC_MEM = M >= 16384;
+    float4* accm = ACC_MEM ? acc_ws + (long)blockIdx.x * (M / 2 + 1) : nullptr;
     __shared__ __attribute__((aligned(16))) unsigned char lds[ConvLds<M>::BYTES];
     cplx* a = reinterpret_cast<cplx*>(lds);
     cplx* lo = a + ConvLds<M>::DATA;
@@ -473,53 +481,128 @@ __global__ __launch_bounds__(conv_threads_dk(M)) void longconv_dk_kernel(const I
     const int tid = threadIdx.x;
     const int c = blockIdx.x;
     build_tables<M, T>(lo, hi, tid);
-    cplx accK[NP], accMK[NP], Vk[NP], Vmk[NP];
+    const float4* Kc = Kf + (long)c * (M / 2 + 1);
+    const float* wc = w_short ? w_short + (long)c * m : nullptr;
+    const bool vec_ok = (L & 1) == 0;
+    const float scale = 1.0f / (float)M;
+    cplx accK[ACC_MEM ? 1 : NP], accMK[ACC_MEM ? 1 : NP], Gk[NP], Gmk[NP];
+    if constexpr (!ACC_MEM) {
 #pragma unroll
-    for (int i = 0; i < NP; ++i) { accK[i] = mk(0.f, 0.f); accMK[i] = mk(0.f, 0.f); }
+        for (int i = 0; i < NP; ++i) { accK[i] = mk(0.f, 0.f); accMK[i] = mk(0.f, 0.f); }
+    }
 
     for (int b = 0; b < B; ++b) {
         const long row = ((long)b * d + c) * L;
-        stage_input<M, T, IO>(V + row, nullptr, 0, L, a, tid);
-        __syncthreads();
-        fft_passes<M, T, false>(a, lo, hi, tid);
-        __syncthreads();
-#pragma unroll
-        for (int i = 0; i < NP; ++i) {
-            const int l = tid + T * i, kk = pair_bin<M>(l);
-            if (l <= M / 2)
-                untangle(a[conv_pad(spectrum_pos<M>(kk))], conj(a[conv_pad(spectrum_pos<M>((M - kk) & (M - 1)))]),
-                         w2m(kk, M), Vk[i], Vmk[i]);
-        }
-        __syncthreads();
+        // ---- spectrum of dZ; correlation with the kernel: DZ conj(K)
         stage_input<M, T, IO>(dZ + row, nullptr, 0, L, a, tid);
         __syncthreads();
         fft_passes<M, T, false>(a, lo, hi, tid);
         __syncthreads();
+        {
+            // (the bin positions and twiddles of a thread's pairs do not depend on b; recomputing them per sequence
+            // is cheap, keeping them in registers across the transforms is not: hide the invariance)
+            int tp = tid;
+            asm volatile("" : "+v"(tp));
+            PairTwiddle<M, T> pw(tp);
 #pragma unroll
-        for (int i = 0; i < NP; ++i) {
-            const int l = tid + T * i, kk = pair_bin<M>(l);
-            if (l <= M / 2) {
-                cplx Gk, Gmk;
-                untangle(a[conv_pad(spectrum_pos<M>(kk))], conj(a[conv_pad(spectrum_pos<M>((M - kk) & (M - 1)))]),
-                         w2m(kk, M), Gk, Gmk);
-                accK[i] = cadd(accK[i], cmul(Gk, conj(Vk[i])));
-                accMK[i] = cadd(accMK[i], cmul(Gmk, conj(Vmk[i])));
+            for (int i = 0; i < NP; ++i) {
+                const int l = tp + T * i;
+                if (l <= M / 2) {
+                    const int kk = pair_bin<M>(l);
+                    const int p1 = conv_pad(spectrum_pos<M>(kk)), p2 = conv_pad(spectrum_pos<M>((M - kk) & (M - 1)));
+                    const cplx w = pw.next(l);
+                    untangle(a[p1], conj(a[p2]), w, Gk[i], Gmk[i]);
+                    const float4 kq = Kc[l];
+                    const cplx K1 = mk(kq.x, -kq.y), K2 = mk(kq.z, -kq.w);
+                    if (kk == 0) {
+                        const float y0 = Gk[i].x * K1.x, ym = Gmk[i].x * K2.x;
+                        a[p1] = mk(0.5f * (y0 + ym), 0.5f * (y0 - ym));
+                    } else {
+                        cplx Zk, Zmk;
+                        tangle(cmul(Gk[i], K1), cmul(Gmk[i], K2), w, Zk, Zmk);
+                        a[p1] = Zk;
+                        if (p2 != p1) a[p2] = Zmk;
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);   // one pair at a time: the unrolled pairs must not pile up in registers
+            }
+        }
+        __syncthreads();
+        fft_passes<M, T, true>(a, lo, hi, tid);
+        __syncthreads();
+        {
+            DVT* y = dV + row;
+            for (int n = tid; n < M; n += T) {
+                const int t = 2 * n;
+                if (t < L) {
+                    const cplx v = a[conv_pad(n)];
+                    if (vec_ok) IoPair<DVT>::store2(y + t, v.x * scale, v.y * scale);
+                    else { y[t] = (DVT)(v.x * scale); if (t + 1 < L) y[t + 1] = (DVT)(v.y * scale); }
+                }
+            }
+        }
+        __syncthreads();
+        // ---- spectrum of v = silu(K_s x) (x itself without a short stage); running sums of DZ conj(V)
+        stage_input<M, T, IO>(X + row, wc, m, L, a, tid);
+        __syncthreads();
+        fft_passes<M, T, false>(a, lo, hi, tid);
+        __syncthreads();
+        {
+            // (the bin positions and twiddles of a thread's pairs do not depend on b; recomputing them per sequence
+            // is cheap, keeping them in registers across the transforms is not: hide the invariance)
+            int tp = tid;
+            asm volatile("" : "+v"(tp));
+            PairTwiddle<M, T> pw(tp);
+#pragma unroll
+            for (int i = 0; i < NP; ++i) {
+                const int l = tp + T * i;
+                if (l <= M / 2) {
+                    const int kk = pair_bin<M>(l);
+                    const cplx w = pw.next(l);
+                    cplx Vk, Vmk;
+                    untangle(a[conv_pad(spectrum_pos<M>(kk))], conj(a[conv_pad(spectrum_pos<M>((M - kk) & (M - 1)))]), w,
+                             Vk, Vmk);
+                    const cplx pk = cmul(Gk[i], conj(Vk)), pmk = cmul(Gmk[i], conj(Vmk));
+                    if constexpr (ACC_MEM) {
+                        float4 t = make_float4(pk.x, pk.y, pmk.x, pmk.y);
+                        if (b > 0) { const float4 o = accm[l]; t.x += o.x; t.y += o.y; t.z += o.z; t.w += o.w; }
+                        accm[l] = t;
+                    } else {
+                        accK[i] = cadd(accK[i], pk);
+                        accMK[i] = cadd(accMK[i], pmk);
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
         __syncthreads();
     }
+    {
+        PairTwiddle<M, T> pw(tid);
 #pragma unroll
-    for (int i = 0; i < NP; ++i) {
-        const int l = tid + T * i, kk = pair_bin<M>(l);
-        if (l <= M / 2) {
-            const int p1 = conv_pad(spectrum_pos<M>(kk)), p2 = conv_pad(spectrum_pos<M>((M - kk) & (M - 1)));
-            if (kk == 0) {
-                a[p1] = mk(0.5f * (accK[i].x + accMK[i].x), 0.5f * (accK[i].x - accMK[i].x));
-            } else {
-                cplx Zk, Zmk;
-                tangle(accK[i], accMK[i], w2m(kk, M), Zk, Zmk);
-                a[p1] = Zk;
-                if (p2 != p1) a[p2] = Zmk;
+        for (int i = 0; i < NP; ++i) {
+            const int l = tid + T * i;
+            if (l <= M / 2) {
+                const int kk = pair_bin<M>(l);
+                const int p1 = conv_pad(spectrum_pos<M>(kk)), p2 = conv_pad(spectrum_pos<M>((M - kk) & (M - 1)));
+                const cplx w = pw.next(l);
+                cplx sk, smk;
+                if constexpr (ACC_MEM) {
+                    const float4 t = B > 0 ? accm[l] : make_float4(0.f, 0.f, 0.f, 0.f);
+                    sk = mk(t.x, t.y);
+                    smk = mk(t.z, t.w);
+                } else {
+                    sk = accK[i];
+                    smk = accMK[i];
+                }
+                if (kk == 0) {
+                    a[p1] = mk(0.5f * (sk.x + smk.x), 0.5f * (sk.x - smk.x));
+                } else {
+                    cplx Zk, Zmk;
+                    tangle(sk, smk, w, Zk, Zmk);
+                    a[p1] = Zk;
+                    if (p2 != p1) a[p2] = Zmk;
+                }
             }
         }
     }
@@ -527,7 +610,6 @@ __global__ __launch_bounds__(conv_threads_dk(M)) void longconv_dk_kernel(const I
     fft_passes<M, T, true>(a, lo, hi, tid);
     __syncthreads();
     float* out = dk + (long)c * L;
-    const float scale = 1.0f / (float)M;
     for (int n = tid; n < M; n += T) {
         const int t = 2 * n;
         if (t < L) {
@@ -540,7 +622,7 @@ __global__ __launch_bounds__(conv_threads_dk(M)) void longconv_dk_kernel(const I
 
 // Gradient through the activation and the short kernel.  dV is the gradient with respect to v = silu(u), u = K_s x:
 //   dU = dV silu'(u),  dX[t] = sum_j w[j] dU[t+j],  dw[c][j] = sum_b sum_t dU[b,c,t] x[b,c,t-j].
-// It also writes v = silu(u) out.  One workgroup per (channel, batch entry, tile of TL steps); x is staged with MT
+// One workgroup per (channel, batch entry, tile of TL steps); x is staged with MT
 // steps of history and dU with MT steps of look-ahead.  Each workgroup leaves its share of the tap sums in `part`
 // ([d][B * tiles][MT]); shortconv_dw_kernel adds the shares of a channel in a fixed order.
 constexpr int kShortTile = 2048, kShortMaxTaps = 16, kShortTilesPerWg = 4;
@@ -549,7 +631,7 @@ constexpr int kShortTile = 2048, kShortMaxTaps = 16, kShortTilesPerWg = 4;
 template <typename IO, int TAPS>
 __global__ __launch_bounds__(256) void shortconv_bwd_kernel(const IO* __restrict__ X, const float* __restrict__ w_short,
                                                            int m, const float* __restrict__ dV, IO* __restrict__ dX,
-                                                           float* __restrict__ part, IO* __restrict__ Vout, int d, int L)
+                                                           float* __restrict__ part, int d, int L)
 {
     constexpr int TL = kShortTile, MT = kShortMaxTaps, H = MT;       // H: halo on either side
     __shared__ __attribute__((aligned(16))) float sx[TL + 2 * H];      // x[t0 - H .. t0 + TL + H)
@@ -579,7 +661,7 @@ __global__ __launch_bounds__(256) void shortconv_bwd_kernel(const IO* __restrict
             const float4 v = *reinterpret_cast<const float4*>(sx + i0 + 4 * r);      // sx index of x[t0 + i] is H + i
             xs[4 * r] = v.x; xs[4 * r + 1] = v.y; xs[4 * r + 2] = v.z; xs[4 * r + 3] = v.w;
         }
-        float du8[8], v8[8], g8[8];
+        float du8[8], g8[8];
         const int tc = t0 + i0;
         const bool whole = vec8 && tc + 8 <= L;         // eight steps in range at a 16-byte aligned address
         if (whole) {
@@ -596,14 +678,6 @@ __global__ __launch_bounds__(256) void shortconv_bwd_kernel(const IO* __restrict
             for (int j = 0; j < TAPS; ++j) u = fmaf(wreg[j], xs[16 + e - j], u);
             const float sg = __builtin_amdgcn_rcpf(1.f + __expf(-u));
             du8[e] = tc + e < L ? g8[e] * sg * (1.f + u * (1.f - sg)) : 0.f;
-            v8[e] = u * sg;                             // v = silu(u), for the long kernel's gradient
-        }
-        if (i0 < TL) {
-            if (whole) store8(Vout + row + tc, v8);
-            else {
-#pragma unroll
-                for (int e = 0; e < 8; ++e) if (tc + e < L) Vout[row + tc + e] = (IO)v8[e];
-            }
         }
         *reinterpret_cast<float4*>(su + i0) = make_float4(du8[0], du8[1], du8[2], du8[3]);
         *reinterpret_cast<float4*>(su + i0 + 4) = make_float4(du8[4], du8[5], du8[6], du8[7]);
@@ -684,7 +758,7 @@ hipError_t launch_longconv_spectrum(const float* k, void* Kf, int d, int L, hipS
     return hipGetLastError();
 }
 
-template <typename IN, typename OUT, bool CONJ>
+template <typename IN, typename OUT>
 static hipError_t conv_dispatch(const IN* X, const float* w, int m, const float4* Kf, OUT* Y, long BD, int d, int L,
                                 hipStream_t st)
 {
@@ -692,10 +766,10 @@ static hipError_t conv_dispatch(const IN* X, const float* w, int m, const float4
     ProfScope prof(KID_CONV_FWD, st);
     const dim3 grid((unsigned)BD);
     switch (M) {
-        case 256: hipLaunchKernelGGL((shortlong_conv_kernel<256, IN, OUT, CONJ>), grid, dim3(conv_threads(256)), 0, st, X, w, m, Kf, Y, d, L); break;
-        case 1024: hipLaunchKernelGGL((shortlong_conv_kernel<1024, IN, OUT, CONJ>), grid, dim3(conv_threads(1024)), 0, st, X, w, m, Kf, Y, d, L); break;
-        case 4096: hipLaunchKernelGGL((shortlong_conv_kernel<4096, IN, OUT, CONJ>), grid, dim3(conv_threads(4096)), 0, st, X, w, m, Kf, Y, d, L); break;
-        case 16384: hipLaunchKernelGGL((shortlong_conv_kernel<16384, IN, OUT, CONJ>), grid, dim3(conv_threads(16384)), 0, st, X, w, m, Kf, Y, d, L); break;
+        case 256: hipLaunchKernelGGL((shortlong_conv_kernel<256, IN, OUT>), grid, dim3(conv_threads(256)), 0, st, X, w, m, Kf, Y, d, L); break;
+        case 1024: hipLaunchKernelGGL((shortlong_conv_kernel<1024, IN, OUT>), grid, dim3(conv_threads(1024)), 0, st, X, w, m, Kf, Y, d, L); break;
+        case 4096: hipLaunchKernelGGL((shortlong_conv_kernel<4096, IN, OUT>), grid, dim3(conv_threads(4096)), 0, st, X, w, m, Kf, Y, d, L); break;
+        case 16384: hipLaunchKernelGGL((shortlong_conv_kernel<16384, IN, OUT>), grid, dim3(conv_threads(16384)), 0, st, X, w, m, Kf, Y, d, L); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -705,55 +779,54 @@ hipError_t launch_shortlong_conv(const void* X, const float* w_short, int m, con
                                  int L, int dtype, hipStream_t st)
 {
     if (dtype == 0)
-        return conv_dispatch<bf16, bf16, false>((const bf16*)X, w_short, m, (const float4*)Kf, (bf16*)Y, BD, d, L, st);
-    return conv_dispatch<float, float, false>((const float*)X, w_short, m, (const float4*)Kf, (float*)Y, BD, d, L, st);
+        return conv_dispatch<bf16, bf16>((const bf16*)X, w_short, m, (const float4*)Kf, (bf16*)Y, BD, d, L, st);
+    return conv_dispatch<float, float>((const float*)X, w_short, m, (const float4*)Kf, (float*)Y, BD, d, L, st);
 }
 
-template <typename IO>
-static hipError_t conv_dk_dispatch(const IO* V, const IO* dZ, float* dk, int B, int d, int L, hipStream_t st)
+template <typename IO, typename DVT>
+static hipError_t conv_longbwd_dispatch(const IO* X, const float* w, int m, const float4* Kf, const IO* dZ, DVT* dV,
+                                        float* dk, float4* acc_ws, int B, int d, int L, hipStream_t st)
 {
     const int M = conv_fft_size(L);
-    ProfScope prof(KID_CONV_DK, st);
+    ProfScope prof(KID_CONV_LONG_BWD, st);
     switch (M) {
-        case 256: hipLaunchKernelGGL((longconv_dk_kernel<256, IO>), dim3(d), dim3(conv_threads_dk(256)), 0, st, V, dZ, dk, B, d, L); break;
-        case 1024: hipLaunchKernelGGL((longconv_dk_kernel<1024, IO>), dim3(d), dim3(conv_threads_dk(1024)), 0, st, V, dZ, dk, B, d, L); break;
-        case 4096: hipLaunchKernelGGL((longconv_dk_kernel<4096, IO>), dim3(d), dim3(conv_threads_dk(4096)), 0, st, V, dZ, dk, B, d, L); break;
-        case 16384: hipLaunchKernelGGL((longconv_dk_kernel<16384, IO>), dim3(d), dim3(conv_threads_dk(16384)), 0, st, V, dZ, dk, B, d, L); break;
+        case 256: hipLaunchKernelGGL((longconv_bwd_kernel<256, IO, DVT>), dim3(d), dim3(conv_threads(256)), 0, st, X, w, m, Kf, dZ, dV, dk, acc_ws, B, d, L); break;
+        case 1024: hipLaunchKernelGGL((longconv_bwd_kernel<1024, IO, DVT>), dim3(d), dim3(conv_threads(1024)), 0, st, X, w, m, Kf, dZ, dV, dk, acc_ws, B, d, L); break;
+        case 4096: hipLaunchKernelGGL((longconv_bwd_kernel<4096, IO, DVT>), dim3(d), dim3(conv_threads(4096)), 0, st, X, w, m, Kf, dZ, dV, dk, acc_ws, B, d, L); break;
+        case 16384: hipLaunchKernelGGL((longconv_bwd_kernel<16384, IO, DVT>), dim3(d), dim3(conv_threads(16384)), 0, st, X, w, m, Kf, dZ, dV, dk, acc_ws, B, d, L); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
 }
 
-// ws: scratch, used only with a short kernel: B*d*L floats (dV), the workgroups' tap sums, then B*d*L elements of
-// the I/O type (v).
+// ws: the running sums of the long-kernel gradient (largest transform size only), then, with a short kernel,
+// B*d*L floats (dV) and the workgroups' tap sums.
 template <typename IO>
 static hipError_t conv_bwd_impl(const IO* X, const float* w_short, int m, const float4* Kf, const IO* dZ, IO* dX,
                                 float* dw, float* dk, float* ws, int B, int d, int L, hipStream_t st)
 {
     hipError_t e;
     const long BD = (long)B * d;
-    if (w_short == nullptr) {
-        // no short stage: v = x and dX is the correlation of dZ with the long kernel itself
-        if ((e = conv_dispatch<IO, IO, true>(dZ, nullptr, 0, Kf, dX, BD, d, L, st)) != hipSuccess) return e;
-        return conv_dk_dispatch<IO>(X, dZ, dk, B, d, L, st);
-    }
+    float4* acc_ws = reinterpret_cast<float4*>(ws);
+    ws += conv_bwd_acc_floats(d, L);
+    if (w_short == nullptr)   // no short stage: v = x and dX is the correlation of dZ with the long kernel itself
+        return conv_longbwd_dispatch<IO, IO>(X, nullptr, 0, Kf, dZ, dX, dk, acc_ws, B, d, L, st);
     float* ws_dV = ws;
     const int tiles = ((L + kShortTile - 1) / kShortTile + kShortTilesPerWg - 1) / kShortTilesPerWg;   // tile groups
     float* ws_part = ws + (size_t)BD * L;                                   // [d][B * tiles][16]
-    IO* ws_V = reinterpret_cast<IO*>(ws_part + (size_t)BD * tiles * kShortMaxTaps);
-    if ((e = conv_dispatch<IO, float, true>(dZ, nullptr, 0, Kf, ws_dV, BD, d, L, st)) != hipSuccess) return e;
+    if ((e = conv_longbwd_dispatch<IO, float>(X, w_short, m, Kf, dZ, ws_dV, dk, acc_ws, B, d, L, st)) != hipSuccess) return e;
     {
         ProfScope prof(KID_CONV_SHORT_BWD, st);
         const dim3 grid(d, B, tiles);
-        if (m <= 4) hipLaunchKernelGGL((shortconv_bwd_kernel<IO, 4>), grid, dim3(256), 0, st, X, w_short, m, ws_dV, dX, ws_part, ws_V, d, L);
-        else if (m <= 8) hipLaunchKernelGGL((shortconv_bwd_kernel<IO, 8>), grid, dim3(256), 0, st, X, w_short, m, ws_dV, dX, ws_part, ws_V, d, L);
-        else if (m <= 12) hipLaunchKernelGGL((shortconv_bwd_kernel<IO, 12>), grid, dim3(256), 0, st, X, w_short, m, ws_dV, dX, ws_part, ws_V, d, L);
-        else hipLaunchKernelGGL((shortconv_bwd_kernel<IO, 16>), grid, dim3(256), 0, st, X, w_short, m, ws_dV, dX, ws_part, ws_V, d, L);
+        if (m <= 4) hipLaunchKernelGGL((shortconv_bwd_kernel<IO, 4>), grid, dim3(256), 0, st, X, w_short, m, ws_dV, dX, ws_part, d, L);
+        else if (m <= 8) hipLaunchKernelGGL((shortconv_bwd_kernel<IO, 8>), grid, dim3(256), 0, st, X, w_short, m, ws_dV, dX, ws_part, d, L);
+        else if (m <= 12) hipLaunchKernelGGL((shortconv_bwd_kernel<IO, 12>), grid, dim3(256), 0, st, X, w_short, m, ws_dV, dX, ws_part, d, L);
+        else hipLaunchKernelGGL((shortconv_bwd_kernel<IO, 16>), grid, dim3(256), 0, st, X, w_short, m, ws_dV, dX, ws_part, d, L);
         if ((e = hipGetLastError()) != hipSuccess) return e;
         hipLaunchKernelGGL(shortconv_dw_kernel, dim3(d), dim3(64), 0, st, ws_part, dw, m, B * tiles);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
-    return conv_dk_dispatch<IO>(ws_V, dZ, dk, B, d, L, st);
+    return hipSuccess;
 }
 
 // Backward of Z = K_l(silu(K_s X)): dX (I/O dtype), dw [d][m] (with a short kernel, m <= 16), dk [d][L] fp32.
