@@ -101,13 +101,25 @@ hipError_t launch_longconv_spectrum(const float* k, void* Kf, int d, int L, hipS
 hipError_t launch_shortlong_conv(const void* X, const float* w_short, int m, const void* Kf, void* Y, long BD, int d,
                                  int L, int dtype, hipStream_t st);
 // Gradient: dX [B][d][L] (I/O dtype), dw [d][m] (only with a short kernel, m <= 16), dk [d][L] fp32.
-// ws: conv_bwd_acc_floats(d, L) floats (running sums of the long-kernel gradient at the largest transform size: they
-// no longer fit the registers of 1024 threads), then, with a short kernel, B*d*L floats (dV) and the workgroups' tap
+// ws: conv_bwd_acc_floats(B, d, L) floats (running sums of the long-kernel gradient: at the largest transform size
+// they no longer fit the registers of 1024 threads, and workgroups that share a channel leave their shares there), then, with a short kernel, B*d*L floats (dV) and the workgroups' tap
 // sums.
-inline size_t conv_bwd_acc_floats(int d, int L)
+// Workgroups that share a channel in the long-stage gradient kernel (each takes every G-th sequence): more than one
+// when the channels alone would leave the GPU underfilled.
+inline int conv_bwd_groups(int B, int d, int L)
 {
     const int M = conv_fft_size(L);
-    return M >= 16384 ? (size_t)d * (M / 2 + 1) * 4 : 0;
+    if (M == 0 || B <= 1 || d <= 0) return 1;
+    const long slots = 256L * (M >= 16384 ? 1 : M >= 4096 ? 3 : 4);      // resident workgroups of that kernel
+    long g = (2 * slots + d - 1) / d;
+    if (g > B) g = B;
+    if (g > 64) g = 64;
+    return g < 1 ? 1 : (int)g;
+}
+inline size_t conv_bwd_acc_floats(int B, int d, int L)
+{
+    const int M = conv_fft_size(L), G = conv_bwd_groups(B, d, L);
+    return (M >= 16384 || G > 1) ? (size_t)G * d * (M / 2 + 1) * 4 : 0;
 }
 hipError_t launch_shortlong_conv_bwd(const void* X, const float* w_short, int m, const void* Kf, const void* dZ,
                                      void* dX, float* dw, float* dk, float* ws_dV, int B, int d, int L, int dtype,

@@ -460,7 +460,10 @@ __global__ __launch_bounds__(conv_threads(M)) void shortlong_conv_kernel(const I
 // and adds DZ conj(V) to the running sums of its bin pairs, also in registers; after the last sequence the sums are
 // transformed back once (dk).  Three transforms per sequence instead of the four of the two separate kernels, at the
 // forward kernel's full thread count.
-template <int M, typename IO, typename DVT>
+// SPLIT: grid.y workgroups share a channel, each takes every grid.y-th sequence and leaves its sums in its own slice
+// of the scratch array ([grid.y][d][M/2 + 1] pairs); longconv_dk_finish_kernel adds the slices up and transforms back.
+// Used when there are too few channels to fill the GPU.
+template <int M, typename IO, typename DVT, bool SPLIT>
 __global__ __launch_bounds__(conv_threads(M)) void longconv_bwd_kernel(const IO* __restrict__ X,
                                                                       const float* __restrict__ w_short, int m,
                                                                       const float4* __restrict__ Kf,
@@ -473,7 +476,7 @@ __global__ __launch_bounds__(conv_threads(M)) void longconv_bwd_kernel(const IO*
     // At the largest size 1024 threads share the register file: the running sums then live in a scratch array in
     // memory ([d][M/2 + 1] pairs; every thread only ever touches its own pairs, between uses they sit in the caches).
     constexpr bool ACC_MEM = M >= 16384;
-    float4* accm = ACC_MEM ? acc_ws + (long)blockIdx.x * (M / 2 + 1) : nullptr;
+    float4* accm = (ACC_MEM || SPLIT) ? acc_ws + ((long)blockIdx.y * d + blockIdx.x) * (M / 2 + 1) : nullptr;
     __shared__ __attribute__((aligned(16))) unsigned char lds[ConvLds<M>::BYTES];
     cplx* a = reinterpret_cast<cplx*>(lds);
     cplx* lo = a + ConvLds<M>::DATA;
@@ -491,7 +494,7 @@ __global__ __launch_bounds__(conv_threads(M)) void longconv_bwd_kernel(const IO*
         for (int i = 0; i < NP; ++i) { accK[i] = mk(0.f, 0.f); accMK[i] = mk(0.f, 0.f); }
     }
 
-    for (int b = 0; b < B; ++b) {
+    for (int b = blockIdx.y; b < B; b += gridDim.y) {
         const long row = ((long)b * d + c) * L;
         // ---- spectrum of dZ; correlation with the kernel: DZ conj(K)
         stage_input<M, T, IO>(dZ + row, nullptr, 0, L, a, tid);
@@ -565,7 +568,7 @@ __global__ __launch_bounds__(conv_threads(M)) void longconv_bwd_kernel(const IO*
                     const cplx pk = cmul(Gk[i], conj(Vk)), pmk = cmul(Gmk[i], conj(Vmk));
                     if constexpr (ACC_MEM) {
                         float4 t = make_float4(pk.x, pk.y, pmk.x, pmk.y);
-                        if (b > 0) { const float4 o = accm[l]; t.x += o.x; t.y += o.y; t.z += o.z; t.w += o.w; }
+                        if (b != (int)blockIdx.y) { const float4 o = accm[l]; t.x += o.x; t.y += o.y; t.z += o.z; t.w += o.w; }
                         accm[l] = t;
                     } else {
                         accK[i] = cadd(accK[i], pk);
@@ -576,6 +579,18 @@ __global__ __launch_bounds__(conv_threads(M)) void longconv_bwd_kernel(const IO*
             }
         }
         __syncthreads();
+    }
+    if constexpr (SPLIT) {
+        // this workgroup's share of the sums stays in its slice of the scratch array (it is there already when the
+        // sums were kept in memory)
+        if constexpr (!ACC_MEM) {
+#pragma unroll
+            for (int i = 0; i < NP; ++i) {
+                const int l = tid + T * i;
+                if (l <= M / 2) accm[l] = make_float4(accK[i].x, accK[i].y, accMK[i].x, accMK[i].y);
+            }
+        }
+        return;
     }
     {
         PairTwiddle<M, T> pw(tid);
@@ -783,19 +798,76 @@ hipError_t launch_shortlong_conv(const void* X, const float* w_short, int m, con
     return conv_dispatch<float, float>((const float*)X, w_short, m, (const float4*)Kf, (float*)Y, BD, d, L, st);
 }
 
+// Second step of the split long-stage gradient: add up the G slices of a channel's sums, transform back, store dk.
+template <int M>
+__global__ __launch_bounds__(conv_threads(M)) void longconv_dk_finish_kernel(const float4* __restrict__ part,
+                                                                            float* __restrict__ dk, int G, int d, int L)
+{
+    constexpr int T = conv_threads(M);
+    __shared__ __attribute__((aligned(16))) unsigned char lds[ConvLds<M>::BYTES];
+    cplx* a = reinterpret_cast<cplx*>(lds);
+    cplx* lo = a + ConvLds<M>::DATA;
+    cplx* hi = lo + 128;
+    const int tid = threadIdx.x;
+    const int c = blockIdx.x;
+    build_tables<M, T>(lo, hi, tid);
+    PairTwiddle<M, T> pw(tid);
+    for (int l = tid; l <= M / 2; l += T) {
+        const int kk = pair_bin<M>(l);
+        const int p1 = conv_pad(spectrum_pos<M>(kk)), p2 = conv_pad(spectrum_pos<M>((M - kk) & (M - 1)));
+        const cplx w = pw.next(l);
+        float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int g = 0; g < G; ++g) {      // fixed order: deterministic
+            const float4 o = part[((long)g * d + c) * (M / 2 + 1) + l];
+            t.x += o.x; t.y += o.y; t.z += o.z; t.w += o.w;
+        }
+        const cplx sk = mk(t.x, t.y), smk = mk(t.z, t.w);
+        if (kk == 0) {
+            a[p1] = mk(0.5f * (sk.x + smk.x), 0.5f * (sk.x - smk.x));
+        } else {
+            cplx Zk, Zmk;
+            tangle(sk, smk, w, Zk, Zmk);
+            a[p1] = Zk;
+            if (p2 != p1) a[p2] = Zmk;
+        }
+    }
+    __syncthreads();
+    fft_passes<M, T, true>(a, lo, hi, tid);
+    __syncthreads();
+    float* out = dk + (long)c * L;
+    const float scale = 1.0f / (float)M;
+    for (int n = tid; n < M; n += T) {
+        const int t = 2 * n;
+        if (t < L) {
+            const cplx v = a[conv_pad(n)];
+            out[t] = v.x * scale;
+            if (t + 1 < L) out[t + 1] = v.y * scale;
+        }
+    }
+}
+
 template <typename IO, typename DVT>
 static hipError_t conv_longbwd_dispatch(const IO* X, const float* w, int m, const float4* Kf, const IO* dZ, DVT* dV,
                                         float* dk, float4* acc_ws, int B, int d, int L, hipStream_t st)
 {
-    const int M = conv_fft_size(L);
+    const int M = conv_fft_size(L), G = conv_bwd_groups(B, d, L);
     ProfScope prof(KID_CONV_LONG_BWD, st);
+    const dim3 grid(d, G);
+#define CHELA_LONGBWD(M_)                                                                                               \
+    case M_:                                                                                                            \
+        if (G > 1) {                                                                                                    \
+            hipLaunchKernelGGL((longconv_bwd_kernel<M_, IO, DVT, true>), grid, dim3(conv_threads(M_)), 0, st, X, w, m, Kf, \
+                               dZ, dV, dk, acc_ws, B, d, L);                                                            \
+            hipLaunchKernelGGL((longconv_dk_finish_kernel<M_>), dim3(d), dim3(conv_threads(M_)), 0, st, acc_ws, dk, G, d, L); \
+        } else                                                                                                          \
+            hipLaunchKernelGGL((longconv_bwd_kernel<M_, IO, DVT, false>), grid, dim3(conv_threads(M_)), 0, st, X, w, m, Kf, \
+                               dZ, dV, dk, acc_ws, B, d, L);                                                            \
+        break;
     switch (M) {
-        case 256: hipLaunchKernelGGL((longconv_bwd_kernel<256, IO, DVT>), dim3(d), dim3(conv_threads(256)), 0, st, X, w, m, Kf, dZ, dV, dk, acc_ws, B, d, L); break;
-        case 1024: hipLaunchKernelGGL((longconv_bwd_kernel<1024, IO, DVT>), dim3(d), dim3(conv_threads(1024)), 0, st, X, w, m, Kf, dZ, dV, dk, acc_ws, B, d, L); break;
-        case 4096: hipLaunchKernelGGL((longconv_bwd_kernel<4096, IO, DVT>), dim3(d), dim3(conv_threads(4096)), 0, st, X, w, m, Kf, dZ, dV, dk, acc_ws, B, d, L); break;
-        case 16384: hipLaunchKernelGGL((longconv_bwd_kernel<16384, IO, DVT>), dim3(d), dim3(conv_threads(16384)), 0, st, X, w, m, Kf, dZ, dV, dk, acc_ws, B, d, L); break;
+        CHELA_LONGBWD(256) CHELA_LONGBWD(1024) CHELA_LONGBWD(4096) CHELA_LONGBWD(16384)
         default: return hipErrorInvalidValue;
     }
+#undef CHELA_LONGBWD
     return hipGetLastError();
 }
 
@@ -808,7 +880,7 @@ static hipError_t conv_bwd_impl(const IO* X, const float* w_short, int m, const 
     hipError_t e;
     const long BD = (long)B * d;
     float4* acc_ws = reinterpret_cast<float4*>(ws);
-    ws += conv_bwd_acc_floats(d, L);
+    ws += conv_bwd_acc_floats(B, d, L);
     if (w_short == nullptr)   // no short stage: v = x and dX is the correlation of dZ with the long kernel itself
         return conv_longbwd_dispatch<IO, IO>(X, nullptr, 0, Kf, dZ, dX, dk, acc_ws, B, d, L, st);
     float* ws_dV = ws;
