@@ -275,7 +275,7 @@ static int fwd_common(const void* Q, const void* K, const void* V, void* O, cons
         // no tokens: the state passes through unchanged
         if (S_out && BH > 0) {
             hipError_t e = S_in ? hipMemcpyAsync(S_out, S_in, sb, hipMemcpyDeviceToDevice, (hipStream_t)stream)
-                                : hipMemsetAsync(S_out, 0, sb, (hipStream_t)stream);
+                                : launch_zero_fill(S_out, sb / sizeof(float), (hipStream_t)stream);
             return e == hipSuccess ? CHELA_OK : CHELA_ERR_HIP;
         }
         return CHELA_OK;
@@ -313,7 +313,7 @@ static int bwd_common(const void* Q, const void* K, const void* V, const void* d
     if (empty) {
         if (dS_in && BH > 0) {
             hipError_t e = dS_out ? hipMemcpyAsync(dS_in, dS_out, sb, hipMemcpyDeviceToDevice, st)
-                                  : hipMemsetAsync(dS_in, 0, sb, st);
+                                  : launch_zero_fill(dS_in, sb / sizeof(float), st);
             return e == hipSuccess ? CHELA_OK : CHELA_ERR_HIP;
         }
         return CHELA_OK;
@@ -395,7 +395,7 @@ static int zbwd_common(const void* Z, const float* aff, const void* V, const voi
     if (rc != CHELA_OK) return rc;
     if (empty) {
         // no tokens: the parameters received no gradient
-        if (d_aff && ab) return hipMemsetAsync(d_aff, 0, ab, (hipStream_t)stream) == hipSuccess ? CHELA_OK : CHELA_ERR_HIP;
+        if (d_aff && ab) return launch_zero_fill(d_aff, ab / sizeof(float), (hipStream_t)stream) == hipSuccess ? CHELA_OK : CHELA_ERR_HIP;
         return CHELA_OK;
     }
     Plan plan = want_saved ? t.bwd : make_plan(BH, N, dk, dv, 64, CHELA_DTYPE_BF16, true, false);
@@ -807,8 +807,8 @@ static int shortlong_bwd_common(const void* X, const float* w_short, int m, cons
     if (B == 0) {
         // no data: the kernels received no gradient
         if (!d_k_long || (w_short && !d_w_short)) return CHELA_ERR_NULL_POINTER;
-        hipError_t e = hipMemsetAsync(d_k_long, 0, (size_t)d * L * 4, st);
-        if (e == hipSuccess && w_short) e = hipMemsetAsync(d_w_short, 0, (size_t)d * m * 4, st);
+        hipError_t e = launch_zero_fill(d_k_long, (size_t)d * L, st);
+        if (e == hipSuccess && w_short) e = launch_zero_fill(d_w_short, (size_t)d * m, st);
         return e == hipSuccess ? CHELA_OK : CHELA_ERR_HIP;
     }
     if (!X || !spectrum || !dZ || !dX || !d_k_long || (w_short && !d_w_short)) return CHELA_ERR_NULL_POINTER;

@@ -32,6 +32,7 @@ hipError_t scan_states(float* states, size_t array_stride, int n_arrays, const i
 // Streaming copy used to calibrate byte counters.
 hipError_t launch_copy(const void* src, void* dst, size_t bytes, hipStream_t st);
 // n_in (1..4) arrays read, n_out (1..4) arrays written, `bytes` each, by a plain grid-stride kernel.
+hipError_t launch_zero_fill(float* p, size_t n_floats, hipStream_t st);      // a fill kernel, not a memset node
 hipError_t launch_stream_probe(const void* const* in, int n_in, void* const* out, int n_out, size_t bytes,
                                hipStream_t st);
 

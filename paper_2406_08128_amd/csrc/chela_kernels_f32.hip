@@ -151,6 +151,22 @@ static hipError_t stream_dispatch(const StreamArgs& a, int n_out, size_t n, dim3
     return hipGetLastError();
 }
 
+// Zero `n` floats.  Used instead of hipMemsetAsync so that every call of the library can be captured into a HIP graph
+// (memset nodes have replayed wrongly on this platform).
+__global__ __launch_bounds__(256) void zero_fill_kernel(float* __restrict__ p, size_t n)
+{
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) p[i] = 0.f;
+}
+
+hipError_t launch_zero_fill(float* p, size_t n, hipStream_t st)
+{
+    if (n == 0) return hipSuccess;
+    size_t blocks = (n + 255) / 256;
+    if (blocks > 2048) blocks = 2048;
+    hipLaunchKernelGGL(zero_fill_kernel, dim3((unsigned)blocks), dim3(256), 0, st, p, n);
+    return hipGetLastError();
+}
+
 hipError_t launch_stream_probe(const void* const* in, int n_in, void* const* out, int n_out, size_t bytes, hipStream_t st)
 {
     StreamArgs a{};

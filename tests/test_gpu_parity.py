@@ -268,6 +268,28 @@ def test_empty_inputs_on_device():
     assert O.shape == (2, 2, 0, 64)
 
 
+def test_no_tokens_pass_states_through_and_zero_parameter_gradients():
+    # the degenerate calls that move no tokens still owe their small outputs: a carried state comes out unchanged
+    # (or zero when none came in), kernels that saw no data get zero gradients
+    e = torch.empty((2, 3, 0, 64), dtype=torch.bfloat16, device="cuda")
+    g = torch.Generator(device="cpu")
+    g.manual_seed(99)
+    S = torch.randn(2, 3, 64, 64, generator=g).cuda()
+    poison = lambda: torch.full((2, 3, 64, 64), float("nan"), device="cuda")
+    _, S1 = binding.chela_linattn_fwd_state(e, e, e, S_in=S, S_out=poison())
+    _, S0 = binding.chela_linattn_fwd_state(e, e, e, S_in=None, S_out=poison())
+    *_, dS1 = binding.chela_linattn_bwd_state(e, e, e, e, S_in=S, dS_out=S)
+    *_, dS0 = binding.chela_linattn_bwd_state(e, e, e, e, S_in=S, dS_out=None)
+    x = make_conv_inputs(1, 3, 300, 5, 5, "bf16")
+    spec = binding.chela_longconv_spectrum(x["k_long"].cuda())
+    eb = torch.empty((0, 3, 300), dtype=torch.bfloat16, device="cuda")
+    dX, dw, dk = binding.chela_shortlong_conv_bwd(eb, x["w_short"].cuda(), spec, eb)
+    torch.cuda.synchronize()
+    assert torch.equal(S1, S) and torch.equal(dS1, S)
+    assert float(S0.abs().max()) == 0.0 and float(dS0.abs().max()) == 0.0
+    assert dX.numel() == 0 and float(dw.abs().max()) == 0.0 and float(dk.abs().max()) == 0.0
+
+
 # ------------------------------------------------------------------------------------------ carried state, decode step
 STATE_SHAPES = [(1, 2, 64, 64, 64), (2, 2, 1000, 64, 64), (1, 3, 2048, 64, 64), (2, 1, 700, 64, 128),
                 (1, 2, 900, 128, 64), (1, 2, 1500, 128, 128), (1, 1, 1, 64, 64)]
