@@ -184,12 +184,33 @@ __device__ __forceinline__ void fft_passes(cplx* a, const cplx* lo, const cplx* 
     }
 }
 
+// raw_t: the pair (x[t], x[t+1]) as it sits in memory, so that a sequence fetched ahead costs as few registers as it
+// costs bytes; raw_pair() reads an aligned pair, raw_scalars() builds one from single reads (odd row lengths, the
+// second element optional), unpack() converts.
 template <typename T> struct IoPair;
 template <> struct IoPair<float> {
+    typedef float2 raw_t;
+    static __device__ __forceinline__ raw_t raw_zero() { return make_float2(0.f, 0.f); }
+    static __device__ __forceinline__ raw_t raw_pair(const float* p) { return *reinterpret_cast<const float2*>(p); }
+    static __device__ __forceinline__ raw_t raw_scalars(const float* p, bool second) { return make_float2(p[0], second ? p[1] : 0.f); }
+    static __device__ __forceinline__ void unpack(raw_t r, float& a, float& b) { a = r.x; b = r.y; }
     static __device__ __forceinline__ void load2(const float* p, float& a, float& b) { const float2 v = *reinterpret_cast<const float2*>(p); a = v.x; b = v.y; }
     static __device__ __forceinline__ void store2(float* p, float a, float b) { *reinterpret_cast<float2*>(p) = make_float2(a, b); }
 };
 template <> struct IoPair<bf16> {
+    typedef unsigned raw_t;
+    static __device__ __forceinline__ raw_t raw_zero() { return 0u; }
+    static __device__ __forceinline__ raw_t raw_pair(const bf16* p) { return *reinterpret_cast<const unsigned*>(p); }
+    static __device__ __forceinline__ raw_t raw_scalars(const bf16* p, bool second)
+    {
+        const unsigned short* q = reinterpret_cast<const unsigned short*>(p);
+        return (unsigned)q[0] | (second ? (unsigned)q[1] << 16 : 0u);
+    }
+    static __device__ __forceinline__ void unpack(raw_t u, float& a, float& b)
+    {
+        a = __builtin_bit_cast(float, u << 16);
+        b = __builtin_bit_cast(float, u & 0xffff0000u);
+    }
     static __device__ __forceinline__ void load2(const bf16* p, float& a, float& b)
     {
         const unsigned u = *reinterpret_cast<const unsigned*>(p);
@@ -299,40 +320,57 @@ __device__ __forceinline__ void tangle(cplx Yk, cplx Ymk, cplx w, cplx& Zk, cplx
 }
 
 
-// x (one sequence of L steps) -> optional short kernel and activation -> packed complex z[n] = v[2n] + i v[2n+1]
-// in a[], zero beyond L.  Ends with the data in place but NOT synchronised.
+// One sequence of L <= M steps in registers: the pairs (x[2n], x[2n+1]) for n = tid + T i.  Only n < M/2 can lie
+// inside the sequence, so half of a thread's M/T slots are enough.  A kernel that walks several sequences fetches the
+// next one into these registers while the transforms of the current one run.
 template <int M, int T, typename IO>
-__device__ __forceinline__ void stage_input(const IO* __restrict__ x, const float* __restrict__ wc, int m, int L,
+struct SeqRegs {
+    static constexpr int HELD = M / T / 2;
+    typename IoPair<IO>::raw_t r[HELD];
+    __device__ __forceinline__ void load(const IO* __restrict__ x, int L, int tid)
+    {
+        const bool vec_ok = (L & 1) == 0;        // rows start on a pair boundary
+#pragma unroll
+        for (int i = 0; i < HELD; ++i) {
+            const int t = 2 * (tid + T * i);
+            r[i] = IoPair<IO>::raw_zero();
+            if (t < L) r[i] = vec_ok ? IoPair<IO>::raw_pair(x + t) : IoPair<IO>::raw_scalars(x + t, t + 1 < L);
+        }
+    }
+};
+
+// x (one sequence of L steps, in registers) -> optional short kernel and activation -> packed complex
+// z[n] = v[2n] + i v[2n+1] in a[], zero beyond L.  Ends with the data in place but NOT synchronised.
+template <int M, int T, typename IO>
+__device__ __forceinline__ void stage_input(const SeqRegs<M, T, IO>& x, const float* __restrict__ wc, int m, int L,
                                             cplx* a, int tid)
 {
-    const bool vec_ok = (L & 1) == 0;        // rows start on a pair boundary
+    constexpr int PER = M / T, HELD = PER / 2;
     if (wc != nullptr) {
         // raw x as floats behind 32 zeros (the zero history), so that no tap needs a bounds check
         float* sx = reinterpret_cast<float*>(a);
         constexpr int ZP = 32;
         if (tid < ZP) sx[tid] = 0.f;
-        for (int n = tid; n < M; n += T) {
-            const int t = 2 * n;
+#pragma unroll
+        for (int i = 0; i < HELD; ++i) {
+            const int t = 2 * (tid + T * i);
             if (t < L) {
-                float v0, v1 = 0.f;
-                if (vec_ok) IoPair<IO>::load2(x + t, v0, v1);
-                else { v0 = (float)x[t]; if (t + 1 < L) v1 = (float)x[t + 1]; }
-                sx[ZP + t] = v0;
-                sx[ZP + t + 1] = v1;
+                float v0, v1;
+                IoPair<IO>::unpack(x.r[i], v0, v1);
+                *reinterpret_cast<float2*>(sx + ZP + t) = make_float2(v0, v1);
             }
         }
         __syncthreads();
-        constexpr int PER = M / T;
-        cplx z[PER];
+        cplx z[HELD];
 #pragma unroll
-        for (int i = 0; i < PER; ++i) z[i] = mk(0.f, 0.f);
+        for (int i = 0; i < HELD; ++i) z[i] = mk(0.f, 0.f);
         // outputs t and t+1 share all but one of their inputs; x is read in aligned pairs (x[t-2p], x[t-2p+1]):
         // x[t-2p+1] meets taps 2p (for t+1) and 2p-1 (for t), x[t-2p] meets taps 2p+1 (for t+1) and 2p (for t)
         for (int p = 0; 2 * p <= m; ++p) {
             const float w2p = 2 * p < m ? wc[2 * p] : 0.f, w2pm1 = p > 0 ? wc[2 * p - 1] : 0.f;
             const float w2pp1 = 2 * p + 1 < m ? wc[2 * p + 1] : 0.f;
 #pragma unroll
-            for (int i = 0; i < PER; ++i) {
+            for (int i = 0; i < HELD; ++i) {
                 const int t = 2 * (tid + T * i);
                 if (t < L) {
                     const float2 xv = *reinterpret_cast<const float2*>(sx + ZP + t - 2 * p);
@@ -342,23 +380,20 @@ __device__ __forceinline__ void stage_input(const IO* __restrict__ x, const floa
             }
         }
 #pragma unroll
-        for (int i = 0; i < PER; ++i) {
+        for (int i = 0; i < HELD; ++i) {
             const int t = 2 * (tid + T * i);
             z[i].x = z[i].x * __builtin_amdgcn_rcpf(1.f + __expf(-z[i].x));
             z[i].y = (t + 1 < L) ? z[i].y * __builtin_amdgcn_rcpf(1.f + __expf(-z[i].y)) : 0.f;
         }
         __syncthreads();
 #pragma unroll
-        for (int i = 0; i < PER; ++i) a[conv_pad(tid + T * i)] = z[i];
+        for (int i = 0; i < PER; ++i) a[conv_pad(tid + T * i)] = i < HELD ? z[i < HELD ? i : 0] : mk(0.f, 0.f);
     } else {
-        for (int n = tid; n < M; n += T) {
-            const int t = 2 * n;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
             float v0 = 0.f, v1 = 0.f;
-            if (t < L) {
-                if (vec_ok) IoPair<IO>::load2(x + t, v0, v1);
-                else { v0 = (float)x[t]; if (t + 1 < L) v1 = (float)x[t + 1]; }
-            }
-            a[conv_pad(n)] = mk(v0, v1);
+            if (i < HELD) IoPair<IO>::unpack(x.r[i < HELD ? i : 0], v0, v1);
+            a[conv_pad(tid + T * i)] = mk(v0, v1);
         }
     }
 }
@@ -376,7 +411,9 @@ __global__ __launch_bounds__(conv_threads(M)) void longconv_spectrum_kernel(cons
     const int tid = threadIdx.x;
     const long c = blockIdx.x;
     build_tables<M, T>(lo, hi, tid);
-    stage_input<M, T, float>(k + c * (long)L, nullptr, 0, L, a, tid);
+    SeqRegs<M, T, float> kr;
+    kr.load(k + c * (long)L, L, tid);
+    stage_input<M, T, float>(kr, nullptr, 0, L, a, tid);
     __syncthreads();
     fft_passes<M, T, false>(a, lo, hi, tid);
     __syncthreads();
@@ -390,64 +427,99 @@ __global__ __launch_bounds__(conv_threads(M)) void longconv_spectrum_kernel(cons
     }
 }
 
-// One workgroup per (b, c).  w_short == nullptr: no short kernel and no activation (plain long convolution).
+// Workgroup g takes the sequences (b, c) = g, g + gridDim.x, ... of the B d in turn (w_short == nullptr: no short
+// kernel and no activation, the plain long convolution).  The launch holds no more workgroups than are resident
+// at once, so that the tables are built once per workgroup, a sequence's input is fetched while the inverse transform
+// of the one before runs, and its kernel spectrum while the forward transform runs: with one workgroup per sequence
+// each of those latencies was exposed once per sequence, since at the larger sizes a compute unit holds one
+// workgroup only.
 template <int M, typename IN, typename OUT>
 __global__ __launch_bounds__(conv_threads(M)) void shortlong_conv_kernel(const IN* __restrict__ X,
                                                                         const float* __restrict__ w_short, int m,
                                                                         const float4* __restrict__ Kf,
-                                                                        OUT* __restrict__ Y, int d, int L)
+                                                                        OUT* __restrict__ Y, int d, int L, long total)
 {
     constexpr int T = conv_threads(M);
+    constexpr int NP = (M / 2) / T + 1;          // bin pairs per thread (the last one only exists for l = M/2)
+    constexpr bool FRESH = sizeof(IN) == 4;
     __shared__ __attribute__((aligned(16))) unsigned char lds[ConvLds<M>::BYTES];
     cplx* a = reinterpret_cast<cplx*>(lds);
     cplx* lo = a + ConvLds<M>::DATA;
     cplx* hi = lo + 128;
     const int tid = threadIdx.x;
-    const long bc = blockIdx.x;
-    const int c = (int)(bc % d);
-    OUT* y = Y + bc * (long)L;
     build_tables<M, T>(lo, hi, tid);
-    stage_input<M, T, IN>(X + bc * (long)L, w_short ? w_short + (long)c * m : nullptr, m, L, a, tid);
-    __syncthreads();
-
-    fft_passes<M, T, false>(a, lo, hi, tid);
-    __syncthreads();
-
-    // ---- spectrum of v times spectrum of the kernel, re-packed for the inverse transform (pairs k, M - k)
-    const float4* Kc = Kf + (long)c * (M / 2 + 1);
-    PairTwiddle<M, T> pw(tid);
-    for (int l = tid; l <= M / 2; l += T) {
-        const int kk = pair_bin<M>(l);
-        const int p1 = conv_pad(spectrum_pos<M>(kk)), p2 = conv_pad(spectrum_pos<M>((M - kk) & (M - 1)));
-        const cplx w = pw.next(l);
-        cplx Xk, Xmk, Zk, Zmk;
-        untangle(a[p1], conj(a[p2]), w, Xk, Xmk);
-        const float4 kq = Kc[l];
-        const cplx K1 = mk(kq.x, kq.y), K2 = mk(kq.z, kq.w);
-        if (kk == 0) {
-            // bins 0 and M are real and share storage slot 0
-            const float y0 = Xk.x * K1.x, ym = Xmk.x * K2.x;
-            a[p1] = mk(0.5f * (y0 + ym), 0.5f * (y0 - ym));
-        } else {
-            tangle(cmul(Xk, K1), cmul(Xmk, K2), w, Zk, Zmk);
-            a[p1] = Zk;
-            if (p2 != p1) a[p2] = Zmk;
+    SeqRegs<M, T, IN> xr;
+    long bc = blockIdx.x;
+    if (bc < total) xr.load(X + bc * (long)L, L, tid);
+    for (; bc < total; bc += gridDim.x) {
+        const int c = (int)(bc % d);
+        OUT* y = Y + bc * (long)L;
+        // what depends on the thread but not on the sequence (LDS addresses, bin positions, twiddles) is recomputed
+        // per sequence behind an opaque copy of the thread index: hoisted out of this loop it would fill the
+        // register file.  With fp32 I/O (twice the registers for the sequence fetched ahead) every stage takes a
+        // fresh copy, so that positions shared between stages do not stay live in between; with bf16 I/O there is
+        // room, and sharing them measured 3 % faster.
+        int tp = tid;
+        asm volatile("" : "+v"(tp));
+        __syncthreads();        // the tables are built / the previous sequence has been read out of a[]
+        stage_input<M, T, IN>(xr, w_short ? w_short + (long)c * m : nullptr, m, L, a, tp);
+        const float4* Kc = Kf + (long)c * (M / 2 + 1);
+        float4 kq[NP];
+#pragma unroll
+        for (int i = 0; i < NP; ++i) {
+            const int l = tp + T * i;
+            if (l <= M / 2) kq[i] = Kc[l];
         }
-    }
-    __syncthreads();
+        __syncthreads();
 
-    fft_passes<M, T, true>(a, lo, hi, tid);
-    __syncthreads();
+        if constexpr (FRESH) { tp = tid; asm volatile("" : "+v"(tp)); }
+        fft_passes<M, T, false>(a, lo, hi, tp);
+        __syncthreads();
 
-    // ---- unpack, scale, store
-    const bool vec_ok = (L & 1) == 0;
-    const float scale = 1.0f / (float)M;
-    for (int n = tid; n < M; n += T) {
-        const int t = 2 * n;
-        if (t < L) {
-            const cplx v = a[conv_pad(n)];
-            if (vec_ok) IoPair<OUT>::store2(y + t, v.x * scale, v.y * scale);
-            else { y[t] = (OUT)(v.x * scale); if (t + 1 < L) y[t + 1] = (OUT)(v.y * scale); }
+        // ---- spectrum of v times spectrum of the kernel, re-packed for the inverse transform (pairs k, M - k)
+        if constexpr (FRESH) { tp = tid; asm volatile("" : "+v"(tp)); }
+        {
+            PairTwiddle<M, T> pw(tp);
+#pragma unroll
+            for (int i = 0; i < NP; ++i) {
+                const int l = tp + T * i;
+                if (l <= M / 2) {
+                    const int kk = pair_bin<M>(l);
+                    const int p1 = conv_pad(spectrum_pos<M>(kk)), p2 = conv_pad(spectrum_pos<M>((M - kk) & (M - 1)));
+                    const cplx w = pw.next(l);
+                    cplx Xk, Xmk, Zk, Zmk;
+                    untangle(a[p1], conj(a[p2]), w, Xk, Xmk);
+                    const cplx K1 = mk(kq[i].x, kq[i].y), K2 = mk(kq[i].z, kq[i].w);
+                    if (kk == 0) {
+                        // bins 0 and M are real and share storage slot 0
+                        const float y0 = Xk.x * K1.x, ym = Xmk.x * K2.x;
+                        a[p1] = mk(0.5f * (y0 + ym), 0.5f * (y0 - ym));
+                    } else {
+                        tangle(cmul(Xk, K1), cmul(Xmk, K2), w, Zk, Zmk);
+                        a[p1] = Zk;
+                        if (p2 != p1) a[p2] = Zmk;
+                    }
+                }
+            }
+        }
+        if (bc + gridDim.x < total) xr.load(X + (bc + gridDim.x) * (long)L, L, tp);     // the next sequence, in flight
+        __syncthreads();
+
+        if constexpr (FRESH) { tp = tid; asm volatile("" : "+v"(tp)); }
+        fft_passes<M, T, true>(a, lo, hi, tp);
+        __syncthreads();
+
+        // ---- unpack, scale, store
+        const bool vec_ok = (L & 1) == 0;
+        const float scale = 1.0f / (float)M;
+#pragma unroll
+        for (int i = 0; i < M / T / 2; ++i) {
+            const int n = tp + T * i, t = 2 * n;
+            if (t < L) {
+                const cplx v = a[conv_pad(n)];
+                if (vec_ok) IoPair<OUT>::store2(y + t, v.x * scale, v.y * scale);
+                else { y[t] = (OUT)(v.x * scale); if (t + 1 < L) y[t + 1] = (OUT)(v.y * scale); }
+            }
         }
     }
 }
@@ -494,18 +566,27 @@ __global__ __launch_bounds__(conv_threads(M)) void longconv_bwd_kernel(const IO*
         for (int i = 0; i < NP; ++i) { accK[i] = mk(0.f, 0.f); accMK[i] = mk(0.f, 0.f); }
     }
 
+    // Inputs are fetched one stage ahead, into registers: dZ of the next sequence while v is transformed, x while the
+    // correlation is transformed back.
+    SeqRegs<M, T, IO> zr, xr;
+    if ((int)blockIdx.y < B) zr.load(dZ + ((long)blockIdx.y * d + c) * L, L, tid);
     for (int b = blockIdx.y; b < B; b += gridDim.y) {
         const long row = ((long)b * d + c) * L;
+        // what depends on the thread but not on the sequence (LDS addresses, bin positions, twiddles) is recomputed per
+        // sequence behind an opaque copy of the thread index: left visible, the compiler keeps all of it in registers
+        // across the transforms and spills
+        // (a fresh copy per stage, or positions shared between stages stay live across the transforms between them)
+        int tp = tid;
+        asm volatile("" : "+v"(tp));
         // ---- spectrum of dZ; correlation with the kernel: DZ conj(K)
-        stage_input<M, T, IO>(dZ + row, nullptr, 0, L, a, tid);
+        stage_input<M, T, IO>(zr, nullptr, 0, L, a, tp);
         __syncthreads();
-        fft_passes<M, T, false>(a, lo, hi, tid);
+        fft_passes<M, T, false>(a, lo, hi, tp);
         __syncthreads();
+        tp = tid;
+        asm volatile("" : "+v"(tp));
+        xr.load(X + row, L, tp);
         {
-            // (the bin positions and twiddles of a thread's pairs do not depend on b; recomputing them per sequence
-            // is cheap, keeping them in registers across the transforms is not: hide the invariance)
-            int tp = tid;
-            asm volatile("" : "+v"(tp));
             PairTwiddle<M, T> pw(tp);
 #pragma unroll
             for (int i = 0; i < NP; ++i) {
@@ -531,12 +612,15 @@ __global__ __launch_bounds__(conv_threads(M)) void longconv_bwd_kernel(const IO*
             }
         }
         __syncthreads();
-        fft_passes<M, T, true>(a, lo, hi, tid);
+        tp = tid;
+        asm volatile("" : "+v"(tp));
+        fft_passes<M, T, true>(a, lo, hi, tp);
         __syncthreads();
         {
             DVT* y = dV + row;
-            for (int n = tid; n < M; n += T) {
-                const int t = 2 * n;
+#pragma unroll
+            for (int i = 0; i < M / T / 2; ++i) {
+                const int n = tp + T * i, t = 2 * n;
                 if (t < L) {
                     const cplx v = a[conv_pad(n)];
                     if (vec_ok) IoPair<DVT>::store2(y + t, v.x * scale, v.y * scale);
@@ -546,15 +630,16 @@ __global__ __launch_bounds__(conv_threads(M)) void longconv_bwd_kernel(const IO*
         }
         __syncthreads();
         // ---- spectrum of v = silu(K_s x) (x itself without a short stage); running sums of DZ conj(V)
-        stage_input<M, T, IO>(X + row, wc, m, L, a, tid);
+        tp = tid;
+        asm volatile("" : "+v"(tp));
+        stage_input<M, T, IO>(xr, wc, m, L, a, tp);
+        if (b + (int)gridDim.y < B) zr.load(dZ + ((long)(b + gridDim.y) * d + c) * L, L, tp);
         __syncthreads();
-        fft_passes<M, T, false>(a, lo, hi, tid);
+        fft_passes<M, T, false>(a, lo, hi, tp);
         __syncthreads();
+        tp = tid;
+        asm volatile("" : "+v"(tp));
         {
-            // (the bin positions and twiddles of a thread's pairs do not depend on b; recomputing them per sequence
-            // is cheap, keeping them in registers across the transforms is not: hide the invariance)
-            int tp = tid;
-            asm volatile("" : "+v"(tp));
             PairTwiddle<M, T> pw(tp);
 #pragma unroll
             for (int i = 0; i < NP; ++i) {
@@ -773,20 +858,39 @@ hipError_t launch_longconv_spectrum(const float* k, void* Kf, int d, int L, hipS
     return hipGetLastError();
 }
 
+// Workgroups of `kernel` that the GPU holds at once (what its LDS and registers allow per compute unit x the units).
+template <typename K>
+static long resident_workgroups(K kernel, int threads)
+{
+    int per_cu = 0, dev = 0, cus = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, threads, 0) != hipSuccess || per_cu < 1) per_cu = 1;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+        cus = 256;
+    (void)hipGetLastError();
+    return (long)cus * per_cu;
+}
+
 template <typename IN, typename OUT>
 static hipError_t conv_dispatch(const IN* X, const float* w, int m, const float4* Kf, OUT* Y, long BD, int d, int L,
                                 hipStream_t st)
 {
     const int M = conv_fft_size(L);
     ProfScope prof(KID_CONV_FWD, st);
-    const dim3 grid((unsigned)BD);
+    // no more workgroups than are resident at once, each with an equal share of the sequences
+#define CHELA_CONV_FWD(M_)                                                                                              \
+    case M_: {                                                                                                          \
+        static const long slots = resident_workgroups(shortlong_conv_kernel<M_, IN, OUT>, conv_threads(M_));            \
+        const long rounds = (BD + slots - 1) / slots;                                                                   \
+        const dim3 grid((unsigned)((BD + rounds - 1) / rounds));                                                        \
+        hipLaunchKernelGGL((shortlong_conv_kernel<M_, IN, OUT>), grid, dim3(conv_threads(M_)), 0, st, X, w, m, Kf, Y, d, \
+                           L, BD);                                                                                      \
+    } break;
     switch (M) {
-        case 256: hipLaunchKernelGGL((shortlong_conv_kernel<256, IN, OUT>), grid, dim3(conv_threads(256)), 0, st, X, w, m, Kf, Y, d, L); break;
-        case 1024: hipLaunchKernelGGL((shortlong_conv_kernel<1024, IN, OUT>), grid, dim3(conv_threads(1024)), 0, st, X, w, m, Kf, Y, d, L); break;
-        case 4096: hipLaunchKernelGGL((shortlong_conv_kernel<4096, IN, OUT>), grid, dim3(conv_threads(4096)), 0, st, X, w, m, Kf, Y, d, L); break;
-        case 16384: hipLaunchKernelGGL((shortlong_conv_kernel<16384, IN, OUT>), grid, dim3(conv_threads(16384)), 0, st, X, w, m, Kf, Y, d, L); break;
+        CHELA_CONV_FWD(256) CHELA_CONV_FWD(1024) CHELA_CONV_FWD(4096) CHELA_CONV_FWD(16384)
         default: return hipErrorInvalidValue;
     }
+#undef CHELA_CONV_FWD
     return hipGetLastError();
 }
 
