@@ -228,6 +228,21 @@ template <> struct IoPair<bf16> {
 };
 
 // Eight consecutive elements at a 16-byte aligned position.
+__device__ __forceinline__ void load8(const float* p, float (&v)[8])
+{
+    const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+}
+__device__ __forceinline__ void load8(const bf16* p, float (&v)[8])
+{
+    const uint4 u = *reinterpret_cast<const uint4*>(p);
+    const unsigned w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        v[2 * e] = __builtin_bit_cast(float, w[e] << 16);
+        v[2 * e + 1] = __builtin_bit_cast(float, w[e] & 0xffff0000u);
+    }
+}
 __device__ __forceinline__ void store8(float* p, const float (&v)[8])
 {
     *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
@@ -747,14 +762,21 @@ __global__ __launch_bounds__(256) void shortconv_bwd_kernel(const IO* __restrict
     for (int tile = blockIdx.z * kShortTilesPerWg; tile < (blockIdx.z + 1) * kShortTilesPerWg && tile * TL < L; ++tile) {
     const int t0 = tile * TL;
     __syncthreads();
-    for (int i = tid; i < TL + 2 * H; i += 256) {
-        const int t = t0 - H + i;
-        sx[i] = (t >= 0 && t < L) ? (float)X[row + t] : 0.f;
+    for (int i8 = tid; i8 < (TL + 2 * H) / 8; i8 += 256) {      // eight steps per thread: one 16-byte load where whole
+        const int t = t0 - H + 8 * i8;
+        float xv[8];
+        if (vec8 && t >= 0 && t + 8 <= L) load8(X + row + t, xv);
+        else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) xv[e] = (t + e >= 0 && t + e < L) ? (float)X[row + t + e] : 0.f;
+        }
+        *reinterpret_cast<float4*>(sx + 8 * i8) = make_float4(xv[0], xv[1], xv[2], xv[3]);
+        *reinterpret_cast<float4*>(sx + 8 * i8 + 4) = make_float4(xv[4], xv[5], xv[6], xv[7]);
     }
     __syncthreads();
     // each thread takes 8 consecutive steps: the 24 inputs they need are read once, as six 16-byte LDS reads
-    for (int ch = tid; ch < (TL + H) / 8; ch += 256) {
-        const int i0 = 8 * ch;
+    {
+        const int i0 = 8 * tid;                         // TL = 8 * 256
         float xs[24];                                   // x[t0 + i0 - 16 .. t0 + i0 + 8)
 #pragma unroll
         for (int r = 0; r < 6; ++r) {
@@ -781,6 +803,16 @@ __global__ __launch_bounds__(256) void shortconv_bwd_kernel(const IO* __restrict
         }
         *reinterpret_cast<float4*>(su + i0) = make_float4(du8[0], du8[1], du8[2], du8[3]);
         *reinterpret_cast<float4*>(su + i0 + 4) = make_float4(du8[4], du8[5], du8[6], du8[7]);
+    }
+    if (tid < H) {
+        // the H steps of look-ahead beyond the tile, one per thread (as two more 8-step pieces they would double the
+        // first wave's share of this phase)
+        const int i = TL + tid, t = t0 + i;
+        float u = 0.f;
+#pragma unroll
+        for (int j = 0; j < TAPS; ++j) u = fmaf(wreg[j], sx[H + i - j], u);
+        const float sg = __builtin_amdgcn_rcpf(1.f + __expf(-u));
+        su[i] = t < L ? dV[row + t] * sg * (1.f + u * (1.f - sg)) : 0.f;
     }
     __syncthreads();
     {
