@@ -1049,3 +1049,124 @@ def test_seeded_shape_sweep_over_the_entry_points(shape):
     for name, a, r in zip(("dQ(nc)", "dK(nc)", "dV(nc)"), gn, oracle_layer.noncausal_bwd(Qn, Kn, Vn, dOn)):
         _check(name, a, r, "bf16")
     _check("Y(nc)", Yn, oracle_layer.gate_norm_fwd(rOn, Gn, EPS), "bf16")
+
+
+# ------------------------------------------------------------------------------------------ the other benchmarked launches
+# Every further launch configuration that bench.py times (its --mode and --workload combinations beyond the five
+# configurations above), at full size, on sampled (b,h) pairs, channels or rows.
+def test_state_carry_lm_full_size_sampled():
+    w = WORKLOADS["lm_bf16"]
+    x = make_inputs(w, with_dO=True)
+    S_in = _state((w.B, w.H, w.dk, w.dv), 21, 2.0)
+    dS_out = _state((w.B, w.H, w.dk, w.dv), 22, 0.5)
+    d = _dev(x)
+    O, S_out = binding.chela_linattn_fwd_state(d["Q"], d["K"], d["V"], S_in=S_in.cuda())
+    dQ, dK, dV, dS_in = binding.chela_linattn_bwd_state(d["Q"], d["K"], d["V"], d["dO"], S_in=S_in.cuda(),
+                                                        dS_out=dS_out.cuda())
+    torch.cuda.synchronize()
+    for b, h in ((0, 0), (2, 5), (3, 11)):
+        print("\nstate, full size: b %d h %d" % (b, h), flush=True)
+        cut = lambda t: to_f64_numpy(t[b:b + 1, h:h + 1])
+        Qn, Kn, Vn, Gn = (cut(x[n]) for n in ("Q", "K", "V", "dO"))
+        rO, rS = oracle.fwd_state(Qn, Kn, Vn, S_in=cut(S_in))
+        rdQ, rdK, rdV, rdS = oracle.bwd_state(Qn, Kn, Vn, Gn, S_in=cut(S_in), dS_out=cut(dS_out))
+        for name, got, ref in (("O", O, rO), ("dQ", dQ, rdQ), ("dK", dK, rdK), ("dV", dV, rdV)):
+            _check(name, got[b:b + 1, h:h + 1], ref, "bf16")
+        for name, got, ref in (("S_out", S_out, rS), ("dS_in", dS_in, rdS)):
+            err = oracle.rel_l2(cut(got), ref)
+            print("   rel-L2 %-5s = %.3e" % (name, err), flush=True)
+            assert err <= 1e-5, (name, err)
+
+
+def test_decode_step_at_the_benchmarked_batch():
+    B, H, dk, dv = 256, 12, 64, 64
+    g = torch.Generator(device="cpu")
+    g.manual_seed(19)
+    q = (torch.randn(B, H, dk, generator=g) / 8).to(torch.bfloat16)
+    k = (torch.randn(B, H, dk, generator=g) / 8).to(torch.bfloat16)
+    v = torch.randn(B, H, dv, generator=g).to(torch.bfloat16)
+    S0 = _state((B, H, dk, dv), 4)
+    S = S0.clone().cuda()
+    o = binding.chela_linattn_step(q.cuda(), k.cuda(), v.cuda(), S)
+    torch.cuda.synchronize()
+    ro, rS = oracle.step(to_f64_numpy(q), to_f64_numpy(k), to_f64_numpy(v), S0.double().numpy())
+    _check("o", o, ro, "bf16")
+    assert oracle.rel_l2(to_f64_numpy(S), rS) <= 1e-5
+
+
+@pytest.mark.parametrize("name", ["lm_bf16", "long_bf16"])
+def test_noncausal_other_workloads_full_size_sampled(name):
+    w = WORKLOADS[name]
+    _run_nc_case(w, heads=_sample_heads(w, k=3))
+
+
+def test_conv_lra_width_sampled_channels():
+    # B32 d512 L4096: forward and gradient as the benchmark launches them (three workgroups per channel going back)
+    B, d, L, m = 32, 512, 4096, 9
+    x = make_conv_inputs(B, d, L, m, 4, "bf16")
+    g = torch.Generator(device="cpu")
+    g.manual_seed(3004)
+    dZ = torch.randn(B, d, L, generator=g, dtype=torch.float32).bfloat16()
+    dev = _dev(x)
+    spec = binding.chela_longconv_spectrum(dev["k_long"])
+    Z = binding.chela_shortlong_conv_fwd(dev["X"], dev["w_short"], spec)
+    dX, dw, dk = binding.chela_shortlong_conv_bwd(dev["X"], dev["w_short"], spec, dZ.cuda())
+    torch.cuda.synchronize()
+    ch = [0, 255, 511]
+    Xn, wn, kn, dZn = (to_f64_numpy(t) for t in (x["X"][:, ch], x["w_short"][ch], x["k_long"][ch], dZ[:, ch]))
+    _check("Z", Z[:, ch], oracle_conv.short_long_conv(Xn, wn, kn), "bf16")
+    rX, rw, rk = oracle_conv.short_long_conv_bwd(Xn, wn, kn, dZn)
+    _check("dX", dX[:, ch], rX, "bf16")
+    _check("dk", dk[ch], rk, "bf16")
+    _check("dw", dw[ch], rw, "bf16")
+
+
+@pytest.mark.parametrize("name", ["lra_bf16", "mixed_bf16"])
+def test_fwd_gated_other_workloads_full_size_sampled(name):
+    w = WORKLOADS[name]
+    x, gx = make_inputs(w, with_dO=False), make_gate_inputs(w)
+    d, gd = _dev(x), _dev(gx)
+    Y, _, _ = binding.chela_linattn_fwd_gated(d["Q"], d["K"], d["V"], gd["G"], EPS)
+    torch.cuda.synchronize()
+    for b, hd in ((0, 0), (w.B // 2, w.H // 2), (w.B - 1, w.H - 1)):
+        print("\ngated %s: b %d h %d" % (name, b, hd), flush=True)
+        Qn, Kn, Vn, Gn = (to_f64_numpy(t[b:b + 1, hd:hd + 1]) for t in (x["Q"], x["K"], x["V"], gx["G"]))
+        _check("Y", Y[b:b + 1, hd:hd + 1], oracle_layer.gated_fwd(Qn, Kn, Vn, Gn, EPS)[1], "bf16")
+
+
+def test_noncausal_fwd_gated_long_full_size_sampled():
+    w = WORKLOADS["long_bf16"]
+    x, gx = make_inputs(w, with_dO=False), make_gate_inputs(w)
+    d, gd = _dev(x), _dev(gx)
+    Y, _ = binding.chela_linattn_noncausal_fwd_gated(d["Q"], d["K"], d["V"], gd["G"], EPS)
+    torch.cuda.synchronize()
+    for b, hd in ((0, 0), (w.B - 1, w.H - 1)):
+        Qn, Kn, Vn, Gn = (to_f64_numpy(t[b:b + 1, hd:hd + 1]) for t in (x["Q"], x["K"], x["V"], gx["G"]))
+        rY = oracle_layer.gate_norm_fwd(oracle_layer.noncausal_fwd(Qn, Kn, Vn), Gn, EPS)
+        _check("Y", Y[b:b + 1, hd:hd + 1], rY, "bf16")
+
+
+def test_layer_core_training_chain_lm_full_size_sampled():
+    # the three calls of bench.py --mode train_layer on the full input; what is local to a (b,h) pair is checked on two
+    # of them (d_affine, a sum over the batch, has its full-size check with the Z training pair above)
+    w = WORKLOADS["lm_bf16"]
+    x, gx = make_z_inputs(w, with_dO=False), make_gate_inputs(w)
+    d, gd = _dev(x), _dev(gx)
+    Y, O, saved = binding.chela_linattn_zfwd_gated(d["Z"], d["affine"], d["V"], gd["G"], EPS, want_O=True, want_saved=True)
+    dO, dG = binding.chela_gate_norm_bwd(O, gd["G"], gd["dY"], EPS)
+    dZ, dA, dV = binding.chela_linattn_zbwd_saved(d["Z"], d["affine"], d["V"], dO, saved)
+    torch.cuda.synchronize()
+    for b, hd in ((0, 0), (3, 11)):
+        print("\nlayer chain, full size: b %d h %d" % (b, hd), flush=True)
+        cut = lambda t: to_f64_numpy(t[b:b + 1, hd:hd + 1])
+        Zn, Vn, Gn, dYn = cut(x["Z"]), cut(x["V"]), cut(gx["G"]), cut(gx["dY"])
+        An = to_f64_numpy(x["affine"][:, hd:hd + 1])
+        Qn, Kn = oracle_layer.qk_from_z(Zn, An)
+        rO, rY = oracle_layer.gated_fwd(Qn, Kn, Vn, Gn, EPS)
+        _check("Y", Y[b:b + 1, hd:hd + 1], rY, "bf16")
+        rdO, rdG = oracle_layer.gate_norm_bwd(rO, Gn, dYn, EPS)
+        _check("dG", dG[b:b + 1, hd:hd + 1], rdG, "bf16")
+        _check("dO", dO[b:b + 1, hd:hd + 1], rdO, "bf16")
+        rZ, _, rV = oracle_layer.zqk_bwd(Zn, An, Vn, rdO)
+        _check("dZ", dZ[b:b + 1, hd:hd + 1], rZ, "bf16")
+        _check("dV", dV[b:b + 1, hd:hd + 1], rV, "bf16")
