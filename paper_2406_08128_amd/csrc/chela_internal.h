@@ -111,7 +111,9 @@ inline int conv_bwd_groups(int B, int d, int L)
 {
     const int M = conv_fft_size(L);
     if (M == 0 || B <= 1 || d <= 0) return 1;
-    const long slots = 256L * (M >= 16384 ? 1 : M >= 4096 ? 3 : 4);      // resident workgroups of that kernel
+    // resident workgroups of that kernel: 256 compute units x what its registers allow per unit (workgroups of 1, 1, 4
+    // and 16 waves at M = 256, 1024, 4096, 16384)
+    const long slots = 256L * (M >= 16384 ? 1 : M >= 4096 ? 3 : M >= 1024 ? 12 : 20);
     long g = (2 * slots + d - 1) / d;
     if (g > B) g = B;
     if (g > 64) g = 64;

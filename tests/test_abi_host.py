@@ -211,7 +211,7 @@ def test_conv_bwd_argument_errors(L):
     assert wsb(2, 4, 100, 0, 0) == 2 * 4 * 129 * 16
     assert wsb(2, 4, 100, 1, 0) == 2 * 4 * 129 * 16 + 2 * 4 * (100 * 4 + 64)
     # enough channels to fill the GPU: one workgroup per channel again
-    assert wsb(8, 4096, 100, 0, 0) == 0
+    assert wsb(8, 16384, 100, 0, 0) == 0
     # at the largest transform size the running sums live in the workspace whatever G is
     assert wsb(1, 4, 16000, 0, 0) == 4 * 8193 * 16
     assert wsb(2, 4, 16000, 0, 0) == 2 * 4 * 8193 * 16

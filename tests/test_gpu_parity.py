@@ -719,11 +719,11 @@ def test_long_conv_alone_bwd(L):
     _run_conv_bwd_case(2, 3, L, 3, "f32", seed=L + 12, short=False)
 
 
-@pytest.mark.parametrize("shape", [(7, 700, 100, 5, "f32"), (5, 512, 3000, 9, "bf16"), (4, 200, 9000, 9, "bf16"),
-                                   (3, 2100, 100, 5, "f32"), (4, 768, 16384, 9, "bf16")])
+@pytest.mark.parametrize("shape", [(40, 700, 100, 5, "f32"), (9, 1100, 1000, 5, "bf16"), (5, 512, 3000, 9, "bf16"),
+                                   (4, 200, 9000, 9, "bf16"), (3, 10300, 100, 5, "f32"), (4, 768, 16384, 9, "bf16")])
 def test_conv_bwd_sequences_dealt_over_workgroups(shape):
-    # widths at which the long-stage gradient kernel gives each channel three workgroups that take every third
-    # sequence (the first three shapes, one per transform size above 256 and one at 256), a width served by one
+    # widths and batch sizes at which the long-stage gradient kernel gives each channel several workgroups, each with
+    # more than one sequence to take (15, 6, 3 and 3 workgroups at the four transform sizes), a width served by one
     # workgroup per channel at a batch size above one and, last, the LM-shaped width as the benchmark launches it (one
     # workgroup per channel, running sums kept in memory); channels are independent, so the oracle takes a sample
     B, d, L, m, dtype = shape
