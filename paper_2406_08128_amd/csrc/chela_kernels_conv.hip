@@ -1026,10 +1026,18 @@ static hipError_t conv_bwd_impl(const IO* X, const float* w_short, int m, const 
     {
         ProfScope prof(KID_CONV_SHORT_BWD, st);
         const dim3 grid(d, B, tiles);
-        if (m <= 4) hipLaunchKernelGGL((shortconv_bwd_kernel<IO, 4>), grid, dim3(256), 0, st, X, w_short, m, ws_dV, dX, ws_part, d, L);
-        else if (m <= 8) hipLaunchKernelGGL((shortconv_bwd_kernel<IO, 8>), grid, dim3(256), 0, st, X, w_short, m, ws_dV, dX, ws_part, d, L);
-        else if (m <= 12) hipLaunchKernelGGL((shortconv_bwd_kernel<IO, 12>), grid, dim3(256), 0, st, X, w_short, m, ws_dV, dX, ws_part, d, L);
-        else hipLaunchKernelGGL((shortconv_bwd_kernel<IO, 16>), grid, dim3(256), 0, st, X, w_short, m, ws_dV, dX, ws_part, d, L);
+        // one instantiation per tap count: the tap loops are a third of this kernel's instructions
+#define CHELA_SHORT_BWD(T_)                                                                                             \
+    case T_:                                                                                                            \
+        hipLaunchKernelGGL((shortconv_bwd_kernel<IO, T_>), grid, dim3(256), 0, st, X, w_short, m, ws_dV, dX, ws_part, d, L); \
+        break;
+        switch (m) {
+            CHELA_SHORT_BWD(1) CHELA_SHORT_BWD(2) CHELA_SHORT_BWD(3) CHELA_SHORT_BWD(4) CHELA_SHORT_BWD(5) CHELA_SHORT_BWD(6)
+            CHELA_SHORT_BWD(7) CHELA_SHORT_BWD(8) CHELA_SHORT_BWD(9) CHELA_SHORT_BWD(10) CHELA_SHORT_BWD(11)
+            CHELA_SHORT_BWD(12) CHELA_SHORT_BWD(13) CHELA_SHORT_BWD(14) CHELA_SHORT_BWD(15) CHELA_SHORT_BWD(16)
+            default: return hipErrorInvalidValue;
+        }
+#undef CHELA_SHORT_BWD
         if ((e = hipGetLastError()) != hipSuccess) return e;
         hipLaunchKernelGGL(shortconv_dw_kernel, dim3(d), dim3(64), 0, st, ws_part, dw, m, B * tiles);
         if ((e = hipGetLastError()) != hipSuccess) return e;
