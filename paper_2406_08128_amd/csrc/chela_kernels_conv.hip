@@ -66,7 +66,6 @@ __device__ __forceinline__ void dft16(cplx (&v)[16])
 }
 
 __host__ __device__ constexpr int conv_threads(int M) { return M / 16 < 64 ? 64 : M / 16; }
-// the kernel-gradient kernel keeps two spectra in registers besides the transform in flight: half as many threads
 __host__ __device__ constexpr bool conv_lead4(int M) { return M == 1024 || M == 16384; }
 __host__ __device__ constexpr int conv_pad(int i) { return i + (i >> 4); }
 
@@ -542,11 +541,10 @@ __global__ __launch_bounds__(conv_threads(M)) void shortlong_conv_kernel(const I
 // The two long-stage gradients in one kernel: they share the spectrum of dZ.  One workgroup per channel walks the
 // batch; per sequence it transforms dZ once, keeps the untangled bins of its own bin pairs in registers, multiplies
 // by the CONJUGATE kernel spectrum (correlation instead of convolution: dV[t] = sum_{s >= t} k[s - t] dZ[s]) and
-// transforms back (out as DVT: fp32 scratch for the
-// short-stage kernel, or dX itself when there is no short stage), then transforms v = silu(K_s x) (recomputed from x)
-// and adds DZ conj(V) to the running sums of its bin pairs, also in registers; after the last sequence the sums are
-// transformed back once (dk).  Three transforms per sequence instead of the four of the two separate kernels, at the
-// forward kernel's full thread count.
+// transforms back (out as DVT: fp32 scratch for the short-stage kernel, or dX itself when there is no short stage),
+// then transforms v = silu(K_s x) (recomputed from x) and adds DZ conj(V) to the running sums of its bin pairs (in
+// registers, at the largest size in memory); after the last sequence the sums are transformed back once (dk).  Three
+// transforms per sequence, where a correlation kernel and a kernel-gradient kernel of their own would need four.
 // SPLIT: grid.y workgroups share a channel, each takes every grid.y-th sequence and leaves its sums in its own slice
 // of the scratch array ([grid.y][d][M/2 + 1] pairs); longconv_dk_finish_kernel adds the slices up and transforms back.
 // Used when there are too few channels to fill the GPU.
