@@ -45,7 +45,10 @@ static long choose_segments(long BH, long n_chunks, long slots, double g_min, do
     if (BH >= 256 || n_chunks <= 4) return 1;
     long best = 1;
     double best_cost = 1e300;
-    const long max_seg = n_chunks / 4 > 0 ? n_chunks / 4 : 1;     // at least 4 chunks per segment
+    // at least 4 chunks per segment -- unless the whole problem fits the GPU at once even with one workgroup per chunk:
+    // then the time is the launches plus the serial chunk steps of a segment, and shorter segments only help
+    const long min_cps = BH * n_chunks <= slots ? 1 : 4;
+    const long max_seg = n_chunks / min_cps > 0 ? n_chunks / min_cps : 1;
     for (long n = 1; n <= max_seg && n <= 4096; ++n) {
         const long cps = (n_chunks + n - 1) / n;
         const long real_n = (n_chunks + cps - 1) / cps;

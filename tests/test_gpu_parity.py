@@ -214,7 +214,8 @@ def test_caller_workspace_and_side_stream():
     d = _dev(make_inputs(w))
     ref = binding.chela_linattn_fwd(d["Q"], d["K"], d["V"])
     gref = binding.chela_linattn_bwd(d["Q"], d["K"], d["V"], d["dO"])
-    need = binding.chela_linattn_workspace_bytes(w.B, w.H, w.N, w.dk, w.dv, 64, True, binding.DTYPE_BF16)
+    need = max(binding.chela_linattn_workspace_bytes(w.B, w.H, w.N, w.dk, w.dv, 64, bwd, binding.DTYPE_BF16)
+               for bwd in (False, True))          # one buffer for both calls: each has its own split
     assert need > 0
     buf = torch.empty(need, dtype=torch.uint8, device="cuda")
     torch.cuda.synchronize()
@@ -935,7 +936,8 @@ def test_training_step_replays_from_a_hip_graph():
     O_ref = binding.chela_linattn_fwd(d["Q"], d["K"], d["V"])
     g_ref = binding.chela_linattn_bwd(d["Q"], d["K"], d["V"], d["dO"])
     Y_ref, _, _ = binding.chela_linattn_fwd_gated(d["Q"], d["K"], d["V"], gx["G"], EPS)
-    need = binding.chela_linattn_workspace_bytes(w.B, w.H, w.N, w.dk, w.dv, 64, True, binding.DTYPE_BF16)
+    need = max(binding.chela_linattn_workspace_bytes(w.B, w.H, w.N, w.dk, w.dv, 64, bwd, binding.DTYPE_BF16)
+               for bwd in (False, True))          # one buffer for both calls: each has its own split
     buf = torch.empty(need, dtype=torch.uint8, device="cuda")
     O, Y = torch.empty_like(O_ref), torch.empty_like(O_ref)
     dQ, dK, dV = (torch.empty_like(t) for t in g_ref)
@@ -1038,7 +1040,9 @@ def test_seeded_shape_sweep_over_the_entry_points(shape):
     _check("O", O, rO, "bf16")
     for name, a, r in zip(("dQ", "dK", "dV"), g1, rg):
         _check(name, a, r, "bf16")
-    assert torch.equal(O2, O) and torch.equal(Og, O)
+    assert torch.equal(Og, O)
+    # (the training pair's forward cuts the sequence where its backward will: another split, other roundings)
+    _check("O(save)", O2, rO, "bf16")
     for name, a, r in zip(("dQ", "dK", "dV"), g2, rg):
         _check(name + "(saved)", a, r, "bf16")
     assert torch.equal(O3.transpose(1, 2), O)
