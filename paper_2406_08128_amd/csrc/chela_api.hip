@@ -17,15 +17,18 @@ static int env_int(const char* name, int dflt)
     return std::atoi(s);
 }
 
-// Workgroups of the sweep kernel that fit the GPU at once (256 compute units x resident workgroups per unit, the
-// latter set by the kernel's LDS and register footprint).
+// Workgroups of the sweep kernel that the plan counts on at once (256 compute units x resident workgroups per unit,
+// the latter set by the kernel's LDS and register footprint).
 static long sweep_slots(int dk, int dv, int chunk, int dtype, bool is_bwd)
 {
     if (dtype != CHELA_DTYPE_BF16) return 512;
     const bool narrow = (dk == 64 && dv == 64), wide = (dk == 128 && dv == 128);
     int per_cu;
     if (is_bwd) per_cu = (chunk == 64 && !wide) ? 2 : 1;      // (one width of 128: the two states share an LDS tile)
-    else if (chunk == 64) per_cu = narrow ? 4 : (wide ? 1 : 2);
+    // (the 64-wide forward sweep holds four per unit, but is planned for two: filling the other two with shorter
+    // segments buys nothing a state more per segment does not cost -- 10 segments instead of 20 at the LM shape took
+    // 2.5 % off the step, 5 % at half that length)
+    else if (chunk == 64) per_cu = wide ? 1 : 2;
     else per_cu = narrow ? 2 : 1;
     return 256L * per_cu;
 }
