@@ -735,30 +735,31 @@ __global__ __launch_bounds__(conv_threads(M)) void longconv_bwd_kernel(const IO*
 
 // Gradient through the activation and the short kernel.  dV is the gradient with respect to v = silu(u), u = K_s x:
 //   dU = dV silu'(u),  dX[t] = sum_j w[j] dU[t+j],  dw[c][j] = sum_b sum_t dU[b,c,t] x[b,c,t-j].
-// One workgroup per (channel, batch entry, tile of TL steps); x is staged with MT
-// steps of history and dU with MT steps of look-ahead.  Each workgroup leaves its share of the tap sums in `part`
-// ([d][B * tiles][MT]); shortconv_dw_kernel adds the shares of a channel in a fixed order.
+// The (batch entry, tile of TL steps) pairs of a channel are dealt out to workgroups in runs of kShortTilesPerWg
+// (a run may cross from one sequence into the next); x is staged with MT steps of history and dU with MT steps of
+// look-ahead.  Each workgroup leaves its share of the tap sums in `part` ([d][n_share][MT]); shortconv_dw_kernel
+// adds the shares of a channel in a fixed order.
 constexpr int kShortTile = 2048, kShortMaxTaps = 16, kShortTilesPerWg = 4;
 
 // TAPS: compile-time bound on the number of taps (m <= TAPS <= 16): the tap loops are as long as the kernel needs.
 template <typename IO, int TAPS>
 __global__ __launch_bounds__(256) void shortconv_bwd_kernel(const IO* __restrict__ X, const float* __restrict__ w_short,
                                                            int m, const float* __restrict__ dV, IO* __restrict__ dX,
-                                                           float* __restrict__ part, int d, int L)
+                                                           float* __restrict__ part, int B, int d, int L, int n_share)
 {
     constexpr int TL = kShortTile, MT = kShortMaxTaps, H = MT;       // H: halo on either side
     __shared__ __attribute__((aligned(16))) float sx[TL + 2 * H];      // x[t0 - H .. t0 + TL + H)
     __shared__ __attribute__((aligned(16))) float su[TL + H + 8];      // dU[t0 .. t0 + TL + H) (+ slack for 16-byte reads)
     __shared__ float red[MT][4];
-    const int tid = threadIdx.x, c = blockIdx.x, b = blockIdx.y;
-    const int n_share = gridDim.y * gridDim.z, share = b * gridDim.z + blockIdx.z;
+    const int tid = threadIdx.x, c = blockIdx.x % d, share = blockIdx.x / d;      // channels fastest
+    const int tiles_per_row = (L + TL - 1) / TL, n_items = B * tiles_per_row;
     float wreg[TAPS], acc[TAPS];
 #pragma unroll
     for (int j = 0; j < TAPS; ++j) { wreg[j] = j < m ? w_short[(long)c * m + j] : 0.f; acc[j] = 0.f; }
-    const long row = ((long)b * d + c) * L;
     const bool vec8 = (L & 7) == 0;       // every row starts 16-byte aligned
-    for (int tile = blockIdx.z * kShortTilesPerWg; tile < (blockIdx.z + 1) * kShortTilesPerWg && tile * TL < L; ++tile) {
-    const int t0 = tile * TL;
+    for (int item = share * kShortTilesPerWg; item < (share + 1) * kShortTilesPerWg && item < n_items; ++item) {
+    const int b = item / tiles_per_row, t0 = (item - b * tiles_per_row) * TL;
+    const long row = ((long)b * d + c) * L;
     __syncthreads();
     for (int i8 = tid; i8 < (TL + 2 * H) / 8; i8 += 256) {      // eight steps per thread: one 16-byte load where whole
         const int t = t0 - H + 8 * i8;
@@ -1018,16 +1019,19 @@ static hipError_t conv_bwd_impl(const IO* X, const float* w_short, int m, const 
     if (w_short == nullptr)   // no short stage: v = x and dX is the correlation of dZ with the long kernel itself
         return conv_longbwd_dispatch<IO, IO>(X, nullptr, 0, Kf, dZ, dX, dk, acc_ws, B, d, L, st);
     float* ws_dV = ws;
-    const int tiles = ((L + kShortTile - 1) / kShortTile + kShortTilesPerWg - 1) / kShortTilesPerWg;   // tile groups
-    float* ws_part = ws + (size_t)BD * L;                                   // [d][B * tiles][16]
+    const long n_items = (long)B * ((L + kShortTile - 1) / kShortTile);                     // (batch entry, tile) pairs
+    const int n_share = (int)((n_items + kShortTilesPerWg - 1) / kShortTilesPerWg);         // workgroups per channel
+    if ((long)d * n_share > 0x7fffffffL) return hipErrorInvalidValue;
+    float* ws_part = ws + (size_t)BD * L;                                   // [d][n_share][16] (room for [d][B * tiles][16])
     if ((e = conv_longbwd_dispatch<IO, float>(X, w_short, m, Kf, dZ, ws_dV, dk, acc_ws, B, d, L, st)) != hipSuccess) return e;
     {
         ProfScope prof(KID_CONV_SHORT_BWD, st);
-        const dim3 grid(d, B, tiles);
+        const dim3 grid((unsigned)((long)d * n_share));
         // one instantiation per tap count: the tap loops are a third of this kernel's instructions
 #define CHELA_SHORT_BWD(T_)                                                                                             \
     case T_:                                                                                                            \
-        hipLaunchKernelGGL((shortconv_bwd_kernel<IO, T_>), grid, dim3(256), 0, st, X, w_short, m, ws_dV, dX, ws_part, d, L); \
+        hipLaunchKernelGGL((shortconv_bwd_kernel<IO, T_>), grid, dim3(256), 0, st, X, w_short, m, ws_dV, dX, ws_part, B, d,  \
+                           L, n_share);                                                                                 \
         break;
         switch (m) {
             CHELA_SHORT_BWD(1) CHELA_SHORT_BWD(2) CHELA_SHORT_BWD(3) CHELA_SHORT_BWD(4) CHELA_SHORT_BWD(5) CHELA_SHORT_BWD(6)
@@ -1037,7 +1041,7 @@ static hipError_t conv_bwd_impl(const IO* X, const float* w_short, int m, const 
         }
 #undef CHELA_SHORT_BWD
         if ((e = hipGetLastError()) != hipSuccess) return e;
-        hipLaunchKernelGGL(shortconv_dw_kernel, dim3(d), dim3(64), 0, st, ws_part, dw, m, B * tiles);
+        hipLaunchKernelGGL(shortconv_dw_kernel, dim3(d), dim3(64), 0, st, ws_part, dw, m, n_share);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     return hipSuccess;
