@@ -265,6 +265,12 @@ size_t chela_linattn_workspace_bytes(int B, int H, int N, int dk, int dv, int ch
  * valid until every call that used it has finished. */
 int chela_set_workspace(void *dev_ptr, size_t bytes);
 
+/* Environment variables read by the library (tuning aids for measurements; results stay within the rounding of any
+ * other split, defaults are what the planner picks):
+ *   CHELA_SEG_TOKENS=n   force segments of n tokens (rounded up to whole chunks) in the causal calls
+ *   CHELA_NC_SEGS=n      force n segments per (b,h) in the non-causal pre-pass
+ *   CHELA_PREPASS_REV=0  walk the forward pre-pass front to back instead of back to front */
+
 /* Human-readable name of a status code (static storage, never NULL). */
 const char *chela_status_string(int status);
 
