@@ -249,6 +249,31 @@ def test_workspace_bytes(L):
         assert w(4, 12, n, 64, 64, 64, 1, 0) <= 2 * 64 * state
 
 
+def test_planner_stays_within_its_bounds_over_random_shapes(L):
+    # whatever the shape, the split is between one segment and one segment per chunk, small problems included, and
+    # the scratch stays a whole number of states per (b,h) pair
+    import random
+    rnd = random.Random(20240611)
+    w = L.chela_linattn_workspace_bytes
+    for _ in range(3000):
+        B, H = rnd.randint(1, 40), rnd.randint(1, 40)
+        N = rnd.choice([1, 63, 64, 65, 200, 1000, 1024, 4096, 5000, 16384, 100000, 1 << 20])
+        dk, dv = rnd.choice([64, 128]), rnd.choice([64, 128])
+        for dtype, chunks in ((0, (64, 128)), (1, (16, 32, 64))):
+            for bwd in (0, 1):
+                chunk = rnd.choice(chunks)
+                ws = w(B, H, N, dk, dv, chunk, bwd, dtype)
+                arrays = 2 if (bwd and dtype == 0) else 1
+                per_state = B * H * dk * dv * 4 * arrays
+                assert ws % per_state == 0, (B, H, N, dk, dv, chunk, bwd, dtype, ws)
+                n_seg = max(1, ws // per_state)                    # (no scratch at all: a single segment)
+                smallest_chunk = 32 if dtype == 1 else 64          # what the kernels tile with at the least
+                assert 1 <= n_seg <= (N + smallest_chunk - 1) // smallest_chunk
+                assert n_seg <= 32768                              # segments ride on a secondary grid dimension
+                if B * H >= 256:
+                    assert n_seg == 1
+
+
 def test_set_workspace_alignment(L):
     assert L.chela_set_workspace(ctypes.c_void_p(0x1001), 1024) == -5
     assert L.chela_set_workspace(None, 0) == 0
