@@ -234,6 +234,32 @@ __device__ __forceinline__ void load_tile_f32(float* lds, const float* base, int
     }
 }
 
+// The same in two steps, so that the loads of the next chunk can be in flight while the current one is worked on:
+// fetch_tile_f32 brings a thread's share of the tile into registers, stash_tile_f32 puts it into LDS.
+template <int C, int D>
+struct TileRegsF32 {
+    static constexpr int V4 = D / 4, NV = C * V4 / 256;
+    float4 v[NV];
+    __device__ __forceinline__ void fetch(const float* base, int c0, int p_end, int N, bool rev, int tid)
+    {
+#pragma unroll
+        for (int n = 0; n < NV; ++n) {
+            const int x = tid + 256 * n, row = x / V4, c4 = x % V4, p = c0 + row;
+            v[n] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (p < p_end) v[n] = *reinterpret_cast<const float4*>(base + (size_t)phys_row(p, N, rev) * D + c4 * 4);
+        }
+    }
+    __device__ __forceinline__ void stash(float* lds, int tid) const
+    {
+#pragma unroll
+        for (int n = 0; n < NV; ++n) {
+            const int x = tid + 256 * n, row = x / V4, c4 = x % V4;
+            float* d = lds + row * (D + 1) + c4 * 4;
+            d[0] = v[n].x; d[1] = v[n].y; d[2] = v[n].z; d[3] = v[n].w;
+        }
+    }
+};
+
 // ------------------------------------------------------------------------------------------------ segment totals
 // out[bh][seg][i*DV + j] = sum over the segment's tokens of K[t][i] * V[t][j].  The last segment's total is never
 // used by an exclusive prefix, so its workgroups leave at once.  Wave w owns output tiles w, w+4, ...
@@ -284,7 +310,7 @@ __global__ __launch_bounds__(256) void f32_seg_state_kernel(const float* __restr
 
 // ------------------------------------------------------------------------------------------------ main sweep
 // One workgroup (4 waves) per (segment, bh).  Wave w owns output rows [32*tb, +32) with tb = w % WT and NJ column
-// tiles, and the state tiles w, w+4, ...  LDS: Q, K [C][DK+1]; V [C][DV+1]; S [DK][DV+1]; P [C][C+1].
+// tiles, and the state tiles w, w+4, ...  LDS: Q, K [C][DK+1]; V [C][DV+1]; S [DK][DV+1]; P [C][C+1] in K's place.
 template <int C, int DK, int DV>
 __global__ __launch_bounds__(256) void f32_sweep_kernel(const float* __restrict__ Q, const float* __restrict__ K,
                                                        const float* __restrict__ V, float* __restrict__ O,
@@ -296,11 +322,15 @@ __global__ __launch_bounds__(256) void f32_sweep_kernel(const float* __restrict_
     constexpr int WT = TB < 4 ? TB : 4, WJ = 4 / WT, NJ = JB / WJ;
     constexpr int NS = IB * JB / 4;
     static_assert(JB % WJ == 0, "unsupported tile shape");
+    // The score tile P takes over K's place once K has done its two jobs (scores, state update): five tiles would be
+    // 83 KB at the 64-wide shape and leave a compute unit to a single workgroup, four leave room for two.
+    constexpr int KP = C * LDK > C * LDP ? C * LDK : C * LDP;
     __shared__ float sQ[C * LDK];
-    __shared__ float sK[C * LDK];
+    __shared__ float sKP[KP];
     __shared__ float sV[C * LDV];
     __shared__ float sS[DK * LDV];
-    __shared__ float sP[C * LDP];
+    float* sK = sKP;
+    float* sP = sKP;
     const int seg = blockIdx.y;
     const long bh = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63;
@@ -326,11 +356,16 @@ __global__ __launch_bounds__(256) void f32_sweep_kernel(const float* __restrict_
                 accS[n][4 * a + b] = s0 ? s0[(ib * 32 + 8 * a + 4 * h + b) * DV + jb * 32 + r] : 0.f;
     }
 
+    TileRegsF32<C, DK> rq, rk;
+    TileRegsF32<C, DV> rv;
+    rq.fetch(Qb, p0, p1, N, rev, tid);
+    rk.fetch(Kb, p0, p1, N, rev, tid);
+    rv.fetch(Vb, p0, p1, N, rev, tid);
     for (int c0 = p0; c0 < p1; c0 += C) {
         __syncthreads();   // previous chunk fully consumed
-        load_tile_f32<C, DK>(sQ, Qb, c0, p1, N, rev, tid);
-        load_tile_f32<C, DK>(sK, Kb, c0, p1, N, rev, tid);
-        load_tile_f32<C, DV>(sV, Vb, c0, p1, N, rev, tid);
+        rq.stash(sQ, tid);
+        rk.stash(sK, tid);
+        rv.stash(sV, tid);
         // publish the state before this chunk, [i][j]
 #pragma unroll
         for (int n = 0; n < NS; ++n) {
@@ -341,18 +376,37 @@ __global__ __launch_bounds__(256) void f32_sweep_kernel(const float* __restrict_
                 for (int b = 0; b < 4; ++b) sS[(ib * 32 + 8 * a + 4 * h + b) * LDV + jb * 32 + r] = accS[n][4 * a + b];
         }
         __syncthreads();
-        // masked scores of this wave's row block: P[t][s] = q_t . k_s for s <= t, written to LDS (rows of tb only)
+        if (c0 + C < p1) {     // the next chunk, in flight during the arithmetic
+            rq.fetch(Qb, c0 + C, p1, N, rev, tid);
+            rk.fetch(Kb, c0 + C, p1, N, rev, tid);
+            rv.fetch(Vb, c0 + C, p1, N, rev, tid);
+        }
+        // masked scores of this wave's row block: P[t][s] = q_t . k_s for s <= t, held in registers for now
+        f32x16 pt[TB];
+#pragma unroll
+        for (int sb = 0; sb < TB; ++sb) {
+            // A[m=t][k=i] = Q[t][i] (row walk), B[k=i][n=s] = K[s][i] (row walk)
+            if (sb <= tb) pt[sb] = gemm_tile(zero16f(), sQ + tb * 32 * LDK, LDK, 1, sK + sb * 32 * LDK, 1, LDK, DK, lane);
+        }
+        // state update S += K^T V (not needed after the segment's last chunk); the published copy in sS is the state
+        // BEFORE this chunk, which is what the output below needs
+        if (c0 + C < p1) {
+#pragma unroll
+            for (int n = 0; n < NS; ++n) {
+                const int id = w + 4 * n, ib = id / JB, jb = id % JB;
+                accS[n] = gemm_tile(accS[n], sK + ib * 32, 1, LDK, sV + jb * 32, LDV, 1, C, lane);
+            }
+        }
+        __syncthreads();   // K has been read for the last time: its place now takes the scores
 #pragma unroll
         for (int sb = 0; sb < TB; ++sb) {
             if (sb <= tb) {
-                // A[m=t][k=i] = Q[t][i] (row walk), B[k=i][n=s] = K[s][i] (row walk)
-                f32x16 p = gemm_tile(zero16f(), sQ + tb * 32 * LDK, LDK, 1, sK + sb * 32 * LDK, 1, LDK, DK, lane);
 #pragma unroll
                 for (int a = 0; a < 4; ++a)
 #pragma unroll
                     for (int b = 0; b < 4; ++b) {
                         const int row = 8 * a + 4 * h + b;   // query within the block; r = key within the block
-                        const float v = (sb == tb && r > row) ? 0.f : p[4 * a + b];
+                        const float v = (sb == tb && r > row) ? 0.f : pt[sb][4 * a + b];
                         sP[(tb * 32 + row) * LDP + sb * 32 + r] = v;
                     }
             }
@@ -373,14 +427,6 @@ __global__ __launch_bounds__(256) void f32_sweep_kernel(const float* __restrict_
                     const int pp = c0 + tb * 32 + 8 * a + 4 * h + b;
                     if (pp < p1) Ob[(size_t)phys_row(pp, N, rev) * DV + j0 + r] = accO[n][4 * a + b];
                 }
-        }
-        // state update S += K^T V (not needed after the segment's last chunk)
-        if (c0 + C < p1) {
-#pragma unroll
-            for (int n = 0; n < NS; ++n) {
-                const int id = w + 4 * n, ib = id / JB, jb = id % JB;
-                accS[n] = gemm_tile(accS[n], sK + ib * 32, 1, LDK, sV + jb * 32, LDV, 1, C, lane);
-            }
         }
     }
 }
