@@ -218,24 +218,9 @@ __device__ __forceinline__ f32x16 gemm_tile(f32x16 acc, const float* a_base, int
     return acc;
 }
 
-// C rows of a row-major [N][D] fp32 matrix, starting at logical position c0 -> LDS tile with leading dimension D+1.
-// Rows at or beyond p_end read as zero.
-template <int C, int D>
-__device__ __forceinline__ void load_tile_f32(float* lds, const float* base, int c0, int p_end, int N, bool rev, int tid)
-{
-    constexpr int V4 = D / 4;   // float4 per row
-#pragma unroll
-    for (int n = 0; n < C * V4 / 256; ++n) {
-        const int x = tid + 256 * n, row = x / V4, c4 = x % V4, p = c0 + row;
-        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (p < p_end) v = *reinterpret_cast<const float4*>(base + (size_t)phys_row(p, N, rev) * D + c4 * 4);
-        float* d = lds + row * (D + 1) + c4 * 4;
-        d[0] = v.x; d[1] = v.y; d[2] = v.z; d[3] = v.w;
-    }
-}
-
-// The same in two steps, so that the loads of the next chunk can be in flight while the current one is worked on:
-// fetch_tile_f32 brings a thread's share of the tile into registers, stash_tile_f32 puts it into LDS.
+// C rows of a row-major [N][D] fp32 matrix, starting at logical position c0 -> LDS tile with leading dimension D+1,
+// in two steps so that the loads of the next chunk can be in flight while the current one is worked on: fetch() brings
+// a thread's share of the tile into registers, stash() puts it into LDS.  Rows at or beyond p_end read as zero.
 template <int C, int D>
 struct TileRegsF32 {
     static constexpr int V4 = D / 4, NV = C * V4 / 256;
@@ -284,11 +269,19 @@ __global__ __launch_bounds__(256) void f32_seg_state_kernel(const float* __restr
     f32x16 acc[NT];
 #pragma unroll
     for (int n = 0; n < NT; ++n) acc[n] = zero16f();
+    TileRegsF32<R, DK> rk;
+    TileRegsF32<R, DV> rv;
+    rk.fetch(Kb, p0, p1, N, rev, tid);
+    rv.fetch(Vb, p0, p1, N, rev, tid);
     for (int c0 = p0; c0 < p1; c0 += R) {
         __syncthreads();
-        load_tile_f32<R, DK>(sK, Kb, c0, p1, N, rev, tid);
-        load_tile_f32<R, DV>(sV, Vb, c0, p1, N, rev, tid);
+        rk.stash(sK, tid);
+        rv.stash(sV, tid);
         __syncthreads();
+        if (c0 + R < p1) {     // the next step's rows, in flight during the products
+            rk.fetch(Kb, c0 + R, p1, N, rev, tid);
+            rv.fetch(Vb, c0 + R, p1, N, rev, tid);
+        }
 #pragma unroll
         for (int n = 0; n < NT; ++n) {
             const int id = w + 4 * n, ib = id / JB, jb = id % JB;
