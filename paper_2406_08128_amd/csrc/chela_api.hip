@@ -21,8 +21,8 @@ static int env_int(const char* name, int dflt)
 // the latter set by the kernel's LDS and register footprint).
 static long sweep_slots(int dk, int dv, int chunk, int dtype, bool is_bwd)
 {
-    if (dtype != CHELA_DTYPE_BF16) return 512;
     const bool narrow = (dk == 64 && dv == 64), wide = (dk == 128 && dv == 128);
+    if (dtype != CHELA_DTYPE_BF16) return narrow ? 512 : 256;     // fp32 sweep: 66 KB of LDS at the 64-wide shape, > 80 KB else
     int per_cu;
     if (is_bwd) per_cu = (chunk == 64 && !wide) ? 2 : 1;      // (one width of 128: the two states share an LDS tile)
     // (the 64-wide forward sweep holds four per unit, but is planned for two: filling the other two with shorter
