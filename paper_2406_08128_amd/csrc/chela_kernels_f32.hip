@@ -374,12 +374,16 @@ __global__ __launch_bounds__(256) void f32_sweep_kernel(const float* __restrict_
             rk.fetch(Kb, c0 + C, p1, N, rev, tid);
             rv.fetch(Vb, c0 + C, p1, N, rev, tid);
         }
-        // masked scores of this wave's row block: P[t][s] = q_t . k_s for s <= t, held in registers for now
-        f32x16 pt[TB];
+        // masked scores P[t][s] = q_t . k_s for s <= t, held in registers for now.  The WJ waves that share a row block
+        // share its score tiles out among themselves (tile sb goes to wave sb % WJ); all of them read the whole row
+        // block back from LDS below.
+        constexpr int NPT = (TB + WJ - 1) / WJ;
+        f32x16 pt[NPT];
 #pragma unroll
         for (int sb = 0; sb < TB; ++sb) {
             // A[m=t][k=i] = Q[t][i] (row walk), B[k=i][n=s] = K[s][i] (row walk)
-            if (sb <= tb) pt[sb] = gemm_tile(zero16f(), sQ + tb * 32 * LDK, LDK, 1, sK + sb * 32 * LDK, 1, LDK, DK, lane);
+            if (sb <= tb && sb % WJ == jg)
+                pt[sb / WJ] = gemm_tile(zero16f(), sQ + tb * 32 * LDK, LDK, 1, sK + sb * 32 * LDK, 1, LDK, DK, lane);
         }
         // state update S += K^T V (not needed after the segment's last chunk); the published copy in sS is the state
         // BEFORE this chunk, which is what the output below needs
@@ -393,18 +397,18 @@ __global__ __launch_bounds__(256) void f32_sweep_kernel(const float* __restrict_
         __syncthreads();   // K has been read for the last time: its place now takes the scores
 #pragma unroll
         for (int sb = 0; sb < TB; ++sb) {
-            if (sb <= tb) {
+            if (sb <= tb && sb % WJ == jg) {
 #pragma unroll
                 for (int a = 0; a < 4; ++a)
 #pragma unroll
                     for (int b = 0; b < 4; ++b) {
                         const int row = 8 * a + 4 * h + b;   // query within the block; r = key within the block
-                        const float v = (sb == tb && r > row) ? 0.f : pt[sb][4 * a + b];
+                        const float v = (sb == tb && r > row) ? 0.f : pt[sb / WJ][4 * a + b];
                         sP[(tb * 32 + row) * LDP + sb * 32 + r] = v;
                     }
             }
         }
-        __syncthreads();   // both waves of a row block wrote the same values; now every wave may read them
+        __syncthreads();   // the row blocks are complete; now every wave may read them
         f32x16 accO[NJ];
 #pragma unroll
         for (int n = 0; n < NJ; ++n) {
