@@ -18,6 +18,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
+MFMA_F32_PEAK_TFLOPS = 157.3    # dense fp32
 
 
 def algorithmic_bytes_per_token_head(dk, dv, es=2):
@@ -214,6 +215,8 @@ def main():
                          "without a mask (the classification models' form); conv: the short-long convolution of "
                          "Sec. 4.2 at the workload's width (B x H*dk channels x N steps); decode: single-token steps of the recurrent form")
     ap.add_argument("--decode-batch", type=int, default=256, help="sequences decoded together in --mode decode")
+    ap.add_argument("--io-dtype", default="workload", choices=["workload", "f32"],
+                    help="f32: run the workload's shape through the fp32 I/O entry points (--mode train only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--graph", action="store_true",
                     help="capture one step into a HIP graph (caller-owned scratch) and time replays of it instead of "
@@ -234,6 +237,10 @@ def main():
     from paper_2406_08128_amd.workloads import WORKLOADS, make_gate_inputs, make_inputs, make_z_inputs, to_f64_numpy
 
     w = WORKLOADS[args.workload]
+    if args.io_dtype == "f32" and w.dtype != "f32":
+        assert args.mode == "train", "--io-dtype f32 goes with --mode train"
+        from paper_2406_08128_amd.workloads import shrink
+        w = shrink(w, dtype="f32", name=w.name + " shape with fp32 I/O")
     torch.cuda.set_device(0)
     if args.mode == "decode":
         return bench_decode(args, w, torch, binding)
@@ -437,7 +444,7 @@ def main():
         dom, dom_b = "bf16_fwd_sweep_kernel", fwd_b
     dom_us = kernels[dom]["avg_us"]
     achieved = dom_b * th / (dom_us * 1e-6) / 1e9
-    traffic = read_traffic(args.traffic_file) if (args.workload == "lm_bf16" and chunk == 64
+    traffic = read_traffic(args.traffic_file) if (args.workload == "lm_bf16" and chunk == 64 and w.dtype == "bf16"
                                                   and args.mode == "train") else None
     roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
@@ -479,7 +486,8 @@ def main():
     whole = {"hbm_GBs_algorithmic": round(step_bytes / (ms_per_step * 1e-3) / 1e9, 1),
              "hbm_frac": round(step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
              "mfma_TFLOPs_full_tile_model": round(step_flops / (ms_per_step * 1e-3) / 1e12, 1),
-             "mfma_frac": round(step_flops / (ms_per_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)}
+             "mfma_frac": round(step_flops / (ms_per_step * 1e-3) / 1e12
+                                / (MFMA_BF16_PEAK_TFLOPS if w.dtype == "bf16" else MFMA_F32_PEAK_TFLOPS), 4)}
 
     cpu = None
     cpu_reps = 1
