@@ -348,8 +348,11 @@ static int bwd_common(const void* Q, const void* K, const void* V, const void* d
                               false, ws, st);
     if (e == hipSuccess)
         e = launch_f32((const float*)K, (const float*)Q, (const float*)dO, (float*)dV, BH, N, dk, dv, p2, true, ws, st);
+    // the third call's segment states dO^T Q are the transposes of the second call's Q^T dO, which are still there
+    const bool same_split = p1.n_seg == p2.n_seg && p1.seg_len == p2.seg_len;
     if (e == hipSuccess)
-        e = launch_f32((const float*)V, (const float*)dO, (const float*)Q, (float*)dK, BH, N, dv, dk, p1, true, ws, st);
+        e = launch_f32((const float*)V, (const float*)dO, (const float*)Q, (float*)dK, BH, N, dv, dk, p1, true, ws, st,
+                       same_split);
     return e == hipSuccess ? CHELA_OK : CHELA_ERR_HIP;
 }
 

@@ -39,7 +39,7 @@ hipError_t launch_stream_probe(const void* const* in, int n_in, void* const* out
 // fp32 path.  `rev` runs the same map on the time-reversed sequence (anti-causal mask), which is what the
 // gradient with respect to K and V is (the backward is three calls of this launcher).
 hipError_t launch_f32(const float* Q, const float* K, const float* V, float* O, long BH, int N, int dk, int dv,
-                      const Plan& plan, bool rev, float* ws, hipStream_t st);
+                      const Plan& plan, bool rev, float* ws, hipStream_t st, bool reuse_states_T = false);
 
 // bf16 path.  S_in / S_out / dS_out / dS_in: optional carried states and their gradients, [BH][dk][dv] fp32.
 // saved (optional): the forward writes the running state at the end of every save_every-th of its segments and of

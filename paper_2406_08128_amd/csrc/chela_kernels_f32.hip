@@ -308,7 +308,7 @@ template <int C, int DK, int DV>
 __global__ __launch_bounds__(256) void f32_sweep_kernel(const float* __restrict__ Q, const float* __restrict__ K,
                                                        const float* __restrict__ V, float* __restrict__ O,
                                                        const float* __restrict__ S0, int N, int seg_len, int n_seg,
-                                                       int rev)
+                                                       int rev, int s0_transposed)
 {
     constexpr int LDK = DK + 1, LDV = DV + 1, LDP = C + 1;
     constexpr int TB = C / 32, JB = DV / 32, IB = DK / 32;
@@ -336,7 +336,8 @@ __global__ __launch_bounds__(256) void f32_sweep_kernel(const float* __restrict_
     float* Ob = O + (size_t)bh * N * DV;
     const int p0 = seg * seg_len, p1 = min(N, p0 + seg_len);
 
-    // start state of this segment (exclusive prefix over earlier segments, zero for the first), as accumulator tiles
+    // start state of this segment (exclusive prefix over earlier segments, zero for the first), as accumulator tiles;
+    // s0_transposed: the array holds the states as [DV][DK] (left there by a call with keys and values exchanged)
     f32x16 accS[NS];
     const float* s0 = (S0 != nullptr && seg > 0) ? S0 + ((size_t)bh * n_seg + seg) * DK * DV : nullptr;
 #pragma unroll
@@ -346,7 +347,9 @@ __global__ __launch_bounds__(256) void f32_sweep_kernel(const float* __restrict_
         for (int a = 0; a < 4; ++a)
 #pragma unroll
             for (int b = 0; b < 4; ++b)
-                accS[n][4 * a + b] = s0 ? s0[(ib * 32 + 8 * a + 4 * h + b) * DV + jb * 32 + r] : 0.f;
+                accS[n][4 * a + b] = !s0 ? 0.f
+                                     : s0_transposed ? s0[(jb * 32 + r) * DK + ib * 32 + 8 * a + 4 * h + b]
+                                                     : s0[(ib * 32 + 8 * a + 4 * h + b) * DV + jb * 32 + r];
     }
 
     TileRegsF32<C, DK> rq, rk;
@@ -430,11 +433,11 @@ __global__ __launch_bounds__(256) void f32_sweep_kernel(const float* __restrict_
 
 template <int DK, int DV>
 static hipError_t launch_f32_impl(const float* Q, const float* K, const float* V, float* O, long BH, int N,
-                                  const Plan& plan, bool rev, float* ws, hipStream_t st)
+                                  const Plan& plan, bool rev, bool reuse_states_T, float* ws, hipStream_t st)
 {
     hipError_t e;
     constexpr int C = (DK == 128 && DV == 128) ? 32 : 64;   // what fits 160 KB of LDS
-    if (plan.n_seg > 1) {
+    if (plan.n_seg > 1 && !reuse_states_T) {
         dim3 grid((unsigned)BH, plan.n_seg);
         {
             ProfScope prof(KID_SEG_STATE_F32, st);
@@ -448,17 +451,20 @@ static hipError_t launch_f32_impl(const float* Q, const float* K, const float* V
     dim3 grid((unsigned)BH, plan.n_seg);
     ProfScope prof(KID_SWEEP_F32, st);
     hipLaunchKernelGGL((f32_sweep_kernel<C, DK, DV>), grid, dim3(256), 0, st, Q, K, V, O, plan.n_seg > 1 ? ws : nullptr,
-                       N, plan.seg_len, plan.n_seg, (int)rev);
+                       N, plan.seg_len, plan.n_seg, (int)rev, (int)reuse_states_T);
     return hipGetLastError();
 }
 
+// reuse_states_T: the workspace already holds the scanned segment states of a call with the same split whose keys
+// and values were this call's values and keys (so each state is the transpose of what this call needs): no pre-pass,
+// no scan, the sweep reads them transposed.
 hipError_t launch_f32(const float* Q, const float* K, const float* V, float* O, long BH, int N, int dk, int dv,
-                      const Plan& plan, bool rev, float* ws, hipStream_t st)
+                      const Plan& plan, bool rev, float* ws, hipStream_t st, bool reuse_states_T)
 {
-    if (dk == 64 && dv == 64) return launch_f32_impl<64, 64>(Q, K, V, O, BH, N, plan, rev, ws, st);
-    if (dk == 64 && dv == 128) return launch_f32_impl<64, 128>(Q, K, V, O, BH, N, plan, rev, ws, st);
-    if (dk == 128 && dv == 64) return launch_f32_impl<128, 64>(Q, K, V, O, BH, N, plan, rev, ws, st);
-    if (dk == 128 && dv == 128) return launch_f32_impl<128, 128>(Q, K, V, O, BH, N, plan, rev, ws, st);
+    if (dk == 64 && dv == 64) return launch_f32_impl<64, 64>(Q, K, V, O, BH, N, plan, rev, reuse_states_T, ws, st);
+    if (dk == 64 && dv == 128) return launch_f32_impl<64, 128>(Q, K, V, O, BH, N, plan, rev, reuse_states_T, ws, st);
+    if (dk == 128 && dv == 64) return launch_f32_impl<128, 64>(Q, K, V, O, BH, N, plan, rev, reuse_states_T, ws, st);
+    if (dk == 128 && dv == 128) return launch_f32_impl<128, 128>(Q, K, V, O, BH, N, plan, rev, reuse_states_T, ws, st);
     return hipErrorInvalidValue;
 }
 

@@ -1083,6 +1083,12 @@ def test_state_carry_lm_full_size_sampled():
             assert err <= 1e-5, (name, err)
 
 
+def test_fp32_io_lm_shape_full_size_sampled():
+    # bench.py --io-dtype f32: the LM shape through the fp32 I/O entry points
+    w = shrink(WORKLOADS["lm_bf16"], dtype="f32")
+    _run_case(w, 64, True, heads=[0, 17, 47])
+
+
 def test_decode_step_at_the_benchmarked_batch():
     B, H, dk, dv = 256, 12, 64, 64
     g = torch.Generator(device="cpu")
