@@ -340,23 +340,32 @@ __global__ __launch_bounds__(256) void f32_sweep_kernel(const float* __restrict_
     // s0_transposed: the array holds the states as [DV][DK] (left there by a call with keys and values exchanged)
     f32x16 accS[NS];
     const float* s0 = (S0 != nullptr && seg > 0) ? S0 + ((size_t)bh * n_seg + seg) * DK * DV : nullptr;
-#pragma unroll
-    for (int n = 0; n < NS; ++n) {
-        const int id = w + 4 * n, ib = id / JB, jb = id % JB;
-#pragma unroll
-        for (int a = 0; a < 4; ++a)
-#pragma unroll
-            for (int b = 0; b < 4; ++b)
-                accS[n][4 * a + b] = !s0 ? 0.f
-                                     : s0_transposed ? s0[(jb * 32 + r) * DK + ib * 32 + 8 * a + 4 * h + b]
-                                                     : s0[(ib * 32 + 8 * a + 4 * h + b) * DV + jb * 32 + r];
-    }
-
+    // (the first chunk's tiles are asked for first: they are what the loop waits for)
     TileRegsF32<C, DK> rq, rk;
     TileRegsF32<C, DV> rv;
     rq.fetch(Qb, p0, p1, N, rev, tid);
     rk.fetch(Kb, p0, p1, N, rev, tid);
     rv.fetch(Vb, p0, p1, N, rev, tid);
+#pragma unroll
+    for (int n = 0; n < NS; ++n) {
+        const int id = w + 4 * n, ib = id / JB, jb = id % JB;
+        // (one uniform branch around each unrolled set of loads, so that the 16 loads of a tile are issued together)
+        if (s0 == nullptr) {
+            accS[n] = zero16f();
+        } else if (s0_transposed) {
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+#pragma unroll
+                for (int b = 0; b < 4; ++b)
+                    accS[n][4 * a + b] = s0[(jb * 32 + r) * DK + ib * 32 + 8 * a + 4 * h + b];
+        } else {
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+#pragma unroll
+                for (int b = 0; b < 4; ++b)
+                    accS[n][4 * a + b] = s0[(ib * 32 + 8 * a + 4 * h + b) * DV + jb * 32 + r];
+        }
+    }
     for (int c0 = p0; c0 < p1; c0 += C) {
         __syncthreads();   // previous chunk fully consumed
         rq.stash(sQ, tid);
