@@ -455,13 +455,21 @@ __global__ __launch_bounds__(conv_threads(M)) void shortlong_conv_kernel(const I
 {
     constexpr int T = conv_threads(M);
     constexpr int NP = (M / 2) / T + 1;          // bin pairs per thread (the last one only exists for l = M/2)
-    constexpr bool FRESH = sizeof(IN) == 4;
+    constexpr bool FRESH = true;
     __shared__ __attribute__((aligned(16))) unsigned char lds[ConvLds<M>::BYTES];
     cplx* a = reinterpret_cast<cplx*>(lds);
     cplx* lo = a + ConvLds<M>::DATA;
     cplx* hi = lo + 128;
     const int tid = threadIdx.x;
     build_tables<M, T>(lo, hi, tid);
+    // The storage positions of a thread's bin pairs (k, M - k), packed two to a register: the one thing that does not
+    // depend on the sequence and is worth its registers (some 40 instructions per pair and sequence otherwise).
+    unsigned pos[NP];
+#pragma unroll
+    for (int i = 0; i < NP; ++i) {
+        const int l = tid + T * i, kk = pair_bin<M>(l <= M / 2 ? l : 0);
+        pos[i] = (unsigned)conv_pad(spectrum_pos<M>(kk)) | (unsigned)conv_pad(spectrum_pos<M>((M - kk) & (M - 1))) << 16;
+    }
     SeqRegs<M, T, IN> xr;
     long bc = blockIdx.x;
     if (bc < total) xr.load(X + bc * (long)L, L, tid);
@@ -470,9 +478,8 @@ __global__ __launch_bounds__(conv_threads(M)) void shortlong_conv_kernel(const I
         OUT* y = Y + bc * (long)L;
         // what depends on the thread but not on the sequence (LDS addresses, bin positions, twiddles) is recomputed
         // per sequence behind an opaque copy of the thread index: hoisted out of this loop it would fill the
-        // register file.  With fp32 I/O (twice the registers for the sequence fetched ahead) every stage takes a
-        // fresh copy, so that positions shared between stages do not stay live in between; with bf16 I/O there is
-        // room, and sharing them measured 3 % faster.
+        // register file.  Every stage takes a fresh copy, so that values shared between stages do not stay live in
+        // between (the registers go to the bin-pair positions above instead).
         int tp = tid;
         asm volatile("" : "+v"(tp));
         __syncthreads();        // the tables are built / the previous sequence has been read out of a[]
@@ -498,13 +505,12 @@ __global__ __launch_bounds__(conv_threads(M)) void shortlong_conv_kernel(const I
             for (int i = 0; i < NP; ++i) {
                 const int l = tp + T * i;
                 if (l <= M / 2) {
-                    const int kk = pair_bin<M>(l);
-                    const int p1 = conv_pad(spectrum_pos<M>(kk)), p2 = conv_pad(spectrum_pos<M>((M - kk) & (M - 1)));
+                    const int p1 = pos[i] & 0xffffu, p2 = pos[i] >> 16;
                     const cplx w = pw.next(l);
                     cplx Xk, Xmk, Zk, Zmk;
                     untangle(a[p1], conj(a[p2]), w, Xk, Xmk);
                     const cplx K1 = mk(kq[i].x, kq[i].y), K2 = mk(kq[i].z, kq[i].w);
-                    if (kk == 0) {
+                    if (l == 0) {       // (pair 0 is bin 0)
                         // bins 0 and M are real and share storage slot 0
                         const float y0 = Xk.x * K1.x, ym = Xmk.x * K2.x;
                         a[p1] = mk(0.5f * (y0 + ym), 0.5f * (y0 - ym));
