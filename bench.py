@@ -183,6 +183,7 @@ def bench_conv(args, w, torch, binding):
         c1 = time.perf_counter()
         cpu = {"value": round(L * nch / d / (c1 - c0), 2), "unit": "tokens/s", "cores": min(oracle.num_threads(), nch),
                "kind": "oracle", "seconds": round(c1 - c0, 3),
+               "cpu_seconds": round((c1 - c0) * min(oracle.num_threads(), nch), 1),
                "sample": "fp64 direct-sum oracle on %d of the %d (batch, channel) sequences; tokens/s = L / (seconds "
                          "scaled to all %d channels of one batch entry)" % (nch, B * d, d)}
     print(json.dumps({
@@ -547,6 +548,7 @@ def main():
                     break
         cpu = {"value": round(cpu_reps * w.tokens / (c1 - c0), 1), "unit": "tokens/s", "cores": oracle.num_threads(),
                "kind": "oracle", "seconds": round(c1 - c0, 3),
+               "cpu_seconds": round((c1 - c0) * oracle.num_threads(), 1),       # wall time x threads: the CPU work done
                "sample": "fp64 oracle, %s, all %d (b,h) pairs of the workload, %d repetition%s"
                          % ("fwd+bwd" if has_bwd else "fwd", w.B * w.H, cpu_reps, "" if cpu_reps == 1 else "s")}
 
