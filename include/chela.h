@@ -39,7 +39,10 @@
  *              an internal allocation that grows on demand (growing it
  *              synchronises the device) and lives until chela_shutdown().
  *              Calls that may overlap in time on different streams must not
- *              share one workspace.
+ *              share one workspace: a call's kernels use the buffer that was
+ *              in force when the call was made, so a caller with two streams
+ *              sets one buffer before the calls on each (the setting itself
+ *              is process-wide and guarded by a mutex).
  *   Errors   : 0 on success, a negative CHELA_ERR_* otherwise.  Every argument
  *              check is done on the host before the first HIP call, so a
  *              rejected call has touched nothing.  No exceptions, no abort.
