@@ -238,6 +238,42 @@ def test_caller_workspace_and_side_stream():
         binding.chela_set_workspace(None)
 
 
+def test_two_streams_with_a_scratch_buffer_each():
+    # calls that overlap in time on two streams, each enqueued while its own buffer is the one in force
+    wa, wb = _small("bf16", N=5000, B=2, H=3, seed=41), _small("bf16", N=7000, B=1, H=5, seed=42)
+    da, db = _dev(make_inputs(wa)), _dev(make_inputs(wb))
+    ref_a = (binding.chela_linattn_fwd(da["Q"], da["K"], da["V"]),) + tuple(
+        binding.chela_linattn_bwd(da["Q"], da["K"], da["V"], da["dO"]))
+    ref_b = (binding.chela_linattn_fwd(db["Q"], db["K"], db["V"]),) + tuple(
+        binding.chela_linattn_bwd(db["Q"], db["K"], db["V"], db["dO"]))
+    need = lambda w: max(binding.chela_linattn_workspace_bytes(w.B, w.H, w.N, w.dk, w.dv, 64, bwd, binding.DTYPE_BF16)
+                         for bwd in (False, True))
+    buf_a = torch.empty(need(wa), dtype=torch.uint8, device="cuda")
+    buf_b = torch.empty(need(wb), dtype=torch.uint8, device="cuda")
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    try:
+        got_a, got_b = [], []
+        for rep in range(3):
+            binding.chela_set_workspace(buf_a)
+            with torch.cuda.stream(sa):
+                got_a.append((binding.chela_linattn_fwd(da["Q"], da["K"], da["V"]),)
+                             + tuple(binding.chela_linattn_bwd(da["Q"], da["K"], da["V"], da["dO"])))
+            binding.chela_set_workspace(buf_b)
+            with torch.cuda.stream(sb):
+                got_b.append((binding.chela_linattn_fwd(db["Q"], db["K"], db["V"]),)
+                             + tuple(binding.chela_linattn_bwd(db["Q"], db["K"], db["V"], db["dO"])))
+        sa.synchronize()
+        sb.synchronize()
+        for got, ref in ((got_a, ref_a), (got_b, ref_b)):
+            for g in got:
+                for x, y in zip(g, ref):
+                    assert torch.equal(x, y)
+    finally:
+        torch.cuda.synchronize()
+        binding.chela_set_workspace(None)
+
+
 def test_more_heads_than_a_grid_dimension_holds():
     # 70 000 (b,h) pairs: more than the 65 535 a secondary grid dimension can carry
     B, H, N, d = 1, 70000, 64, 64
