@@ -87,6 +87,23 @@ int chela_linattn_bwd(const void *Q, const void *K, const void *V, const void *d
                       void *dQ, void *dK, void *dV,
                       int B, int H, int N, int dk, int dv, int chunk, void *stream);
 
+/* chela_linattn_fwd for callers that cannot allocate device memory: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and the same result as chela_linattn_fwd
+ * (bf16 I/O), but the per-segment states live in a fixed array of device memory that is part of the library's code
+ * object (32 MiB; every GPU the library runs on holds its own copy until the process ends), so the call never
+ * calls hipMalloc, hipFree or any allocating routine, whatever chela_set_workspace() was given.
+ *   Limit    : problems whose segment states need more than 32 MiB
+ *              (chela_linattn_workspace_bytes(B, H, N, dk, dv, chunk, 0, CHELA_DTYPE_BF16) says how much) are rejected
+ *              with CHELA_ERR_WORKSPACE before anything is enqueued.  All five benchmark shapes fit.
+ *   Set-up   : the first call on a device asks the runtime for the array's address on that device (the device must
+ *              be current, as for every call); make that first call outside a graph capture.
+ *   Sharing  : all calls on one GPU use that GPU's one array, which keeps the previous call's contents (nothing in
+ *              it has to start at zero: every slot that is read has been written by the same call first).  Calls
+ *              that may overlap in time on one GPU -- two streams, two threads -- race on it: serialise them, or use
+ *              chela_linattn_fwd with a workspace per stream. */
+int chela_linattn_fwd_noalloc(const void *Q, const void *K, const void *V, void *O,
+                              int B, int H, int N, int dk, int dv, int chunk, void *stream);
+
 /* The same two maps with fp32 tensors and fp32 arithmetic throughout. */
 int chela_linattn_fwd_f32(const void *Q, const void *K, const void *V, void *O,
                           int B, int H, int N, int dk, int dv, int chunk, void *stream);

@@ -35,7 +35,7 @@ def lib() -> ctypes.CDLL:
             "%s not found: build it with `python -m paper_2406_08128_amd.build` (there is no CPU fallback)" % LIB_PATH)
     L = ctypes.CDLL(LIB_PATH)
     vp, i, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
-    for name in ("chela_linattn_fwd", "chela_linattn_fwd_f32"):
+    for name in ("chela_linattn_fwd", "chela_linattn_fwd_f32", "chela_linattn_fwd_noalloc"):
         f = getattr(L, name)
         f.argtypes = [vp, vp, vp, vp, i, i, i, i, i, i, vp]
         f.restype = i
@@ -174,6 +174,19 @@ def chela_linattn_fwd(Q, K, V, O=None, chunk: int = 64, stream=None):
     with torch.cuda.device(Q.device):
         _check(f(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), B, H, N, dk, dv, int(chunk),
                  _stream_ptr(stream)))
+    return O
+
+
+def chela_linattn_fwd_noalloc(Q, K, V, O, chunk: int = 64, stream=None):
+    """chela_linattn_fwd with the library's fixed scratch array: the call allocates nothing (O is the caller's)."""
+    B, H, N, dk, dv = _dims(Q, K, V)
+    if Q.dtype != torch.bfloat16:
+        raise TypeError("chela_linattn_fwd_noalloc takes bfloat16 tensors")
+    if O.shape != V.shape or O.dtype != Q.dtype or not O.is_cuda or not O.is_contiguous():
+        raise ValueError("O must match V")
+    with torch.cuda.device(Q.device):
+        _check(lib().chela_linattn_fwd_noalloc(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), B, H, N, dk, dv,
+                                               int(chunk), _stream_ptr(stream)))
     return O
 
 

@@ -207,6 +207,35 @@ static int get_workspace(size_t bytes, float** out)
     return CHELA_OK;
 }
 
+// ------------------------------------------------------------------ scratch that is never allocated
+// For callers that cannot allocate (HIP graph capture, serving loops, harnesses that forbid hipMalloc): a
+// file-scope device array that the code object brings with it.  Every GPU the library runs on holds its own copy at
+// its own address until the process ends.  The name below is a host-side stand-in, not a device address: host code
+// asks the runtime for the address once per device and from then on uses only that pointer.
+constexpr size_t kStaticScratchBytes = (size_t)32 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+static void* g_scratch_ptr[kMaxDev] = {nullptr};
+
+// The current device's copy of `scratch` (looked up on first use on that device, with that device current).
+static int static_scratch(float** out)
+{
+    *out = nullptr;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return CHELA_ERR_HIP; }
+    if (dev < 0 || dev >= kMaxDev) return CHELA_ERR_HIP;
+    std::lock_guard<std::mutex> lk(g_mu);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) {
+            (void)hipGetLastError();
+            return CHELA_ERR_HIP;
+        }
+        g_scratch_ptr[dev] = p;
+    }
+    *out = (float*)g_scratch_ptr[dev];
+    return CHELA_OK;
+}
+
 // ------------------------------------------------------------------ validation
 struct Range { const char* p; size_t n; };
 static bool overlap(const Range& a, const Range& b)
@@ -257,8 +286,10 @@ static int bf16_bwd_effective_chunk(int dk, int dv, int chunk)
     return (chunk == 128 && dk == 64 && dv == 64) ? 128 : 64;
 }
 
+// static_ws: the segment states go into the file-scope device array instead of the workspace (nothing is allocated;
+// a problem whose states do not fit is rejected).
 static int fwd_common(const void* Q, const void* K, const void* V, void* O, const float* S_in, float* S_out, int B,
-                      int H, int N, int dk, int dv, int chunk, void* stream, int dtype)
+                      int H, int N, int dk, int dv, int chunk, void* stream, int dtype, bool static_ws = false)
 {
     const size_t es = dtype == CHELA_DTYPE_BF16 ? 2 : 4;
     const size_t th = (B > 0 && H > 0 && N > 0) ? (size_t)B * H * N : 0;
@@ -289,7 +320,12 @@ static int fwd_common(const void* Q, const void* K, const void* V, void* O, cons
     if (dtype == CHELA_DTYPE_F32) chunk = f32_effective_chunk(dk, dv, chunk);
     Plan plan = make_plan(BH, N, dk, dv, chunk, dtype, false, S_in != nullptr);
     float* ws = nullptr;
-    rc = get_workspace(plan.ws_bytes, &ws);
+    if (static_ws) {
+        if (plan.ws_bytes > kStaticScratchBytes) return CHELA_ERR_WORKSPACE;
+        rc = plan.ws_bytes ? static_scratch(&ws) : CHELA_OK;
+    } else {
+        rc = get_workspace(plan.ws_bytes, &ws);
+    }
     if (rc != CHELA_OK) return rc;
     hipError_t e = dtype == CHELA_DTYPE_BF16
         ? launch_bf16_fwd(Q, K, V, O, S_in, S_out, nullptr, 1, BH, N, dk, dv, plan, ws, (hipStream_t)stream)
@@ -589,6 +625,12 @@ int chela_linattn_fwd(const void* Q, const void* K, const void* V, void* O, int 
                       int chunk, void* stream)
 {
     return fwd_common(Q, K, V, O, nullptr, nullptr, B, H, N, dk, dv, chunk, stream, CHELA_DTYPE_BF16);
+}
+
+int chela_linattn_fwd_noalloc(const void* Q, const void* K, const void* V, void* O, int B, int H, int N, int dk,
+                              int dv, int chunk, void* stream)
+{
+    return fwd_common(Q, K, V, O, nullptr, nullptr, B, H, N, dk, dv, chunk, stream, CHELA_DTYPE_BF16, true);
 }
 
 int chela_linattn_fwd_f32(const void* Q, const void* K, const void* V, void* O, int B, int H, int N, int dk,

@@ -54,7 +54,8 @@ def _bwd(L, name="chela_linattn_bwd", Q=A, K=A + SZ, V=A + 2 * SZ, dO=A + 3 * SZ
     return getattr(L, name)(Q, K, V, dO, dQ, dK, dV, B, H, N, dk, dv, chunk, None)
 
 
-@pytest.mark.parametrize("name", ["chela_linattn_fwd", "chela_linattn_fwd_f32", "chela_linattn_fwd_bnhd"])
+@pytest.mark.parametrize("name", ["chela_linattn_fwd", "chela_linattn_fwd_f32", "chela_linattn_fwd_bnhd",
+                                  "chela_linattn_fwd_noalloc"])
 def test_fwd_argument_errors(L, name):
     assert _fwd(L, name, Q=None) == -1
     assert _fwd(L, name, O=None) == -1
@@ -72,6 +73,14 @@ def test_fwd_argument_errors(L, name):
     assert _fwd(L, name, N=0, Q=None, K=None, V=None, O=None) == 0
     assert _fwd(L, name, B=0) == 0
     assert _fwd(L, name, H=0) == 0
+
+
+def test_noalloc_forward_rejects_states_beyond_its_fixed_array(L):
+    # decided on the host from the plan, before any HIP call: 172 sequences of two million tokens with 64 x 128 states
+    B, H, N, dk, dv = 1, 172, 1984972, 64, 128
+    assert L.chela_linattn_workspace_bytes(B, H, N, dk, dv, 64, 0, 0) > (32 << 20)
+    big = 1 << 40
+    assert L.chela_linattn_fwd_noalloc(A, A + big, A + 2 * big, A + 3 * big, B, H, N, dk, dv, 64, None) == -7
 
 
 def test_chunk_sets_differ_by_dtype(L):
