@@ -82,7 +82,12 @@ int chela_linattn_fwd(const void *Q, const void *K, const void *V, void *O,
  *   dQ_t = sum_{s<=t} (dO_t . v_s) k_s
  *   dK_s = sum_{t>=s} (dO_t . v_s) q_t
  *   dV_s = sum_{t>=s} (q_t . k_s) dO_t
- * dO: [B,H,N,dv] in; dQ, dK: [B,H,N,dk] out; dV: [B,H,N,dv] out. */
+ * dO: [B,H,N,dv] in; dQ, dK: [B,H,N,dk] out; dV: [B,H,N,dv] out.
+ * The sweep walks a stretch of a sequence (at most 8192 tokens) from its end to its start and obtains the state in
+ * front of each chunk by subtracting the chunk's K^T V from the state behind it, in fp32.  Two consequences: dQ_t
+ * depends on the keys and values AFTER t within such a stretch through rounding of the order of 1e-7 of the state
+ * (never through more: the exact terms cancel), and a non-finite key or value row makes dQ non-finite for the
+ * earlier tokens of its stretch as well as for the later ones.  dK and dV depend on nothing before their token. */
 int chela_linattn_bwd(const void *Q, const void *K, const void *V, const void *dO,
                       void *dQ, void *dK, void *dV,
                       int B, int H, int N, int dk, int dv, int chunk, void *stream);
@@ -181,6 +186,10 @@ int chela_linattn_bwd_saved(const void *Q, const void *K, const void *V, const v
                             void *dQ, void *dK, void *dV,
                             int B, int H, int N, int dk, int dv, int chunk, void *stream);
 size_t chela_linattn_saved_bytes(int B, int H, int N, int dk, int dv, int chunk);
+/* Scratch of the training pair, which splits the sequences on a grid of its own (the forward cuts wherever the
+ * backward will want a state): bytes chela_linattn_fwd_save and the gated forwards given `saved` (is_bwd = 0) or
+ * chela_linattn_bwd_saved (is_bwd = 1) take from the workspace; 0 for invalid arguments. */
+size_t chela_linattn_train_workspace_bytes(int B, int H, int N, int dk, int dv, int chunk, int is_bwd);
 
 /* ---- non-causal form (Sec. 2.1, Eq. 2 as written, without Norm): O = Q (K^T V), every token sees every token.
  * This is what the paper's sequence classifiers run (no mask); bf16 I/O, fp32 accumulation, the d_k x d_v matrix
@@ -274,9 +283,13 @@ int chela_linattn_step_gated(const void *q, const void *k, const void *v, const 
                              int B, int H, int dk, int dv, void *stream);
 
 /* Bytes of device scratch one call with these arguments needs, with or without
- * carried states (0 if the arguments are invalid).  The size is O(B*H*dk*dv*segments)
- * with a bounded number of segments per (b,h): it does not grow with N once
- * the GPU is full, which is the fixed-memory property claimed in Sec. 1. */
+ * carried states (0 if the arguments are invalid; the training pair has its own query,
+ * chela_linattn_train_workspace_bytes).  The size is B*H*dk*dv*4 bytes per segment.
+ * Forward: the number of segments per (b,h) is set by the GPU, not by N, so the scratch
+ * does not grow with N once the GPU is full -- the fixed-memory property claimed in
+ * Sec. 1.  bf16 backward: in addition no segment is longer than 8192 tokens (see
+ * chela_linattn_bwd), i.e. at least two states per 8192 tokens of a sequence: 0.4 % of
+ * the bytes of the tensors themselves. */
 size_t chela_linattn_workspace_bytes(int B, int H, int N, int dk, int dv, int chunk,
                                      int is_bwd, int dtype);
 

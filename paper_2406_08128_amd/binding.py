@@ -67,6 +67,8 @@ def lib() -> ctypes.CDLL:
     L.chela_linattn_bwd_saved.restype = i
     L.chela_linattn_saved_bytes.argtypes = [i, i, i, i, i, i]
     L.chela_linattn_saved_bytes.restype = sz
+    L.chela_linattn_train_workspace_bytes.argtypes = [i, i, i, i, i, i, i]
+    L.chela_linattn_train_workspace_bytes.restype = sz
     f32 = ctypes.c_float
     L.chela_linattn_fwd_gated.argtypes = [vp] * 7 + [f32, i, i, i, i, i, i, vp]
     L.chela_linattn_fwd_gated.restype = i
@@ -619,6 +621,10 @@ def chela_linattn_step_gated(q, k, v, g, S, eps, y=None, stream=None):
 
 def chela_linattn_workspace_bytes(B, H, N, dk, dv, chunk, is_bwd, dtype) -> int:
     return int(lib().chela_linattn_workspace_bytes(B, H, N, dk, dv, chunk, int(bool(is_bwd)), int(dtype)))
+
+
+def chela_linattn_train_workspace_bytes(B, H, N, dk, dv, chunk, is_bwd) -> int:
+    return int(lib().chela_linattn_train_workspace_bytes(B, H, N, dk, dv, chunk, int(bool(is_bwd))))
 
 
 def chela_set_workspace(buf: Optional[torch.Tensor]) -> None:

@@ -17,6 +17,8 @@ static int env_int(const char* name, int dflt)
     return std::atoi(s);
 }
 
+constexpr long kMaxBwdWalkTokens = 8192;   // longest stretch the bf16 backward walks its state back over
+
 // Workgroups of the sweep kernel that the plan counts on at once (256 compute units x resident workgroups per unit,
 // the latter set by the kernel's LDS and register footprint).
 static long sweep_slots(int dk, int dv, int chunk, int dtype, bool is_bwd)
@@ -68,7 +70,7 @@ static long choose_segments(long BH, long n_chunks, long slots, double g_min, do
     return best;
 }
 
-Plan make_plan(long BH, int N, int dk, int dv, int chunk, int dtype, bool is_bwd, bool stateful)
+Plan make_plan(long BH, int N, int dk, int dv, int chunk, int dtype, bool is_bwd, bool stateful, bool can_checkpoint)
 {
     Plan p{};
     p.chunk = chunk;
@@ -85,12 +87,30 @@ Plan make_plan(long BH, int N, int dk, int dv, int chunk, int dtype, bool is_bwd
     if (forced > 0) cps = (forced + chunk - 1) / chunk;
     if (cps > n_chunks) cps = n_chunks;
     if (cps < 1) cps = 1;
+    // The bf16 backward sweep enters a segment with the state at the segment's END and walks it back one chunk per
+    // step in fp32 (S_{c-1} = S_c - K_c^T V_c).  For states that grow with the position (keys and values with a
+    // non-zero mean) the rounding of that walk, relative to the small early states, grows with the length walked to
+    // the power 1.5: measured on such data, the worst row of dQ in the first chunk is off by 1e-2 of its norm after
+    // 32768 tokens, 2.8e-2 after 65536, 0.23 after 262144, against 4e-3 .. 6e-3 from bf16 rounding alone.  The walk
+    // is therefore never longer than kMaxBwdWalkTokens (1.2e-3 by the same law): a single segment whose sweep builds
+    // the state itself drops copies of it on the way forward and picks them up on the way back; every other plan
+    // gets shorter segments (more states to scan, nothing else).
+    const long max_walk = kMaxBwdWalkTokens / chunk;
+    if (is_bwd && dtype == CHELA_DTYPE_BF16 && cps > max_walk) {
+        if (cps >= n_chunks && !stateful && can_checkpoint) p.ckpt_every = (int)max_walk;
+        else if (forced <= 0) cps = max_walk;
+    }
     if ((n_chunks + cps - 1) / cps > 32768) cps = (n_chunks + 32767) / 32768;   // segments ride on grid.y
     p.seg_len = (int)(cps * chunk);
     p.n_seg = (int)((n_chunks + cps - 1) / cps);
     const int n_states = (dtype == CHELA_DTYPE_BF16 && is_bwd) ? 2 : 1;   // fp32 bwd reuses one array 3 times
     // a carried-in state goes through the scan even when there is a single segment
-    p.ws_bytes = (p.n_seg > 1 || stateful) ? (size_t)BH * p.n_seg * p.state_elems * sizeof(float) * n_states : 0;
+    if (p.n_seg > 1 || stateful) {
+        p.ckpt_every = 0;
+        p.ws_bytes = (size_t)BH * p.n_seg * p.state_elems * sizeof(float) * n_states;
+    } else {
+        p.ws_bytes = (size_t)BH * (size_t)plan_n_ckpt(p, N) * p.state_elems * sizeof(float);
+    }
     return p;
 }
 
@@ -362,7 +382,7 @@ static int bwd_common(const void* Q, const void* K, const void* V, const void* d
     }
     if (dtype == CHELA_DTYPE_BF16) {
         Plan plan = make_plan(BH, N, dk, dv, bf16_bwd_effective_chunk(dk, dv, chunk), dtype, true,
-                              S_in != nullptr || dS_out != nullptr);
+                              S_in != nullptr || dS_out != nullptr, true);
         float* ws = nullptr;
         rc = get_workspace(plan.ws_bytes, &ws);
         if (rc != CHELA_OK) return rc;
@@ -443,7 +463,7 @@ static int zbwd_common(const void* Z, const float* aff, const void* V, const voi
         if (d_aff && ab) return launch_zero_fill(d_aff, ab / sizeof(float), (hipStream_t)stream) == hipSuccess ? CHELA_OK : CHELA_ERR_HIP;
         return CHELA_OK;
     }
-    Plan plan = want_saved ? t.bwd : make_plan(BH, N, dk, dv, 64, CHELA_DTYPE_BF16, true, false);
+    Plan plan = want_saved ? t.bwd : make_plan(BH, N, dk, dv, 64, CHELA_DTYPE_BF16, true, false, true);
     float* ws = nullptr;
     rc = get_workspace(plan.ws_bytes + zbwd_extra_ws_bytes(BH, plan, dk), &ws);
     if (rc != CHELA_OK) return rc;
@@ -562,7 +582,7 @@ static int bnhd_common(const void* Q, const void* K, const void* V, const void* 
     bool empty = false;
     int rc = validate(in_v, inb, 4, out_v, outb, 3, B, H, N, dk, dv, chunk, CHELA_DTYPE_BF16, &empty);
     if (rc != CHELA_OK || empty) return rc;
-    Plan plan = make_plan((long)B * H, N, dk, dv, 64, CHELA_DTYPE_BF16, is_bwd, false);
+    Plan plan = make_plan((long)B * H, N, dk, dv, 64, CHELA_DTYPE_BF16, is_bwd, false, true);
     float* ws = nullptr;
     rc = get_workspace(plan.ws_bytes, &ws);
     if (rc != CHELA_OK) return rc;
@@ -695,8 +715,12 @@ size_t chela_linattn_z_workspace_bytes(int B, int H, int N, int dk, int dv, int 
     if (!((dk == 64 || dk == 128) && (dv == 64 || dv == 128))) return 0;
     if (!(chunk == 64 || chunk == 128)) return 0;
     const long BH = (long)B * H;
-    Plan plan = make_plan(BH, N, dk, dv, 64, CHELA_DTYPE_BF16, is_bwd != 0, false);
-    return plan.ws_bytes + (is_bwd ? zbwd_extra_ws_bytes(BH, plan, dk) : 0);
+    Plan plan = make_plan(BH, N, dk, dv, 64, CHELA_DTYPE_BF16, is_bwd != 0, false, true);
+    size_t need = plan.ws_bytes + (is_bwd ? zbwd_extra_ws_bytes(BH, plan, dk) : 0);
+    // the training pair (chela_linattn_zfwd_save / _zbwd_saved, the gated forward with `saved`) splits on its own grid
+    const TrainPlans t = make_train_plans(BH, N, dk, dv, 64);
+    const size_t pair = is_bwd ? t.bwd.ws_bytes + zbwd_extra_ws_bytes(BH, t.bwd, dk) : t.fwd.ws_bytes;
+    return need > pair ? need : pair;
 }
 
 int chela_linattn_fwd_save(const void* Q, const void* K, const void* V, void* O, void* saved, int B, int H, int N,
@@ -934,8 +958,11 @@ size_t chela_linattn_workspace_bytes(int B, int H, int N, int dk, int dv, int ch
     if (!((dk == 64 || dk == 128) && (dv == 64 || dv == 128))) return 0;
     if (dtype == CHELA_DTYPE_BF16) {
         if (!(chunk == 64 || chunk == 128)) return 0;
-        if (is_bwd) chunk = bf16_bwd_effective_chunk(dk, dv, chunk);
-        return make_plan((long)B * H, N, dk, dv, chunk, dtype, is_bwd != 0, true).ws_bytes;
+        // the larger need of the calls this query stands for: with and without carried states
+        const int cb = is_bwd ? bf16_bwd_effective_chunk(dk, dv, chunk) : chunk;
+        const size_t a = make_plan((long)B * H, N, dk, dv, cb, dtype, is_bwd != 0, true, true).ws_bytes;
+        const size_t b = make_plan((long)B * H, N, dk, dv, cb, dtype, is_bwd != 0, false, true).ws_bytes;
+        return a > b ? a : b;
     }
     if (dtype != CHELA_DTYPE_F32) return 0;
     if (!(chunk == 16 || chunk == 32 || chunk == 64)) return 0;
@@ -945,6 +972,20 @@ size_t chela_linattn_workspace_bytes(int B, int H, int N, int dk, int dv, int ch
         if (b > a) a = b;
     }
     return a;
+}
+
+size_t chela_linattn_train_workspace_bytes(int B, int H, int N, int dk, int dv, int chunk, int is_bwd)
+{
+    if (B <= 0 || H <= 0 || N <= 0) return 0;
+    if (!((dk == 64 || dk == 128) && (dv == 64 || dv == 128))) return 0;
+    if (!(chunk == 64 || chunk == 128)) return 0;
+    size_t need = 0;
+    for (int c : {chunk, 64}) {      // (the gated forwards that fill `saved` always tile with 64 tokens)
+        const TrainPlans t = make_train_plans((long)B * H, N, dk, dv, c);
+        const size_t x = is_bwd ? t.bwd.ws_bytes : t.fwd.ws_bytes;
+        if (x > need) need = x;
+    }
+    return need;
 }
 
 int chela_set_workspace(void* dev_ptr, size_t bytes)

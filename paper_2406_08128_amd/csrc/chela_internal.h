@@ -15,9 +15,22 @@ struct Plan {
     int n_seg;     // segments per (b,h); 1 means no pre-pass and no workspace
     size_t state_elems;  // dk*dv
     size_t ws_bytes;     // scratch bytes for the whole call
+    int ckpt_every;      // bf16 backward with a single segment: the sweep's first pass leaves the running state every
+                         // ckpt_every chunks and its walk back picks those copies up again (0: none needed)
 };
 
-Plan make_plan(long BH, int N, int dk, int dv, int chunk, int dtype, bool is_bwd, bool stateful);
+// Checkpoints of a single-segment backward: how many, and where they live ([BH][n][dk*dv] fp32 at the workspace's start).
+inline long plan_n_ckpt(const Plan& p, int N)
+{
+    if (p.ckpt_every <= 0) return 0;
+    const long n_ch = ((long)N + p.chunk - 1) / p.chunk;
+    return (n_ch - 1) / p.ckpt_every;
+}
+
+// can_checkpoint: the caller's backward builds the state itself in a first pass over the sequence when there is a
+// single segment (the plain calls without carried or saved states), so long single segments are allowed.
+Plan make_plan(long BH, int N, int dk, int dv, int chunk, int dtype, bool is_bwd, bool stateful,
+               bool can_checkpoint = false);
 
 // scan modes for scan_states()
 enum { SCAN_EXCL_PREFIX = 0, SCAN_INCL_PREFIX = 1, SCAN_EXCL_SUFFIX = 2 };

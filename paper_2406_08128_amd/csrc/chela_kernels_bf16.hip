@@ -691,6 +691,11 @@ __device__ __forceinline__ void fwd_sweep_body(const bf16* __restrict__ Qb, cons
 //             P = (Q K^T) o M,  dP = (dO V^T) o M, every output accumulated transposed.
 // Send == nullptr means the whole sequence is this one segment: S is then built here, R starts at zero.
 // R_final, if given, receives the state R after the segment's first chunk has been added ([dk][dv], fp32).
+// ckpt (only with Send == nullptr; may be null): the pass that builds S leaves a copy of the running state after
+// every ckpt_every chunks there, and the walk back takes that copy up again when it reaches the same place, so that
+// the fp32 rounding of the walk never accumulates over more than ckpt_every chunks (for states that grow with the
+// position it would otherwise swamp the small states of the first chunks of a long sequence).  Every lane writes and
+// later reads its own registers' worth: [copy][wave][tile][lane][16] floats.
 //
 // ZQK (Eq. 11-12, Q = alpha_q Z + beta_q, K = alpha_k Z + beta_k): Qb points at Z, Kb is unused, dQb receives
 // dZ = alpha_q dQ + alpha_k dK and dKb is unused.  The parameter gradients are sums over tokens,
@@ -754,7 +759,8 @@ __device__ __forceinline__ void bwd_sweep_body(const bf16* __restrict__ Qb, cons
                                                const float* __restrict__ Send, const float* __restrict__ Rnext,
                                                float* __restrict__ R_final, const float* __restrict__ aff,
                                                size_t aff_stride, float* __restrict__ part, int ldk, int ldv,
-                                               int ntok, unsigned char* lds, int tid, int w, int lane)
+                                               int ntok, unsigned char* lds, int tid, int w, int lane,
+                                               float* ckpt = nullptr, int ckpt_every = 0)
 {
     constexpr int LDK = DK + PAD, LDV = DV + PAD;
     constexpr int TB = C / 32, JB = DV / 32, IB = DK / 32;
@@ -817,6 +823,16 @@ __device__ __forceinline__ void bwd_sweep_body(const bf16* __restrict__ Qb, cons
                     accNS[n] = mfma(__builtin_bit_cast(bf16x8, a), ld_tr(sK, LDK, s0, ib * 32, lane), accNS[n]);
                 }
             }
+            if (ckpt != nullptr && (ci + 1) % ckpt_every == 0 && ci + 1 < n_ch) {
+                float4* dst = reinterpret_cast<float4*>(ckpt + (size_t)((ci + 1) / ckpt_every - 1) * (DK * DV)) +
+                              ((size_t)(w * NS) * 64 + lane) * 4;
+#pragma unroll
+                for (int n = 0; n < NS; ++n)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        dst[(size_t)n * 256 + q] = make_float4(accNS[n][4 * q], accNS[n][4 * q + 1], accNS[n][4 * q + 2],
+                                                               accNS[n][4 * q + 3]);
+            }
         }
         __syncthreads();
     }
@@ -853,6 +869,18 @@ __device__ __forceinline__ void bwd_sweep_body(const bf16* __restrict__ Qb, cons
             if (!ZQK) rk.load(Kb + (size_t)(c0 - C) * ldk, ldk, C, tid);
             rv.load(Vb + (size_t)(c0 - C) * ldv, ldv, C, tid);
             rg.load(Gb + (size_t)(c0 - C) * ldv, ldv, C, tid);
+        }
+        if (ckpt != nullptr && (ci + 1) % ckpt_every == 0 && ci + 1 < n_ch) {
+            // the state after this chunk as the first pass left it, in place of the one walked back to here
+            const float4* src = reinterpret_cast<const float4*>(ckpt + (size_t)((ci + 1) / ckpt_every - 1) * (DK * DV)) +
+                                ((size_t)(w * NS) * 64 + lane) * 4;
+#pragma unroll
+            for (int n = 0; n < NS; ++n)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float4 v = src[(size_t)n * 256 + q];
+                    accNS[n][4 * q] = v.x; accNS[n][4 * q + 1] = v.y; accNS[n][4 * q + 2] = v.z; accNS[n][4 * q + 3] = v.w;
+                }
         }
         // roll S back over this chunk: (-S^T) += V^T K, then publish S (state before this chunk)
 #pragma unroll
@@ -1180,7 +1208,8 @@ void bf16_bwd_sweep_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ 
                                                             bf16* __restrict__ dV, const float* __restrict__ Send,
                                                             const float* __restrict__ Rnext, float* __restrict__ dS_in,
                                                             const float* __restrict__ aff, int H,
-                                                            float* __restrict__ part, int N, int seg_len, int n_seg)
+                                                            float* __restrict__ part, int N, int seg_len, int n_seg,
+                                                            float* ckpt, int ckpt_every)
 {
     __shared__ __attribute__((aligned(16))) unsigned char lds[BwdLds<C, DK, DV, ZQK>::BYTES];
     const int seg = blockIdx.y;
@@ -1197,7 +1226,12 @@ void bf16_bwd_sweep_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ 
                                    (dS_in != nullptr && seg == 0) ? dS_in + (size_t)bh * DK * DV : nullptr,
                                    ZQK ? aff + (size_t)(bh % H) * DK : nullptr, (size_t)H * DK,
                                    ZQK ? part + ((size_t)bh * n_seg + seg) * 4 * DK : nullptr, NH ? H * DK : DK,
-                                   NH ? H * DV : DV, p1 - p0, lds, tid, w, lane);
+                                   NH ? H * DV : DV, p1 - p0, lds, tid, w, lane,
+                                   // (a single segment: N tokens, (n_ch - 1) / ckpt_every copies per (b,h) pair)
+                                   (ckpt != nullptr && ckpt_every > 0)
+                                       ? ckpt + (size_t)bh * (size_t)(((N + C - 1) / C - 1) / ckpt_every) * DK * DV
+                                       : nullptr,
+                                   ckpt_every);
 }
 
 // Adds up the workgroups' shares of the parameter gradients: part is [B][H][n_seg][4][DK], out is [4][H][DK].
@@ -1506,7 +1540,7 @@ static hipError_t bwd_impl(const bf16* Q, const bf16* K, const bf16* V, const bf
             ProfScope prof(KID_BWD_SWEEP_BF16, st);
             hipLaunchKernelGGL((bf16_bwd_sweep_kernel<C, DK, DV, ZQK, NH>), grid, dim3(256), 0, st, Q, K, V, dO, dQ, dK,
                                dV, saved, plan.n_seg > 1 ? wsR : nullptr, dS_in, aff, H, wsP, N, plan.seg_len,
-                               plan.n_seg);
+                               plan.n_seg, (float*)nullptr, 0);
             if ((e = hipGetLastError()) != hipSuccess) return e;
         }
         if (ZQK) {
@@ -1518,9 +1552,11 @@ static hipError_t bwd_impl(const bf16* Q, const bf16* K, const bf16* V, const bf
     }
     const bool use_ws = plan.n_seg > 1 || S_in != nullptr || dS_out != nullptr;
     const size_t state_floats = use_ws ? (size_t)BH * plan.n_seg * DK * DV : 0;
+    // a single segment that is long: copies of the running state at the workspace's start (see bwd_sweep_body)
+    const long n_ckpt = use_ws ? 0 : plan_n_ckpt(plan, N);
     float* wsS = ws;
     float* wsR = ws ? ws + state_floats : nullptr;
-    float* wsP = ZQK ? ws + 2 * state_floats : nullptr;
+    float* wsP = ZQK ? ws + (use_ws ? 2 * state_floats : (size_t)BH * n_ckpt * DK * DV) : nullptr;
     if (use_ws) {
         SegStateArgs a{};
         // S^T totals: every segment is needed (inclusive prefix); R^T totals: the first is never used (exclusive suffix)
@@ -1540,7 +1576,7 @@ static hipError_t bwd_impl(const bf16* Q, const bf16* K, const bf16* V, const bf
         ProfScope prof(KID_BWD_SWEEP_BF16, st);
         hipLaunchKernelGGL((bf16_bwd_sweep_kernel<C, DK, DV, ZQK, NH>), grid, dim3(256), 0, st, Q, K, V, dO, dQ, dK, dV,
                            use_ws ? wsS : nullptr, use_ws ? wsR : nullptr, dS_in, aff, H, wsP, N, plan.seg_len,
-                           plan.n_seg);
+                           plan.n_seg, n_ckpt > 0 ? ws : nullptr, n_ckpt > 0 ? plan.ckpt_every : 0);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     if (ZQK) {

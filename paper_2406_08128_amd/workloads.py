@@ -142,6 +142,25 @@ def make_conv_inputs(B: int, d: int, L: int, m: int, seed: int, dtype: str = "bf
     return {"X": x.to(_torch_dtype(dtype)).contiguous(), "w_short": (nw / m).contiguous(), "k_long": k_long}
 
 
+def make_growing_state_inputs(B: int, H: int, N: int, dk: int, dv: int, seed: int, device) -> Dict[str, torch.Tensor]:
+    """Inputs whose running state K^T V grows linearly with the position: {"Q","K","V","dO"}, bf16, drawn ON `device`.
+
+    Recipe: torch.Generator(device).manual_seed(seed); torch.randn in fp32 in the order x_q, x_k, x_v, x_g;
+    Q = (elu(x_q) + 1) / 128, K = (elu(x_k) + 1) / 128 (the positive feature map of the long-sequence workload),
+    V = silu(x_v) (what the activation in front of the values leaves: mean about 0.2, not zero), dO = x_g; cast to
+    bf16 last.  Drawn on the device because the shapes this is for (hundreds of (b,h) pairs times tens of thousands
+    of tokens) would take minutes and tens of GB on the host; tests copy the (b,h) pairs they hand to the oracle back."""
+    g = torch.Generator(device=device)
+    g.manual_seed(seed)
+    def draw(d):
+        return torch.randn(B, H, N, d, generator=g, dtype=torch.float32, device=device)
+    q = ((torch.nn.functional.elu(draw(dk)) + 1.0) / 128.0).to(torch.bfloat16)
+    k = ((torch.nn.functional.elu(draw(dk)) + 1.0) / 128.0).to(torch.bfloat16)
+    v = torch.nn.functional.silu(draw(dv)).to(torch.bfloat16)
+    dO = draw(dv).to(torch.bfloat16)
+    return {"Q": q.contiguous(), "K": k.contiguous(), "V": v.contiguous(), "dO": dO.contiguous()}
+
+
 def to_f64_numpy(t: torch.Tensor):
     """Exact up-cast of an fp32/bf16 tensor to a float64 numpy array (oracle input)."""
     return t.detach().to("cpu").to(torch.float64).numpy()

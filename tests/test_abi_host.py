@@ -255,7 +255,8 @@ def test_workspace_bytes(L):
     # fixed-memory property: the number of segments is set by the GPU, not by N, so the scratch stays bounded
     for n in (1 << 16, 1 << 18, 1 << 20):
         assert w(4, 12, n, 64, 64, 64, 0, 0) <= 64 * state
-        assert w(4, 12, n, 64, 64, 64, 1, 0) <= 2 * 64 * state
+        # (the bf16 backward keeps its segments within 8192 tokens: two states per 8192 tokens and pair, no more)
+        assert 2 * (n // 8192) * state <= w(4, 12, n, 64, 64, 64, 1, 0) <= 2 * max(64, n // 8192) * state
 
 
 def test_planner_stays_within_its_bounds_over_random_shapes(L):
@@ -272,15 +273,38 @@ def test_planner_stays_within_its_bounds_over_random_shapes(L):
             for bwd in (0, 1):
                 chunk = rnd.choice(chunks)
                 ws = w(B, H, N, dk, dv, chunk, bwd, dtype)
+                # (the query covers every call of its kind -- with and without carried states, the training pair --
+                # so it is a whole number of states per pair, at most two arrays of them)
+                per_state = B * H * dk * dv * 4
                 arrays = 2 if (bwd and dtype == 0) else 1
-                per_state = B * H * dk * dv * 4 * arrays
                 assert ws % per_state == 0, (B, H, N, dk, dv, chunk, bwd, dtype, ws)
-                n_seg = max(1, ws // per_state)                    # (no scratch at all: a single segment)
+                n_seg = max(1, ws // (per_state * arrays))         # (no scratch at all: a single segment)
                 smallest_chunk = 32 if dtype == 1 else 64          # what the kernels tile with at the least
                 assert 1 <= n_seg <= (N + smallest_chunk - 1) // smallest_chunk
                 assert n_seg <= 32768                              # segments ride on a secondary grid dimension
-                if B * H >= 256:
-                    assert n_seg == 1
+                if B * H >= 256 and (N <= 8192 or dtype == 1):
+                    assert n_seg == 1                              # (longer bf16 sequences: the backward's walk is capped)
+                if dtype == 0 and not bwd:
+                    # the forward of the training pair cuts at least where its backward will keep a state
+                    tw = L.chela_linattn_train_workspace_bytes(B, H, N, dk, dv, chunk, 0)
+                    sv = L.chela_linattn_saved_bytes(B, H, N, dk, dv, chunk)
+                    assert tw % per_state == 0 and (tw >= sv or sv == per_state)
+
+
+def test_forward_query_covers_the_training_pairs_forward(L):
+    # 96 (b,h) pairs of 16384 tokens: the plain forward plans 5 segments, the forward that saves states for the backward
+    # cuts where the backward will, 16 times per sequence; the one query has to cover both
+    state = 64 * 64 * 4
+    assert L.chela_linattn_train_workspace_bytes(8, 12, 16384, 64, 64, 64, 0) >= 96 * 16 * state
+    assert L.chela_linattn_workspace_bytes(8, 12, 16384, 64, 64, 64, 0, 0) < 96 * 16 * state
+
+
+def test_backward_walk_is_capped(L):
+    # bf16 backward: no segment is longer than 8192 tokens unless the sweep checkpoints its own first pass
+    # (a single segment without carried states): 300 pairs of 65536 tokens need 7 copies each, or, with carried
+    # states, two arrays of 8 segments
+    state = 64 * 64 * 4
+    assert L.chela_linattn_workspace_bytes(300, 1, 65536, 64, 64, 64, 1, 0) == 300 * 2 * 8 * state
 
 
 def test_set_workspace_alignment(L):
