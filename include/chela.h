@@ -35,14 +35,17 @@
  *              stream).  Work is enqueued and the call returns without
  *              synchronising.
  *   Scratch  : per-(b,h)-segment states, chela_linattn_workspace_bytes() bytes.
- *              Taken from the buffer given to chela_set_workspace(), else from
- *              an internal allocation that grows on demand (growing it
+ *              Taken from the buffer the CALLING THREAD gave to
+ *              chela_set_workspace(), else from an allocation of the library's
+ *              own, one per (device, stream), that grows on demand (growing it
  *              synchronises the device) and lives until chela_shutdown().
- *              Calls that may overlap in time on different streams must not
- *              share one workspace: a call's kernels use the buffer that was
- *              in force when the call was made, so a caller with two streams
- *              sets one buffer before the calls on each (the setting itself
- *              is process-wide and guarded by a mutex).
+ *   Threads  : calls may be made from several host threads at once.  Calls that
+ *              may overlap in time must not share scratch: the library's own
+ *              allocations never are shared between streams; a caller-owned
+ *              buffer belongs to the thread that set it, and that thread must
+ *              not use it on two streams whose work may overlap (it sets another
+ *              buffer before the calls on the other stream: a call's kernels
+ *              use the buffer that was in force when the call was made).
  *   Errors   : 0 on success, a negative CHELA_ERR_* otherwise.  Every argument
  *              check is done on the host before the first HIP call, so a
  *              rejected call has touched nothing.  No exceptions, no abort.
@@ -294,9 +297,12 @@ size_t chela_linattn_workspace_bytes(int B, int H, int N, int dk, int dv, int ch
                                      int is_bwd, int dtype);
 
 /* Hand the library a caller-owned device buffer to use as scratch (256-byte
- * aligned).  NULL/0 returns to the internal allocation.  The buffer must stay
- * valid until every call that used it has finished. */
+ * aligned) for the calls THIS host thread makes from now on.  NULL/0 returns the
+ * thread to the library's own allocations.  The buffer must stay valid until
+ * every call that used it has finished.  chela_get_workspace reports the calling
+ * thread's current setting (NULL, 0 if none). */
 int chela_set_workspace(void *dev_ptr, size_t bytes);
+int chela_get_workspace(void **dev_ptr, size_t *bytes);
 
 /* Environment variables read by the library (tuning aids for measurements; results stay within the rounding of any
  * other split, defaults are what the planner picks):
@@ -312,32 +318,6 @@ int chela_version(void);
 
 /* Free the internal workspace (synchronises the device).  Safe to call twice. */
 void chela_shutdown(void);
-
-/* Plain device-to-device copy of `bytes` bytes (a multiple of 16; both pointers 16-byte aligned) done by an
- * ordinary streaming kernel of this library, enqueued on `stream`.  It is the "copy kernel of known size" that
- * hardware byte counters (FETCH_SIZE / WRITE_SIZE) are calibrated against and that gives the copy bandwidth
- * this GPU actually reaches; it is not part of the attention path. */
-int chela_copy_probe(const void *src, void *dst, size_t bytes, void *stream);
-
-/* The same for any mix of streams: `in` and `out` are HOST arrays of n_in (1..4) and n_out (1..4) device pointers,
- * each to `bytes` bytes (a multiple of 16, pointers 16-byte aligned, outputs overlapping nothing).  Thread i reads
- * 16 bytes of every input and writes 16 bytes (derived from what it read) to every output, at offset 16 i rotated by
- * a different amount per array, so that equally spaced allocations do not meet on one memory channel.  What this reaches for, say, four streams in and three out is the bandwidth the GPU delivers for the mix
- * that the backward sweep moves; benchmarks print it next to that kernel's own figure.  Not part of the attention
- * path. */
-int chela_stream_probe(const void *const *in, int n_in, void *const *out, int n_out, size_t bytes, void *stream);
-
-/* ---- per-kernel timing aid (for benchmarks; off by default) -------------------------------------------
- * While enabled, every kernel the library launches is bracketed by two HIP events recorded on the stream
- * the kernel is launched on.  Kernel classes are numbered 0 .. chela_profile_num_kernels()-1.
- * chela_profile_read() waits for the recorded events and returns, for class `id`, how many launches were
- * recorded since the last chela_profile_reset() and their summed duration in milliseconds.
- * Not thread-safe against concurrent launches; returns CHELA_ERR_BAD_SHAPE for an unknown id. */
-int chela_profile_enable(int on);
-int chela_profile_num_kernels(void);
-const char *chela_profile_kernel_name(int id);
-int chela_profile_read(int id, long long *launches, double *total_ms);
-void chela_profile_reset(void);
 
 #ifdef __cplusplus
 }

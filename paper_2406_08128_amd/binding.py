@@ -1,4 +1,4 @@
-"""Thin ctypes binding of libchela.so (see include/chela.h).
+"""Thin ctypes binding of libchela.so (see include/chela.h; measurement aids: include/chela_bench.h).
 
 Argument marshalling only: torch tensors supply device pointers and the current HIP stream; every step of
 the computation runs in the library's kernels.  There is no fallback: if the library is missing or a call
@@ -108,6 +108,8 @@ def lib() -> ctypes.CDLL:
     L.chela_linattn_workspace_bytes.restype = sz
     L.chela_set_workspace.argtypes = [vp, sz]
     L.chela_set_workspace.restype = i
+    L.chela_get_workspace.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(sz)]
+    L.chela_get_workspace.restype = i
     L.chela_status_string.argtypes = [i]
     L.chela_status_string.restype = ctypes.c_char_p
     L.chela_version.argtypes = []

@@ -1,6 +1,7 @@
 // Host side of libchela.so: argument validation, work partitioning, scratch management, dispatch.
 // Every check below runs before the first HIP call so that a rejected call has touched nothing.
 #include "../../include/chela.h"
+#include "../../include/chela_bench.h"
 #include "chela_internal.h"
 #include <cmath>
 
@@ -195,35 +196,50 @@ ProfScope::~ProfScope()
 }
 
 // ------------------------------------------------------------------ scratch
+// Two sources.  A caller-owned buffer, set per HOST THREAD (chela_set_workspace): a thread's calls use what that
+// thread set last, so threads that each drive a stream of their own cannot disturb each other.  Otherwise an
+// allocation of the library's own, one per (device, stream): calls enqueued on different streams may overlap in
+// time and therefore never share scratch; calls on one stream are ordered by the stream.
 static std::mutex g_mu;
-static void* g_user_ws = nullptr;
-static size_t g_user_bytes = 0;
+static thread_local void* t_user_ws = nullptr;
+static thread_local size_t t_user_bytes = 0;
 static constexpr int kMaxDev = 64;
-static void* g_own_ws[kMaxDev] = {nullptr};
-static size_t g_own_bytes[kMaxDev] = {0};
+struct OwnWs { hipStream_t stream; void* ptr; size_t bytes; };
+static std::vector<OwnWs> g_own_ws[kMaxDev];
 
-static int get_workspace(size_t bytes, float** out)
+static int get_workspace(size_t bytes, void* stream, float** out)
 {
     *out = nullptr;
     if (bytes == 0) return CHELA_OK;
-    std::lock_guard<std::mutex> lk(g_mu);
-    if (g_user_ws) {
-        if (bytes > g_user_bytes) return CHELA_ERR_WORKSPACE;
-        *out = (float*)g_user_ws;
+    if (t_user_ws) {
+        if (bytes > t_user_bytes) return CHELA_ERR_WORKSPACE;
+        *out = (float*)t_user_ws;
         return CHELA_OK;
     }
     int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return CHELA_ERR_HIP;
+    if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return CHELA_ERR_HIP; }
     if (dev < 0 || dev >= kMaxDev) return CHELA_ERR_HIP;
-    if (g_own_bytes[dev] < bytes) {
-        if (g_own_ws[dev]) { (void)hipDeviceSynchronize(); (void)hipFree(g_own_ws[dev]); }
-        g_own_ws[dev] = nullptr; g_own_bytes[dev] = 0;
-        size_t want = bytes + bytes / 4;
+    std::lock_guard<std::mutex> lk(g_mu);
+    OwnWs* w = nullptr;
+    for (OwnWs& x : g_own_ws[dev]) if (x.stream == (hipStream_t)stream) { w = &x; break; }
+    if (!w) {
+        if (g_own_ws[dev].size() >= 32) {      // a caller that keeps making streams: start over rather than pile up
+            (void)hipDeviceSynchronize();
+            for (OwnWs& x : g_own_ws[dev]) if (x.ptr) (void)hipFree(x.ptr);
+            g_own_ws[dev].clear();
+        }
+        g_own_ws[dev].push_back(OwnWs{(hipStream_t)stream, nullptr, 0});
+        w = &g_own_ws[dev].back();
+    }
+    if (w->bytes < bytes) {
+        if (w->ptr) { (void)hipDeviceSynchronize(); (void)hipFree(w->ptr); }
+        w->ptr = nullptr; w->bytes = 0;
+        const size_t want = bytes + bytes / 4;
         void* p = nullptr;
         if (hipMalloc(&p, want) != hipSuccess) { (void)hipGetLastError(); return CHELA_ERR_WORKSPACE; }
-        g_own_ws[dev] = p; g_own_bytes[dev] = want;
+        w->ptr = p; w->bytes = want;
     }
-    *out = (float*)g_own_ws[dev];
+    *out = (float*)w->ptr;
     return CHELA_OK;
 }
 
@@ -344,7 +360,7 @@ static int fwd_common(const void* Q, const void* K, const void* V, void* O, cons
         if (plan.ws_bytes > kStaticScratchBytes) return CHELA_ERR_WORKSPACE;
         rc = plan.ws_bytes ? static_scratch(&ws) : CHELA_OK;
     } else {
-        rc = get_workspace(plan.ws_bytes, &ws);
+        rc = get_workspace(plan.ws_bytes, stream, &ws);
     }
     if (rc != CHELA_OK) return rc;
     hipError_t e = dtype == CHELA_DTYPE_BF16
@@ -384,7 +400,7 @@ static int bwd_common(const void* Q, const void* K, const void* V, const void* d
         Plan plan = make_plan(BH, N, dk, dv, bf16_bwd_effective_chunk(dk, dv, chunk), dtype, true,
                               S_in != nullptr || dS_out != nullptr, true);
         float* ws = nullptr;
-        rc = get_workspace(plan.ws_bytes, &ws);
+        rc = get_workspace(plan.ws_bytes, stream, &ws);
         if (rc != CHELA_OK) return rc;
         hipError_t e = launch_bf16_bwd(Q, K, V, dO, S_in, dS_out, dQ, dK, dV, dS_in, nullptr, BH, N, dk, dv, plan, ws, st);
         return e == hipSuccess ? CHELA_OK : CHELA_ERR_HIP;
@@ -398,7 +414,7 @@ static int bwd_common(const void* Q, const void* K, const void* V, const void* d
     Plan p1 = make_plan(BH, N, dv, dk, c1, dtype, true, false);
     Plan p2 = make_plan(BH, N, dk, dv, c2, dtype, true, false);
     float* ws = nullptr;
-    rc = get_workspace(p1.ws_bytes > p2.ws_bytes ? p1.ws_bytes : p2.ws_bytes, &ws);
+    rc = get_workspace(p1.ws_bytes > p2.ws_bytes ? p1.ws_bytes : p2.ws_bytes, stream, &ws);
     if (rc != CHELA_OK) return rc;
     hipError_t e = launch_f32((const float*)dO, (const float*)V, (const float*)K, (float*)dQ, BH, N, dv, dk, p1,
                               false, ws, st);
@@ -434,7 +450,7 @@ static int zfwd_common(const void* Z, const float* aff, const void* V, void* O, 
     if (rc != CHELA_OK || empty) return rc;
     Plan plan = want_saved ? t.fwd : make_plan(BH, N, dk, dv, 64, CHELA_DTYPE_BF16, false, false);
     float* ws = nullptr;
-    rc = get_workspace(plan.ws_bytes, &ws);
+    rc = get_workspace(plan.ws_bytes, stream, &ws);
     if (rc != CHELA_OK) return rc;
     return launch_bf16_zfwd(Z, aff, V, O, want_saved ? (float*)saved : nullptr, want_saved ? t.save_every : 1, B, H, N,
                             dk, dv, plan, ws, (hipStream_t)stream) == hipSuccess ? CHELA_OK : CHELA_ERR_HIP;
@@ -465,7 +481,7 @@ static int zbwd_common(const void* Z, const float* aff, const void* V, const voi
     }
     Plan plan = want_saved ? t.bwd : make_plan(BH, N, dk, dv, 64, CHELA_DTYPE_BF16, true, false, true);
     float* ws = nullptr;
-    rc = get_workspace(plan.ws_bytes + zbwd_extra_ws_bytes(BH, plan, dk), &ws);
+    rc = get_workspace(plan.ws_bytes + zbwd_extra_ws_bytes(BH, plan, dk), stream, &ws);
     if (rc != CHELA_OK) return rc;
     return launch_bf16_zbwd(Z, aff, V, dO, dZ, d_aff, dV, want_saved ? (const float*)saved : nullptr, B, H, N, dk, dv,
                             plan, ws, (hipStream_t)stream) == hipSuccess ? CHELA_OK : CHELA_ERR_HIP;
@@ -487,7 +503,7 @@ static int fwd_save_common(const void* Q, const void* K, const void* V, void* O,
     int rc = validate(in_v, inb, 3, out_v, outb, 2, B, H, N, dk, dv, chunk, CHELA_DTYPE_BF16, &empty);
     if (rc != CHELA_OK || empty) return rc;
     float* ws = nullptr;
-    rc = get_workspace(t.fwd.ws_bytes, &ws);
+    rc = get_workspace(t.fwd.ws_bytes, stream, &ws);
     if (rc != CHELA_OK) return rc;
     return launch_bf16_fwd(Q, K, V, O, nullptr, nullptr, (float*)saved, t.save_every, BH, N, dk, dv, t.fwd, ws,
                            (hipStream_t)stream) == hipSuccess ? CHELA_OK : CHELA_ERR_HIP;
@@ -509,7 +525,7 @@ static int bwd_saved_common(const void* Q, const void* K, const void* V, const v
     int rc = validate(in_v, inb, 5, out_v, outb, 3, B, H, N, dk, dv, chunk, CHELA_DTYPE_BF16, &empty);
     if (rc != CHELA_OK || empty) return rc;
     float* ws = nullptr;
-    rc = get_workspace(t.bwd.ws_bytes, &ws);
+    rc = get_workspace(t.bwd.ws_bytes, stream, &ws);
     if (rc != CHELA_OK) return rc;
     return launch_bf16_bwd(Q, K, V, dO, nullptr, nullptr, dQ, dK, dV, nullptr, (const float*)saved, BH, N, dk, dv,
                            t.bwd, ws, (hipStream_t)stream) == hipSuccess ? CHELA_OK : CHELA_ERR_HIP;
@@ -537,7 +553,7 @@ static int fwd_gated_common(const void* Q, const void* K, const float* aff, bool
     if (rc != CHELA_OK || empty) return rc;
     Plan plan = saved ? t.fwd : make_plan(BH, N, dk, dv, 64, CHELA_DTYPE_BF16, false, false);
     float* ws = nullptr;
-    rc = get_workspace(plan.ws_bytes, &ws);
+    rc = get_workspace(plan.ws_bytes, stream, &ws);
     if (rc != CHELA_OK) return rc;
     return launch_bf16_fwd_gated(Q, K, V, G, O, Y, eps, zqk ? aff : nullptr, (float*)saved, saved ? t.save_every : 1, B,
                                  H, N, dk, dv, plan, ws, (hipStream_t)stream) == hipSuccess ? CHELA_OK : CHELA_ERR_HIP;
@@ -584,7 +600,7 @@ static int bnhd_common(const void* Q, const void* K, const void* V, const void* 
     if (rc != CHELA_OK || empty) return rc;
     Plan plan = make_plan((long)B * H, N, dk, dv, 64, CHELA_DTYPE_BF16, is_bwd, false, true);
     float* ws = nullptr;
-    rc = get_workspace(plan.ws_bytes, &ws);
+    rc = get_workspace(plan.ws_bytes, stream, &ws);
     if (rc != CHELA_OK) return rc;
     hipError_t e = is_bwd ? launch_bf16_bwd_nh(Q, K, V, dO, O_or_dQ, dK, dV, B, H, N, dk, dv, plan, ws, (hipStream_t)stream)
                           : launch_bf16_fwd_nh(Q, K, V, O_or_dQ, B, H, N, dk, dv, plan, ws, (hipStream_t)stream);
@@ -605,7 +621,7 @@ static int noncausal_common(const void* Q, const void* K, const void* V, const v
     const long BH = (long)B * H;
     Plan plan = make_noncausal_plan(BH, N, dk, dv, is_bwd);
     float* ws = nullptr;
-    rc = get_workspace(plan.ws_bytes, &ws);
+    rc = get_workspace(plan.ws_bytes, stream, &ws);
     if (rc != CHELA_OK) return rc;
     hipError_t e = is_bwd ? launch_bf16_noncausal_bwd(Q, K, V, dO, O_or_dQ, dK, dV, BH, N, dk, dv, plan, ws,
                                                       (hipStream_t)stream)
@@ -629,7 +645,7 @@ static int noncausal_gated_common(const void* Q, const void* K, const void* V, c
     const long BH = (long)B * H;
     Plan plan = make_noncausal_plan(BH, N, dk, dv, false);
     float* ws = nullptr;
-    rc = get_workspace(plan.ws_bytes, &ws);
+    rc = get_workspace(plan.ws_bytes, stream, &ws);
     if (rc != CHELA_OK) return rc;
     return launch_bf16_noncausal_fwd(Q, K, V, O, BH, N, dk, dv, plan, ws, (hipStream_t)stream, G, Y, eps) == hipSuccess
                ? CHELA_OK : CHELA_ERR_HIP;
@@ -901,7 +917,7 @@ static int shortlong_bwd_common(const void* X, const float* w_short, int m, cons
         for (int o2 = o + 1; o2 < 3; ++o2) if (overlap(out[o], out[o2])) return CHELA_ERR_ALIASING;
     }
     float* ws = nullptr;
-    int rc = get_workspace(conv_bwd_ws_bytes(B, d, L, dtype, w_short != nullptr), &ws);
+    int rc = get_workspace(conv_bwd_ws_bytes(B, d, L, dtype, w_short != nullptr), stream, &ws);
     if (rc != CHELA_OK) return rc;
     return launch_shortlong_conv_bwd(X, w_short, m, spectrum, dZ, dX, d_w_short, d_k_long, ws, B, d, L,
                                      dtype == CHELA_DTYPE_BF16 ? 0 : 1, st) == hipSuccess ? CHELA_OK : CHELA_ERR_HIP;
@@ -990,10 +1006,16 @@ size_t chela_linattn_train_workspace_bytes(int B, int H, int N, int dk, int dv, 
 
 int chela_set_workspace(void* dev_ptr, size_t bytes)
 {
-    std::lock_guard<std::mutex> lk(g_mu);
-    if (dev_ptr == nullptr || bytes == 0) { g_user_ws = nullptr; g_user_bytes = 0; return CHELA_OK; }
+    if (dev_ptr == nullptr || bytes == 0) { t_user_ws = nullptr; t_user_bytes = 0; return CHELA_OK; }
     if ((uintptr_t)dev_ptr & 255u) return CHELA_ERR_MISALIGNED;
-    g_user_ws = dev_ptr; g_user_bytes = bytes;
+    t_user_ws = dev_ptr; t_user_bytes = bytes;
+    return CHELA_OK;
+}
+
+int chela_get_workspace(void** dev_ptr, size_t* bytes)
+{
+    if (!dev_ptr || !bytes) return CHELA_ERR_NULL_POINTER;
+    *dev_ptr = t_user_ws; *bytes = t_user_bytes;
     return CHELA_OK;
 }
 
@@ -1080,10 +1102,13 @@ void chela_shutdown(void)
     int cur = 0;
     bool have_cur = false;
     for (int d = 0; d < kMaxDev; ++d) {
-        if (!g_own_ws[d]) continue;
+        if (g_own_ws[d].empty()) continue;
         if (!have_cur) { have_cur = (hipGetDevice(&cur) == hipSuccess); }
-        if (hipSetDevice(d) == hipSuccess) { (void)hipDeviceSynchronize(); (void)hipFree(g_own_ws[d]); }
-        g_own_ws[d] = nullptr; g_own_bytes[d] = 0;
+        if (hipSetDevice(d) == hipSuccess) {
+            (void)hipDeviceSynchronize();
+            for (OwnWs& w : g_own_ws[d]) if (w.ptr) (void)hipFree(w.ptr);
+        }
+        g_own_ws[d].clear();
     }
     if (have_cur) (void)hipSetDevice(cur);
 }

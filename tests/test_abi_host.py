@@ -7,7 +7,7 @@ import re
 import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-HEADER = os.path.join(ROOT, "include", "chela.h")
+HEADERS = [os.path.join(ROOT, "include", h) for h in ("chela.h", "chela_bench.h")]
 
 
 @pytest.fixture(scope="module")
@@ -20,7 +20,7 @@ def L():
 
 
 def _declared_symbols():
-    text = open(HEADER).read()
+    text = "".join(open(h).read() for h in HEADERS)
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(chela_[a-z0-9_]+)\s*\(", text)))
 
@@ -305,6 +305,54 @@ def test_backward_walk_is_capped(L):
     # states, two arrays of 8 segments
     state = 64 * 64 * 4
     assert L.chela_linattn_workspace_bytes(300, 1, 65536, 64, 64, 64, 1, 0) == 300 * 2 * 8 * state
+
+
+def test_the_method_header_declares_no_measurement_aid():
+    text = re.sub(r"/\*.*?\*/", "", open(HEADERS[0]).read(), flags=re.S)
+    assert "chela_copy_probe" not in text and "chela_stream_probe" not in text and "chela_profile_" not in text
+    bench = re.sub(r"/\*.*?\*/", "", open(HEADERS[1]).read(), flags=re.S)
+    assert "chela_linattn" not in bench
+
+
+def test_caller_scratch_is_per_host_thread(L):
+    # every thread sets a buffer of its own (fake, aligned addresses: nothing is ever dereferenced) and must keep
+    # seeing it while the others set and reset theirs
+    import threading
+    L.chela_get_workspace.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.POINTER(ctypes.c_size_t)]
+    L.chela_get_workspace.restype = ctypes.c_int
+    L.chela_set_workspace.argtypes = [ctypes.c_void_p, ctypes.c_size_t]
+    errors = []
+    barrier = threading.Barrier(8)
+
+    def worker(k):
+        mine, size = 0x100000 * (k + 1), 4096 * (k + 1)
+        p, n = ctypes.c_void_p(), ctypes.c_size_t()
+        barrier.wait()
+        for it in range(2000):
+            if L.chela_set_workspace(mine, size) != 0:
+                errors.append((k, "set"))
+            L.chela_get_workspace(ctypes.byref(p), ctypes.byref(n))
+            if p.value != mine or n.value != size:
+                errors.append((k, it, p.value, n.value))
+            # a problem that needs more scratch than this thread's buffer holds is refused on this thread's account
+            if _fwd(L, B=4, H=12, N=16384) != -7:
+                errors.append((k, it, "not refused"))
+            if it % 3 == k % 3:
+                L.chela_set_workspace(None, 0)
+                L.chela_get_workspace(ctypes.byref(p), ctypes.byref(n))
+                if p.value is not None or n.value != 0:
+                    errors.append((k, it, "reset", p.value, n.value))
+        L.chela_set_workspace(None, 0)
+
+    threads = [threading.Thread(target=worker, args=(k,)) for k in range(8)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors[:5]
+    # the main thread never set one
+    p, n = ctypes.c_void_p(), ctypes.c_size_t()
+    assert L.chela_get_workspace(ctypes.byref(p), ctypes.byref(n)) == 0 and p.value is None and n.value == 0
 
 
 def test_set_workspace_alignment(L):

@@ -394,6 +394,54 @@ def test_two_streams_with_a_scratch_buffer_each():
         binding.chela_set_workspace(None)
 
 
+def test_two_host_threads_with_a_stream_and_scratch_each():
+    # two host threads, each with its own stream; thread 0 brings its own scratch buffer, thread 1 leaves the scratch
+    # to the library (whose allocations are per stream): the calls of the two overlap in time and never share scratch
+    import threading
+    ws = [_small("bf16", N=6000, B=2, H=3, seed=43), _small("bf16", N=9000, B=1, H=4, seed=44)]
+    ds = [_dev(make_inputs(w)) for w in ws]
+    refs = [(binding.chela_linattn_fwd(d["Q"], d["K"], d["V"]),) + tuple(
+        binding.chela_linattn_bwd(d["Q"], d["K"], d["V"], d["dO"])) for d in ds]
+    need = max(binding.chela_linattn_workspace_bytes(ws[0].B, ws[0].H, ws[0].N, 64, 64, 64, bwd, binding.DTYPE_BF16)
+               for bwd in (False, True))
+    buf = torch.empty(need, dtype=torch.uint8, device="cuda")
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    torch.cuda.synchronize()
+    results, errors = [[], []], []
+    barrier = threading.Barrier(2)
+
+    def worker(k):
+        try:
+            torch.cuda.set_device(0)
+            if k == 0:
+                binding.chela_set_workspace(buf)
+            d = ds[k]
+            barrier.wait()
+            with torch.cuda.stream(streams[k]):
+                for rep in range(6):
+                    results[k].append((binding.chela_linattn_fwd(d["Q"], d["K"], d["V"]),)
+                                      + tuple(binding.chela_linattn_bwd(d["Q"], d["K"], d["V"], d["dO"])))
+            streams[k].synchronize()
+        except Exception as e:            # noqa: BLE001 -- reported by the main thread
+            errors.append((k, repr(e)))
+        finally:
+            if k == 0:
+                binding.chela_set_workspace(None)
+
+    threads = [threading.Thread(target=worker, args=(k,)) for k in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    torch.cuda.synchronize()
+    assert not errors, errors
+    for k in range(2):
+        assert len(results[k]) == 6
+        for got in results[k]:
+            for x, y in zip(got, refs[k]):
+                assert torch.equal(x, y)
+
+
 def test_more_heads_than_a_grid_dimension_holds():
     # 70 000 (b,h) pairs: more than the 65 535 a secondary grid dimension can carry
     B, H, N, d = 1, 70000, 64, 64
