@@ -21,10 +21,12 @@ _lib = None
 def _load():
     global _lib
     if _lib is None:
-        if not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(
-                os.path.join(os.path.dirname(_LIB), "chela_oracle.c")):
+        # CHELA_ORACLE_LIB: another build of the same source to load instead (the sanitizer build of the test tier)
+        path = os.environ.get("CHELA_ORACLE_LIB") or _LIB
+        if path == _LIB and (not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(
+                os.path.join(os.path.dirname(_LIB), "chela_oracle.c"))):
             _build(force=True)
-        _lib = ctypes.CDLL(_LIB)
+        _lib = ctypes.CDLL(path)
         dp = ctypes.POINTER(ctypes.c_double)
         i = ctypes.c_int
         for name in ("chela_oracle_fwd_quadratic", "chela_oracle_fwd_recurrent"):

@@ -30,10 +30,12 @@ def lib() -> ctypes.CDLL:
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(LIB_PATH):
+    # CHELA_LIB: another build of the same library to load instead of the in-tree one (the sanitizer tier of the tests)
+    path = os.environ.get("CHELA_LIB") or LIB_PATH
+    if not os.path.exists(path):
         raise FileNotFoundError(
-            "%s not found: build it with `python -m paper_2406_08128_amd.build` (there is no CPU fallback)" % LIB_PATH)
-    L = ctypes.CDLL(LIB_PATH)
+            "%s not found: build it with `python -m paper_2406_08128_amd.build` (there is no CPU fallback)" % path)
+    L = ctypes.CDLL(path)
     vp, i, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
     for name in ("chela_linattn_fwd", "chela_linattn_fwd_f32", "chela_linattn_fwd_noalloc"):
         f = getattr(L, name)

@@ -45,6 +45,31 @@ def build(verbose: bool = True) -> str:
     return LIB
 
 
+def build_host_ubsan(verbose: bool = False) -> str:
+    """libchela with the HOST half of the API file (argument checks, planner, scratch bookkeeping) compiled under
+    UndefinedBehaviorSanitizer in trap mode: undefined behaviour stops the process, and no sanitizer runtime has to be
+    loaded.  The kernels' objects are the ordinary ones (built first if they are missing).  For the CPU test tier only:
+    the result lives in the build folder and is never what the binding loads by default."""
+    objs = [os.path.join(OBJ_DIR, os.path.splitext(src)[0] + ".o") for src in SOURCES]
+    if not all(os.path.exists(o) for o in objs):
+        build(verbose=False)
+    api_obj = os.path.join(OBJ_DIR, "chela_api_ubsan.o")
+    san = ["-Xarch_host", "-fsanitize=undefined", "-Xarch_host", "-fsanitize-trap=undefined",
+           "-Xarch_host", "-fno-sanitize-recover=undefined"]
+    cmd = [HIPCC, *[f for f in FLAGS if f != "-O3"], "-O1", *san, "-c", os.path.join(CSRC, "chela_api.hip"), "-o", api_obj]
+    r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc (host UBSan) failed:\n" + r.stdout)
+    lib = os.path.join(OBJ_DIR, "libchela_ubsan.so")
+    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, api_obj, *objs[1:]]
+    r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("link failed:\n" + r.stdout)
+    if verbose:
+        print("built", lib)
+    return lib
+
+
 if __name__ == "__main__":
     build()
     sys.exit(0)

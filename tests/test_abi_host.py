@@ -368,6 +368,7 @@ def test_shutdown_is_idempotent(L):
 def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
     from paper_2406_08128_amd import binding
     monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.delenv("CHELA_LIB", raising=False)
     monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "nope.so"))
     with pytest.raises(FileNotFoundError):
         binding.lib()
