@@ -33,15 +33,33 @@ def flops_per_token_head(dk, dv, C):
     return 2 * C * (dk + dv) + 4 * dk * dv, 6 * C * dk + 4 * C * dv + 10 * dk * dv
 
 
-def read_traffic(path):
-    """HBM bytes per launch of the dominant kernel as measured by rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE),
-    taken from a committed profile summary; None if the summary is absent."""
+def read_profile(path, sources_hash):
+    """The `key: value` lines of a committed rocprofv3 summary (profiles/*.txt, written by
+    paper_2406_08128_amd/profile_summary.py) and where they come from.  Counter figures cannot be measured by an
+    ordinary run, so the line quotes the committed ones -- but only while the summary was taken on the kernel
+    sources this tree holds (its kernel_sources_sha256 equals the tree's) and, where the repository's history is at
+    hand, its commit is an ancestor of HEAD.  Returns (values or None, source description)."""
+    src = {"file": os.path.relpath(path, ROOT)}
     try:
         txt = open(path).read()
     except OSError:
-        return None
-    m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", txt, flags=re.M)
-    return float(m.group(1)) if m else None
+        src["status"] = "absent"
+        return None, src
+    kv = dict(re.findall(r"^([A-Za-z_][A-Za-z0-9_\[\]]*):\s*(.+?)\s*$", txt, flags=re.M))
+    src["commit"] = kv.get("commit", "unknown").split()[0]
+    src["kernel_sources_sha256"] = kv.get("kernel_sources_sha256", "unknown")
+    if src["kernel_sources_sha256"] != sources_hash:
+        src["status"] = "stale: taken on other kernel sources than this tree's (%s); not quoted" % sources_hash
+        return None, src
+    if os.path.isdir(os.path.join(ROOT, ".git")) and re.fullmatch(r"[0-9a-f]{40}", src["commit"]):
+        import subprocess
+        r = subprocess.run(["git", "-C", ROOT, "merge-base", "--is-ancestor", src["commit"], "HEAD"],
+                           stdout=subprocess.DEVNULL, stderr=subprocess.DEVNULL)
+        if r.returncode != 0:
+            src["status"] = "stale: its commit is not an ancestor of HEAD; not quoted"
+            return None, src
+    src["status"] = "current"
+    return kv, src
 
 
 def bench_decode(args, w, torch, binding):
@@ -226,6 +244,7 @@ def main():
                     help="also run the library's plain copy kernel on a buffer of this many MiB (3 launches): the "
                          "kernel of known size that rocprofv3 byte counters are calibrated against")
     ap.add_argument("--traffic-file", default=os.path.join(ROOT, "profiles", "bwd_sweep_lm_bf16_pmc.txt"))
+    ap.add_argument("--mfma-file", default=os.path.join(ROOT, "profiles", "mfma_counters_lm_bf16.txt"))
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU (one MI355X per box); --gpus %d is not supported. "
@@ -445,11 +464,28 @@ def main():
         dom, dom_b = "bf16_fwd_sweep_kernel", fwd_b
     dom_us = kernels[dom]["avg_us"]
     achieved = dom_b * th / (dom_us * 1e-6) / 1e9
-    traffic = read_traffic(args.traffic_file) if (args.workload == "lm_bf16" and chunk == 64 and w.dtype == "bf16"
-                                                  and args.mode == "train") else None
+    sources_hash = binding.kernel_sources_sha256()
+    headline = args.workload == "lm_bf16" and chunk == 64 and w.dtype == "bf16" and args.mode == "train"
+    traffic, traffic_src, mfma_counted = None, None, None
+    if headline:
+        # counters of the dominant kernel, from the committed summaries of rocprofv3 --pmc runs of this same command
+        kv, traffic_src = read_profile(args.traffic_file, sources_hash)
+        if kv and "traffic_bytes_per_launch" in kv:
+            traffic = float(kv["traffic_bytes_per_launch"])
+        kv, mfma_src = read_profile(args.mfma_file, sources_hash)
+        mfma_counted = {"source": mfma_src}
+        if kv and "mfma_flop_per_launch" in kv:
+            fl = float(kv["mfma_flop_per_launch"])
+            mfma_counted.update({"flop_per_launch": fl, "TFLOPs": round(fl / (dom_us * 1e-6) / 1e12, 1),
+                                 "frac_of_peak": round(fl / (dom_us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+                                 "pipe_busy_frac": float(kv["mfma_busy_frac"]) if "mfma_busy_frac" in kv else None})
     roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "algorithmic_bytes_per_launch": dom_b * th, "avg_launch_us": round(dom_us, 2)}
+    if traffic_src is not None:
+        roofline["traffic_source"] = traffic_src
+    if mfma_counted is not None:
+        roofline["mfma_counted"] = mfma_counted
     # What the GPU delivers for the dominant kernel's mix of streams when nothing but streaming is asked of it: the
     # library's plain grid-stride kernel on as many read and written arrays, of the same total size.
     if dom == "bf16_bwd_sweep_kernel":
@@ -482,6 +518,47 @@ def main():
     roofline["stream_mix"] = {"reads": n_rd, "writes": n_wr, "bytes_per_launch": each * (n_rd + n_wr),
                               "avg_launch_us": round(sp_us, 2), "GB/s": round(sp_gbs, 1)}
     roofline["frac_of_stream_mix"] = round(achieved / sp_gbs, 4)
+    # The matrix rate the GPU delivers when nothing but matrix instructions are asked of it (registers only).
+    mf_blocks, mf_iters = 256 * 8, 4096
+    mf_out = torch.empty(mf_blocks * 256, dtype=torch.float32, device="cuda")
+    for _ in range(2):
+        binding.chela_mfma_probe(mf_out, mf_blocks, mf_iters)
+    torch.cuda.synchronize()
+    binding.chela_profile_reset()
+    binding.chela_profile_enable(True)
+    for _ in range(5):
+        mf_flop = binding.chela_mfma_probe(mf_out, mf_blocks, mf_iters)
+    torch.cuda.synchronize()
+    mp = binding.chela_profile_read()["mfma_probe_kernel"]
+    binding.chela_profile_enable(False)
+    binding.chela_profile_reset()
+    del mf_out
+    mfma_measured = mf_flop / (mp[1] / mp[0] * 1e-3) / 1e12
+    measured_peaks = {"mfma_bf16_TFLOPs": round(mfma_measured, 1),
+                      "mfma_bf16_frac_of_published": round(mfma_measured / MFMA_BF16_PEAK_TFLOPS, 4),
+                      "stream_mix_GBs": round(sp_gbs, 1),
+                      "note": "plain kernels of this library: matrix instructions on registers only; a grid-stride "
+                              "stream over as many read and written arrays as the dominant kernel moves"}
+
+    # Forward and backward on their own (outside the region `value` is computed from).
+    phases = None
+    if has_bwd and args.mode == "train" and not args.graph:
+        def time_loop(fn):
+            for _ in range(max(2, args.warmup // 2)):
+                fn()
+            torch.cuda.synchronize()
+            a = time.perf_counter()
+            for _ in range(args.steps):
+                fn()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - a) * 1e3 / args.steps
+        f_ms = time_loop(lambda: binding.chela_linattn_fwd(d["Q"], d["K"], d["V"], O=O, chunk=chunk))
+        b_ms = time_loop(lambda: binding.chela_linattn_bwd(d["Q"], d["K"], d["V"], d["dO"], dQ=dQ, dK=dK, dV=dV,
+                                                           chunk=chunk))
+        phases = {"fwd_ms": round(f_ms, 4), "bwd_ms": round(b_ms, 4),
+                  "note": "each call timed in a loop of its own: what a kernel finds in the memory-side cache "
+                          "differs from the alternating step, so the two need not add up to ms_per_step"}
+
     step_bytes = (fwd_b + (bwd_b if has_bwd else 0)) * th
     step_flops = (fwd_f + (bwd_f if has_bwd else 0)) * th
     whole = {"hbm_GBs_algorithmic": round(step_bytes / (ms_per_step * 1e-3) / 1e9, 1),
@@ -489,9 +566,22 @@ def main():
              "mfma_TFLOPs_full_tile_model": round(step_flops / (ms_per_step * 1e-3) / 1e12, 1),
              "mfma_frac": round(step_flops / (ms_per_step * 1e-3) / 1e12
                                 / (MFMA_BF16_PEAK_TFLOPS if w.dtype == "bf16" else MFMA_F32_PEAK_TFLOPS), 4)}
+    if w.dtype == "bf16":
+        whole["mfma_frac_of_measured_peak"] = round(step_flops / (ms_per_step * 1e-3) / 1e12 / mfma_measured, 4)
+    whole["hbm_frac_of_stream_mix"] = round(step_bytes / (ms_per_step * 1e-3) / 1e9 / sp_gbs, 4)
+    target = None
+    if headline:
+        target = {"north_star": ">= 50 % of peak bf16 MFMA at B4 H12 N16384 d64, as shown by rocprof",
+                  "met": False,
+                  "mfma_frac_whole_step_full_tile_model": whole["mfma_frac"],
+                  "mfma_frac_dominant_kernel_counted": (mfma_counted or {}).get("frac_of_peak"),
+                  "why": "the path is HBM-bound: 1408 B and 114688 FLOP per token-head at chunk 64 = 81 FLOP/B against "
+                         "a ridge of 312 FLOP/B; even at the 8 TB/s floor (138 us per step) chunk 64 would be 26 % of "
+                         "peak.  The primary roofline is the HBM one (roofline.frac, whole_step.hbm_frac)."}
 
     cpu = None
     cpu_reps = 1
+    parity_rel_l2 = None
     if not args.no_cpu_baseline:
         import oracle
         if args.mode in ("nc_gated", "nc_gated_unfused"):
@@ -546,6 +636,21 @@ def main():
                 c1 = time.perf_counter()
                 if c1 - c0 >= 1.0 or cpu_reps >= 8:
                     break
+        if args.mode == "train" and w.dtype in ("bf16", "f32"):
+            # rel-L2 of every output against the oracle on a sample of (b,h) pairs (outside every timed region)
+            O_s = binding.chela_linattn_fwd(d["Q"], d["K"], d["V"], chunk=chunk)
+            outs = [O_s] + (list(binding.chela_linattn_bwd(d["Q"], d["K"], d["V"], d["dO"], chunk=chunk)) if has_bwd else [])
+            torch.cuda.synchronize()
+            bh = w.B * w.H
+            pick = sorted({0, bh // 3, bh - 1})
+            sel = lambda t: t.reshape(1, bh, w.N, -1)[:, pick]
+            Qs, Ks, Vs = (to_f64_numpy(sel(x[n])) for n in ("Q", "K", "V"))
+            refs = [oracle.fwd_recurrent(Qs, Ks, Vs)]
+            if has_bwd:
+                refs += list(oracle.bwd_recurrent(Qs, Ks, Vs, to_f64_numpy(sel(x["dO"]))))
+            parity_rel_l2 = {n: float("%.3e" % oracle.rel_l2(to_f64_numpy(sel(g)), r))
+                             for n, g, r in zip(("O", "dQ", "dK", "dV"), outs, refs)}
+            parity_rel_l2["sample"] = "(b,h) pairs %s of %d, every token; bar %s" % (pick, bh, "2e-2" if w.dtype == "bf16" else "1e-5")
         cpu = {"value": round(cpu_reps * w.tokens / (c1 - c0), 1), "unit": "tokens/s", "cores": oracle.num_threads(),
                "kind": "oracle", "seconds": round(c1 - c0, 3),
                "cpu_seconds": round((c1 - c0) * oracle.num_threads(), 1),       # wall time x threads: the CPU work done
@@ -583,9 +688,17 @@ def main():
                    "tokens_per_step": w.tokens, "token_heads_per_step": th},
         "roofline": roofline,
         "whole_step": whole,
+        "measured_peaks": measured_peaks,
         "kernels": {k: {"launches": v["launches"], "avg_us": round(v["avg_us"], 2)} for k, v in kernels.items()},
         "cpu_baseline": cpu,
+        "build": {"kernel_sources_sha256": sources_hash},
     }
+    if phases is not None:
+        out["phases"] = phases
+    if parity_rel_l2 is not None:
+        out["parity_rel_l2"] = parity_rel_l2
+    if target is not None:
+        out["target"] = target
     print(json.dumps(out))
 
 

@@ -308,7 +308,9 @@ int chela_get_workspace(void **dev_ptr, size_t *bytes);
  * other split, defaults are what the planner picks):
  *   CHELA_SEG_TOKENS=n   force segments of n tokens (rounded up to whole chunks) in the causal calls
  *   CHELA_NC_SEGS=n      force n segments per (b,h) in the non-causal pre-pass
- *   CHELA_PREPASS_REV=0  walk the forward pre-pass front to back instead of back to front */
+ *   CHELA_PREPASS_REV=0  walk the forward pre-pass front to back instead of back to front
+ *   CHELA_FOLD_SCAN=0    always scan the segment totals in a kernel of its own (by default the sweep's workgroups add
+ *                        them up themselves when the states of one sequence's segments come to at most 256 KB) */
 
 /* Human-readable name of a status code (static storage, never NULL). */
 const char *chela_status_string(int status);

@@ -27,6 +27,13 @@ int chela_copy_probe(const void *src, void *dst, size_t bytes, void *stream);
  * path. */
 int chela_stream_probe(const void *const *in, int n_in, void *const *out, int n_out, size_t bytes, void *stream);
 
+/* Matrix-core rate probe: `blocks` workgroups of four waves, each wave issuing iters * 16 bf16 matrix instructions
+ * (v_mfma_f32_32x32x16_bf16, 32768 FLOP each) on registers, four independent accumulator tiles per wave so that no
+ * instruction waits for another; nothing is read from memory.  `out` receives blocks * 256 floats (16-byte aligned).
+ * FLOP of one launch = blocks * 4 * iters * 16 * 32768; divided by the launch's duration it is the matrix rate this GPU
+ * delivers at the clock it runs at, to set beside the published 2.5 PFLOP/s. */
+int chela_mfma_probe(float *out, int blocks, int iters, void *stream);
+
 /* ---- per-kernel timing aid (for benchmarks; off by default) -------------------------------------------
  * While enabled, every kernel the library launches is bracketed by two HIP events recorded on the stream
  * the kernel is launched on.  Kernel classes are numbered 0 .. chela_profile_num_kernels()-1.

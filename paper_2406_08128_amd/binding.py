@@ -122,6 +122,8 @@ def lib() -> ctypes.CDLL:
     L.chela_copy_probe.restype = i
     L.chela_stream_probe.argtypes = [ctypes.POINTER(vp), i, ctypes.POINTER(vp), i, sz, vp]
     L.chela_stream_probe.restype = i
+    L.chela_mfma_probe.argtypes = [vp, i, i, vp]
+    L.chela_mfma_probe.restype = i
     L.chela_profile_enable.argtypes = [i]
     L.chela_profile_enable.restype = i
     L.chela_profile_num_kernels.argtypes = []
@@ -665,6 +667,28 @@ def chela_stream_probe(inputs, outputs, stream=None) -> None:
     ins = (ctypes.c_void_p * max(len(inputs), 1))(*[t.data_ptr() for t in inputs])
     outs = (ctypes.c_void_p * max(len(outputs), 1))(*[t.data_ptr() for t in outputs])
     _check(lib().chela_stream_probe(ins, len(inputs), outs, len(outputs), nbytes, _stream_ptr(stream)))
+
+
+def chela_mfma_probe(out: torch.Tensor, blocks: int, iters: int, stream=None) -> int:
+    """Matrix-core rate probe (registers only); `out`: at least blocks * 256 floats.  Returns the FLOP of the launch."""
+    if out.dtype != torch.float32 or not out.is_cuda or out.numel() < blocks * 256:
+        raise ValueError("out must be a float32 device tensor of at least blocks * 256 elements")
+    _check(lib().chela_mfma_probe(out.data_ptr(), int(blocks), int(iters), _stream_ptr(stream)))
+    return blocks * 4 * iters * 16 * 32768
+
+
+def kernel_sources_sha256() -> str:
+    """Hash of the sources the library is built from (csrc/*, in name order): what a committed profile summary was
+    taken on is compared with what the tree holds now."""
+    import hashlib
+    h = hashlib.sha256()
+    d = os.path.join(_HERE, "csrc")
+    for name in sorted(os.listdir(d)):
+        if name.endswith((".hip", ".h")):
+            h.update(name.encode())
+            with open(os.path.join(d, name), "rb") as f:
+                h.update(f.read())
+    return h.hexdigest()[:16]
 
 
 def chela_profile_enable(on: bool) -> None:

@@ -176,7 +176,7 @@ static const char* const kKernelNames[KID_COUNT] = {
     "bf16_seg_state_kernel", "scan_states_kernel", "bf16_fwd_sweep_kernel", "bf16_bwd_sweep_kernel",
     "f32_seg_state_kernel", "f32_sweep_kernel", "copy_probe_kernel", "bf16_step_kernel", "affine_grad_kernel",
     "bf16_apply_state_kernel", "longconv_spectrum_kernel", "shortlong_conv_kernel",
-    "shortconv_bwd_kernel", "longconv_bwd_kernel", "gate_norm_kernel", "stream_probe_kernel"};
+    "shortconv_bwd_kernel", "longconv_bwd_kernel", "gate_norm_kernel", "stream_probe_kernel", "mfma_probe_kernel"};
 
 ProfScope::ProfScope(int id, hipStream_t s) : slot(-1), st(s)
 {
@@ -1066,6 +1066,15 @@ int chela_stream_probe(const void* const* in, int n_in, void* const* out, int n_
             if (overlap(ro, Range{(const char*)out[j], bytes})) return CHELA_ERR_ALIASING;
     }
     return launch_stream_probe(in, n_in, out, n_out, bytes, (hipStream_t)stream) == hipSuccess ? CHELA_OK : CHELA_ERR_HIP;
+}
+
+int chela_mfma_probe(float* out, int blocks, int iters, void* stream)
+{
+    if (blocks < 0 || iters < 0 || blocks > (1 << 20) || iters > (1 << 24)) return CHELA_ERR_BAD_SHAPE;
+    if (blocks == 0) return CHELA_OK;
+    if (!out) return CHELA_ERR_NULL_POINTER;
+    if ((uintptr_t)out & 15u) return CHELA_ERR_MISALIGNED;
+    return launch_mfma_probe(out, blocks, iters, (hipStream_t)stream) == hipSuccess ? CHELA_OK : CHELA_ERR_HIP;
 }
 
 int chela_profile_enable(int on) { g_prof_on = (on != 0); return CHELA_OK; }

@@ -48,6 +48,8 @@ hipError_t launch_copy(const void* src, void* dst, size_t bytes, hipStream_t st)
 hipError_t launch_zero_fill(float* p, size_t n_floats, hipStream_t st);      // a fill kernel, not a memset node
 hipError_t launch_stream_probe(const void* const* in, int n_in, void* const* out, int n_out, size_t bytes,
                                hipStream_t st);
+// Matrix-core rate probe: blocks * 4 waves, each issuing iters * 16 bf16 32x32x16 matrix instructions; out: blocks * 256 floats.
+hipError_t launch_mfma_probe(float* out, int blocks, int iters, hipStream_t st);
 
 // fp32 path.  `rev` runs the same map on the time-reversed sequence (anti-causal mask), which is what the
 // gradient with respect to K and V is (the backward is three calls of this launcher).
@@ -143,7 +145,7 @@ hipError_t launch_shortlong_conv_bwd(const void* X, const float* w_short, int m,
 
 // Kernel classes for the per-kernel timing aid.
 enum { KID_SEG_STATE_BF16 = 0, KID_SCAN = 1, KID_FWD_SWEEP_BF16 = 2, KID_BWD_SWEEP_BF16 = 3, KID_SEG_STATE_F32 = 4,
-       KID_SWEEP_F32 = 5, KID_COPY = 6, KID_STEP_BF16 = 7, KID_AFFINE_GRAD = 8, KID_APPLY_BF16 = 9, KID_CONV_SPECTRUM = 10, KID_CONV_FWD = 11, KID_CONV_SHORT_BWD = 12, KID_CONV_LONG_BWD = 13, KID_GATE_NORM = 14, KID_STREAM_PROBE = 15, KID_COUNT = 16 };
+       KID_SWEEP_F32 = 5, KID_COPY = 6, KID_STEP_BF16 = 7, KID_AFFINE_GRAD = 8, KID_APPLY_BF16 = 9, KID_CONV_SPECTRUM = 10, KID_CONV_FWD = 11, KID_CONV_SHORT_BWD = 12, KID_CONV_LONG_BWD = 13, KID_GATE_NORM = 14, KID_STREAM_PROBE = 15, KID_MFMA_PROBE = 16, KID_COUNT = 17 };
 
 // Brackets one kernel launch with HIP events on its stream while profiling is enabled; otherwise does nothing.
 struct ProfScope {

@@ -340,6 +340,46 @@ __device__ __forceinline__ void load_state(f32x16* acc, const float* src, int w,
     }
 }
 
+// The same for the sum of `count` states that lie one behind the other at src (count == 0 or src == nullptr: zero):
+// a workgroup that adds up the segment totals in front of (or behind) its own segment itself, in a fixed order,
+// instead of reading what a scan kernel left.  The loads of two states are in flight at a time.
+template <int DA, int DB, bool NEG>
+__device__ __forceinline__ void sum_states(f32x16* acc, const float* src, int count, int w, int lane)
+{
+    constexpr int BB = DB / 32, NT = (DA / 32) * BB / 4;
+    constexpr int U = 4;                 // states whose loads are in flight together
+    const int r = lane & 31, h = lane >> 5;
+    if (src == nullptr) count = 0;
+#pragma unroll
+    for (int n = 0; n < NT; ++n) {
+        const int id = w + 4 * n, ab = id / BB, bb = id % BB;
+        const float* p = src + (ab * 32 + 4 * h) * DB + bb * 32 + r;
+        f32x16 t = zero16();
+        int k = 0;
+        for (; k + U <= count; k += U) {
+            float x[U][16];
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int a = 0; a < 4; ++a)
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) x[u][4 * a + b] = p[(size_t)(k + u) * (DA * DB) + (8 * a + b) * DB];
+#pragma unroll
+            for (int u = 0; u < U; ++u)          // (the order of the additions is the order of the states)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) t[e] += x[u][e];
+        }
+        for (; k < count; ++k) {
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+#pragma unroll
+                for (int b = 0; b < 4; ++b) t[4 * a + b] += p[(size_t)k * (DA * DB) + (8 * a + b) * DB];
+        }
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[n][e] = NEG ? -t[e] : t[e];
+    }
+}
+
 // Write a [DA][DB] state held as accumulator tiles into LDS as bf16, TRANSPOSED: dst[b][a] (row stride DA + PAD).
 // A lane owns 4 consecutive a for one b, i.e. 8 contiguous bytes of dst.  NEG writes the negated value.
 template <int DA, int DB, bool NEG>
@@ -532,7 +572,7 @@ struct FwdLds {
 template <int C, int DK, int DV, bool ZQK, bool SAVE, bool GATE = false, bool STAGE = false>
 __device__ __forceinline__ void fwd_sweep_body(const bf16* __restrict__ Qb, const bf16* __restrict__ Kb,
                                                const bf16* __restrict__ Vb, bf16* __restrict__ Ob,
-                                               const float* __restrict__ S0, float* __restrict__ S_final,
+                                               const float* __restrict__ S0, int n_s0, float* __restrict__ S_final,
                                                float* __restrict__ S_final_T, const float* __restrict__ aff,
                                                size_t aff_stride, int ldk, int ldv, int ntok, unsigned char* lds,
                                                int tid, int w, int lane, const bf16* __restrict__ Gb = nullptr,
@@ -569,7 +609,7 @@ __device__ __forceinline__ void fwd_sweep_body(const bf16* __restrict__ Qb, cons
     }
 
     f32x16 accS[NS];
-    load_state<DK, DV, false>(accS, S0, w, lane);
+    sum_states<DK, DV, false>(accS, S0, n_s0, w, lane);     // (n_s0 states, one behind the other, are added up)
 
     for (int c0 = 0; c0 < ntok; c0 += C) {
         if (ZQK) {
@@ -690,6 +730,8 @@ __device__ __forceinline__ void fwd_sweep_body(const bf16* __restrict__ Qb, cons
 // Per chunk:  dQ = dP K + dO S^T',  dK = dP^T Q + V R^T',  dV = P^T dO + K R,
 //             P = (Q K^T) o M,  dP = (dO V^T) o M, every output accumulated transposed.
 // Send == nullptr means the whole sequence is this one segment: S is then built here, R starts at zero.
+// Otherwise the start states are sums of n_send and n_rnext states that lie one behind the other at Send and Rnext
+// (one each if a scan has run; the segment totals themselves if not; Rnext may be null: zero).
 // R_final, if given, receives the state R after the segment's first chunk has been added ([dk][dv], fp32).
 // ckpt (only with Send == nullptr; may be null): the pass that builds S leaves a copy of the running state after
 // every ckpt_every chunks there, and the walk back takes that copy up again when it reaches the same place, so that
@@ -756,7 +798,8 @@ template <int C, int DK, int DV, bool ZQK>
 __device__ __forceinline__ void bwd_sweep_body(const bf16* __restrict__ Qb, const bf16* __restrict__ Kb,
                                                const bf16* __restrict__ Vb, const bf16* __restrict__ Gb,
                                                bf16* __restrict__ dQb, bf16* __restrict__ dKb, bf16* __restrict__ dVb,
-                                               const float* __restrict__ Send, const float* __restrict__ Rnext,
+                                               const float* __restrict__ Send, int n_send,
+                                               const float* __restrict__ Rnext, int n_rnext,
                                                float* __restrict__ R_final, const float* __restrict__ aff,
                                                size_t aff_stride, float* __restrict__ part, int ldk, int ldv,
                                                int ntok, unsigned char* lds, int tid, int w, int lane,
@@ -845,8 +888,8 @@ __device__ __forceinline__ void bwd_sweep_body(const bf16* __restrict__ Qb, cons
         rg.load(Gb + (size_t)c0 * ldv, ldv, ntok - c0, tid);
     }
     if (Send != nullptr) {
-        load_state<DV, DK, true>(accNS, Send, w, lane);
-        load_state<DV, DK, false>(accRT, Rnext, w, lane);
+        sum_states<DV, DK, true>(accNS, Send, n_send, w, lane);      // (n_send, n_rnext states are added up)
+        sum_states<DV, DK, false>(accRT, Rnext, n_rnext, w, lane);
     }
 
     for (int ci = n_ch - 1; ci >= 0; --ci) {
@@ -1139,7 +1182,8 @@ void bf16_fwd_sweep_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ 
                                                             const float* __restrict__ S0, float* __restrict__ S_out,
                                                             const float* __restrict__ aff, int H,
                                                             float* __restrict__ saved, int save_every,
-                                                            int first_loads_state, int N, int seg_len, int n_seg)
+                                                            int first_loads_state, int N, int seg_len, int n_seg,
+                                                            int fold)
 {
     // whole-row stores through a staging tile where its LDS and registers cost nothing that matters: not the
     // contiguous 64-wide shape (it would lose its fourth workgroup per unit; with [B,N,H,d] rows, H * d apart, the
@@ -1163,8 +1207,11 @@ void bf16_fwd_sweep_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ 
         const int n_slots = (n_seg + save_every - 1) / save_every, slot = (seg + save_every) / save_every - 1;
         save_to = saved + ((size_t)bh * n_slots + slot) * DK * DV;
     }
+    // fold: S0 holds the segments' own totals (no scan has run): this workgroup adds up those in front of its segment
+    const float* s0 = fold ? ((S0 != nullptr && seg > 0) ? S0 + (size_t)bh * n_seg * DK * DV : nullptr)
+                           : (has_state ? S0 + ((size_t)bh * n_seg + seg) * DK * DV : nullptr);
     fwd_sweep_body<C, DK, DV, ZQK, SAVE, false, STAGE>(Q + rk, ZQK ? nullptr : K + rk, V + rv, O + rv,
-                                   has_state ? S0 + ((size_t)bh * n_seg + seg) * DK * DV : nullptr,
+                                   s0, fold ? seg : 1,
                                    (S_out != nullptr && seg == n_seg - 1) ? S_out + (size_t)bh * DK * DV : nullptr,
                                    save_to, ZQK ? aff + (size_t)(bh % H) * DK : nullptr, (size_t)H * DK,
                                    NH ? H * DK : DK, NH ? H * DV : DV, p1 - p0, lds, tid, w, lane);
@@ -1176,7 +1223,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((C == 64 &&
 void bf16_fwd_gated_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, const bf16* __restrict__ V,
                            const bf16* __restrict__ G, bf16* __restrict__ O, bf16* __restrict__ Y, float eps,
                            const float* __restrict__ S0, const float* __restrict__ aff, int H,
-                           float* __restrict__ saved, int save_every, int N, int seg_len, int n_seg)
+                           float* __restrict__ saved, int save_every, int N, int seg_len, int n_seg, int fold)
 {
     __shared__ __attribute__((aligned(16))) unsigned char lds[FwdLds<C, DK, DV, ZQK, true>::BYTES];
     const int seg = blockIdx.y;
@@ -1191,9 +1238,9 @@ void bf16_fwd_gated_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ 
         save_to = saved + ((size_t)bh * n_slots + slot) * DK * DV;
     }
     fwd_sweep_body<C, DK, DV, ZQK, SAVE, true>(Q + rk, ZQK ? nullptr : K + rk, V + rv, O ? O + rv : nullptr,
-                                               (S0 != nullptr && seg > 0) ? S0 + ((size_t)bh * n_seg + seg) * DK * DV
-                                                                          : nullptr,
-                                               nullptr, save_to, ZQK ? aff + (size_t)(bh % H) * DK : nullptr,
+                                               (S0 != nullptr && seg > 0)
+                                                   ? S0 + ((size_t)bh * n_seg + (fold ? 0 : seg)) * DK * DV : nullptr,
+                                               fold ? seg : 1, nullptr, save_to, ZQK ? aff + (size_t)(bh % H) * DK : nullptr,
                                                (size_t)H * DK, DK, DV, p1 - p0, lds, tid, w, lane, G + rv, Y + rv, eps);
 }
 
@@ -1209,7 +1256,7 @@ void bf16_bwd_sweep_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ 
                                                             const float* __restrict__ Rnext, float* __restrict__ dS_in,
                                                             const float* __restrict__ aff, int H,
                                                             float* __restrict__ part, int N, int seg_len, int n_seg,
-                                                            float* ckpt, int ckpt_every)
+                                                            float* ckpt, int ckpt_every, int fold)
 {
     __shared__ __attribute__((aligned(16))) unsigned char lds[BwdLds<C, DK, DV, ZQK>::BYTES];
     const int seg = blockIdx.y;
@@ -1219,10 +1266,17 @@ void bf16_bwd_sweep_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ 
     const int p0 = seg * seg_len, p1 = min(N, p0 + seg_len);
     const size_t rk = row_offset<DK>(NH, bh, H, N, p0), rv = row_offset<DV>(NH, bh, H, N, p0);
     const size_t soff = ((size_t)bh * n_seg + seg) * DK * DV;
-    // the scan leaves zeros in the last segment's R slot, so Rnext can be read for every segment
+    // After a scan: one state each (the scan leaves zeros in the last segment's R slot, so Rnext can be read for every
+    // segment).  fold bit 0 / bit 1: Send / Rnext hold the segments' own totals and this workgroup adds up those up
+    // to and including its segment / those behind its segment.
+    const size_t head = (size_t)bh * n_seg * DK * DV, st = (size_t)DK * DV;
+    const float* send = Send ? ((fold & 1) ? Send + head : Send + soff) : nullptr;
+    const float* rnext = Rnext ? ((fold & 2) ? (seg + 1 < n_seg ? Rnext + head + (size_t)(seg + 1) * st : nullptr)
+                                             : Rnext + soff)
+                               : nullptr;
     // dS_in: gradient with respect to the carried-in state = R after the very first chunk (segment 0's workgroup)
     bwd_sweep_body<C, DK, DV, ZQK>(Q + rk, ZQK ? nullptr : K + rk, V + rv, dO + rv, dQ + rk, ZQK ? nullptr : dK + rk,
-                                   dV + rv, Send ? Send + soff : nullptr, Rnext ? Rnext + soff : nullptr,
+                                   dV + rv, send, (fold & 1) ? seg + 1 : 1, rnext, (fold & 2) ? n_seg - 1 - seg : 1,
                                    (dS_in != nullptr && seg == 0) ? dS_in + (size_t)bh * DK * DV : nullptr,
                                    ZQK ? aff + (size_t)(bh % H) * DK : nullptr, (size_t)H * DK,
                                    ZQK ? part + ((size_t)bh * n_seg + seg) * 4 * DK : nullptr, NH ? H * DK : DK,
@@ -1430,6 +1484,20 @@ static int prepass_reverse()
     return v;
 }
 
+// Short rows of segments: the sweep's workgroups add up the segment totals themselves (each reads the totals in front
+// of or behind its own segment, which the memory-side cache still holds) and no scan kernel is launched.  That saves
+// a launch of about 10 us whose work is latency, and costs every workgroup n/2 state reads at its start: it pays
+// while those reads stay small next to the segment's own tiles (measured: 64 x 64 states, 10 segments: step 0.343 ->
+// 0.337 ms; 64 x 128, step 0.280 -> 0.265 ms; 128 x 128 states, 16 segments: 0.327 -> 0.332 ms, so not there).
+// CHELA_FOLD_SCAN=0 (read per call, a tuning aid) keeps the scan.
+static bool fold_scan(const Plan& plan, bool stateful)
+{
+    if (stateful || plan.n_seg < 2) return false;
+    if ((size_t)plan.n_seg * plan.state_elems * sizeof(float) > ((size_t)256 << 10)) return false;
+    const char* e = getenv("CHELA_FOLD_SCAN");
+    return !(e && atoi(e) == 0);
+}
+
 template <int DA, int DB, int AFF = 0, bool NH = false, bool NT = false>
 static hipError_t run_seg_state(const SegStateArgs& a, int npairs, const int* scan_modes, const float* const* init,
                                 bool init_transposed, long BH, int N, const Plan& plan, hipStream_t st,
@@ -1458,6 +1526,7 @@ static hipError_t fwd_impl(const bf16* Q, const bf16* K, const bf16* V, bf16* O,
 {
     hipError_t e;
     const bool use_ws = plan.n_seg > 1 || S_in != nullptr;
+    const bool fold = fold_scan(plan, S_in != nullptr);
     if (use_ws) {
         SegStateArgs a{};
         a.X[0] = ZQK ? Q : K; a.Y[0] = V; a.out[0] = ws; a.skip_seg[0] = plan.n_seg - 1;
@@ -1466,7 +1535,8 @@ static hipError_t fwd_impl(const bf16* Q, const bf16* K, const bf16* V, bf16* O,
         if (ZQK) { a.alpha[0] = aff + 2 * (size_t)H * DK; a.beta[0] = aff + 3 * (size_t)H * DK; }
         const int mode = SCAN_EXCL_PREFIX;
         const float* init[2] = {S_in, nullptr};
-        if ((e = run_seg_state<DK, DV, ZQK ? 1 : 0, NH>(a, 1, &mode, init, false, BH, N, plan, st)) != hipSuccess) return e;
+        if ((e = run_seg_state<DK, DV, ZQK ? 1 : 0, NH>(a, 1, &mode, init, false, BH, N, plan, st, !fold)) != hipSuccess)
+            return e;
     }
     dim3 grid((unsigned)BH, plan.n_seg);
     ProfScope prof(KID_FWD_SWEEP_BF16, st);
@@ -1474,11 +1544,11 @@ static hipError_t fwd_impl(const bf16* Q, const bf16* K, const bf16* V, bf16* O,
     if (saved != nullptr)
         hipLaunchKernelGGL((bf16_fwd_sweep_kernel<C, DK, DV, ZQK, true, NH>), grid, dim3(256), 0, st, Q, K, V, O,
                            use_ws ? ws : nullptr, S_out, aff, H, saved, save_every, S_in != nullptr ? 1 : 0, N,
-                           plan.seg_len, plan.n_seg);
+                           plan.seg_len, plan.n_seg, fold ? 1 : 0);
     else
         hipLaunchKernelGGL((bf16_fwd_sweep_kernel<C, DK, DV, ZQK, false, NH>), grid, dim3(256), 0, st, Q, K, V, O,
                            use_ws ? ws : nullptr, S_out, aff, H, (float*)nullptr, 1, S_in != nullptr ? 1 : 0, N,
-                           plan.seg_len, plan.n_seg);
+                           plan.seg_len, plan.n_seg, fold ? 1 : 0);
     return hipGetLastError();
 }
 
@@ -1489,6 +1559,7 @@ static hipError_t fwd_gated_impl(const bf16* Q, const bf16* K, const bf16* V, co
                                  const Plan& plan, float* ws, hipStream_t st)
 {
     hipError_t e;
+    const bool fold = fold_scan(plan, false);
     if (plan.n_seg > 1) {
         SegStateArgs a{};
         a.X[0] = ZQK ? Q : K; a.Y[0] = V; a.out[0] = ws; a.skip_seg[0] = plan.n_seg - 1;
@@ -1497,17 +1568,19 @@ static hipError_t fwd_gated_impl(const bf16* Q, const bf16* K, const bf16* V, co
         if (ZQK) { a.alpha[0] = aff + 2 * (size_t)H * DK; a.beta[0] = aff + 3 * (size_t)H * DK; }
         const int mode = SCAN_EXCL_PREFIX;
         const float* init[2] = {nullptr, nullptr};
-        if ((e = run_seg_state<DK, DV, ZQK ? 1 : 0, false>(a, 1, &mode, init, false, BH, N, plan, st)) != hipSuccess)
+        if ((e = run_seg_state<DK, DV, ZQK ? 1 : 0, false>(a, 1, &mode, init, false, BH, N, plan, st, !fold)) != hipSuccess)
             return e;
     }
     dim3 grid((unsigned)BH, plan.n_seg);
     ProfScope prof(KID_FWD_SWEEP_BF16, st);
     if (saved != nullptr)
         hipLaunchKernelGGL((bf16_fwd_gated_kernel<64, DK, DV, ZQK, true>), grid, dim3(256), 0, st, Q, K, V, G, O, Y, eps,
-                           plan.n_seg > 1 ? ws : nullptr, aff, H, saved, save_every, N, plan.seg_len, plan.n_seg);
+                           plan.n_seg > 1 ? ws : nullptr, aff, H, saved, save_every, N, plan.seg_len, plan.n_seg,
+                           fold ? 1 : 0);
     else
         hipLaunchKernelGGL((bf16_fwd_gated_kernel<64, DK, DV, ZQK, false>), grid, dim3(256), 0, st, Q, K, V, G, O, Y,
-                           eps, plan.n_seg > 1 ? ws : nullptr, aff, H, (float*)nullptr, 1, N, plan.seg_len, plan.n_seg);
+                           eps, plan.n_seg > 1 ? ws : nullptr, aff, H, (float*)nullptr, 1, N, plan.seg_len, plan.n_seg,
+                           fold ? 1 : 0);
     return hipGetLastError();
 }
 
@@ -1526,13 +1599,15 @@ static hipError_t bwd_impl(const bf16* Q, const bf16* K, const bf16* V, const bf
         // suffix sums of dO^T Q remain to be built, from dO and Q (or Z) alone.
         float* wsR = ws;
         float* wsP = ZQK ? ws + (plan.n_seg > 1 ? (size_t)BH * plan.n_seg * DK * DV : 0) : nullptr;
+        const bool fold_saved = fold_scan(plan, false);      // (the saved states are complete; only R is summed)
         if (plan.n_seg > 1) {
             SegStateArgs a{};
             a.X[0] = dO; a.Y[0] = Q; a.out[0] = wsR; a.skip_seg[0] = 0;
             a.H = H;
             if (ZQK) { a.alpha[0] = aff; a.beta[0] = aff + (size_t)H * DK; }
             const int mode = SCAN_EXCL_SUFFIX;
-            if ((e = run_seg_state<DV, DK, ZQK ? 2 : 0, NH>(a, 1, &mode, nullptr, false, BH, N, plan, st)) != hipSuccess)
+            if ((e = run_seg_state<DV, DK, ZQK ? 2 : 0, NH>(a, 1, &mode, nullptr, false, BH, N, plan, st, !fold_saved)) !=
+                hipSuccess)
                 return e;
         }
         {
@@ -1540,7 +1615,7 @@ static hipError_t bwd_impl(const bf16* Q, const bf16* K, const bf16* V, const bf
             ProfScope prof(KID_BWD_SWEEP_BF16, st);
             hipLaunchKernelGGL((bf16_bwd_sweep_kernel<C, DK, DV, ZQK, NH>), grid, dim3(256), 0, st, Q, K, V, dO, dQ, dK,
                                dV, saved, plan.n_seg > 1 ? wsR : nullptr, dS_in, aff, H, wsP, N, plan.seg_len,
-                               plan.n_seg, (float*)nullptr, 0);
+                               plan.n_seg, (float*)nullptr, 0, fold_saved ? 2 : 0);
             if ((e = hipGetLastError()) != hipSuccess) return e;
         }
         if (ZQK) {
@@ -1551,6 +1626,7 @@ static hipError_t bwd_impl(const bf16* Q, const bf16* K, const bf16* V, const bf
         return e;
     }
     const bool use_ws = plan.n_seg > 1 || S_in != nullptr || dS_out != nullptr;
+    const bool fold = fold_scan(plan, S_in != nullptr || dS_out != nullptr);
     const size_t state_floats = use_ws ? (size_t)BH * plan.n_seg * DK * DV : 0;
     // a single segment that is long: copies of the running state at the workspace's start (see bwd_sweep_body)
     const long n_ckpt = use_ws ? 0 : plan_n_ckpt(plan, N);
@@ -1569,14 +1645,15 @@ static hipError_t bwd_impl(const bf16* Q, const bf16* K, const bf16* V, const bf
         }
         const int modes[2] = {SCAN_INCL_PREFIX, SCAN_EXCL_SUFFIX};
         const float* init[2] = {S_in, dS_out};   // given as [dk][dv]; the arrays are [dv][dk]
-        if ((e = run_seg_state<DV, DK, ZQK ? 2 : 0, NH>(a, 2, modes, init, true, BH, N, plan, st)) != hipSuccess) return e;
+        if ((e = run_seg_state<DV, DK, ZQK ? 2 : 0, NH>(a, 2, modes, init, true, BH, N, plan, st, !fold)) != hipSuccess)
+            return e;
     }
     {
         dim3 grid((unsigned)BH, plan.n_seg);
         ProfScope prof(KID_BWD_SWEEP_BF16, st);
         hipLaunchKernelGGL((bf16_bwd_sweep_kernel<C, DK, DV, ZQK, NH>), grid, dim3(256), 0, st, Q, K, V, dO, dQ, dK, dV,
                            use_ws ? wsS : nullptr, use_ws ? wsR : nullptr, dS_in, aff, H, wsP, N, plan.seg_len,
-                           plan.n_seg, n_ckpt > 0 ? ws : nullptr, n_ckpt > 0 ? plan.ckpt_every : 0);
+                           plan.n_seg, n_ckpt > 0 ? ws : nullptr, n_ckpt > 0 ? plan.ckpt_every : 0, fold ? 3 : 0);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     if (ZQK) {

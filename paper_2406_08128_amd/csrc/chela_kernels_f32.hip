@@ -188,6 +188,45 @@ hipError_t launch_stream_probe(const void* const* in, int n_in, void* const* out
 
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
+// ------------------------------------------------------------------------------------------------ matrix-core probe
+// Nothing but v_mfma_f32_32x32x16_bf16 on registers: every wave keeps four independent accumulator tiles going, so
+// that an instruction never waits for the one before it, `iters` rounds of four.  What this reaches is the matrix
+// rate the GPU actually delivers (clock included), the yardstick next to the published 2.5 PFLOP/s.
+typedef __attribute__((ext_vector_type(8))) __bf16 probe_bf16x8;
+
+__global__ __launch_bounds__(256) void mfma_probe_kernel(float* __restrict__ out, int iters)
+{
+    const int lane = threadIdx.x & 63;
+    probe_bf16x8 a, b;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { a[e] = (__bf16)(1.0f / (1 + ((lane + e) & 7))); b[e] = (__bf16)(0.25f * ((lane ^ e) & 3)); }
+    f32x16 acc[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[q][e] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[q], 0, 0, 0);
+    }
+    float t = 0.f;
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) t += acc[q][e];
+    out[(size_t)blockIdx.x * 256 + threadIdx.x] = t;          // keeps the arithmetic alive
+}
+
+// `out` holds blocks * 256 floats; each of the blocks * 4 waves issues iters * 16 matrix instructions of 32768 FLOP.
+hipError_t launch_mfma_probe(float* out, int blocks, int iters, hipStream_t st)
+{
+    ProfScope prof(KID_MFMA_PROBE, st);
+    hipLaunchKernelGGL(mfma_probe_kernel, dim3((unsigned)blocks), dim3(256), 0, st, out, iters);
+    return hipGetLastError();
+}
+
 __device__ __forceinline__ f32x16 mfma_f32(float a, float b, f32x16 c)
 {
     return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
