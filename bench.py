@@ -519,7 +519,7 @@ def main():
                               "avg_launch_us": round(sp_us, 2), "GB/s": round(sp_gbs, 1)}
     roofline["frac_of_stream_mix"] = round(achieved / sp_gbs, 4)
     # The matrix rate the GPU delivers when nothing but matrix instructions are asked of it (registers only).
-    mf_blocks, mf_iters = 256 * 8, 4096
+    mf_blocks, mf_iters = 256 * 8, 1024
     mf_out = torch.empty(mf_blocks * 256, dtype=torch.float32, device="cuda")
     for _ in range(2):
         binding.chela_mfma_probe(mf_out, mf_blocks, mf_iters)

@@ -343,6 +343,45 @@ __device__ __forceinline__ void load_state(f32x16* acc, const float* src, int w,
 // The same for the sum of `count` states that lie one behind the other at src (count == 0 or src == nullptr: zero):
 // a workgroup that adds up the segment totals in front of (or behind) its own segment itself, in a fixed order,
 // instead of reading what a scan kernel left.  The loads of two states are in flight at a time.
+// The same sum for states stored in ACCUMULATOR ORDER, [wave][tile][lane][16] floats: what a lane adds up is then 64
+// contiguous bytes per state and tile, four 16-byte loads instead of sixteen 4-byte ones.  The pre-pass writes its
+// totals that way when the sweeps are going to add them up (same widths, so the same tile-to-wave mapping).
+template <int DA, int DB, bool NEG>
+__device__ __forceinline__ void sum_states_acc(f32x16* acc, const float* src, int count, int w, int lane)
+{
+    constexpr int NT = (DA / 32) * (DB / 32) / 4;
+    constexpr int U = 4;                 // states whose loads are in flight together
+    if (src == nullptr) count = 0;
+#pragma unroll
+    for (int n = 0; n < NT; ++n) {
+        const float4* p = reinterpret_cast<const float4*>(src) + ((size_t)(w * NT + n) * 64 + lane) * 4;
+        f32x16 t = zero16();
+        int k = 0;
+        for (; k + U <= count; k += U) {
+            float4 x[U][4];
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) x[u][q] = p[(size_t)(k + u) * (DA * DB / 4) + q];
+#pragma unroll
+            for (int u = 0; u < U; ++u)          // (the order of the additions is the order of the states)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    t[4 * q] += x[u][q].x; t[4 * q + 1] += x[u][q].y; t[4 * q + 2] += x[u][q].z; t[4 * q + 3] += x[u][q].w;
+                }
+        }
+        for (; k < count; ++k) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float4 v = p[(size_t)k * (DA * DB / 4) + q];
+                t[4 * q] += v.x; t[4 * q + 1] += v.y; t[4 * q + 2] += v.z; t[4 * q + 3] += v.w;
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[n][e] = NEG ? -t[e] : t[e];
+    }
+}
+
 template <int DA, int DB, bool NEG>
 __device__ __forceinline__ void sum_states(f32x16* acc, const float* src, int count, int w, int lane)
 {
@@ -448,7 +487,8 @@ template <int DA, int DB, int AFF, bool NTL = false>
 __device__ __forceinline__ void prepass_body(const bf16* __restrict__ X, const bf16* __restrict__ Y,
                                              float* __restrict__ out, const float* __restrict__ alpha,
                                              const float* __restrict__ beta, int lda, int ldb, int ntok,
-                                             unsigned char* lds, int tid, int w, int lane, bool rev = false)
+                                             unsigned char* lds, int tid, int w, int lane, bool rev = false,
+                                             bool acc_order = false)
 {
     constexpr int R = 64;
     constexpr int PF = 2;          // 64-token blocks in flight per workgroup: this kernel only reads, so it lives
@@ -533,6 +573,17 @@ __device__ __forceinline__ void prepass_body(const bf16* __restrict__ X, const b
             }
         }
     }
+    if (acc_order) {
+        // for a sweep that adds the totals up itself (sum_states_acc): [wave][tile][lane][16]
+#pragma unroll
+        for (int n = 0; n < NT; ++n) {
+            float4* dst = reinterpret_cast<float4*>(out) + ((size_t)(w * NT + n) * 64 + lane) * 4;
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                dst[q] = make_float4(acc[n][4 * q], acc[n][4 * q + 1], acc[n][4 * q + 2], acc[n][4 * q + 3]);
+        }
+        return;
+    }
     const int r = lane & 31, h = lane >> 5;
 #pragma unroll
     for (int n = 0; n < NT; ++n) {
@@ -572,7 +623,8 @@ struct FwdLds {
 template <int C, int DK, int DV, bool ZQK, bool SAVE, bool GATE = false, bool STAGE = false>
 __device__ __forceinline__ void fwd_sweep_body(const bf16* __restrict__ Qb, const bf16* __restrict__ Kb,
                                                const bf16* __restrict__ Vb, bf16* __restrict__ Ob,
-                                               const float* __restrict__ S0, int n_s0, float* __restrict__ S_final,
+                                               const float* __restrict__ S0, int n_s0, bool s0_acc,
+                                               float* __restrict__ S_final,
                                                float* __restrict__ S_final_T, const float* __restrict__ aff,
                                                size_t aff_stride, int ldk, int ldv, int ntok, unsigned char* lds,
                                                int tid, int w, int lane, const bf16* __restrict__ Gb = nullptr,
@@ -609,7 +661,9 @@ __device__ __forceinline__ void fwd_sweep_body(const bf16* __restrict__ Qb, cons
     }
 
     f32x16 accS[NS];
-    sum_states<DK, DV, false>(accS, S0, n_s0, w, lane);     // (n_s0 states, one behind the other, are added up)
+    // (n_s0 states, one behind the other, are added up; s0_acc: they are stored in accumulator order)
+    if (s0_acc) sum_states_acc<DK, DV, false>(accS, S0, n_s0, w, lane);
+    else sum_states<DK, DV, false>(accS, S0, n_s0, w, lane);
 
     for (int c0 = 0; c0 < ntok; c0 += C) {
         if (ZQK) {
@@ -799,7 +853,7 @@ __device__ __forceinline__ void bwd_sweep_body(const bf16* __restrict__ Qb, cons
                                                const bf16* __restrict__ Vb, const bf16* __restrict__ Gb,
                                                bf16* __restrict__ dQb, bf16* __restrict__ dKb, bf16* __restrict__ dVb,
                                                const float* __restrict__ Send, int n_send,
-                                               const float* __restrict__ Rnext, int n_rnext,
+                                               const float* __restrict__ Rnext, int n_rnext, int acc_mask,
                                                float* __restrict__ R_final, const float* __restrict__ aff,
                                                size_t aff_stride, float* __restrict__ part, int ldk, int ldv,
                                                int ntok, unsigned char* lds, int tid, int w, int lane,
@@ -888,8 +942,11 @@ __device__ __forceinline__ void bwd_sweep_body(const bf16* __restrict__ Qb, cons
         rg.load(Gb + (size_t)c0 * ldv, ldv, ntok - c0, tid);
     }
     if (Send != nullptr) {
-        sum_states<DV, DK, true>(accNS, Send, n_send, w, lane);      // (n_send, n_rnext states are added up)
-        sum_states<DV, DK, false>(accRT, Rnext, n_rnext, w, lane);
+        // (n_send, n_rnext states are added up; acc_mask bit 0 / 1: those of S / R are stored in accumulator order)
+        if (acc_mask & 1) sum_states_acc<DV, DK, true>(accNS, Send, n_send, w, lane);
+        else sum_states<DV, DK, true>(accNS, Send, n_send, w, lane);
+        if (acc_mask & 2) sum_states_acc<DV, DK, false>(accRT, Rnext, n_rnext, w, lane);
+        else sum_states<DV, DK, false>(accRT, Rnext, n_rnext, w, lane);
     }
 
     for (int ci = n_ch - 1; ci >= 0; --ci) {
@@ -1141,6 +1198,7 @@ struct SegStateArgs {
     const float* beta[2];
     int H;
     int reverse[2];    // walk the segment's blocks from its end to its start (same sum)
+    int acc_order;     // write the totals in accumulator order, for sweeps that add them up themselves
 };
 
 // NH: the tensors are [B,N,H,d] (token rows H * d apart) instead of [B,H,N,d]; args.H is then the head count.
@@ -1171,7 +1229,8 @@ void bf16_seg_state_kernel(SegStateArgs args, int N, int seg_len, int n_seg)
     prepass_body<DA, DB, AFF, NT>(args.X[z] + row_offset<DA>(NH, bh, args.H, N, p0),
                                   args.Y[z] + row_offset<DB>(NH, bh, args.H, N, p0),
                                   args.out[z] + ((size_t)bh * n_seg + seg) * DA * DB, al, be, NH ? args.H * DA : DA,
-                                  NH ? args.H * DB : DB, p1 - p0, lds, tid, w, lane, args.reverse[z] != 0);
+                                  NH ? args.H * DB : DB, p1 - p0, lds, tid, w, lane, args.reverse[z] != 0,
+                                  args.acc_order != 0);
 }
 
 // (the narrowest shape is asked to stay within the 128 registers that let four workgroups share a compute unit)
@@ -1211,7 +1270,7 @@ void bf16_fwd_sweep_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ 
     const float* s0 = fold ? ((S0 != nullptr && seg > 0) ? S0 + (size_t)bh * n_seg * DK * DV : nullptr)
                            : (has_state ? S0 + ((size_t)bh * n_seg + seg) * DK * DV : nullptr);
     fwd_sweep_body<C, DK, DV, ZQK, SAVE, false, STAGE>(Q + rk, ZQK ? nullptr : K + rk, V + rv, O + rv,
-                                   s0, fold ? seg : 1,
+                                   s0, fold ? seg : 1, fold != 0,
                                    (S_out != nullptr && seg == n_seg - 1) ? S_out + (size_t)bh * DK * DV : nullptr,
                                    save_to, ZQK ? aff + (size_t)(bh % H) * DK : nullptr, (size_t)H * DK,
                                    NH ? H * DK : DK, NH ? H * DV : DV, p1 - p0, lds, tid, w, lane);
@@ -1240,7 +1299,7 @@ void bf16_fwd_gated_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ 
     fwd_sweep_body<C, DK, DV, ZQK, SAVE, true>(Q + rk, ZQK ? nullptr : K + rk, V + rv, O ? O + rv : nullptr,
                                                (S0 != nullptr && seg > 0)
                                                    ? S0 + ((size_t)bh * n_seg + (fold ? 0 : seg)) * DK * DV : nullptr,
-                                               fold ? seg : 1, nullptr, save_to, ZQK ? aff + (size_t)(bh % H) * DK : nullptr,
+                                               fold ? seg : 1, fold != 0, nullptr, save_to, ZQK ? aff + (size_t)(bh % H) * DK : nullptr,
                                                (size_t)H * DK, DK, DV, p1 - p0, lds, tid, w, lane, G + rv, Y + rv, eps);
 }
 
@@ -1276,7 +1335,7 @@ void bf16_bwd_sweep_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ 
                                : nullptr;
     // dS_in: gradient with respect to the carried-in state = R after the very first chunk (segment 0's workgroup)
     bwd_sweep_body<C, DK, DV, ZQK>(Q + rk, ZQK ? nullptr : K + rk, V + rv, dO + rv, dQ + rk, ZQK ? nullptr : dK + rk,
-                                   dV + rv, send, (fold & 1) ? seg + 1 : 1, rnext, (fold & 2) ? n_seg - 1 - seg : 1,
+                                   dV + rv, send, (fold & 1) ? seg + 1 : 1, rnext, (fold & 2) ? n_seg - 1 - seg : 1, fold,
                                    (dS_in != nullptr && seg == 0) ? dS_in + (size_t)bh * DK * DV : nullptr,
                                    ZQK ? aff + (size_t)(bh % H) * DK : nullptr, (size_t)H * DK,
                                    ZQK ? part + ((size_t)bh * n_seg + seg) * 4 * DK : nullptr, NH ? H * DK : DK,
@@ -1490,12 +1549,13 @@ static int prepass_reverse()
 // while those reads stay small next to the segment's own tiles (measured: 64 x 64 states, 10 segments: step 0.343 ->
 // 0.337 ms; 64 x 128, step 0.280 -> 0.265 ms; 128 x 128 states, 16 segments: 0.327 -> 0.332 ms, so not there).
 // CHELA_FOLD_SCAN=0 (read per call, a tuning aid) keeps the scan.
-static bool fold_scan(const Plan& plan, bool stateful)
+static bool fold_scan(const Plan& plan, bool stateful, bool is_bwd = false)
 {
     if (stateful || plan.n_seg < 2) return false;
     if ((size_t)plan.n_seg * plan.state_elems * sizeof(float) > ((size_t)256 << 10)) return false;
     const char* e = getenv("CHELA_FOLD_SCAN");
-    return !(e && atoi(e) == 0);
+    const int mode = e ? atoi(e) : 2;          // 0: never, 1: forward calls only, 2: forward and backward calls
+    return is_bwd ? mode >= 2 : mode >= 1;
 }
 
 template <int DA, int DB, int AFF = 0, bool NH = false, bool NT = false>
@@ -1532,6 +1592,7 @@ static hipError_t fwd_impl(const bf16* Q, const bf16* K, const bf16* V, bf16* O,
         a.X[0] = ZQK ? Q : K; a.Y[0] = V; a.out[0] = ws; a.skip_seg[0] = plan.n_seg - 1;
         a.H = H;
         a.reverse[0] = prepass_reverse();
+        a.acc_order = fold ? 1 : 0;
         if (ZQK) { a.alpha[0] = aff + 2 * (size_t)H * DK; a.beta[0] = aff + 3 * (size_t)H * DK; }
         const int mode = SCAN_EXCL_PREFIX;
         const float* init[2] = {S_in, nullptr};
@@ -1565,6 +1626,7 @@ static hipError_t fwd_gated_impl(const bf16* Q, const bf16* K, const bf16* V, co
         a.X[0] = ZQK ? Q : K; a.Y[0] = V; a.out[0] = ws; a.skip_seg[0] = plan.n_seg - 1;
         a.H = H;
         a.reverse[0] = prepass_reverse();
+        a.acc_order = fold ? 1 : 0;
         if (ZQK) { a.alpha[0] = aff + 2 * (size_t)H * DK; a.beta[0] = aff + 3 * (size_t)H * DK; }
         const int mode = SCAN_EXCL_PREFIX;
         const float* init[2] = {nullptr, nullptr};
@@ -1599,11 +1661,12 @@ static hipError_t bwd_impl(const bf16* Q, const bf16* K, const bf16* V, const bf
         // suffix sums of dO^T Q remain to be built, from dO and Q (or Z) alone.
         float* wsR = ws;
         float* wsP = ZQK ? ws + (plan.n_seg > 1 ? (size_t)BH * plan.n_seg * DK * DV : 0) : nullptr;
-        const bool fold_saved = fold_scan(plan, false);      // (the saved states are complete; only R is summed)
+        const bool fold_saved = fold_scan(plan, false, true);      // (the saved states are complete; only R is summed)
         if (plan.n_seg > 1) {
             SegStateArgs a{};
             a.X[0] = dO; a.Y[0] = Q; a.out[0] = wsR; a.skip_seg[0] = 0;
             a.H = H;
+            a.acc_order = fold_saved ? 1 : 0;
             if (ZQK) { a.alpha[0] = aff; a.beta[0] = aff + (size_t)H * DK; }
             const int mode = SCAN_EXCL_SUFFIX;
             if ((e = run_seg_state<DV, DK, ZQK ? 2 : 0, NH>(a, 1, &mode, nullptr, false, BH, N, plan, st, !fold_saved)) !=
@@ -1626,7 +1689,7 @@ static hipError_t bwd_impl(const bf16* Q, const bf16* K, const bf16* V, const bf
         return e;
     }
     const bool use_ws = plan.n_seg > 1 || S_in != nullptr || dS_out != nullptr;
-    const bool fold = fold_scan(plan, S_in != nullptr || dS_out != nullptr);
+    const bool fold = fold_scan(plan, S_in != nullptr || dS_out != nullptr, true);
     const size_t state_floats = use_ws ? (size_t)BH * plan.n_seg * DK * DV : 0;
     // a single segment that is long: copies of the running state at the workspace's start (see bwd_sweep_body)
     const long n_ckpt = use_ws ? 0 : plan_n_ckpt(plan, N);
@@ -1639,6 +1702,7 @@ static hipError_t bwd_impl(const bf16* Q, const bf16* K, const bf16* V, const bf
         a.X[0] = V;  a.Y[0] = ZQK ? Q : K; a.out[0] = wsS; a.skip_seg[0] = -1;
         a.X[1] = dO; a.Y[1] = Q;           a.out[1] = wsR; a.skip_seg[1] = 0;
         a.H = H;
+        a.acc_order = fold ? 1 : 0;
         if (ZQK) {
             a.alpha[0] = aff + 2 * (size_t)H * DK; a.beta[0] = aff + 3 * (size_t)H * DK;   // K
             a.alpha[1] = aff;                      a.beta[1] = aff + (size_t)H * DK;       // Q
