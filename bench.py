@@ -559,6 +559,42 @@ def main():
                   "note": "each call timed in a loop of its own: what a kernel finds in the memory-side cache "
                           "differs from the alternating step, so the two need not add up to ms_per_step"}
 
+    # What plain streaming kernels need for the bytes this step's kernels HAVE to move in the three-launch structure
+    # (every input once per pass that needs it, every output once; states left out): the pre-pass of the forward call
+    # reads K, V of all but the last segment, its sweep reads Q, K, V and writes O, the backward's pre-pass reads
+    # Q, K, V, dO, its sweep reads them again and writes dQ, dK, dV.  Each line is the stream probe on as many arrays
+    # of the tensors' size (widths differ: arrays of the mean width, same total bytes).
+    stream_floor = None
+    if headline:
+        def probe_us(n_rd, n_wr, total_bytes):
+            each = (int(total_bytes) // (n_rd + n_wr)) // 16 * 16
+            n_sets = min(8, max(2, -(-(1 << 30) // max(1, each * (n_rd + n_wr)))))
+            sets = [[torch.zeros(each, dtype=torch.uint8, device="cuda") for _ in range(n_rd + n_wr)] for _ in range(n_sets)]
+            for i in range(3):
+                binding.chela_stream_probe(sets[i % n_sets][:n_rd], sets[i % n_sets][n_rd:])
+            torch.cuda.synchronize()
+            binding.chela_profile_reset()
+            binding.chela_profile_enable(True)
+            for i in range(16):
+                binding.chela_stream_probe(sets[i % n_sets][:n_rd], sets[i % n_sets][n_rd:])
+            torch.cuda.synchronize()
+            r = binding.chela_profile_read()["stream_probe_kernel"]
+            binding.chela_profile_enable(False)
+            binding.chela_profile_reset()
+            return r[1] * 1e3 / r[0]
+        tb_k, tb_v = th * w.dk * es, th * w.dv * es
+        parts = {"fwd_prepass_2r": probe_us(2, 0, 0.9 * (tb_k + tb_v)),
+                 "fwd_sweep_3r_1w": probe_us(3, 1, 2 * tb_k + 2 * tb_v),
+                 "bwd_prepass_4r": probe_us(4, 0, 2 * tb_k + 2 * tb_v),
+                 "bwd_sweep_4r_3w": probe_us(4, 3, 4 * tb_k + 3 * tb_v)}
+        tot = sum(parts.values())
+        stream_floor = {"us_per_part": {k: round(v, 1) for k, v in parts.items()}, "us": round(tot, 1),
+                        "bytes": int(0.9 * (tb_k + tb_v) + 2 * (2 * tb_k + 2 * tb_v) + 4 * tb_k + 3 * tb_v),
+                        "step_over_floor": round(ms_per_step * 1e3 / tot, 3),
+                        "note": "plain grid-stride kernels moving what the pre-passes and sweeps of this step must "
+                                "move (kernel time only, no launch gaps): the step cannot beat this without moving "
+                                "fewer bytes, i.e. without another structure than pre-pass + sweep per call"}
+
     step_bytes = (fwd_b + (bwd_b if has_bwd else 0)) * th
     step_flops = (fwd_f + (bwd_f if has_bwd else 0)) * th
     whole = {"hbm_GBs_algorithmic": round(step_bytes / (ms_per_step * 1e-3) / 1e9, 1),
@@ -569,6 +605,8 @@ def main():
     if w.dtype == "bf16":
         whole["mfma_frac_of_measured_peak"] = round(step_flops / (ms_per_step * 1e-3) / 1e12 / mfma_measured, 4)
     whole["hbm_frac_of_stream_mix"] = round(step_bytes / (ms_per_step * 1e-3) / 1e9 / sp_gbs, 4)
+    if stream_floor is not None:
+        whole["stream_floor"] = stream_floor
     target = None
     if headline:
         target = {"north_star": ">= 50 % of peak bf16 MFMA at B4 H12 N16384 d64, as shown by rocprof",

@@ -19,7 +19,9 @@ extern "C" {
  * this GPU actually reaches; it is not part of the attention path. */
 int chela_copy_probe(const void *src, void *dst, size_t bytes, void *stream);
 
-/* The same for any mix of streams: `in` and `out` are HOST arrays of n_in (1..4) and n_out (1..4) device pointers,
+/* The same for any mix of streams: `in` and `out` are HOST arrays of n_in (1..4) and n_out (0..4) device pointers
+ * (n_out = 0: a read-only mix; `out` may then be NULL, and the inputs must not hold the 32-bit patterns 0x9e3779b9 /
+ * 0x7f4a7c15 the kernel uses to keep its loads alive -- zero-filled buffers do not),
  * each to `bytes` bytes (a multiple of 16, pointers 16-byte aligned, outputs overlapping nothing).  Thread i reads
  * 16 bytes of every input and writes 16 bytes (derived from what it read) to every output, at offset 16 i rotated by
  * a different amount per array, so that equally spaced allocations do not meet on one memory channel.  What this reaches for, say, four streams in and three out is the bandwidth the GPU delivers for the mix

@@ -1048,9 +1048,9 @@ int chela_copy_probe(const void* src, void* dst, size_t bytes, void* stream)
 
 int chela_stream_probe(const void* const* in, int n_in, void* const* out, int n_out, size_t bytes, void* stream)
 {
-    if (n_in < 1 || n_in > 4 || n_out < 1 || n_out > 4) return CHELA_ERR_BAD_SHAPE;
+    if (n_in < 1 || n_in > 4 || n_out < 0 || n_out > 4) return CHELA_ERR_BAD_SHAPE;
     if (bytes == 0) return CHELA_OK;
-    if (!in || !out) return CHELA_ERR_NULL_POINTER;
+    if (!in || (n_out > 0 && !out)) return CHELA_ERR_NULL_POINTER;
     if (bytes & 15u) return CHELA_ERR_MISALIGNED;
     for (int k = 0; k < n_in; ++k) {
         if (!in[k]) return CHELA_ERR_NULL_POINTER;

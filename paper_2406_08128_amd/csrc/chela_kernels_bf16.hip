@@ -346,11 +346,11 @@ __device__ __forceinline__ void load_state(f32x16* acc, const float* src, int w,
 // The same sum for states stored in ACCUMULATOR ORDER, [wave][tile][lane][16] floats: what a lane adds up is then 64
 // contiguous bytes per state and tile, four 16-byte loads instead of sixteen 4-byte ones.  The pre-pass writes its
 // totals that way when the sweeps are going to add them up (same widths, so the same tile-to-wave mapping).
-template <int DA, int DB, bool NEG>
+// U: states whose loads are in flight together (16 registers each; the caller knows how many it has to spare).
+template <int DA, int DB, bool NEG, int U>
 __device__ __forceinline__ void sum_states_acc(f32x16* acc, const float* src, int count, int w, int lane)
 {
     constexpr int NT = (DA / 32) * (DB / 32) / 4;
-    constexpr int U = 4;                 // states whose loads are in flight together
     if (src == nullptr) count = 0;
 #pragma unroll
     for (int n = 0; n < NT; ++n) {
@@ -662,7 +662,7 @@ __device__ __forceinline__ void fwd_sweep_body(const bf16* __restrict__ Qb, cons
 
     f32x16 accS[NS];
     // (n_s0 states, one behind the other, are added up; s0_acc: they are stored in accumulator order)
-    if (s0_acc) sum_states_acc<DK, DV, false>(accS, S0, n_s0, w, lane);
+    if (s0_acc) sum_states_acc<DK, DV, false, 4>(accS, S0, n_s0, w, lane);
     else sum_states<DK, DV, false>(accS, S0, n_s0, w, lane);
 
     for (int c0 = 0; c0 < ntok; c0 += C) {
@@ -943,9 +943,9 @@ __device__ __forceinline__ void bwd_sweep_body(const bf16* __restrict__ Qb, cons
     }
     if (Send != nullptr) {
         // (n_send, n_rnext states are added up; acc_mask bit 0 / 1: those of S / R are stored in accumulator order)
-        if (acc_mask & 1) sum_states_acc<DV, DK, true>(accNS, Send, n_send, w, lane);
+        if (acc_mask & 1) sum_states_acc<DV, DK, true, 8>(accNS, Send, n_send, w, lane);
         else sum_states<DV, DK, true>(accNS, Send, n_send, w, lane);
-        if (acc_mask & 2) sum_states_acc<DV, DK, false>(accRT, Rnext, n_rnext, w, lane);
+        if (acc_mask & 2) sum_states_acc<DV, DK, false, 8>(accRT, Rnext, n_rnext, w, lane);
         else sum_states<DV, DK, false>(accRT, Rnext, n_rnext, w, lane);
     }
 

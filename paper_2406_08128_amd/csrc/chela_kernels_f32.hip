@@ -135,6 +135,9 @@ __global__ __launch_bounds__(256) void stream_probe_kernel(StreamArgs a, size_t 
             a.out[k][j] = x;
             x.x += 1u;
         }
+        // nothing to write (a read-only mix): a store the compiler cannot rule out keeps the loads alive; the probe's
+        // inputs never hold the pattern, so nothing is ever stored (the address is the thread's own element of input 0)
+        if (NO == 0 && (x.x ^ x.y) == 0x9e3779b9u && x.z == 0x7f4a7c15u) const_cast<uint4*>(a.in[0])[i] = x;
     }
 }
 
@@ -142,6 +145,7 @@ template <int NI>
 static hipError_t stream_dispatch(const StreamArgs& a, int n_out, size_t n, dim3 grid, hipStream_t st)
 {
     switch (n_out) {
+    case 0: hipLaunchKernelGGL((stream_probe_kernel<NI, 0>), grid, dim3(256), 0, st, a, n); break;
     case 1: hipLaunchKernelGGL((stream_probe_kernel<NI, 1>), grid, dim3(256), 0, st, a, n); break;
     case 2: hipLaunchKernelGGL((stream_probe_kernel<NI, 2>), grid, dim3(256), 0, st, a, n); break;
     case 3: hipLaunchKernelGGL((stream_probe_kernel<NI, 3>), grid, dim3(256), 0, st, a, n); break;

@@ -428,7 +428,8 @@ def test_stream_probe_argument_errors(L):
     outs = (vp * 3)(A + 4 * SZ, A + 5 * SZ, A + 6 * SZ)
     assert f(ins, 0, outs, 3, 1024, None) == -2
     assert f(ins, 5, outs, 3, 1024, None) == -2
-    assert f(ins, 4, outs, 0, 1024, None) == -2
+    assert f(ins, 4, outs, -1, 1024, None) == -2          # (0 outputs is a read-only mix: allowed)
+    assert f(ins, 4, outs, 5, 1024, None) == -2
     assert f(ins, 4, outs, 3, 0, None) == 0
     assert f(None, 4, outs, 3, 1024, None) == -1
     assert f(ins, 4, outs, 3, 1000, None) == -5
