@@ -129,7 +129,7 @@ def _opt_state(S, B, H, dk, dv):
 
 
 def fwd_state(Q, K, V, S_in=None):
-    """(O, S_out) with the running state started at S_in (zero if None): segment-wise processing, Sec. 5.2."""
+    """(O, S_out) with the running state started at S_in (zero if None): segment-wise processing, Sec. 5.3."""
     Q, K, V = _f64(Q), _f64(K), _f64(V)
     B, H, N, dk, dv = _shapes(Q, K, V)
     S_in, p_in = _opt_state(S_in, B, H, dk, dv)

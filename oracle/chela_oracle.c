@@ -172,7 +172,7 @@ void chela_oracle_bwd_recurrent(const double *Q, const double *K, const double *
 }
 
 /* ==========================================================================
- * State carry-in / carry-out (segment-wise processing, Sec. 5.2 and App. A:
+ * State carry-in / carry-out (segment-wise processing, Sec. 5.3 and App. A:
  * training data is split into segments of consecutive chunks and test data
  * is processed segment by segment).  The running state of the recurrent form
  * is the only thing one segment hands to the next:
