@@ -129,7 +129,7 @@ int chela_linattn_bwd_bnhd(const void *Q, const void *K, const void *V, const vo
                            void *dQ, void *dK, void *dV,
                            int B, int H, int N, int dk, int dv, int chunk, void *stream);
 
-/* ---- carried state (segment-wise processing, Sec. 5.2 / App. A: sequences are cut into segments that are
+/* ---- carried state (segment-wise processing, Sec. 5.3 / App. A: sequences are cut into segments that are
  * processed one after the other; the running d_k x d_v state is all one segment hands to the next) ------------
  * Same maps as above, bf16 I/O, with the state made explicit.  States are fp32, [B, H, dk, dv], 16-byte aligned.
  *   forward : S_0 = S_in (NULL: zero);  O_t = q_t . (S_in + sum_{s<=t} k_s v_s^T);  S_out = S_in + sum_s k_s v_s^T
