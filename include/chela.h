@@ -267,7 +267,7 @@ int chela_shortlong_conv_fwd_f32(const void *X, const float *w_short, int m, con
  *     du = dv * silu'(u),  dX[t] = sum_j w_short[j] du[t+j]         ([B,d,L] out, I/O dtype)
  *     d_w_short[c,j] = sum_b sum_t du[b,c,t] X[b,c,t-j]             ([d,m] fp32 out, overwritten)
  * Nothing is saved by the forward call: u and v are recomputed from X.  With w_short = NULL (no short stage) dX = dv,
- * v = X and d_w_short is ignored.  The backward supports m <= 16 taps.  Scratch (library workspace):
+ * v = X and d_w_short is ignored.  m <= 32 as in the forward.  Scratch (library workspace):
  * chela_shortlong_conv_bwd_workspace_bytes().  Sums over batch and time are taken in a fixed order (deterministic). */
 int chela_shortlong_conv_bwd(const void *X, const float *w_short, int m, const void *spectrum, const void *dZ,
                              void *dX, float *d_w_short, float *d_k_long, int B, int d, int L, void *stream);

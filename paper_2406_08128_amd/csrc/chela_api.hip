@@ -875,7 +875,7 @@ static size_t conv_bwd_ws_bytes(int B, int d, int L, int dtype, bool has_short)
     if (!has_short) return acc;
     const size_t n = (size_t)B * d * L, tiles = ((size_t)L + 2047) / 2048;
     (void)dtype;
-    return acc + n * sizeof(float) + (size_t)B * d * tiles * 16 * sizeof(float);
+    return acc + n * sizeof(float) + (size_t)B * d * tiles * 32 * sizeof(float);
 }
 
 size_t chela_shortlong_conv_bwd_workspace_bytes(int B, int d, int L, int has_short_kernel, int dtype)
@@ -889,7 +889,7 @@ static int shortlong_bwd_common(const void* X, const float* w_short, int m, cons
                                 void* stream)
 {
     if (B < 0 || d < 0 || L < 0) return CHELA_ERR_BAD_SHAPE;
-    if (w_short != nullptr && (m < 1 || m > 16)) return CHELA_ERR_BAD_SHAPE;      // the backward keeps <= 16 tap sums
+    if (w_short != nullptr && (m < 1 || m > 32)) return CHELA_ERR_BAD_SHAPE;
     if (B > 65535) return CHELA_ERR_BAD_SHAPE;                                    // batch entries ride on grid.y
     if ((unsigned long long)B * (unsigned long long)d > 0x7fffffffull) return CHELA_ERR_BAD_SHAPE;
     if (d == 0 || L == 0) return CHELA_OK;

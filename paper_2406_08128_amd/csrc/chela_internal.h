@@ -116,7 +116,7 @@ int conv_fft_size(int L);
 hipError_t launch_longconv_spectrum(const float* k, void* Kf, int d, int L, hipStream_t st);
 hipError_t launch_shortlong_conv(const void* X, const float* w_short, int m, const void* Kf, void* Y, long BD, int d,
                                  int L, int dtype, hipStream_t st);
-// Gradient: dX [B][d][L] (I/O dtype), dw [d][m] (only with a short kernel, m <= 16), dk [d][L] fp32.
+// Gradient: dX [B][d][L] (I/O dtype), dw [d][m] (only with a short kernel, m <= 32), dk [d][L] fp32.
 // ws: conv_bwd_acc_floats(B, d, L) floats (running sums of the long-kernel gradient: at the largest transform size
 // they no longer fit the registers of 1024 threads, and workgroups that share a channel leave their shares there), then, with a short kernel, B*d*L floats (dV) and the workgroups' tap
 // sums.

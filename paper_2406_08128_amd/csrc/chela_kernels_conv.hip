@@ -745,15 +745,18 @@ __global__ __launch_bounds__(conv_threads(M)) void longconv_bwd_kernel(const IO*
 // (a run may cross from one sequence into the next); x is staged with MT steps of history and dU with MT steps of
 // look-ahead.  Each workgroup leaves its share of the tap sums in `part` ([d][n_share][MT]); shortconv_dw_kernel
 // adds the shares of a channel in a fixed order.
-constexpr int kShortTile = 2048, kShortMaxTaps = 16, kShortTilesPerWg = 4;
+constexpr int kShortTile = 2048, kShortMaxTaps = 32, kShortTilesPerWg = 4;
 
-// TAPS: compile-time bound on the number of taps (m <= TAPS <= 16): the tap loops are as long as the kernel needs.
+// TAPS: compile-time bound on the number of taps (m <= TAPS <= 32): the tap loops are as long as the kernel needs.
+// Up to 16 taps every count has its own instantiation (the paper's sizes, 3 and 2 log10 L + 1, stay below 16 for any
+// L up to 10^7) with 16 steps of history and look-ahead; longer kernels share one with 32.
 template <typename IO, int TAPS>
 __global__ __launch_bounds__(256) void shortconv_bwd_kernel(const IO* __restrict__ X, const float* __restrict__ w_short,
                                                            int m, const float* __restrict__ dV, IO* __restrict__ dX,
                                                            float* __restrict__ part, int B, int d, int L, int n_share)
 {
-    constexpr int TL = kShortTile, MT = kShortMaxTaps, H = MT;       // H: halo on either side
+    constexpr int TL = kShortTile, MT = TAPS <= 16 ? 16 : 32, H = MT;  // H: halo on either side
+    constexpr int NX = MT + 8;                                        // inputs behind eight consecutive outputs
     __shared__ __attribute__((aligned(16))) float sx[TL + 2 * H];      // x[t0 - H .. t0 + TL + H)
     __shared__ __attribute__((aligned(16))) float su[TL + H + 8];      // dU[t0 .. t0 + TL + H) (+ slack for 16-byte reads)
     __shared__ float red[MT][4];
@@ -779,12 +782,12 @@ __global__ __launch_bounds__(256) void shortconv_bwd_kernel(const IO* __restrict
         *reinterpret_cast<float4*>(sx + 8 * i8 + 4) = make_float4(xv[4], xv[5], xv[6], xv[7]);
     }
     __syncthreads();
-    // each thread takes 8 consecutive steps: the 24 inputs they need are read once, as six 16-byte LDS reads
+    // each thread takes 8 consecutive steps: the MT + 8 inputs they need are read once, as 16-byte LDS reads
     {
         const int i0 = 8 * tid;                         // TL = 8 * 256
-        float xs[24];                                   // x[t0 + i0 - 16 .. t0 + i0 + 8)
+        float xs[NX];                                   // x[t0 + i0 - MT .. t0 + i0 + 8)
 #pragma unroll
-        for (int r = 0; r < 6; ++r) {
+        for (int r = 0; r < NX / 4; ++r) {
             const float4 v = *reinterpret_cast<const float4*>(sx + i0 + 4 * r);      // sx index of x[t0 + i] is H + i
             xs[4 * r] = v.x; xs[4 * r + 1] = v.y; xs[4 * r + 2] = v.z; xs[4 * r + 3] = v.w;
         }
@@ -802,7 +805,7 @@ __global__ __launch_bounds__(256) void shortconv_bwd_kernel(const IO* __restrict
         for (int e = 0; e < 8; ++e) {
             float u = 0.f;
 #pragma unroll
-            for (int j = 0; j < TAPS; ++j) u = fmaf(wreg[j], xs[16 + e - j], u);
+            for (int j = 0; j < TAPS; ++j) u = fmaf(wreg[j], xs[MT + e - j], u);
             const float sg = __builtin_amdgcn_rcpf(1.f + __expf(-u));
             du8[e] = tc + e < L ? g8[e] * sg * (1.f + u * (1.f - sg)) : 0.f;
         }
@@ -822,9 +825,9 @@ __global__ __launch_bounds__(256) void shortconv_bwd_kernel(const IO* __restrict
     __syncthreads();
     {
         const int i0 = 8 * tid;                         // TL = 8 * 256
-        float xs[24], ds[24];                           // x as above; dU[t0 + i0 .. t0 + i0 + 24)
+        float xs[NX], ds[NX];                           // x as above; dU[t0 + i0 .. t0 + i0 + MT + 8)
 #pragma unroll
-        for (int r = 0; r < 6; ++r) {
+        for (int r = 0; r < NX / 4; ++r) {
             const float4 v = *reinterpret_cast<const float4*>(sx + i0 + 4 * r);
             xs[4 * r] = v.x; xs[4 * r + 1] = v.y; xs[4 * r + 2] = v.z; xs[4 * r + 3] = v.w;
             const float4 g = *reinterpret_cast<const float4*>(su + i0 + 4 * r);
@@ -837,7 +840,7 @@ __global__ __launch_bounds__(256) void shortconv_bwd_kernel(const IO* __restrict
 #pragma unroll
             for (int j = 0; j < TAPS; ++j) {
                 dx = fmaf(wreg[j], ds[e + j], dx);
-                acc[j] = fmaf(ds[e], xs[16 + e - j], acc[j]);
+                acc[j] = fmaf(ds[e], xs[MT + e - j], acc[j]);
             }
             dx8[e] = dx;
         }
@@ -858,7 +861,8 @@ __global__ __launch_bounds__(256) void shortconv_bwd_kernel(const IO* __restrict
         if ((tid & 63) == 0) red[j][tid >> 6] = v;
     }
     __syncthreads();
-    if (tid < TAPS) part[((long)c * n_share + share) * MT + tid] = red[tid][0] + red[tid][1] + red[tid][2] + red[tid][3];
+    if (tid < TAPS)
+        part[((long)c * n_share + share) * kShortMaxTaps + tid] = red[tid][0] + red[tid][1] + red[tid][2] + red[tid][3];
 }
 
 __global__ __launch_bounds__(64) void shortconv_dw_kernel(const float* __restrict__ part, float* __restrict__ dw, int m,
@@ -1028,7 +1032,7 @@ static hipError_t conv_bwd_impl(const IO* X, const float* w_short, int m, const 
     const long n_items = (long)B * ((L + kShortTile - 1) / kShortTile);                     // (batch entry, tile) pairs
     const int n_share = (int)((n_items + kShortTilesPerWg - 1) / kShortTilesPerWg);         // workgroups per channel
     if ((long)d * n_share > 0x7fffffffL) return hipErrorInvalidValue;
-    float* ws_part = ws + (size_t)BD * L;                                   // [d][n_share][16] (room for [d][B * tiles][16])
+    float* ws_part = ws + (size_t)BD * L;                                   // [d][n_share][32] (room for [d][B * tiles][32])
     if ((e = conv_longbwd_dispatch<IO, float>(X, w_short, m, Kf, dZ, ws_dV, dk, acc_ws, B, d, L, st)) != hipSuccess) return e;
     {
         ProfScope prof(KID_CONV_SHORT_BWD, st);
@@ -1043,7 +1047,10 @@ static hipError_t conv_bwd_impl(const IO* X, const float* w_short, int m, const 
             CHELA_SHORT_BWD(1) CHELA_SHORT_BWD(2) CHELA_SHORT_BWD(3) CHELA_SHORT_BWD(4) CHELA_SHORT_BWD(5) CHELA_SHORT_BWD(6)
             CHELA_SHORT_BWD(7) CHELA_SHORT_BWD(8) CHELA_SHORT_BWD(9) CHELA_SHORT_BWD(10) CHELA_SHORT_BWD(11)
             CHELA_SHORT_BWD(12) CHELA_SHORT_BWD(13) CHELA_SHORT_BWD(14) CHELA_SHORT_BWD(15) CHELA_SHORT_BWD(16)
-            default: return hipErrorInvalidValue;
+            default:
+                if (m < 17 || m > kShortMaxTaps) return hipErrorInvalidValue;
+                hipLaunchKernelGGL((shortconv_bwd_kernel<IO, 32>), grid, dim3(256), 0, st, X, w_short, m, ws_dV, dX, ws_part,
+                                   B, d, L, n_share);
         }
 #undef CHELA_SHORT_BWD
         if ((e = hipGetLastError()) != hipSuccess) return e;
@@ -1053,7 +1060,7 @@ static hipError_t conv_bwd_impl(const IO* X, const float* w_short, int m, const 
     return hipSuccess;
 }
 
-// Backward of Z = K_l(silu(K_s X)): dX (I/O dtype), dw [d][m] (with a short kernel, m <= 16), dk [d][L] fp32.
+// Backward of Z = K_l(silu(K_s X)): dX (I/O dtype), dw [d][m] (with a short kernel, m <= 32), dk [d][L] fp32.
 hipError_t launch_shortlong_conv_bwd(const void* X, const float* w_short, int m, const void* Kf, const void* dZ,
                                      void* dX, float* dw, float* dk, float* ws, int B, int d, int L, int dtype,
                                      hipStream_t st)

@@ -213,21 +213,21 @@ def test_conv_bwd_argument_errors(L):
     g, wsb = L.chela_shortlong_conv_bwd, L.chela_shortlong_conv_bwd_workspace_bytes
     X, W, S, dZ, dX, dW, dK = A, A + SZ, A + 2 * SZ, A + 3 * SZ, A + 4 * SZ, A + 5 * SZ, A + 6 * SZ
     # one sequence: a single workgroup per channel, no shares of the long-kernel gradient to keep
-    assert wsb(1, 4, 100, 1, 0) == 1 * 4 * (100 * 4 + 64) and wsb(1, 4, 100, 1, 1) == 1 * 4 * (100 * 4 + 64)
+    assert wsb(1, 4, 100, 1, 0) == 1 * 4 * (100 * 4 + 128) and wsb(1, 4, 100, 1, 1) == 1 * 4 * (100 * 4 + 128)
     assert wsb(1, 4, 100, 0, 0) == 0 and wsb(2, 4, 100, 1, 7) == 0
     # few channels: the sequences are dealt out to G workgroups per channel (G = 2 here, at most the batch size), each
     # leaving d * (M/2 + 1) pairs of sums
     assert wsb(2, 4, 100, 0, 0) == 2 * 4 * 129 * 16
-    assert wsb(2, 4, 100, 1, 0) == 2 * 4 * 129 * 16 + 2 * 4 * (100 * 4 + 64)
+    assert wsb(2, 4, 100, 1, 0) == 2 * 4 * 129 * 16 + 2 * 4 * (100 * 4 + 128)
     # enough channels to fill the GPU: one workgroup per channel again
     assert wsb(8, 16384, 100, 0, 0) == 0
     # at the largest transform size the running sums live in the workspace whatever G is
     assert wsb(1, 4, 16000, 0, 0) == 4 * 8193 * 16
     assert wsb(2, 4, 16000, 0, 0) == 2 * 4 * 8193 * 16
-    assert wsb(2, 4, 16000, 1, 0) == 2 * 4 * 8193 * 16 + 2 * 4 * (16000 * 4 + 8 * 64)
+    assert wsb(2, 4, 16000, 1, 0) == 2 * 4 * 8193 * 16 + 2 * 4 * (16000 * 4 + 8 * 128)
     assert g(None, W, 9, S, dZ, dX, dW, dK, 2, 4, 100, None) == -1
     assert g(X, W, 9, S, dZ, dX, None, dK, 2, 4, 100, None) == -1
-    assert g(X, W, 17, S, dZ, dX, dW, dK, 2, 4, 100, None) == -2          # the backward keeps at most 16 tap sums
+    assert g(X, W, 33, S, dZ, dX, dW, dK, 2, 4, 100, None) == -2          # at most 32 taps, as in the forward
     assert g(X, W, 9, S, dZ, dX, dW, dK, 2, 4, 20000, None) == -2
     assert g(X, W, 9, S, dZ, X, dW, dK, 2, 4, 100, None) == -6
     assert g(X, W, 9, S, dZ, dX, dW, dX, 2, 4, 100, None) == -6

@@ -890,7 +890,8 @@ def _run_conv_bwd_case(B, d, L, m, dtype, seed, short=True):
 @pytest.mark.parametrize("shape", [(1, 1, 1, 1), (2, 3, 7, 3), (1, 2, 255, 9), (2, 2, 257, 5), (3, 2, 1000, 9),
                                    (1, 2, 2049, 16), (2, 2, 4096, 9), (1, 2, 5000, 9), (2, 1, 16384, 9),
                                    (1, 2, 300, 4), (1, 2, 300, 8), (1, 2, 300, 12), (1, 2, 300, 13)]
-                         + [(2, 2, 2100, m) for m in range(1, 17)])       # every tap count has its own kernel
+                         + [(2, 2, 2100, m) for m in range(1, 17)]        # every tap count up to 16 has its own kernel
+                         + [(2, 2, 2100, 17), (1, 2, 4100, 24), (2, 1, 300, 32), (1, 2, 5000, 32)])   # longer ones share one
 def test_shortlong_conv_bwd_f32(shape):
     B, d, L, m = shape
     _run_conv_bwd_case(B, d, L, m, "f32", seed=L + 10)
