@@ -269,6 +269,32 @@ def test_single_segment_backward_checkpoints_its_walk(shape, monkeypatch):
             _check("d_affine[%d]" % q, dA[q], rA[q], "bf16")
 
 
+@pytest.mark.parametrize("mode", ["0", "1", "2"])
+def test_scan_in_a_kernel_of_its_own_or_folded_into_the_sweeps(mode, monkeypatch):
+    # the segment totals are added up by a scan kernel (0), by the forward sweep's workgroups (1) or by both sweeps'
+    # (2, the default where the states are small): every variant against the oracle, all entry points that share it
+    monkeypatch.setenv("CHELA_FOLD_SCAN", mode)
+    for B, H, N, dk, dv in ((2, 3, 7000, 64, 64), (1, 4, 5000, 64, 128), (1, 2, 6100, 128, 64)):
+        w = shrink(WORKLOADS["lm_bf16"], B=B, H=H, N=N, dk=dk, dv=dv, seed=500 + N)
+        x, gx = make_inputs(w, with_dO=True), make_gate_inputs(w)
+        d, gd = _dev(x), _dev(gx)
+        O = binding.chela_linattn_fwd(d["Q"], d["K"], d["V"])
+        g1 = binding.chela_linattn_bwd(d["Q"], d["K"], d["V"], d["dO"])
+        O2, saved = binding.chela_linattn_fwd_save(d["Q"], d["K"], d["V"])
+        g2 = binding.chela_linattn_bwd_saved(d["Q"], d["K"], d["V"], d["dO"], saved)
+        Y, _, _ = binding.chela_linattn_fwd_gated(d["Q"], d["K"], d["V"], gd["G"], EPS)
+        torch.cuda.synchronize()
+        print("\nfold mode %s, shape %s" % (mode, (B, H, N, dk, dv)), flush=True)
+        Qn, Kn, Vn, dOn, Gn = (to_f64_numpy(t) for t in (x["Q"], x["K"], x["V"], x["dO"], gx["G"]))
+        rO, rg = oracle.fwd_recurrent(Qn, Kn, Vn), oracle.bwd_recurrent(Qn, Kn, Vn, dOn)
+        _check("O", O, rO, "bf16")
+        _check("O(save)", O2, rO, "bf16")
+        for name, a, b2, r in zip(("dQ", "dK", "dV"), g1, g2, rg):
+            _check(name, a, r, "bf16")
+            _check(name + "(saved)", b2, r, "bf16")
+        _check("Y", Y, oracle_layer.gate_norm_fwd(rO, Gn, EPS), "bf16")
+
+
 def test_training_pair_scratch_sized_by_its_own_query():
     # 96 (b,h) pairs of 16384 tokens: the training pair's forward cuts each sequence 16 times, the plain forward 5
     w = shrink(WORKLOADS["lm_bf16"], B=8, H=12, N=16384, seed=63)
