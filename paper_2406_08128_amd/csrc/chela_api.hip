@@ -40,15 +40,21 @@ static long sweep_slots(int dk, int dv, int chunk, int dtype, bool is_bwd)
 // read and written by the scan and read by the sweep), too few leave compute units idle, and a workgroup count just
 // above a multiple of what the GPU holds at once wastes most of a round.  The plan minimises a small cost model, in
 // units of one chunk step of one workgroup on a full GPU:
-//     sweep  = (full rounds + g(fill of the last round)) * (chunks per segment + 0.5)
-//     states = segments * heads * w
+//     sweep  = (full rounds + g(fill of the last round)) * (chunks per segment + 0.5) * (1 + 0.09 (rounds - 1))
+//     states = segments * heads * w   (+ 2 when there are too many segments for the sweeps to add the totals up
+//                                        themselves: then the scan is a kernel of its own)
 // g() says that a sparsely filled last round runs its workgroups faster, but not proportionally (and not at all when
 // a compute unit only ever holds one workgroup: then nothing hides that workgroup's latencies); w is the measured
-// cost of one more segment state relative to a chunk step.  With 256 or more (b,h) pairs one workgroup per pair keeps
+// cost of one more segment state relative to a chunk step.  The factor on several rounds is measured too: at 48
+// (b,h) pairs of 32768 and 65536 tokens, one round of 480 long-lived workgroups beat two rounds of 480 by 7 .. 10 %
+// and three rounds of 512 by 13 .. 19 %, forward and backward alike (fewer, longer streams; no tail in which the
+// last round's stragglers have the GPU to themselves).  Segments longer than max_cps chunks are not considered
+// (see make_plan), a single segment always is.  With single_from or more (b,h) pairs one workgroup per pair keeps
 // every unit busy and the pre-pass (which re-reads K and V) disappears altogether, so no segmentation is used.
-static long choose_segments(long BH, long n_chunks, long slots, double g_min, double w_state)
+static long choose_segments(long BH, long n_chunks, long slots, double g_min, double w_state, long max_cps,
+                            long max_folded_segments, long single_from)
 {
-    if (BH >= 256 || n_chunks <= 4) return 1;
+    if (BH >= single_from || n_chunks <= 4) return 1;
     long best = 1;
     double best_cost = 1e300;
     // at least 4 chunks per segment -- unless the whole problem fits the GPU at once even with one workgroup per chunk:
@@ -59,13 +65,17 @@ static long choose_segments(long BH, long n_chunks, long slots, double g_min, do
         const long cps = (n_chunks + n - 1) / n;
         const long real_n = (n_chunks + cps - 1) / cps;
         if (real_n != n) continue;                                 // same split as a smaller n
+        if (n > 1 && max_cps > 0 && cps > max_cps) continue;
         const long wgs = BH * n;
         const long full = wgs / slots;
         const double f = (double)(wgs - full * slots) / (double)slots;
         double g = 0.0;
         if (f > 0.0) { g = f / 0.75; if (g > 1.0) g = 1.0; if (g < g_min) g = g_min; }
-        double cost = ((double)full + g) * ((double)cps + 0.5) + (double)(n * BH) * w_state;
+        const long rounds = full + (f > 0.0 ? 1 : 0);
+        double cost = ((double)full + g) * ((double)cps + 0.5) * (1.0 + 0.09 * (double)(rounds - 1))
+                    + (double)(n * BH) * w_state;
         if (n > 1) cost += 0.5 * (double)(n_chunks * BH) / (double)slots + 3.0;   // pre-pass re-read + two more launches
+        if (n > 1 && n > max_folded_segments) cost += 2.0;                        // the scan as a kernel of its own
         if (cost < best_cost) { best_cost = cost; best = n; }
     }
     return best;
@@ -82,7 +92,18 @@ Plan make_plan(long BH, int N, int dk, int dv, int chunk, int dtype, bool is_bwd
     // one more state costs about 48 KB (fp32, 64 x 64) of traffic spread over the whole GPU; a chunk step moves
     // 32 KB (forward) or 56 KB (backward) per resident workgroup
     const double w_state = (is_bwd ? 0.0019 : 0.0033) * ((double)dk * dv / 4096.0) * (512.0 / (double)slots);
-    long n_seg = choose_segments(BH, n_chunks, slots, slots > 256 ? 0.55 : 1.0, w_state);
+    const long max_walk = kMaxBwdWalkTokens / chunk;
+    const bool walk_capped = is_bwd && dtype == CHELA_DTYPE_BF16;
+    const long max_folded = stateful ? 0 : (long)(kMaxFoldedStateBytes / (p.state_elems * sizeof(float)));
+    // A forward workgroup runs faster with fewer neighbours (the GPU's bandwidth is what it shares); a backward
+    // workgroup does not: its chunk step took 5.0 .. 5.1 us with 192, 384 and 480 workgroups on the GPU alike
+    // (192 sequences of 16384 tokens: one segment each 1307 us, two 839 us).
+    // So 256 sequences, one workgroup per unit, still gain from two segments each in the backward (250 sequences of
+    // 4096 tokens: 272 us against 337 us), while the forward is at its best there with one.
+    const bool lone_is_slow = is_bwd && dtype == CHELA_DTYPE_BF16;
+    const double g_min = (slots > 256 && !lone_is_slow) ? 0.55 : 1.0;
+    long n_seg = choose_segments(BH, n_chunks, slots, g_min, w_state, walk_capped ? max_walk : 0, max_folded,
+                                 lone_is_slow && slots > 256 ? 257 : 256);
     long cps = (n_chunks + n_seg - 1) / n_seg;
     const int forced = env_int("CHELA_SEG_TOKENS", 0);
     if (forced > 0) cps = (forced + chunk - 1) / chunk;
@@ -96,8 +117,7 @@ Plan make_plan(long BH, int N, int dk, int dv, int chunk, int dtype, bool is_bwd
     // is therefore never longer than kMaxBwdWalkTokens (1.2e-3 by the same law): a single segment whose sweep builds
     // the state itself drops copies of it on the way forward and picks them up on the way back; every other plan
     // gets shorter segments (more states to scan, nothing else).
-    const long max_walk = kMaxBwdWalkTokens / chunk;
-    if (is_bwd && dtype == CHELA_DTYPE_BF16 && cps > max_walk) {
+    if (walk_capped && cps > max_walk) {
         if (cps >= n_chunks && !stateful && can_checkpoint) p.ckpt_every = (int)max_walk;
         else if (forced <= 0) cps = max_walk;
     }
@@ -126,6 +146,16 @@ TrainPlans make_train_plans(long BH, int N, int dk, int dv, int chunk)
     t.fwd = make_plan(BH, N, dk, dv, cb, CHELA_DTYPE_BF16, false, false);   // both calls tile with the same chunk
     t.save_every = 1;
     if (BH <= 0 || N <= 0) return t;
+    // 256 sequences: the plain backward gains from cutting each in two; the pair gains less, since its backward has
+    // no pre-pass to lose and its forward pays for the cut -- 3 % with 64 x 64 states, and with larger states it
+    // loses 6 % (32 x 8 sequences of 4096 tokens, 64 x 128: 492 us uncut, 524 us cut)
+    const long n_chunks = ((long)N + cb - 1) / cb;
+    if (BH >= 256 && !(dk == 64 && dv == 64) && t.bwd.n_seg > 1 && n_chunks * cb <= kMaxBwdWalkTokens &&
+        env_int("CHELA_SEG_TOKENS", 0) <= 0) {
+        t.bwd.seg_len = (int)(n_chunks * cb);
+        t.bwd.n_seg = 1;
+        t.bwd.ckpt_every = 0;
+    }
     const long cps_b = t.bwd.seg_len / cb;             // chunks per backward segment
     const double want = (double)t.fwd.n_seg / (double)t.bwd.n_seg;
     long best = 1;

@@ -19,6 +19,10 @@ struct Plan {
                          // ckpt_every chunks and its walk back picks those copies up again (0: none needed)
 };
 
+// The sweeps add the segment totals up themselves (no scan kernel) while one (b,h) pair's totals stay below this:
+// every workgroup re-reads, on average, half of them from the L2.
+constexpr size_t kMaxFoldedStateBytes = (size_t)256 << 10;
+
 // Checkpoints of a single-segment backward: how many, and where they live ([BH][n][dk*dv] fp32 at the workspace's start).
 inline long plan_n_ckpt(const Plan& p, int N)
 {

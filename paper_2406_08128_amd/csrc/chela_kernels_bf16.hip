@@ -1552,7 +1552,7 @@ static int prepass_reverse()
 static bool fold_scan(const Plan& plan, bool stateful, bool is_bwd = false)
 {
     if (stateful || plan.n_seg < 2) return false;
-    if ((size_t)plan.n_seg * plan.state_elems * sizeof(float) > ((size_t)256 << 10)) return false;
+    if ((size_t)plan.n_seg * plan.state_elems * sizeof(float) > kMaxFoldedStateBytes) return false;
     const char* e = getenv("CHELA_FOLD_SCAN");
     const int mode = e ? atoi(e) : 2;          // 0: never, 1: forward calls only, 2: forward and backward calls
     return is_bwd ? mode >= 2 : mode >= 1;

@@ -3,7 +3,8 @@
     python -m paper_2406_08128_amd.profile_summary stats   <dir>/..._kernel_stats.csv  --command "<full command>" --title "..."
     python -m paper_2406_08128_amd.profile_summary traffic --fetch <csv> --write <csv> --kernel bf16_bwd_sweep_kernel \
                                                             --copy-mib 1024 --command "..." --title "..."
-    python -m paper_2406_08128_amd.profile_summary counters <..._counter_collection.csv> --command "..." --title "..."
+    python -m paper_2406_08128_amd.profile_summary counters <..._counter_collection.csv>... --command "..." --title "..."
+    python -m paper_2406_08128_amd.profile_summary stats-multi --section NAME CSV [--section NAME CSV ...] --command "..." --title "..."
 
 Every summary starts with the commit and the hash of the kernel sources it was taken on (bench.py quotes a summary's
 figures only while that hash is the tree's), the title and the command, and prints kernel names with their template
@@ -36,10 +37,15 @@ def demangle(name: str) -> str:
             rest = rest[1:]
             while True:
                 a = re.match(r"L([ib])(\d+)E", rest)
-                if not a:
+                if a:
+                    args.append(a.group(2) if a.group(1) == "i" else ("true" if a.group(2) == "1" else "false"))
+                    rest = rest[a.end():]
+                    continue
+                t = re.match(r"DF16b|f", rest)           # type arguments: bfloat16, float
+                if not t:
                     break
-                args.append(a.group(2) if a.group(1) == "i" else ("true" if a.group(2) == "1" else "false"))
-                rest = rest[a.end():]
+                args.append("bf16" if t.group(0) == "DF16b" else "float")
+                rest = rest[t.end():]
         return ident + ("<%s>" % ", ".join(args) if args else "")
     if n.startswith("_Z"):
         try:
@@ -48,6 +54,7 @@ def demangle(name: str) -> str:
             pass
     n = re.sub(r"^void ", "", n)
     n = n.replace("chela::", "")
+    n = n.replace("bool _Accum", "bf16")      # (how rocprofv3's own demangler prints the bfloat16 type)
     depth, out = 0, []
     for ch in n:                       # cut the parameter list: the first '(' outside template brackets
         if ch == "<":
@@ -75,31 +82,49 @@ def header(title: str, command: str) -> str:
 
 
 def cmd_stats(a):
-    rows = []
+    print(header(a.title, a.command))
+    print("Source: %s (the library's kernels only)\n" % a.csv)
+    print(_stats_table(a.csv))
+    print()
     for r in csv.DictReader(open(a.csv)):
+        if "chela" in r["Name"]:
+            print("avg_ns[%s]: %.0f" % (demangle(r["Name"]).split("<")[0], float(r["AverageNs"])))
+    if a.note:
+        print("\n" + a.note)
+
+
+def _stats_table(path):
+    rows = []
+    for r in csv.DictReader(open(path)):
         if "chela" not in r["Name"]:
             continue
         rows.append((demangle(r["Name"]), int(r["Calls"]), int(r["TotalDurationNs"]), float(r["AverageNs"]),
                      int(r["MinNs"]), int(r["MaxNs"])))
     tot = sum(x[2] for x in rows) or 1
+    out = ["%-62s %6s %12s %10s %7s %9s %9s" % ("kernel", "calls", "total_ns", "avg_ns", "share", "min_ns", "max_ns")]
+    for x in sorted(rows, key=lambda x: -x[2]):
+        out.append("%-62s %6d %12d %10.0f %6.1f%% %9d %9d" % (x[0], x[1], x[2], x[3], 100.0 * x[2] / tot, x[4], x[5]))
+    return "\n".join(out)
+
+
+def cmd_stats_multi(a):
+    """Several runs of one command pattern in one summary: --section "ARGS or name" CSV, repeated."""
     print(header(a.title, a.command))
-    print("Source: %s (the library's kernels only)\n" % a.csv)
-    print("%-62s %6s %12s %10s %7s %9s %9s" % ("kernel", "calls", "total_ns", "avg_ns", "share", "min_ns", "max_ns"))
-    for x in sorted(rows, key=lambda x: -x[2]):
-        print("%-62s %6d %12d %10.0f %6.1f%% %9d %9d" % (x[0], x[1], x[2], x[3], 100.0 * x[2] / tot, x[4], x[5]))
-    print()
-    for x in sorted(rows, key=lambda x: -x[2]):
-        print("avg_ns[%s]: %.0f" % (x[0].split("<")[0], x[3]))
+    for name, path in a.section:
+        print("== %s   (%s)" % (name, path))
+        print(_stats_table(path))
+        print()
     if a.note:
-        print("\n" + a.note)
+        print(a.note)
 
 
-def _means(path):
+def _means(*paths):
     agg = collections.defaultdict(lambda: collections.defaultdict(list))
-    for r in csv.DictReader(open(path)):
-        if "chela" not in r["Kernel_Name"]:
-            continue
-        agg[demangle(r["Kernel_Name"])][r["Counter_Name"]].append(float(r["Counter_Value"]))
+    for path in paths:
+        for r in csv.DictReader(open(path)):
+            if "chela" not in r["Kernel_Name"]:
+                continue
+            agg[demangle(r["Kernel_Name"])][r["Counter_Name"]].append(float(r["Counter_Value"]))
     return {k: {c: sum(v) / len(v) for c, v in d.items()} for k, d in agg.items()}
 
 
@@ -136,13 +161,21 @@ def cmd_traffic(a):
 
 
 def cmd_counters(a):
-    m = _means(a.csv)
+    m = _means(*a.csv)
     cols = sorted({c for d in m.values() for c in d})
     print(header(a.title, a.command))
-    print("Mean per dispatch:\n")
-    print("%-62s " % "kernel" + " ".join("%28s" % c for c in cols))
-    for k in sorted(m):
-        print("%-62s " % k + " ".join("%28.4e" % m[k].get(c, float("nan")) for c in cols))
+    if len(cols) > 5:      # many counters: one kernel per block, one counter per line
+        for k in sorted(m):
+            print("Mean per dispatch of %s:" % k)
+            for c in cols:
+                if c in m[k]:
+                    print("  %-28s %18.0f" % (c, m[k][c]))
+            print()
+    else:
+        print("Mean per dispatch:\n")
+        print("%-62s " % "kernel" + " ".join("%28s" % c for c in cols))
+        for k in sorted(m):
+            print("%-62s " % k + " ".join("%28.4e" % m[k].get(c, float("nan")) for c in cols))
     if a.kernel:
         dom = [k for k in sorted(m) if k.startswith(a.kernel)]
         if dom and "SQ_INSTS_VALU_MFMA_MOPS_BF16" in m[dom[0]]:
@@ -161,15 +194,17 @@ def cmd_counters(a):
 def main():
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
     sub = ap.add_subparsers(dest="what", required=True)
-    for name in ("stats", "traffic", "counters"):
+    for name in ("stats", "stats-multi", "traffic", "counters"):
         p = sub.add_parser(name)
         p.add_argument("--title", required=True)
         p.add_argument("--command", required=True)
         p.add_argument("--note", default="")
         if name == "stats":
             p.add_argument("csv")
+        elif name == "stats-multi":
+            p.add_argument("--section", nargs=2, action="append", required=True, metavar=("NAME", "CSV"))
         elif name == "counters":
-            p.add_argument("csv")
+            p.add_argument("csv", nargs="+")
             p.add_argument("--kernel", default="")
         else:
             p.add_argument("--fetch", required=True)
@@ -177,7 +212,7 @@ def main():
             p.add_argument("--kernel", required=True)
             p.add_argument("--copy-mib", type=int, default=1024)
     a = ap.parse_args()
-    {"stats": cmd_stats, "traffic": cmd_traffic, "counters": cmd_counters}[a.what](a)
+    {"stats": cmd_stats, "stats-multi": cmd_stats_multi, "traffic": cmd_traffic, "counters": cmd_counters}[a.what](a)
 
 
 if __name__ == "__main__":

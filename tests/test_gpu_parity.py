@@ -217,12 +217,35 @@ def test_backward_with_a_growing_state_full():
     _run_case(shrink(WORKLOADS["long_bf16"], H=6, N=20000, dk=64, dv=64, backward=True, seed=82), 64, True)
 
 
+def test_exactly_256_sequences_forward_uncut_backward_cut_in_two():
+    # one workgroup per compute unit: the forward sweeps every sequence in one piece, the backward (whose lone
+    # workgroup would leave its unit half idle) cuts each in two; whole tensors, ragged length; and the training
+    # pair, which follows the backward's cut with 64 x 64 states and stays uncut with 64 x 128
+    state = 64 * 64 * 4
+    assert binding.chela_linattn_workspace_bytes(32, 8, 1500, 64, 64, 64, True, binding.DTYPE_BF16) == 2 * 2 * 256 * state
+    _run_case(shrink(WORKLOADS["lm_bf16"], B=32, H=8, N=1500, seed=85), 64, True)
+    assert binding.chela_linattn_train_workspace_bytes(32, 8, 1500, 64, 128, 64, True) == 0
+    for dv in (64, 128):
+        w = shrink(WORKLOADS["lm_bf16"], B=32, H=8, N=1500, dv=dv, seed=86 + dv)
+        x = make_inputs(w)
+        d = _dev(x)
+        O, saved = binding.chela_linattn_fwd_save(d["Q"], d["K"], d["V"])
+        g = binding.chela_linattn_bwd_saved(d["Q"], d["K"], d["V"], d["dO"], saved)
+        torch.cuda.synchronize()
+        Qn, Kn, Vn, Gn = (to_f64_numpy(x[n]) for n in ("Q", "K", "V", "dO"))
+        print("\n256 sequences, training pair, dv %d" % dv, flush=True)
+        _check("O", O, oracle.fwd_recurrent(Qn, Kn, Vn), "bf16")
+        for name, got, r in zip(("dQ", "dK", "dV"), g, oracle.bwd_recurrent(Qn, Kn, Vn, Gn)):
+            _check(name, got, r, "bf16")
+
+
 def test_backward_many_heads_long_sequences_growing_state():
-    # 256 (b,h) pairs, so the planner would give every pair a single segment, of 40 000 tokens, values with a
-    # non-zero mean (silu of a Gaussian) and positive queries and keys: the state grows linearly, and the backward's
+    # 264 (b,h) pairs, so the planner gives every pair a single segment, of 40 000 tokens (more than the backward
+    # walks back in one stretch: the sweep leaves itself copies of the state), values with a non-zero mean (silu of a Gaussian) and positive queries and keys: the state grows linearly, and the backward's
     # walk back from the end of a segment has to stay accurate for the first, smallest states.  Every row of the
     # sampled pairs is held to the row bound.
-    B, H, N, dk, dv = 32, 8, 40000, 64, 64
+    B, H, N, dk, dv = 33, 8, 40000, 64, 64
+    assert binding.chela_linattn_workspace_bytes(B, H, N, dk, dv, 64, False, binding.DTYPE_BF16) == B * H * dk * dv * 4
     d = make_growing_state_inputs(B, H, N, dk, dv, 91, "cuda")
     O = binding.chela_linattn_fwd(d["Q"], d["K"], d["V"])
     dQ, dK, dV = binding.chela_linattn_bwd(d["Q"], d["K"], d["V"], d["dO"])
@@ -240,7 +263,7 @@ def test_backward_many_heads_long_sequences_growing_state():
                                    (1, 1, 9000, 128, 64, 64), (1, 2, 8300, 128, 128, 64)])
 def test_single_segment_backward_checkpoints_its_walk(shape, monkeypatch):
     # One segment per sequence and more than 8192 tokens: the sweep's first pass leaves copies of the running state,
-    # its walk back picks them up.  (The planner gives a sequence a single segment only among 256 or more of them;
+    # its walk back picks them up.  (The planner gives a sequence a single segment only among more than 256 of them;
     # here the segment length is forced instead so that the case stays small.)  Positive keys and values: the state
     # grows, which is what the copies are for.  Also through the Z entry points and the [B,N,H,d] layout.
     B, H, N, dk, dv, chunk = shape
@@ -296,8 +319,8 @@ def test_scan_in_a_kernel_of_its_own_or_folded_into_the_sweeps(mode, monkeypatch
 
 
 def test_training_pair_scratch_sized_by_its_own_query():
-    # 96 (b,h) pairs of 16384 tokens: the training pair's forward cuts each sequence 16 times, the plain forward 5
-    w = shrink(WORKLOADS["lm_bf16"], B=8, H=12, N=16384, seed=63)
+    # 24 (b,h) pairs of 4096 tokens: the training pair's forward cuts each sequence 16 times, the plain forward 8
+    w = shrink(WORKLOADS["lm_bf16"], B=2, H=12, N=4096, seed=63)
     d = _dev(make_inputs(w))
     sizes = [binding.chela_linattn_train_workspace_bytes(w.B, w.H, w.N, w.dk, w.dv, 64, bwd) for bwd in (False, True)]
     assert sizes[0] > binding.chela_linattn_workspace_bytes(w.B, w.H, w.N, w.dk, w.dv, 64, False, binding.DTYPE_BF16)

@@ -55,8 +55,8 @@ def test_noalloc_forward_twice_second_call_smaller():
 
 
 def test_noalloc_rejects_what_does_not_fit():
-    # 172 long sequences with 64 x 128 states: the planner's split needs several hundred MiB of segment states
-    B, H, N, dk, dv = 1, 172, 1984972, 64, 128
+    # 149 long sequences with 128 x 128 states: the planner's split needs 46 MiB of segment states
+    B, H, N, dk, dv = 1, 149, 1984972, 128, 128
     need = binding.chela_linattn_workspace_bytes(B, H, N, dk, dv, 64, False, binding.DTYPE_BF16)
     assert need > (32 << 20)
     L = binding.lib()
