@@ -562,6 +562,22 @@ def main():
                   "note": "each call timed in a loop of its own: what a kernel finds in the memory-side cache "
                           "differs from the alternating step, so the two need not add up to ms_per_step"}
 
+    # The same step through the training pair (the forward leaves the boundary states, the backward's pre-pass then
+    # reads Q and dO only): what a training loop that calls both would use.  Outside the region `value` comes from.
+    training_pair = None
+    if phases is not None and w.dtype == "bf16":
+        sv = torch.empty(max(binding.chela_linattn_saved_bytes(w.B, w.H, w.N, w.dk, w.dv, chunk), 16) // 4,
+                         dtype=torch.float32, device="cuda")
+
+        def pair_step():
+            binding.chela_linattn_fwd_save(d["Q"], d["K"], d["V"], O=O, saved=sv, chunk=chunk)
+            binding.chela_linattn_bwd_saved(d["Q"], d["K"], d["V"], d["dO"], sv, dQ=dQ, dK=dK, dV=dV, chunk=chunk)
+        p_ms = time_loop(pair_step)
+        training_pair = {"entry_points": "chela_linattn_fwd_save + chela_linattn_bwd_saved",
+                         "ms_per_step": round(p_ms, 4), "tokens_per_s": round(w.tokens / (p_ms * 1e-3), 1),
+                         "vs_plain_pair": round(p_ms / ms_per_step, 4)}
+        del sv
+
     # What plain streaming kernels need for the bytes this step's kernels HAVE to move in the three-launch structure
     # (every input once per pass that needs it, every output once; states left out): the pre-pass of the forward call
     # reads K, V of all but the last segment, its sweep reads Q, K, V and writes O, the backward's pre-pass reads
@@ -736,6 +752,8 @@ def main():
     }
     if phases is not None:
         out["phases"] = phases
+    if training_pair is not None:
+        out["training_pair"] = training_pair
     if parity_rel_l2 is not None:
         out["parity_rel_l2"] = parity_rel_l2
     if target is not None:
