@@ -38,7 +38,9 @@
  *              Taken from the buffer the CALLING THREAD gave to
  *              chela_set_workspace(), else from an allocation of the library's
  *              own, one per (device, stream), that grows on demand (growing it
- *              synchronises the device) and lives until chela_shutdown().
+ *              synchronises the device) and lives until chela_shutdown(); at most
+ *              64 streams per device are served this way, the next one gets
+ *              CHELA_ERR_WORKSPACE (hand in buffers, or shut down in between).
  *   Threads  : calls may be made from several host threads at once.  Calls that
  *              may overlap in time must not share scratch: the library's own
  *              allocations never are shared between streams; a caller-owned

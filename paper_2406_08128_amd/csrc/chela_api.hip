@@ -235,6 +235,7 @@ static thread_local void* t_user_ws = nullptr;
 static thread_local size_t t_user_bytes = 0;
 static constexpr int kMaxDev = 64;
 struct OwnWs { hipStream_t stream; void* ptr; size_t bytes; };
+static constexpr size_t kMaxOwnStreams = 64;    // per device
 static std::vector<OwnWs> g_own_ws[kMaxDev];
 
 static int get_workspace(size_t bytes, void* stream, float** out)
@@ -253,11 +254,10 @@ static int get_workspace(size_t bytes, void* stream, float** out)
     OwnWs* w = nullptr;
     for (OwnWs& x : g_own_ws[dev]) if (x.stream == (hipStream_t)stream) { w = &x; break; }
     if (!w) {
-        if (g_own_ws[dev].size() >= 32) {      // a caller that keeps making streams: start over rather than pile up
-            (void)hipDeviceSynchronize();
-            for (OwnWs& x : g_own_ws[dev]) if (x.ptr) (void)hipFree(x.ptr);
-            g_own_ws[dev].clear();
-        }
+        // Nothing is ever taken away from a stream that may still have work in flight (another thread may hold a
+        // pointer it has not launched with yet): a caller that goes through more streams than this hands in
+        // buffers of its own, or calls chela_shutdown() at a quiet moment.
+        if (g_own_ws[dev].size() >= kMaxOwnStreams) return CHELA_ERR_WORKSPACE;
         g_own_ws[dev].push_back(OwnWs{(hipStream_t)stream, nullptr, 0});
         w = &g_own_ws[dev].back();
     }
