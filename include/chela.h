@@ -245,7 +245,10 @@ int chela_gate_norm_bwd(const void *O, const void *G, const void *dY, void *dO, 
 /* ---- short-long convolutions (Sec. 4.2, Eq. 8): Z = K_l( silu( K_s(X) ) ), the other half of the token mixer -----
  * Depthwise (one kernel per channel) and causal with zero history:
  *     v[b,c,t] = silu( sum_{j<m, j<=t} w_short[c,j] * X[b,c,t-j] ),   Z[b,c,t] = sum_{s<=t} k_long[c,s] * v[b,c,t-s].
- *   X, Z     : [B, d, L] (time fastest), bf16 (plain name) or fp32 (_f32); fp32 arithmetic throughout.
+ *   X, Z     : [B, d, L] (time fastest), bf16 (plain name) or fp32 (_f32).  Arithmetic is fp32 throughout, with one
+ *              exception: bf16 I/O with 4096 < L <= 16384, L a multiple of 8, runs the transforms on the matrix
+ *              cores with half-precision operands and fp32 sums (input scaled by its largest magnitude, kernel by
+ *              its 1-norm, so no range is lost): 5e-4 relative before the output is rounded to bf16 (2e-3).
  *   w_short  : [d, m] fp32, 1 <= m <= 32: the paper's two parallel short kernels (sizes 3 and 2 log10(L) + 1) summed
  *              tap by tap into one, i.e. after the structural re-parameterisation of Sec. 4.2.  NULL: no short kernel
  *              and no activation (v = X), a plain long convolution.
@@ -255,7 +258,8 @@ int chela_gate_norm_bwd(const void *O, const void *G, const void *dY, void *dO, 
  *              until the kernel's weights change.
  * Sequences are zero-padded on chip to twice a transform length M >= L (M in {256, 1024, 4096, 16384}), which makes
  * the circular product of Eq. 7 equal the causal sum; L > 16384 is rejected (CHELA_ERR_BAD_SHAPE).  The forward
- * needs no scratch.  Pointers 16-byte aligned; Z must not overlap an input.  Everything else as for the calls above. */
+ * needs no scratch.  Pointers 16-byte aligned; Z must not overlap an input.  Everything else as for the calls above.
+ * Environment (read per call, tuning aid): CHELA_CONV_MATRIX=0 keeps the vector-ALU kernels for every size. */
 size_t chela_longconv_spectrum_bytes(int d, int L);
 int chela_longconv_spectrum(const float *k_long, void *spectrum, int d, int L, void *stream);
 int chela_shortlong_conv_fwd(const void *X, const float *w_short, int m, const void *spectrum, void *Z,

@@ -11,7 +11,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libchela.so")
-SOURCES = ["chela_api.hip", "chela_kernels_f32.hip", "chela_kernels_bf16.hip", "chela_kernels_conv.hip"]
+SOURCES = ["chela_api.hip", "chela_kernels_f32.hip", "chela_kernels_bf16.hip", "chela_kernels_conv.hip",
+           "chela_kernels_convmx.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed-fp32 VALU forms are switched off for every device compile (they have given wrong results on this pool)
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",

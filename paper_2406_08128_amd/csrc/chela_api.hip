@@ -852,7 +852,8 @@ size_t chela_linattn_noncausal_workspace_bytes(int B, int H, int N, int dk, int 
 size_t chela_longconv_spectrum_bytes(int d, int L)
 {
     const int M = (d > 0 && L > 0) ? conv_fft_size(L) : 0;
-    return M ? (size_t)d * (size_t)(M / 2 + 1) * 4 * sizeof(float) : 0;     // one (K[k], K[M-k]) pair per 16 bytes
+    // one (K[k], K[M-k]) pair per 16 bytes; behind them, for the sizes the matrix-core kernel serves, its own copy
+    return M ? conv_pairs_bytes(d, L) + convmx_spectrum_bytes(d, L) : 0;
 }
 
 int chela_longconv_spectrum(const float* k_long, void* spectrum, int d, int L, void* stream)
@@ -864,7 +865,11 @@ int chela_longconv_spectrum(const float* k_long, void* spectrum, int d, int L, v
     if (((uintptr_t)k_long | (uintptr_t)spectrum) & 15u) return CHELA_ERR_MISALIGNED;
     if (overlap(Range{(const char*)k_long, (size_t)d * L * 4}, Range{(const char*)spectrum, chela_longconv_spectrum_bytes(d, L)}))
         return CHELA_ERR_ALIASING;
-    return launch_longconv_spectrum(k_long, spectrum, d, L, (hipStream_t)stream) == hipSuccess ? CHELA_OK : CHELA_ERR_HIP;
+    if (launch_longconv_spectrum(k_long, spectrum, d, L, (hipStream_t)stream) != hipSuccess) return CHELA_ERR_HIP;
+    if (convmx_spectrum_bytes(d, L) &&
+        launch_convmx_spectrum(k_long, spectrum, (char*)spectrum + conv_pairs_bytes(d, L), d, L, (hipStream_t)stream) != hipSuccess)
+        return CHELA_ERR_HIP;
+    return CHELA_OK;
 }
 
 static int shortlong_common(const void* X, const float* w_short, int m, const void* spectrum, void* Y, int B, int d,
@@ -882,6 +887,9 @@ static int shortlong_common(const void* X, const float* w_short, int m, const vo
     if (overlap(ry, Range{(const char*)X, tb}) || overlap(ry, Range{(const char*)spectrum, chela_longconv_spectrum_bytes(d, L)}) ||
         (w_short && overlap(ry, Range{(const char*)w_short, (size_t)d * m * 4})))
         return CHELA_ERR_ALIASING;
+    if (convmx_applies(L, dtype == CHELA_DTYPE_BF16 ? 0 : 1))
+        return launch_convmx_fwd(X, w_short, m, (const char*)spectrum + conv_pairs_bytes(d, L), Y, B, d, L,
+                                 (hipStream_t)stream) == hipSuccess ? CHELA_OK : CHELA_ERR_HIP;
     return launch_shortlong_conv(X, w_short, m, spectrum, Y, (long)B * d, d, L, dtype == CHELA_DTYPE_BF16 ? 0 : 1,
                                  (hipStream_t)stream) == hipSuccess ? CHELA_OK : CHELA_ERR_HIP;
 }

@@ -118,6 +118,18 @@ hipError_t launch_bf16_step(const void* q, const void* k, const void* v, float* 
 // L steps (0: L too long); the kernel spectrum is [d][M/2 + 1] pairs of complex fp32.  dtype 0: bf16 I/O, 1: fp32 I/O.
 int conv_fft_size(int L);
 hipError_t launch_longconv_spectrum(const float* k, void* Kf, int d, int L, hipStream_t st);
+// The forward convolution on the matrix cores (bf16 I/O, 4096 < L <= 16384): its own copy of the kernel spectrum
+// (convmx_spectrum_bytes, derived from the pairs above) lives behind them in the caller's spectrum buffer.
+bool convmx_applies(int L, int dtype);
+size_t convmx_spectrum_bytes(int d, int L);
+hipError_t launch_convmx_spectrum(const float* k_long, const void* pairs, void* extra, int d, int L, hipStream_t st);
+hipError_t launch_convmx_fwd(const void* X, const float* w_short, int m, const void* extra, void* Y, int B, int d, int L,
+                             hipStream_t st);
+inline size_t conv_pairs_bytes(int d, int L)       // the (K[k], K[M-k]) pairs, rounded up to 256 bytes
+{
+    const int M = conv_fft_size(L);
+    return M ? (((size_t)d * (size_t)(M / 2 + 1) * 4 * sizeof(float)) + 255) & ~(size_t)255 : 0;
+}
 hipError_t launch_shortlong_conv(const void* X, const float* w_short, int m, const void* Kf, void* Y, long BD, int d,
                                  int L, int dtype, hipStream_t st);
 // Gradient: dX [B][d][L] (I/O dtype), dw [d][m] (only with a short kernel, m <= 32), dk [d][L] fp32.

@@ -845,6 +845,47 @@ def test_shortlong_conv_bf16(shape):
     _run_conv_case(B, d, L, m, "bf16", seed=L + 1)
 
 
+@pytest.mark.parametrize("shape", [(3, 2, 5000, 9, True), (1, 1, 4104, 3, True), (2, 3, 9000, 5, False),
+                                   (4, 5, 16384, 32, True), (1, 3, 12344, 1, True), (5, 2, 8200, 17, True)])
+def test_shortlong_conv_bf16_matrix_core_sizes(shape):
+    # 4096 < L <= 16384 with L a multiple of 8: the kernel whose transforms run on the matrix cores (pairs of
+    # sequences of a channel as one complex signal; odd batch sizes leave one alone), every tap count class, with and
+    # without the short stage
+    B, d, L, m, short = shape
+    _run_conv_case(B, d, L, m, "bf16", seed=L + 5, short=short)
+
+
+def test_matrix_core_conv_scales_with_its_input_and_kernel(monkeypatch):
+    # half-precision operands inside: the input is scaled by its largest magnitude and the kernel's spectrum by the
+    # kernel's 1-norm, so values far outside the half-precision range must come through unharmed, and the result
+    # must agree with the vector-ALU kernel (fp32 throughout) on the same data
+    x = make_conv_inputs(2, 3, 8192, 9, 17, "bf16")
+    dev = _dev(x)
+    for xs, ks in ((1.0, 1.0), (3.0e4, 1.0e-6), (1.0e-5, 2.0e5)):
+        X = (dev["X"].float() * xs).to(torch.bfloat16)
+        k = (dev["k_long"] * ks).contiguous()
+        spec = binding.chela_longconv_spectrum(k)
+        Z = binding.chela_shortlong_conv_fwd(X, None, spec)            # plain long convolution: linear in both
+        monkeypatch.setenv("CHELA_CONV_MATRIX", "0")
+        Z0 = binding.chela_shortlong_conv_fwd(X, None, spec)
+        monkeypatch.delenv("CHELA_CONV_MATRIX")
+        torch.cuda.synchronize()
+        want = oracle_conv.short_long_conv(to_f64_numpy(X.cpu()), None, to_f64_numpy(k.cpu()))
+        assert torch.isfinite(Z.float()).all()
+        _check("Z(x*%g, k*%g)" % (xs, ks), Z, want, "bf16")
+        assert oracle.rel_l2(to_f64_numpy(Z), to_f64_numpy(Z0)) <= 4e-3
+    # a constant input (all its energy in one bin) through an impulse kernel, and an all-zero pair
+    X = torch.full((2, 1, 16384), 3.0, dtype=torch.bfloat16, device="cuda")
+    k = torch.zeros(1, 16384, device="cuda")
+    k[0, 0] = 2.0
+    Z = binding.chela_shortlong_conv_fwd(X, None, binding.chela_longconv_spectrum(k))
+    assert oracle.rel_l2(to_f64_numpy(Z), np.full((2, 1, 16384), 6.0)) <= 4e-3
+    Z = binding.chela_shortlong_conv_fwd(torch.zeros_like(X), None, binding.chela_longconv_spectrum(k))
+    assert float(Z.float().abs().max()) == 0.0
+    Z = binding.chela_shortlong_conv_fwd(X, None, binding.chela_longconv_spectrum(torch.zeros_like(k)))
+    assert float(Z.float().abs().max()) == 0.0
+
+
 @pytest.mark.parametrize("L", [300, 4096, 16384])
 def test_long_conv_alone(L):
     _run_conv_case(1, 3, L, 3, "f32", seed=L + 2, short=False)
