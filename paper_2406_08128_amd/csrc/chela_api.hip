@@ -853,7 +853,9 @@ size_t chela_longconv_spectrum_bytes(int d, int L)
 {
     const int M = (d > 0 && L > 0) ? conv_fft_size(L) : 0;
     // one (K[k], K[M-k]) pair per 16 bytes; behind them, for the sizes the matrix-core kernel serves, its own copy
-    return M ? conv_pairs_bytes(d, L) + convmx_spectrum_bytes(d, L) : 0;
+    if (!M) return 0;
+    const size_t extra = convmx_spectrum_bytes(d, L);
+    return extra ? conv_pairs_bytes(d, L) + extra : (size_t)d * (size_t)(M / 2 + 1) * 4 * sizeof(float);
 }
 
 int chela_longconv_spectrum(const float* k_long, void* spectrum, int d, int L, void* stream)

@@ -125,7 +125,7 @@ size_t convmx_spectrum_bytes(int d, int L);
 hipError_t launch_convmx_spectrum(const float* k_long, const void* pairs, void* extra, int d, int L, hipStream_t st);
 hipError_t launch_convmx_fwd(const void* X, const float* w_short, int m, const void* extra, void* Y, int B, int d, int L,
                              hipStream_t st);
-inline size_t conv_pairs_bytes(int d, int L)       // the (K[k], K[M-k]) pairs, rounded up to 256 bytes
+inline size_t conv_pairs_bytes(int d, int L)       // the (K[k], K[M-k]) pairs: where the matrix-core copy starts
 {
     const int M = conv_fft_size(L);
     return M ? (((size_t)d * (size_t)(M / 2 + 1) * 4 * sizeof(float)) + 255) & ~(size_t)255 : 0;

@@ -192,7 +192,11 @@ def test_noncausal_argument_errors(L):
 
 def test_conv_argument_errors(L):
     sb, sp, f = L.chela_longconv_spectrum_bytes, L.chela_longconv_spectrum, L.chela_shortlong_conv_fwd
-    assert sb(3, 16384) == 3 * 8193 * 16 and sb(3, 16385) == 0 and sb(0, 64) == 0
+    # the (K[k], K[M-k]) pairs; for 4096 < L <= 16384 also the copy the matrix-core kernel reads (32768 complex
+    # numbers and a scale per channel), each of the two parts rounded up to 256 bytes
+    up = lambda n: (n + 255) // 256 * 256
+    assert sb(3, 4096) == 3 * 2049 * 16 and sb(3, 16385) == 0 and sb(0, 64) == 0
+    assert sb(3, 16384) == up(3 * 8193 * 16) + 3 * 32768 * 8 + up(3 * 4)
     assert sb(2, 257) == 2 * 513 * 16 and sb(2, 256) == 2 * 129 * 16 and sb(1, 1) == 129 * 16
     K, S, X, W, Y = A, A + SZ, A + 2 * SZ, A + 3 * SZ, A + 4 * SZ
     assert sp(None, S, 4, 100, None) == -1
