@@ -272,6 +272,9 @@ int chela_shortlong_conv_fwd_f32(const void *X, const float *w_short, int m, con
  *     d_k_long[c,s] = sum_b sum_{t>=s} dZ[b,c,t] v[b,c,t-s]         ([d,L] fp32 out, overwritten)
  *     du = dv * silu'(u),  dX[t] = sum_j w_short[j] du[t+j]         ([B,d,L] out, I/O dtype)
  *     d_w_short[c,j] = sum_b sum_t du[b,c,t] X[b,c,t-j]             ([d,m] fp32 out, overwritten)
+ * bf16 I/O with 4096 < L <= 16384, L a multiple of 8, runs the long-stage transforms on the matrix cores like the
+ * forward (half-precision operands, fp32 sums): d_k_long and d_w_short, although they leave as fp32, then carry
+ * 3e-4 .. 8e-4 of relative error instead of 1e-6 (CHELA_CONV_MATRIX=0: the vector-ALU kernels, fp32 throughout).
  * Nothing is saved by the forward call: u and v are recomputed from X.  With w_short = NULL (no short stage) dX = dv,
  * v = X and d_w_short is ignored.  m <= 32 as in the forward.  Scratch (library workspace):
  * chela_shortlong_conv_bwd_workspace_bytes().  Sums over batch and time are taken in a fixed order (deterministic). */

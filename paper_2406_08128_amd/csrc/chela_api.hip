@@ -911,7 +911,7 @@ int chela_shortlong_conv_fwd_f32(const void* X, const float* w_short, int m, con
 static size_t conv_bwd_ws_bytes(int B, int d, int L, int dtype, bool has_short)
 {
     if (B <= 0 || d <= 0 || L <= 0) return 0;
-    const size_t acc = conv_bwd_acc_floats(B, d, L) * sizeof(float);      // running sums of the long-kernel gradient
+    const size_t acc = conv_bwd_acc_floats(B, d, L, dtype == CHELA_DTYPE_BF16) * sizeof(float);      // running sums of the long-kernel gradient
     if (!has_short) return acc;
     const size_t n = (size_t)B * d * L, tiles = ((size_t)L + 2047) / 2048;
     (void)dtype;

@@ -125,6 +125,10 @@ size_t convmx_spectrum_bytes(int d, int L);
 hipError_t launch_convmx_spectrum(const float* k_long, const void* pairs, void* extra, int d, int L, hipStream_t st);
 hipError_t launch_convmx_fwd(const void* X, const float* w_short, int m, const void* extra, void* Y, int B, int d, int L,
                              hipStream_t st);
+// The two long-stage gradients (dV: fp32 for the short-stage kernel, or dX itself in bf16 when there is no short stage;
+// Hs: 32768 words of scratch for each of up to kConvMxMaxWgs workgroups).
+hipError_t launch_convmx_longbwd(const void* X, const float* w_short, int m, const void* extra, const void* dZ, void* dV,
+                                 bool dv_is_f32, float* dk, float* Hs, int B, int d, int L, hipStream_t st);
 inline size_t conv_pairs_bytes(int d, int L)       // the (K[k], K[M-k]) pairs: where the matrix-core copy starts
 {
     const int M = conv_fft_size(L);
@@ -138,6 +142,7 @@ hipError_t launch_shortlong_conv(const void* X, const float* w_short, int m, con
 // sums.
 // Workgroups that share a channel in the long-stage gradient kernel (each takes every G-th sequence): more than one
 // when the channels alone would leave the GPU underfilled.
+constexpr int kConvMxMaxWgs = 256;       // workgroups of the matrix-core gradient kernel at most
 inline int conv_bwd_groups(int B, int d, int L)
 {
     const int M = conv_fft_size(L);
@@ -150,10 +155,14 @@ inline int conv_bwd_groups(int B, int d, int L)
     if (g > 64) g = 64;
     return g < 1 ? 1 : (int)g;
 }
-inline size_t conv_bwd_acc_floats(int B, int d, int L)
+inline size_t conv_bwd_acc_floats(int B, int d, int L, bool bf16_io)
 {
     const int M = conv_fft_size(L), G = conv_bwd_groups(B, d, L);
-    return (M >= 16384 || G > 1) ? (size_t)G * d * (M / 2 + 1) * 4 : 0;
+    const size_t pairs = (M >= 16384 || G > 1) ? (size_t)G * d * (M / 2 + 1) * 4 : 0;
+    // (the matrix-core kernel -- bf16 I/O, 4096 < L <= 16384, L a multiple of 8 -- parks one spectrum of half-precision
+    // pairs per workgroup; sized for either kernel, whichever runs)
+    const size_t mx = (bf16_io && M >= 16384 && (L & 7) == 0) ? (size_t)kConvMxMaxWgs * 32768 : 0;
+    return pairs > mx ? pairs : mx;
 }
 hipError_t launch_shortlong_conv_bwd(const void* X, const float* w_short, int m, const void* Kf, const void* dZ,
                                      void* dX, float* dw, float* dk, float* ws_dV, int B, int d, int L, int dtype,

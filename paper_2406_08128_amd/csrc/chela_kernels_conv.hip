@@ -1025,15 +1025,22 @@ static hipError_t conv_bwd_impl(const IO* X, const float* w_short, int m, const 
     hipError_t e;
     const long BD = (long)B * d;
     float4* acc_ws = reinterpret_cast<float4*>(ws);
-    ws += conv_bwd_acc_floats(B, d, L);
-    if (w_short == nullptr)   // no short stage: v = x and dX is the correlation of dZ with the long kernel itself
+    ws += conv_bwd_acc_floats(B, d, L, sizeof(IO) == 2);
+    // bf16 I/O at the lengths the matrix-core kernels serve: its own copy of the spectrum lies behind the pairs
+    const bool mx = sizeof(IO) == 2 && convmx_applies(L, 0);
+    const void* mx_spec = (const char*)Kf + conv_pairs_bytes(d, L);
+    if (w_short == nullptr) { // no short stage: v = x and dX is the correlation of dZ with the long kernel itself
+        if (mx) return launch_convmx_longbwd(X, nullptr, 0, mx_spec, dZ, dX, false, dk, (float*)acc_ws, B, d, L, st);
         return conv_longbwd_dispatch<IO, IO>(X, nullptr, 0, Kf, dZ, dX, dk, acc_ws, B, d, L, st);
+    }
     float* ws_dV = ws;
     const long n_items = (long)B * ((L + kShortTile - 1) / kShortTile);                     // (batch entry, tile) pairs
     const int n_share = (int)((n_items + kShortTilesPerWg - 1) / kShortTilesPerWg);         // workgroups per channel
     if ((long)d * n_share > 0x7fffffffL) return hipErrorInvalidValue;
     float* ws_part = ws + (size_t)BD * L;                                   // [d][n_share][32] (room for [d][B * tiles][32])
-    if ((e = conv_longbwd_dispatch<IO, float>(X, w_short, m, Kf, dZ, ws_dV, dk, acc_ws, B, d, L, st)) != hipSuccess) return e;
+    e = mx ? launch_convmx_longbwd(X, w_short, m, mx_spec, dZ, ws_dV, true, dk, (float*)acc_ws, B, d, L, st)
+           : conv_longbwd_dispatch<IO, float>(X, w_short, m, Kf, dZ, ws_dV, dk, acc_ws, B, d, L, st);
+    if (e != hipSuccess) return e;
     {
         ProfScope prof(KID_CONV_SHORT_BWD, st);
         const dim3 grid((unsigned)((long)d * n_share));

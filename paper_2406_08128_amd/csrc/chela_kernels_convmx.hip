@@ -213,22 +213,23 @@ __device__ __forceinline__ void mx_store(unsigned* cube, const f32x16 (&acc)[2],
 
 // One pass over the cube in place: wave w takes tiles w, w + MX_W, ... (32 columns each).  KS: steps of the contraction
 // (2 when only the first 16 inputs along the axis can be non-zero), RB: row blocks wanted (1: results 0..15 only).
-// TW: MX_TW_NONE, MX_TW_T2 (`fixed` holds the rotations) or MX_TW_F1 / MX_TW_I2 (built here, stepped per tile).
+// TW: MX_TW_NONE, MX_TW_T2 (the same rotations for every tile) or MX_TW_F1 / MX_TW_I2 (stepped from tile to tile).
 template <int AX, int TW, int KS, int RB>
-__device__ __forceinline__ void mx_pass(unsigned* cube, const f16x8 (&A)[2][4], const MxRot& fixed, const float2* T2,
-                                        const float2* T1, int w, int lane)
+__device__ __forceinline__ void mx_pass(unsigned* cube, const f16x8 (&A)[2][4], const float2* T2, const float2* T1, int w,
+                                        int lane)
 {
     const int col = lane & 31, h = lane >> 5;
     constexpr bool RUN = TW == MX_TW_F1 || TW == MX_TW_I2;
     MxRot cur, step;
     if (RUN) mx_rot_start<TW>(cur, step, T2, T1, w, col, h);
+    if (TW == MX_TW_T2) mx_rot_fixed(cur, T2, col, h);
 #pragma unroll 1
     for (int t = w; t < 32; t += MX_W) {
         f16x8 Bv[4];
         f32x16 acc[2];
         mx_load<AX, KS>(cube, t, col, h, Bv);
         mx_mul<KS, RB>(A, Bv, acc);
-        mx_store<AX, TW != MX_TW_NONE, RB>(cube, acc, RUN ? cur : fixed, t, col, h);
+        mx_store<AX, TW != MX_TW_NONE, RB>(cube, acc, cur, t, col, h);
         if (RUN) {
 #pragma unroll
             for (int j = 0; j < 16; ++j) cur.v[j] = mx_cmul(cur.v[j], step.v[j]);
@@ -237,12 +238,13 @@ __device__ __forceinline__ void mx_pass(unsigned* cube, const f16x8 (&A)[2][4], 
 }
 
 // Spectrum of one channel's long kernel for these passes: bin k = k1 + 32 k2 + 1024 k3 of the 32768-point transform,
-// divided by 4 |k|_1, stored where the lane that holds it after the forward passes will look:
+// divided by 4 |k|_1, as half-precision (re, im) pairs, stored where the lane that holds it after the forward passes
+// will look:
 // index ((k1 * 4 + s) * 64 + lane) * 4 + i with lane = k2 + 32 h and k3 = 8 s + 4 h + i.  Taken from the array of
 // (K[k], K[16384 - k]) pairs, k = 0 .. 8192, that the spectrum kernel of the other convolution kernels leaves (the
 // spectrum of a real sequence: the upper half is the conjugate of the lower).  scale[c] = 4 |k|_1.
 __global__ __launch_bounds__(1024) void convmx_spectrum_kernel(const float* __restrict__ k_long,
-                                                               const float4* __restrict__ pairs, float2* __restrict__ Ks,
+                                                               const float4* __restrict__ pairs, unsigned* __restrict__ Ks,
                                                                float* __restrict__ scale, int L)
 {
     __shared__ float red[16];
@@ -260,7 +262,7 @@ __global__ __launch_bounds__(1024) void convmx_spectrum_kernel(const float* __re
     const float inv = n1 > 0.f ? 0.25f / n1 : 0.f;
     if (tid == 0) scale[c] = n1 > 0.f ? 4.f * n1 : 0.f;
     const float4* pc = pairs + c * (long)(8192 + 1);
-    float2* out = Ks + c * (long)MX_N;
+    unsigned* out = Ks + c * (long)MX_N;
     for (int o = tid; o < MX_N; o += 1024) {
         const int t = o >> 10, s = (o >> 8) & 3, ln = (o >> 2) & 63, i = o & 3;
         const int k = t + 32 * (ln & 31) + 1024 * (8 * s + 4 * (ln >> 5) + i);
@@ -272,7 +274,7 @@ __global__ __launch_bounds__(1024) void convmx_spectrum_kernel(const float* __re
         const float4 v = pc[l];
         float re = second ? v.z : v.x, im = second ? v.w : v.y;
         if (upper) im = -im;
-        out[o] = make_float2(re * inv, im * inv);
+        out[o] = mx_pack(re * inv, im * inv);
     }
 }
 
@@ -318,7 +320,7 @@ __device__ __forceinline__ void mx_steps(const bf16* __restrict__ row, bool pres
 // silu(K_s x)); 0: no short kernel, v = x.  L is a multiple of 8.
 template <int HALO>
 __global__ __launch_bounds__(MX_T) void convmx_fwd_kernel(const bf16* __restrict__ X, const float* __restrict__ w_short,
-                                                          int m, const float2* __restrict__ Ks,
+                                                          int m, const unsigned* __restrict__ Ks,
                                                           const float* __restrict__ kscale, bf16* __restrict__ Y, int B,
                                                           int d, int L, long n_pairs)
 {
@@ -339,8 +341,6 @@ __global__ __launch_bounds__(MX_T) void convmx_fwd_kernel(const bf16* __restrict
     f16x8 A[2][4];
     mx_build_matrix(A, lane);
     __syncthreads();
-    MxRot fixed;
-    mx_rot_fixed(fixed, T2, lane & 31, lane >> 5);
     const int PB = (B + 1) / 2;
     const int col = lane & 31, h = lane >> 5;
     const int my_d1 = tid >> 5, my_d2 = tid & 31;      // the cube row that holds this thread's 32 steps
@@ -376,17 +376,19 @@ __global__ __launch_bounds__(MX_T) void convmx_fwd_kernel(const bf16* __restrict
             }
         }
         // the spectrum pieces of this wave's first tile of the third pass, on their way while the first two passes run
-        const float4* kc = reinterpret_cast<const float4*>(Ks + (long)c * MX_N);
-        float4 kq[8];
+        const u32x4* kc = reinterpret_cast<const u32x4*>(Ks + (long)c * MX_N);
+        u32x4 kq[4];
 #pragma unroll
-        for (int q = 0; q < 8; ++q) kq[q] = kc[((w * 4 + (q >> 1)) * 64 + lane) * 2 + (q & 1)];
+        for (int q = 0; q < 4; ++q) kq[q] = kc[(w * 4 + q) * 64 + lane];
         __syncthreads();
         // ---- forward: axis 1 (only planes 0..15 hold data), axis 2
-        mx_pass<MX_AX1, MX_TW_F1, 2, 2>(cube, A, fixed, T2, T1, w, lane);
+        mx_pass<MX_AX1, MX_TW_F1, 2, 2>(cube, A, T2, T1, w, lane);
         __syncthreads();
-        mx_pass<MX_AX2, MX_TW_T2, 4, 2>(cube, A, fixed, T2, T1, w, lane);
+        mx_pass<MX_AX2, MX_TW_T2, 4, 2>(cube, A, T2, T1, w, lane);
         __syncthreads();
         // ---- axis 3 forward, times the kernel's spectrum, conjugate, axis 3 on the way back: in registers
+        MxRot fixed;
+        mx_rot_fixed(fixed, T2, col, h);
 #pragma unroll 1
         for (int t = w; t < 32; t += MX_W) {
             f16x8 Bv[4];
@@ -399,23 +401,23 @@ __global__ __launch_bounds__(MX_T) void convmx_fwd_kernel(const bf16* __restrict
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const float zr = mx_re(acc, s, i), zi = mx_im(acc, s, i);
-                    const float4 q4 = kq[2 * s + (i >> 1)];
-                    const float kr = (i & 1) ? q4.z : q4.x, ki = (i & 1) ? q4.w : q4.y;
+                    float kr, ki;
+                    mx_unpack(kq[s][i], kr, ki);
                     v[i] = mx_pack(zr * kr - zi * ki, -(zr * ki + zi * kr));
                 }
                 Bv[s] = __builtin_bit_cast(f16x8, v);
             }
             if (t + MX_W < 32) {
 #pragma unroll
-                for (int q = 0; q < 8; ++q) kq[q] = kc[(((t + MX_W) * 4 + (q >> 1)) * 64 + lane) * 2 + (q & 1)];
+                for (int q = 0; q < 4; ++q) kq[q] = kc[((t + MX_W) * 4 + q) * 64 + lane];
             }
             mx_mul<4, 2>(A, Bv, acc);
             mx_store<MX_AX3, true, 2>(cube, acc, fixed, t, col, h);
         }
         __syncthreads();
-        mx_pass<MX_AX2, MX_TW_I2, 4, 2>(cube, A, fixed, T2, T1, w, lane);
+        mx_pass<MX_AX2, MX_TW_I2, 4, 2>(cube, A, T2, T1, w, lane);
         __syncthreads();
-        mx_pass<MX_AX1, MX_TW_NONE, 4, 1>(cube, A, fixed, T2, T1, w, lane);     // only steps n < 16384 are wanted
+        mx_pass<MX_AX1, MX_TW_NONE, 4, 1>(cube, A, T2, T1, w, lane);     // only steps n < 16384 are wanted
         __syncthreads();
         // ---- out: y_a = Re, y_b = -Im (the conjugate that closes the way back), scales put back
         const float osc = kscale[c] / (s1 * (float)MX_N);
@@ -442,6 +444,275 @@ __global__ __launch_bounds__(MX_T) void convmx_fwd_kernel(const bf16* __restrict
     }
 }
 
+// One row (32 steps) of each sequence of a pair out of the cube after the way back: a = Re, b = -Im, times `osc`.
+template <typename OUT>
+__device__ __forceinline__ void mx_rows_out(const unsigned* cube, OUT* __restrict__ ya, OUT* __restrict__ yb, bool two,
+                                            int tid, int L, float osc)
+{
+    const int d1 = tid >> 5, d2 = tid & 31;
+    if (32 * tid >= L) return;
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        if (32 * tid + 8 * g < L) {
+            const u32x4 v0 = *reinterpret_cast<const u32x4*>(cube + mx_addr(d1, d2, 8 * g));
+            const u32x4 v1 = *reinterpret_cast<const u32x4*>(cube + mx_addr(d1, d2, 8 * g + 4));
+            float fa[8], fb[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                float re, im;
+                mx_unpack(e < 4 ? v0[e & 3] : v1[e & 3], re, im);
+                fa[e] = re * osc;
+                fb[e] = -im * osc;
+            }
+            if (sizeof(OUT) == 2) {
+                typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+                bf16x8 oa, ob;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) { oa[e] = (bf16)fa[e]; ob[e] = (bf16)fb[e]; }
+                *reinterpret_cast<bf16x8*>(ya + 32 * tid + 8 * g) = oa;
+                if (two) *reinterpret_cast<bf16x8*>(yb + 32 * tid + 8 * g) = ob;
+            } else {
+                float4* pa = reinterpret_cast<float4*>(ya + 32 * tid + 8 * g);
+                pa[0] = make_float4(fa[0], fa[1], fa[2], fa[3]);
+                pa[1] = make_float4(fa[4], fa[5], fa[6], fa[7]);
+                if (two) {
+                    float4* pq = reinterpret_cast<float4*>(yb + 32 * tid + 8 * g);
+                    pq[0] = make_float4(fb[0], fb[1], fb[2], fb[3]);
+                    pq[1] = make_float4(fb[4], fb[5], fb[6], fb[7]);
+                }
+            }
+        }
+    }
+}
+
+// From each thread's own largest magnitude and sum of squares: 1 / (largest magnitude in the workgroup) (1 if that is
+// zero) and the workgroup's sum of squares; two barriers.
+__device__ __forceinline__ float mx_inv_max(float mx, float& ss, float* red, int lane, int w)
+{
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) {
+        mx = fmaxf(mx, __shfl_xor(mx, o));
+        ss += __shfl_xor(ss, o);
+    }
+    __syncthreads();            // (the previous use of red[] is over)
+    if (lane == 0) { red[w] = mx; red[MX_W + w] = ss; }
+    __syncthreads();
+    float bm = 0.f;
+    ss = 0.f;
+#pragma unroll
+    for (int i = 0; i < MX_W; ++i) { bm = fmaxf(bm, red[i]); ss += red[MX_W + i]; }
+    return bm > 0.f ? 1.0f / bm : 1.0f;
+}
+
+__device__ __forceinline__ void mx_rows_in(unsigned* cube, const float (&va)[32], const float (&vb)[32], float s, int tid)
+{
+#pragma unroll
+    for (int g = 0; g < 8; ++g) {
+        u32x4 v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = mx_pack(va[4 * g + e] * s, vb[4 * g + e] * s);
+        *reinterpret_cast<u32x4*>(cube + mx_addr(tid >> 5, tid & 31, 4 * g)) = v;
+    }
+}
+
+// The two long-stage gradients of the convolution (they share the spectrum of dZ), pairs of sequences as above; one
+// workgroup walks the pairs of a channel, then the next channel blockIdx.x + gridDim.x, ...
+//   dv = corr(dZ, k_long):   Wd = T(dZ_a + i dZ_b);  conj(T'(conj(Wd conj(K)))) / N:  Re -> dv_a, Im -> dv_b
+//   dk[c][s] = sum_b sum_t dZ_b[t] v_b[t - s]:  Wv = T(v_a + i v_b), v = silu(K_s x) recomputed;  for the two real
+//   sequences of a pair DZ_a conj(V_a) + DZ_b conj(V_b) = (H[k] + conj H[-k]) / 2 with H = Wd conj(Wv), whose transform
+//   back is the real part of that of H: the pair's share of dk is Re T'(conj H) / N, added up over the pairs in the time
+//   domain (64 KB per channel, each step by the thread that owns it), so no spectrum-sized sums ever go to memory.
+//   Range of H: sum_k |Wd||Wv| <= |Wd|_2 |Wv|_2 = N |z_d|_2 |z_v|_2, so H times 32768 / (N |z_d|_2 |z_v|_2) keeps every
+//   sum on the way back within 32768 and leaves a typical bin at order one.
+//   Wd waits in memory while v is transformed (this workgroup's own 128 KB, in the order its lanes hold it).
+// dV: fp32 [B][d][L] for the short-stage kernel, or dX itself (bf16) when there is no short stage (HALO = 0, v = x).
+template <int HALO, typename DVT>
+__global__ __launch_bounds__(MX_T) void convmx_longbwd_kernel(const bf16* __restrict__ X, const float* __restrict__ w_short,
+                                                              int m, const unsigned* __restrict__ Ks,
+                                                              const float* __restrict__ kscale,
+                                                              const bf16* __restrict__ dZ, DVT* __restrict__ dV,
+                                                              float* __restrict__ dk, u32x4* __restrict__ Wds,
+                                                              int B, int d, int L)
+{
+    __shared__ __attribute__((aligned(16))) unsigned cube[MX_CUBE];
+    __shared__ float2 T2[1024];
+    __shared__ float2 T1[1024];
+    __shared__ float red[2 * MX_W];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    for (int e = tid; e < 1024; e += MX_T) {
+        const int a = e >> 5, b = e & 31;
+        float sn, cs;
+        sincospif(-2.0f * (float)(a * b) / 1024.0f, &sn, &cs);
+        T2[e] = make_float2(cs, sn);
+        sincospif(-2.0f * (float)(a * b) / 32768.0f, &sn, &cs);
+        T1[e] = make_float2(cs, sn);
+    }
+    f16x8 A[2][4];
+    mx_build_matrix(A, lane);
+    __syncthreads();
+    const int PB = (B + 1) / 2;
+    const int col = lane & 31, h = lane >> 5;
+    constexpr int NT = 32 / MX_W;        // tiles of a pass per wave
+    u32x4* wdm = Wds + (size_t)blockIdx.x * (MX_N / 4);
+
+    for (int c = blockIdx.x; c < d; c += gridDim.x) {
+        const u32x4* kc = reinterpret_cast<const u32x4*>(Ks + (long)c * MX_N);
+        const float* wc = HALO ? w_short + (long)c * m : nullptr;
+        const float ksc = kscale[c];
+        for (int pb = 0; pb < PB; ++pb) {
+            const bool two = 2 * pb + 1 < B;
+            const long row_a = ((long)(2 * pb) * d + c) * (long)L, row_b = row_a + (long)d * L;
+            float s_d, n_d = 0.f;
+            {
+                float va[32], vb[32];
+                mx_steps<0>(dZ + row_a, true, 32 * tid, L, nullptr, 0, va);
+                mx_steps<0>(dZ + row_b, two, 32 * tid, L, nullptr, 0, vb);
+                float mx = 0.f;
+#pragma unroll
+                for (int i = 0; i < 32; ++i) {
+                    mx = fmaxf(mx, fmaxf(fabsf(va[i]), fabsf(vb[i])));
+                    n_d = fmaf(va[i], va[i], fmaf(vb[i], vb[i], n_d));
+                }
+                s_d = mx_inv_max(mx, n_d, red, lane, w);      // (its barriers: the cube is free again)
+                mx_rows_in(cube, va, vb, s_d, tid);
+            }
+            __syncthreads();
+            mx_pass<MX_AX1, MX_TW_F1, 2, 2>(cube, A, T2, T1, w, lane);
+            __syncthreads();
+            mx_pass<MX_AX2, MX_TW_T2, 4, 2>(cube, A, T2, T1, w, lane);
+            __syncthreads();
+            {
+                MxRot fixed;
+                mx_rot_fixed(fixed, T2, col, h);
+                u32x4 kq[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) kq[q] = kc[(w * 4 + q) * 64 + lane];
+#pragma unroll 1
+                for (int n = 0; n < NT; ++n) {
+                    const int t = w + MX_W * n;
+                    f16x8 Bv[4];
+                    f32x16 acc[2];
+                    mx_load<MX_AX3, 4>(cube, t, col, h, Bv);
+                    mx_mul<4, 2>(A, Bv, acc);
+#pragma unroll
+                    for (int s = 0; s < 4; ++s) {
+                        u32x4 v, keep;
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const float zr = mx_re(acc, s, i), zi = mx_im(acc, s, i);
+                            keep[i] = mx_pack(zr, zi);
+                            float kr, ki;
+                            mx_unpack(kq[s][i], kr, ki);
+                            // conj(Z conj(K)) = (zr kr + zi ki) + i (zr ki - zi kr)
+                            v[i] = mx_pack(zr * kr + zi * ki, zr * ki - zi * kr);
+                        }
+                        Bv[s] = __builtin_bit_cast(f16x8, v);
+                        wdm[(t * 4 + s) * 64 + lane] = keep;
+                    }
+                    if (n + 1 < NT) {       // the next tile's pieces of the spectrum, on their way during the products
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) kq[q] = kc[((t + MX_W) * 4 + q) * 64 + lane];
+                    }
+                    mx_mul<4, 2>(A, Bv, acc);
+                    mx_store<MX_AX3, true, 2>(cube, acc, fixed, t, col, h);
+                }
+            }
+            __syncthreads();
+            mx_pass<MX_AX2, MX_TW_I2, 4, 2>(cube, A, T2, T1, w, lane);
+            __syncthreads();
+            mx_pass<MX_AX1, MX_TW_NONE, 4, 1>(cube, A, T2, T1, w, lane);
+            __syncthreads();
+            mx_rows_out<DVT>(cube, dV + row_a, dV + row_b, two, tid, L, ksc / (s_d * (float)MX_N));
+
+            // ---- v = silu(K_s x) (or x), its spectrum, H (+)= Wd conj(Wv) with the two scales taken out
+            float s_v, n_v = 0.f;
+            {
+                float va[32], vb[32];
+                mx_steps<HALO>(X + row_a, true, 32 * tid, L, wc, m, va);
+                mx_steps<HALO>(X + row_b, two, 32 * tid, L, wc, m, vb);
+                float mx = 0.f;
+#pragma unroll
+                for (int i = 0; i < 32; ++i) {
+                    mx = fmaxf(mx, fmaxf(fabsf(va[i]), fabsf(vb[i])));
+                    n_v = fmaf(va[i], va[i], fmaf(vb[i], vb[i], n_v));
+                }
+                s_v = mx_inv_max(mx, n_v, red, lane, w);      // (its barriers: dv has been read out of the cube)
+                mx_rows_in(cube, va, vb, s_v, tid);
+            }
+            __syncthreads();
+            mx_pass<MX_AX1, MX_TW_F1, 2, 2>(cube, A, T2, T1, w, lane);
+            __syncthreads();
+            mx_pass<MX_AX2, MX_TW_T2, 4, 2>(cube, A, T2, T1, w, lane);
+            __syncthreads();
+            // |z|_2 of the scaled signals: sqrt(sum of squares) * scale
+            const float nn = sqrtf(n_d) * s_d * sqrtf(n_v) * s_v;
+            const float g = nn > 0.f ? 1.0f / nn : 0.f;          // = 32768 / (N |z_d|_2 |z_v|_2)
+            {
+                MxRot fixed;
+                mx_rot_fixed(fixed, T2, col, h);
+                u32x4 wn[4];                                     // Wd of the tile in hand, fetched one tile ahead
+#pragma unroll
+                for (int s = 0; s < 4; ++s) wn[s] = wdm[(w * 4 + s) * 64 + lane];
+#pragma unroll 1
+                for (int n = 0; n < NT; ++n) {
+                    const int t = w + MX_W * n;
+                    f16x8 Bv[4];
+                    f32x16 acc[2];
+                    mx_load<MX_AX3, 4>(cube, t, col, h, Bv);
+                    mx_mul<4, 2>(A, Bv, acc);
+#pragma unroll
+                    for (int s = 0; s < 4; ++s) {
+                        u32x4 v;
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            float dr, di;
+                            mx_unpack(wn[s][i], dr, di);
+                            const float vr = mx_re(acc, s, i), vi = mx_im(acc, s, i);
+                            // conj(Wd conj(Wv)) = (dr vr + di vi) + i (dr vi - di vr)
+                            v[i] = mx_pack((dr * vr + di * vi) * g, (dr * vi - di * vr) * g);
+                        }
+                        Bv[s] = __builtin_bit_cast(f16x8, v);
+                    }
+                    if (n + 1 < NT) {
+#pragma unroll
+                        for (int s = 0; s < 4; ++s) wn[s] = wdm[((t + MX_W) * 4 + s) * 64 + lane];
+                    }
+                    mx_mul<4, 2>(A, Bv, acc);
+                    mx_store<MX_AX3, true, 2>(cube, acc, fixed, t, col, h);
+                }
+            }
+            __syncthreads();
+            mx_pass<MX_AX2, MX_TW_I2, 4, 2>(cube, A, T2, T1, w, lane);
+            __syncthreads();
+            mx_pass<MX_AX1, MX_TW_NONE, 4, 1>(cube, A, T2, T1, w, lane);
+            __syncthreads();
+            // this pair's share of dk: Re / (N g s_d s_v), each step by the thread that owns it
+            if (32 * tid < L) {
+                const float osc = g > 0.f ? 1.0f / (g * s_d * s_v * (float)MX_N) : 0.f;
+                float* out = dk + (long)c * L + 32 * tid;
+#pragma unroll
+                for (int q = 0; q < 8; ++q) {
+                    if (32 * tid + 4 * q < L) {
+                        const u32x4 v = *reinterpret_cast<const u32x4*>(cube + mx_addr(tid >> 5, tid & 31, 4 * q));
+                        float r0, r1, r2, r3, im;
+                        mx_unpack(v[0], r0, im);
+                        mx_unpack(v[1], r1, im);
+                        mx_unpack(v[2], r2, im);
+                        mx_unpack(v[3], r3, im);
+                        float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
+                        if (pb > 0) o = *reinterpret_cast<const float4*>(out + 4 * q);
+                        o.x += r0 * osc; o.y += r1 * osc; o.z += r2 * osc; o.w += r3 * osc;
+                        *reinterpret_cast<float4*>(out + 4 * q) = o;
+                    }
+                }
+            }
+            // (the next stage starts with barriers before it touches the cube)
+        }
+        __syncthreads();        // the cube is free for the next channel
+    }
+}
+
 // ------------------------------------------------------------------------------------------------ host side
 bool convmx_applies(int L, int dtype)
 {
@@ -454,13 +725,13 @@ bool convmx_applies(int L, int dtype)
 size_t convmx_spectrum_bytes(int d, int L)
 {
     if (d <= 0 || L <= 4096 || L > MX_L_MAX) return 0;
-    return (size_t)d * MX_N * sizeof(float2) + (((size_t)d * sizeof(float) + 255) & ~(size_t)255);
+    return (size_t)d * MX_N * sizeof(unsigned) + (((size_t)d * sizeof(float) + 255) & ~(size_t)255);
 }
 
 hipError_t launch_convmx_spectrum(const float* k_long, const void* pairs, void* extra, int d, int L, hipStream_t st)
 {
-    float2* Ks = (float2*)extra;
-    float* scale = (float*)((char*)extra + (size_t)d * MX_N * sizeof(float2));
+    unsigned* Ks = (unsigned*)extra;
+    float* scale = (float*)((char*)extra + (size_t)d * MX_N * sizeof(unsigned));
     hipLaunchKernelGGL(convmx_spectrum_kernel, dim3(d), dim3(1024), 0, st, k_long, (const float4*)pairs, Ks, scale, L);
     return hipGetLastError();
 }
@@ -468,8 +739,8 @@ hipError_t launch_convmx_spectrum(const float* k_long, const void* pairs, void* 
 hipError_t launch_convmx_fwd(const void* X, const float* w_short, int m, const void* extra, void* Y, int B, int d, int L,
                              hipStream_t st)
 {
-    const float2* Ks = (const float2*)extra;
-    const float* scale = (const float*)((const char*)extra + (size_t)d * MX_N * sizeof(float2));
+    const unsigned* Ks = (const unsigned*)extra;
+    const float* scale = (const float*)((const char*)extra + (size_t)d * MX_N * sizeof(unsigned));
     const long n_pairs = (long)d * ((B + 1) / 2);
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) != hipSuccess ||
@@ -489,6 +760,34 @@ hipError_t launch_convmx_fwd(const void* X, const float* w_short, int m, const v
     else
         hipLaunchKernelGGL((convmx_fwd_kernel<32>), grid, dim3(MX_T), 0, st, (const bf16*)X, w_short, m, Ks, scale,
                            (bf16*)Y, B, d, L, n_pairs);
+    return hipGetLastError();
+}
+
+hipError_t launch_convmx_longbwd(const void* X, const float* w_short, int m, const void* extra, const void* dZ, void* dV,
+                                 bool dv_is_f32, float* dk, float* Hs, int B, int d, int L, hipStream_t st)
+{
+    const unsigned* Ks = (const unsigned*)extra;
+    const float* scale = (const float*)((const char*)extra + (size_t)d * MX_N * sizeof(unsigned));
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+        cus = 256;
+    (void)hipGetLastError();
+    if (cus > kConvMxMaxWgs) cus = kConvMxMaxWgs;       // (the scratch behind the sums holds that many workgroups' Wd)
+    const int rounds = (d + cus - 1) / cus;
+    const dim3 grid((unsigned)((d + rounds - 1) / rounds));
+    ProfScope prof(KID_CONV_LONG_BWD, st);
+#define CHELA_MX_BWD(H_, T_)                                                                                            \
+    hipLaunchKernelGGL((convmx_longbwd_kernel<H_, T_>), grid, dim3(MX_T), 0, st, (const bf16*)X, w_short, m, Ks, scale,  \
+                       (const bf16*)dZ, (T_*)dV, dk, (u32x4*)Hs, B, d, L)
+    if (!w_short) {
+        if (dv_is_f32) CHELA_MX_BWD(0, float); else CHELA_MX_BWD(0, bf16);
+    } else if (m <= 9) {
+        if (dv_is_f32) CHELA_MX_BWD(8, float); else CHELA_MX_BWD(8, bf16);
+    } else {
+        if (dv_is_f32) CHELA_MX_BWD(32, float); else CHELA_MX_BWD(32, bf16);
+    }
+#undef CHELA_MX_BWD
     return hipGetLastError();
 }
 

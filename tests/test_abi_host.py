@@ -193,10 +193,10 @@ def test_noncausal_argument_errors(L):
 def test_conv_argument_errors(L):
     sb, sp, f = L.chela_longconv_spectrum_bytes, L.chela_longconv_spectrum, L.chela_shortlong_conv_fwd
     # the (K[k], K[M-k]) pairs; for 4096 < L <= 16384 also the copy the matrix-core kernel reads (32768 complex
-    # numbers and a scale per channel), each of the two parts rounded up to 256 bytes
+    # half-precision numbers and a scale per channel), each of the two parts rounded up to 256 bytes
     up = lambda n: (n + 255) // 256 * 256
     assert sb(3, 4096) == 3 * 2049 * 16 and sb(3, 16385) == 0 and sb(0, 64) == 0
-    assert sb(3, 16384) == up(3 * 8193 * 16) + 3 * 32768 * 8 + up(3 * 4)
+    assert sb(3, 16384) == up(3 * 8193 * 16) + 3 * 32768 * 4 + up(3 * 4)
     assert sb(2, 257) == 2 * 513 * 16 and sb(2, 256) == 2 * 129 * 16 and sb(1, 1) == 129 * 16
     K, S, X, W, Y = A, A + SZ, A + 2 * SZ, A + 3 * SZ, A + 4 * SZ
     assert sp(None, S, 4, 100, None) == -1
@@ -226,9 +226,13 @@ def test_conv_bwd_argument_errors(L):
     # enough channels to fill the GPU: one workgroup per channel again
     assert wsb(8, 16384, 100, 0, 0) == 0
     # at the largest transform size the running sums live in the workspace whatever G is
-    assert wsb(1, 4, 16000, 0, 0) == 4 * 8193 * 16
-    assert wsb(2, 4, 16000, 0, 0) == 2 * 4 * 8193 * 16
-    assert wsb(2, 4, 16000, 1, 0) == 2 * 4 * 8193 * 16 + 2 * 4 * (16000 * 4 + 8 * 128)
+    assert wsb(1, 4, 16001, 0, 0) == 4 * 8193 * 16 and wsb(1, 4, 16000, 0, 1) == 4 * 8193 * 16
+    # bf16 I/O with 4096 < L <= 16384, L a multiple of 8: room for the matrix-core kernel as well (a spectrum of
+    # half-precision pairs for each of 256 workgroups), whichever of the two kernels runs
+    assert wsb(1, 4, 16000, 0, 0) == 256 * 32768 * 4
+    assert wsb(2, 4, 16000, 0, 1) == 2 * 4 * 8193 * 16
+    assert wsb(2, 4, 16000, 1, 1) == 2 * 4 * 8193 * 16 + 2 * 4 * (16000 * 4 + 8 * 128)
+    assert wsb(2, 4, 16000, 1, 0) == 256 * 32768 * 4 + 2 * 4 * (16000 * 4 + 8 * 128)
     assert g(None, W, 9, S, dZ, dX, dW, dK, 2, 4, 100, None) == -1
     assert g(X, W, 9, S, dZ, dX, None, dK, 2, 4, 100, None) == -1
     assert g(X, W, 33, S, dZ, dX, dW, dK, 2, 4, 100, None) == -2          # at most 32 taps, as in the forward

@@ -993,6 +993,39 @@ def test_shortlong_conv_bwd_bf16(shape):
     _run_conv_bwd_case(B, d, L, m, "bf16", seed=L + 11)
 
 
+@pytest.mark.parametrize("shape", [(3, 2, 5000, 9, True), (1, 1, 4104, 3, True), (2, 3, 9000, 5, False),
+                                   (4, 3, 16384, 32, True), (5, 2, 8200, 17, True)])
+def test_shortlong_conv_bwd_bf16_matrix_core_sizes(shape):
+    # the gradient kernel whose transforms run on the matrix cores (4096 < L <= 16384, L a multiple of 8): odd batch
+    # sizes, several pairs per channel (dk adds up over them), every tap count class, with and without the short stage
+    B, d, L, m, short = shape
+    _run_conv_bwd_case(B, d, L, m, "bf16", seed=L + 13, short=short)
+
+
+def test_matrix_core_conv_gradient_scales_with_its_inputs():
+    # half-precision operands inside, every signal scaled on the way in: gradients of inputs far outside the
+    # half-precision range (and of an all-zero upstream gradient) come through
+    x = make_conv_inputs(2, 2, 8192, 9, 19, "bf16")
+    g = torch.Generator(device="cpu")
+    g.manual_seed(77)
+    dZ0 = torch.randn(2, 2, 8192, generator=g, dtype=torch.float32)
+    for xs, ks, gs in ((3.0e4, 1.0e-6, 1.0e-5), (1.0e-5, 2.0e5, 3.0e4)):
+        X = (x["X"].float() * xs).to(torch.bfloat16)
+        k = (x["k_long"] * ks).contiguous()
+        dZ = (dZ0 * gs).to(torch.bfloat16)
+        spec = binding.chela_longconv_spectrum(k.cuda())
+        dX, _, dk = binding.chela_shortlong_conv_bwd(X.cuda(), None, spec, dZ.cuda())
+        torch.cuda.synchronize()
+        rX, _, rk = oracle_conv.short_long_conv_bwd(to_f64_numpy(X), None, to_f64_numpy(k), to_f64_numpy(dZ))
+        _check("dX(x*%g, k*%g, g*%g)" % (xs, ks, gs), dX, rX, "bf16")
+        _check("dk(x*%g, k*%g, g*%g)" % (xs, ks, gs), dk, rk, "bf16")
+    spec = binding.chela_longconv_spectrum(x["k_long"].cuda())
+    dX, dw, dk = binding.chela_shortlong_conv_bwd(x["X"].cuda(), x["w_short"].cuda(), spec,
+                                                  torch.zeros(2, 2, 8192, dtype=torch.bfloat16, device="cuda"))
+    torch.cuda.synchronize()
+    assert float(dX.float().abs().max()) == 0.0 and float(dk.abs().max()) == 0.0 and float(dw.abs().max()) == 0.0
+
+
 @pytest.mark.parametrize("L", [300, 4096])
 def test_long_conv_alone_bwd(L):
     _run_conv_bwd_case(2, 3, L, 3, "f32", seed=L + 12, short=False)
