@@ -188,6 +188,10 @@ def bench_conv(args, w, torch, binding):
     flops = B * d * (2 * 5 * M * math.log2(M) + 20 * M / 2 + 2 * m * L)       # one launch of the forward kernel
     alg = B * d * L * es * 2 + d * (M // 2 + 1) * 16   # X in, Z out, the kernel spectrum once
     achieved = flops / (us * 1e-6) / 1e12
+    # bf16 I/O at 4096 < L <= 16384 (L a multiple of 8) runs the transforms on the matrix cores: 1280 instructions of
+    # 32768 flop per pair of sequences and forward call, fp16 operands, fp32 sums
+    matrix = dt == "bf16" and 4096 < L <= 16384 and L % 8 == 0 and os.environ.get("CHELA_CONV_MATRIX", "1") != "0"
+    mfma_flop = d * ((B + 1) // 2) * 1280 * 32768 if matrix else 0
     cpu = None
     if not args.no_cpu_baseline:
         from oracle import conv as oracle_conv
@@ -207,13 +211,20 @@ def bench_conv(args, w, torch, binding):
     print(json.dumps({
         "metric": "short-long convolution %s tokens/s" % ("fwd+bwd" if train else "fwd"), "value": round(B * L / (ms * 1e-3), 1), "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "conv at %s width: B%d d%d L%d, short kernel %d taps + silu + long kernel of L taps, %s I/O, "
-                               "fp32 arithmetic" % (w.name, B, d, L, m, dt)},
+        "scaling": "weak", "vs_baseline": None, "dtype": "f16" if matrix else "f32", "data": "synthetic",
+        "config": {"workload": "conv at %s width: B%d d%d L%d, short kernel %d taps + silu + long kernel of L taps, %s I/O, %s"
+                               % (w.name, B, d, L, m, dt, "transforms on the matrix cores (fp16 operands, fp32 sums), the "
+                                  "rest fp32" if matrix else "fp32 arithmetic")},
         "roofline": {"bound": "alu", "kernel": "shortlong_conv_kernel", "achieved": round(achieved, 2), "peak": 157.3,
                      "unit": "TFLOP/s", "frac": round(achieved / 157.3, 4), "traffic": None,
                      "flop_model_per_launch": flops, "avg_launch_us": us,
-                     "hbm_GBs_algorithmic": round(alg / (us * 1e-6) / 1e9, 1)},
+                     "hbm_GBs_algorithmic": round(alg / (us * 1e-6) / 1e9, 1),
+                     "note": "flop model of the method (5 M log2 M per transform), whatever executes it"
+                             + ("; the matrix cores execute %.3g flop per launch = %.0f TFLOP/s (%.3f of the 2.5 PFLOP/s "
+                                "fp16 peak): the kernel is bound by the vector ALU work around them (rotations, "
+                                "conversions, short kernel and activation)"
+                                % (mfma_flop, mfma_flop / (us * 1e-6) / 1e12, mfma_flop / (us * 1e-6) / 2.5e15)
+                                if matrix else "")},
         "kernels": kernels, "cpu_baseline": cpu}))
 
 
