@@ -595,7 +595,7 @@ def main():
     # Q, K, V, dO, its sweep reads them again and writes dQ, dK, dV.  Each line is the stream probe on as many arrays
     # of the tensors' size (widths differ: arrays of the mean width, same total bytes).
     stream_floor = None
-    if headline:
+    if args.mode == "train" and w.dtype == "bf16" and not args.graph:
         def probe_us(n_rd, n_wr, total_bytes):
             each = (int(total_bytes) // (n_rd + n_wr)) // 16 * 16
             n_sets = min(8, max(2, -(-(1 << 30) // max(1, each * (n_rd + n_wr)))))
@@ -613,13 +613,22 @@ def main():
             binding.chela_profile_reset()
             return r[1] * 1e3 / r[0]
         tb_k, tb_v = th * w.dk * es, th * w.dv * es
-        parts = {"fwd_prepass_2r": probe_us(2, 0, 0.9 * (tb_k + tb_v)),
-                 "fwd_sweep_3r_1w": probe_us(3, 1, 2 * tb_k + 2 * tb_v),
-                 "bwd_prepass_4r": probe_us(4, 0, 2 * tb_k + 2 * tb_v),
-                 "bwd_sweep_4r_3w": probe_us(4, 3, 4 * tb_k + 3 * tb_v)}
+        # segments per sequence of the forward call's plan (one: no pre-pass at all)
+        n_seg = max(1, binding.chela_linattn_workspace_bytes(w.B, w.H, w.N, w.dk, w.dv, chunk, False, binding.DTYPE_BF16)
+                    // (w.B * w.H * w.dk * w.dv * 4))
+        seg_frac = (n_seg - 1) / n_seg
+        parts = {}
+        if n_seg > 1:
+            parts["fwd_prepass_2r"] = probe_us(2, 0, seg_frac * (tb_k + tb_v))
+        parts["fwd_sweep_3r_1w"] = probe_us(3, 1, 2 * tb_k + 2 * tb_v)
+        if has_bwd:
+            parts["bwd_prepass_4r"] = probe_us(4, 0, 2 * tb_k + 2 * tb_v)
+            parts["bwd_sweep_4r_3w"] = probe_us(4, 3, 4 * tb_k + 3 * tb_v)
         tot = sum(parts.values())
         stream_floor = {"us_per_part": {k: round(v, 1) for k, v in parts.items()}, "us": round(tot, 1),
-                        "bytes": int(0.9 * (tb_k + tb_v) + 2 * (2 * tb_k + 2 * tb_v) + 4 * tb_k + 3 * tb_v),
+                        "bytes": int((seg_frac * (tb_k + tb_v) if n_seg > 1 else 0) + (2 * tb_k + 2 * tb_v)
+                                     + ((2 * tb_k + 2 * tb_v) + 4 * tb_k + 3 * tb_v if has_bwd else 0)),
+                        "segments_per_sequence": n_seg,
                         "step_over_floor": round(ms_per_step * 1e3 / tot, 3),
                         "note": "plain grid-stride kernels moving what the pre-passes and sweeps of this step must "
                                 "move (kernel time only, no launch gaps): the step cannot beat this without moving "
