@@ -994,10 +994,13 @@ def test_shortlong_conv_bwd_bf16(shape):
 
 
 @pytest.mark.parametrize("shape", [(3, 2, 5000, 9, True), (1, 1, 4104, 3, True), (2, 3, 9000, 5, False),
-                                   (4, 3, 16384, 32, True), (5, 2, 8200, 17, True)])
+                                   (4, 3, 16384, 32, True), (5, 2, 8200, 17, True), (4, 1, 8200, 10, True),
+                                   (4, 1, 16376, 10, True), (6, 1, 8216, 9, True), (4, 2, 4128, 12, True),
+                                   (7, 1, 12296, 1, True), (4, 1, 8200, 5, False), (2, 2, 16384, 9, True)])
 def test_shortlong_conv_bwd_bf16_matrix_core_sizes(shape):
     # the gradient kernel whose transforms run on the matrix cores (4096 < L <= 16384, L a multiple of 8): odd batch
-    # sizes, several pairs per channel (dk adds up over them), every tap count class, with and without the short stage
+    # sizes, several pairs per channel (dk adds up over them), every tap count class, with and without the short stage,
+    # lengths whose last row of 32 steps is partly filled
     B, d, L, m, short = shape
     _run_conv_bwd_case(B, d, L, m, "bf16", seed=L + 13, short=short)
 
