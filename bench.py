@@ -183,10 +183,13 @@ def bench_conv(args, w, torch, binding):
     kernels = {k: {"launches": n, "avg_us": round(t * 1e3 / n, 2)} for k, (n, t) in prof.items()}
     us = kernels["shortlong_conv_kernel"]["avg_us"]      # (with the backward: mean over its two kinds of launch)
     M = 256 if L <= 256 else 1024 if L <= 1024 else 4096 if L <= 4096 else 16384
+    nb = (L + 16383) // 16384 if L > 16384 else 0     # beyond 16384 steps: blocks of 16384, nb (nb + 1) / 2 block pairs
+    if nb:
+        M = 1 << (L - 1).bit_length()                 # the flop model stays the method's: one transform of 2 M >= 2 L points
     # ALU model per sequence: two complex FFTs of length M at 5 M log2 M flops + 20 flops per spectrum pair + short kernel
     import math
     flops = B * d * (2 * 5 * M * math.log2(M) + 20 * M / 2 + 2 * m * L)       # one launch of the forward kernel
-    alg = B * d * L * es * 2 + d * (M // 2 + 1) * 16   # X in, Z out, the kernel spectrum once
+    alg = B * d * L * es * 2 + d * ((nb * 8193) if nb else (M // 2 + 1)) * 16   # X in, Z out, the kernel spectrum once
     achieved = flops / (us * 1e-6) / 1e12
     # bf16 I/O at 4096 < L <= 16384 (L a multiple of 8) runs the transforms on the matrix cores: 1280 instructions of
     # 32768 flop per pair of sequences and forward call, fp16 operands, fp32 sums
@@ -195,7 +198,8 @@ def bench_conv(args, w, torch, binding):
     cpu = None
     if not args.no_cpu_baseline:
         from oracle import conv as oracle_conv
-        nch = min(d, 512)                                # bounded sample: the direct sum is O(L^2) per sequence
+        # bounded sample: the direct sum is O(L^2) per sequence (512 channels at 16384 steps, fewer beyond)
+        nch = min(d, 512, max(16, int(7e10 / (L * L / 2))))
         Xn = to_f64_numpy(x["X"][:1, :nch]); wn = to_f64_numpy(x["w_short"][:nch]); kn = to_f64_numpy(x["k_long"][:nch])
         import oracle
         c0 = time.perf_counter()
@@ -214,7 +218,9 @@ def bench_conv(args, w, torch, binding):
         "scaling": "weak", "vs_baseline": None, "dtype": "f16" if matrix else "f32", "data": "synthetic",
         "config": {"workload": "conv at %s width: B%d d%d L%d, short kernel %d taps + silu + long kernel of L taps, %s I/O, %s"
                                % (w.name, B, d, L, m, dt, "transforms on the matrix cores (fp16 operands, fp32 sums), the "
-                                  "rest fp32" if matrix else "fp32 arithmetic")},
+                                  "rest fp32" if matrix else "fp32 arithmetic" + (", %d blocks of 16384 steps (%d forward "
+                                  "block transforms and %d inverse ones per sequence)" % (nb, nb * (nb + 1) // 2, nb)
+                                  if nb else ""))},
         "roofline": {"bound": "alu", "kernel": "shortlong_conv_kernel", "achieved": round(achieved, 2), "peak": 157.3,
                      "unit": "TFLOP/s", "frac": round(achieved / 157.3, 4), "traffic": None,
                      "flop_model_per_launch": flops, "avg_launch_us": us,

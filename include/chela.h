@@ -257,8 +257,12 @@ int chela_gate_norm_bwd(const void *O, const void *G, const void *dY, void *dO, 
  *              chela_longconv_spectrum_bytes(d, L) bytes that is valid for this d and L and is reused for every batch
  *              until the kernel's weights change.
  * Sequences are zero-padded on chip to twice a transform length M >= L (M in {256, 1024, 4096, 16384}), which makes
- * the circular product of Eq. 7 equal the causal sum; L > 16384 is rejected (CHELA_ERR_BAD_SHAPE).  The forward
- * needs no scratch.  Pointers 16-byte aligned; Z must not overlap an input.  Everything else as for the calls above.
+ * the circular product of Eq. 7 equal the causal sum.  16384 < L <= 1048576: the sequence and the kernel are cut into
+ * blocks of 16384 steps; every block goes through the same on-chip transform, the products of a block of the input
+ * with the blocks of the kernel that reach from it into an output block are added up on the spectra, and one inverse
+ * transform per output block follows (fp32 arithmetic for either I/O type; exact up to rounding like the single
+ * transform, but its work grows with the square of the number of blocks, and `spectrum` holds one spectrum per
+ * channel and block: 128 KB each).  L > 1048576 is rejected (CHELA_ERR_BAD_SHAPE).  The forward needs no scratch.  Pointers 16-byte aligned; Z must not overlap an input.  Everything else as for the calls above.
  * Environment (read per call, tuning aid): CHELA_CONV_MATRIX=0 keeps the vector-ALU kernels for every size. */
 size_t chela_longconv_spectrum_bytes(int d, int L);
 int chela_longconv_spectrum(const float *k_long, void *spectrum, int d, int L, void *stream);

@@ -852,6 +852,7 @@ size_t chela_linattn_noncausal_workspace_bytes(int B, int H, int N, int dk, int 
 size_t chela_longconv_spectrum_bytes(int d, int L)
 {
     const int M = (d > 0 && L > 0) ? conv_fft_size(L) : 0;
+    if (d > 0 && L > 0 && conv_blocks(L)) return conv_blocked_spectrum_bytes(d, L);
     // one (K[k], K[M-k]) pair per 16 bytes; behind them, for the sizes the matrix-core kernel serves, its own copy
     if (!M) return 0;
     const size_t extra = convmx_spectrum_bytes(d, L);
@@ -862,7 +863,7 @@ int chela_longconv_spectrum(const float* k_long, void* spectrum, int d, int L, v
 {
     if (d < 0 || L < 0) return CHELA_ERR_BAD_SHAPE;
     if (d == 0 || L == 0) return CHELA_OK;
-    if (conv_fft_size(L) == 0) return CHELA_ERR_BAD_SHAPE;
+    if (conv_fft_size(L) == 0 && conv_blocks(L) == 0) return CHELA_ERR_BAD_SHAPE;
     if (!k_long || !spectrum) return CHELA_ERR_NULL_POINTER;
     if (((uintptr_t)k_long | (uintptr_t)spectrum) & 15u) return CHELA_ERR_MISALIGNED;
     if (overlap(Range{(const char*)k_long, (size_t)d * L * 4}, Range{(const char*)spectrum, chela_longconv_spectrum_bytes(d, L)}))
@@ -881,7 +882,7 @@ static int shortlong_common(const void* X, const float* w_short, int m, const vo
     if (w_short != nullptr && (m < 1 || m > 32)) return CHELA_ERR_BAD_SHAPE;
     if ((unsigned long long)B * (unsigned long long)d > 0x7fffffffull) return CHELA_ERR_BAD_SHAPE;
     if (B == 0 || d == 0 || L == 0) return CHELA_OK;
-    if (conv_fft_size(L) == 0) return CHELA_ERR_BAD_SHAPE;
+    if (conv_fft_size(L) == 0 && conv_blocks(L) == 0) return CHELA_ERR_BAD_SHAPE;
     if (!X || !spectrum || !Y) return CHELA_ERR_NULL_POINTER;
     if (((uintptr_t)X | (uintptr_t)spectrum | (uintptr_t)Y | (uintptr_t)w_short) & 15u) return CHELA_ERR_MISALIGNED;
     const size_t es = dtype == CHELA_DTYPE_BF16 ? 2 : 4, tb = (size_t)B * d * L * es;
@@ -933,7 +934,7 @@ static int shortlong_bwd_common(const void* X, const float* w_short, int m, cons
     if (B > 65535) return CHELA_ERR_BAD_SHAPE;                                    // batch entries ride on grid.y
     if ((unsigned long long)B * (unsigned long long)d > 0x7fffffffull) return CHELA_ERR_BAD_SHAPE;
     if (d == 0 || L == 0) return CHELA_OK;
-    if (conv_fft_size(L) == 0) return CHELA_ERR_BAD_SHAPE;
+    if (conv_fft_size(L) == 0 && conv_blocks(L) == 0) return CHELA_ERR_BAD_SHAPE;
     hipStream_t st = (hipStream_t)stream;
     if (B == 0) {
         // no data: the kernels received no gradient

@@ -117,6 +117,15 @@ hipError_t launch_bf16_step(const void* q, const void* k, const void* v, float* 
 // Short-long convolutions (Sec. 4.2).  conv_fft_size(L): length M of the complex transform used for sequences of
 // L steps (0: L too long); the kernel spectrum is [d][M/2 + 1] pairs of complex fp32.  dtype 0: bf16 I/O, 1: fp32 I/O.
 int conv_fft_size(int L);
+// Longer sequences (16384 < L <= kConvMaxL) are convolved block by block, 16384 steps per block: the number of
+// blocks (0: L is served by one transform, or too long).  The spectrum buffer then holds one spectrum per channel
+// and block, [d][blocks][8193] pairs of complex fp32.
+constexpr int kConvMaxL = 1 << 20;
+inline int conv_blocks(int L) { return (L > 16384 && L <= kConvMaxL) ? (L + 16383) / 16384 : 0; }
+inline size_t conv_blocked_spectrum_bytes(int d, int L)
+{
+    return (size_t)d * (size_t)conv_blocks(L) * 8193 * 4 * sizeof(float);
+}
 hipError_t launch_longconv_spectrum(const float* k, void* Kf, int d, int L, hipStream_t st);
 // The forward convolution on the matrix cores (bf16 I/O, 4096 < L <= 16384): its own copy of the kernel spectrum
 // (convmx_spectrum_bytes, derived from the pairs above) lives behind them in the caller's spectrum buffer.
@@ -157,6 +166,7 @@ inline int conv_bwd_groups(int B, int d, int L)
 }
 inline size_t conv_bwd_acc_floats(int B, int d, int L, bool bf16_io)
 {
+    if (conv_blocks(L)) return conv_blocked_spectrum_bytes(d, L) / sizeof(float);    // one sum per channel and block distance
     const int M = conv_fft_size(L), G = conv_bwd_groups(B, d, L);
     const size_t pairs = (M >= 16384 || G > 1) ? (size_t)G * d * (M / 2 + 1) * 4 : 0;
     // (the matrix-core kernel -- bf16 I/O, 4096 < L <= 16384, L a multiple of 8 -- parks one spectrum of half-precision

@@ -341,9 +341,11 @@ template <int M, int T, typename IO>
 struct SeqRegs {
     static constexpr int HELD = M / T / 2;
     typename IoPair<IO>::raw_t r[HELD];
-    __device__ __forceinline__ void load(const IO* __restrict__ x, int L, int tid)
+    // vec_ok: x sits on a pair boundary (rows of an even number of steps; a block of a longer row may hold an even
+    // number of steps and still start on an odd element, so the blocked kernels pass the parity of the whole row)
+    __device__ __forceinline__ void load(const IO* __restrict__ x, int L, int tid) { load(x, L, tid, (L & 1) == 0); }
+    __device__ __forceinline__ void load(const IO* __restrict__ x, int L, int tid, bool vec_ok)
     {
-        const bool vec_ok = (L & 1) == 0;        // rows start on a pair boundary
 #pragma unroll
         for (int i = 0; i < HELD; ++i) {
             const int t = 2 * (tid + T * i);
@@ -355,16 +357,18 @@ struct SeqRegs {
 
 // x (one sequence of L steps, in registers) -> optional short kernel and activation -> packed complex
 // z[n] = v[2n] + i v[2n+1] in a[], zero beyond L.  Ends with the data in place but NOT synchronised.
+// hist (only read with a short kernel): null for a sequence's first step (zero history), else a pointer at the first
+// of these L steps inside a longer row, whose 32 predecessors are then the history.
 template <int M, int T, typename IO>
 __device__ __forceinline__ void stage_input(const SeqRegs<M, T, IO>& x, const float* __restrict__ wc, int m, int L,
-                                            cplx* a, int tid)
+                                            cplx* a, int tid, const IO* __restrict__ hist = nullptr)
 {
     constexpr int PER = M / T, HELD = PER / 2;
     if (wc != nullptr) {
-        // raw x as floats behind 32 zeros (the zero history), so that no tap needs a bounds check
+        // raw x as floats behind 32 steps of history (zeros at a sequence's start), so that no tap needs a bounds check
         float* sx = reinterpret_cast<float*>(a);
         constexpr int ZP = 32;
-        if (tid < ZP) sx[tid] = 0.f;
+        if (tid < ZP) sx[tid] = hist != nullptr ? (float)hist[tid - ZP] : 0.f;
 #pragma unroll
         for (int i = 0; i < HELD; ++i) {
             const int t = 2 * (tid + T * i);
@@ -875,6 +879,326 @@ __global__ __launch_bounds__(64) void shortconv_dw_kernel(const float* __restric
     dw[(long)c * m + j] = t;
 }
 
+
+// =============================================================================================== sequences beyond one transform
+// L > 16384: the sequence and the long kernel are cut into blocks of BK = 16384 steps, x_0 .. x_{nb-1} and
+// k_0 .. k_{nb-1}.  Output block j of the causal sum is
+//     y_j = sum_{i <= j}  low half of  circ_{2 BK}( [x_i ; 0] , [k_{j-i} ; k_{j-i-1}] )          (k_{-1} = 0)
+// (the taps that reach from block i into block j are the 2 BK - 1 taps around lag (j - i) BK: the upper half of the
+// second operand holds the ones below that lag, which a circular product of length 2 BK wraps onto the low outputs
+// exactly where they belong).  So every block is transformed by the same length-M machinery as a short sequence
+// (zero upper half in, low half out), the sum over i is taken on the spectra, in registers, and one inverse
+// transform per output block follows.  The spectrum of [k_m ; k_{m-1}] is A_m + (-1)^bin A_{m-1} with A_m the
+// spectrum of [k_m ; 0] (a shift by half the period), which is what longconv_spectrum_blocked_kernel stores:
+// [d][nb][M/2 + 1] pairs in pair order.  The two long-stage gradients have the same shape:
+//     dv_i = sum_{j >= i} low half of the circular CORRELATION of [dz_j ; 0] with [k_{j-i} ; k_{j-i-1}]   (conjugate spectra),
+//     dk_m = low half of the inverse of  D_m + (-1)^bin D_{m+1},   D_m = sum_b sum_i DZ_{i+m} conj(V_i).
+// The work per sequence grows with nb (nb + 1) / 2 block pairs, against nb log nb for one long transform held in
+// memory: this path is here so that no length is refused, not to be the fastest way to convolve a million steps.
+constexpr int kBlkM = 16384;                 // transform length and block length (steps)
+
+// Spectra G_m of the blocks of the long kernel; one workgroup per (channel, block).
+__global__ __launch_bounds__(conv_threads(kBlkM)) void longconv_spectrum_blocked_kernel(const float* __restrict__ k,
+                                                                                       float4* __restrict__ Gf, int L,
+                                                                                       int nb)
+{
+    constexpr int M = kBlkM, T = conv_threads(M), NP = (M / 2) / T + 1;
+    __shared__ __attribute__((aligned(16))) unsigned char lds[ConvLds<M>::BYTES];
+    cplx* a = reinterpret_cast<cplx*>(lds);
+    cplx* lo = a + ConvLds<M>::DATA;
+    cplx* hi = lo + 128;
+    const int tid = threadIdx.x;
+    const long c = blockIdx.x;
+    const int mb = blockIdx.y;
+    const bool row_vec = (L & 1) == 0;
+    build_tables<M, T>(lo, hi, tid);
+    float4 sum[NP];
+#pragma unroll
+    for (int i = 0; i < NP; ++i) sum[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int which = (mb > 0 ? mb - 1 : mb); which <= mb; ++which) {
+        const int len = min(M, L - which * M);
+        SeqRegs<M, T, float> kr;
+        kr.load(k + c * (long)L + (long)which * M, len, tid, row_vec);
+        __syncthreads();                  // tables built / the block before has been read out of a[]
+        stage_input<M, T, float>(kr, nullptr, 0, len, a, tid);
+        __syncthreads();
+        fft_passes<M, T, false>(a, lo, hi, tid);
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < NP; ++i) {
+            const int l = tid + T * i;
+            if (l <= M / 2) {
+                const int kk = pair_bin<M>(l);
+                cplx Xk, Xmk;
+                untangle(a[conv_pad(spectrum_pos<M>(kk))], conj(a[conv_pad(spectrum_pos<M>((M - kk) & (M - 1)))]),
+                         w2m(kk, M), Xk, Xmk);
+                // the block before sits in the upper half of the period: (-1)^bin (bins kk and M - kk: same parity)
+                const float sg = (which < mb && (kk & 1)) ? -1.f : 1.f;
+                sum[i].x += sg * Xk.x; sum[i].y += sg * Xk.y; sum[i].z += sg * Xmk.x; sum[i].w += sg * Xmk.y;
+            }
+        }
+    }
+    float4* out = Gf + (c * nb + mb) * (long)(M / 2 + 1);
+#pragma unroll
+    for (int i = 0; i < NP; ++i) {
+        const int l = tid + T * i;
+        if (l <= M / 2) out[l] = sum[i];
+    }
+}
+
+// Forward (CORR = false: X -> optional short kernel and activation -> causal sum with the long kernel, block `blk` of
+// the output from the blocks 0 .. blk of the input) and correlation (CORR = true: dZ -> dV, block blk from the blocks
+// blk .. nb-1, conjugate spectra; no short stage).  Work items (sequence, output block), the costliest blocks first,
+// dealt to a launch of no more workgroups than are resident at once.
+template <typename IN, typename OUT, bool CORR>
+__global__ __launch_bounds__(conv_threads(kBlkM)) void longconv_blocked_kernel(const IN* __restrict__ X,
+                                                                              const float* __restrict__ w_short, int m,
+                                                                              const float4* __restrict__ Gf,
+                                                                              OUT* __restrict__ Y, int d, int L, int nb,
+                                                                              long BD)
+{
+    constexpr int M = kBlkM, T = conv_threads(M), NP = (M / 2) / T + 1;
+    __shared__ __attribute__((aligned(16))) unsigned char lds[ConvLds<M>::BYTES];
+    cplx* a = reinterpret_cast<cplx*>(lds);
+    cplx* lo = a + ConvLds<M>::DATA;
+    cplx* hi = lo + 128;
+    const int tid = threadIdx.x;
+    const bool row_vec = (L & 1) == 0;
+    const float scale = 1.0f / (float)M;
+    build_tables<M, T>(lo, hi, tid);
+    const long items = BD * nb;
+    for (long id = blockIdx.x; id < items; id += gridDim.x) {
+        const int r = (int)(id / BD);
+        const long bc = id - (long)r * BD;
+        const int blk = CORR ? r : nb - 1 - r;            // costliest first: nb - blk (CORR) or blk + 1 input blocks
+        const int c = (int)(bc % d);
+        const int o0 = CORR ? blk : 0, o1 = CORR ? nb - 1 : blk;
+        const IN* xrow = X + bc * (long)L;
+        const float* wc = (!CORR && w_short) ? w_short + (long)c * m : nullptr;
+        cplx accK[NP], accMK[NP];                           // sums over the input blocks of X_o G_|o - blk|, bins k and M - k
+#pragma unroll
+        for (int i = 0; i < NP; ++i) { accK[i] = mk(0.f, 0.f); accMK[i] = mk(0.f, 0.f); }
+        SeqRegs<M, T, IN> xr;
+        xr.load(xrow + (long)o0 * M, min(M, L - o0 * M), tid, row_vec);
+        for (int o = o0; o <= o1; ++o) {
+            int tp = tid;
+            asm volatile("" : "+v"(tp));
+            __syncthreads();    // tables built / a[] has been read out
+            stage_input<M, T, IN>(xr, wc, m, min(M, L - o * M), a, tp, (wc && o > 0) ? xrow + (long)o * M : nullptr);
+            if (o < o1) xr.load(xrow + (long)(o + 1) * M, min(M, L - (o + 1) * M), tp, row_vec);   // the next block, in flight
+            __syncthreads();
+            tp = tid;
+            asm volatile("" : "+v"(tp));
+            fft_passes<M, T, false>(a, lo, hi, tp);
+            __syncthreads();
+            tp = tid;
+            asm volatile("" : "+v"(tp));
+            const float4* Gc = Gf + ((long)c * nb + (CORR ? o - blk : blk - o)) * (long)(M / 2 + 1);
+            float4 kq[NP];
+#pragma unroll
+            for (int i = 0; i < NP; ++i) {
+                const int l = tp + T * i;
+                if (l <= M / 2) kq[i] = Gc[l];
+            }
+            PairTwiddle<M, T> pw(tp);
+#pragma unroll
+            for (int i = 0; i < NP; ++i) {
+                const int l = tp + T * i;
+                if (l <= M / 2) {
+                    const int kk = pair_bin<M>(l);
+                    const cplx w = pw.next(l);
+                    cplx Xk, Xmk;
+                    untangle(a[conv_pad(spectrum_pos<M>(kk))], conj(a[conv_pad(spectrum_pos<M>((M - kk) & (M - 1)))]), w,
+                             Xk, Xmk);
+                    const cplx K1 = mk(kq[i].x, CORR ? -kq[i].y : kq[i].y), K2 = mk(kq[i].z, CORR ? -kq[i].w : kq[i].w);
+                    accK[i] = cadd(accK[i], cmul(Xk, K1));
+                    accMK[i] = cadd(accMK[i], cmul(Xmk, K2));
+                }
+                __builtin_amdgcn_sched_barrier(0);   // one pair at a time: the unrolled pairs must not pile up in registers
+            }
+        }
+        __syncthreads();        // every thread has read its bins of the last input block
+        {
+            int tp = tid;
+            asm volatile("" : "+v"(tp));
+            PairTwiddle<M, T> pw(tp);
+#pragma unroll
+            for (int i = 0; i < NP; ++i) {
+                const int l = tp + T * i;
+                if (l <= M / 2) {
+                    const int kk = pair_bin<M>(l);
+                    const int p1 = conv_pad(spectrum_pos<M>(kk)), p2 = conv_pad(spectrum_pos<M>((M - kk) & (M - 1)));
+                    const cplx w = pw.next(l);
+                    if (kk == 0) {      // bins 0 and M are real and share storage slot 0
+                        a[p1] = mk(0.5f * (accK[i].x + accMK[i].x), 0.5f * (accK[i].x - accMK[i].x));
+                    } else {
+                        cplx Zk, Zmk;
+                        tangle(accK[i], accMK[i], w, Zk, Zmk);
+                        a[p1] = Zk;
+                        if (p2 != p1) a[p2] = Zmk;
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        {
+            int tp = tid;
+            asm volatile("" : "+v"(tp));
+            fft_passes<M, T, true>(a, lo, hi, tp);
+            __syncthreads();
+            OUT* y = Y + bc * (long)L + (long)blk * M;
+            const int len = min(M, L - blk * M);
+#pragma unroll
+            for (int i = 0; i < M / T / 2; ++i) {
+                const int n = tp + T * i, t = 2 * n;
+                if (t < len) {
+                    const cplx v = a[conv_pad(n)];
+                    if (row_vec) IoPair<OUT>::store2(y + t, v.x * scale, v.y * scale);
+                    else { y[t] = (OUT)(v.x * scale); if (t + 1 < len) y[t + 1] = (OUT)(v.y * scale); }
+                }
+            }
+        }
+    }
+}
+
+// Sums D_mb = sum_b sum_i DZ_{i+mb} conj(V_i) of one channel and one block distance, kept in memory ([d][nb][M/2 + 1]
+// pairs; every thread only ever touches its own pairs).  One workgroup per (channel, distance), the distances with
+// the most block pairs first.
+template <typename IO>
+__global__ __launch_bounds__(conv_threads(kBlkM)) void longconv_dk_blocked_kernel(const IO* __restrict__ X,
+                                                                                 const float* __restrict__ w_short, int m,
+                                                                                 const IO* __restrict__ dZ,
+                                                                                 float4* __restrict__ acc_ws, int B, int d,
+                                                                                 int L, int nb)
+{
+    constexpr int M = kBlkM, T = conv_threads(M), NP = (M / 2) / T + 1;
+    __shared__ __attribute__((aligned(16))) unsigned char lds[ConvLds<M>::BYTES];
+    cplx* a = reinterpret_cast<cplx*>(lds);
+    cplx* lo = a + ConvLds<M>::DATA;
+    cplx* hi = lo + 128;
+    const int tid = threadIdx.x;
+    const int c = blockIdx.x, mb = blockIdx.y;
+    const bool row_vec = (L & 1) == 0;
+    build_tables<M, T>(lo, hi, tid);
+    float4* accm = acc_ws + ((long)c * nb + mb) * (long)(M / 2 + 1);
+    const float* wc = w_short ? w_short + (long)c * m : nullptr;
+    const int n_i = nb - mb;                     // block pairs (i, i + mb) per sequence
+    const long n_pairs = (long)B * n_i;
+    cplx Gk[NP], Gmk[NP];
+    SeqRegs<M, T, IO> zr, xr;
+    zr.load(dZ + (long)c * L + (long)mb * M, min(M, L - mb * M), tid, row_vec);      // pair 0: b = 0, i = 0
+    for (long pr = 0; pr < n_pairs; ++pr) {
+        const int b = (int)(pr / n_i), i = (int)(pr - (long)b * n_i), j = i + mb;
+        const long row = ((long)b * d + c) * (long)L;
+        int tp = tid;
+        asm volatile("" : "+v"(tp));
+        __syncthreads();        // tables built / a[] has been read out
+        stage_input<M, T, IO>(zr, nullptr, 0, min(M, L - j * M), a, tp);
+        xr.load(X + row + (long)i * M, min(M, L - i * M), tp, row_vec);
+        __syncthreads();
+        fft_passes<M, T, false>(a, lo, hi, tp);
+        __syncthreads();
+        tp = tid;
+        asm volatile("" : "+v"(tp));
+        {
+            PairTwiddle<M, T> pw(tp);
+#pragma unroll
+            for (int q = 0; q < NP; ++q) {
+                const int l = tp + T * q;
+                if (l <= M / 2) {
+                    const int kk = pair_bin<M>(l);
+                    untangle(a[conv_pad(spectrum_pos<M>(kk))], conj(a[conv_pad(spectrum_pos<M>((M - kk) & (M - 1)))]),
+                             pw.next(l), Gk[q], Gmk[q]);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        __syncthreads();
+        tp = tid;
+        asm volatile("" : "+v"(tp));
+        stage_input<M, T, IO>(xr, wc, m, min(M, L - i * M), a, tp, (wc && i > 0) ? X + row + (long)i * M : nullptr);
+        if (pr + 1 < n_pairs) {
+            const int b2 = (int)((pr + 1) / n_i), i2 = (int)(pr + 1 - (long)b2 * n_i);
+            zr.load(dZ + ((long)b2 * d + c) * (long)L + (long)(i2 + mb) * M, min(M, L - (i2 + mb) * M), tp, row_vec);
+        }
+        __syncthreads();
+        fft_passes<M, T, false>(a, lo, hi, tp);
+        __syncthreads();
+        tp = tid;
+        asm volatile("" : "+v"(tp));
+        {
+            PairTwiddle<M, T> pw(tp);
+#pragma unroll
+            for (int q = 0; q < NP; ++q) {
+                const int l = tp + T * q;
+                if (l <= M / 2) {
+                    const int kk = pair_bin<M>(l);
+                    cplx Vk, Vmk;
+                    untangle(a[conv_pad(spectrum_pos<M>(kk))], conj(a[conv_pad(spectrum_pos<M>((M - kk) & (M - 1)))]),
+                             pw.next(l), Vk, Vmk);
+                    const cplx pk = cmul(Gk[q], conj(Vk)), pmk = cmul(Gmk[q], conj(Vmk));
+                    float4 t = make_float4(pk.x, pk.y, pmk.x, pmk.y);
+                    if (pr > 0) { const float4 o = accm[l]; t.x += o.x; t.y += o.y; t.z += o.z; t.w += o.w; }
+                    accm[l] = t;
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    }
+}
+
+// dk block mb of a channel from the sums above: inverse of D_mb + (-1)^bin D_{mb+1}, low half.
+__global__ __launch_bounds__(conv_threads(kBlkM)) void longconv_dk_blocked_finish_kernel(const float4* __restrict__ acc_ws,
+                                                                                        float* __restrict__ dk, int d,
+                                                                                        int L, int nb)
+{
+    constexpr int M = kBlkM, T = conv_threads(M);
+    __shared__ __attribute__((aligned(16))) unsigned char lds[ConvLds<M>::BYTES];
+    cplx* a = reinterpret_cast<cplx*>(lds);
+    cplx* lo = a + ConvLds<M>::DATA;
+    cplx* hi = lo + 128;
+    const int tid = threadIdx.x;
+    const int c = blockIdx.x, mb = blockIdx.y;
+    build_tables<M, T>(lo, hi, tid);
+    const float4* D0 = acc_ws + ((long)c * nb + mb) * (long)(M / 2 + 1);
+    const float4* D1 = mb + 1 < nb ? D0 + (M / 2 + 1) : nullptr;
+    PairTwiddle<M, T> pw(tid);
+    for (int l = tid; l <= M / 2; l += T) {
+        const int kk = pair_bin<M>(l);
+        const int p1 = conv_pad(spectrum_pos<M>(kk)), p2 = conv_pad(spectrum_pos<M>((M - kk) & (M - 1)));
+        const cplx w = pw.next(l);
+        float4 t = D0[l];
+        if (D1 != nullptr) {
+            const float4 o = D1[l];
+            const float sg = (kk & 1) ? -1.f : 1.f;
+            t.x += sg * o.x; t.y += sg * o.y; t.z += sg * o.z; t.w += sg * o.w;
+        }
+        const cplx sk = mk(t.x, t.y), smk = mk(t.z, t.w);
+        if (kk == 0) {
+            a[p1] = mk(0.5f * (sk.x + smk.x), 0.5f * (sk.x - smk.x));
+        } else {
+            cplx Zk, Zmk;
+            tangle(sk, smk, w, Zk, Zmk);
+            a[p1] = Zk;
+            if (p2 != p1) a[p2] = Zmk;
+        }
+    }
+    __syncthreads();
+    fft_passes<M, T, true>(a, lo, hi, tid);
+    __syncthreads();
+    float* out = dk + (long)c * L + (long)mb * M;
+    const int len = min(M, L - mb * M);
+    const float scale = 1.0f / (float)M;
+    for (int n = tid; n < M / 2; n += T) {
+        const int t = 2 * n;
+        if (t < len) {
+            const cplx v = a[conv_pad(n)];
+            out[t] = v.x * scale;
+            if (t + 1 < len) out[t + 1] = v.y * scale;
+        }
+    }
+}
+
 int conv_fft_size(int L)
 {
     if (L <= 256) return 256;
@@ -889,6 +1213,10 @@ hipError_t launch_longconv_spectrum(const float* k, void* Kf, int d, int L, hipS
     const int M = conv_fft_size(L);
     ProfScope prof(KID_CONV_SPECTRUM, st);
     float4* out = (float4*)Kf;
+    if (const int nb = conv_blocks(L)) {
+        hipLaunchKernelGGL(longconv_spectrum_blocked_kernel, dim3(d, nb), dim3(conv_threads(kBlkM)), 0, st, k, out, L, nb);
+        return hipGetLastError();
+    }
     switch (M) {
         case 256: hipLaunchKernelGGL((longconv_spectrum_kernel<256>), dim3(d), dim3(conv_threads(256)), 0, st, k, out, L); break;
         case 1024: hipLaunchKernelGGL((longconv_spectrum_kernel<1024>), dim3(d), dim3(conv_threads(1024)), 0, st, k, out, L); break;
@@ -912,12 +1240,27 @@ static long resident_workgroups(K kernel, int threads)
     return (long)cus * per_cu;
 }
 
+// The blocked kernel for L > 16384: work items (sequence, output block) over no more workgroups than are resident.
+template <typename IN, typename OUT, bool CORR>
+static hipError_t conv_blocked_launch(const IN* X, const float* w, int m, const float4* Gf, OUT* Y, long BD, int d, int L,
+                                      hipStream_t st)
+{
+    const int nb = conv_blocks(L);
+    static const long slots = resident_workgroups(longconv_blocked_kernel<IN, OUT, CORR>, conv_threads(kBlkM));
+    const long items = BD * nb;
+    const dim3 grid((unsigned)(items < slots ? items : slots));
+    hipLaunchKernelGGL((longconv_blocked_kernel<IN, OUT, CORR>), grid, dim3(conv_threads(kBlkM)), 0, st, X, w, m, Gf, Y, d,
+                       L, nb, BD);
+    return hipGetLastError();
+}
+
 template <typename IN, typename OUT>
 static hipError_t conv_dispatch(const IN* X, const float* w, int m, const float4* Kf, OUT* Y, long BD, int d, int L,
                                 hipStream_t st)
 {
     const int M = conv_fft_size(L);
     ProfScope prof(KID_CONV_FWD, st);
+    if (conv_blocks(L)) return conv_blocked_launch<IN, OUT, false>(X, w, m, Kf, Y, BD, d, L, st);
     // no more workgroups than are resident at once, each with an equal share of the sequences
 #define CHELA_CONV_FWD(M_)                                                                                              \
     case M_: {                                                                                                          \
@@ -997,6 +1340,18 @@ static hipError_t conv_longbwd_dispatch(const IO* X, const float* w, int m, cons
 {
     const int M = conv_fft_size(L), G = conv_bwd_groups(B, d, L);
     ProfScope prof(KID_CONV_LONG_BWD, st);
+    if (const int nb = conv_blocks(L)) {
+        // dV block by block (correlation with the kernel's blocks), then the sums of the kernel gradient per block
+        // distance and their way back
+        hipError_t e = conv_blocked_launch<IO, DVT, true>(dZ, nullptr, 0, Kf, dV, (long)B * d, d, L, st);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL((longconv_dk_blocked_kernel<IO>), dim3(d, nb), dim3(conv_threads(kBlkM)), 0, st, X, w, m, dZ,
+                           acc_ws, B, d, L, nb);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+        hipLaunchKernelGGL(longconv_dk_blocked_finish_kernel, dim3(d, nb), dim3(conv_threads(kBlkM)), 0, st, acc_ws, dk, d,
+                           L, nb);
+        return hipGetLastError();
+    }
     const dim3 grid(d, G);
 #define CHELA_LONGBWD(M_)                                                                                               \
     case M_:                                                                                                            \

@@ -195,19 +195,22 @@ def test_conv_argument_errors(L):
     # the (K[k], K[M-k]) pairs; for 4096 < L <= 16384 also the copy the matrix-core kernel reads (32768 complex
     # half-precision numbers and a scale per channel), each of the two parts rounded up to 256 bytes
     up = lambda n: (n + 255) // 256 * 256
-    assert sb(3, 4096) == 3 * 2049 * 16 and sb(3, 16385) == 0 and sb(0, 64) == 0
+    assert sb(3, 4096) == 3 * 2049 * 16 and sb(0, 64) == 0
+    # beyond 16384 steps: one spectrum per channel and block of 16384 steps, up to 2^20 steps
+    assert sb(3, 16385) == 3 * 2 * 8193 * 16 and sb(2, 65536) == 2 * 4 * 8193 * 16 and sb(1, 65537) == 5 * 8193 * 16
+    assert sb(1, 1 << 20) == 64 * 8193 * 16 and sb(3, (1 << 20) + 1) == 0
     assert sb(3, 16384) == up(3 * 8193 * 16) + 3 * 32768 * 4 + up(3 * 4)
     assert sb(2, 257) == 2 * 513 * 16 and sb(2, 256) == 2 * 129 * 16 and sb(1, 1) == 129 * 16
     K, S, X, W, Y = A, A + SZ, A + 2 * SZ, A + 3 * SZ, A + 4 * SZ
     assert sp(None, S, 4, 100, None) == -1
     assert sp(K, S + 8, 4, 100, None) == -5
-    assert sp(K, S, 4, 20000, None) == -2
+    assert sp(K, S, 4, (1 << 20) + 1, None) == -2
     assert sp(K, K, 4, 100, None) == -6
     assert sp(K, S, 0, 100, None) == 0
     assert f(None, W, 9, S, Y, 2, 4, 100, None) == -1
     assert f(X, W, 0, S, Y, 2, 4, 100, None) == -2
     assert f(X, W, 33, S, Y, 2, 4, 100, None) == -2
-    assert f(X, W, 9, S, Y, 2, 4, 16385, None) == -2
+    assert f(X, W, 9, S, Y, 2, 4, (1 << 20) + 1, None) == -2
     assert f(X, W, 9, S, X, 2, 4, 100, None) == -6
     assert f(X, W, 9, S, Y + 6, 2, 4, 100, None) == -5
     assert f(X, None, 0, S, Y, 0, 4, 100, None) == 0
@@ -233,10 +236,13 @@ def test_conv_bwd_argument_errors(L):
     assert wsb(2, 4, 16000, 0, 1) == 2 * 4 * 8193 * 16
     assert wsb(2, 4, 16000, 1, 1) == 2 * 4 * 8193 * 16 + 2 * 4 * (16000 * 4 + 8 * 128)
     assert wsb(2, 4, 16000, 1, 0) == 256 * 32768 * 4 + 2 * 4 * (16000 * 4 + 8 * 128)
+    # beyond 16384 steps: one running sum per channel and block distance, whatever the batch size and I/O type
+    assert wsb(3, 4, 40000, 0, 0) == 4 * 3 * 8193 * 16 and wsb(1, 4, 40000, 0, 1) == 4 * 3 * 8193 * 16
+    assert wsb(2, 4, 40000, 1, 0) == 4 * 3 * 8193 * 16 + 2 * 4 * (40000 * 4 + 20 * 128)
     assert g(None, W, 9, S, dZ, dX, dW, dK, 2, 4, 100, None) == -1
     assert g(X, W, 9, S, dZ, dX, None, dK, 2, 4, 100, None) == -1
     assert g(X, W, 33, S, dZ, dX, dW, dK, 2, 4, 100, None) == -2          # at most 32 taps, as in the forward
-    assert g(X, W, 9, S, dZ, dX, dW, dK, 2, 4, 20000, None) == -2
+    assert g(X, W, 9, S, dZ, dX, dW, dK, 2, 4, (1 << 20) + 1, None) == -2
     assert g(X, W, 9, S, dZ, X, dW, dK, 2, 4, 100, None) == -6
     assert g(X, W, 9, S, dZ, dX, dW, dX, 2, 4, 100, None) == -6
     assert g(X, W, 9, S, dZ + 2, dX, dW, dK, 2, 4, 100, None) == -5

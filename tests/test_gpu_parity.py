@@ -1059,6 +1059,52 @@ def test_conv_bwd_sequences_dealt_over_workgroups(shape):
     _check("dw", dw[ch], rw, dtype)
 
 
+# ------------------------------------------------------------------------------------------ convolutions beyond 16384 steps
+@pytest.mark.parametrize("shape", [(1, 2, 16385, 9, "f32", True), (2, 3, 20000, 5, "f32", True),
+                                   (1, 2, 40001, 9, "f32", True), (1, 2, 65536, 3, "f32", True),
+                                   (1, 2, 33000, 3, "f32", False), (2, 2, 32768, 9, "bf16", True),
+                                   (1, 3, 50001, 17, "bf16", True), (3, 1, 36864, 32, "bf16", False)])
+def test_shortlong_conv_longer_than_one_transform(shape):
+    # L > 16384: blocks of 16384 steps, the sum over the input blocks taken on the spectra; one step beyond a block,
+    # ragged and odd lengths (rows that start on odd elements), whole blocks, every tap-count class, both I/O types
+    B, d, L, m, dtype, short = shape
+    _run_conv_case(B, d, L, m, dtype, seed=L + 21, short=short)
+
+
+@pytest.mark.parametrize("shape", [(2, 2, 16385, 9, "f32", True), (2, 3, 40001, 5, "f32", True),
+                                   (1, 2, 65536, 9, "f32", True), (2, 2, 20000, 3, "f32", False),
+                                   (2, 2, 32768, 9, "bf16", True), (3, 1, 50001, 17, "bf16", True)])
+def test_shortlong_conv_bwd_longer_than_one_transform(shape):
+    B, d, L, m, dtype, short = shape
+    _run_conv_bwd_case(B, d, L, m, dtype, seed=L + 23, short=short)
+
+
+def test_long_conv_delay_across_blocks_and_determinism():
+    # a unit impulse at a lag beyond the first block as the long kernel: the output is the activated short-conv
+    # output delayed by that lag, whichever blocks the lag reaches across; two runs agree bit for bit
+    L, lag = 45000, 20011
+    x = make_conv_inputs(1, 2, L, 9, 31, "f32")
+    dev = _dev(x)
+    k = torch.zeros_like(dev["k_long"])
+    k[:, lag] = 1.0
+    spec = binding.chela_longconv_spectrum(k)
+    Z1 = binding.chela_shortlong_conv_fwd(dev["X"], dev["w_short"], spec)
+    Z2 = binding.chela_shortlong_conv_fwd(dev["X"], dev["w_short"], spec)
+    torch.cuda.synchronize()
+    assert torch.equal(Z1, Z2)
+    v = oracle_conv.short_conv(to_f64_numpy(x["X"]), to_f64_numpy(x["w_short"]))
+    want = np.zeros_like(v)
+    want[..., lag:] = v[..., :-lag]
+    assert oracle.rel_l2(to_f64_numpy(Z1), want) <= 1e-5
+    g = torch.Generator(device="cpu")
+    g.manual_seed(5)
+    dZ = torch.randn(1, 2, L, generator=g, dtype=torch.float32).cuda()
+    a = binding.chela_shortlong_conv_bwd(dev["X"], dev["w_short"], spec, dZ)
+    b = binding.chela_shortlong_conv_bwd(dev["X"], dev["w_short"], spec, dZ)
+    torch.cuda.synchronize()
+    assert all(torch.equal(p, q) for p, q in zip(a, b))
+
+
 # ------------------------------------------------------------------------------------------ [B,N,H,d] layout
 @pytest.mark.parametrize("shape", [(1, 1, 64, 64, 64), (2, 3, 1000, 64, 64), (1, 5, 9000, 64, 64), (3, 2, 1100, 64, 128),
                                    (1, 3, 1300, 128, 64), (2, 2, 700, 128, 128), (1, 2, 1, 64, 64)])
