@@ -108,19 +108,22 @@ def test_lra_bf16_full(chunk):
     _run_case(w, chunk, False)
 
 
-def test_lm_bf16_full():
+@pytest.mark.parametrize("chunk", [64, 128])
+def test_lm_bf16_full(chunk):
     w = WORKLOADS["lm_bf16"]
-    _run_case(w, 64, True)
+    _run_case(w, chunk, True)
 
 
-def test_long_bf16_full():
+@pytest.mark.parametrize("chunk", [64, 128])
+def test_long_bf16_full(chunk):
     w = WORKLOADS["long_bf16"]
-    _run_case(w, 64, False)
+    _run_case(w, chunk, False)
 
 
-def test_mixed_bf16_full():
+@pytest.mark.parametrize("chunk", [64, 128])
+def test_mixed_bf16_full(chunk):
     w = WORKLOADS["mixed_bf16"]
-    _run_case(w, 64, True)
+    _run_case(w, chunk, True)
 
 
 # ------------------------------------------------------------------------------------------ properties on the GPU
@@ -1103,6 +1106,36 @@ def test_long_conv_delay_across_blocks_and_determinism():
     b = binding.chela_shortlong_conv_bwd(dev["X"], dev["w_short"], spec, dZ)
     torch.cuda.synchronize()
     assert all(torch.equal(p, q) for p, q in zip(a, b))
+
+
+def test_long_conv_at_the_longest_supported_length():
+    # 2^20 steps, 64 blocks: the direct-sum oracle would need 5e11 products per sequence, so the check goes through
+    # what is exact at any size.  With a unit impulse at lag g as the long kernel the forward delays its input by g
+    # steps, dX is dZ advanced by g steps, and the kernel gradient at lag s is the plain dot product of dZ with the
+    # input delayed by s steps (taken here in fp64 for a sample of lags from every part of the range).
+    L, lag = 1 << 20, 700001
+    g = torch.Generator(device="cpu")
+    g.manual_seed(41)
+    X = torch.randn(1, 1, L, generator=g, dtype=torch.float32)
+    dZ = torch.randn(1, 1, L, generator=g, dtype=torch.float32)
+    k = torch.zeros(1, L)
+    k[0, lag] = 1.0
+    spec = binding.chela_longconv_spectrum(k.cuda())
+    Z = binding.chela_shortlong_conv_fwd(X.cuda(), None, spec)
+    dX, _, dk = binding.chela_shortlong_conv_bwd(X.cuda(), None, spec, dZ.cuda())
+    torch.cuda.synchronize()
+    x, gz = to_f64_numpy(X)[0, 0], to_f64_numpy(dZ)[0, 0]
+    want = np.zeros(L)
+    want[lag:] = x[:-lag]
+    assert oracle.rel_l2(to_f64_numpy(Z)[0, 0], want) <= 1e-5
+    want = np.zeros(L)
+    want[:-lag] = gz[lag:]
+    assert oracle.rel_l2(to_f64_numpy(dX)[0, 0], want) <= 1e-5
+    lags = [0, 1, 16383, 16384, 16385, 500000, 700001, L - 16385, L - 2, L - 1]
+    got = to_f64_numpy(dk)[0, lags]
+    ref = np.array([np.dot(gz[s:], x[:L - s]) for s in lags])
+    # (sums of up to 2^20 products of unit-variance terms: the bar is taken against the size such a sum has)
+    assert np.abs(got - ref).max() <= 1e-5 * np.sqrt(L)
 
 
 # ------------------------------------------------------------------------------------------ [B,N,H,d] layout
