@@ -896,13 +896,18 @@ __global__ __launch_bounds__(64) void shortconv_dw_kernel(const float* __restric
 // The work per sequence grows with nb (nb + 1) / 2 block pairs, against nb log nb for one long transform held in
 // memory: this path is here so that no length is refused, not to be the fastest way to convolve a million steps.
 constexpr int kBlkM = 16384;                 // transform length and block length (steps)
+// Threads per workgroup of the blocked kernels.  1024 leave each thread 128 registers, which the 36 accumulators of the
+// forward kernel overflow (40-70 spilled registers); 512 threads with 256 registers each spill nothing and were
+// measured slower all the same (2.39 against 1.94 ms at B1 d2048 L65536): sixteen waves hide the transforms' LDS
+// latencies better than eight.
+constexpr int kBlkT = conv_threads(kBlkM);
 
 // Spectra G_m of the blocks of the long kernel; one workgroup per (channel, block).
-__global__ __launch_bounds__(conv_threads(kBlkM)) void longconv_spectrum_blocked_kernel(const float* __restrict__ k,
+__global__ __launch_bounds__(kBlkT) void longconv_spectrum_blocked_kernel(const float* __restrict__ k,
                                                                                        float4* __restrict__ Gf, int L,
                                                                                        int nb)
 {
-    constexpr int M = kBlkM, T = conv_threads(M), NP = (M / 2) / T + 1;
+    constexpr int M = kBlkM, T = kBlkT, NP = (M / 2) / T + 1;
     __shared__ __attribute__((aligned(16))) unsigned char lds[ConvLds<M>::BYTES];
     cplx* a = reinterpret_cast<cplx*>(lds);
     cplx* lo = a + ConvLds<M>::DATA;
@@ -951,13 +956,13 @@ __global__ __launch_bounds__(conv_threads(kBlkM)) void longconv_spectrum_blocked
 // blk .. nb-1, conjugate spectra; no short stage).  Work items (sequence, output block), the costliest blocks first,
 // dealt to a launch of no more workgroups than are resident at once.
 template <typename IN, typename OUT, bool CORR>
-__global__ __launch_bounds__(conv_threads(kBlkM)) void longconv_blocked_kernel(const IN* __restrict__ X,
+__global__ __launch_bounds__(kBlkT) void longconv_blocked_kernel(const IN* __restrict__ X,
                                                                               const float* __restrict__ w_short, int m,
                                                                               const float4* __restrict__ Gf,
                                                                               OUT* __restrict__ Y, int d, int L, int nb,
                                                                               long BD)
 {
-    constexpr int M = kBlkM, T = conv_threads(M), NP = (M / 2) / T + 1;
+    constexpr int M = kBlkM, T = kBlkT, NP = (M / 2) / T + 1;
     __shared__ __attribute__((aligned(16))) unsigned char lds[ConvLds<M>::BYTES];
     cplx* a = reinterpret_cast<cplx*>(lds);
     cplx* lo = a + ConvLds<M>::DATA;
@@ -1065,13 +1070,13 @@ __global__ __launch_bounds__(conv_threads(kBlkM)) void longconv_blocked_kernel(c
 // pairs; every thread only ever touches its own pairs).  One workgroup per (channel, distance), the distances with
 // the most block pairs first.
 template <typename IO>
-__global__ __launch_bounds__(conv_threads(kBlkM)) void longconv_dk_blocked_kernel(const IO* __restrict__ X,
+__global__ __launch_bounds__(kBlkT) void longconv_dk_blocked_kernel(const IO* __restrict__ X,
                                                                                  const float* __restrict__ w_short, int m,
                                                                                  const IO* __restrict__ dZ,
                                                                                  float4* __restrict__ acc_ws, int B, int d,
                                                                                  int L, int nb)
 {
-    constexpr int M = kBlkM, T = conv_threads(M), NP = (M / 2) / T + 1;
+    constexpr int M = kBlkM, T = kBlkT, NP = (M / 2) / T + 1;
     __shared__ __attribute__((aligned(16))) unsigned char lds[ConvLds<M>::BYTES];
     cplx* a = reinterpret_cast<cplx*>(lds);
     cplx* lo = a + ConvLds<M>::DATA;
@@ -1148,11 +1153,11 @@ __global__ __launch_bounds__(conv_threads(kBlkM)) void longconv_dk_blocked_kerne
 }
 
 // dk block mb of a channel from the sums above: inverse of D_mb + (-1)^bin D_{mb+1}, low half.
-__global__ __launch_bounds__(conv_threads(kBlkM)) void longconv_dk_blocked_finish_kernel(const float4* __restrict__ acc_ws,
+__global__ __launch_bounds__(kBlkT) void longconv_dk_blocked_finish_kernel(const float4* __restrict__ acc_ws,
                                                                                         float* __restrict__ dk, int d,
                                                                                         int L, int nb)
 {
-    constexpr int M = kBlkM, T = conv_threads(M);
+    constexpr int M = kBlkM, T = kBlkT;
     __shared__ __attribute__((aligned(16))) unsigned char lds[ConvLds<M>::BYTES];
     cplx* a = reinterpret_cast<cplx*>(lds);
     cplx* lo = a + ConvLds<M>::DATA;
@@ -1214,7 +1219,7 @@ hipError_t launch_longconv_spectrum(const float* k, void* Kf, int d, int L, hipS
     ProfScope prof(KID_CONV_SPECTRUM, st);
     float4* out = (float4*)Kf;
     if (const int nb = conv_blocks(L)) {
-        hipLaunchKernelGGL(longconv_spectrum_blocked_kernel, dim3(d, nb), dim3(conv_threads(kBlkM)), 0, st, k, out, L, nb);
+        hipLaunchKernelGGL(longconv_spectrum_blocked_kernel, dim3(d, nb), dim3(kBlkT), 0, st, k, out, L, nb);
         return hipGetLastError();
     }
     switch (M) {
@@ -1246,10 +1251,10 @@ static hipError_t conv_blocked_launch(const IN* X, const float* w, int m, const 
                                       hipStream_t st)
 {
     const int nb = conv_blocks(L);
-    static const long slots = resident_workgroups(longconv_blocked_kernel<IN, OUT, CORR>, conv_threads(kBlkM));
+    static const long slots = resident_workgroups(longconv_blocked_kernel<IN, OUT, CORR>, kBlkT);
     const long items = BD * nb;
     const dim3 grid((unsigned)(items < slots ? items : slots));
-    hipLaunchKernelGGL((longconv_blocked_kernel<IN, OUT, CORR>), grid, dim3(conv_threads(kBlkM)), 0, st, X, w, m, Gf, Y, d,
+    hipLaunchKernelGGL((longconv_blocked_kernel<IN, OUT, CORR>), grid, dim3(kBlkT), 0, st, X, w, m, Gf, Y, d,
                        L, nb, BD);
     return hipGetLastError();
 }
@@ -1345,10 +1350,10 @@ static hipError_t conv_longbwd_dispatch(const IO* X, const float* w, int m, cons
         // distance and their way back
         hipError_t e = conv_blocked_launch<IO, DVT, true>(dZ, nullptr, 0, Kf, dV, (long)B * d, d, L, st);
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL((longconv_dk_blocked_kernel<IO>), dim3(d, nb), dim3(conv_threads(kBlkM)), 0, st, X, w, m, dZ,
+        hipLaunchKernelGGL((longconv_dk_blocked_kernel<IO>), dim3(d, nb), dim3(kBlkT), 0, st, X, w, m, dZ,
                            acc_ws, B, d, L, nb);
         if ((e = hipGetLastError()) != hipSuccess) return e;
-        hipLaunchKernelGGL(longconv_dk_blocked_finish_kernel, dim3(d, nb), dim3(conv_threads(kBlkM)), 0, st, acc_ws, dk, d,
+        hipLaunchKernelGGL(longconv_dk_blocked_finish_kernel, dim3(d, nb), dim3(kBlkT), 0, st, acc_ws, dk, d,
                            L, nb);
         return hipGetLastError();
     }
