@@ -291,9 +291,14 @@ __device__ __forceinline__ void flush_stage(const bf16* stage, bf16* out, int ld
 #pragma unroll
     for (int n = 0; n < ROWS * PPR / 256; ++n) {
         const int x = tid + 256 * n, row = x / PPR, piece = x % PPR;
-        if (row < valid_rows)
-            *reinterpret_cast<uint4*>(out + ((unsigned)row * (unsigned)ld + (unsigned)piece * 8u)) =
-                *reinterpret_cast<const uint4*>(stage + stage_at<D>(row, piece));
+        if (row < valid_rows) {
+            // streaming ("non-temporal") stores: nothing here reads an output again, whole 128-byte lines leave at
+            // once, and lines that do not linger in the memory-side cache do not push the inputs out of it
+            const uint4 t = *reinterpret_cast<const uint4*>(stage + stage_at<D>(row, piece));
+            u32x4v tv;
+            tv[0] = t.x; tv[1] = t.y; tv[2] = t.z; tv[3] = t.w;
+            __builtin_nontemporal_store(tv, reinterpret_cast<u32x4v*>(out + ((unsigned)row * (unsigned)ld + (unsigned)piece * 8u)));
+        }
     }
 }
 
@@ -1233,9 +1238,11 @@ void bf16_seg_state_kernel(SegStateArgs args, int N, int seg_len, int n_seg)
                                   args.acc_order != 0);
 }
 
-// (the narrowest shape is asked to stay within the 128 registers that let four workgroups share a compute unit)
+// (the narrowest shape is asked to stay within the registers that let three workgroups share a compute unit: with its
+// staging tile it takes 45 KB of LDS)
 template <int C, int DK, int DV, bool ZQK, bool SAVE, bool NH>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((C == 64 && DK == 64 && DV == 64) ? (NH ? 3 : 4) : 1)))
+__global__ __launch_bounds__(256)
+__attribute__((amdgpu_waves_per_eu((C == 64 && DK == 64 && DV == 64) ? 3 : 1)))
 void bf16_fwd_sweep_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K,
                                                             const bf16* __restrict__ V, bf16* __restrict__ O,
                                                             const float* __restrict__ S0, float* __restrict__ S_out,
@@ -1244,10 +1251,11 @@ void bf16_fwd_sweep_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ 
                                                             int first_loads_state, int N, int seg_len, int n_seg,
                                                             int fold)
 {
-    // whole-row stores through a staging tile where its LDS and registers cost nothing that matters: not the
-    // contiguous 64-wide shape (it would lose its fourth workgroup per unit; with [B,N,H,d] rows, H * d apart, the
-    // tile pays for itself there too), not the 128 x 128 shape (out of registers: measured slower)
-    constexpr bool STAGE = C == 64 && !(DK == 128 && DV == 128) && (NH || DK != DV);
+    // whole-row streaming stores through a staging tile: every 64-token shape but 128 x 128 (there the tile costs
+    // registers the sweep needs: sweep 196 -> 211 us on B1 H16 N65536, which the faster pre-pass behind it does not
+    // repay).  The contiguous 64-wide shape gives up its fourth workgroup per unit for the tile and gains all the same
+    // (256 .. 1024 sequences of 4096 tokens: 2 .. 10 % faster; the planner never asks for more than two per unit).
+    constexpr bool STAGE = C == 64 && !(DK == 128 && DV == 128);
     __shared__ __attribute__((aligned(16))) unsigned char
         lds[STAGE ? FwdLds<C, DK, DV, ZQK>::STAGED : FwdLds<C, DK, DV, ZQK>::BYTES];
     const int seg = blockIdx.y;
