@@ -614,7 +614,7 @@ struct FwdLds {
     static constexpr int TILES = (2 * C * LDK + C * LDV + DV * LDK) * 2;
     static constexpr int SMALL = (ZQK ? 4 * DK * 4 : 0) + (GATE ? 4 * C * 4 : 0);      // affine parameters, sums of squares
     static constexpr int BYTES = TILES + SMALL + (GATE ? C * LDV * 2 : 0);            // + the gate tile
-    static constexpr int STAGED = BYTES + C * DV * 2;                                 // + a staging tile for the output
+    static constexpr int STAGED = BYTES + (GATE ? 2 : 1) * C * DV * 2;                // + staging tile(s) for the output(s)
 };
 
 // GATE (Eq. 9, Y = Norm(O) * G with Norm(o) = o / sqrt(mean_j o_j^2 + eps) over the head's DV features): Gb and Yb
@@ -625,6 +625,8 @@ struct FwdLds {
 // (whole 128- or 256-byte rows, one chunk ahead, via LDS) and is picked up from LDS in the order the output tile is
 // stored in; fetching it from HBM in that order directly (32 bytes per row and instruction) cost 20 % more time.
 // STAGE: the output tile leaves through an LDS staging tile as whole rows, after the barrier that ends the chunk.
+// With GATE the gated output Y has a staging tile of its own: it is filled after that barrier (the normalisation needs
+// every wave's share of the sums of squares) and leaves after the NEXT chunk's first barrier, or after the loop.
 template <int C, int DK, int DV, bool ZQK, bool SAVE, bool GATE = false, bool STAGE = false>
 __device__ __forceinline__ void fwd_sweep_body(const bf16* __restrict__ Qb, const bf16* __restrict__ Kb,
                                                const bf16* __restrict__ Vb, bf16* __restrict__ Ob,
@@ -670,6 +672,9 @@ __device__ __forceinline__ void fwd_sweep_body(const bf16* __restrict__ Qb, cons
     if (s0_acc) sum_states_acc<DK, DV, false, 4>(accS, S0, n_s0, w, lane);
     else sum_states<DK, DV, false>(accS, S0, n_s0, w, lane);
 
+    // staging tiles (STAGE): O, or with GATE: Y then O
+    bf16* sOutY = reinterpret_cast<bf16*>(lds + FwdLds<C, DK, DV, ZQK, GATE>::BYTES);
+    bf16* sOutO = GATE ? sOutY + C * DV : sOutY;
     for (int c0 = 0; c0 < ntok; c0 += C) {
         if (ZQK) {
             rq.store_affine(sQ, sAff, sAff + DK, tid);
@@ -682,6 +687,8 @@ __device__ __forceinline__ void fwd_sweep_body(const bf16* __restrict__ Qb, cons
         if (GATE) rg.store(sG, tid);
         state_to_lds_T<DK, DV, false>(sST, accS, w, lane);
         __syncthreads();
+        if (GATE && STAGE && c0 > 0)    // the chunk before's gated output, complete in its staging tile since that barrier
+            flush_stage<C, DV>(sOutY, Yb + (size_t)(c0 - C) * ldv, ldv, C, tid);
         const bool more = c0 + C < ntok;
         if (more) {
             rq.load(Qb + (size_t)(c0 + C) * ldk, ldk, ntok - c0 - C, tid);
@@ -719,10 +726,9 @@ __device__ __forceinline__ void fwd_sweep_body(const bf16* __restrict__ Qb, cons
             }
         }
         const int valid = ntok - (c0 + tb * 32);
-        if (STAGE) {
-            bf16* sOut = reinterpret_cast<bf16*>(lds + FwdLds<C, DK, DV, ZQK, GATE>::BYTES);
+        if (STAGE && (!GATE || Ob != nullptr)) {
 #pragma unroll
-            for (int n = 0; n < NJ; ++n) stage_tile_T<DV>(sOut, tb * 32, (jg * NJ + n) * 32, accO[n], lane);
+            for (int n = 0; n < NJ; ++n) stage_tile_T<DV>(sOutO, tb * 32, (jg * NJ + n) * 32, accO[n], lane);
         } else if (!GATE || Ob != nullptr) {
             bf16* rows = Ob + (size_t)(c0 + tb * 32) * ldv;
 #pragma unroll
@@ -759,20 +765,31 @@ __device__ __forceinline__ void fwd_sweep_body(const bf16* __restrict__ Qb, cons
             }
         }
         __syncthreads();
-        if (STAGE)   // (the staging tile is next written after the next chunk's first barrier)
-            flush_stage<C, DV>(reinterpret_cast<const bf16*>(lds + FwdLds<C, DK, DV, ZQK, GATE>::BYTES),
-                           Ob + (size_t)c0 * ldv, ldv, ntok - c0, tid);
+        if (STAGE && (!GATE || Ob != nullptr))   // (the staging tile is next written after the next chunk's first barrier)
+            flush_stage<C, DV>(sOutO, Ob + (size_t)c0 * ldv, ldv, ntok - c0, tid);
         if (GATE) {
             // (the next chunk writes sSq only after its own first barrier, which every wave reaches after this read)
             float tot = 0.f;
 #pragma unroll
             for (int g = 0; g < WJ; ++g) tot += sSq[g * C + tb * 32 + (lane & 31)];
             const float rinv = __builtin_amdgcn_rsqf(fmaf(tot, 1.f / DV, eps));
-            bf16* rows = Yb + (size_t)(c0 + tb * 32) * ldv;
+            if (STAGE) {
+                // (the tile was last read, by the flush above, before the barrier that has just ended this chunk)
 #pragma unroll
-            for (int n = 0; n < NJ; ++n)
-                store_tile_T(rows, ldv, (jg * NJ + n) * 32, gate_tile(accO[n], gate[n], rinv), valid, lane);
+                for (int n = 0; n < NJ; ++n)
+                    stage_tile_T<DV>(sOutY, tb * 32, (jg * NJ + n) * 32, gate_tile(accO[n], gate[n], rinv), lane);
+            } else {
+                bf16* rows = Yb + (size_t)(c0 + tb * 32) * ldv;
+#pragma unroll
+                for (int n = 0; n < NJ; ++n)
+                    store_tile_T(rows, ldv, (jg * NJ + n) * 32, gate_tile(accO[n], gate[n], rinv), valid, lane);
+            }
         }
+    }
+    if (GATE && STAGE && ntok > 0) {
+        __syncthreads();        // the last chunk's gated tile is complete
+        const int c_last = ((ntok - 1) / C) * C;
+        flush_stage<C, DV>(sOutY, Yb + (size_t)c_last * ldv, ldv, ntok - c_last, tid);
     }
     if (S_final != nullptr) store_state<DK, DV>(S_final, accS, w, lane);
     if (SAVE && S_final_T != nullptr) store_state_T<DK, DV>(S_final_T, accS, w, lane);   // [dv][dk], as the backward reads it
@@ -1286,13 +1303,18 @@ void bf16_fwd_sweep_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ 
 
 // The forward sweep with the Eq. 9 epilogue: Y = Norm(O) * G; O is written too when it is given.
 template <int C, int DK, int DV, bool ZQK, bool SAVE>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((C == 64 && DK == 64 && DV == 64) ? 3 : 1)))
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((C == 64 && DK == 64 && DV == 64) ? 2 : 1)))
 void bf16_fwd_gated_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, const bf16* __restrict__ V,
                            const bf16* __restrict__ G, bf16* __restrict__ O, bf16* __restrict__ Y, float eps,
                            const float* __restrict__ S0, const float* __restrict__ aff, int H,
                            float* __restrict__ saved, int save_every, int N, int seg_len, int n_seg, int fold)
 {
-    __shared__ __attribute__((aligned(16))) unsigned char lds[FwdLds<C, DK, DV, ZQK, true>::BYTES];
+    // Both outputs through staging tiles, as in the plain forward sweep, at the 64-wide shape: 63 KB, two per unit
+    // (LM shape 107 -> 100 us, 256 sequences of 4096 tokens 133 -> 110 us).  With one width of 128 the two tiles would
+    // leave a unit to a single workgroup (104 KB): measured 7 % slower, so those shapes keep the direct stores.
+    constexpr bool STAGE = C == 64 && DK == 64 && DV == 64;
+    __shared__ __attribute__((aligned(16))) unsigned char
+        lds[STAGE ? FwdLds<C, DK, DV, ZQK, true>::STAGED : FwdLds<C, DK, DV, ZQK, true>::BYTES];
     const int seg = blockIdx.y;
     const long bh = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63;
@@ -1304,7 +1326,7 @@ void bf16_fwd_gated_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ 
         const int n_slots = (n_seg + save_every - 1) / save_every, slot = (seg + save_every) / save_every - 1;
         save_to = saved + ((size_t)bh * n_slots + slot) * DK * DV;
     }
-    fwd_sweep_body<C, DK, DV, ZQK, SAVE, true>(Q + rk, ZQK ? nullptr : K + rk, V + rv, O ? O + rv : nullptr,
+    fwd_sweep_body<C, DK, DV, ZQK, SAVE, true, STAGE>(Q + rk, ZQK ? nullptr : K + rk, V + rv, O ? O + rv : nullptr,
                                                (S0 != nullptr && seg > 0)
                                                    ? S0 + ((size_t)bh * n_seg + (fold ? 0 : seg)) * DK * DV : nullptr,
                                                fold ? seg : 1, fold != 0, nullptr, save_to, ZQK ? aff + (size_t)(bh % H) * DK : nullptr,

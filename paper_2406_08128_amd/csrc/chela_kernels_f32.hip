@@ -477,7 +477,9 @@ __global__ __launch_bounds__(256) void f32_sweep_kernel(const float* __restrict_
 #pragma unroll
                 for (int b = 0; b < 4; ++b) {
                     const int pp = c0 + tb * 32 + 8 * a + 4 * h + b;
-                    if (pp < p1) Ob[(size_t)phys_row(pp, N, rev) * DV + j0 + r] = accO[n][4 * a + b];
+                    // (a streaming store: 32 lanes write one whole 128-byte line, and nothing here reads it again)
+                    if (pp < p1)
+                        __builtin_nontemporal_store(accO[n][4 * a + b], &Ob[(size_t)phys_row(pp, N, rev) * DV + j0 + r]);
                 }
         }
     }
