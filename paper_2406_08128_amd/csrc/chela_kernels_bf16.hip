@@ -284,7 +284,7 @@ __device__ __forceinline__ void stage_tile_T(bf16* stage, int row0, int col0, co
 }
 
 // ROWS x D staged tile -> rows of the row-major matrix at `out` (leading dimension ld), the first valid_rows of them.
-template <int ROWS, int D>
+template <int ROWS, int D, bool NTS = true>
 __device__ __forceinline__ void flush_stage(const bf16* stage, bf16* out, int ld, int valid_rows, int tid)
 {
     constexpr int PPR = D / 8;      // 16-byte pieces per row
@@ -295,9 +295,13 @@ __device__ __forceinline__ void flush_stage(const bf16* stage, bf16* out, int ld
             // streaming ("non-temporal") stores: nothing here reads an output again, whole 128-byte lines leave at
             // once, and lines that do not linger in the memory-side cache do not push the inputs out of it
             const uint4 t = *reinterpret_cast<const uint4*>(stage + stage_at<D>(row, piece));
-            u32x4v tv;
-            tv[0] = t.x; tv[1] = t.y; tv[2] = t.z; tv[3] = t.w;
-            __builtin_nontemporal_store(tv, reinterpret_cast<u32x4v*>(out + ((unsigned)row * (unsigned)ld + (unsigned)piece * 8u)));
+            if (NTS) {
+                u32x4v tv;
+                tv[0] = t.x; tv[1] = t.y; tv[2] = t.z; tv[3] = t.w;
+                __builtin_nontemporal_store(tv, reinterpret_cast<u32x4v*>(out + ((unsigned)row * (unsigned)ld + (unsigned)piece * 8u)));
+            } else {
+                *reinterpret_cast<uint4*>(out + ((unsigned)row * (unsigned)ld + (unsigned)piece * 8u)) = t;
+            }
         }
     }
 }
@@ -904,6 +908,9 @@ __device__ __forceinline__ void bwd_sweep_body(const bf16* __restrict__ Qb, cons
     make_masks<true>(maskK, lane);
     make_masks<false>(maskQ, lane);
 
+    // (plain loads: with the streaming hint this sweep gets 7 us faster at the LM shape, and a step on tensors that
+    // nothing has touched just before 1.7 % faster, but the forward call that follows on the same tensors loses more
+    // than that on the K and V it no longer finds in the memory-side cache: 0.290 -> 0.294 ms per step)
     TileRegs<C, DK> rq, rk;            // with ZQK only rq is used in the main loop: it holds Z
     TileRegs<C, DV> rv, rg;
     f32x16 accNS[NS], accRT[NS];       // states, transposed: [DV][DK]; accNS holds MINUS S^T
@@ -1457,7 +1464,12 @@ __global__ __launch_bounds__(256) void gate_norm_kernel(const bf16* __restrict__
         if (!BWD) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) y[e] = x[e] * rinv * gg[e];
+#ifdef CHELA_EXP_GN_NT
+            if (r < rows) { const uint4 t = pack8(y); u32x4v tv; tv[0] = t.x; tv[1] = t.y; tv[2] = t.z; tv[3] = t.w;
+                __builtin_nontemporal_store(tv, reinterpret_cast<u32x4v*>(out0 + off)); }
+#else
             if (r < rows) *reinterpret_cast<uint4*>(out0 + off) = pack8(y);
+#endif
         } else {
             // n = r o, u = dY g:  dG = dY n,  dO = r (u - n mean(u n))
             float dy[8], u[8], dg[8];
@@ -1474,8 +1486,18 @@ __global__ __launch_bounds__(256) void gate_norm_kernel(const bf16* __restrict__
 #pragma unroll
             for (int e = 0; e < 8; ++e) y[e] = rinv * fmaf(-x[e], m, u[e]);
             if (r < rows) {
+#if defined(CHELA_EXP_GN_NT) && CHELA_EXP_GN_NT >= 2
+                { const uint4 t = pack8(y); u32x4v tv; tv[0] = t.x; tv[1] = t.y; tv[2] = t.z; tv[3] = t.w;
+                  __builtin_nontemporal_store(tv, reinterpret_cast<u32x4v*>(out0 + off)); }
+#else
                 *reinterpret_cast<uint4*>(out0 + off) = pack8(y);
+#endif
+#ifdef CHELA_EXP_GN_NT
+                { const uint4 t = pack8(dg); u32x4v tv; tv[0] = t.x; tv[1] = t.y; tv[2] = t.z; tv[3] = t.w;
+                  __builtin_nontemporal_store(tv, reinterpret_cast<u32x4v*>(out1 + off)); }
+#else
                 *reinterpret_cast<uint4*>(out1 + off) = pack8(dg);
+#endif
             }
         }
     }
