@@ -666,8 +666,12 @@ def main():
                         "segments_per_sequence": n_seg,
                         "step_over_floor": round(ms_per_step * 1e3 / tot, 3),
                         "note": "plain grid-stride kernels moving what the pre-passes and sweeps of this step must "
-                                "move (kernel time only, no launch gaps): the step cannot beat this without moving "
-                                "fewer bytes, i.e. without another structure than pre-pass + sweep per call"}
+                                "move, each on arrays that nothing has touched just before (kernel time only, no "
+                                "launch gaps).  A step below this (step_over_floor < 1) has found part of what it "
+                                "reads in the 256 MB memory-side cache: a sweep re-reads what its pre-pass has just "
+                                "read, and the outputs leave as streaming stores so that they do not push those "
+                                "lines out; rotating_sets gives the step when at least no call finds its inputs "
+                                "there because the step before used the same tensors"}
 
     step_bytes = (fwd_b + (bwd_b if has_bwd else 0)) * th
     step_flops = (fwd_f + (bwd_f if has_bwd else 0)) * th
