@@ -1066,7 +1066,8 @@ def test_conv_bwd_sequences_dealt_over_workgroups(shape):
 @pytest.mark.parametrize("shape", [(1, 2, 16385, 9, "f32", True), (2, 3, 20000, 5, "f32", True),
                                    (1, 2, 40001, 9, "f32", True), (1, 2, 65536, 3, "f32", True),
                                    (1, 2, 33000, 3, "f32", False), (2, 2, 32768, 9, "bf16", True),
-                                   (1, 3, 50001, 17, "bf16", True), (3, 1, 36864, 32, "bf16", False)])
+                                   (1, 3, 50001, 17, "bf16", True), (3, 1, 36864, 32, "bf16", False),
+                                   (1, 2, 20001, 32, "f32", True)])
 def test_shortlong_conv_longer_than_one_transform(shape):
     # L > 16384: blocks of 16384 steps, the sum over the input blocks taken on the spectra; one step beyond a block,
     # ragged and odd lengths (rows that start on odd elements), whole blocks, every tap-count class, both I/O types
@@ -1076,7 +1077,8 @@ def test_shortlong_conv_longer_than_one_transform(shape):
 
 @pytest.mark.parametrize("shape", [(2, 2, 16385, 9, "f32", True), (2, 3, 40001, 5, "f32", True),
                                    (1, 2, 65536, 9, "f32", True), (2, 2, 20000, 3, "f32", False),
-                                   (2, 2, 32768, 9, "bf16", True), (3, 1, 50001, 17, "bf16", True)])
+                                   (2, 2, 32768, 9, "bf16", True), (3, 1, 50001, 17, "bf16", True),
+                                   (1, 2, 20001, 32, "f32", True)])
 def test_shortlong_conv_bwd_longer_than_one_transform(shape):
     B, d, L, m, dtype, short = shape
     _run_conv_bwd_case(B, d, L, m, dtype, seed=L + 23, short=short)
