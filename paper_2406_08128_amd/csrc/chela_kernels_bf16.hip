@@ -833,7 +833,10 @@ struct BwdLds {
     static constexpr int WORK = TILES + (ZQK ? C * LDK * 2 + 4 * DK * 4 : 0);
     // 64-wide heads: the output tiles leave through unpadded staging tiles (whole-line stores), 8 KB each
     static constexpr bool STAGE = (C == 64 && DK == 64 && DV == 64);
-    static constexpr int BYTES = WORK + (STAGE ? (ZQK ? 2 : 3) * C * 64 * 2 : 0);
+    // one width of 128 (without the Eq. 11-12 prologue): the 64-wide outputs take turns in ONE 8 KB staging tile, which
+    // is what still fits beside two resident workgroups (78.8 / 79.9 KB); the 128-wide ones keep their direct stores
+    static constexpr bool STAGE_NARROW = SHARE && !ZQK && DK == 64;
+    static constexpr int BYTES = WORK + (STAGE ? (ZQK ? 2 : 3) * C * 64 * 2 : 0) + (STAGE_NARROW ? C * 64 * 2 : 0);
 };
 
 // Sum over the tokens of a wave half for the parameter gradients.  x holds, per lane, 16 values of one token (the
@@ -980,6 +983,167 @@ __device__ __forceinline__ void bwd_sweep_body(const bf16* __restrict__ Qb, cons
 
     for (int ci = n_ch - 1; ci >= 0; --ci) {
         const int c0 = ci * C;
+        if constexpr (SHARE && !ZQK) {
+            // One width of 128: the two published states share one LDS tile.  The gradients that need R (dK, dV) come
+            // first, on the R published with the tiles; then S takes R's place for dQ: four barriers per chunk.  The
+            // 64-wide outputs go through one staging tile in turn (dK or dV after the second barrier, dQ after the
+            // last) and leave as whole-line streaming stores.  Every sum is formed as in the general flow below.
+            bf16* sSt = sOutQ;
+            rq.store(sQ, tid);
+            rk.store(sK, tid);
+            rv.store(sV, tid);
+            rg.store(sG, tid);
+            state_to_lds_T<DV, DK, false>(sR, accRT, w, lane);      // R: the state after this chunk
+            __syncthreads();
+            if (ci > 0) {
+                rq.load(Qb + (size_t)(c0 - C) * ldk, ldk, C, tid);
+                rk.load(Kb + (size_t)(c0 - C) * ldk, ldk, C, tid);
+                rv.load(Vb + (size_t)(c0 - C) * ldv, ldv, C, tid);
+                rg.load(Gb + (size_t)(c0 - C) * ldv, ldv, C, tid);
+            }
+            if (ckpt != nullptr && (ci + 1) % ckpt_every == 0 && ci + 1 < n_ch) {
+                const float4* src = reinterpret_cast<const float4*>(ckpt + (size_t)((ci + 1) / ckpt_every - 1) * (DK * DV)) +
+                                    ((size_t)(w * NS) * 64 + lane) * 4;
+#pragma unroll
+                for (int n = 0; n < NS; ++n)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const float4 v = src[(size_t)n * 256 + q];
+                        accNS[n][4 * q] = v.x; accNS[n][4 * q + 1] = v.y; accNS[n][4 * q + 2] = v.z; accNS[n][4 * q + 3] = v.w;
+                    }
+            }
+            const int valid = ntok - (c0 + rb * 32);
+            {   // dK^T for key block sb = rb:  dK^T = Q^T dP + R V^T
+                bf16x8 bV[DV / 16];
+#pragma unroll
+                for (int kk = 0; kk < DV / 16; ++kk) bV[kk] = ld_nat(sV, LDV, rb * 32, kk * 16, lane);
+                f32x16 acc[NI];
+#pragma unroll
+                for (int n = 0; n < NI; ++n) acc[n] = zero16();
+#pragma unroll
+                for (int n = 0; n < NI; ++n)
+#pragma unroll
+                    for (int kk = 0; kk < DV / 16; ++kk)
+                        acc[n] = mfma(ld_nat(sR, LDV, (cg * NI + n) * 32, kk * 16, lane), bV[kk], acc[n]);
+#pragma unroll
+                for (int tb = 0; tb < TB; ++tb) {
+                    if (tb >= rb) {
+                        f32x16 t = zero16();   // dP[t][s] = dO_t . v_s
+#pragma unroll
+                        for (int kk = 0; kk < DV / 16; ++kk) t = mfma(ld_nat(sG, LDV, tb * 32, kk * 16, lane), bV[kk], t);
+                        bf16x8 t0, t1;
+                        if (tb == rb) cvt_tile_masked(t, maskQ, t0, t1);
+                        else cvt_tile(t, t0, t1);
+#pragma unroll
+                        for (int n = 0; n < NI; ++n) {
+                            acc[n] = mfma(ld_tr_perm(sQ, LDK, tb * 32, (cg * NI + n) * 32, lane), t0, acc[n]);
+                            acc[n] = mfma(ld_tr_perm(sQ, LDK, tb * 32 + 16, (cg * NI + n) * 32, lane), t1, acc[n]);
+                        }
+                    }
+                }
+                bf16* rows = dKb + (size_t)(c0 + rb * 32) * ldk;
+#pragma unroll
+                for (int n = 0; n < NI; ++n) {
+                    if (DK == 64) stage_tile_T<64>(sSt, rb * 32, (cg * NI + n) * 32, acc[n], lane);
+                    else store_tile_T(rows, ldk, (cg * NI + n) * 32, acc[n], valid, lane);
+                }
+            }
+            {   // dV^T for key block sb = rb:  dV^T = dO^T P + R^T K^T
+                bf16x8 bK[DK / 16];
+#pragma unroll
+                for (int kk = 0; kk < DK / 16; ++kk) bK[kk] = ld_nat(sK, LDK, rb * 32, kk * 16, lane);
+                f32x16 acc[NJ];
+#pragma unroll
+                for (int n = 0; n < NJ; ++n) acc[n] = zero16();
+#pragma unroll
+                for (int n = 0; n < NJ; ++n)
+#pragma unroll
+                    for (int kk = 0; kk < DK / 16; ++kk)
+                        acc[n] = mfma(ld_tr(sR, LDV, kk * 16, (cg * NJ + n) * 32, lane), bK[kk], acc[n]);
+#pragma unroll
+                for (int tb = 0; tb < TB; ++tb) {
+                    if (tb >= rb) {
+                        f32x16 t = zero16();   // P[t][s] = q_t . k_s
+#pragma unroll
+                        for (int kk = 0; kk < DK / 16; ++kk) t = mfma(ld_nat(sQ, LDK, tb * 32, kk * 16, lane), bK[kk], t);
+                        bf16x8 t0, t1;
+                        if (tb == rb) cvt_tile_masked(t, maskQ, t0, t1);
+                        else cvt_tile(t, t0, t1);
+#pragma unroll
+                        for (int n = 0; n < NJ; ++n) {
+                            acc[n] = mfma(ld_tr_perm(sG, LDV, tb * 32, (cg * NJ + n) * 32, lane), t0, acc[n]);
+                            acc[n] = mfma(ld_tr_perm(sG, LDV, tb * 32 + 16, (cg * NJ + n) * 32, lane), t1, acc[n]);
+                        }
+                    }
+                }
+                bf16* rows = dVb + (size_t)(c0 + rb * 32) * ldv;
+#pragma unroll
+                for (int n = 0; n < NJ; ++n) {
+                    store_tile_T(rows, ldv, (cg * NJ + n) * 32, acc[n], valid, lane);
+                }
+            }
+            // R^T += dO^T Q (after the segment's first chunk only if the final state is asked for), and S rolled back
+            // over this chunk: (-S^T) += V^T K
+            if (ci > 0 || R_final != nullptr) {
+#pragma unroll
+                for (int n = 0; n < NS; ++n) {
+                    const int id = w + 4 * n, jb = id / IB, ib = id % IB;
+#pragma unroll
+                    for (int s0 = 0; s0 < C; s0 += 16)
+                        accRT[n] = mfma(ld_tr(sG, LDV, s0, jb * 32, lane), ld_tr(sQ, LDK, s0, ib * 32, lane), accRT[n]);
+                }
+            }
+#pragma unroll
+            for (int n = 0; n < NS; ++n) {
+                const int id = w + 4 * n, jb = id / IB, ib = id % IB;
+#pragma unroll
+                for (int s0 = 0; s0 < C; s0 += 16)
+                    accNS[n] = mfma(ld_tr(sV, LDV, s0, jb * 32, lane), ld_tr(sK, LDK, s0, ib * 32, lane), accNS[n]);
+            }
+            __syncthreads();            // every wave is done with R (and has staged its 64-wide tile)
+            if (DK == 64) flush_stage<C, 64>(sSt, dKb + (size_t)c0 * ldk, ldk, ntok - c0, tid);
+            state_to_lds_T<DV, DK, true>(sS, accNS, w, lane);       // S: the state before this chunk
+            __syncthreads();
+            {   // dQ^T for token block tb = rb:  dQ^T = K^T dP^T + S dO^T
+                f32x16 acc[NI];
+                bf16x8 bG[DV / 16];
+#pragma unroll
+                for (int kk = 0; kk < DV / 16; ++kk) bG[kk] = ld_nat(sG, LDV, rb * 32, kk * 16, lane);
+#pragma unroll
+                for (int n = 0; n < NI; ++n) acc[n] = zero16();
+#pragma unroll
+                for (int n = 0; n < NI; ++n)
+#pragma unroll
+                    for (int kk = 0; kk < DV / 16; ++kk)
+                        acc[n] = mfma(ld_nat(sS, LDV, (cg * NI + n) * 32, kk * 16, lane), bG[kk], acc[n]);
+#pragma unroll
+                for (int sb = 0; sb < TB; ++sb) {
+                    if (sb <= rb) {
+                        f32x16 t = zero16();   // dP^T[s][t] = v_s . dO_t
+#pragma unroll
+                        for (int kk = 0; kk < DV / 16; ++kk) t = mfma(ld_nat(sV, LDV, sb * 32, kk * 16, lane), bG[kk], t);
+                        bf16x8 t0, t1;
+                        if (sb == rb) cvt_tile_masked(t, maskK, t0, t1);
+                        else cvt_tile(t, t0, t1);
+#pragma unroll
+                        for (int n = 0; n < NI; ++n) {
+                            acc[n] = mfma(ld_tr_perm(sK, LDK, sb * 32, (cg * NI + n) * 32, lane), t0, acc[n]);
+                            acc[n] = mfma(ld_tr_perm(sK, LDK, sb * 32 + 16, (cg * NI + n) * 32, lane), t1, acc[n]);
+                        }
+                    }
+                }
+                bf16* rows = dQb + (size_t)(c0 + rb * 32) * ldk;
+#pragma unroll
+                for (int n = 0; n < NI; ++n) {
+                    // (the staging tile was last read by the flush above, before the barrier that let S in)
+                    if (DK == 64) stage_tile_T<64>(sSt, rb * 32, (cg * NI + n) * 32, acc[n], lane);
+                    else store_tile_T(rows, ldk, (cg * NI + n) * 32, acc[n], valid, lane);
+                }
+            }
+            __syncthreads();            // tiles, S and the staged dQ are done with
+            if (DK == 64) flush_stage<C, 64>(sSt, dQb + (size_t)c0 * ldk, ldk, ntok - c0, tid);
+            continue;
+        }
         if (ZQK) {
             rq.store_affine(sQ, sAff, sAff + DK, tid);
             rq.store_affine(sK, sAff + 2 * DK, sAff + 3 * DK, tid);
