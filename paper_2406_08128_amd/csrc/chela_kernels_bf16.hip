@@ -1443,7 +1443,10 @@ void bf16_fwd_sweep_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ 
     // registers the sweep needs: sweep 196 -> 211 us on B1 H16 N65536, which the faster pre-pass behind it does not
     // repay).  The contiguous 64-wide shape gives up its fourth workgroup per unit for the tile and gains all the same
     // (256 .. 1024 sequences of 4096 tokens: 2 .. 10 % faster; the planner never asks for more than two per unit).
-    constexpr bool STAGE = C == 64 && !(DK == 128 && DV == 128);
+    // 128-token chunks at the 64-wide shape take a 16 KB tile (80.9 KB in all, still two per unit): 256 sequences of
+    // 4096 tokens 104 -> 91 us.  (The backward sweep with 128-token chunks loses as much in the sweep as the kernels
+    // around it gain: left with direct stores.)
+    constexpr bool STAGE = (C == 64 && !(DK == 128 && DV == 128)) || (C == 128 && DK == 64 && DV == 64);
     __shared__ __attribute__((aligned(16))) unsigned char
         lds[STAGE ? FwdLds<C, DK, DV, ZQK>::STAGED : FwdLds<C, DK, DV, ZQK>::BYTES];
     const int seg = blockIdx.y;
