@@ -23,6 +23,10 @@ struct Plan {
 // every workgroup re-reads, on average, half of them from the L2.
 constexpr size_t kMaxFoldedStateBytes = (size_t)256 << 10;
 
+// The memory-side cache holds 256 MB.  A backward call whose four input tensors come to more than this reads two of
+// them (dO, Q) with the streaming hint in its pre-pass, so that the other two stay cached for the sweep.
+constexpr size_t kStreamPairAboveBytes = (size_t)224 << 20;
+
 // Checkpoints of a single-segment backward: how many, and where they live ([BH][n][dk*dv] fp32 at the workspace's start).
 inline long plan_n_ckpt(const Plan& p, int N)
 {

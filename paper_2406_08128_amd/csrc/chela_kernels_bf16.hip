@@ -911,11 +911,15 @@ __device__ __forceinline__ void bwd_sweep_body(const bf16* __restrict__ Qb, cons
     make_masks<true>(maskK, lane);
     make_masks<false>(maskQ, lane);
 
-    // (plain loads: with the streaming hint this sweep gets 7 us faster at the LM shape, and a step on tensors that
-    // nothing has touched just before 1.7 % faster, but the forward call that follows on the same tensors loses more
-    // than that on the K and V it no longer finds in the memory-side cache: 0.290 -> 0.294 ms per step)
-    TileRegs<C, DK> rq, rk;            // with ZQK only rq is used in the main loop: it holds Z
-    TileRegs<C, DV> rv, rg;
+    // Q and dO with the streaming hint, K and V without: nothing reads Q and dO again after this sweep, and the
+    // pre-pass has left K and V in the memory-side cache for it (launch_bf16_bwd).  With the hint on all four the
+    // forward call that follows on the same tensors loses more on the K and V it no longer finds there than this sweep
+    // gains (0.290 -> 0.294 ms per step at the LM shape).
+    // (Not with ZQK: Z stands for Q and K alike, both pairs of the pre-pass read it, and the hint measured 0.7 % slower.)
+    TileRegs<C, DK, !ZQK> rq;          // with ZQK only rq is used in the main loop: it holds Z
+    TileRegs<C, DK> rk;
+    TileRegs<C, DV> rv;
+    TileRegs<C, DV, !ZQK> rg;
     f32x16 accNS[NS], accRT[NS];       // states, transposed: [DV][DK]; accNS holds MINUS S^T
     bf16* sZ = reinterpret_cast<bf16*>(lds + BwdLds<C, DK, DV, false>::TILES);
     float* sAff = reinterpret_cast<float*>(sZ + C * LDK);
@@ -1402,7 +1406,8 @@ __device__ __forceinline__ size_t row_offset(bool nh, long bh, int H, int N, int
 }
 
 // NT: the two tensors are not read again after this kernel (streaming hint on their loads).
-template <int DA, int DB, int AFF, bool NH, bool NT>
+// NT1: the hint on the second pair's loads only (see bwd_impl).
+template <int DA, int DB, int AFF, bool NH, bool NT, bool NT1 = false>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((DA == 64 && DB == 64) ? (AFF == 0 ? 6 : 5) : 1)))
 void bf16_seg_state_kernel(SegStateArgs args, int N, int seg_len, int n_seg)
 {
@@ -1418,6 +1423,14 @@ void bf16_seg_state_kernel(SegStateArgs args, int N, int seg_len, int n_seg)
         const size_t hoff = (size_t)(bh % args.H) * (AFF == 1 ? DA : DB);
         al = args.alpha[z] + hoff;
         be = args.beta[z] + hoff;
+    }
+    if (NT1 && z == 1) {     // (uniform over the workgroup)
+        prepass_body<DA, DB, AFF, true>(args.X[z] + row_offset<DA>(NH, bh, args.H, N, p0),
+                                        args.Y[z] + row_offset<DB>(NH, bh, args.H, N, p0),
+                                        args.out[z] + ((size_t)bh * n_seg + seg) * DA * DB, al, be, NH ? args.H * DA : DA,
+                                        NH ? args.H * DB : DB, p1 - p0, lds, tid, w, lane, args.reverse[z] != 0,
+                                        args.acc_order != 0);
+        return;
     }
     prepass_body<DA, DB, AFF, NT>(args.X[z] + row_offset<DA>(NH, bh, args.H, N, p0),
                                   args.Y[z] + row_offset<DB>(NH, bh, args.H, N, p0),
@@ -1780,14 +1793,18 @@ static bool fold_scan(const Plan& plan, bool stateful, bool is_bwd = false)
 template <int DA, int DB, int AFF = 0, bool NH = false, bool NT = false>
 static hipError_t run_seg_state(const SegStateArgs& a, int npairs, const int* scan_modes, const float* const* init,
                                 bool init_transposed, long BH, int N, const Plan& plan, hipStream_t st,
-                                bool do_scan = true)
+                                bool do_scan = true, bool stream_second_pair = false)
 {
     hipError_t e;
     {
         dim3 grid((unsigned)BH, plan.n_seg, npairs);
         ProfScope prof(KID_SEG_STATE_BF16, st);
-        hipLaunchKernelGGL((bf16_seg_state_kernel<DA, DB, AFF, NH, NT>), grid, dim3(256), 0, st, a, N, plan.seg_len,
-                           plan.n_seg);
+        if (AFF == 0 && !NT && stream_second_pair)
+            hipLaunchKernelGGL((bf16_seg_state_kernel<DA, DB, AFF == 0 ? 0 : AFF, NH, false, AFF == 0 && !NT>), grid,
+                               dim3(256), 0, st, a, N, plan.seg_len, plan.n_seg);
+        else
+            hipLaunchKernelGGL((bf16_seg_state_kernel<DA, DB, AFF, NH, NT>), grid, dim3(256), 0, st, a, N, plan.seg_len,
+                               plan.n_seg);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     if (!do_scan) return hipSuccess;
@@ -1922,13 +1939,19 @@ static hipError_t bwd_impl(const bf16* Q, const bf16* K, const bf16* V, const bf
         a.X[1] = dO; a.Y[1] = Q;           a.out[1] = wsR; a.skip_seg[1] = 0;
         a.H = H;
         a.acc_order = fold ? 1 : 0;
+        // The sweep re-reads all four tensors right after this pre-pass.  Once they no longer fit the memory-side
+        // cache together, dO and Q are read with the streaming hint, here and in the sweep, so that K and V stay in it
+        // whole instead of all four fighting for it: LM shape (403 MB) 0.292 -> 0.283 ms per step, backward sweep
+        // 140 -> 130.5 us; 0.298 -> 0.293 ms on three sets of tensors used in turn.
+        const bool stream_dO_Q = !ZQK && (size_t)BH * N * (2 * DK + 2 * DV) * sizeof(bf16) > kStreamPairAboveBytes;
         if (ZQK) {
             a.alpha[0] = aff + 2 * (size_t)H * DK; a.beta[0] = aff + 3 * (size_t)H * DK;   // K
             a.alpha[1] = aff;                      a.beta[1] = aff + (size_t)H * DK;       // Q
         }
         const int modes[2] = {SCAN_INCL_PREFIX, SCAN_EXCL_SUFFIX};
         const float* init[2] = {S_in, dS_out};   // given as [dk][dv]; the arrays are [dv][dk]
-        if ((e = run_seg_state<DV, DK, ZQK ? 2 : 0, NH>(a, 2, modes, init, true, BH, N, plan, st, !fold)) != hipSuccess)
+        if ((e = run_seg_state<DV, DK, ZQK ? 2 : 0, NH>(a, 2, modes, init, true, BH, N, plan, st, !fold, stream_dO_Q)) !=
+            hipSuccess)
             return e;
     }
     {
