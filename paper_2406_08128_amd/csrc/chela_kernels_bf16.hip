@@ -2171,7 +2171,11 @@ static hipError_t noncausal_bwd_impl(const bf16* Q, const bf16* K, const bf16* V
     a.X[0] = V;  a.Y[0] = K; a.out[0] = wsS; a.skip_seg[0] = -1;
     a.X[1] = dO; a.Y[1] = Q; a.out[1] = wsR; a.skip_seg[1] = -1;
     const int modes[2] = {SCAN_INCL_PREFIX, SCAN_INCL_PREFIX};
-    if ((e = run_seg_state<DV, DK>(a, 2, modes, nullptr, false, BH, N, plan, st, plan.n_seg > 1)) != hipSuccess) return e;
+    // (as in the causal backward: once the four tensors exceed the memory-side cache, dO and Q go through it with the
+    // streaming hint, so that V and K are still there for the second and third of the kernels below)
+    const bool stream_dO_Q = (size_t)BH * N * (2 * DK + 2 * DV) * sizeof(bf16) > kStreamPairAboveBytes;
+    if ((e = run_seg_state<DV, DK>(a, 2, modes, nullptr, false, BH, N, plan, st, plan.n_seg > 1, stream_dO_Q)) != hipSuccess)
+        return e;
     const size_t last = (size_t)(plan.n_seg - 1) * el, stride = plan.n_seg * el;
     // dQ = dO S^T, dK = V R^T, dV = K R
     if ((e = run_apply<DV, DK, false>(dO, dQ, wsS + last, stride, BH, N, st)) != hipSuccess) return e;
