@@ -1644,12 +1644,10 @@ __global__ __launch_bounds__(256) void gate_norm_kernel(const bf16* __restrict__
         if (!BWD) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) y[e] = x[e] * rinv * gg[e];
-#ifdef CHELA_EXP_GN_NT
-            if (r < rows) { const uint4 t = pack8(y); u32x4v tv; tv[0] = t.x; tv[1] = t.y; tv[2] = t.z; tv[3] = t.w;
-                __builtin_nontemporal_store(tv, reinterpret_cast<u32x4v*>(out0 + off)); }
-#else
+            // (plain stores: with the streaming hint on these whole-row stores the kernel after it gains where the
+            // tensors are small and this kernel loses where they are large -- LM shape -3 %, 256 sequences of 4096
+            // tokens +2 % on the two-pass epilogue)
             if (r < rows) *reinterpret_cast<uint4*>(out0 + off) = pack8(y);
-#endif
         } else {
             // n = r o, u = dY g:  dG = dY n,  dO = r (u - n mean(u n))
             float dy[8], u[8], dg[8];
@@ -1666,18 +1664,8 @@ __global__ __launch_bounds__(256) void gate_norm_kernel(const bf16* __restrict__
 #pragma unroll
             for (int e = 0; e < 8; ++e) y[e] = rinv * fmaf(-x[e], m, u[e]);
             if (r < rows) {
-#if defined(CHELA_EXP_GN_NT) && CHELA_EXP_GN_NT >= 2
-                { const uint4 t = pack8(y); u32x4v tv; tv[0] = t.x; tv[1] = t.y; tv[2] = t.z; tv[3] = t.w;
-                  __builtin_nontemporal_store(tv, reinterpret_cast<u32x4v*>(out0 + off)); }
-#else
                 *reinterpret_cast<uint4*>(out0 + off) = pack8(y);
-#endif
-#ifdef CHELA_EXP_GN_NT
-                { const uint4 t = pack8(dg); u32x4v tv; tv[0] = t.x; tv[1] = t.y; tv[2] = t.z; tv[3] = t.w;
-                  __builtin_nontemporal_store(tv, reinterpret_cast<u32x4v*>(out1 + off)); }
-#else
                 *reinterpret_cast<uint4*>(out1 + off) = pack8(dg);
-#endif
             }
         }
     }
